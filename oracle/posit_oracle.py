@@ -1,0 +1,560 @@
+"""Plain CPU oracle for quire-exact posit arithmetic (PositNN, arXiv 2105.00053).
+
+TEST INFRASTRUCTURE ONLY.  This module is the slow, obviously-correct definition
+that the GPU library is compared against.  It is imported by the tests, by the
+smoke check and by the CPU-baseline leg of the benchmark, never by the product
+path, and it shares no code with the HIP sources.
+
+Everything here is exact integer / rational arithmetic (Python ``int`` and
+``fractions.Fraction``): no floats take part in any result.
+
+What each function follows
+--------------------------
+* ``decode``            : Sec. 2, Eq. 2 (sign, regime run-length k, exponent,
+                          fraction; two's complement first when negative).
+* ``PositFormat``       : Sec. 3.1, Table 1 (nbits/es pairs, dynamic range,
+                          quire width).
+* ``round_to_posit``    : the single rounding the paper delegates to the Posit
+                          Standard (Sec. 3.2): nearest, ties to the even
+                          encoding, never to zero or NaR.  Two independent
+                          formulations, ``round_constructive`` and
+                          ``round_by_search``, must agree.
+* ``quire_*`` / ``gemm``: Sec. 2 (quire = exact sum of products) and Sec. 3.3
+                          (quire accumulation in matrix products and
+                          convolutions, one rounding at the end).
+* ``conv2d_*``          : Sec. 3.1 (layers inherit LibTorch semantics:
+                          cross-correlation, NCHW / OIHW, zero padding) and its
+                          two adjoints, which the framework writes by hand
+                          because it has no automatic differentiation.
+* ``from_float`` / ``to_float`` / ``convert``: Fig. 2 utilities (tensor
+                          conversion, copies of a tensor in several formats).
+* ``axpy``              : Fig. 2 optimizer (SGD), y <- round(y + alpha*x).
+
+Readings of points the paper leaves open (all listed in the design notes):
+the quire is a Q-bit two's-complement integer whose unit is minpos^2 and which
+wraps modulo 2^Q; NaR is absorbing; a bias is added inside the quire; missing
+exponent bits read as zero.
+
+Parity pins: every function here is pinned by tests that do not reuse its own
+formula (exhaustive round trips, encodings fixed by the definition, Table 1's
+dot-product limits, brute-force rational sums, integer matmul and float64
+library convolutions for posit<8,0>).  The choices "bias inside the quire",
+"one quire over the whole batch reduction" and "single rounding in the SGD
+update" cannot be pinned to the paper's own framework: parity unpinned for
+those three readings (the definition here is the contract).
+"""
+
+from fractions import Fraction
+import math
+
+
+class _NaRType:
+    """Not-a-Real: the pattern 10...0."""
+
+    _inst = None
+
+    def __new__(cls):
+        if cls._inst is None:
+            cls._inst = super().__new__(cls)
+        return cls._inst
+
+    def __repr__(self):
+        return "NaR"
+
+
+NaR = _NaRType()
+
+
+class PositFormat:
+    """posit<n, es> with its quire (Table 1)."""
+
+    def __init__(self, n, es, quire_bits):
+        self.n = n
+        self.es = es
+        self.quire_bits = quire_bits
+        self.mask = (1 << n) - 1
+        self.nar = 1 << (n - 1)
+        self.useed = 2 ** (2 ** es)
+        # maxpos = useed^(n-2); minpos = 1/maxpos  (Table 1, "dynamic range")
+        self.max_scale = (n - 2) * (2 ** es)
+        self.maxpos = Fraction(2) ** self.max_scale
+        self.minpos = 1 / self.maxpos
+        self.maxpos_pattern = self.nar - 1
+        self.minpos_pattern = 1
+        # unit of the quire's least significant bit
+        self.quire_unit = self.minpos * self.minpos
+
+    def __repr__(self):
+        return "posit<%d,%d>" % (self.n, self.es)
+
+
+P8 = PositFormat(8, 0, 32)
+P16 = PositFormat(16, 1, 128)
+P32 = PositFormat(32, 2, 512)
+FORMATS = {"p8": P8, "p16": P16, "p32": P32}
+
+
+# --------------------------------------------------------------------------
+# decode (Eq. 2)
+# --------------------------------------------------------------------------
+
+def decode(p, fmt):
+    """Pattern -> exact value as a Fraction, or NaR."""
+    n, es = fmt.n, fmt.es
+    p &= fmt.mask
+    if p == 0:
+        return Fraction(0)
+    if p == fmt.nar:
+        return NaR
+    negative = (p >> (n - 1)) & 1
+    if negative:
+        p = (-p) & fmt.mask  # two's complement before reading the fields
+    bits = [(p >> i) & 1 for i in range(n - 2, -1, -1)]  # below the sign, MSB first
+    r = bits[0]
+    m = 1
+    while m < len(bits) and bits[m] == r:
+        m += 1
+    k = (m - 1) if r == 1 else -m
+    rest = bits[m + 1:]  # drop the bit that ended the run, if there was room for it
+    exp_bits = rest[:es]
+    exp_bits = exp_bits + [0] * (es - len(exp_bits))  # truncated exponent bits are zeros
+    e = 0
+    for b in exp_bits:
+        e = 2 * e + b
+    frac_bits = rest[es:]
+    f_num = 0
+    for b in frac_bits:
+        f_num = 2 * f_num + b
+    f = Fraction(f_num, 2 ** len(frac_bits))
+    value = Fraction(2) ** ((2 ** es) * k + e) * (1 + f)
+    return -value if negative else value
+
+
+_tables = {}
+
+
+def decode_table(fmt):
+    """All 2^n decoded values (n <= 16 only); built by calling ``decode``."""
+    key = (fmt.n, fmt.es)
+    if key not in _tables:
+        if fmt.n > 16:
+            raise ValueError("table only for n <= 16")
+        _tables[key] = [decode(p, fmt) for p in range(1 << fmt.n)]
+    return _tables[key]
+
+
+def _value(p, fmt):
+    p = int(p) & fmt.mask
+    if fmt.n <= 16:
+        return decode_table(fmt)[p]
+    return decode(p, fmt)
+
+
+def to_minpos_units(p, fmt):
+    """Integer v with value = v * minpos (every posit is such a multiple), or NaR."""
+    v = _value(p, fmt)
+    if v is NaR:
+        return NaR
+    u = v / fmt.minpos
+    assert u.denominator == 1
+    return u.numerator
+
+
+# --------------------------------------------------------------------------
+# rounding: exact rational -> posit<n,es>
+# --------------------------------------------------------------------------
+
+def _floor_log2(x):
+    """floor(log2(x)) for a positive Fraction."""
+    s = x.numerator.bit_length() - x.denominator.bit_length()
+    if Fraction(2) ** s > x:
+        s -= 1
+    assert Fraction(2) ** s <= x < Fraction(2) ** (s + 1)
+    return s
+
+
+def round_constructive(x, fmt):
+    """Write out regime | exponent | fraction, keep n-1 bits, nearest-even."""
+    x = Fraction(x)
+    n, es = fmt.n, fmt.es
+    if x == 0:
+        return 0
+    negative = x < 0
+    a = -x if negative else x
+    if a >= fmt.maxpos:
+        body = fmt.maxpos_pattern
+    elif a <= fmt.minpos:
+        body = fmt.minpos_pattern
+    else:
+        scale = _floor_log2(a)
+        f = a / Fraction(2) ** scale - 1  # in [0, 1)
+        k = scale >> es  # floor division
+        e = scale - (k << es)
+        if k >= 0:
+            regime = ((1 << (k + 1)) - 1) << 1  # k+1 ones, then a zero
+            rlen = k + 2
+        else:
+            regime = 1  # -k zeros, then a one
+            rlen = -k + 1
+        prefix = (regime << es) | e
+        plen = rlen + es
+        keep = n - 1
+        # the unbounded string, read as a binary number with `keep` integer bits
+        exact = (prefix + f) * Fraction(2) ** (keep - plen)
+        body = exact.numerator // exact.denominator
+        rem = exact - body
+        if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (body & 1)):
+            body += 1
+        assert 1 <= body <= fmt.maxpos_pattern
+    return (-body) & fmt.mask if negative else body
+
+
+def round_by_search(x, fmt):
+    """Find the two neighbouring patterns; their midpoint is the (n+1)-bit posit between."""
+    x = Fraction(x)
+    if x == 0:
+        return 0
+    negative = x < 0
+    a = -x if negative else x
+    if a >= fmt.maxpos:
+        body = fmt.maxpos_pattern
+    elif a <= fmt.minpos:
+        body = fmt.minpos_pattern
+    else:
+        lo, hi = 1, fmt.maxpos_pattern  # decode(lo) < a < decode(hi), patterns are monotone
+        while hi - lo > 1:
+            mid = (lo + hi) // 2
+            vm = decode(mid, fmt)
+            if vm == a:
+                lo = hi = mid
+                break
+            if vm < a:
+                lo = mid
+            else:
+                hi = mid
+        if lo == hi:
+            body = lo
+        else:
+            wider = PositFormat(fmt.n + 1, fmt.es, 0)
+            midpoint = decode(2 * lo + 1, wider)
+            if a < midpoint:
+                body = lo
+            elif a > midpoint:
+                body = hi
+            else:
+                body = lo if (lo & 1) == 0 else hi
+    return (-body) & fmt.mask if negative else body
+
+
+def round_to_posit(x, fmt):
+    """The rounding every result goes through exactly once."""
+    if x is NaR:
+        return fmt.nar
+    return round_constructive(x, fmt)
+
+
+# --------------------------------------------------------------------------
+# quire: exact sum of products, Q-bit two's complement in units of minpos^2
+# --------------------------------------------------------------------------
+
+def quire_wrap(total, fmt):
+    """Reduce an exact integer (units of minpos^2) to the Q-bit signed range."""
+    q = fmt.quire_bits
+    t = total & ((1 << q) - 1)
+    if t >> (q - 1):
+        t -= 1 << q
+    return t
+
+
+def quire_fits(total, fmt):
+    q = fmt.quire_bits
+    return -(1 << (q - 1)) <= total <= (1 << (q - 1)) - 1
+
+
+def quire_round(total, fin, fout):
+    """Wrapped quire integer -> posit in fout."""
+    return round_to_posit(Fraction(quire_wrap(total, fin)) * fin.quire_unit, fout)
+
+
+def quire_dot(a, b, fin, bias=None):
+    """Exact sum_k a[k]*b[k] (+ bias*1) as an integer in units of minpos^2, or NaR."""
+    total = 0
+    nar = False
+    for pa, pb in zip(a, b):
+        ua = to_minpos_units(pa, fin)
+        ub = to_minpos_units(pb, fin)
+        if ua is NaR or ub is NaR:
+            nar = True
+            continue
+        total += ua * ub
+    if bias is not None:
+        ubias = to_minpos_units(bias, fin)
+        if ubias is NaR:
+            nar = True
+        else:
+            total += ubias * (1 << fin.max_scale)  # bias times the value one
+    return NaR if nar else total
+
+
+def dot(a, b, fin, fout, bias=None):
+    t = quire_dot(a, b, fin, bias)
+    if t is NaR:
+        return fout.nar
+    return quire_round(t, fin, fout)
+
+
+def gemm(A, B, fin, fout, trans_a=False, trans_b=False, bias=None):
+    """C[i][j] = round_fout( sum_k op(A)[i][k] * op(B)[k][j] (+ bias[j]) ).
+
+    A, B are lists of rows of patterns (as stored, before op()).  Returns rows.
+    """
+    if trans_a:
+        A = [list(r) for r in zip(*A)] if A and A[0] else []
+    Bt = B if trans_b else ([list(r) for r in zip(*B)] if B and len(B[0]) else [])
+    # Bt[j] is column j of op(B)
+    C = []
+    for i in range(len(A)):
+        row = []
+        for j in range(len(Bt)):
+            row.append(dot(A[i], Bt[j], fin, fout, None if bias is None else bias[j]))
+        C.append(row)
+    return C
+
+
+# --------------------------------------------------------------------------
+# convolution (cross-correlation, NCHW / OIHW, zero padding, stride) and adjoints
+# --------------------------------------------------------------------------
+
+class ConvShape:
+    def __init__(self, N, C, H, W, K, R, S, pad_h=0, pad_w=0, stride_h=1, stride_w=1):
+        self.N, self.C, self.H, self.W = N, C, H, W
+        self.K, self.R, self.S = K, R, S
+        self.pad_h, self.pad_w = pad_h, pad_w
+        self.stride_h, self.stride_w = stride_h, stride_w
+        self.OH = (H + 2 * pad_h - R) // stride_h + 1
+        self.OW = (W + 2 * pad_w - S) // stride_w + 1
+
+
+def _units_list(flat, fmt):
+    return [to_minpos_units(p, fmt) for p in flat]
+
+
+def conv2d_fwd_quire(x, w, sh, fin, bias=None):
+    """Exact y[n][k][oh][ow] = sum_{c,r,s} x[n][c][oh*sh+r-ph][ow*sw+s-pw] * w[k][c][r][s] (+bias[k]).
+
+    x, w, bias are flat sequences of patterns (NCHW, OIHW).  Returns a flat list
+    of integers in units of minpos^2 (or NaR).
+    """
+    xu = _units_list(x, fin)
+    wu = _units_list(w, fin)
+    bu = None if bias is None else _units_list(bias, fin)
+    one = 1 << fin.max_scale
+    out = []
+    for n in range(sh.N):
+        for k in range(sh.K):
+            for oh in range(sh.OH):
+                for ow in range(sh.OW):
+                    total = 0
+                    nar = False
+                    for c in range(sh.C):
+                        for r in range(sh.R):
+                            ih = oh * sh.stride_h + r - sh.pad_h
+                            if ih < 0 or ih >= sh.H:
+                                continue
+                            for s in range(sh.S):
+                                iw = ow * sh.stride_w + s - sh.pad_w
+                                if iw < 0 or iw >= sh.W:
+                                    continue
+                                a = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw]
+                                b = wu[((k * sh.C + c) * sh.R + r) * sh.S + s]
+                                if a is NaR or b is NaR:
+                                    nar = True
+                                else:
+                                    total += a * b
+                    if bu is not None:
+                        if bu[k] is NaR:
+                            nar = True
+                        else:
+                            total += bu[k] * one
+                    out.append(NaR if nar else total)
+    return out
+
+
+def conv2d_bwd_data_quire(dy, w, sh, fin):
+    """Exact dx[n][c][h][w] = sum over (k,r,s,oh,ow) with oh*sh+r-ph == h, ow*sw+s-pw == w of dy*w."""
+    dyu = _units_list(dy, fin)
+    wu = _units_list(w, fin)
+    out = []
+    for n in range(sh.N):
+        for c in range(sh.C):
+            for h in range(sh.H):
+                for ww in range(sh.W):
+                    total = 0
+                    nar = False
+                    for k in range(sh.K):
+                        for r in range(sh.R):
+                            t = h + sh.pad_h - r
+                            if t < 0 or t % sh.stride_h:
+                                continue
+                            oh = t // sh.stride_h
+                            if oh >= sh.OH:
+                                continue
+                            for s in range(sh.S):
+                                u = ww + sh.pad_w - s
+                                if u < 0 or u % sh.stride_w:
+                                    continue
+                                ow = u // sh.stride_w
+                                if ow >= sh.OW:
+                                    continue
+                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow]
+                                b = wu[((k * sh.C + c) * sh.R + r) * sh.S + s]
+                                if a is NaR or b is NaR:
+                                    nar = True
+                                else:
+                                    total += a * b
+                    out.append(NaR if nar else total)
+    return out
+
+
+def conv2d_bwd_weight_quire(dy, x, sh, fin):
+    """Exact dw[k][c][r][s] = sum_{n,oh,ow} dy[n][k][oh][ow] * x[n][c][oh*sh+r-ph][ow*sw+s-pw]."""
+    dyu = _units_list(dy, fin)
+    xu = _units_list(x, fin)
+    out = []
+    for k in range(sh.K):
+        for c in range(sh.C):
+            for r in range(sh.R):
+                for s in range(sh.S):
+                    total = 0
+                    nar = False
+                    for n in range(sh.N):
+                        for oh in range(sh.OH):
+                            ih = oh * sh.stride_h + r - sh.pad_h
+                            if ih < 0 or ih >= sh.H:
+                                continue
+                            for ow in range(sh.OW):
+                                iw = ow * sh.stride_w + s - sh.pad_w
+                                if iw < 0 or iw >= sh.W:
+                                    continue
+                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow]
+                                b = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw]
+                                if a is NaR or b is NaR:
+                                    nar = True
+                                else:
+                                    total += a * b
+                    out.append(NaR if nar else total)
+    return out
+
+
+def conv2d_bias_grad_quire(dy, sh, fin):
+    """Exact dbias[k] = sum_{n,oh,ow} dy[n][k][oh][ow] * 1."""
+    dyu = _units_list(dy, fin)
+    one = 1 << fin.max_scale
+    out = []
+    for k in range(sh.K):
+        total = 0
+        nar = False
+        for n in range(sh.N):
+            for i in range(sh.OH * sh.OW):
+                a = dyu[(n * sh.K + k) * sh.OH * sh.OW + i]
+                if a is NaR:
+                    nar = True
+                else:
+                    total += a * one
+        out.append(NaR if nar else total)
+    return out
+
+
+def _round_quires(qs, fin, fout):
+    return [fout.nar if t is NaR else quire_round(t, fin, fout) for t in qs]
+
+
+def conv2d_fwd(x, w, sh, fin, fout, bias=None):
+    return _round_quires(conv2d_fwd_quire(x, w, sh, fin, bias), fin, fout)
+
+
+def conv2d_bwd_data(dy, w, sh, fin, fout):
+    return _round_quires(conv2d_bwd_data_quire(dy, w, sh, fin), fin, fout)
+
+
+def conv2d_bwd_weight(dy, x, sh, fin, fout):
+    return _round_quires(conv2d_bwd_weight_quire(dy, x, sh, fin), fin, fout)
+
+
+def conv2d_bias_grad(dy, sh, fin, fout):
+    return _round_quires(conv2d_bias_grad_quire(dy, sh, fin), fin, fout)
+
+
+# --------------------------------------------------------------------------
+# conversions
+# --------------------------------------------------------------------------
+
+def from_float(x, fmt):
+    """IEEE value (a Python float holding the f32/f64 exactly) -> posit; NaN, +-Inf -> NaR."""
+    x = float(x)
+    if math.isnan(x) or math.isinf(x):
+        return fmt.nar
+    return round_to_posit(Fraction(x), fmt)  # Fraction(float) is exact; -0.0 -> 0
+
+
+def ieee_round(x, precision, emin):
+    """Exact rational -> nearest-even binary float with `precision` significand bits
+    and minimum normal exponent `emin` (subnormals below).  Returns a Fraction."""
+    x = Fraction(x)
+    if x == 0:
+        return Fraction(0)
+    negative = x < 0
+    a = -x if negative else x
+    e = max(_floor_log2(a), emin)
+    ulp = Fraction(2) ** (e - (precision - 1))
+    q = a / ulp
+    body = q.numerator // q.denominator
+    rem = q - body
+    if rem > Fraction(1, 2) or (rem == Fraction(1, 2) and (body & 1)):
+        body += 1
+    r = body * ulp
+    return -r if negative else r
+
+
+def to_float(p, fmt, kind="f64"):
+    """posit -> IEEE binary32 / binary64 value (as a Python float); NaR -> NaN.
+
+    All three standard formats fit both IEEE types without overflow, so only
+    the significand rounding of ieee_round matters."""
+    v = _value(p, fmt)
+    if v is NaR:
+        return float("nan")
+    if kind == "f32":
+        r = ieee_round(v, 24, -126)
+    elif kind == "f64":
+        r = ieee_round(v, 53, -1022)
+    else:
+        raise ValueError(kind)
+    out = r.numerator / r.denominator  # exact: r is representable
+    assert Fraction(out) == r
+    return out
+
+
+def convert(p, fsrc, fdst):
+    """posit<a> -> posit<b>: round the exact value once."""
+    return round_to_posit(_value(p, fsrc), fdst)
+
+
+# --------------------------------------------------------------------------
+# axpy (SGD update): y <- round(y + alpha * x)
+# --------------------------------------------------------------------------
+
+def axpy(alpha, x, y, fx, fy, fcopy=None):
+    """alpha and y are patterns in fy, x in fx.  Exact inside, one rounding.
+
+    Returns new y, or (new y, narrowed copy of new y in fcopy)."""
+    va = _value(alpha, fy)
+    vx = _value(x, fx)
+    vy = _value(y, fy)
+    if va is NaR or vx is NaR or vy is NaR:
+        ynew = fy.nar
+    else:
+        ynew = round_to_posit(vy + va * vx, fy)
+    if fcopy is None:
+        return ynew
+    return ynew, convert(ynew, fy, fcopy)
