@@ -1,0 +1,138 @@
+/* positnn.h - C ABI of the quire-exact posit library for AMD MI355X (gfx950).
+ *
+ * The library implements the hot path of posit neural-network training as
+ * described in "PositNN: Training Deep Neural Networks with Mixed Low-Precision
+ * Posit" (arXiv 2105.00053): every matrix product and convolution (forward,
+ * backward-data, backward-weight) is a set of dot products whose operands are
+ * posit<n,es> numbers (Sec. 2, Eq. 2), whose products are accumulated without
+ * any rounding in a quire (Sec. 2; widths in Table 1) and which are rounded to a
+ * posit exactly once at the end (Sec. 3.3, "option to use quires for the
+ * accumulations").  Around it sit the bandwidth-bound helpers of Fig. 2:
+ * tensor conversion, copies of a tensor in several posit formats, and the SGD
+ * weight update.
+ *
+ * General conventions
+ *  - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *    never allocates, frees or keeps device memory and has no mutable global
+ *    state; calls are asynchronous on `stream` (a hipStream_t passed as void*,
+ *    NULL = the default stream).
+ *  - posit<8,0> / <16,1> / <32,2> elements are stored as uint8 / uint16 / uint32
+ *    bit patterns; PNN_F32 / PNN_F64 are IEEE binary32 / binary64.
+ *  - Outputs must not alias inputs, except `y` of posit_axpy (updated in place).
+ *  - Every function returns a pnn_status.  Invalid arguments (null pointer,
+ *    negative size, leading dimension too small, unknown format) give
+ *    PNN_EINVAL and nothing is launched; a format combination that is not
+ *    built gives PNN_EUNSUPPORTED; a workspace smaller than the matching
+ *    *_workspace() query gives PNN_EWORKSPACE; a HIP launch error gives
+ *    PNN_EHIP.  Zero-sized problems return PNN_OK and touch nothing.
+ *  - Special values: the pattern 10...0 (NaR) in any operand that takes part in
+ *    an output makes that output NaR, also when it is multiplied by zero.
+ *  - The quire of format `fin` is a two's-complement integer of 32 / 128 / 512
+ *    bits (Table 1) whose unit is minpos^2; it wraps modulo 2^bits if a sum ever
+ *    leaves that range (Table 1 guarantees 127 / 32767 / 2^31-1 products).
+ */
+#ifndef POSITNN_H
+#define POSITNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PNN_POSIT8_0 = 0,  /* posit<8,0>,  uint8  storage, 32-bit quire  (Table 1) */
+    PNN_POSIT16_1 = 1, /* posit<16,1>, uint16 storage, 128-bit quire (Table 1) */
+    PNN_POSIT32_2 = 2, /* posit<32,2>, uint32 storage, 512-bit quire (Table 1) */
+    PNN_F32 = 100,     /* IEEE binary32: posit_round / posit_convert only */
+    PNN_F64 = 101      /* IEEE binary64: posit_round / posit_convert only */
+} pnn_dtype;
+
+typedef enum {
+    PNN_OK = 0,
+    PNN_EINVAL = 1,
+    PNN_EUNSUPPORTED = 2,
+    PNN_EWORKSPACE = 3,
+    PNN_EHIP = 4
+} pnn_status;
+
+/* Quire-exact matrix product (Sec. 3.3; Linear layer forward, backward-data and
+ * backward-weight are its three transposition cases, Sec. 3.1):
+ *
+ *   C[i,j] = round_fout( sum_k op(A)[i,k] * op(B)[k,j]  (+ bias[j]) ),  i < M, j < N
+ *
+ * op(X) = X or X^T (transX != 0).  All matrices are row-major as stored; lda,
+ * ldb, ldc are row pitches in elements (lda >= K, or >= M when transA; ldb >= N,
+ * or >= K when transB; ldc >= N).  A, B and bias (length N, may be NULL) are in
+ * format `fin`, which also fixes the quire; C is in `fout`.  The sum is exact,
+ * the bias enters the quire as bias*1, and one rounding (nearest, ties to the
+ * even pattern, never to zero or NaR) produces C.  K == 0 gives the rounded
+ * bias (or zero).  `workspace` (device, 16-byte aligned) must hold at least
+ * posit_gemm_workspace(...) bytes; it may be NULL when that query returns 0. */
+int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
+               int64_t M, int64_t N, int64_t K,
+               const void* A, int64_t lda, const void* B, int64_t ldb,
+               const void* bias, void* C, int64_t ldc,
+               void* workspace, size_t workspace_bytes);
+
+/* Bytes of device workspace posit_gemm wants for this problem (0 = none). */
+size_t posit_gemm_workspace(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K);
+
+/* 2-D convolution geometry (Sec. 3.1: layers follow LibTorch semantics):
+ * cross-correlation, activations NCHW, weights [K][C][R][S], zero padding,
+ * dilation 1, one group.  Output size OH = (H + 2*pad_h - R) / stride_h + 1. */
+typedef struct {
+    int64_t N, C, H, W; /* input batch, channels, height, width */
+    int64_t K, R, S;    /* output channels, kernel height, kernel width */
+    int64_t pad_h, pad_w, stride_h, stride_w;
+} pnn_conv2d_desc;
+
+/* y[n,k,oh,ow] = round_fout( sum_{c,r,s} x[n,c,oh*stride_h+r-pad_h,ow*stride_w+s-pad_w] * w[k,c,r,s] (+ bias[k]) )
+ * taps outside the image contribute exact zeros.  x, w, bias (nullable) in fin; y in fout. */
+int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                     const void* x, const void* w, const void* bias, void* y,
+                     void* workspace, size_t workspace_bytes);
+
+/* Adjoint with respect to x: dx[n,c,h,w] = round_fout( sum of dy[n,k,oh,ow] * w[k,c,r,s]
+ * over all (k,r,s,oh,ow) with oh*stride_h+r-pad_h == h and ow*stride_w+s-pad_w == w ). */
+int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                          const void* dy, const void* w, void* dx,
+                          void* workspace, size_t workspace_bytes);
+
+/* Adjoint with respect to w: dw[k,c,r,s] = round_fout( sum_{n,oh,ow} dy[n,k,oh,ow] *
+ * x[n,c,oh*stride_h+r-pad_h,ow*stride_w+s-pad_w] ): ONE quire over the whole
+ * batch, one rounding.  dbias (nullable) receives round_fout( sum_{n,oh,ow} dy[n,k,oh,ow] ). */
+int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                            const void* dy, const void* x, void* dw, void* dbias,
+                            void* workspace, size_t workspace_bytes);
+
+/* which: 0 = fwd, 1 = bwd_data, 2 = bwd_weight.  Bytes of workspace (0 = none). */
+size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
+
+/* Float tensor -> posit tensor (Fig. 2, tensor conversion): dst[i] = round_dst(src[i]),
+ * src_float in {PNN_F32, PNN_F64}.  NaN and +-Inf give NaR, -0.0 gives 0,
+ * nonzero values never round to zero (they clamp to +-minpos / +-maxpos). */
+int posit_round(void* stream, int src_float, int dst_posit, int64_t n, const void* src, void* dst);
+
+/* posit -> posit of another format (one rounding; exact when widening
+ * <8,0> -> <16,1> -> <32,2>), or posit -> PNN_F32 / PNN_F64 (exact, except
+ * posit<32,2> -> binary32 which rounds to nearest even; NaR gives NaN). */
+int posit_convert(void* stream, int src, int dst, int64_t n, const void* src_ptr, void* dst_ptr);
+
+/* SGD-style update (Fig. 2, optimizer): y[i] = round_fy( y[i] + alpha * x[i] ),
+ * exact inside, one rounding.  alpha_bits is a posit pattern of format fy (for
+ * SGD: the rounded value of -learning_rate); x is in fx, y in fy (in place).
+ * When y_copy is not NULL it receives round_fcopy(new y[i]): the narrow copy
+ * of the weights that the compute kernels read (Sec. 3.3).  fcopy is ignored
+ * when y_copy is NULL. */
+int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int64_t n,
+               const void* x, void* y, int fcopy, void* y_copy);
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* posit_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POSITNN_H */

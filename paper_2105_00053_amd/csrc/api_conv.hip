@@ -1,0 +1,178 @@
+// posit_conv2d_fwd / bwd_data / bwd_weight: quire-exact convolution and its two
+// adjoints (paper Sec. 3.1: layers follow LibTorch semantics and the backward
+// passes are written by hand; Sec. 3.3: quire accumulation in convolutions).
+// Each is an implicit GEMM over the tiled quire kernel:
+//   fwd        rows (n,oh,ow)  x cols k          reduce over (c,r,s)
+//   bwd_data   rows (n,h,w)    x cols c          reduce over (k,r,s)
+//   bwd_weight rows k          x cols (c,r,s)    reduce over (n,oh,ow)
+#include "api_common.h"
+#include "quire_gemm.h"
+
+namespace pnn {
+
+template <class F> struct ConvTile;
+template <> struct ConvTile<P8> { static constexpr int TM = 4, TN = 4; };
+template <> struct ConvTile<P16> { static constexpr int TM = 4, TN = 4; };
+template <> struct ConvTile<P32> { static constexpr int TM = 2, TN = 2; };
+
+inline bool conv_geom(const pnn_conv2d_desc* d, ConvGeom* g) {
+    if (!d) return false;
+    if (d->N < 0 || d->C < 0 || d->H <= 0 || d->W <= 0 || d->K < 0 || d->R <= 0 || d->S <= 0) return false;
+    if (d->pad_h < 0 || d->pad_w < 0 || d->stride_h <= 0 || d->stride_w <= 0) return false;
+    if (d->H + 2 * d->pad_h < d->R || d->W + 2 * d->pad_w < d->S) return false;
+    const int64_t lim = (int64_t)1 << 30;
+    if (d->N >= lim || d->C >= lim || d->H >= lim || d->W >= lim || d->K >= lim || d->R >= lim || d->S >= lim) return false;
+    g->N = (int)d->N; g->C = (int)d->C; g->H = (int)d->H; g->W = (int)d->W;
+    g->K = (int)d->K; g->R = (int)d->R; g->S = (int)d->S;
+    g->ph = (int)d->pad_h; g->pw = (int)d->pad_w; g->sh = (int)d->stride_h; g->sw = (int)d->stride_w;
+    g->OH = (int)((d->H + 2 * d->pad_h - d->R) / d->stride_h + 1);
+    g->OW = (int)((d->W + 2 * d->pad_w - d->S) / d->stride_w + 1);
+    // every index the kernels form must fit 31 bits
+    if ((int64_t)g->C * g->R * g->S >= lim || (int64_t)g->K * g->R * g->S >= lim) return false;
+    if ((int64_t)g->N * g->OH * g->OW >= lim || (int64_t)g->N * g->H * g->W >= lim) return false;
+    return true;
+}
+
+struct ConvDims {
+    int64_t M, N, K;
+};
+
+inline ConvDims conv_dims(int which, const ConvGeom& g) {
+    ConvDims d;
+    if (which == 0) { d.M = (int64_t)g.N * g.OH * g.OW; d.N = g.K; d.K = (int64_t)g.C * g.R * g.S; }
+    else if (which == 1) { d.M = (int64_t)g.N * g.H * g.W; d.N = g.C; d.K = (int64_t)g.K * g.R * g.S; }
+    else { d.M = g.K; d.N = (int64_t)g.C * g.R * g.S; d.K = (int64_t)g.N * g.OH * g.OW; }
+    return d;
+}
+
+template <class F>
+GemmPlan conv_plan(const ConvDims& d) {
+    return plan_split(d.M, d.N, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
+}
+
+// bias-gradient row sum: M = K channels, one column, same reduction as bwd_weight
+template <class F>
+GemmPlan dbias_plan(const ConvDims& d) {
+    return plan_split(d.M, 1, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
+}
+
+template <class F>
+size_t conv_ws(int which, const ConvGeom& g) {
+    const ConvDims d = conv_dims(which, g);
+    if (d.M <= 0 || d.N <= 0) return 0;
+    size_t b = conv_plan<F>(d).ws_bytes;
+    if (which == 2) {
+        const size_t b2 = dbias_plan<F>(d).ws_bytes;
+        if (b2 > b) b = b2;
+    }
+    return b;
+}
+
+template <class F>
+int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const void* w, const void* bias, void* y,
+             void* ws, size_t ws_bytes) {
+    typedef typename Storage<F::N>::T T;
+    const ConvDims d = conv_dims(0, g);
+    const GemmPlan plan = conv_plan<F>(d);
+    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+    ConvFwdX<T> a{(const T*)x, g, d.M, d.K};
+    MatrixOperand<T, true> b{(const T*)w, d.K, d.N, d.K};
+    NchwOut out{(int64_t)g.OH * g.OW, (int64_t)g.K};
+    return hip_status(launch_quire_gemm<F, decltype(a), decltype(b), NchwOut, ConvTile<F>::TM, ConvTile<F>::TN>(
+        st, a, b, out, d.M, d.N, d.K, bias, y, fout, ws, plan));
+}
+
+template <class F>
+int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
+    typedef typename Storage<F::N>::T T;
+    const ConvDims d = conv_dims(1, g);
+    const GemmPlan plan = conv_plan<F>(d);
+    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+    ConvBwdDataDy<T> a{(const T*)dy, g, d.M, d.K};
+    ConvBwdDataW<T> b{(const T*)w, g, d.N, d.K};
+    NchwOut out{(int64_t)g.H * g.W, (int64_t)g.C};
+    return hip_status(launch_quire_gemm<F, decltype(a), decltype(b), NchwOut, ConvTile<F>::TM, ConvTile<F>::TN>(
+        st, a, b, out, d.M, d.N, d.K, nullptr, dx, fout, ws, plan));
+}
+
+template <class F>
+int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* x, void* dw, void* dbias,
+                    void* ws, size_t ws_bytes) {
+    typedef typename Storage<F::N>::T T;
+    const ConvDims d = conv_dims(2, g);
+    const GemmPlan plan = conv_plan<F>(d);
+    const GemmPlan bplan = dbias_plan<F>(d);
+    const size_t need = (dbias && bplan.ws_bytes > plan.ws_bytes) ? bplan.ws_bytes : plan.ws_bytes;
+    if (need > 0 && (!ws || ws_bytes < need)) return PNN_EWORKSPACE;
+    ConvBwdWeightDy<T> a{(const T*)dy, g, d.M, d.K};
+    ConvBwdWeightX<T> b{(const T*)x, g, d.N, d.K};
+    RowMajorOut out{d.N};
+    hipError_t e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
+        st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
+    if (e == hipSuccess && dbias) {
+        // dbias[k] = sum dy[n,k,:,:] * 1 : the same kernel against a column of ones
+        // (stream order keeps the shared workspace safe)
+        OnesOperand ones{1u << (F::N - 2), 1, d.K};
+        RowMajorOut bout{1};
+        e = launch_quire_gemm<F, decltype(a), OnesOperand, RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
+            st, a, ones, bout, d.M, 1, d.K, nullptr, dbias, fout, ws, bplan);
+    }
+    return hip_status(e);
+}
+
+}  // namespace pnn
+
+using namespace pnn;
+
+extern "C" size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc) {
+    (void)fout;
+    ConvGeom g;
+    if (which < 0 || which > 2 || !is_posit(fin) || !conv_geom(desc, &g)) return 0;
+    switch (fin) {
+        case PNN_POSIT8_0: return conv_ws<P8>(which, g);
+        case PNN_POSIT16_1: return conv_ws<P16>(which, g);
+        default: return conv_ws<P32>(which, g);
+    }
+}
+
+extern "C" int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* x, const void* w,
+                                const void* bias, void* y, void* workspace, size_t workspace_bytes) {
+    ConvGeom g;
+    if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
+    if (g.N == 0 || g.K == 0) return PNN_OK;
+    if (!y || (g.C > 0 && (!x || !w))) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fin) {
+        case PNN_POSIT8_0: return conv_fwd<P8>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
+        case PNN_POSIT16_1: return conv_fwd<P16>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
+        default: return conv_fwd<P32>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
+    }
+}
+
+extern "C" int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* dy,
+                                     const void* w, void* dx, void* workspace, size_t workspace_bytes) {
+    ConvGeom g;
+    if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
+    if (g.N == 0 || g.C == 0) return PNN_OK;
+    if (!dx || (g.K > 0 && (!dy || !w))) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fin) {
+        case PNN_POSIT8_0: return conv_bwd_data<P8>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
+        case PNN_POSIT16_1: return conv_bwd_data<P16>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
+        default: return conv_bwd_data<P32>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
+    }
+}
+
+extern "C" int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* dy,
+                                       const void* x, void* dw, void* dbias, void* workspace, size_t workspace_bytes) {
+    ConvGeom g;
+    if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
+    if (g.K == 0 || g.C == 0) return PNN_OK;
+    if (!dw || (g.N > 0 && (!dy || !x))) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fin) {
+        case PNN_POSIT8_0: return conv_bwd_weight<P8>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
+        case PNN_POSIT16_1: return conv_bwd_weight<P16>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
+        default: return conv_bwd_weight<P32>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
+    }
+}

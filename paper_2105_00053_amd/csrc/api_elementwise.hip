@@ -1,0 +1,202 @@
+// posit_round, posit_convert, posit_axpy: the bandwidth-bound entry points
+// (paper Fig. 2: tensor conversion, mixed-precision copies, SGD).  One thread
+// handles a short vector of consecutive elements so that the widest type moves
+// 16 bytes per access; a scalar kernel covers unaligned pointers and the tail.
+#include "api_common.h"
+#include "elementwise_ops.h"
+
+namespace pnn {
+
+template <class T, int V>
+struct alignas(sizeof(T) * V) Pack {
+    T v[V];
+};
+
+template <class TS, class TD, int V, class Op>
+__global__ __launch_bounds__(256) void map_vec_kernel(const TS* __restrict__ src, TD* __restrict__ dst, int64_t nvec, Op op) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nvec) return;
+    const Pack<TS, V> in = reinterpret_cast<const Pack<TS, V>*>(src)[i];
+    Pack<TD, V> o;
+#pragma unroll
+    for (int j = 0; j < V; ++j) o.v[j] = (TD)op((uint64_t)in.v[j]);
+    reinterpret_cast<Pack<TD, V>*>(dst)[i] = o;
+}
+
+template <class TS, class TD, class Op>
+__global__ __launch_bounds__(256) void map_scalar_kernel(const TS* __restrict__ src, TD* __restrict__ dst, int64_t begin, int64_t n, Op op) {
+    const int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    dst[i] = (TD)op((uint64_t)src[i]);
+}
+
+template <class TS, class TD, class Op>
+int launch_map(hipStream_t st, const void* src, void* dst, int64_t n, Op op) {
+    constexpr int WIDE = sizeof(TS) > sizeof(TD) ? sizeof(TS) : sizeof(TD);
+    constexpr int V = 16 / WIDE;
+    int64_t done = 0;
+    if (aligned(src, sizeof(TS) * V) && aligned(dst, sizeof(TD) * V)) {
+        const int64_t nvec = n / V;
+        if (nvec > 0) {
+            hipLaunchKernelGGL((map_vec_kernel<TS, TD, V, Op>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
+                               (const TS*)src, (TD*)dst, nvec, op);
+            done = nvec * V;
+        }
+    }
+    if (done < n) {
+        const int64_t rest = n - done;
+        hipLaunchKernelGGL((map_scalar_kernel<TS, TD, Op>), dim3((unsigned)((rest + 255) / 256)), dim3(256), 0, st,
+                           (const TS*)src, (TD*)dst, done, n, op);
+    }
+    return hip_status(hipGetLastError());
+}
+
+template <class TX, class TY, class TC, int V, class Op, class Cp>
+__global__ __launch_bounds__(256) void axpy_vec_kernel(const TX* __restrict__ x, TY* __restrict__ y, TC* __restrict__ yc,
+                                                       int64_t nvec, Op op, Cp cp) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nvec) return;
+    const Pack<TX, V> xv = reinterpret_cast<const Pack<TX, V>*>(x)[i];
+    Pack<TY, V> yv = reinterpret_cast<Pack<TY, V>*>(y)[i];
+    Pack<TC, V> cv;
+#pragma unroll
+    for (int j = 0; j < V; ++j) {
+        const uint32_t r = op((uint32_t)xv.v[j], (uint32_t)yv.v[j]);
+        yv.v[j] = (TY)r;
+        cv.v[j] = (TC)cp((uint64_t)r);
+    }
+    reinterpret_cast<Pack<TY, V>*>(y)[i] = yv;
+    if (yc) reinterpret_cast<Pack<TC, V>*>(yc)[i] = cv;
+}
+
+template <class TX, class TY, class TC, class Op, class Cp>
+__global__ __launch_bounds__(256) void axpy_scalar_kernel(const TX* __restrict__ x, TY* __restrict__ y, TC* __restrict__ yc,
+                                                          int64_t begin, int64_t n, Op op, Cp cp) {
+    const int64_t i = begin + (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t r = op((uint32_t)x[i], (uint32_t)y[i]);
+    y[i] = (TY)r;
+    if (yc) yc[i] = (TC)cp((uint64_t)r);
+}
+
+template <class FX, class FY, class FC>
+int launch_axpy(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* y, void* yc) {
+    typedef typename Storage<FX::N>::T TX;
+    typedef typename Storage<FY::N>::T TY;
+    typedef typename Storage<FC::N>::T TC;
+    constexpr int W0 = sizeof(TX) > sizeof(TY) ? sizeof(TX) : sizeof(TY);
+    constexpr int WIDE = W0 > (int)sizeof(TC) ? W0 : (int)sizeof(TC);
+    constexpr int V = 16 / WIDE;
+    Axpy<FX, FY> op;
+    op.alpha = alpha;
+    PositToPosit<FY, FC> cp;
+    int64_t done = 0;
+    if (aligned(x, sizeof(TX) * V) && aligned(y, sizeof(TY) * V) && (!yc || aligned(yc, sizeof(TC) * V))) {
+        const int64_t nvec = n / V;
+        if (nvec > 0) {
+            hipLaunchKernelGGL((axpy_vec_kernel<TX, TY, TC, V, Axpy<FX, FY>, PositToPosit<FY, FC>>),
+                               dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, (const TX*)x, (TY*)y, (TC*)yc, nvec, op, cp);
+            done = nvec * V;
+        }
+    }
+    if (done < n) {
+        const int64_t rest = n - done;
+        hipLaunchKernelGGL((axpy_scalar_kernel<TX, TY, TC, Axpy<FX, FY>, PositToPosit<FY, FC>>),
+                           dim3((unsigned)((rest + 255) / 256)), dim3(256), 0, st, (const TX*)x, (TY*)y, (TC*)yc, done, n, op, cp);
+    }
+    return hip_status(hipGetLastError());
+}
+
+template <class FX, class FY>
+int axpy_pick_copy(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* y, int fcopy, void* yc) {
+    if (!yc) return launch_axpy<FX, FY, FY>(st, alpha, n, x, y, nullptr);
+    switch (fcopy) {
+        case PNN_POSIT8_0: return launch_axpy<FX, FY, P8>(st, alpha, n, x, y, yc);
+        case PNN_POSIT16_1: return launch_axpy<FX, FY, P16>(st, alpha, n, x, y, yc);
+        case PNN_POSIT32_2: return launch_axpy<FX, FY, P32>(st, alpha, n, x, y, yc);
+    }
+    return PNN_EINVAL;
+}
+
+template <class FX>
+int axpy_pick_y(hipStream_t st, int fy, uint32_t alpha, int64_t n, const void* x, void* y, int fcopy, void* yc) {
+    switch (fy) {
+        case PNN_POSIT8_0: return axpy_pick_copy<FX, P8>(st, alpha, n, x, y, fcopy, yc);
+        case PNN_POSIT16_1: return axpy_pick_copy<FX, P16>(st, alpha, n, x, y, fcopy, yc);
+        case PNN_POSIT32_2: return axpy_pick_copy<FX, P32>(st, alpha, n, x, y, fcopy, yc);
+    }
+    return PNN_EINVAL;
+}
+
+template <class FS>
+int convert_from(hipStream_t st, int dst, int64_t n, const void* s, void* d) {
+    typedef typename Storage<FS::N>::T TS;
+    switch (dst) {
+        case PNN_POSIT8_0: return launch_map<TS, uint8_t>(st, s, d, n, PositToPosit<FS, P8>());
+        case PNN_POSIT16_1: return launch_map<TS, uint16_t>(st, s, d, n, PositToPosit<FS, P16>());
+        case PNN_POSIT32_2: return launch_map<TS, uint32_t>(st, s, d, n, PositToPosit<FS, P32>());
+        case PNN_F32: return launch_map<TS, uint32_t>(st, s, d, n, PositToF32<FS>());
+        case PNN_F64: return launch_map<TS, uint64_t>(st, s, d, n, PositToF64<FS>());
+    }
+    return PNN_EINVAL;
+}
+
+}  // namespace pnn
+
+using namespace pnn;
+
+extern "C" int posit_round(void* stream, int src_float, int dst_posit, int64_t n, const void* src, void* dst) {
+    if (!is_float(src_float) || !is_posit(dst_posit) || n < 0) return PNN_EINVAL;
+    if (n == 0) return PNN_OK;
+    if (!src || !dst) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    if (src_float == PNN_F32) {
+        switch (dst_posit) {
+            case PNN_POSIT8_0: return launch_map<uint32_t, uint8_t>(st, src, dst, n, RoundF32<P8>());
+            case PNN_POSIT16_1: return launch_map<uint32_t, uint16_t>(st, src, dst, n, RoundF32<P16>());
+            default: return launch_map<uint32_t, uint32_t>(st, src, dst, n, RoundF32<P32>());
+        }
+    }
+    switch (dst_posit) {
+        case PNN_POSIT8_0: return launch_map<uint64_t, uint8_t>(st, src, dst, n, RoundF64<P8>());
+        case PNN_POSIT16_1: return launch_map<uint64_t, uint16_t>(st, src, dst, n, RoundF64<P16>());
+        default: return launch_map<uint64_t, uint32_t>(st, src, dst, n, RoundF64<P32>());
+    }
+}
+
+extern "C" int posit_convert(void* stream, int src, int dst, int64_t n, const void* src_ptr, void* dst_ptr) {
+    if (!is_posit(src) || !(is_posit(dst) || is_float(dst)) || n < 0) return PNN_EINVAL;
+    if (n == 0) return PNN_OK;
+    if (!src_ptr || !dst_ptr) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (src) {
+        case PNN_POSIT8_0: return convert_from<P8>(st, dst, n, src_ptr, dst_ptr);
+        case PNN_POSIT16_1: return convert_from<P16>(st, dst, n, src_ptr, dst_ptr);
+        default: return convert_from<P32>(st, dst, n, src_ptr, dst_ptr);
+    }
+}
+
+extern "C" int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int64_t n, const void* x, void* y,
+                          int fcopy, void* y_copy) {
+    if (!is_posit(fx) || !is_posit(fy) || n < 0) return PNN_EINVAL;
+    if (y_copy && !is_posit(fcopy)) return PNN_EINVAL;
+    if (n == 0) return PNN_OK;
+    if (!x || !y) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fx) {
+        case PNN_POSIT8_0: return axpy_pick_y<P8>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
+        case PNN_POSIT16_1: return axpy_pick_y<P16>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
+        default: return axpy_pick_y<P32>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
+    }
+}
+
+extern "C" const char* posit_status_string(int status) {
+    switch (status) {
+        case PNN_OK: return "ok";
+        case PNN_EINVAL: return "invalid argument";
+        case PNN_EUNSUPPORTED: return "unsupported format combination";
+        case PNN_EWORKSPACE: return "workspace too small";
+        case PNN_EHIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}

@@ -1,0 +1,85 @@
+// posit_gemm: quire-exact matrix product (paper Sec. 3.3; the Linear layer's
+// forward, backward-data and backward-weight passes of Sec. 3.1 are its
+// transposition cases).
+#include "api_common.h"
+#include "quire_gemm.h"
+
+namespace pnn {
+
+template <class F> struct GemmTile;
+template <> struct GemmTile<P8> { static constexpr int TM = 4, TN = 4; };
+template <> struct GemmTile<P16> { static constexpr int TM = 4, TN = 4; };
+template <> struct GemmTile<P32> { static constexpr int TM = 2, TN = 2; };
+
+template <class F>
+GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
+    return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
+}
+
+template <class F>
+int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                  const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias, void* C, int64_t ldc,
+                  void* ws, size_t ws_bytes) {
+    typedef typename Storage<F::N>::T T;
+    constexpr int TM = GemmTile<F>::TM, TN = GemmTile<F>::TN;
+    const GemmPlan plan = gemm_plan<F>(M, N, K);
+    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+    RowMajorOut out;
+    out.ld = ldc;
+    hipError_t e;
+    // op(A)[i,k]: k contiguous unless transA.  op(B)[k,j] seen as rows j: k contiguous only when transB.
+    if (!transA && !transB) {
+        MatrixOperand<T, true> a{(const T*)A, lda, M, K};
+        MatrixOperand<T, false> b{(const T*)B, ldb, N, K};
+        e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, TM, TN>(st, a, b, out, M, N, K, bias, C, fout, ws, plan);
+    } else if (!transA && transB) {
+        MatrixOperand<T, true> a{(const T*)A, lda, M, K};
+        MatrixOperand<T, true> b{(const T*)B, ldb, N, K};
+        e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, TM, TN>(st, a, b, out, M, N, K, bias, C, fout, ws, plan);
+    } else if (transA && !transB) {
+        MatrixOperand<T, false> a{(const T*)A, lda, M, K};
+        MatrixOperand<T, false> b{(const T*)B, ldb, N, K};
+        e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, TM, TN>(st, a, b, out, M, N, K, bias, C, fout, ws, plan);
+    } else {
+        MatrixOperand<T, false> a{(const T*)A, lda, M, K};
+        MatrixOperand<T, true> b{(const T*)B, ldb, N, K};
+        e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, TM, TN>(st, a, b, out, M, N, K, bias, C, fout, ws, plan);
+    }
+    return hip_status(e);
+}
+
+}  // namespace pnn
+
+using namespace pnn;
+
+extern "C" size_t posit_gemm_workspace(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K) {
+    (void)fout; (void)transA; (void)transB;
+    if (!is_posit(fin) || M <= 0 || N <= 0 || K < 0) return 0;
+    switch (fin) {
+        case PNN_POSIT8_0: return gemm_plan<P8>(M, N, K).ws_bytes;
+        case PNN_POSIT16_1: return gemm_plan<P16>(M, N, K).ws_bytes;
+        default: return gemm_plan<P32>(M, N, K).ws_bytes;
+    }
+}
+
+extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                          const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias, void* C, int64_t ldc,
+                          void* workspace, size_t workspace_bytes) {
+    if (!is_posit(fin) || !is_posit(fout) || M < 0 || N < 0 || K < 0) return PNN_EINVAL;
+    if (M == 0 || N == 0) return PNN_OK;
+    if (!C || ldc < N) return PNN_EINVAL;
+    if (K > 0) {
+        if (!A || !B) return PNN_EINVAL;
+        if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return PNN_EINVAL;
+    }
+    if (M * N >= ((int64_t)1 << 40) || K >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fin) {
+        case PNN_POSIT8_0:
+            return gemm_dispatch<P8>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
+        case PNN_POSIT16_1:
+            return gemm_dispatch<P16>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
+        default:
+            return gemm_dispatch<P32>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
+    }
+}

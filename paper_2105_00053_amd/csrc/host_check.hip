@@ -1,0 +1,91 @@
+// Host build of the scalar device functions (decode, encode, quire read-out,
+// exact add) so that unit tests can drive them on a machine without a GPU.
+// Test scaffolding: nothing in the library links or calls this file.
+#include "elementwise_ops.h"
+#include "quire_arith.h"
+
+using namespace pnn;
+
+namespace {
+template <class Op>
+void run_map(Op op, int64_t n, const uint64_t* in, uint64_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = op(in[i]);
+}
+
+template <class FS>
+int convert_host(int dst, int64_t n, const uint64_t* in, uint64_t* out) {
+    switch (dst) {
+        case 0: run_map(PositToPosit<FS, P8>(), n, in, out); return 0;
+        case 1: run_map(PositToPosit<FS, P16>(), n, in, out); return 0;
+        case 2: run_map(PositToPosit<FS, P32>(), n, in, out); return 0;
+        case 100: run_map(PositToF32<FS>(), n, in, out); return 0;
+        case 101: run_map(PositToF64<FS>(), n, in, out); return 0;
+    }
+    return 1;
+}
+
+template <class FX, class FY>
+void axpy_host(uint32_t alpha, int64_t n, const uint64_t* x, const uint64_t* y, uint64_t* out) {
+    Axpy<FX, FY> op;
+    op.alpha = alpha;
+    for (int64_t i = 0; i < n; ++i) out[i] = op((uint32_t)x[i], (uint32_t)y[i]);
+}
+
+// dot product of n staged operands through Arith<F>, rounded to fout
+template <class F>
+uint32_t dot_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    typedef Arith<F> AR;
+    uint32_t q[AR::L];
+    for (int l = 0; l < AR::L; ++l) q[l] = 0;
+    bool nar = false;
+    for (int64_t i = 0; i < n; ++i) {
+        if (a[i] == F::NAR || b[i] == F::NAR) nar = true;
+        AR::mac(q, AR::stage(a[i]), AR::stage(b[i]));
+    }
+    if (has_bias) {
+        if (bias == F::NAR) nar = true;
+        else AR::add_value(q, AR::stage(bias));
+    }
+    if (fout == 0) return nar ? P8::NAR : quire_round<F, P8, AR::L>(q);
+    if (fout == 1) return nar ? P16::NAR : quire_round<F, P16, AR::L>(q);
+    return nar ? P32::NAR : quire_round<F, P32, AR::L>(q);
+}
+}  // namespace
+
+extern "C" {
+
+int hostcheck_round(int src_float, int dst, int64_t n, const uint64_t* in, uint64_t* out) {
+    if (src_float == 100) {
+        if (dst == 0) run_map(RoundF32<P8>(), n, in, out);
+        else if (dst == 1) run_map(RoundF32<P16>(), n, in, out);
+        else run_map(RoundF32<P32>(), n, in, out);
+    } else {
+        if (dst == 0) run_map(RoundF64<P8>(), n, in, out);
+        else if (dst == 1) run_map(RoundF64<P16>(), n, in, out);
+        else run_map(RoundF64<P32>(), n, in, out);
+    }
+    return 0;
+}
+
+int hostcheck_convert(int src, int dst, int64_t n, const uint64_t* in, uint64_t* out) {
+    if (src == 0) return convert_host<P8>(dst, n, in, out);
+    if (src == 1) return convert_host<P16>(dst, n, in, out);
+    return convert_host<P32>(dst, n, in, out);
+}
+
+int hostcheck_axpy(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t* x, const uint64_t* y, uint64_t* out) {
+#define CASE(FX, FY, a, b) if (fx == a && fy == b) { axpy_host<FX, FY>(alpha, n, x, y, out); return 0; }
+    CASE(P8, P8, 0, 0) CASE(P8, P16, 0, 1) CASE(P8, P32, 0, 2)
+    CASE(P16, P8, 1, 0) CASE(P16, P16, 1, 1) CASE(P16, P32, 1, 2)
+    CASE(P32, P8, 2, 0) CASE(P32, P16, 2, 1) CASE(P32, P32, 2, 2)
+#undef CASE
+    return 1;
+}
+
+uint32_t hostcheck_dot(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    if (fin == 0) return dot_host<P8>(fout, n, a, b, has_bias, bias);
+    if (fin == 1) return dot_host<P16>(fout, n, a, b, has_bias, bias);
+    return dot_host<P32>(fout, n, a, b, has_bias, bias);
+}
+
+}  // extern "C"

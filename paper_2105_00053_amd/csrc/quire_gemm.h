@@ -1,0 +1,398 @@
+// Tiled quire-exact GEMM kernel shared by posit_gemm and the three convolution
+// entry points (paper Sec. 3.3: matrix products and convolutions accumulate in
+// the quire and round once; Sec. 3.1: forward, backward-data and backward-weight
+// are written out by hand).  The convolutions are "implicit GEMMs": the kernel
+// is the same, only the functors that map (row, k) of the virtual matrices to
+// an address in the NCHW / KCRS tensors differ.
+//
+// Work split: one 256-thread workgroup computes a BM x BN tile of C.  For each
+// KT-wide slice of the reduction, the threads fetch patterns from HBM, decode
+// them once (Eq. 2) into the staged form of Arith<FIN>, and park them in LDS;
+// then each thread multiplies its TM x TN register tile against the slice,
+// adding every exact product into per-output quire limbs held in VGPRs.  NaR
+// never enters the arithmetic: a NaR pattern is staged as zero and raises an
+// LDS flag for its row (of A) or column (of B), applied when the tile is
+// rounded.  With gridDim.z > 1 the reduction is split across workgroups, which
+// write their limb partial sums to a workspace; a second kernel merges the
+// partial quires with carry and rounds (exact, order-independent).
+#pragma once
+
+#include "quire_arith.h"
+
+namespace pnn {
+
+// ---- operand functors: pattern of virtual element (row, k); zero outside ----
+
+// Row-major matrix; KFAST: element (row,k) at p[row*ld + k], else at p[k*ld + row].
+template <class T, bool KFAST_>
+struct MatrixOperand {
+    static constexpr bool KFAST = KFAST_;
+    const T* p;
+    int64_t ld, rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        return KFAST_ ? p[row * ld + k] : p[k * ld + row];
+    }
+};
+
+// A column of ones (pattern `one`): turns the kernel into a row sum (bias gradient).
+struct OnesOperand {
+    static constexpr bool KFAST = true;
+    uint32_t one;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        return (row < rows && k < K) ? one : 0u;
+    }
+};
+
+struct ConvGeom {
+    int N, C, H, W, K, R, S, ph, pw, sh, sw, OH, OW;
+};
+
+// Forward, left operand: row = (n, oh, ow), k = (c, r, s) -> x[n, c, oh*sh+r-ph, ow*sw+s-pw]
+template <class T>
+struct ConvFwdX {
+    static constexpr bool KFAST = false;
+    const T* x;
+    ConvGeom g;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        const int ohw = g.OH * g.OW;
+        const int n = (int)(row / ohw), rem = (int)(row % ohw);
+        const int oh = rem / g.OW, ow = rem % g.OW;
+        const int rs = g.R * g.S;
+        const int c = (int)k / rs, t = (int)k % rs;
+        const int r = t / g.S, s = t % g.S;
+        const int ih = oh * g.sh + r - g.ph, iw = ow * g.sw + s - g.pw;
+        if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0u;
+        return x[(((int64_t)n * g.C + c) * g.H + ih) * g.W + iw];
+    }
+};
+
+// Backward-data, left operand: row = (n, h, w), k = (ko, r, s) -> dy[n, ko, (h+ph-r)/sh, (w+pw-s)/sw]
+template <class T>
+struct ConvBwdDataDy {
+    static constexpr bool KFAST = false;
+    const T* dy;
+    ConvGeom g;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        const int hw = g.H * g.W;
+        const int n = (int)(row / hw), rem = (int)(row % hw);
+        const int h = rem / g.W, w = rem % g.W;
+        const int rs = g.R * g.S;
+        const int ko = (int)k / rs, t = (int)k % rs;
+        const int r = t / g.S, s = t % g.S;
+        const int th = h + g.ph - r, tw = w + g.pw - s;
+        if (th < 0 || tw < 0) return 0u;
+        const int oh = th / g.sh, ow = tw / g.sw;
+        if (oh * g.sh != th || ow * g.sw != tw || oh >= g.OH || ow >= g.OW) return 0u;
+        return dy[(((int64_t)n * g.K + ko) * g.OH + oh) * g.OW + ow];
+    }
+};
+
+// Backward-data, right operand: row = c, k = (ko, r, s) -> w[ko, c, r, s]
+template <class T>
+struct ConvBwdDataW {
+    static constexpr bool KFAST = true;
+    const T* w;
+    ConvGeom g;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        const int rs = g.R * g.S;
+        const int ko = (int)k / rs, t = (int)k % rs;
+        return w[((int64_t)ko * g.C + row) * rs + t];
+    }
+};
+
+// Backward-weight, left operand: row = ko, k = (n, oh, ow) -> dy[n, ko, oh, ow]
+template <class T>
+struct ConvBwdWeightDy {
+    static constexpr bool KFAST = true;
+    const T* dy;
+    ConvGeom g;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        const int ohw = g.OH * g.OW;
+        const int n = (int)(k / ohw), rem = (int)(k % ohw);
+        return dy[((int64_t)n * g.K + row) * ohw + rem];
+    }
+};
+
+// Backward-weight, right operand: row = (c, r, s), k = (n, oh, ow) -> x[n, c, oh*sh+r-ph, ow*sw+s-pw]
+template <class T>
+struct ConvBwdWeightX {
+    static constexpr bool KFAST = true;
+    const T* x;
+    ConvGeom g;
+    int64_t rows, K;
+    __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
+        if (row >= rows || k >= K) return 0u;
+        const int ohw = g.OH * g.OW;
+        const int n = (int)(k / ohw), rem = (int)(k % ohw);
+        const int oh = rem / g.OW, ow = rem % g.OW;
+        const int rs = g.R * g.S;
+        const int c = (int)row / rs, t = (int)row % rs;
+        const int r = t / g.S, s = t % g.S;
+        const int ih = oh * g.sh + r - g.ph, iw = ow * g.sw + s - g.pw;
+        if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) return 0u;
+        return x[(((int64_t)n * g.C + c) * g.H + ih) * g.W + iw];
+    }
+};
+
+// ---- where output (row, col) lives ----
+
+struct RowMajorOut {
+    int64_t ld;
+    __device__ __forceinline__ int64_t operator()(int64_t row, int64_t col) const { return row * ld + col; }
+};
+
+// row = (n, spatial), col = channel  ->  [n][channel][spatial]
+struct NchwOut {
+    int64_t spatial, channels;
+    __device__ __forceinline__ int64_t operator()(int64_t row, int64_t col) const {
+        const int64_t n = row / spatial, rem = row % spatial;
+        return (n * channels + col) * spatial + rem;
+    }
+};
+
+// Workspace layout for a split reduction, per split z:
+//   limbs  [z][M*N][L] uint32   partial quires
+//   rowflag[z][M], colflag[z][N] uint32   NaR seen in that row of A / column of B
+struct SplitWs {
+    uint32_t* limbs;
+    uint32_t* rowflag;
+    uint32_t* colflag;
+};
+
+constexpr int GEMM_THREADS = 256;
+constexpr int GEMM_KT = 16;
+
+// Round an L-limb quire of format FIN to the output format chosen at run time
+// (0 = posit<8,0>, 1 = posit<16,1>, 2 = posit<32,2>) and store it.
+template <class FIN, int L>
+__device__ __forceinline__ void round_store(const uint32_t (&q)[L], bool nar, int fout, void* C, int64_t at) {
+    Real r;
+    const bool nonzero = quire_to_real<L>(q, FIN::QFRAC, r);
+    if (fout == 0) {
+        ((uint8_t*)C)[at] = (uint8_t)(nar ? P8::NAR : nonzero ? encode<P8>(r) : 0u);
+    } else if (fout == 1) {
+        ((uint16_t*)C)[at] = (uint16_t)(nar ? P16::NAR : nonzero ? encode<P16>(r) : 0u);
+    } else {
+        ((uint32_t*)C)[at] = nar ? P32::NAR : nonzero ? encode<P32>(r) : 0u;
+    }
+}
+
+template <class FIN, class OpA, class OpB, class Out, int TM, int TN>
+__global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
+    OpA opa, OpB opb, Out out, int64_t M, int64_t N, int64_t K, int64_t k_per_split,
+    const typename Storage<FIN::N>::T* __restrict__ bias, void* __restrict__ C, int fout,
+    SplitWs ws, int tiles_n) {
+    typedef Arith<FIN> AR;
+    typedef typename AR::Elem Elem;
+    constexpr int L = AR::L;
+    constexpr int BM = 16 * TM, BN = 16 * TN, KT = GEMM_KT;
+
+    __shared__ Elem As[KT][BM + 1];
+    __shared__ Elem Bs[KT][BN + 1];
+    __shared__ uint32_t rowNaR[BM];
+    __shared__ uint32_t colNaR[BN];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int64_t tile = blockIdx.x;
+    const int64_t m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int64_t kbeg = (int64_t)blockIdx.z * k_per_split;
+    const int64_t kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
+
+    for (int i = tid; i < BM; i += GEMM_THREADS) rowNaR[i] = 0;
+    for (int i = tid; i < BN; i += GEMM_THREADS) colNaR[i] = 0;
+
+    uint32_t acc[TM][TN][L];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int l = 0; l < L; ++l) acc[i][j][l] = 0;
+
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
+        __syncthreads();  // previous slice fully consumed (and flags initialised)
+        // stage A: consecutive threads walk the dimension that is contiguous in memory
+        for (int e = tid; e < BM * KT; e += GEMM_THREADS) {
+            const int kk = OpA::KFAST ? (e % KT) : (e / BM);
+            const int r = OpA::KFAST ? (e / KT) : (e % BM);
+            const int64_t k = k0 + kk;
+            const uint32_t p = (k < kend) ? opa(m0 + r, k) : 0u;
+            if (p == FIN::NAR) rowNaR[r] = 1;
+            As[kk][r] = AR::stage(p);
+        }
+        for (int e = tid; e < BN * KT; e += GEMM_THREADS) {
+            const int kk = OpB::KFAST ? (e % KT) : (e / BN);
+            const int r = OpB::KFAST ? (e / KT) : (e % BN);
+            const int64_t k = k0 + kk;
+            const uint32_t p = (k < kend) ? opb(n0 + r, k) : 0u;
+            if (p == FIN::NAR) colNaR[r] = 1;
+            Bs[kk][r] = AR::stage(p);
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int kk = 0; kk < KT; ++kk) {
+            Elem a[TM], b[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) a[i] = As[kk][ty * TM + i];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) b[j] = Bs[kk][tx * TN + j];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) AR::mac(acc[i][j], a[i], b[j]);
+        }
+    }
+    __syncthreads();
+
+    if (gridDim.z == 1) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = m0 + ty * TM + i;
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t n = n0 + tx * TN + j;
+                if (n >= N) continue;
+                bool nar = (rowNaR[ty * TM + i] | colNaR[tx * TN + j]) != 0;
+                if (bias) {
+                    const uint32_t bp = bias[n];
+                    if (bp == FIN::NAR) nar = true;
+                    else AR::add_value(acc[i][j], AR::stage(bp));
+                }
+                round_store<FIN, L>(acc[i][j], nar, fout, C, out(m, n));
+            }
+        }
+    } else {
+        const int64_t z = blockIdx.z;
+        uint32_t* lim = ws.limbs + z * M * N * L;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int64_t m = m0 + ty * TM + i;
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int64_t n = n0 + tx * TN + j;
+                if (n >= N) continue;
+#pragma unroll
+                for (int l = 0; l < L; ++l) lim[(m * N + n) * L + l] = acc[i][j][l];
+            }
+        }
+        // several tiles share a row (or column) of flags: OR them together
+        for (int i = tid; i < BM; i += GEMM_THREADS)
+            if (m0 + i < M && rowNaR[i]) atomicOr(&ws.rowflag[z * M + m0 + i], 1u);
+        for (int i = tid; i < BN; i += GEMM_THREADS)
+            if (n0 + i < N && colNaR[i]) atomicOr(&ws.colflag[z * N + n0 + i], 1u);
+    }
+}
+
+// Zero the NaR flags of a split reduction (the limb partials are fully overwritten).
+template <int UNUSED = 0>
+__global__ void split_clear_kernel(uint32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// Merge the per-split partial quires (multi-word add with carry), add the bias,
+// round once, store.
+template <class FIN, class Out>
+__global__ void split_merge_kernel(SplitWs ws, int splits, int64_t M, int64_t N,
+                                   const typename Storage<FIN::N>::T* __restrict__ bias,
+                                   void* __restrict__ C, int fout, Out out) {
+    typedef Arith<FIN> AR;
+    constexpr int L = AR::L;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= M * N) return;
+    const int64_t m = idx / N, n = idx % N;
+    uint32_t q[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) q[l] = 0;
+    bool nar = false;
+    for (int z = 0; z < splits; ++z) {
+        uint32_t part[L];
+#pragma unroll
+        for (int l = 0; l < L; ++l) part[l] = ws.limbs[((int64_t)z * M * N + idx) * L + l];
+        quire_merge<L>(q, part);
+        nar = nar || ws.rowflag[(int64_t)z * M + m] || ws.colflag[(int64_t)z * N + n];
+    }
+    if (bias) {
+        const uint32_t bp = bias[n];
+        if (bp == FIN::NAR) nar = true;
+        else AR::add_value(q, AR::stage(bp));
+    }
+    round_store<FIN, L>(q, nar, fout, C, out(m, n));
+}
+
+// ---- host side ----
+
+struct GemmPlan {
+    int splits;
+    int64_t k_per_split;
+    size_t ws_bytes;
+};
+
+// How many ways to split the reduction: only when the output tiles alone cannot
+// fill the chip and the reduction is long.
+inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int L) {
+    GemmPlan p;
+    const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
+    int splits = 1;
+    const int64_t target = 1024;  // workgroups wanted: 4 per CU on 256 CUs
+    if (tiles < 256 && K >= 1024) {
+        int64_t s = target / (tiles > 0 ? tiles : 1);
+        const int64_t max_by_k = K / 256;  // keep at least 256 reduction steps per split
+        if (s > max_by_k) s = max_by_k;
+        if (s > 256) s = 256;
+        if (s >= 2) splits = (int)s;
+    }
+    int64_t kps = (K + splits - 1) / splits;
+    kps = (kps + GEMM_KT - 1) / GEMM_KT * GEMM_KT;
+    if (kps < GEMM_KT) kps = GEMM_KT;
+    splits = (int)((K + kps - 1) / kps);
+    if (splits < 1) splits = 1;
+    p.splits = splits;
+    p.k_per_split = kps;
+    p.ws_bytes = splits > 1 ? (size_t)splits * ((size_t)M * N * L + M + N) * sizeof(uint32_t) : 0;
+    return p;
+}
+
+template <class FIN, class OpA, class OpB, class Out, int TM, int TN>
+hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb, const Out& out,
+                             int64_t M, int64_t N, int64_t K, const void* bias, void* C, int fout,
+                             void* workspace, const GemmPlan& plan) {
+    typedef typename Storage<FIN::N>::T TI;
+    constexpr int BM = 16 * TM, BN = 16 * TN, L = Arith<FIN>::L;
+    const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    SplitWs ws;
+    ws.limbs = nullptr;
+    ws.rowflag = nullptr;
+    ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)workspace;
+        ws.rowflag = ws.limbs + (size_t)plan.splits * M * N * L;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * M;
+        const int64_t nflags = (int64_t)plan.splits * (M + N);
+        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, ws.rowflag, nflags);
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN>), grid, dim3(GEMM_THREADS), 0, stream,
+                       opa, opb, out, M, N, K, plan.k_per_split, (const TI*)bias, C, fout, ws, (int)tiles_n);
+    if (plan.splits > 1) {
+        const int64_t total = M * N;
+        hipLaunchKernelGGL((split_merge_kernel<FIN, Out>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                           ws, plan.splits, M, N, (const TI*)bias, C, fout, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pnn

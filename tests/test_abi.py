@@ -1,0 +1,73 @@
+"""The C-ABI library loads and exports every function include/positnn.h declares;
+argument validation returns the documented status codes (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "positnn.h")
+LIB = os.path.join(ROOT, "paper_2105_00053_amd", "libpositnn_hip.so")
+
+
+def _declared():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(posit_[a-z0-9_]+)\s*\(", src)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB):
+        from paper_2105_00053_amd import build
+        build.build()
+    return ctypes.CDLL(LIB)
+
+
+def test_header_declares_the_expected_entry_points():
+    assert _declared() == sorted([
+        "posit_gemm", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
+        "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string"])
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in _declared():
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    lib.posit_status_string.restype = ctypes.c_char_p
+    seen = {lib.posit_status_string(i) for i in range(5)}
+    assert len(seen) == 5 and all(seen)
+    assert lib.posit_status_string(99)
+
+
+def test_argument_validation_without_launch():
+    from paper_2105_00053_amd import binding as b
+    L = b.load()
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(0x1000)  # never dereferenced: the calls below are rejected before any launch
+    EINVAL = 1
+    assert L.posit_gemm(null, 7, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # unknown format
+    assert L.posit_gemm(null, 0, 0, 0, 0, -1, 4, 4, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL     # negative size
+    assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 4, null, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # null A
+    assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # lda < K
+    assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 2, null, 0) == EINVAL      # ldc < N
+    assert L.posit_gemm(null, 0, 0, 0, 0, 0, 4, 4, null, 4, null, 4, null, null, 4, null, 0) == 0           # empty: ok, nothing touched
+    assert L.posit_round(null, 0, 0, 4, fake, fake) == EINVAL      # source must be a float type
+    assert L.posit_round(null, 100, 100, 4, fake, fake) == EINVAL  # destination must be a posit
+    assert L.posit_round(null, 100, 0, 0, null, null) == 0
+    assert L.posit_convert(null, 100, 0, 4, fake, fake) == EINVAL
+    assert L.posit_axpy(null, 0, 1, 0, 4, null, fake, -1, null) == EINVAL
+    assert L.posit_axpy(null, 0, 1, 0, 4, fake, fake, 9, fake) == EINVAL  # bad copy format
+    d = b.ConvDesc(1, 1, 4, 4, 1, 5, 5, 0, 0, 1, 1)  # kernel larger than the padded image
+    assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, null, 0) == EINVAL
+    d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 0, 1)  # zero stride
+    assert L.posit_conv2d_bwd_data(null, 0, 0, ctypes.byref(d), fake, fake, fake, null, 0) == EINVAL
+    assert L.posit_conv2d_bwd_weight(null, 0, 0, None, fake, fake, fake, null, null, 0) == EINVAL
+    # a split reduction without the workspace it asks for
+    need = L.posit_gemm_workspace(0, 1, 0, 0, 32, 288, 131072)
+    assert need > 0
+    assert L.posit_gemm(null, 0, 1, 0, 0, 32, 288, 131072, fake, 131072, fake, 288, null, fake, 288, null, 0) == 3
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 0

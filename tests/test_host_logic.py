@@ -1,0 +1,138 @@
+"""The library's scalar device functions (decode, encode, quire limbs, exact add),
+compiled for the host, against the oracle.  Runs without a GPU; the kernels
+call exactly these functions."""
+import ctypes
+import os
+
+import numpy as np
+import pytest
+
+from oracle import fast
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+LIB = os.path.join(ROOT, "paper_2105_00053_amd", "libpositnn_hostcheck.so")
+CODE = {"p8": 0, "p16": 1, "p32": 2, "f32": 100, "f64": 101}
+BITS = {"p8": 8, "p16": 16, "p32": 32}
+
+
+@pytest.fixture(scope="module")
+def hc():
+    if not os.path.exists(LIB):
+        from paper_2105_00053_amd import build
+        build.build()
+    L = ctypes.CDLL(LIB)
+    vp, i64, ci = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    L.hostcheck_round.argtypes = [ci, ci, i64, vp, vp]
+    L.hostcheck_convert.argtypes = [ci, ci, i64, vp, vp]
+    L.hostcheck_axpy.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
+    L.hostcheck_dot.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
+    L.hostcheck_dot.restype = ctypes.c_uint32
+    return L
+
+
+def _p(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _patterns(rng, n, fmt, special=0.03):
+    b = BITS[fmt]
+    a = rng.integers(0, 1 << b, size=n, dtype=np.uint64)
+    sp = rng.choice(np.array([0, 1, 2, (1 << (b - 1)) - 1, (1 << (b - 1)) - 2, (1 << b) - 1, (1 << (b - 1)) + 1, 1 << (b - 1), 1 << (b - 2)],
+                             dtype=np.uint64), size=n)
+    return np.where(rng.random(n) < special, sp, a)
+
+
+@pytest.mark.parametrize("dst", ["p8", "p16", "p32"])
+def test_round_from_floats(hc, dst):
+    rng = np.random.default_rng(1)
+    x = (rng.standard_normal(200000) * np.exp2(rng.uniform(-70, 70, 200000))).astype(np.float32)
+    x[:10] = [0.0, -0.0, np.inf, -np.inf, np.nan, 1e-45, -1e-45, 3.4e38, 1.0, -1.0]
+    bits = x.view(np.uint32).astype(np.uint64)
+    out = np.zeros_like(bits)
+    hc.hostcheck_round(100, CODE[dst], len(bits), _p(bits), _p(out))
+    assert np.array_equal(out, fast.round_from_float(x, dst).astype(np.uint64))
+    xd = rng.standard_normal(200000) * np.exp2(rng.uniform(-300, 300, 200000))
+    xd[:6] = [5e-324, -5e-324, 1.7e308, np.nan, -np.inf, 2.0 ** -120]
+    bits = xd.view(np.uint64).copy()
+    hc.hostcheck_round(101, CODE[dst], len(bits), _p(bits), _p(out))
+    assert np.array_equal(out, fast.round_from_float(xd, dst).astype(np.uint64))
+
+
+@pytest.mark.parametrize("src", ["p8", "p16", "p32"])
+@pytest.mark.parametrize("dst", ["p8", "p16", "p32", "f32", "f64"])
+def test_convert(hc, src, dst):
+    if src == "p32":
+        pats = _patterns(np.random.default_rng(2), 300000, "p32")
+    else:
+        pats = np.arange(1 << BITS[src], dtype=np.uint64)
+    out = np.zeros_like(pats)
+    assert hc.hostcheck_convert(CODE[src], CODE[dst], len(pats), _p(pats), _p(out)) == 0
+    if dst in ("f32", "f64"):
+        want = fast.to_float(pats, src, dst)
+        got = out.astype(np.uint32).view(np.float32) if dst == "f32" else out.view(np.float64)
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan)
+        assert np.array_equal(got[~nan], want[~nan])
+    else:
+        assert np.array_equal(out, fast.convert(pats, src, dst).astype(np.uint64))
+
+
+@pytest.mark.parametrize("fx", ["p8", "p16", "p32"])
+@pytest.mark.parametrize("fy", ["p8", "p16", "p32"])
+def test_axpy(hc, fx, fy):
+    rng = np.random.default_rng(BITS[fx] + 7 * BITS[fy])
+    n = 60000
+    x = _patterns(rng, n, fx)
+    y = _patterns(rng, n, fy)
+    # near-cancelling cases: y close to -alpha*x
+    alphas = [int(fast.round_from_float(np.array([-0.1], dtype=np.float32), fy)[0]), 1 << (BITS[fy] - 2),
+              int(_patterns(rng, 1, fy, 0)[0]), 0, 1 << (BITS[fy] - 1), (1 << (BITS[fy] - 2)) | (1 << (BITS[fy] - 1))]
+    for alpha in alphas:
+        out = np.zeros(n, dtype=np.uint64)
+        assert hc.hostcheck_axpy(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
+        want = fast.axpy(alpha, x, y, fx, fy)
+        assert np.array_equal(out, want.astype(np.uint64)), alpha
+    # y = -x in the same format with alpha = 1 cancels exactly; y = -x +- 1 pattern nearly cancels
+    if fx == fy:
+        one = 1 << (BITS[fy] - 2)
+        mask = (1 << BITS[fy]) - 1
+        for delta in (0, 1, -1, 2):
+            y2 = ((-x.astype(np.int64) + delta) & mask).astype(np.uint64)
+            out = np.zeros(n, dtype=np.uint64)
+            hc.hostcheck_axpy(CODE[fx], CODE[fy], one, n, _p(x), _p(y2), _p(out))
+            assert np.array_equal(out, fast.axpy(one, x, y2, fx, fy).astype(np.uint64))
+
+
+@pytest.mark.parametrize("fin", ["p8", "p16", "p32"])
+@pytest.mark.parametrize("fout", ["p8", "p16", "p32"])
+def test_quire_dot(hc, fin, fout):
+    rng = np.random.default_rng(BITS[fin] * 3 + BITS[fout])
+    for trial in range(300):
+        K = int(rng.integers(0, 40))
+        special = [0.0, 0.05, 0.5][trial % 3]
+        a = _patterns(rng, K, fin, special).astype(np.uint32)
+        b = _patterns(rng, K, fin, special).astype(np.uint32)
+        if trial % 4:
+            nar = 1 << (BITS[fin] - 1)
+            a[a == nar] = 1
+            b[b == nar] = 1
+        if trial % 7 == 3 and K >= 2:
+            # exact cancellation of the two largest terms leaves only small ones
+            a[1] = a[0]
+            b[1] = (-b[0].astype(np.int64)) & ((1 << BITS[fin]) - 1)
+        has_bias = trial % 2
+        bias = int(_patterns(rng, 1, fin, 0.1)[0])
+        got = hc.hostcheck_dot(CODE[fin], CODE[fout], K, _p(a), _p(b), has_bias, bias)
+        want, _ = fast.gemm(a.reshape(1, K), b.reshape(K, 1), fin, fout,
+                            bias=np.array([bias]) if has_bias else None, threads=1)
+        assert got == int(want[0, 0]), (trial, K)
+
+
+def test_quire_dot_wraps_like_the_oracle(hc):
+    a = np.full(128, 0x7F, dtype=np.uint32)
+    assert hc.hostcheck_dot(0, 0, 128, _p(a), _p(a), 0, 0) == 0x81
+    assert hc.hostcheck_dot(0, 0, 127, _p(a), _p(a), 0, 0) == 0x7F
+    a16 = np.full(40000, 0x7FFF, dtype=np.uint32)
+    for K in (32767, 32768, 40000):
+        want, _ = fast.gemm(a16[:K].reshape(1, K), a16[:K].reshape(K, 1), "p16", "p16", threads=1)
+        assert hc.hostcheck_dot(1, 1, K, _p(a16), _p(a16), 0, 0) == int(want[0, 0])
