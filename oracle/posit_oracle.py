@@ -32,8 +32,10 @@ What each function follows
 
 Readings of points the paper leaves open (all listed in the design notes):
 the quire is a Q-bit two's-complement integer whose unit is minpos^2 and which
-wraps modulo 2^Q; NaR is absorbing; a bias is added inside the quire; missing
-exponent bits read as zero.
+wraps modulo 2^Q; NaR is absorbing (NaR * 0 = NaR); a bias is added inside the
+quire; missing exponent bits read as zero; a convolution is the matrix product
+of its unfolded (im2col) form, so zero padding and taps without a partner are
+zero OPERANDS: a NaR weight makes its whole output channel NaR.
 
 Parity pins: every function here is pinned by tests that do not reuse its own
 formula (exhaustive round trips, encodings fixed by the definition, Table 1's
@@ -359,13 +361,11 @@ def conv2d_fwd_quire(x, w, sh, fin, bias=None):
                     for c in range(sh.C):
                         for r in range(sh.R):
                             ih = oh * sh.stride_h + r - sh.pad_h
-                            if ih < 0 or ih >= sh.H:
-                                continue
                             for s in range(sh.S):
                                 iw = ow * sh.stride_w + s - sh.pad_w
-                                if iw < 0 or iw >= sh.W:
-                                    continue
-                                a = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw]
+                                inside = 0 <= ih < sh.H and 0 <= iw < sh.W
+                                # a padded position holds the value zero and is an operand like any other
+                                a = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw] if inside else 0
                                 b = wu[((k * sh.C + c) * sh.R + r) * sh.S + s]
                                 if a is NaR or b is NaR:
                                     nar = True
@@ -381,7 +381,8 @@ def conv2d_fwd_quire(x, w, sh, fin, bias=None):
 
 
 def conv2d_bwd_data_quire(dy, w, sh, fin):
-    """Exact dx[n][c][h][w] = sum over (k,r,s,oh,ow) with oh*sh+r-ph == h, ow*sw+s-pw == w of dy*w."""
+    """Exact dx[n][c][h][w] = sum over (k,r,s) of dy[n][k][oh][ow]*w[k][c][r][s] with oh*sh+r-ph == h,
+    ow*sw+s-pw == w; a (k,r,s) without such an (oh,ow) multiplies the weight by a zero operand."""
     dyu = _units_list(dy, fin)
     wu = _units_list(w, fin)
     out = []
@@ -394,19 +395,14 @@ def conv2d_bwd_data_quire(dy, w, sh, fin):
                     for k in range(sh.K):
                         for r in range(sh.R):
                             t = h + sh.pad_h - r
-                            if t < 0 or t % sh.stride_h:
-                                continue
                             oh = t // sh.stride_h
-                            if oh >= sh.OH:
-                                continue
+                            row_ok = t >= 0 and t % sh.stride_h == 0 and oh < sh.OH
                             for s in range(sh.S):
                                 u = ww + sh.pad_w - s
-                                if u < 0 or u % sh.stride_w:
-                                    continue
                                 ow = u // sh.stride_w
-                                if ow >= sh.OW:
-                                    continue
-                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow]
+                                ok = row_ok and u >= 0 and u % sh.stride_w == 0 and ow < sh.OW
+                                # a tap with no output position behind it is a zero operand
+                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow] if ok else 0
                                 b = wu[((k * sh.C + c) * sh.R + r) * sh.S + s]
                                 if a is NaR or b is NaR:
                                     nar = True
@@ -430,14 +426,11 @@ def conv2d_bwd_weight_quire(dy, x, sh, fin):
                     for n in range(sh.N):
                         for oh in range(sh.OH):
                             ih = oh * sh.stride_h + r - sh.pad_h
-                            if ih < 0 or ih >= sh.H:
-                                continue
                             for ow in range(sh.OW):
                                 iw = ow * sh.stride_w + s - sh.pad_w
-                                if iw < 0 or iw >= sh.W:
-                                    continue
+                                inside = 0 <= ih < sh.H and 0 <= iw < sh.W
                                 a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow]
-                                b = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw]
+                                b = xu[((n * sh.C + c) * sh.H + ih) * sh.W + iw] if inside else 0
                                 if a is NaR or b is NaR:
                                     nar = True
                                 else:

@@ -13,7 +13,8 @@
 // Sec. 3.3; hand-written backward passes = Sec. 3.1; tensor conversion, SGD =
 // Fig. 2; worker threads split the rows of the left operand = Sec. 3.3.
 // Readings where the paper is silent are those of the Python oracle (modular
-// quire, NaR absorbing, bias inside the quire, truncated exponent bits are 0).
+// quire, NaR absorbing, bias inside the quire, truncated exponent bits are 0,
+// padding and partner-less convolution taps are zero operands).
 //
 // Pins: agreement with the Python oracle on every entry point (tests), which is
 // itself pinned to the definition.  Not tuned: no blocking, no SIMD, no tables.
@@ -230,6 +231,9 @@ struct Conv {
     int64_t N, C, H, W, K, R, S, ph, pw, sh, sw, OH, OW;
 };
 
+Decoded make_zero() { Decoded d; d.zero = true; return d; }
+const Decoded zero = make_zero();
+
 }  // namespace
 
 extern "C" {
@@ -299,11 +303,11 @@ int oracle_conv2d_fwd(int fin_c, int fout_c, const int64_t* d, const void* x, co
                     for (int64_t ci = 0; ci < c.C; ++ci)
                         for (int64_t r = 0; r < c.R; ++r) {
                             const int64_t ih = oh * c.sh + r - c.ph;
-                            if (ih < 0 || ih >= c.H) continue;
                             for (int64_t s = 0; s < c.S; ++s) {
                                 const int64_t iw = ow * c.sw + s - c.pw;
-                                if (iw < 0 || iw >= c.W) continue;
-                                mac(q, nar, xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)],
+                                const bool inside = ih >= 0 && ih < c.H && iw >= 0 && iw < c.W;
+                                // a padded position holds zero and is an operand like any other
+                                mac(q, nar, inside ? xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)] : zero,
                                     wd[(size_t)(((k * c.C + ci) * c.R + r) * c.S + s)]);
                             }
                         }
@@ -334,15 +338,12 @@ int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* 
                     for (int64_t k = 0; k < c.K; ++k)
                         for (int64_t r = 0; r < c.R; ++r) {
                             const int64_t t = h + c.ph - r;
-                            if (t < 0 || t % c.sh) continue;
-                            const int64_t oh = t / c.sh;
-                            if (oh >= c.OH) continue;
+                            const bool row_ok = t >= 0 && t % c.sh == 0 && t / c.sh < c.OH;
                             for (int64_t s = 0; s < c.S; ++s) {
                                 const int64_t u = ww + c.pw - s;
-                                if (u < 0 || u % c.sw) continue;
-                                const int64_t ow = u / c.sw;
-                                if (ow >= c.OW) continue;
-                                mac(q, nar, dyd[(size_t)(((n * c.K + k) * c.OH + oh) * c.OW + ow)],
+                                const bool ok = row_ok && u >= 0 && u % c.sw == 0 && u / c.sw < c.OW;
+                                // a tap with no output position behind it is a zero operand
+                                mac(q, nar, ok ? dyd[(size_t)(((n * c.K + k) * c.OH + t / c.sh) * c.OW + u / c.sw)] : zero,
                                     wd[(size_t)(((k * c.C + ci) * c.R + r) * c.S + s)]);
                             }
                         }
@@ -373,12 +374,11 @@ int oracle_conv2d_bwd_weight(int fin_c, int fout_c, const int64_t* d, const void
                     for (int64_t n = 0; n < c.N; ++n)
                         for (int64_t oh = 0; oh < c.OH; ++oh) {
                             const int64_t ih = oh * c.sh + r - c.ph;
-                            if (ih < 0 || ih >= c.H) continue;
                             for (int64_t ow = 0; ow < c.OW; ++ow) {
                                 const int64_t iw = ow * c.sw + s - c.pw;
-                                if (iw < 0 || iw >= c.W) continue;
+                                const bool inside = ih >= 0 && ih < c.H && iw >= 0 && iw < c.W;
                                 mac(q, nar, dyd[(size_t)(((n * c.K + k) * c.OH + oh) * c.OW + ow)],
-                                    xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)]);
+                                    inside ? xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)] : zero);
                             }
                         }
                     store(dw, ((k * c.C + ci) * c.R + r) * c.S + s, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);

@@ -260,3 +260,62 @@ def test_axpy():
         assert po.axpy(0, rng.getrandbits(15), y, po.P16, po.P16) == y  # alpha = 0
         assert po.axpy(0x4000, (-y) & 0xFFFF, y, po.P16, po.P16) == 0  # y + 1*(-y)
     assert po.axpy(0x8000, 0x4000, 0x4000, po.P16, po.P16) == 0x8000
+
+
+def test_conv_is_the_matrix_product_of_its_unfolded_form_including_nar():
+    """Zero padding materialised (pattern 0) and every pass written as a plain
+    gemm over the unfolded operand: same bits, NaR included (NaR * 0 = NaR)."""
+    rng = random.Random(12)
+    sh = po.ConvShape(2, 2, 4, 5, 3, 3, 2, 1, 1, 2, 1)
+    fmt = po.P8
+
+    def rnd(n, nar_at=()):
+        v = [rng.getrandbits(8) for _ in range(n)]
+        v = [p if p != 0x80 else 0x40 for p in v]
+        for i in nar_at:
+            v[i] = 0x80
+        return v
+
+    x = rnd(sh.N * sh.C * sh.H * sh.W, nar_at=(7,))
+    w = rnd(sh.K * sh.C * sh.R * sh.S, nar_at=(5,))  # NaR in output channel 0
+    dy = rnd(sh.N * sh.K * sh.OH * sh.OW, nar_at=(3,))
+
+    def xat(n, c, ih, iw):
+        return x[((n * sh.C + c) * sh.H + ih) * sh.W + iw] if 0 <= ih < sh.H and 0 <= iw < sh.W else 0
+
+    # forward: rows (n,oh,ow), reduction (c,r,s)
+    cols = [[xat(n, c, oh * sh.stride_h + r - sh.pad_h, ow * sh.stride_w + s - sh.pad_w)
+             for c in range(sh.C) for r in range(sh.R) for s in range(sh.S)]
+            for n in range(sh.N) for oh in range(sh.OH) for ow in range(sh.OW)]
+    Wm = [w[k * sh.C * sh.R * sh.S:(k + 1) * sh.C * sh.R * sh.S] for k in range(sh.K)]
+    Y = po.gemm(cols, Wm, fmt, fmt, trans_b=True)
+    y = po.conv2d_fwd(x, w, sh, fmt, fmt)
+    for n in range(sh.N):
+        for k in range(sh.K):
+            for i in range(sh.OH * sh.OW):
+                assert y[(n * sh.K + k) * sh.OH * sh.OW + i] == Y[n * sh.OH * sh.OW + i][k]
+    assert all(y[(n * sh.K + 0) * sh.OH * sh.OW + i] == 0x80 for n in range(sh.N) for i in range(sh.OH * sh.OW))
+    # backward-weight: rows k, columns (c,r,s), reduction (n,oh,ow)
+    dyT = [[dy[(n * sh.K + k) * sh.OH * sh.OW + i] for n in range(sh.N) for i in range(sh.OH * sh.OW)] for k in range(sh.K)]
+    DW = po.gemm(dyT, cols, fmt, po.P16)
+    dw = po.conv2d_bwd_weight(dy, x, sh, fmt, po.P16)
+    assert dw == [DW[k][j] for k in range(sh.K) for j in range(sh.C * sh.R * sh.S)]
+    # backward-data: rows (n,h,w), columns c, reduction (k,r,s)
+
+    def dyat(n, k, h, ww, r, s):
+        t, u = h + sh.pad_h - r, ww + sh.pad_w - s
+        if t < 0 or u < 0 or t % sh.stride_h or u % sh.stride_w:
+            return 0
+        oh, ow = t // sh.stride_h, u // sh.stride_w
+        return dy[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow] if oh < sh.OH and ow < sh.OW else 0
+
+    rows = [[dyat(n, k, h, ww, r, s) for k in range(sh.K) for r in range(sh.R) for s in range(sh.S)]
+            for n in range(sh.N) for h in range(sh.H) for ww in range(sh.W)]
+    Wc = [[w[((k * sh.C + c) * sh.R + r) * sh.S + s] for k in range(sh.K) for r in range(sh.R) for s in range(sh.S)]
+          for c in range(sh.C)]
+    DX = po.gemm(rows, Wc, fmt, fmt, trans_b=True)
+    dx = po.conv2d_bwd_data(dy, w, sh, fmt, fmt)
+    for n in range(sh.N):
+        for c in range(sh.C):
+            for i in range(sh.H * sh.W):
+                assert dx[(n * sh.C + c) * sh.H * sh.W + i] == DX[n * sh.H * sh.W + i][c]
