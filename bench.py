@@ -1,0 +1,153 @@
+#!/usr/bin/env python3
+"""Benchmark of the quire-exact posit hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--size S] [--no-cpu]
+
+Workload (BASELINE config 5, the one the metric is quoted on): posit<8,0> quire
+GEMM with M = N = K = 4096, operands N(0,1) rounded to posit<8,0>, all inputs
+resident in HBM before timing starts.  One step is one pass over every stage of
+the path on that batch:
+
+    float32 -> posit<8,0> rounding of A and B        (posit_round)
+    C = round(A @ B), 32-bit quire, one rounding      (posit_gemm)
+    C -> posit<16,1> (exact widening)                 (posit_convert)
+    W <- round(W - lr * C) in posit<16,1>, plus the
+        posit<8,0> copy of the new W                  (posit_axpy)
+
+`value` is M*N*K multiply-accumulates divided by the time of the whole step.
+`roofline` is for the GEMM kernel alone, timed with HIP events on the launch
+stream: achieved MAC/s against the integer-VALU peak of the chip for the fastest
+exact primitive (one packed 16-bit dot-product lane-op = 2 MACs):
+256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 = 78.6 TMAC/s.
+`cpu_baseline` times the (untuned) C++ oracle on a sample of rows of the same GEMM.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--size", type=int, default=4096, help="M = N = K")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path is data-parallel over rows of A; "
+              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import paper_2105_00053_amd as pn
+    import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    pn.load()
+    torch.cuda.set_device(0)
+    S = args.size
+    A32, B32 = workloads.gemm_operands(5, S)
+    Af = torch.from_numpy(A32).cuda()
+    Bf = torch.from_numpy(B32).cuda()
+    W = pn.posit_round(torch.from_numpy(workloads.normal_matrix(5, 7, (S, S))).cuda(), "p16")
+    lr_bits = 0xEB33  # -(0x14CD): posit<16,1> pattern of -0.1 (two's complement of the pattern of 0.1)
+    A8 = torch.empty((S, S), dtype=torch.uint8, device="cuda")
+    B8 = torch.empty((S, S), dtype=torch.uint8, device="cuda")
+    C8 = torch.empty((S, S), dtype=torch.uint8, device="cuda")
+    C16 = torch.empty((S, S), dtype=torch.uint16, device="cuda")
+    W8 = torch.empty((S, S), dtype=torch.uint8, device="cuda")
+    need = pn.posit_gemm_workspace("p8", "p8", False, False, S, S, S)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+
+    def step(i=None):
+        pn.posit_round(Af, "p8", out=A8)
+        pn.posit_round(Bf, "p8", out=B8)
+        if i is not None:
+            ev[i][0].record()
+        pn.posit_gemm(A8, B8, "p8", "p8", out=C8, workspace=ws)
+        if i is not None:
+            ev[i][1].record()
+        pn.posit_convert(C8, "p8", "p16", out=C16)
+        pn.posit_axpy(lr_bits, C16, W, "p16", "p16", fcopy="p8", y_copy=W8)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    gemm_ms = sum(a.elapsed_time(b) for a, b in ev) / args.steps
+    macs = float(S) ** 3
+    value = macs / (ms_per_step * 1e-3) / 1e9  # GMAC/s over the whole step
+    achieved = macs / (gemm_ms * 1e-3) / 1e12  # TMAC/s of the GEMM kernel
+
+    result = {
+        "metric": "quire-exact posit MAC/s (GMAC/s) + % of integer-VALU peak, posit<8,0> GEMM",
+        "value": round(value, 1),
+        "unit": "GMAC/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "int32",
+        "data": "synthetic",
+        "config": {"workload": "posit<8,0> quire GEMM M=N=K=%d (BASELINE config 5), step = round A,B + gemm + convert + axpy" % S,
+                   "fin": "posit<8,0>", "fout": "posit<8,0>", "quire_bits": 32},
+        "roofline": {
+            "bound": "alu",
+            "kernel": "p8_gemm_kernel",
+            "achieved": round(achieved, 3),
+            "peak": round(PEAK_TMACS, 1),
+            "unit": "TMAC/s",
+            "frac": round(achieved / PEAK_TMACS, 4),
+            "kernel_ms": round(gemm_ms, 4),
+            "traffic": None,
+        },
+    }
+
+    if not args.no_cpu:
+        from oracle import fast
+        threads = fast.hw_threads()
+        A8n = A8.cpu().numpy()
+        B8n = B8.cpu().numpy()
+        rows = args.cpu_rows or max(8, min(S, (8 * threads * 4096 * 4096) // (S * S)))
+        t0 = time.perf_counter()
+        Cn, overflowed = fast.gemm(A8n, B8n, "p8", "p8", rows=(0, rows), threads=threads)
+        dt = time.perf_counter() - t0
+        mism = int((Cn[:rows] != C8[:rows].cpu().numpy()).sum())
+        result["cpu_baseline"] = {
+            "value": round(rows * float(S) * S / dt / 1e9, 4),
+            "unit": "GMAC/s",
+            "cores": threads,
+            "kind": "oracle",
+            "sample": "first %d rows of C (of %d), full K, C++ oracle with %d threads, %.1f s" % (rows, S, threads, dt),
+            "mismatches_vs_gpu": mism,
+            "quire_overflows": int(overflowed),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

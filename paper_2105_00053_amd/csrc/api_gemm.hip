@@ -2,7 +2,7 @@
 // forward, backward-data and backward-weight passes of Sec. 3.1 are its
 // transposition cases).
 #include "api_common.h"
-#include "quire_gemm.h"
+#include "gemm_p8.h"
 
 namespace pnn {
 
@@ -11,8 +11,12 @@ template <> struct GemmTile<P8> { static constexpr int TM = 4, TN = 4; };
 template <> struct GemmTile<P16> { static constexpr int TM = 4, TN = 4; };
 template <> struct GemmTile<P32> { static constexpr int TM = 2, TN = 2; };
 
+// posit<8,0> problems with both output dimensions beyond one small tile take the dot2 kernel
+inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
+
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
+    if (F::N == 8 && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
 }
 
@@ -27,6 +31,17 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     RowMajorOut out;
     out.ld = ldc;
     hipError_t e;
+    if (F::N == 8 && use_p8_kernel(M, N)) {
+        const uint8_t* a8 = (const uint8_t*)A;
+        const uint8_t* b8 = (const uint8_t*)B;
+        const uint8_t* bias8 = (const uint8_t*)bias;
+        // operand tiles are (rows x k): A's rows are m, B's rows are n; B is k-contiguous only when transposed
+        if (!transA && !transB) e = launch_p8_gemm<true, false>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
+        else if (!transA && transB) e = launch_p8_gemm<true, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
+        else if (transA && !transB) e = launch_p8_gemm<false, false>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
+        else e = launch_p8_gemm<false, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
+        return hip_status(e);
+    }
     // op(A)[i,k]: k contiguous unless transA.  op(B)[k,j] seen as rows j: k contiguous only when transB.
     if (!transA && !transB) {
         MatrixOperand<T, true> a{(const T*)A, lda, M, K};
@@ -72,7 +87,7 @@ extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int trans
         if (!A || !B) return PNN_EINVAL;
         if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return PNN_EINVAL;
     }
-    if (M * N >= ((int64_t)1 << 40) || K >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
+    if (M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     switch (fin) {
         case PNN_POSIT8_0:

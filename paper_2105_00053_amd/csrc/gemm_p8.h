@@ -1,0 +1,346 @@
+// posit<8,0> quire GEMM, the throughput kernel (paper Sec. 3.3: quire-accumulated
+// matrix product; Table 1: 32-bit quire for 8-bit posits).
+//
+// Every posit<8,0> value is a whole number of minpos = 2^-6 no larger than 2^12
+// in magnitude, so a decoded operand is a 14-bit signed integer and the 32-bit
+// quire is an int32 counting units of minpos^2 = 2^-12.  One v_dot2_i32_i16
+// performs two exact multiply-adds into that quire, which makes the packed
+// 16-bit dot product the fastest exact integer-VALU primitive for this format.
+//
+// Layout of the work: a 256-thread workgroup owns a 128 x 128 tile of C and
+// walks the reduction 32 elements at a time.  Patterns are fetched with 16-byte
+// (k-contiguous operand) or 8-byte (row-contiguous operand) coalesced loads,
+// decoded through a 256-entry table in LDS (Eq. 2 evaluated once per pattern
+// when the workgroup starts) and stored to LDS as pairs (k, k+1) packed in one
+// 32-bit word, [k-pair][row].  Each thread then reads 4+4 A words and 4+4 B
+// words per k-pair with four 128-bit LDS loads and issues 64 dot2 instructions
+// on its 8 x 8 register tile.  Global loads for the next slice are in flight
+// while the current one is consumed; LDS is double-buffered so one barrier per
+// slice suffices.  NaR patterns decode to zero and raise a per-row / per-column
+// flag that is applied when the tile is rounded.
+#pragma once
+
+#include "quire_gemm.h"
+
+namespace pnn {
+
+constexpr int P8_BM = 128, P8_BN = 128, P8_KT = 32, P8_KP = P8_KT / 2;
+
+typedef short p8_short2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ int32_t dot2_acc(uint32_t a, uint32_t b, int32_t c) {
+    return __builtin_amdgcn_sdot2(__builtin_bit_cast(p8_short2, a), __builtin_bit_cast(p8_short2, b), c, false);
+}
+
+// nonzero iff one of the four bytes of w is 0x80 (NaR)
+__device__ __forceinline__ uint32_t nar_bytes(uint32_t w) {
+    const uint32_t t = w ^ 0x80808080u;
+    return (t - 0x01010101u) & ~t & 0x80808080u;
+}
+
+struct P8Frag {
+    uint32_t w[4];
+};
+
+// Fetch this thread's 16 bytes of a 128-row x 32-k operand tile.
+//  KFAST (k contiguous in memory): thread t holds row t/2, k offsets (t%2)*16 .. +15.
+//  otherwise (rows contiguous):    thread t holds k-pair t/16, rows (t%16)*8 .. +7:
+//                                  w[0..1] = the 8 bytes at k even, w[2..3] = at k odd.
+// `fast` says the tile is interior and the addresses are aligned; otherwise bytes
+// are fetched one by one and read as zero outside [0,R) x [0,kend).
+template <bool KFAST>
+__device__ __forceinline__ P8Frag p8_fetch(const uint8_t* __restrict__ p, int64_t ld, int R, int r0, int k0, int kend,
+                                           int t, bool fast) {
+    P8Frag f;
+    if (KFAST) {
+        const int row = r0 + (t >> 1), kk = k0 + (t & 1) * 16;
+        if (fast) {
+            const uint4 v = *reinterpret_cast<const uint4*>(p + (int64_t)row * ld + kk);
+            f.w[0] = v.x; f.w[1] = v.y; f.w[2] = v.z; f.w[3] = v.w;
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t w = 0;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int k = kk + 4 * i + b;
+                    const uint32_t byte = (row < R && k < kend) ? p[(int64_t)row * ld + k] : 0u;
+                    w |= byte << (8 * b);
+                }
+                f.w[i] = w;
+            }
+        }
+    } else {
+        const int k = k0 + 2 * (t >> 4), row = r0 + (t & 15) * 8;
+        if (fast) {
+            const uint2 lo = *reinterpret_cast<const uint2*>(p + (int64_t)k * ld + row);
+            const uint2 hi = *reinterpret_cast<const uint2*>(p + (int64_t)(k + 1) * ld + row);
+            f.w[0] = lo.x; f.w[1] = lo.y; f.w[2] = hi.x; f.w[3] = hi.y;
+        } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    uint32_t w = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int r = row + 4 * i + b;
+                        const uint32_t byte = (r < R && k + h < kend) ? p[(int64_t)(k + h) * ld + r] : 0u;
+                        w |= byte << (8 * b);
+                    }
+                    f.w[2 * h + i] = w;
+                }
+            }
+        }
+    }
+    return f;
+}
+
+// Decode the fetched patterns through the LDS table and store them as packed
+// (k, k+1) pairs into dst[k-pair][row]; raise flags[row] for NaR patterns.
+template <bool KFAST>
+__device__ __forceinline__ void p8_stage(const P8Frag& f, uint32_t (*dst)[P8_BM], const uint16_t* tab, uint32_t* flags, int t) {
+    const uint32_t nar = nar_bytes(f.w[0]) | nar_bytes(f.w[1]) | nar_bytes(f.w[2]) | nar_bytes(f.w[3]);
+    if (KFAST) {
+        const int row = t >> 1, kp0 = (t & 1) * 8;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t w = f.w[i];
+            const uint32_t d0 = (uint32_t)tab[w & 0xFFu] | ((uint32_t)tab[(w >> 8) & 0xFFu] << 16);
+            const uint32_t d1 = (uint32_t)tab[(w >> 16) & 0xFFu] | ((uint32_t)tab[w >> 24] << 16);
+            dst[kp0 + 2 * i][row] = d0;
+            dst[kp0 + 2 * i + 1][row] = d1;
+        }
+        if (nar) flags[row] = 1;
+    } else {
+        const int kp = t >> 4, c = (t & 15) * 8;
+        uint32_t d[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t lo = (f.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+            const uint32_t hi = (f.w[2 + (j >> 2)] >> (8 * (j & 3))) & 0xFFu;
+            d[j] = (uint32_t)tab[lo] | ((uint32_t)tab[hi] << 16);
+        }
+        *reinterpret_cast<uint4*>(&dst[kp][c]) = make_uint4(d[0], d[1], d[2], d[3]);
+        *reinterpret_cast<uint4*>(&dst[kp][c + 4]) = make_uint4(d[4], d[5], d[6], d[7]);
+        if (nar) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t lo = (f.w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                const uint32_t hi = (f.w[2 + (j >> 2)] >> (8 * (j & 3))) & 0xFFu;
+                if (lo == 0x80u || hi == 0x80u) flags[c + j] = 1;
+            }
+        }
+    }
+}
+
+// int32 quire (units of 2^-12) -> posit<8,0>, nearest, ties to even pattern,
+// clamped to +-minpos / +-maxpos.  32-bit arithmetic only: the bit string after
+// the sign is assembled at the top of a word and cut after 7 bits.
+__device__ __forceinline__ uint32_t p8_round_quire(int32_t q) {
+    if (q == 0) return 0u;
+    const bool neg = q < 0;
+    const uint32_t mag = neg ? (0u - (uint32_t)q) : (uint32_t)q;
+    const int lz = __clz((int)mag);
+    const int k = 19 - lz;  // floor(log2(mag)) - 12
+    uint32_t body;
+    if (k >= 6) {
+        body = 0x7Fu;
+    } else if (k < -6) {
+        body = 0x01u;
+    } else {
+        const uint32_t frac = (mag << lz) << 1;  // fraction bits at the top, leading one gone
+        uint32_t s;
+        if (k >= 0) s = (uint32_t)((int32_t)0x80000000 >> k) | (frac >> (k + 2));  // k+1 ones, a zero, fraction
+        else s = (0x80000000u | (frac >> 1)) >> (-k);                              // -k zeros, a one, fraction
+        const uint32_t r = s >> 24;  // 7 kept bits and the guard bit
+        const uint32_t sticky = (s & 0x00FFFFFFu) ? 1u : 0u;
+        body = (r >> 1) + ((r & 1u) & (sticky | ((r >> 1) & 1u)));
+    }
+    return neg ? ((0u - body) & 0xFFu) : body;
+}
+
+template <bool A_KFAST, bool B_KFAST>
+__global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
+    const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
+    const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout,
+    int M, int N, int K, int k_per_split, int tiles_m, int tiles_n, int a_aligned, int b_aligned, SplitWs ws) {
+    __shared__ __attribute__((aligned(16))) uint32_t As[2][P8_KP][P8_BM];
+    __shared__ __attribute__((aligned(16))) uint32_t Bs[2][P8_KP][P8_BN];
+    __shared__ uint16_t tab[256];
+    __shared__ uint32_t rowNaR[P8_BM];
+    __shared__ uint32_t colNaR[P8_BN];
+
+    const int t = threadIdx.x;
+    const int tx = t & 15, ty = t >> 4;
+
+    // XCD-aware order: consecutive workgroup ids go round-robin to the 8 XCDs, so give each XCD
+    // a contiguous run of tiles (neighbouring tiles share operand panels in that XCD's L2).
+    const int nblk = tiles_m * tiles_n;
+    int lid = blockIdx.x;
+    if ((nblk & 7) == 0) lid = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+    // tiles are walked in bands of 8 tile-rows, column by column inside a band
+    const int band = lid / (8 * tiles_n);
+    const int band_rows = (tiles_m - band * 8) < 8 ? (tiles_m - band * 8) : 8;
+    const int in_band = lid - band * 8 * tiles_n;
+    const int m0 = (band * 8 + in_band % band_rows) * P8_BM;
+    const int n0 = (in_band / band_rows) * P8_BN;
+
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
+
+    tab[t] = (uint16_t)Arith<P8>::stage((uint32_t)t);
+    if (t < P8_BM) rowNaR[t] = 0; else colNaR[t - P8_BM] = 0;
+
+    int32_t acc[8][8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0;
+
+    const bool a_rows_in = (m0 + P8_BM <= M) && a_aligned;
+    const bool b_rows_in = (n0 + P8_BN <= N) && b_aligned;
+    const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
+
+    __syncthreads();  // table and flags ready
+    if (nkt > 0) {
+        const bool kin = kbeg + P8_KT <= kend;
+        const P8Frag fa = p8_fetch<A_KFAST>(A, lda, M, m0, kbeg, kend, t, a_rows_in && kin);
+        const P8Frag fb = p8_fetch<B_KFAST>(B, ldb, N, n0, kbeg, kend, t, b_rows_in && kin);
+        p8_stage<A_KFAST>(fa, As[0], tab, rowNaR, t);
+        p8_stage<B_KFAST>(fb, Bs[0], tab, colNaR, t);
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nkt;
+        P8Frag fa, fb;
+        if (more) {
+            const int k0 = kbeg + (kt + 1) * P8_KT;
+            const bool kin = k0 + P8_KT <= kend;
+            fa = p8_fetch<A_KFAST>(A, lda, M, m0, k0, kend, t, a_rows_in && kin);
+            fb = p8_fetch<B_KFAST>(B, ldb, N, n0, k0, kend, t, b_rows_in && kin);
+        }
+#pragma unroll 2
+        for (int kp = 0; kp < P8_KP; ++kp) {
+            const uint4 a0 = *reinterpret_cast<const uint4*>(&As[cur][kp][ty * 4]);
+            const uint4 a1 = *reinterpret_cast<const uint4*>(&As[cur][kp][64 + ty * 4]);
+            const uint4 b0 = *reinterpret_cast<const uint4*>(&Bs[cur][kp][tx * 4]);
+            const uint4 b1 = *reinterpret_cast<const uint4*>(&Bs[cur][kp][64 + tx * 4]);
+            const uint32_t a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+            const uint32_t b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
+        }
+        if (more) {
+            p8_stage<A_KFAST>(fa, As[cur ^ 1], tab, rowNaR, t);
+            p8_stage<B_KFAST>(fb, Bs[cur ^ 1], tab, colNaR, t);
+        }
+        __syncthreads();
+    }
+
+    // rows / columns of this thread's register tile
+    if (gridDim.z == 1) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int lr = (i < 4) ? ty * 4 + i : 64 + ty * 4 + (i - 4);
+            const int m = m0 + lr;
+            if (m >= M) continue;
+            const bool rnar = rowNaR[lr] != 0;
+#pragma unroll
+            for (int jh = 0; jh < 2; ++jh) {
+                const int lc = jh * 64 + tx * 4;
+                const int n = n0 + lc;
+                uint32_t res[4];
+                bool narv[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    int32_t q = acc[i][jh * 4 + j];
+                    bool nar = rnar || colNaR[lc + j] != 0;
+                    if (bias && n + j < N) {
+                        const uint32_t bp = bias[n + j];
+                        if (bp == 0x80u) nar = true;
+                        else q += (int32_t)(int16_t)tab[bp] << P8::MAXS;  // + bias * 1
+                    }
+                    narv[j] = nar;
+                    res[j] = (uint32_t)q;
+                }
+                if (fout == 0) {
+                    uint32_t out[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) out[j] = narv[j] ? 0x80u : p8_round_quire((int32_t)res[j]);
+                    uint8_t* crow = (uint8_t*)C + (int64_t)m * ldc + n;
+                    if (n + 4 <= N && (((uintptr_t)crow) & 3) == 0) {
+                        *reinterpret_cast<uint32_t*>(crow) = out[0] | (out[1] << 8) | (out[2] << 16) | (out[3] << 24);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < N) crow[j] = (uint8_t)out[j];
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        if (n + j >= N) continue;
+                        const uint32_t q1[1] = {res[j]};
+                        round_store<P8, 1>(q1, narv[j], fout, C, (int64_t)m * ldc + n + j);
+                    }
+                }
+            }
+        }
+    } else {
+        const int64_t z = blockIdx.z;
+        uint32_t* lim = ws.limbs + z * (int64_t)M * N;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int lr = (i < 4) ? ty * 4 + i : 64 + ty * 4 + (i - 4);
+            const int m = m0 + lr;
+            if (m >= M) continue;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int n = n0 + ((j < 4) ? tx * 4 + j : 64 + tx * 4 + (j - 4));
+                if (n < N) lim[(int64_t)m * N + n] = (uint32_t)acc[i][j];
+            }
+        }
+        if (t < P8_BM) {
+            if (m0 + t < M && rowNaR[t]) atomicOr(&ws.rowflag[z * M + m0 + t], 1u);
+        } else {
+            const int c = t - P8_BM;
+            if (n0 + c < N && colNaR[c]) atomicOr(&ws.colflag[z * N + n0 + c], 1u);
+        }
+    }
+}
+
+// Host launcher.  Returns hipSuccess or the launch error.
+template <bool A_KFAST, bool B_KFAST>
+hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                          const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N, int64_t K,
+                          void* workspace, const GemmPlan& plan) {
+    const int tiles_m = (int)((M + P8_BM - 1) / P8_BM), tiles_n = (int)((N + P8_BN - 1) / P8_BN);
+    // vector loads need aligned addresses: 16 bytes along k, 8 bytes along rows
+    const int a_al = A_KFAST ? (((uintptr_t)A % 16 == 0) && (lda % 16 == 0)) : (((uintptr_t)A % 8 == 0) && (lda % 8 == 0));
+    const int b_al = B_KFAST ? (((uintptr_t)B % 16 == 0) && (ldb % 16 == 0)) : (((uintptr_t)B % 8 == 0) && (ldb % 8 == 0));
+    SplitWs ws;
+    ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)workspace;
+        ws.rowflag = ws.limbs + (size_t)plan.splits * M * N;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * M;
+        const int64_t nflags = (int64_t)plan.splits * (M + N);
+        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, ws.rowflag, nflags);
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    hipLaunchKernelGGL((p8_gemm_kernel<A_KFAST, B_KFAST>), grid, dim3(256), 0, stream, A, lda, B, ldb, bias, C, ldc, fout,
+                       (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, a_al, b_al, ws);
+    if (plan.splits > 1) {
+        RowMajorOut out{ldc};
+        const int64_t total = M * N;
+        hipLaunchKernelGGL((split_merge_kernel<P8, RowMajorOut>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
+                           ws, plan.splits, M, N, bias, C, fout, out);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace pnn

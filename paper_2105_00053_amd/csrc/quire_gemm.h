@@ -343,7 +343,7 @@ struct GemmPlan {
 
 // How many ways to split the reduction: only when the output tiles alone cannot
 // fill the chip and the reduction is long.
-inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int L) {
+inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int L, int KT = GEMM_KT) {
     GemmPlan p;
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     int splits = 1;
@@ -356,8 +356,8 @@ inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int 
         if (s >= 2) splits = (int)s;
     }
     int64_t kps = (K + splits - 1) / splits;
-    kps = (kps + GEMM_KT - 1) / GEMM_KT * GEMM_KT;
-    if (kps < GEMM_KT) kps = GEMM_KT;
+    kps = (kps + KT - 1) / KT * KT;
+    if (kps < KT) kps = KT;
     splits = (int)((K + kps - 1) / kps);
     if (splits < 1) splits = 1;
     p.splits = splits;
