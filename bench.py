@@ -32,6 +32,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s
+# HBM-side bytes per launch of the GEMM kernel at 4096^3, from two rocprofv3 --pmc passes
+# (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE 92322 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 16384 KiB.
+GEMM_4096_TRAFFIC_BYTES = int((2.0 * 92322 + 16384) * 1024)
 
 
 def main():
@@ -42,6 +45,8 @@ def main():
     ap.add_argument("--size", type=int, default=4096, help="M = N = K")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one 256 MiB device copy before timing (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path is data-parallel over rows of A; "
@@ -86,6 +91,15 @@ def main():
         pn.posit_convert(C8, "p8", "p16", out=C16)
         pn.posit_axpy(lr_bits, C16, W, "p16", "p16", fcopy="p8", y_copy=W8)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        src.fill_(1)
+        torch.cuda.synchronize()
+        dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -123,7 +137,8 @@ def main():
             "unit": "TMAC/s",
             "frac": round(achieved / PEAK_TMACS, 4),
             "kernel_ms": round(gemm_ms, 4),
-            "traffic": None,
+            "algorithmic_bytes": 3 * S * S,
+            "traffic": GEMM_4096_TRAFFIC_BYTES if S == 4096 else None,
         },
     }
 
