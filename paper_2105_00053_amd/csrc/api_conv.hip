@@ -6,7 +6,7 @@
 //   bwd_data   rows (n,h,w)    x cols c          reduce over (k,r,s)
 //   bwd_weight rows k          x cols (c,r,s)    reduce over (n,oh,ow)
 #include "api_common.h"
-#include "quire_gemm.h"
+#include "conv_p8.h"
 
 namespace pnn {
 
@@ -45,6 +45,48 @@ inline ConvDims conv_dims(int which, const ConvGeom& g) {
     return d;
 }
 
+
+template <class Out>
+hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
+                          const GemmPlan& plan, const Out& merge_out) {
+    const P8ConvTile tl = p8_conv_tile(p.M, p.N, p.K);
+    const int tiles_m = (p.M + tl.bm - 1) / tl.bm, tiles_n = (p.N + tl.bn - 1) / tl.bn;
+    SplitWs ws;
+    ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)wsp;
+        ws.rowflag = ws.limbs + (size_t)plan.splits * p.M * p.N;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * p.Mw;
+        const int64_t nflags = (int64_t)plan.splits * (p.M + p.N);
+        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
+#define PNN_LAUNCH_CONV(TY, TX, TM, TN)                                                                                   \
+    hipLaunchKernelGGL((p8_conv_kernel<TY, TX, TM, TN>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, \
+                       p.K, (int)plan.k_per_split, tiles_n, ws, p.transposed)
+    if (tl.bm == 128 && tl.bn == 128) PNN_LAUNCH_CONV(16, 16, 8, 8);
+    else if (tl.bm == 256 && tl.bn == 64) PNN_LAUNCH_CONV(32, 8, 8, 8);
+    else if (tl.bm == 256 && tl.bn == 32) PNN_LAUNCH_CONV(32, 8, 8, 4);
+    else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_CONV(16, 16, 8, 4);
+    else PNN_LAUNCH_CONV(16, 16, 4, 4);
+#undef PNN_LAUNCH_CONV
+    if (plan.splits > 1) launch_split_merge<P8, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
+    return hipGetLastError();
+}
+
+hipError_t p8_conv_launch_rowmajor(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
+                                   const GemmPlan& plan, int64_t ld) {
+    RowMajorOut o{ld};
+    return p8_conv_launch(st, p, bias, C, fout, wsp, plan, o);
+}
+
+hipError_t p8_conv_launch_nchw(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
+                               const GemmPlan& plan, int64_t spatial, int64_t channels) {
+    NchwOut o{spatial, channels};
+    return p8_conv_launch(st, p, bias, C, fout, wsp, plan, o);
+}
+
 template <class F>
 GemmPlan conv_plan(const ConvDims& d) {
     return plan_split(d.M, d.N, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
@@ -61,6 +103,10 @@ size_t conv_ws(int which, const ConvGeom& g) {
     const ConvDims d = conv_dims(which, g);
     if (d.M <= 0 || d.N <= 0) return 0;
     size_t b = conv_plan<F>(d).ws_bytes;
+    if (F::N == 8 && p8_conv_eligible(which, g)) {
+        const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
+        b = p8_conv_plan(p.M, p.N, p.K).ws_bytes;
+    }
     if (which == 2) {
         const size_t b2 = dbias_plan<F>(d).ws_bytes;
         if (b2 > b) b = b2;
@@ -73,6 +119,13 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
              void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(0, g);
+    if (F::N == 8 && p8_conv_eligible(0, g)) {
+        const P8ConvProblem p = p8_problem(0, g, x, w);
+        const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
+        if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+        NchwOut mout{(int64_t)g.OH * g.OW, (int64_t)g.K};
+        return hip_status(p8_conv_launch(st, p, (const uint8_t*)bias, y, fout, ws, plan, mout));
+    }
     const GemmPlan plan = conv_plan<F>(d);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
     ConvFwdX<T> a{(const T*)x, g, d.M, d.K};
@@ -86,6 +139,13 @@ template <class F>
 int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
+    if (F::N == 8 && p8_conv_eligible(1, g)) {
+        const P8ConvProblem p = p8_problem(1, g, dy, w);
+        const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
+        if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+        NchwOut mout{(int64_t)g.H * g.W, (int64_t)g.C};
+        return hip_status(p8_conv_launch(st, p, nullptr, dx, fout, ws, plan, mout));
+    }
     const GemmPlan plan = conv_plan<F>(d);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
     ConvBwdDataDy<T> a{(const T*)dy, g, d.M, d.K};
@@ -100,15 +160,25 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
                     void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(2, g);
-    const GemmPlan plan = conv_plan<F>(d);
+    const bool fastp8 = F::N == 8 && p8_conv_eligible(2, g);
+    GemmPlan plan = conv_plan<F>(d);
+    P8ConvProblem p8p;
+    if (fastp8) {
+        p8p = p8_problem(2, g, dy, x);
+        plan = p8_conv_plan(p8p.M, p8p.N, p8p.K);
+    }
     const GemmPlan bplan = dbias_plan<F>(d);
     const size_t need = (dbias && bplan.ws_bytes > plan.ws_bytes) ? bplan.ws_bytes : plan.ws_bytes;
     if (need > 0 && (!ws || ws_bytes < need)) return PNN_EWORKSPACE;
     ConvBwdWeightDy<T> a{(const T*)dy, g, d.M, d.K};
     ConvBwdWeightX<T> b{(const T*)x, g, d.N, d.K};
     RowMajorOut out{d.N};
-    hipError_t e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
-        st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
+    hipError_t e;
+    if (fastp8)
+        e = p8_conv_launch(st, p8p, nullptr, dw, fout, ws, plan, out);
+    else
+        e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
+            st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
     if (e == hipSuccess && dbias) {
         // dbias[k] = sum dy[n,k,:,:] * 1 : the same kernel against a column of ones
         // (stream order keeps the shared workspace safe)

@@ -2,7 +2,7 @@
 // forward, backward-data and backward-weight passes of Sec. 3.1 are its
 // transposition cases).
 #include "api_common.h"
-#include "gemm_p8.h"
+#include "conv_p8.h"
 
 namespace pnn {
 
@@ -17,6 +17,8 @@ inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
     if (F::N == 8 && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
+    // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
+    if (F::N == 8 && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
 }
 
@@ -41,6 +43,10 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
         else if (transA && !transB) e = launch_p8_gemm<false, false>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
         else e = launch_p8_gemm<false, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
         return hip_status(e);
+    }
+    if (F::N == 8 && p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
+        const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
+        return hip_status(p8_conv_launch_rowmajor(st, p, (const uint8_t*)bias, C, fout, ws, plan, ldc));
     }
     // op(A)[i,k]: k contiguous unless transA.  op(B)[k,j] seen as rows j: k contiguous only when transB.
     if (!transA && !transB) {

@@ -336,9 +336,7 @@ hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, con
                        (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, a_al, b_al, ws);
     if (plan.splits > 1) {
         RowMajorOut out{ldc};
-        const int64_t total = M * N;
-        hipLaunchKernelGGL((split_merge_kernel<P8, RowMajorOut>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                           ws, plan.splits, M, N, bias, C, fout, out);
+        launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
     }
     return hipGetLastError();
 }

@@ -303,37 +303,80 @@ __global__ void split_clear_kernel(uint32_t* p, int64_t n) {
     if (i < n) p[i] = 0;
 }
 
-// Merge the per-split partial quires (multi-word add with carry), add the bias,
-// round once, store.
-template <class FIN, class Out>
-__global__ void split_merge_kernel(SplitWs ws, int splits, int64_t M, int64_t N,
-                                   const typename Storage<FIN::N>::T* __restrict__ bias,
-                                   void* __restrict__ C, int fout, Out out) {
+// Merge the per-split partial quires, add the bias, round once, store.  A
+// 256-thread workgroup handles 32 consecutive outputs; its 8 thread rows each sum
+// every 8th split (independent loads in flight, 128-byte coalesced rows), then the
+// 8 partial quires of an output are combined through LDS with carry-propagating adds.
+// Integer addition modulo 2^(32 L) is associative, so the order does not matter.
+// With few splits one thread per output (ZG = 1) is enough.
+template <class FIN, class Out, int MERGE_ZG>
+__global__ __launch_bounds__(256) void split_merge_kernel(SplitWs ws, int splits, int64_t M, int64_t N,
+                                                          const typename Storage<FIN::N>::T* __restrict__ bias,
+                                                          void* __restrict__ C, int fout, Out out) {
     typedef Arith<FIN> AR;
     constexpr int L = AR::L;
-    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (idx >= M * N) return;
-    const int64_t m = idx / N, n = idx % N;
+    constexpr int MERGE_OUTS = 256 / MERGE_ZG;
+    __shared__ uint32_t part_s[MERGE_ZG > 1 ? MERGE_ZG : 1][MERGE_ZG > 1 ? MERGE_OUTS : 1][L];
+    __shared__ uint32_t nar_s[MERGE_ZG > 1 ? MERGE_ZG : 1][MERGE_ZG > 1 ? MERGE_OUTS : 1];
+    const int o = threadIdx.x % MERGE_OUTS, zg = threadIdx.x / MERGE_OUTS;
+    const int64_t total = M * N;
+    const int64_t idx = (int64_t)blockIdx.x * MERGE_OUTS + o;
+    const bool live = idx < total;
+    const int64_t m = live ? idx / N : 0, n = live ? idx % N : 0;
     uint32_t q[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) q[l] = 0;
-    bool nar = false;
-    for (int z = 0; z < splits; ++z) {
-        uint32_t part[L];
+    uint32_t nar = 0;
+    if (live) {
+#pragma unroll 4
+        for (int z = zg; z < splits; z += MERGE_ZG) {
+            uint32_t part[L];
 #pragma unroll
-        for (int l = 0; l < L; ++l) part[l] = ws.limbs[((int64_t)z * M * N + idx) * L + l];
-        quire_merge<L>(q, part);
-        nar = nar || ws.rowflag[(int64_t)z * M + m] || ws.colflag[(int64_t)z * N + n];
+            for (int l = 0; l < L; ++l) part[l] = ws.limbs[((int64_t)z * total + idx) * L + l];
+            quire_merge<L>(q, part);
+            nar |= ws.rowflag[(int64_t)z * M + m] | ws.colflag[(int64_t)z * N + n];
+        }
     }
+    if (MERGE_ZG > 1) {
+#pragma unroll
+        for (int l = 0; l < L; ++l) part_s[zg][o][l] = q[l];
+        nar_s[zg][o] = nar;
+        __syncthreads();
+        if (zg != 0) return;
+#pragma unroll
+        for (int g = 1; g < MERGE_ZG; ++g) {
+            uint32_t part[L];
+#pragma unroll
+            for (int l = 0; l < L; ++l) part[l] = part_s[g][o][l];
+            quire_merge<L>(q, part);
+            nar |= nar_s[g][o];
+        }
+    }
+    if (!live) return;
+    bool isnar = nar != 0;
     if (bias) {
         const uint32_t bp = bias[n];
-        if (bp == FIN::NAR) nar = true;
+        if (bp == FIN::NAR) isnar = true;
         else AR::add_value(q, AR::stage(bp));
     }
-    round_store<FIN, L>(q, nar, fout, C, out(m, n));
+    round_store<FIN, L>(q, isnar, fout, C, out(m, n));
 }
 
 // ---- host side ----
+
+template <class FIN, class Out>
+void launch_split_merge(hipStream_t stream, const SplitWs& ws, int splits, int64_t M, int64_t N, const void* bias, void* C, int fout,
+                        const Out& out) {
+    typedef typename Storage<FIN::N>::T TI;
+    const int64_t total = M * N;
+    if (splits >= 16) {
+        hipLaunchKernelGGL((split_merge_kernel<FIN, Out, 8>), dim3((unsigned)((total + 31) / 32)), dim3(256), 0, stream, ws, splits, M, N,
+                           (const TI*)bias, C, fout, out);
+    } else {
+        hipLaunchKernelGGL((split_merge_kernel<FIN, Out, 1>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, ws, splits, M, N,
+                           (const TI*)bias, C, fout, out);
+    }
+}
 
 struct GemmPlan {
     int splits;
@@ -387,11 +430,7 @@ hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb,
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN>), grid, dim3(GEMM_THREADS), 0, stream,
                        opa, opb, out, M, N, K, plan.k_per_split, (const TI*)bias, C, fout, ws, (int)tiles_n);
-    if (plan.splits > 1) {
-        const int64_t total = M * N;
-        hipLaunchKernelGGL((split_merge_kernel<FIN, Out>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream,
-                           ws, plan.splits, M, N, (const TI*)bias, C, fout, out);
-    }
+    if (plan.splits > 1) launch_split_merge<FIN, Out>(stream, ws, plan.splits, M, N, bias, C, fout, out);
     return hipGetLastError();
 }
 
