@@ -69,6 +69,26 @@ PNN_HD uint32_t quire_round(const uint32_t (&q)[L]) {
     return encode<FOUT>(r);
 }
 
+// 128-bit quire (posit<16,1>): the sign-extended product shifted by s & 63 is a
+// 128-bit value (x0, x1); products landing in the upper half (s >= 64) only keep x0
+// (the rest is beyond bit 127, i.e. gone modulo 2^128).  One 128-bit add follows.
+PNN_HD void quire_add128(uint32_t (&q)[4], int32_t P, int s) {
+    typedef unsigned __int128 u128;
+    const int off = s & 63;
+    const int64_t p64 = (int64_t)P;
+    const uint64_t x0 = (uint64_t)p64 << off;
+    const uint64_t x1 = (uint64_t)((p64 >> 1) >> (63 - off));  // bits 64..127 of the shifted value
+    const bool upper = s >= 64;
+    const uint64_t a0 = upper ? 0ull : x0;
+    const uint64_t a1 = upper ? x0 : x1;
+    u128 Q = ((u128)(((uint64_t)q[3] << 32) | q[2]) << 64) | (((uint64_t)q[1] << 32) | q[0]);
+    Q += ((u128)a1 << 64) | a0;
+    q[0] = (uint32_t)Q;
+    q[1] = (uint32_t)(Q >> 32);
+    q[2] = (uint32_t)(Q >> 64);
+    q[3] = (uint32_t)(Q >> 96);
+}
+
 template <class F>
 struct Arith;
 
@@ -121,10 +141,10 @@ struct Arith<P16> {
 #else
         const int32_t P = sa * sb;
 #endif
-        quire_add32<4>(q, P, (int)(a >> 16) + (int)(b >> 16));
+        quire_add128(q, P, (int)(a >> 16) + (int)(b >> 16));
     }
     PNN_HD static void add_value(uint32_t (&q)[4], Elem a) {
-        quire_add32<4>(q, (int16_t)(a & 0xFFFFu), (int)(a >> 16) + P16::MAXS);
+        quire_add128(q, (int16_t)(a & 0xFFFFu), (int)(a >> 16) + P16::MAXS);
     }
 };
 

@@ -384,16 +384,17 @@ struct GemmPlan {
     size_t ws_bytes;
 };
 
-// How many ways to split the reduction: only when the output tiles alone cannot
-// fill the chip and the reduction is long.
+// How many ways to split the reduction: when the output tiles alone leave the
+// 256 CUs short of about four workgroups each and the reduction is long enough
+// to keep at least 256 steps per slice.
 inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int L, int KT = GEMM_KT) {
     GemmPlan p;
     const int64_t tiles = ((M + BM - 1) / BM) * ((N + BN - 1) / BN);
     int splits = 1;
-    const int64_t target = 1024;  // workgroups wanted: 4 per CU on 256 CUs
-    if (tiles < 256 && K >= 1024) {
-        int64_t s = target / (tiles > 0 ? tiles : 1);
-        const int64_t max_by_k = K / 256;  // keep at least 256 reduction steps per split
+    const int64_t target = 1024;
+    if (tiles < target && K >= 1024) {
+        int64_t s = (target + tiles - 1) / (tiles > 0 ? tiles : 1);
+        const int64_t max_by_k = K / 256;
         if (s > max_by_k) s = max_by_k;
         if (s > 256) s = 256;
         if (s >= 2) splits = (int)s;
