@@ -30,6 +30,48 @@ __global__ __launch_bounds__(256) void map_scalar_kernel(const TS* __restrict__ 
     dst[i] = (TD)op((uint64_t)src[i]);
 }
 
+// 8-bit sources: the conversion is a function of 256 patterns, so each workgroup
+// evaluates it once into an LDS table and then only looks bytes up.  One thread
+// produces one 16-byte store (V = 16 / sizeof(TD) elements), so that both the
+// loads and the stores of a wavefront are contiguous.
+template <class TD, class Op>
+__global__ __launch_bounds__(256) void map_p8_table_kernel(const uint8_t* __restrict__ src, TD* __restrict__ dst, int64_t nvec, Op op) {
+    constexpr int V = 16 / sizeof(TD);
+    __shared__ TD table[256];
+    table[threadIdx.x] = (TD)op((uint64_t)threadIdx.x);
+    __syncthreads();
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= nvec) return;
+    const Pack<uint8_t, V> in = reinterpret_cast<const Pack<uint8_t, V>*>(src)[i];
+    Pack<TD, V> o;
+#pragma unroll
+    for (int j = 0; j < V; ++j) o.v[j] = table[in.v[j]];
+    reinterpret_cast<Pack<TD, V>*>(dst)[i] = o;
+}
+
+template <class TS, class TD, class Op>
+int launch_map(hipStream_t st, const void* src, void* dst, int64_t n, Op op);
+
+template <class TD, class Op>
+int launch_map_p8(hipStream_t st, const void* src, void* dst, int64_t n, Op op) {
+    int64_t done = 0;
+    constexpr int V = 16 / sizeof(TD);
+    if (aligned(src, V) && aligned(dst, 16)) {
+        const int64_t nvec = n / V;
+        if (nvec > 0) {
+            hipLaunchKernelGGL((map_p8_table_kernel<TD, Op>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
+                               (const uint8_t*)src, (TD*)dst, nvec, op);
+            done = nvec * V;
+        }
+    }
+    if (done < n) {
+        const int64_t rest = n - done;
+        hipLaunchKernelGGL((map_scalar_kernel<uint8_t, TD, Op>), dim3((unsigned)((rest + 255) / 256)), dim3(256), 0, st,
+                           (const uint8_t*)src, (TD*)dst, done, n, op);
+    }
+    return hip_status(hipGetLastError());
+}
+
 template <class TS, class TD, class Op>
 int launch_map(hipStream_t st, const void* src, void* dst, int64_t n, Op op) {
     constexpr int WIDE = sizeof(TS) > sizeof(TD) ? sizeof(TS) : sizeof(TD);
@@ -58,15 +100,15 @@ __global__ __launch_bounds__(256) void axpy_vec_kernel(const TX* __restrict__ x,
     if (i >= nvec) return;
     const Pack<TX, V> xv = reinterpret_cast<const Pack<TX, V>*>(x)[i];
     Pack<TY, V> yv = reinterpret_cast<Pack<TY, V>*>(y)[i];
-    Pack<TC, V> cv;
 #pragma unroll
-    for (int j = 0; j < V; ++j) {
-        const uint32_t r = op((uint32_t)xv.v[j], (uint32_t)yv.v[j]);
-        yv.v[j] = (TY)r;
-        cv.v[j] = (TC)cp((uint64_t)r);
-    }
+    for (int j = 0; j < V; ++j) yv.v[j] = (TY)op((uint32_t)xv.v[j], (uint32_t)yv.v[j]);
     reinterpret_cast<Pack<TY, V>*>(y)[i] = yv;
-    if (yc) reinterpret_cast<Pack<TC, V>*>(yc)[i] = cv;
+    if (yc) {  // narrowed copy of the new y (uniform branch)
+        Pack<TC, V> cv;
+#pragma unroll
+        for (int j = 0; j < V; ++j) cv.v[j] = (TC)cp((uint64_t)yv.v[j]);
+        reinterpret_cast<Pack<TC, V>*>(yc)[i] = cv;
+    }
 }
 
 template <class TX, class TY, class TC, class Op, class Cp>
@@ -131,6 +173,16 @@ int axpy_pick_y(hipStream_t st, int fy, uint32_t alpha, int64_t n, const void* x
 template <class FS>
 int convert_from(hipStream_t st, int dst, int64_t n, const void* s, void* d) {
     typedef typename Storage<FS::N>::T TS;
+    if (FS::N == 8) {
+        switch (dst) {
+            case PNN_POSIT8_0: return launch_map_p8<uint8_t>(st, s, d, n, PositToPosit<FS, P8>());
+            case PNN_POSIT16_1: return launch_map_p8<uint16_t>(st, s, d, n, PositToPosit<FS, P16>());
+            case PNN_POSIT32_2: return launch_map_p8<uint32_t>(st, s, d, n, PositToPosit<FS, P32>());
+            case PNN_F32: return launch_map_p8<uint32_t>(st, s, d, n, PositToF32<FS>());
+            case PNN_F64: return launch_map_p8<uint64_t>(st, s, d, n, PositToF64<FS>());
+        }
+        return PNN_EINVAL;
+    }
     switch (dst) {
         case PNN_POSIT8_0: return launch_map<TS, uint8_t>(st, s, d, n, PositToPosit<FS, P8>());
         case PNN_POSIT16_1: return launch_map<TS, uint16_t>(st, s, d, n, PositToPosit<FS, P16>());

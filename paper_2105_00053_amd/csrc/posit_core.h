@@ -144,6 +144,116 @@ PNN_HD uint32_t encode(const Real& r) {
     return r.neg ? ((0u - body) & F::MASK) : body;
 }
 
+// 32-bit variants for the bandwidth-bound kernels: a posit carries at most 27
+// fraction bits, so a decoded value fits a 32-bit fraction, and for formats of at
+// most 16 bits the cut string regime | exponent | fraction fits one 32-bit word.
+struct Real32 {
+    bool neg;
+    int scale;
+    uint32_t frac;  // fraction bits at the top
+    bool sticky;
+};
+
+PNN_HD Real32 narrow(const Real& r) {
+    Real32 o;
+    o.neg = r.neg;
+    o.scale = r.scale;
+    o.frac = (uint32_t)(r.frac >> 32);
+    o.sticky = r.sticky || ((uint32_t)r.frac != 0);
+    return o;
+}
+
+PNN_HD Real widen(const Real32& r) {
+    Real o;
+    o.neg = r.neg;
+    o.scale = r.scale;
+    o.frac = (uint64_t)r.frac << 32;
+    o.sticky = r.sticky;
+    return o;
+}
+
+template <class F>
+PNN_HD Real32 decode_fields32(uint32_t p) {
+    Real32 r;
+    r.neg = (p >> (F::N - 1)) & 1u;
+    const uint32_t x = r.neg ? ((0u - p) & F::MASK) : p;
+    const uint32_t y = x << (33 - F::N);
+    const uint32_t lead = y >> 31;
+    const int run = clz32(lead ? ~y : y);
+    const int k = lead ? run - 1 : -run;
+    const uint32_t rest = (y << run) << 1;
+    int e = 0;
+    uint32_t fr = rest;
+    if (F::ES > 0) {
+        e = (int)(rest >> (32 - F::ES));
+        fr = rest << F::ES;
+    }
+    r.scale = k * (1 << F::ES) + e;
+    r.frac = fr;
+    r.sticky = false;
+    return r;
+}
+
+// Same rounding as encode<F>, in one 32-bit word; F::N <= 16.
+template <class F>
+PNN_HD uint32_t encode32(const Real32& r) {
+    static_assert(F::N <= 16, "32-bit encoder is for formats of at most 16 bits");
+    uint32_t body;
+    if (r.scale >= F::MAXS) {
+        body = F::NAR - 1u;
+    } else if (r.scale < -F::MAXS) {
+        body = 1u;
+    } else {
+        const int k = r.scale >> F::ES;
+        const uint32_t e = (uint32_t)(r.scale & ((1 << F::ES) - 1));
+        const int rl = k >= 0 ? k + 2 : 1 - k;
+        const uint32_t regime = k >= 0 ? ((1u << (k + 2)) - 2u) : 1u;
+        const int hl = rl + F::ES;  // 2 .. N-1+ES <= 17
+        const uint32_t head = (regime << F::ES) | e;
+        const uint32_t w = (head << (32 - hl)) | (r.frac >> hl);
+        bool sticky = r.sticky || ((r.frac << (32 - hl)) != 0);
+        body = w >> (33 - F::N);
+        const uint32_t guard = (w >> (32 - F::N)) & 1u;
+        sticky = sticky || ((w << F::N) != 0);
+        body += guard & ((sticky ? 1u : 0u) | (body & 1u));
+    }
+    return r.neg ? ((0u - body) & F::MASK) : body;
+}
+
+// Straight-line form of encode32 for code that is already branch-free: a scale
+// beyond the format is replaced by the largest (smallest) regular scale with an
+// all-ones (zero) fraction, which rounds to maxpos (minpos).
+template <class F>
+PNN_HD uint32_t encode32_flat(const Real32& r) {
+    static_assert(F::N <= 16, "32-bit encoder is for formats of at most 16 bits");
+    const bool over = r.scale >= F::MAXS, under = r.scale < -F::MAXS;
+    const int scale = over ? F::MAXS - 1 : (under ? -F::MAXS : r.scale);
+    const uint32_t frac = over ? 0xFFFFFFFFu : (under ? 0u : r.frac);
+    const bool sticky_in = over ? true : (under ? false : r.sticky);
+    const int k = scale >> F::ES;
+    const uint32_t e = (uint32_t)(scale & ((1 << F::ES) - 1));
+    const bool pos = k >= 0;
+    const int rl = pos ? k + 2 : 1 - k;
+    const uint32_t regime = pos ? ((1u << ((k + 2) & 31)) - 2u) : 1u;
+    const int hl = rl + F::ES;
+    const uint32_t head = (regime << F::ES) | e;
+    const uint32_t w = (head << (32 - hl)) | (frac >> hl);
+    const bool sticky = sticky_in || ((frac << (32 - hl)) != 0) || ((w << F::N) != 0);
+    uint32_t body = w >> (33 - F::N);
+    const uint32_t guard = (w >> (32 - F::N)) & 1u;
+    body += guard & ((sticky ? 1u : 0u) | (body & 1u));
+    return r.neg ? ((0u - body) & F::MASK) : body;
+}
+
+// Encoder chosen by destination width.
+template <class F>
+PNN_HD uint32_t encode_any(const Real32& r) {
+    if (F::N <= 16) {
+        return encode32<Fmt<(F::N <= 16 ? F::N : 16), F::ES>>(r);
+    }
+    return encode<F>(widen(r));
+}
+
 // Read a quire of L 32-bit limbs (two's complement, LSB weight 2^-qfrac) out as a
 // Real.  Returns false when the quire is exactly zero.  All limb indices are
 // compile-time so the limbs stay in registers.
@@ -204,6 +314,18 @@ PNN_HD int real_from_f32(uint32_t bits, Real& r) {
         r.scale = (int)ex - 127;
         r.frac = (uint64_t)man << 41;
     }
+    return 1;
+}
+
+PNN_HD int real32_from_f32(uint32_t bits, Real32& r) {
+    const uint32_t ex = (bits >> 23) & 0xFFu;
+    const uint32_t man = bits & 0x7FFFFFu;
+    if (ex == 0xFFu) return 2;
+    if (ex == 0 && man == 0) return 0;
+    r.neg = bits >> 31;
+    r.sticky = ex == 0;                       // subnormal: only "nonzero and tiny" matters
+    r.scale = ex == 0 ? -1000 : (int)ex - 127;
+    r.frac = ex == 0 ? 0u : man << 9;
     return 1;
 }
 

@@ -103,6 +103,24 @@ def test_axpy(hc, fx, fy):
             assert np.array_equal(out, fast.axpy(one, x, y2, fx, fy).astype(np.uint64))
 
 
+@pytest.mark.parametrize("fx,fy", [("p8", "p16"), ("p16", "p16"), ("p8", "p8"), ("p16", "p8"), ("p32", "p32"), ("p16", "p32")])
+def test_axpy_near_cancellation(hc, fx, fy):
+    """y chosen as the rounded value of -alpha*x, then nudged by a few patterns: the sum
+    cancels almost completely, which is where an inexact alignment would show."""
+    rng = np.random.default_rng(BITS[fx] * 5 + BITS[fy])
+    n = 40000
+    x = _patterns(rng, n, fx, special=0.0)
+    mask = (1 << BITS[fy]) - 1
+    for alpha in (int(fast.round_from_float(np.array([-0.1], dtype=np.float32), fy)[0]), int(_patterns(rng, 1, fy, 0)[0]) | 1):
+        zero = np.zeros(n, dtype=np.uint64)
+        t = fast.axpy(alpha, x, zero, fx, fy).astype(np.int64)  # round(alpha * x)
+        for delta in (0, 1, -1, 3, -7, 64):
+            y = ((-t + delta) & mask).astype(np.uint64)
+            out = np.zeros(n, dtype=np.uint64)
+            assert hc.hostcheck_axpy(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
+            assert np.array_equal(out, fast.axpy(alpha, x, y, fx, fy).astype(np.uint64)), (alpha, delta)
+
+
 @pytest.mark.parametrize("fin", ["p8", "p16", "p32"])
 @pytest.mark.parametrize("fout", ["p8", "p16", "p32"])
 def test_quire_dot(hc, fin, fout):
