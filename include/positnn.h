@@ -129,6 +129,39 @@ int posit_convert(void* stream, int src, int dst, int64_t n, const void* src_ptr
 int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int64_t n,
                const void* x, void* y, int fcopy, void* y_copy);
 
+/* ---- exact layer glue (Fig. 2: ReLU activation, maximum and average pooling) ----
+ * None of these is a dot product, but each has an exact definition on posit patterns, so a
+ * whole training step can stay on the device and remain bit-comparable with the oracle.
+ * posit ordering is the signed-integer ordering of the patterns (Sec. 2: two's complement). */
+
+/* y[i] = x[i] if x[i] > 0, else 0 (NaR stays NaR).  In place allowed (y == x). */
+int posit_relu(void* stream, int fmt, int64_t n, const void* x, void* y);
+
+/* dx[i] = dy[i] where the forward output y_fwd[i] is positive, else 0 (NaR where y_fwd[i] is NaR).
+ * y_fwd in fmt_y, dy and dx in fmt_d. */
+int posit_relu_bwd(void* stream, int fmt_y, int fmt_d, int64_t n, const void* y_fwd, const void* dy, void* dx);
+
+/* Non-overlapping kh x kw maximum pooling of `planes` images of H x W (planes = batch * channels):
+ * y[p,oh,ow] = max over the window, compared as signed integers (NaR is the smallest pattern);
+ * idx[p,oh,ow] (uint8) = position of the FIRST maximum in row-major window order.  H, W must be
+ * multiples of kh, kw; kh*kw <= 255. */
+int posit_maxpool2d_fwd(void* stream, int fmt, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                        const void* x, void* y, void* idx);
+
+/* Routes dy[p,oh,ow] to the recorded window position of dx, zeros elsewhere. */
+int posit_maxpool2d_bwd(void* stream, int fmt, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                        const void* dy, const void* idx, void* dx);
+
+/* Non-overlapping kh x kw average pooling with kh*kw a power of two: the exact quire dot product of the
+ * window with the weight 1/(kh*kw), one rounding: y = round_fout( sum_window x * 2^-log2(kh*kw) ).
+ * Identical to posit_conv2d_fwd on a one-channel image with a constant kernel and stride = window. */
+int posit_avgpool2d_fwd(void* stream, int fin, int fout, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                        const void* x, void* y);
+
+/* Adjoint of the above: dx[p,h,w] = round_fout( dy[p,h/kh,w/kw] * 2^-log2(kh*kw) ). */
+int posit_avgpool2d_bwd(void* stream, int fin, int fout, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                        const void* dy, void* dx);
+
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* posit_status_string(int status);
 

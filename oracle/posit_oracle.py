@@ -29,6 +29,9 @@ What each function follows
 * ``from_float`` / ``to_float`` / ``convert``: Fig. 2 utilities (tensor
                           conversion, copies of a tensor in several formats).
 * ``axpy``              : Fig. 2 optimizer (SGD), y <- round(y + alpha*x).
+* ``relu`` / ``maxpool2d_*`` / ``avgpool2d_*``: Fig. 2 activation and pooling
+                          layers, by value (max is taken on decoded values;
+                          average pooling is a quire dot with 1/window).
 
 Readings of points the paper leaves open (all listed in the design notes):
 the quire is a Q-bit two's-complement integer whose unit is minpos^2 and which
@@ -551,3 +554,90 @@ def axpy(alpha, x, y, fx, fy, fcopy=None):
     if fcopy is None:
         return ynew
     return ynew, convert(ynew, fy, fcopy)
+
+
+# --------------------------------------------------------------------------
+# layer glue with exact definitions (Fig. 2: ReLU, maximum / average pooling)
+# --------------------------------------------------------------------------
+
+def relu(x, fmt):
+    """max(x, 0) element by element; NaR stays NaR."""
+    out = []
+    for p in x:
+        v = _value(p, fmt)
+        out.append(fmt.nar if v is NaR else (int(p) & fmt.mask if v > 0 else 0))
+    return out
+
+
+def relu_bwd(y_fwd, dy, fmt_y, fmt_d):
+    """dy where the forward output is positive, 0 elsewhere, NaR where the output was NaR."""
+    out = []
+    for py, pd in zip(y_fwd, dy):
+        v = _value(py, fmt_y)
+        out.append(fmt_d.nar if v is NaR else (int(pd) & fmt_d.mask if v > 0 else 0))
+    return out
+
+
+def _less(a, b):
+    """value order with NaR below every real"""
+    if b is NaR:
+        return False
+    if a is NaR:
+        return True
+    return a < b
+
+
+def maxpool2d_fwd(x, planes, H, W, kh, kw, fmt):
+    """Non-overlapping windows; returns (values, index of the first maximum in row-major window order)."""
+    OH, OW = H // kh, W // kw
+    ys, idx = [], []
+    for p in range(planes):
+        for oh in range(OH):
+            for ow in range(OW):
+                best, bi = None, 0
+                for r in range(kh):
+                    for c in range(kw):
+                        pat = int(x[(p * H + oh * kh + r) * W + ow * kw + c]) & fmt.mask
+                        v = _value(pat, fmt)
+                        if best is None or _less(best[0], v):
+                            best, bi = (v, pat), r * kw + c
+                ys.append(best[1])
+                idx.append(bi)
+    return ys, idx
+
+
+def maxpool2d_bwd(dy, idx, planes, H, W, kh, kw):
+    OH, OW = H // kh, W // kw
+    dx = [0] * (planes * H * W)
+    for p in range(planes):
+        for oh in range(OH):
+            for ow in range(OW):
+                o = (p * OH + oh) * OW + ow
+                r, c = divmod(idx[o], kw)
+                dx[(p * H + oh * kh + r) * W + ow * kw + c] = int(dy[o])
+    return dx
+
+
+def avgpool2d_fwd(x, planes, H, W, kh, kw, fin, fout):
+    """Exact quire dot product of each window with the weight 1/(kh*kw) (a power of two), one rounding."""
+    wpat = round_to_posit(Fraction(1, kh * kw), fin)
+    assert decode(wpat, fin) == Fraction(1, kh * kw)
+    OH, OW = H // kh, W // kw
+    out = []
+    for p in range(planes):
+        for oh in range(OH):
+            for ow in range(OW):
+                win = [x[(p * H + oh * kh + r) * W + ow * kw + c] for r in range(kh) for c in range(kw)]
+                out.append(dot(win, [wpat] * len(win), fin, fout))
+    return out
+
+
+def avgpool2d_bwd(dy, planes, H, W, kh, kw, fin, fout):
+    wpat = round_to_posit(Fraction(1, kh * kw), fin)
+    OH, OW = H // kh, W // kw
+    out = []
+    for p in range(planes):
+        for h in range(H):
+            for w in range(W):
+                out.append(dot([dy[(p * OH + h // kh) * OW + w // kw]], [wpat], fin, fout))
+    return out

@@ -54,9 +54,16 @@ def load():
     L.posit_round.argtypes = [vp, ci, ci, i64, vp, vp]
     L.posit_convert.argtypes = [vp, ci, ci, i64, vp, vp]
     L.posit_axpy.argtypes = [vp, ci, ci, u32, i64, vp, vp, ci, vp]
+    L.posit_relu.argtypes = [vp, ci, i64, vp, vp]
+    L.posit_relu_bwd.argtypes = [vp, ci, ci, i64, vp, vp, vp]
+    L.posit_maxpool2d_fwd.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, vp, vp]
+    L.posit_maxpool2d_bwd.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, vp, vp]
+    L.posit_avgpool2d_fwd.argtypes = [vp, ci, ci, i64, i64, i64, i64, i64, vp, vp]
+    L.posit_avgpool2d_bwd.argtypes = [vp, ci, ci, i64, i64, i64, i64, i64, vp, vp]
     L.posit_status_string.argtypes = [ci]
     L.posit_status_string.restype = ctypes.c_char_p
-    for name in ("posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight", "posit_round", "posit_convert", "posit_axpy"):
+    for name in ("posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight", "posit_round", "posit_convert", "posit_axpy",
+                 "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"):
         getattr(L, name).restype = ci
     _lib = L
     return L
@@ -205,3 +212,64 @@ def posit_axpy(alpha_bits, x, y, fx, fy, fcopy=None, y_copy=None):
     _check(load().posit_axpy(_stream(), fx, fy, int(alpha_bits) & 0xFFFFFFFF, y.numel(), _dev(x, fx, "x"), _dev(y, fy, "y"),
                              fc, _dev(y_copy, fc, "y_copy") if fcopy is not None else None))
     return (y, y_copy) if fcopy is not None else y
+
+
+def posit_relu(x, fmt, out=None):
+    fmt = _code(fmt)
+    if out is None:
+        out = torch.empty_like(x)
+    _check(load().posit_relu(_stream(), fmt, x.numel(), _dev(x, fmt, "x"), _dev(out, fmt, "y")))
+    return out
+
+
+def posit_relu_bwd(y_fwd, dy, fmt_y, fmt_d, out=None):
+    fmt_y, fmt_d = _code(fmt_y), _code(fmt_d)
+    if y_fwd.numel() != dy.numel():
+        raise PositError("y_fwd and dy differ in size")
+    if out is None:
+        out = torch.empty_like(dy)
+    _check(load().posit_relu_bwd(_stream(), fmt_y, fmt_d, dy.numel(), _dev(y_fwd, fmt_y, "y_fwd"), _dev(dy, fmt_d, "dy"), _dev(out, fmt_d, "dx")))
+    return out
+
+
+def _planes(x):
+    if x.dim() < 2:
+        raise PositError("pooling takes [..., H, W] tensors")
+    h, w = x.shape[-2], x.shape[-1]
+    return x.numel() // (h * w) if h * w else 0, h, w
+
+
+def posit_maxpool2d_fwd(x, fmt, kh=2, kw=2):
+    """Returns (y, idx): idx is the uint8 window position of the first maximum."""
+    fmt = _code(fmt)
+    planes, h, w = _planes(x)
+    shape = tuple(x.shape[:-2]) + (h // kh, w // kw)
+    y = torch.empty(shape, dtype=x.dtype, device=x.device)
+    idx = torch.empty(shape, dtype=torch.uint8, device=x.device)
+    _check(load().posit_maxpool2d_fwd(_stream(), fmt, planes, h, w, kh, kw, _dev(x, fmt, "x"), _dev(y, fmt, "y"), _dev(idx, P8, "idx")))
+    return y, idx
+
+
+def posit_maxpool2d_bwd(dy, idx, fmt, kh=2, kw=2):
+    fmt = _code(fmt)
+    planes, oh, ow = _planes(dy)
+    shape = tuple(dy.shape[:-2]) + (oh * kh, ow * kw)
+    dx = torch.empty(shape, dtype=dy.dtype, device=dy.device)
+    _check(load().posit_maxpool2d_bwd(_stream(), fmt, planes, oh * kh, ow * kw, kh, kw, _dev(dy, fmt, "dy"), _dev(idx, P8, "idx"), _dev(dx, fmt, "dx")))
+    return dx
+
+
+def posit_avgpool2d_fwd(x, fin, fout, kh=2, kw=2):
+    fin, fout = _code(fin), _code(fout)
+    planes, h, w = _planes(x)
+    y = torch.empty(tuple(x.shape[:-2]) + (h // kh, w // kw), dtype=TORCH_DTYPE[fout], device=x.device)
+    _check(load().posit_avgpool2d_fwd(_stream(), fin, fout, planes, h, w, kh, kw, _dev(x, fin, "x"), _dev(y, fout, "y")))
+    return y
+
+
+def posit_avgpool2d_bwd(dy, fin, fout, kh=2, kw=2):
+    fin, fout = _code(fin), _code(fout)
+    planes, oh, ow = _planes(dy)
+    dx = torch.empty(tuple(dy.shape[:-2]) + (oh * kh, ow * kw), dtype=TORCH_DTYPE[fout], device=dy.device)
+    _check(load().posit_avgpool2d_bwd(_stream(), fin, fout, planes, oh * kh, ow * kw, kh, kw, _dev(dy, fin, "dy"), _dev(dx, fout, "dx")))
+    return dx

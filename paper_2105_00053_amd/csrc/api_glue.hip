@@ -1,0 +1,252 @@
+// Exact layer glue between the dot-product layers (paper Fig. 2: ReLU, maximum and
+// average pooling): bandwidth-bound kernels on posit patterns.  ReLU and max
+// pooling only compare patterns as signed integers; average pooling is the quire
+// dot product of the window with the weight 2^-log2(window), rounded once.
+#include "api_common.h"
+#include "quire_gemm.h"
+
+namespace pnn {
+
+template <class T>
+__device__ __forceinline__ int32_t as_signed(T p) {
+    // sign-extend an N-bit pattern: posit order == signed integer order
+    return (int32_t)((uint32_t)p << (32 - 8 * sizeof(T))) >> (32 - 8 * sizeof(T));
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void relu_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const T p = x[i];
+    const T nar = (T)((T)1 << (8 * sizeof(T) - 1));
+    y[i] = (as_signed(p) > 0 || p == nar) ? p : (T)0;
+}
+
+template <class TY, class TD>
+__global__ __launch_bounds__(256) void relu_bwd_kernel(const TY* __restrict__ yf, const TD* __restrict__ dy, TD* __restrict__ dx, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const TY yv = yf[i];
+    const TY ynar = (TY)((TY)1 << (8 * sizeof(TY) - 1));
+    const TD dnar = (TD)((TD)1 << (8 * sizeof(TD) - 1));
+    dx[i] = yv == ynar ? dnar : (as_signed(yv) > 0 ? dy[i] : (TD)0);
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, uint8_t* __restrict__ idx,
+                                                          int64_t total, int H, int W, int kh, int kw) {
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total) return;
+    const int OW = W / kw, OH = H / kh;
+    const int ow = (int)(o % OW);
+    const int64_t t = o / OW;
+    const int oh = (int)(t % OH);
+    const int64_t p = t / OH;
+    const T* base = x + (p * H + (int64_t)oh * kh) * W + (int64_t)ow * kw;
+    T best = base[0];
+    int bi = 0;
+    for (int r = 0; r < kh; ++r)
+        for (int c = 0; c < kw; ++c) {
+            const T v = base[(int64_t)r * W + c];
+            if (as_signed(v) > as_signed(best)) { best = v; bi = r * kw + c; }
+        }
+    y[o] = best;
+    idx[o] = (uint8_t)bi;
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void maxpool_bwd_kernel(const T* __restrict__ dy, const uint8_t* __restrict__ idx, T* __restrict__ dx,
+                                                          int64_t total_in, int H, int W, int kh, int kw) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total_in) return;
+    const int w = (int)(i % W);
+    const int64_t t = i / W;
+    const int h = (int)(t % H);
+    const int64_t p = t / H;
+    const int OW = W / kw, OH = H / kh;
+    const int64_t o = (p * OH + h / kh) * OW + w / kw;
+    const int pos = (h % kh) * kw + (w % kw);
+    dx[i] = (idx[o] == pos) ? dy[o] : (T)0;
+}
+
+// average pooling: quire dot of the window with the weight 2^-shift (a posit of FIN), one rounding
+template <class FIN>
+__global__ __launch_bounds__(256) void avgpool_fwd_kernel(const typename Storage<FIN::N>::T* __restrict__ x, void* __restrict__ y, int fout,
+                                                          int64_t total, int H, int W, int kh, int kw, uint32_t weight) {
+    typedef Arith<FIN> AR;
+    const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (o >= total) return;
+    const int OW = W / kw, OH = H / kh;
+    const int ow = (int)(o % OW);
+    const int64_t t = o / OW;
+    const int oh = (int)(t % OH);
+    const int64_t p = t / OH;
+    const typename Storage<FIN::N>::T* base = x + (p * H + (int64_t)oh * kh) * W + (int64_t)ow * kw;
+    uint32_t q[AR::L];
+#pragma unroll
+    for (int l = 0; l < AR::L; ++l) q[l] = 0;
+    bool nar = false;
+    const typename AR::Elem wq = AR::stage(weight);
+    for (int r = 0; r < kh; ++r)
+        for (int c = 0; c < kw; ++c) {
+            const uint32_t v = base[(int64_t)r * W + c];
+            if (v == FIN::NAR) nar = true;
+            AR::mac(q, AR::stage(v), wq);
+        }
+    round_store<FIN, AR::L>(q, nar, fout, y, o);
+}
+
+template <class FIN>
+__global__ __launch_bounds__(256) void avgpool_bwd_kernel(const typename Storage<FIN::N>::T* __restrict__ dy, void* __restrict__ dx, int fout,
+                                                          int64_t total_in, int H, int W, int kh, int kw, uint32_t weight) {
+    typedef Arith<FIN> AR;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total_in) return;
+    const int w = (int)(i % W);
+    const int64_t t = i / W;
+    const int h = (int)(t % H);
+    const int64_t p = t / H;
+    const int OW = W / kw, OH = H / kh;
+    const uint32_t v = dy[(p * OH + h / kh) * OW + w / kw];
+    uint32_t q[AR::L];
+#pragma unroll
+    for (int l = 0; l < AR::L; ++l) q[l] = 0;
+    AR::mac(q, AR::stage(v), AR::stage(weight));
+    round_store<FIN, AR::L>(q, v == FIN::NAR, fout, dx, i);
+}
+
+inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }
+
+// pattern of 2^-shift in posit<N,ES>: one / useed^k ... found by construction: value 2^-s has
+// regime k = floor(-s / 2^ES), exponent e = -s - k*2^ES, no fraction.
+inline uint32_t pow2_pattern(int nbits, int es, int s) {
+    const int scale = -s;
+    int k = scale >> es;  // floor
+    const int e = scale - k * (1 << es);
+    // k < 0 here (s > 0): -k zeros, a one, then the exponent bits
+    const int rl = 1 - k;
+    const int used = rl + es;                 // bits after the sign
+    uint32_t body = ((1u << es) | (uint32_t)e);  // "1" then e
+    body = body << ((nbits - 1) - used);
+    return s == 0 ? (1u << (nbits - 2)) : body;
+}
+
+inline int window_shift(int64_t kh, int64_t kw) {
+    const int64_t a = kh * kw;
+    if (a <= 0 || (a & (a - 1))) return -1;
+    int s = 0;
+    while (((int64_t)1 << s) < a) ++s;
+    return s;
+}
+
+inline bool pool_args_ok(int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw) {
+    if (planes < 0 || H <= 0 || W <= 0 || kh <= 0 || kw <= 0) return false;
+    if (H % kh || W % kw || kh * kw > 255) return false;
+    if (H >= ((int64_t)1 << 30) || W >= ((int64_t)1 << 30)) return false;
+    return true;
+}
+
+}  // namespace pnn
+
+using namespace pnn;
+
+extern "C" int posit_relu(void* stream, int fmt, int64_t n, const void* x, void* y) {
+    if (!is_posit(fmt) || n < 0) return PNN_EINVAL;
+    if (n == 0) return PNN_OK;
+    if (!x || !y) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fmt) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL(relu_kernel<uint8_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint8_t*)x, (uint8_t*)y, n); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL(relu_kernel<uint16_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)y, n); break;
+        default: hipLaunchKernelGGL(relu_kernel<uint32_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)y, n); break;
+    }
+    return hip_status(hipGetLastError());
+}
+
+namespace pnn {
+template <class TY>
+void relu_bwd_pick(hipStream_t st, int fmt_d, int64_t n, const void* yf, const void* dy, void* dx) {
+    switch (fmt_d) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint8_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint8_t*)dy, (uint8_t*)dx, n); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint16_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint16_t*)dy, (uint16_t*)dx, n); break;
+        default: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint32_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint32_t*)dy, (uint32_t*)dx, n); break;
+    }
+}
+}  // namespace pnn
+
+extern "C" int posit_relu_bwd(void* stream, int fmt_y, int fmt_d, int64_t n, const void* y_fwd, const void* dy, void* dx) {
+    if (!is_posit(fmt_y) || !is_posit(fmt_d) || n < 0) return PNN_EINVAL;
+    if (n == 0) return PNN_OK;
+    if (!y_fwd || !dy || !dx) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    switch (fmt_y) {
+        case PNN_POSIT8_0: relu_bwd_pick<uint8_t>(st, fmt_d, n, y_fwd, dy, dx); break;
+        case PNN_POSIT16_1: relu_bwd_pick<uint16_t>(st, fmt_d, n, y_fwd, dy, dx); break;
+        default: relu_bwd_pick<uint32_t>(st, fmt_d, n, y_fwd, dy, dx); break;
+    }
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int posit_maxpool2d_fwd(void* stream, int fmt, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                                   const void* x, void* y, void* idx) {
+    if (!is_posit(fmt) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
+    if (planes == 0) return PNN_OK;
+    if (!x || !y || !idx) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = planes * (H / kh) * (W / kw);
+    switch (fmt) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL(maxpool_fwd_kernel<uint8_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)x, (uint8_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+        default: hipLaunchKernelGGL(maxpool_fwd_kernel<uint32_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+    }
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int posit_maxpool2d_bwd(void* stream, int fmt, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                                   const void* dy, const void* idx, void* dx) {
+    if (!is_posit(fmt) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
+    if (planes == 0) return PNN_OK;
+    if (!dy || !dx || !idx) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = planes * H * W;
+    switch (fmt) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL(maxpool_bwd_kernel<uint8_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)dy, (const uint8_t*)idx, (uint8_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)dy, (const uint8_t*)idx, (uint16_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+        default: hipLaunchKernelGGL(maxpool_bwd_kernel<uint32_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)dy, (const uint8_t*)idx, (uint32_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
+    }
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int posit_avgpool2d_fwd(void* stream, int fin, int fout, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                                   const void* x, void* y) {
+    if (!is_posit(fin) || !is_posit(fout) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
+    const int s = window_shift(kh, kw);
+    if (s < 0) return PNN_EUNSUPPORTED;
+    if (planes == 0) return PNN_OK;
+    if (!x || !y) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = planes * (H / kh) * (W / kw);
+    switch (fin) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL(avgpool_fwd_kernel<P8>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(8, 0, s)); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL(avgpool_fwd_kernel<P16>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(16, 1, s)); break;
+        default: hipLaunchKernelGGL(avgpool_fwd_kernel<P32>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(32, 2, s)); break;
+    }
+    return hip_status(hipGetLastError());
+}
+
+extern "C" int posit_avgpool2d_bwd(void* stream, int fin, int fout, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
+                                   const void* dy, void* dx) {
+    if (!is_posit(fin) || !is_posit(fout) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
+    const int s = window_shift(kh, kw);
+    if (s < 0) return PNN_EUNSUPPORTED;
+    if (planes == 0) return PNN_OK;
+    if (!dy || !dx) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    const int64_t total = planes * H * W;
+    switch (fin) {
+        case PNN_POSIT8_0: hipLaunchKernelGGL(avgpool_bwd_kernel<P8>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(8, 0, s)); break;
+        case PNN_POSIT16_1: hipLaunchKernelGGL(avgpool_bwd_kernel<P16>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(16, 1, s)); break;
+        default: hipLaunchKernelGGL(avgpool_bwd_kernel<P32>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(32, 2, s)); break;
+    }
+    return hip_status(hipGetLastError());
+}

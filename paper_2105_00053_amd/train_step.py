@@ -1,0 +1,126 @@
+"""Device-resident training step for small CNNs described as layer lists.
+
+Chains the library's entry points (convolution / linear forward, backward-data,
+backward-weight, ReLU, pooling, SGD update) so that a LeNet-5-shaped or
+CifarNet-shaped step runs without leaving the GPU.  Pure orchestration: every
+number is produced by a kernel of libpositnn_hip.so, except the softmax /
+cross-entropy gradient, for which the paper gives no posit algorithm: it is
+evaluated in float64 by torch on the device (logits -> float64 exactly,
+softmax, minus one-hot, divided by the batch) and rounded to posit<16,1> by
+posit_round.
+
+Formats (mixed precision of Sec. 3.3 / Fig. 3): activations, weight copies and
+back-propagated errors posit<8,0>; weight gradients rounded from the quire to
+posit<16,1>; master weights and optimizer posit<16,1>.
+"""
+import torch
+
+from . import binding as pn
+
+ALPHA_MINUS_0P1 = 0xEB33  # posit<16,1> pattern of -(0x14CD), the rounded -0.1
+
+
+class Net:
+    """Weights of a layer list [("conv", cin, cout, k, pad) | ("fc", in, out) | ("relu",) |
+    ("avgpool",) | ("maxpool",) | ("flatten",)] as posit<16,1> masters and posit<8,0> copies."""
+
+    def __init__(self, layers, params_f32):
+        self.layers = layers
+        self.w16, self.b16, self.w8, self.b8 = [], [], [], []
+        for w, b in params_f32:
+            w16 = pn.posit_round(w.contiguous(), "p16")
+            b16 = pn.posit_round(b.contiguous(), "p16")
+            self.w16.append(w16)
+            self.b16.append(b16)
+            self.w8.append(pn.posit_convert(w16, "p16", "p8"))
+            self.b8.append(pn.posit_convert(b16, "p16", "p8"))
+
+
+def loss_gradient(logits_p8, labels):
+    """(softmax(logits) - onehot) / batch in float64 on the device, rounded to posit<16,1> then posit<8,0>."""
+    z = pn.posit_convert(logits_p8, "p8", "f64")
+    p = torch.softmax(z, dim=1)
+    p[torch.arange(p.shape[0], device=p.device), labels] -= 1.0
+    g16 = pn.posit_round((p / p.shape[0]).contiguous(), "p16")
+    return pn.posit_convert(g16, "p16", "p8"), g16
+
+
+def forward(net, x8, tape=None):
+    li = 0
+    x = x8
+    for layer in net.layers:
+        kind = layer[0]
+        if kind == "conv":
+            _, cin, cout, k, pad = layer
+            d = pn.conv_desc(tuple(x.shape), (cout, cin, k, k), (pad, pad), (1, 1))
+            y = pn.posit_conv2d_fwd(x, net.w8[li], d, "p8", "p8", bias=net.b8[li])
+            if tape is not None:
+                tape.append(("conv", li, d, x))
+            x = y
+            li += 1
+        elif kind == "fc":
+            y = pn.posit_gemm(x, net.w8[li], "p8", "p8", trans_b=True, bias=net.b8[li])
+            if tape is not None:
+                tape.append(("fc", li, None, x))
+            x = y
+            li += 1
+        elif kind == "relu":
+            x = pn.posit_relu(x, "p8")
+            if tape is not None:
+                tape.append(("relu", None, None, x))
+        elif kind == "avgpool":
+            if tape is not None:
+                tape.append(("avgpool", None, None, None))
+            x = pn.posit_avgpool2d_fwd(x, "p8", "p8")
+        elif kind == "maxpool":
+            x, idx = pn.posit_maxpool2d_fwd(x, "p8")
+            if tape is not None:
+                tape.append(("maxpool", None, idx, None))
+        elif kind == "flatten":
+            if tape is not None:
+                tape.append(("flatten", None, None, tuple(x.shape)))
+            x = x.reshape(x.shape[0], -1)
+    return x
+
+
+def backward_and_update(net, tape, dy, alpha=ALPHA_MINUS_0P1, grads=None):
+    """Back-propagates dy (posit<8,0>) through the tape and applies the SGD update layer by
+    layer.  When `grads` is a list, (layer, dw, db) posit<16,1> tensors are appended to it."""
+    for kind, li, aux, saved in reversed(tape):
+        if kind == "fc":
+            dw = pn.posit_gemm(dy, saved, "p8", "p16", trans_a=True)
+            ones = torch.full((dy.shape[0], 1), 0x40, dtype=torch.uint8, device=dy.device)
+            db = pn.posit_gemm(dy, ones, "p8", "p16", trans_a=True).reshape(-1)
+            dx = pn.posit_gemm(dy, net.w8[li], "p8", "p8")
+            _update(net, li, dw, db, alpha, grads)
+            dy = dx
+        elif kind == "conv":
+            dw, db = pn.posit_conv2d_bwd_weight(dy, saved, aux, "p8", "p16", with_bias=True)
+            dx = pn.posit_conv2d_bwd_data(dy, net.w8[li], aux, "p8", "p8") if li > 0 else None
+            _update(net, li, dw, db, alpha, grads)
+            dy = dx
+        elif kind == "relu":
+            dy = pn.posit_relu_bwd(saved, dy, "p8", "p8")
+        elif kind == "avgpool":
+            dy = pn.posit_avgpool2d_bwd(dy, "p8", "p8")
+        elif kind == "maxpool":
+            dy = pn.posit_maxpool2d_bwd(dy, aux, "p8")
+        elif kind == "flatten":
+            dy = dy.reshape(saved)
+
+
+def _update(net, li, dw, db, alpha, grads):
+    if grads is not None:
+        grads.append((li, dw.clone(), db.clone()))
+    pn.posit_axpy(alpha, dw.reshape(-1), net.w16[li].reshape(-1), "p16", "p16", fcopy="p8", y_copy=net.w8[li].reshape(-1))
+    pn.posit_axpy(alpha, db.reshape(-1), net.b16[li].reshape(-1), "p16", "p16", fcopy="p8", y_copy=net.b8[li].reshape(-1))
+
+
+def training_step(net, x_f32, labels, alpha=ALPHA_MINUS_0P1, grads=None):
+    """One full step; returns the logits (posit<8,0>)."""
+    x8 = pn.posit_round(x_f32.contiguous(), "p8")
+    tape = []
+    logits = forward(net, x8, tape)
+    dy, _ = loss_gradient(logits, labels)
+    backward_and_update(net, tape, dy, alpha, grads)
+    return logits

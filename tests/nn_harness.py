@@ -72,7 +72,7 @@ def avgpool_desc(shape):
     return _conv_desc(n * c, 1, h, w, 1, 2, 0, 2)
 
 
-def training_step(net, batch, x_f32, params_f32, labels, check=True, timers=None):
+def training_step(net, batch, x_f32, params_f32, labels, check=True, timers=None, final_state=None):
     """Runs forward, backward and update.  Returns the log [(name, outputs, mismatches)]."""
     log = []
     # master weights posit<16,1>, compute copies posit<8,0>
@@ -192,6 +192,8 @@ def training_step(net, batch, x_f32, params_f32, labels, check=True, timers=None
             dy = maxpool_bwd(dy, d, saved)
         elif kind == "flatten":
             dy = np.ascontiguousarray(dy.reshape(saved))
+    if final_state is not None:
+        final_state.update(dict(logits=logits, W16=W16, B16=B16, W8=W8, B8=B8))
     return log
 
 

@@ -28,7 +28,8 @@ def lib():
 def test_header_declares_the_expected_entry_points():
     assert _declared() == sorted([
         "posit_gemm", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
-        "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string"])
+        "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string",
+        "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"])
 
 
 def test_every_declared_symbol_is_exported(lib):

@@ -28,3 +28,29 @@ def test_config4_cifarnet_step_batch128():
     names = _run(workloads.CIFARNET, 128)
     for needed in ("conv0 fwd", "conv4 fwd", "fc5 fwd", "fc5 bwd_data", "conv4 bwd_weight", "conv1 bwd_data", "conv0 bwd_bias", "sgd w3"):
         assert needed in names, needed
+
+
+@pytest.mark.parametrize("net,batch", [(workloads.LENET, 64), (workloads.CIFARNET, 128)])
+def test_device_resident_step_matches_layerwise_harness(net, batch):
+    """The all-on-GPU step (library glue kernels for ReLU / pooling, nothing on the host) ends in
+    exactly the weights the layer-by-layer, oracle-checked harness ends in."""
+    import numpy as np
+    import torch
+
+    from paper_2105_00053_amd import train_step
+    from gpu_util import to_np
+
+    x, params, labels = workloads.network_inputs(net, batch)
+    state = {}
+    log = nn_harness.training_step(net, batch, x, params, labels, final_state=state)
+    assert all(bad == 0 for _, _, bad in log)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+    logits = train_step.training_step(model, dev(x), torch.from_numpy(labels).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(to_np(logits, "p8"), state["logits"])
+    for li in range(len(params)):
+        assert np.array_equal(to_np(model.w16[li], "p16"), state["W16"][li]), "master weights of layer %d" % li
+        assert np.array_equal(to_np(model.b16[li], "p16"), state["B16"][li])
+        assert np.array_equal(to_np(model.w8[li], "p8"), state["W8"][li])
+        assert np.array_equal(to_np(model.b8[li], "p8"), state["B8"][li])

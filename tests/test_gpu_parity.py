@@ -291,3 +291,44 @@ def test_conv_bwd_weight_long_reduction_splits():
     wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, "p8", "p16", with_bias=True)
     _assert_equal(to_np(dw, "p16"), wdw, "split bwd_weight")
     _assert_equal(to_np(db, "p16"), wdb, "split dbias")
+
+
+# ---------------- layer glue ----------------
+
+@pytest.mark.parametrize("fmt", ["p8", "p16", "p32"])
+def test_relu_forward_backward(fmt):
+    rng = np.random.default_rng(BITS[fmt])
+    n = 30001
+    x = rand_patterns(rng, n, fmt, special=0.05)
+    y = to_np(pn.posit_relu(to_dev(x), fmt), fmt)
+    _assert_equal(y, np.array(po.relu(x.tolist(), PF[fmt])), "relu")
+    dy = rand_patterns(rng, n, "p16")
+    dx = to_np(pn.posit_relu_bwd(to_dev(y), to_dev(dy), fmt, "p16"), "p16")
+    _assert_equal(dx, np.array(po.relu_bwd(y.tolist(), dy.tolist(), PF[fmt], po.P16)), "relu bwd")
+
+
+@pytest.mark.parametrize("fmt", ["p8", "p16"])
+@pytest.mark.parametrize("kh,kw", [(2, 2), (3, 2)])
+def test_maxpool_forward_backward(fmt, kh, kw):
+    rng = np.random.default_rng(kh + kw + BITS[fmt])
+    planes, H, W = 14, 12, 10
+    x = rand_patterns(rng, (2, 7, H, W), fmt, special=0.1)
+    y, idx = pn.posit_maxpool2d_fwd(to_dev(x), fmt, kh, kw)
+    wy, widx = po.maxpool2d_fwd(x.flatten().tolist(), planes, H, W, kh, kw, PF[fmt])
+    _assert_equal(to_np(y, fmt).flatten(), np.array(wy), "maxpool fwd")
+    _assert_equal(idx.cpu().numpy().flatten(), np.array(widx), "maxpool idx")
+    dy = rand_patterns(rng, tuple(y.shape), fmt)
+    dx = pn.posit_maxpool2d_bwd(to_dev(dy), idx, fmt, kh, kw)
+    _assert_equal(to_np(dx, fmt).flatten(), np.array(po.maxpool2d_bwd(dy.flatten().tolist(), widx, planes, H, W, kh, kw)), "maxpool bwd")
+
+
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p16", "p8"), ("p8", "p16"), ("p32", "p32")])
+def test_avgpool_forward_backward(fin, fout):
+    rng = np.random.default_rng(BITS[fin] + 3 * BITS[fout])
+    planes, H, W, kh, kw = 6, 8, 12, 2, 2
+    x = rand_patterns(rng, (planes, H, W), fin, special=0.05)
+    y = pn.posit_avgpool2d_fwd(to_dev(x), fin, fout, kh, kw)
+    _assert_equal(to_np(y, fout).flatten(), np.array(po.avgpool2d_fwd(x.flatten().tolist(), planes, H, W, kh, kw, PF[fin], PF[fout])), "avgpool fwd")
+    dy = rand_patterns(rng, (planes, H // kh, W // kw), fin, special=0.05)
+    dx = pn.posit_avgpool2d_bwd(to_dev(dy), fin, fout, kh, kw)
+    _assert_equal(to_np(dx, fout).flatten(), np.array(po.avgpool2d_bwd(dy.flatten().tolist(), planes, H, W, kh, kw, PF[fin], PF[fout])), "avgpool bwd")
