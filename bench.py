@@ -37,6 +37,42 @@ PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s
 GEMM_4096_TRAFFIC_BYTES = int((2.0 * 92322 + 16384) * 1024)
 
 
+def _time_ms(torch, fn, reps, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def extra_measurements(torch, pn, workloads):
+    """The other BASELINE configs, for the record (not part of `value`): GEMM kernels of configs 2 and 5
+    and whole training steps of configs 3 and 4 (device-resident, see paper_2105_00053_amd/train_step.py)."""
+    import numpy as np
+    from paper_2105_00053_amd import train_step
+    out = {}
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    for cfg, fmt, S, sigma, ext in ((5, "p8", 1024, 1.0, False), (5, "p8", 2048, 1.0, False), (2, "p16", 1024, 0.1, True), (5, "p32", 1024, 1.0, False)):
+        A, B = workloads.gemm_operands(cfg, S, sigma=sigma, extremes=ext)
+        Ap, Bp = pn.posit_round(dev(A), fmt), pn.posit_round(dev(B), fmt)
+        C = torch.empty((S, S), dtype=Ap.dtype, device="cuda")
+        ws = torch.empty(max(16, pn.posit_gemm_workspace(fmt, fmt, False, False, S, S, S)), dtype=torch.uint8, device="cuda")
+        ms = _time_ms(torch, lambda: pn.posit_gemm(Ap, Bp, fmt, fmt, out=C, workspace=ws), 10 if fmt != "p32" else 3)
+        out["gemm_%s_%d" % (fmt, S)] = {"ms": round(ms, 4), "TMAC/s": round(S ** 3 / ms / 1e9, 3)}
+    for name, net in (("lenet5_step_batch64", workloads.LENET), ("cifarnet_step_batch128", workloads.CIFARNET)):
+        x, params, labels = workloads.network_inputs(net)
+        model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+        xd, ld = dev(x), torch.from_numpy(labels).cuda()
+        ms = _time_ms(torch, lambda: train_step.training_step(model, xd, ld), 10, warm=3)
+        out[name] = {"ms": round(ms, 3)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -45,6 +81,7 @@ def main():
     ap.add_argument("--size", type=int, default=4096, help="M = N = K")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other BASELINE configs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy before timing (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -142,12 +179,15 @@ def main():
         },
     }
 
+    if not args.no_extra:
+        result["extra"] = extra_measurements(torch, pn, workloads)
+
     if not args.no_cpu:
         from oracle import fast
         threads = fast.hw_threads()
         A8n = A8.cpu().numpy()
         B8n = B8.cpu().numpy()
-        rows = args.cpu_rows or max(8, min(S, (8 * threads * 4096 * 4096) // (S * S)))
+        rows = args.cpu_rows or max(8, min(S, (64 * threads * 4096 * 4096) // (S * S)))  # about 15 s of CPU work
         t0 = time.perf_counter()
         Cn, overflowed = fast.gemm(A8n, B8n, "p8", "p8", rows=(0, rows), threads=threads)
         dt = time.perf_counter() - t0
