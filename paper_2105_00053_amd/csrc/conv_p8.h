@@ -24,8 +24,12 @@ namespace pnn {
 // n / d for 0 <= n < 2^31 by multiply-high (d >= 1)
 struct FastDiv {
     uint32_t d, mul, shift;
-    __device__ __forceinline__ uint32_t div(uint32_t n) const {
+    PNN_HD uint32_t div(uint32_t n) const {
+#if defined(__HIP_DEVICE_COMPILE__)
         return (uint32_t)((__umulhi(n, mul) + n) >> shift);
+#else
+        return (uint32_t)(((uint32_t)(((uint64_t)n * mul) >> 32) + n) >> shift);
+#endif
     }
 };
 
@@ -46,7 +50,7 @@ struct AffineIndex {
     int part2, part1, part0, partc;
     int y1, y0, yc;    // y depends on c1 (and c0 for flattened cases), x on c0
     int x1, x0, xc;
-    __device__ __forceinline__ void eval(uint32_t idx, int& part, int& y, int& x) const {
+    PNN_HD void eval(uint32_t idx, int& part, int& y, int& x) const {
         const uint32_t c2 = d1d0.div(idx);
         const uint32_t rem = idx - c2 * d1d0.d;
         const uint32_t c1 = d0.div(rem);
@@ -71,7 +75,7 @@ struct P8ConvOut {
     FastDiv md;          // m = c1 * md.d + c0
     int64_t m1, m0;      // mpart = c1 * m1 + c0 * m0
     int64_t nstride;
-    __device__ __forceinline__ int64_t at(int m, int n) const {
+    PNN_HD int64_t at(int m, int n) const {
         const uint32_t c1 = md.div((uint32_t)m);
         const uint32_t c0 = (uint32_t)m - c1 * md.d;
         return (int64_t)c1 * m1 + (int64_t)c0 * m0 + (int64_t)n * nstride;

@@ -3,6 +3,7 @@
 // Test scaffolding: nothing in the library links or calls this file.
 #include "elementwise_ops.h"
 #include "quire_arith.h"
+#include "conv_p8.h"
 
 using namespace pnn;
 
@@ -86,6 +87,28 @@ uint32_t hostcheck_dot(int fin, int fout, int64_t n, const uint32_t* a, const ui
     if (fin == 0) return dot_host<P8>(fout, n, a, b, has_bias, bias);
     if (fin == 1) return dot_host<P16>(fout, n, a, b, has_bias, bias);
     return dot_host<P32>(fout, n, a, b, has_bias, bias);
+}
+
+// Implicit-GEMM gather descriptors of the posit<8,0> convolution path, evaluated on the host:
+// for virtual element (row, k) of operand A or B of pass `which` (0 fwd, 1 bwd-data, 2 bwd-weight),
+// returns 1 and the tensor offset when the element is inside its bounds, 0 when it is a zero operand.
+// geom = N, C, H, W, K, R, S, pad_h, pad_w, stride_h, stride_w.  dims receives M, N, K of the kernel view.
+int hostcheck_conv_gather(int which, const int64_t* geom, int operand_b, int64_t row, int64_t k, int64_t* offset, int64_t* dims,
+                          int64_t* out_index) {
+    ConvGeom g;
+    g.N = (int)geom[0]; g.C = (int)geom[1]; g.H = (int)geom[2]; g.W = (int)geom[3]; g.K = (int)geom[4]; g.R = (int)geom[5]; g.S = (int)geom[6];
+    g.ph = (int)geom[7]; g.pw = (int)geom[8]; g.sh = (int)geom[9]; g.sw = (int)geom[10];
+    g.OH = (g.H + 2 * g.ph - g.R) / g.sh + 1;
+    g.OW = (g.W + 2 * g.pw - g.S) / g.sw + 1;
+    const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
+    dims[0] = p.M; dims[1] = p.N; dims[2] = p.K;
+    const P8Gather& op = operand_b ? p.B : p.A;
+    int rp, ry, rx, kp, ky, kx;
+    op.row.eval((uint32_t)row, rp, ry, rx);
+    op.k.eval((uint32_t)k, kp, ky, kx);
+    *offset = (int64_t)rp + kp;
+    if (out_index) *out_index = p.out.at((int)row, (int)k);  // (row, k) reused as output (m, n)
+    return ((uint32_t)(ry + ky) < (uint32_t)op.LY) && ((uint32_t)(rx + kx) < (uint32_t)op.LX);
 }
 
 }  // extern "C"

@@ -27,6 +27,7 @@ def hc():
     L.hostcheck_axpy.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     L.hostcheck_dot.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_dot.restype = ctypes.c_uint32
+    L.hostcheck_conv_gather.argtypes = [ci, vp, ci, i64, i64, vp, vp, vp]
     return L
 
 
@@ -154,3 +155,71 @@ def test_quire_dot_wraps_like_the_oracle(hc):
     for K in (32767, 32768, 40000):
         want, _ = fast.gemm(a16[:K].reshape(1, K), a16[:K].reshape(K, 1), "p16", "p16", threads=1)
         assert hc.hostcheck_dot(1, 1, K, _p(a16), _p(a16), 0, 0) == int(want[0, 0])
+
+
+def test_conv_gather_descriptors_match_direct_indexing(hc):
+    """The run-time affine descriptors of the posit<8,0> implicit-GEMM convolution (row / k
+    decompositions by multiply-high division, separable offsets and bounds) against the direct
+    NCHW / KCRS index formulas, for random geometries, all three passes, both operands, and
+    the output index map."""
+    import random
+    rng = random.Random(5)
+    i64 = ctypes.c_int64
+    for trial in range(40):
+        N, C, H, W, K = rng.randint(1, 3), rng.randint(1, 4), rng.randint(3, 9), rng.randint(3, 9), rng.randint(1, 4)
+        R, S = rng.randint(1, min(4, H)), rng.randint(1, min(4, W))
+        ph, pw, sh, sw = rng.randint(0, 2), rng.randint(0, 2), rng.randint(1, 2), rng.randint(1, 2)
+        OH, OW = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+        geom = (i64 * 11)(N, C, H, W, K, R, S, ph, pw, sh, sw)
+
+        def query(which, b, row, k, want_out=False):
+            off, dims, oidx = i64(0), (i64 * 3)(), i64(0)
+            ok = hc.hostcheck_conv_gather(which, geom, b, row, k, ctypes.byref(off), dims, ctypes.byref(oidx))
+            return ok, off.value, tuple(dims), oidx.value
+
+        def xoff(n, c, ih, iw):
+            return ((n * C + c) * H + ih) * W + iw if 0 <= ih < H and 0 <= iw < W else None
+
+        # forward: A rows (n,oh,ow) x k (c,r,s) on x ; B rows ko on w ; output y[n,ko,oh,ow]
+        M, Nn, Kk = N * OH * OW, K, C * R * S
+        for _ in range(200):
+            m, k, ko = rng.randrange(M), rng.randrange(Kk), rng.randrange(Nn)
+            n, rem = divmod(m, OH * OW); oh, ow = divmod(rem, OW)
+            c, rs = divmod(k, R * S); r, s = divmod(rs, S)
+            ok, off, dims, _ = query(0, 0, m, k)
+            assert dims == (M, Nn, Kk)
+            want = xoff(n, c, oh * sh + r - ph, ow * sw + s - pw)
+            assert (off if ok else None) == want
+            ok, off, _, _ = query(0, 1, ko, k)
+            assert ok and off == ko * Kk + k
+            _, _, _, oidx = query(0, 0, m, ko)
+            assert oidx == ((n * K + ko) * OH + oh) * OW + ow
+        # backward-weight (transposed): A rows (c,r,s) x k (n,oh,ow) on x ; B rows ko on dy ; output dw[ko,(c,r,s)]
+        M, Nn, Kk = C * R * S, K, N * OH * OW
+        for _ in range(200):
+            m, k, ko = rng.randrange(M), rng.randrange(Kk), rng.randrange(Nn)
+            c, rs = divmod(m, R * S); r, s = divmod(rs, S)
+            n, rem = divmod(k, OH * OW); oh, ow = divmod(rem, OW)
+            ok, off, dims, _ = query(2, 0, m, k)
+            assert dims == (M, Nn, Kk)
+            assert (off if ok else None) == xoff(n, c, oh * sh + r - ph, ow * sw + s - pw)
+            ok, off, _, _ = query(2, 1, ko, k)
+            assert ok and off == ((n * K + ko) * OH + oh) * OW + ow
+            _, _, _, oidx = query(2, 0, m, ko)
+            assert oidx == ko * M + m
+        if sh == 1 and sw == 1:
+            # backward-data: A rows (n,h,w) x k (ko,r,s) on dy ; B rows c on w ; output dx[n,c,h,w]
+            M, Nn, Kk = N * H * W, C, K * R * S
+            for _ in range(200):
+                m, k, c = rng.randrange(M), rng.randrange(Kk), rng.randrange(Nn)
+                n, rem = divmod(m, H * W); h, w = divmod(rem, W)
+                ko, rs = divmod(k, R * S); r, s = divmod(rs, S)
+                oh, ow = h + ph - r, w + pw - s
+                ok, off, dims, _ = query(1, 0, m, k)
+                assert dims == (M, Nn, Kk)
+                want = ((n * K + ko) * OH + oh) * OW + ow if 0 <= oh < OH and 0 <= ow < OW else None
+                assert (off if ok else None) == want
+                ok, off, _, _ = query(1, 1, c, k)
+                assert ok and off == ((ko * C + c) * R + r) * S + s
+                _, _, _, oidx = query(1, 0, m, c)
+                assert oidx == ((n * C + c) * H + h) * W + w
