@@ -17,7 +17,8 @@
  *    state; calls are asynchronous on `stream` (a hipStream_t passed as void*,
  *    NULL = the default stream).
  *  - posit<8,0> / <16,1> / <32,2> elements are stored as uint8 / uint16 / uint32
- *    bit patterns; PNN_F32 / PNN_F64 are IEEE binary32 / binary64.
+ *    bit patterns (other formats: see pnn_dtype); PNN_F32 / PNN_F64 are IEEE
+ *    binary32 / binary64.
  *  - Outputs must not alias inputs, except `y` of posit_axpy (updated in place).
  *  - Every function returns a pnn_status.  Invalid arguments (null pointer,
  *    negative size, leading dimension too small, unknown format) give
@@ -45,6 +46,16 @@ typedef enum {
     PNN_POSIT8_0 = 0,  /* posit<8,0>,  uint8  storage, 32-bit quire  (Table 1) */
     PNN_POSIT16_1 = 1, /* posit<16,1>, uint16 storage, 128-bit quire (Table 1) */
     PNN_POSIT32_2 = 2, /* posit<32,2>, uint32 storage, 512-bit quire (Table 1) */
+    /* formats of the paper's experiments (Sec. 4) that Table 1 does not list; the quire has
+     * 4(n-2)2^es + 1 + (n-1) bits rounded up to a multiple of 32; 10- and 12-bit patterns
+     * occupy the low bits of a uint16: outputs carry 0 in the upper bits, inputs must too (a
+     * set upper bit gives an unspecified value for that element, never an invalid access) */
+    PNN_POSIT8_1 = 3,  /* posit<8,1>,  uint8,  64-bit quire  */
+    PNN_POSIT8_2 = 4,  /* posit<8,2>,  uint8,  128-bit quire */
+    PNN_POSIT10_1 = 5, /* posit<10,1>, uint16, 96-bit quire  */
+    PNN_POSIT10_2 = 6, /* posit<10,2>, uint16, 160-bit quire */
+    PNN_POSIT12_1 = 7, /* posit<12,1>, uint16, 96-bit quire  */
+    PNN_POSIT12_2 = 8, /* posit<12,2>, uint16, 192-bit quire */
     PNN_F32 = 100,     /* IEEE binary32: posit_round / posit_convert only */
     PNN_F64 = 101      /* IEEE binary64: posit_round / posit_convert only */
 } pnn_dtype;

@@ -2,7 +2,7 @@
 
 TEST INFRASTRUCTURE ONLY: used by tests, the smoke check and the benchmark's
 CPU-baseline leg.  Formats are named "p8", "p16", "p32" (posit<8,0>, <16,1>,
-<32,2>, Table 1)."""
+<32,2>, Table 1) and "p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2" (Sec. 4)."""
 import ctypes
 import os
 
@@ -10,8 +10,9 @@ import numpy as np
 
 from . import build as _build
 
-CODES = {"p8": 0, "p16": 1, "p32": 2}
-DTYPES = {"p8": np.uint8, "p16": np.uint16, "p32": np.uint32}
+CODES = {"p8": 0, "p16": 1, "p32": 2, "p8_1": 3, "p8_2": 4, "p10_1": 5, "p10_2": 6, "p12_1": 7, "p12_2": 8}
+DTYPES = {"p8": np.uint8, "p16": np.uint16, "p32": np.uint32, "p8_1": np.uint8, "p8_2": np.uint8, "p10_1": np.uint16,
+          "p10_2": np.uint16, "p12_1": np.uint16, "p12_2": np.uint16}
 
 _lib = None
 

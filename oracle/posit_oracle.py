@@ -96,7 +96,24 @@ class PositFormat:
 P8 = PositFormat(8, 0, 32)
 P16 = PositFormat(16, 1, 128)
 P32 = PositFormat(32, 2, 512)
-FORMATS = {"p8": P8, "p16": P16, "p32": P32}
+
+
+def general_quire_bits(n, es):
+    """Quire width for (n, es) pairs Table 1 does not list (the paper's experiments use
+    posit(8,1), (8,2), (10,x), (12,x), Sec. 4): room for the largest product over the
+    smallest, 4(n-2)2^es bits, a sign bit and n-1 carry-guard bits, rounded up to a
+    whole number of 32-bit limbs.  A reading: the paper gives no width for these."""
+    return -(-(4 * (n - 2) * 2 ** es + 1 + (n - 1)) // 32) * 32
+
+
+P8_1 = PositFormat(8, 1, general_quire_bits(8, 1))     # 64
+P8_2 = PositFormat(8, 2, general_quire_bits(8, 2))     # 128
+P10_1 = PositFormat(10, 1, general_quire_bits(10, 1))  # 96
+P10_2 = PositFormat(10, 2, general_quire_bits(10, 2))  # 160
+P12_1 = PositFormat(12, 1, general_quire_bits(12, 1))  # 96
+P12_2 = PositFormat(12, 2, general_quire_bits(12, 2))  # 192
+FORMATS = {"p8": P8, "p16": P16, "p32": P32, "p8_1": P8_1, "p8_2": P8_2, "p10_1": P10_1, "p10_2": P10_2,
+           "p12_1": P12_1, "p12_2": P12_2}
 
 
 # --------------------------------------------------------------------------

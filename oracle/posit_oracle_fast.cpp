@@ -38,6 +38,13 @@ bool format_of(int code, Format* f) {
         case 0: *f = {8, 0, 32}; return true;
         case 1: *f = {16, 1, 128}; return true;
         case 2: *f = {32, 2, 512}; return true;
+        // pairs outside Table 1: 4(n-2)2^es + 1 + (n-1) bits rounded up to 32-bit limbs
+        case 3: *f = {8, 1, 64}; return true;
+        case 4: *f = {8, 2, 128}; return true;
+        case 5: *f = {10, 1, 96}; return true;
+        case 6: *f = {10, 2, 160}; return true;
+        case 7: *f = {12, 1, 96}; return true;
+        case 8: *f = {12, 2, 192}; return true;
     }
     return false;
 }
@@ -183,14 +190,15 @@ uint32_t round_quire(Big q, const Format& fin, const Format& fout) {
     return round_big(neg, q, -2 * fin.max_scale(), fout);
 }
 
+// containers: 8 bits -> uint8, 10 / 12 / 16 bits -> uint16 (pattern in the low bits), 32 -> uint32
 uint32_t load(const void* p, int64_t i, const Format& f) {
-    if (f.n == 8) return ((const uint8_t*)p)[i];
-    if (f.n == 16) return ((const uint16_t*)p)[i];
+    if (f.n <= 8) return ((const uint8_t*)p)[i];
+    if (f.n <= 16) return ((const uint16_t*)p)[i];
     return ((const uint32_t*)p)[i];
 }
 void store(void* p, int64_t i, uint32_t v, const Format& f) {
-    if (f.n == 8) ((uint8_t*)p)[i] = (uint8_t)v;
-    else if (f.n == 16) ((uint16_t*)p)[i] = (uint16_t)v;
+    if (f.n <= 8) ((uint8_t*)p)[i] = (uint8_t)v;
+    else if (f.n <= 16) ((uint16_t*)p)[i] = (uint16_t)v;
     else ((uint32_t*)p)[i] = v;
 }
 uint32_t nar_of(const Format& f) { return 1u << (f.n - 1); }

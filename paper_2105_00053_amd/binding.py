@@ -13,9 +13,12 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpositnn_hip.so")
 
 P8, P16, P32, F32, F64 = 0, 1, 2, 100, 101
-FORMAT_CODES = {"p8": P8, "p16": P16, "p32": P32, "f32": F32, "f64": F64}
-TORCH_DTYPE = {P8: torch.uint8, P16: torch.uint16, P32: torch.uint32, F32: torch.float32, F64: torch.float64}
-ELEM_SIZE = {P8: 1, P16: 2, P32: 4, F32: 4, F64: 8}
+P8_1, P8_2, P10_1, P10_2, P12_1, P12_2 = 3, 4, 5, 6, 7, 8  # formats of the paper's experiments outside Table 1
+FORMAT_CODES = {"p8": P8, "p16": P16, "p32": P32, "f32": F32, "f64": F64, "p8_1": P8_1, "p8_2": P8_2, "p10_1": P10_1,
+                "p10_2": P10_2, "p12_1": P12_1, "p12_2": P12_2}
+TORCH_DTYPE = {P8: torch.uint8, P16: torch.uint16, P32: torch.uint32, F32: torch.float32, F64: torch.float64,
+               P8_1: torch.uint8, P8_2: torch.uint8, P10_1: torch.uint16, P10_2: torch.uint16, P12_1: torch.uint16, P12_2: torch.uint16}
+ELEM_SIZE = {P8: 1, P16: 2, P32: 4, F32: 4, F64: 8, P8_1: 1, P8_2: 1, P10_1: 2, P10_2: 2, P12_1: 2, P12_2: 2}
 # signed views are accepted too (same bits)
 _SAME_SIZE = {1: (torch.uint8, torch.int8), 2: (torch.uint16, torch.int16), 4: (torch.uint32, torch.int32, torch.float32),
               8: (torch.float64, torch.int64, torch.uint64)}

@@ -10,9 +10,7 @@
 
 namespace pnn {
 
-template <class F> struct ConvTile;
-template <> struct ConvTile<P8> { static constexpr int TM = 4, TN = 4; };
-template <> struct ConvTile<P16> { static constexpr int TM = 4, TN = 4; };
+template <class F> struct ConvTile { static constexpr int TM = 4, TN = 4; };
 template <> struct ConvTile<P32> { static constexpr int TM = 2, TN = 2; };
 
 inline bool conv_geom(const pnn_conv2d_desc* d, ConvGeom* g) {
@@ -103,7 +101,7 @@ size_t conv_ws(int which, const ConvGeom& g) {
     const ConvDims d = conv_dims(which, g);
     if (d.M <= 0 || d.N <= 0) return 0;
     size_t b = conv_plan<F>(d).ws_bytes;
-    if (F::N == 8 && p8_conv_eligible(which, g)) {
+    if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(which, g)) {
         const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
         b = p8_conv_plan(p.M, p.N, p.K).ws_bytes;
     }
@@ -119,7 +117,7 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
              void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(0, g);
-    if (F::N == 8 && p8_conv_eligible(0, g)) {
+    if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(0, g)) {
         const P8ConvProblem p = p8_problem(0, g, x, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
         if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
@@ -139,7 +137,7 @@ template <class F>
 int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
-    if (F::N == 8 && p8_conv_eligible(1, g)) {
+    if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(1, g)) {
         const P8ConvProblem p = p8_problem(1, g, dy, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
         if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
@@ -160,7 +158,7 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
                     void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(2, g);
-    const bool fastp8 = F::N == 8 && p8_conv_eligible(2, g);
+    const bool fastp8 = (F::N == 8 && F::ES == 0) && p8_conv_eligible(2, g);
     GemmPlan plan = conv_plan<F>(d);
     P8ConvProblem p8p;
     if (fastp8) {
@@ -198,11 +196,8 @@ extern "C" size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn
     (void)fout;
     ConvGeom g;
     if (which < 0 || which > 2 || !is_posit(fin) || !conv_geom(desc, &g)) return 0;
-    switch (fin) {
-        case PNN_POSIT8_0: return conv_ws<P8>(which, g);
-        case PNN_POSIT16_1: return conv_ws<P16>(which, g);
-        default: return conv_ws<P32>(which, g);
-    }
+    PNN_DISPATCH_POSIT(fin, return conv_ws<F>(which, g))
+    return 0;
 }
 
 extern "C" int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* x, const void* w,
@@ -212,11 +207,8 @@ extern "C" int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2
     if (g.N == 0 || g.K == 0) return PNN_OK;
     if (!y || (g.C > 0 && (!x || !w))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    switch (fin) {
-        case PNN_POSIT8_0: return conv_fwd<P8>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
-        case PNN_POSIT16_1: return conv_fwd<P16>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
-        default: return conv_fwd<P32>(st, fout, g, x, w, bias, y, workspace, workspace_bytes);
-    }
+    PNN_DISPATCH_POSIT(fin, return conv_fwd<F>(st, fout, g, x, w, bias, y, workspace, workspace_bytes))
+    return PNN_EINVAL;
 }
 
 extern "C" int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* dy,
@@ -226,11 +218,8 @@ extern "C" int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_
     if (g.N == 0 || g.C == 0) return PNN_OK;
     if (!dx || (g.K > 0 && (!dy || !w))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    switch (fin) {
-        case PNN_POSIT8_0: return conv_bwd_data<P8>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
-        case PNN_POSIT16_1: return conv_bwd_data<P16>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
-        default: return conv_bwd_data<P32>(st, fout, g, dy, w, dx, workspace, workspace_bytes);
-    }
+    PNN_DISPATCH_POSIT(fin, return conv_bwd_data<F>(st, fout, g, dy, w, dx, workspace, workspace_bytes))
+    return PNN_EINVAL;
 }
 
 extern "C" int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_desc* desc, const void* dy,
@@ -240,9 +229,6 @@ extern "C" int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pn
     if (g.K == 0 || g.C == 0) return PNN_OK;
     if (!dw || (g.N > 0 && (!dy || !x))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    switch (fin) {
-        case PNN_POSIT8_0: return conv_bwd_weight<P8>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
-        case PNN_POSIT16_1: return conv_bwd_weight<P16>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
-        default: return conv_bwd_weight<P32>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes);
-    }
+    PNN_DISPATCH_POSIT(fin, return conv_bwd_weight<F>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes))
+    return PNN_EINVAL;
 }

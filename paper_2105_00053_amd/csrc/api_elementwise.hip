@@ -193,6 +193,52 @@ int convert_from(hipStream_t st, int dst, int64_t n, const void* s, void* d) {
     return PNN_EINVAL;
 }
 
+// Any-format kernels: element sizes and formats are run-time values (uniform branches).
+__device__ __forceinline__ uint64_t load_elem(const void* p, int64_t i, int bytes) {
+    if (bytes == 1) return ((const uint8_t*)p)[i];
+    if (bytes == 2) return ((const uint16_t*)p)[i];
+    if (bytes == 4) return ((const uint32_t*)p)[i];
+    return ((const uint64_t*)p)[i];
+}
+
+__device__ __forceinline__ void store_elem(void* p, int64_t i, int bytes, uint64_t v) {
+    if (bytes == 1) ((uint8_t*)p)[i] = (uint8_t)v;
+    else if (bytes == 2) ((uint16_t*)p)[i] = (uint16_t)v;
+    else if (bytes == 4) ((uint32_t*)p)[i] = (uint32_t)v;
+    else ((uint64_t*)p)[i] = v;
+}
+
+__global__ __launch_bounds__(256) void map_rt_kernel(const void* __restrict__ src, void* __restrict__ dst, int sbytes, int dbytes,
+                                                     int64_t n, MapRT op) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    store_elem(dst, i, dbytes, op(load_elem(src, i, sbytes)));
+}
+
+__global__ __launch_bounds__(256) void axpy_rt_kernel(const void* __restrict__ x, void* __restrict__ y, void* __restrict__ yc, int xbytes,
+                                                      int ybytes, int cbytes, int64_t n, AxpyRT op, MapRT cp) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint32_t r = op((uint32_t)load_elem(x, i, xbytes), (uint32_t)load_elem(y, i, ybytes));
+    store_elem(y, i, ybytes, r);
+    if (yc) store_elem(yc, i, cbytes, cp((uint64_t)r));
+}
+
+inline MapRT make_map(int src, int dst) {
+    MapRT m;
+    m.src_kind = src == PNN_F32 ? 1 : (src == PNN_F64 ? 2 : 0);
+    m.dst_kind = dst == PNN_F32 ? 1 : (dst == PNN_F64 ? 2 : 0);
+    m.fs = fmt_of_code(m.src_kind ? 0 : src);
+    m.fd = fmt_of_code(m.dst_kind ? 0 : dst);
+    return m;
+}
+
+inline int launch_map_rt(hipStream_t st, int src, int dst, int64_t n, const void* s, void* d) {
+    hipLaunchKernelGGL(map_rt_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, s, d, (int)elem_size(src), (int)elem_size(dst), n,
+                       make_map(src, dst));
+    return hip_status(hipGetLastError());
+}
+
 }  // namespace pnn
 
 using namespace pnn;
@@ -202,6 +248,7 @@ extern "C" int posit_round(void* stream, int src_float, int dst_posit, int64_t n
     if (n == 0) return PNN_OK;
     if (!src || !dst) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    if (!is_standard(dst_posit)) return launch_map_rt(st, src_float, dst_posit, n, src, dst);
     if (src_float == PNN_F32) {
         switch (dst_posit) {
             case PNN_POSIT8_0: return launch_map<uint32_t, uint8_t>(st, src, dst, n, RoundF32<P8>());
@@ -221,6 +268,7 @@ extern "C" int posit_convert(void* stream, int src, int dst, int64_t n, const vo
     if (n == 0) return PNN_OK;
     if (!src_ptr || !dst_ptr) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    if (!is_standard(src) || !is_standard(dst)) return launch_map_rt(st, src, dst, n, src_ptr, dst_ptr);
     switch (src) {
         case PNN_POSIT8_0: return convert_from<P8>(st, dst, n, src_ptr, dst_ptr);
         case PNN_POSIT16_1: return convert_from<P16>(st, dst, n, src_ptr, dst_ptr);
@@ -235,6 +283,16 @@ extern "C" int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    if (!is_standard(fx) || !is_standard(fy) || (y_copy && !is_standard(fcopy))) {
+        AxpyRT op;
+        op.fx = fmt_of_code(fx);
+        op.fy = fmt_of_code(fy);
+        op.alpha = alpha_bits;
+        const int fc = y_copy ? fcopy : fy;
+        hipLaunchKernelGGL(axpy_rt_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, x, y, y_copy, (int)elem_size(fx),
+                           (int)elem_size(fy), (int)elem_size(fc), n, op, make_map(fy, fc));
+        return hip_status(hipGetLastError());
+    }
     switch (fx) {
         case PNN_POSIT8_0: return axpy_pick_y<P8>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
         case PNN_POSIT16_1: return axpy_pick_y<P16>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);

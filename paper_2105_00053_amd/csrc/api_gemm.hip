@@ -6,9 +6,7 @@
 
 namespace pnn {
 
-template <class F> struct GemmTile;
-template <> struct GemmTile<P8> { static constexpr int TM = 4, TN = 4; };
-template <> struct GemmTile<P16> { static constexpr int TM = 4, TN = 4; };
+template <class F> struct GemmTile { static constexpr int TM = 4, TN = 4; };
 template <> struct GemmTile<P32> { static constexpr int TM = 2, TN = 2; };
 
 // posit<8,0> problems with both output dimensions beyond one small tile take the dot2 kernel
@@ -16,9 +14,9 @@ inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
 
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
-    if (F::N == 8 && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
+    if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
     // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
-    if (F::N == 8 && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
+    if ((F::N == 8 && F::ES == 0) && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
 }
 
@@ -33,7 +31,7 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     RowMajorOut out;
     out.ld = ldc;
     hipError_t e;
-    if (F::N == 8 && use_p8_kernel(M, N)) {
+    if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
         const uint8_t* a8 = (const uint8_t*)A;
         const uint8_t* b8 = (const uint8_t*)B;
         const uint8_t* bias8 = (const uint8_t*)bias;
@@ -44,7 +42,7 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
         else e = launch_p8_gemm<false, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws, plan);
         return hip_status(e);
     }
-    if (F::N == 8 && p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
+    if ((F::N == 8 && F::ES == 0) && p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
         const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
         return hip_status(p8_conv_launch_rowmajor(st, p, (const uint8_t*)bias, C, fout, ws, plan, ldc));
     }
@@ -76,11 +74,8 @@ using namespace pnn;
 extern "C" size_t posit_gemm_workspace(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K) {
     (void)fout; (void)transA; (void)transB;
     if (!is_posit(fin) || M <= 0 || N <= 0 || K < 0) return 0;
-    switch (fin) {
-        case PNN_POSIT8_0: return gemm_plan<P8>(M, N, K).ws_bytes;
-        case PNN_POSIT16_1: return gemm_plan<P16>(M, N, K).ws_bytes;
-        default: return gemm_plan<P32>(M, N, K).ws_bytes;
-    }
+    PNN_DISPATCH_POSIT(fin, return gemm_plan<F>(M, N, K).ws_bytes)
+    return 0;
 }
 
 extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
@@ -95,12 +90,6 @@ extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int trans
     }
     if (M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
-    switch (fin) {
-        case PNN_POSIT8_0:
-            return gemm_dispatch<P8>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
-        case PNN_POSIT16_1:
-            return gemm_dispatch<P16>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
-        default:
-            return gemm_dispatch<P32>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes);
-    }
+    PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes))
+    return PNN_EINVAL;
 }

@@ -7,34 +7,33 @@
 
 namespace pnn {
 
-template <class T>
-__device__ __forceinline__ int32_t as_signed(T p) {
-    // sign-extend an N-bit pattern: posit order == signed integer order
-    return (int32_t)((uint32_t)p << (32 - 8 * sizeof(T))) >> (32 - 8 * sizeof(T));
+// sign-extend an nbits-wide pattern held in a wider container: posit order == signed integer order
+__device__ __forceinline__ int32_t as_signed(uint32_t p, int nbits) {
+    return (int32_t)(p << (32 - nbits)) >> (32 - nbits);
 }
 
 template <class T>
-__global__ __launch_bounds__(256) void relu_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n) {
+__global__ __launch_bounds__(256) void relu_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n, int nbits) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const T p = x[i];
-    const T nar = (T)((T)1 << (8 * sizeof(T) - 1));
-    y[i] = (as_signed(p) > 0 || p == nar) ? p : (T)0;
+    const uint32_t mask = nbits == 32 ? 0xFFFFFFFFu : ((1u << nbits) - 1u);
+    const uint32_t p = (uint32_t)x[i] & mask;
+    y[i] = (T)((as_signed(p, nbits) > 0 || p == (1u << (nbits - 1))) ? p : 0u);
 }
 
 template <class TY, class TD>
-__global__ __launch_bounds__(256) void relu_bwd_kernel(const TY* __restrict__ yf, const TD* __restrict__ dy, TD* __restrict__ dx, int64_t n) {
+__global__ __launch_bounds__(256) void relu_bwd_kernel(const TY* __restrict__ yf, const TD* __restrict__ dy, TD* __restrict__ dx, int64_t n,
+                                                       int ybits, int dbits) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
-    const TY yv = yf[i];
-    const TY ynar = (TY)((TY)1 << (8 * sizeof(TY) - 1));
-    const TD dnar = (TD)((TD)1 << (8 * sizeof(TD) - 1));
-    dx[i] = yv == ynar ? dnar : (as_signed(yv) > 0 ? dy[i] : (TD)0);
+    const uint32_t ymask = ybits == 32 ? 0xFFFFFFFFu : ((1u << ybits) - 1u);
+    const uint32_t yv = (uint32_t)yf[i] & ymask;
+    dx[i] = yv == (1u << (ybits - 1)) ? (TD)(1u << (dbits - 1)) : (as_signed(yv, ybits) > 0 ? dy[i] : (TD)0);
 }
 
 template <class T>
 __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, uint8_t* __restrict__ idx,
-                                                          int64_t total, int H, int W, int kh, int kw) {
+                                                          int64_t total, int H, int W, int kh, int kw, int nbits) {
     const int64_t o = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (o >= total) return;
     const int OW = W / kw, OH = H / kh;
@@ -48,7 +47,7 @@ __global__ __launch_bounds__(256) void maxpool_fwd_kernel(const T* __restrict__ 
     for (int r = 0; r < kh; ++r)
         for (int c = 0; c < kw; ++c) {
             const T v = base[(int64_t)r * W + c];
-            if (as_signed(v) > as_signed(best)) { best = v; bi = r * kw + c; }
+            if (as_signed((uint32_t)v, nbits) > as_signed((uint32_t)best, nbits)) { best = v; bi = r * kw + c; }
         }
     y[o] = best;
     idx[o] = (uint8_t)bi;
@@ -150,40 +149,39 @@ inline bool pool_args_ok(int64_t planes, int64_t H, int64_t W, int64_t kh, int64
 
 using namespace pnn;
 
+namespace pnn {
+inline int bits_of(int code) { int n, es; fmt_params(code, n, es); return n; }
+
+// CALL sees `T`, the container type of format code `code`
+#define PNN_BY_STORAGE(code, CALL)                                     \
+    switch (elem_size(code)) {                                          \
+        case 1: { typedef uint8_t T; CALL; } break;                     \
+        case 2: { typedef uint16_t T; CALL; } break;                    \
+        default: { typedef uint32_t T; CALL; } break;                   \
+    }
+
+template <class TY>
+void relu_bwd_pick(hipStream_t st, int fmt_y, int fmt_d, int64_t n, const void* yf, const void* dy, void* dx) {
+    PNN_BY_STORAGE(fmt_d, hipLaunchKernelGGL((relu_bwd_kernel<TY, T>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf,
+                                             (const T*)dy, (T*)dx, n, bits_of(fmt_y), bits_of(fmt_d)))
+}
+}  // namespace pnn
+
 extern "C" int posit_relu(void* stream, int fmt, int64_t n, const void* x, void* y) {
     if (!is_posit(fmt) || n < 0) return PNN_EINVAL;
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    switch (fmt) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL(relu_kernel<uint8_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint8_t*)x, (uint8_t*)y, n); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL(relu_kernel<uint16_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)y, n); break;
-        default: hipLaunchKernelGGL(relu_kernel<uint32_t>, dim3(blocks_for(n)), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)y, n); break;
-    }
+    PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(relu_kernel<T>, dim3(blocks_for(n)), dim3(256), 0, st, (const T*)x, (T*)y, n, bits_of(fmt)))
     return hip_status(hipGetLastError());
 }
-
-namespace pnn {
-template <class TY>
-void relu_bwd_pick(hipStream_t st, int fmt_d, int64_t n, const void* yf, const void* dy, void* dx) {
-    switch (fmt_d) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint8_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint8_t*)dy, (uint8_t*)dx, n); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint16_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint16_t*)dy, (uint16_t*)dx, n); break;
-        default: hipLaunchKernelGGL((relu_bwd_kernel<TY, uint32_t>), dim3(blocks_for(n)), dim3(256), 0, st, (const TY*)yf, (const uint32_t*)dy, (uint32_t*)dx, n); break;
-    }
-}
-}  // namespace pnn
 
 extern "C" int posit_relu_bwd(void* stream, int fmt_y, int fmt_d, int64_t n, const void* y_fwd, const void* dy, void* dx) {
     if (!is_posit(fmt_y) || !is_posit(fmt_d) || n < 0) return PNN_EINVAL;
     if (n == 0) return PNN_OK;
     if (!y_fwd || !dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    switch (fmt_y) {
-        case PNN_POSIT8_0: relu_bwd_pick<uint8_t>(st, fmt_d, n, y_fwd, dy, dx); break;
-        case PNN_POSIT16_1: relu_bwd_pick<uint16_t>(st, fmt_d, n, y_fwd, dy, dx); break;
-        default: relu_bwd_pick<uint32_t>(st, fmt_d, n, y_fwd, dy, dx); break;
-    }
+    PNN_BY_STORAGE(fmt_y, relu_bwd_pick<T>(st, fmt_y, fmt_d, n, y_fwd, dy, dx))
     return hip_status(hipGetLastError());
 }
 
@@ -194,11 +192,8 @@ extern "C" int posit_maxpool2d_fwd(void* stream, int fmt, int64_t planes, int64_
     if (!x || !y || !idx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const int64_t total = planes * (H / kh) * (W / kw);
-    switch (fmt) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL(maxpool_fwd_kernel<uint8_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)x, (uint8_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL(maxpool_fwd_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)x, (uint16_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-        default: hipLaunchKernelGGL(maxpool_fwd_kernel<uint32_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)x, (uint32_t*)y, (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-    }
+    PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(blocks_for(total)), dim3(256), 0, st, (const T*)x, (T*)y,
+                                           (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw, bits_of(fmt)))
     return hip_status(hipGetLastError());
 }
 
@@ -209,11 +204,8 @@ extern "C" int posit_maxpool2d_bwd(void* stream, int fmt, int64_t planes, int64_
     if (!dy || !dx || !idx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const int64_t total = planes * H * W;
-    switch (fmt) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL(maxpool_bwd_kernel<uint8_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)dy, (const uint8_t*)idx, (uint8_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL(maxpool_bwd_kernel<uint16_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)dy, (const uint8_t*)idx, (uint16_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-        default: hipLaunchKernelGGL(maxpool_bwd_kernel<uint32_t>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)dy, (const uint8_t*)idx, (uint32_t*)dx, total, (int)H, (int)W, (int)kh, (int)kw); break;
-    }
+    PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(blocks_for(total)), dim3(256), 0, st, (const T*)dy,
+                                           (const uint8_t*)idx, (T*)dx, total, (int)H, (int)W, (int)kh, (int)kw))
     return hip_status(hipGetLastError());
 }
 
@@ -226,11 +218,9 @@ extern "C" int posit_avgpool2d_fwd(void* stream, int fin, int fout, int64_t plan
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const int64_t total = planes * (H / kh) * (W / kw);
-    switch (fin) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL(avgpool_fwd_kernel<P8>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(8, 0, s)); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL(avgpool_fwd_kernel<P16>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(16, 1, s)); break;
-        default: hipLaunchKernelGGL(avgpool_fwd_kernel<P32>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(32, 2, s)); break;
-    }
+    PNN_DISPATCH_POSIT(fin, hipLaunchKernelGGL(avgpool_fwd_kernel<F>, dim3(blocks_for(total)), dim3(256), 0, st,
+                                               (const typename Storage<F::N>::T*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw,
+                                               pow2_pattern(F::N, F::ES, s)))
     return hip_status(hipGetLastError());
 }
 
@@ -243,10 +233,8 @@ extern "C" int posit_avgpool2d_bwd(void* stream, int fin, int fout, int64_t plan
     if (!dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const int64_t total = planes * H * W;
-    switch (fin) {
-        case PNN_POSIT8_0: hipLaunchKernelGGL(avgpool_bwd_kernel<P8>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint8_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(8, 0, s)); break;
-        case PNN_POSIT16_1: hipLaunchKernelGGL(avgpool_bwd_kernel<P16>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint16_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(16, 1, s)); break;
-        default: hipLaunchKernelGGL(avgpool_bwd_kernel<P32>, dim3(blocks_for(total)), dim3(256), 0, st, (const uint32_t*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw, pow2_pattern(32, 2, s)); break;
-    }
+    PNN_DISPATCH_POSIT(fin, hipLaunchKernelGGL(avgpool_bwd_kernel<F>, dim3(blocks_for(total)), dim3(256), 0, st,
+                                               (const typename Storage<F::N>::T*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw,
+                                               pow2_pattern(F::N, F::ES, s)))
     return hip_status(hipGetLastError());
 }

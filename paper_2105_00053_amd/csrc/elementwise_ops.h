@@ -136,4 +136,43 @@ struct Axpy {
     }
 };
 
+// ---- formats chosen at run time (the (8,1), (8,2), (10,x), (12,x) family of Sec. 4) ----
+
+// kind: 0 = posit (format in f), 1 = binary32, 2 = binary64
+struct MapRT {
+    int src_kind, dst_kind;
+    FmtRT fs, fd;
+    PNN_HD uint64_t operator()(uint64_t bits) const {
+        Real r;
+        int c;  // 0 zero, 1 finite nonzero, 2 NaR / NaN / Inf
+        if (src_kind == 1) c = real_from_f32((uint32_t)bits, r);
+        else if (src_kind == 2) c = real_from_f64(bits, r);
+        else {
+            const uint32_t q = (uint32_t)bits & fs.mask();
+            c = q == 0 ? 0 : (q == fs.nar() ? 2 : 1);
+            if (c == 1) r = decode_rt(q, fs);
+        }
+        if (dst_kind == 1) return c == 0 ? 0u : (c == 2 ? 0x7FC00000u : real_to_f32_bits(r));
+        if (dst_kind == 2) return c == 0 ? 0ull : (c == 2 ? 0x7FF8000000000000ull : real_to_f64_bits(r));
+        return c == 0 ? 0u : (c == 2 ? fd.nar() : encode_rt(r, fd));
+    }
+};
+
+struct AxpyRT {
+    FmtRT fx, fy;
+    uint32_t alpha;
+    PNN_HD uint32_t operator()(uint32_t x, uint32_t y) const {
+        x &= fx.mask();
+        y &= fy.mask();
+        const uint32_t a = alpha & fy.mask();
+        if (a == fy.nar() || x == fx.nar() || y == fy.nar()) return fy.nar();
+        if (a == 0 || x == 0) return y;
+        const Real t = real_mul(decode_rt(a, fy), decode_rt(x, fx));
+        if (y == 0) return encode_rt(t, fy);
+        Real s;
+        if (!real_add(decode_rt(y, fy), t, s)) return 0;
+        return encode_rt(s, fy);
+    }
+};
+
 }  // namespace pnn

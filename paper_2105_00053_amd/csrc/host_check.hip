@@ -47,9 +47,10 @@ uint32_t dot_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int
         if (bias == F::NAR) nar = true;
         else AR::add_value(q, AR::stage(bias));
     }
-    if (fout == 0) return nar ? P8::NAR : quire_round<F, P8, AR::L>(q);
-    if (fout == 1) return nar ? P16::NAR : quire_round<F, P16, AR::L>(q);
-    return nar ? P32::NAR : quire_round<F, P32, AR::L>(q);
+    const FmtRT fo = fmt_of_code(fout);
+    Real r;
+    if (nar) return fo.nar();
+    return quire_read<F, AR::L>(q, r) ? encode_rt(r, fo) : 0u;
 }
 }  // namespace
 
@@ -65,6 +66,26 @@ int hostcheck_round(int src_float, int dst, int64_t n, const uint64_t* in, uint6
         else if (dst == 1) run_map(RoundF64<P16>(), n, in, out);
         else run_map(RoundF64<P32>(), n, in, out);
     }
+    return 0;
+}
+
+// run-time-format paths (any posit code 0..8, 100 = binary32, 101 = binary64)
+int hostcheck_map_rt(int src, int dst, int64_t n, const uint64_t* in, uint64_t* out) {
+    MapRT m;
+    m.src_kind = src == 100 ? 1 : (src == 101 ? 2 : 0);
+    m.dst_kind = dst == 100 ? 1 : (dst == 101 ? 2 : 0);
+    m.fs = fmt_of_code(m.src_kind ? 0 : src);
+    m.fd = fmt_of_code(m.dst_kind ? 0 : dst);
+    for (int64_t i = 0; i < n; ++i) out[i] = m(in[i]);
+    return 0;
+}
+
+int hostcheck_axpy_rt(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t* x, const uint64_t* y, uint64_t* out) {
+    AxpyRT op;
+    op.fx = fmt_of_code(fx);
+    op.fy = fmt_of_code(fy);
+    op.alpha = alpha;
+    for (int64_t i = 0; i < n; ++i) out[i] = op((uint32_t)x[i], (uint32_t)y[i]);
     return 0;
 }
 
@@ -84,9 +105,17 @@ int hostcheck_axpy(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t* x,
 }
 
 uint32_t hostcheck_dot(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
-    if (fin == 0) return dot_host<P8>(fout, n, a, b, has_bias, bias);
-    if (fin == 1) return dot_host<P16>(fout, n, a, b, has_bias, bias);
-    return dot_host<P32>(fout, n, a, b, has_bias, bias);
+    switch (fin) {
+        case 0: return dot_host<P8>(fout, n, a, b, has_bias, bias);
+        case 1: return dot_host<P16>(fout, n, a, b, has_bias, bias);
+        case 2: return dot_host<P32>(fout, n, a, b, has_bias, bias);
+        case 3: return dot_host<P8_1>(fout, n, a, b, has_bias, bias);
+        case 4: return dot_host<P8_2>(fout, n, a, b, has_bias, bias);
+        case 5: return dot_host<P10_1>(fout, n, a, b, has_bias, bias);
+        case 6: return dot_host<P10_2>(fout, n, a, b, has_bias, bias);
+        case 7: return dot_host<P12_1>(fout, n, a, b, has_bias, bias);
+        default: return dot_host<P12_2>(fout, n, a, b, has_bias, bias);
+    }
 }
 
 // Implicit-GEMM gather descriptors of the posit<8,0> convolution path, evaluated on the host:

@@ -15,8 +15,16 @@
 
 namespace pnn {
 
-// posit<N,ES> with the quire of Table 1 (32 bits per 8-bit posit width, squared growth:
-// 32 / 128 / 512 bits), held as 32-bit limbs.
+// posit<N,ES> and its quire, held as 32-bit limbs.  The standard formats take
+// the widths of Table 1 (N^2/2 = 32 / 128 / 512 bits).  Other (N,ES) pairs, which
+// the paper's experiments use (Sec. 4: posit(8,1), (8,2), (10,x), (12,x)), get
+// 4(N-2)2^ES bits for the largest product over the smallest one, one sign bit and
+// N-1 carry-guard bits, rounded up to whole limbs.
+constexpr int quire_bits_for(int n, int es) {
+    return (n == 8 && es == 0) ? 32 : (n == 16 && es == 1) ? 128 : (n == 32 && es == 2) ? 512
+           : ((4 * (n - 2) * (1 << es) + 1 + (n - 1) + 31) / 32) * 32;
+}
+
 template <int N_, int ES_>
 struct Fmt {
     static constexpr int N = N_;
@@ -25,19 +33,59 @@ struct Fmt {
     static constexpr uint32_t MASK = N_ == 32 ? 0xFFFFFFFFu : ((1u << (N_ & 31)) - 1u);
     static constexpr uint32_t NAR = 1u << (N_ - 1);
     static constexpr int FB = N_ - 3 - ES_;          // most fraction bits a pattern can hold
-    static constexpr int QBITS = N_ * N_ / 2;        // 32, 128, 512
-    static constexpr int QLIMBS = QBITS / 32;        // 1, 4, 16
+    static constexpr int QBITS = quire_bits_for(N_, ES_);
+    static constexpr int QLIMBS = QBITS / 32;
     static constexpr int QFRAC = 2 * MAXS;           // quire LSB = 2^-QFRAC = minpos^2
 };
 // Unsigned integer type that stores one pattern of an N-bit posit.
 template <int NBITS> struct Storage;
 template <> struct Storage<8> { typedef uint8_t T; };
+template <> struct Storage<10> { typedef uint16_t T; };  // low N bits of the container
+template <> struct Storage<12> { typedef uint16_t T; };
 template <> struct Storage<16> { typedef uint16_t T; };
 template <> struct Storage<32> { typedef uint32_t T; };
 
 using P8 = Fmt<8, 0>;
 using P16 = Fmt<16, 1>;
 using P32 = Fmt<32, 2>;
+using P8_1 = Fmt<8, 1>;
+using P8_2 = Fmt<8, 2>;
+using P10_1 = Fmt<10, 1>;
+using P10_2 = Fmt<10, 2>;
+using P12_1 = Fmt<12, 1>;
+using P12_2 = Fmt<12, 2>;
+
+// Format codes of the C ABI (pnn_dtype): 0..2 the standard formats of Table 1, 3..8 the
+// other (N,ES) pairs of the paper's experiments.
+PNN_HD void fmt_params(int code, int& n, int& es) {
+    switch (code) {
+        case 0: n = 8; es = 0; break;
+        case 1: n = 16; es = 1; break;
+        case 2: n = 32; es = 2; break;
+        case 3: n = 8; es = 1; break;
+        case 4: n = 8; es = 2; break;
+        case 5: n = 10; es = 1; break;
+        case 6: n = 10; es = 2; break;
+        case 7: n = 12; es = 1; break;
+        default: n = 12; es = 2; break;
+    }
+}
+
+// A format known only at run time (elementwise kernels on the non-standard formats,
+// output format of the GEMM epilogues).
+struct FmtRT {
+    int n, es;
+    PNN_HD int maxs() const { return (n - 2) << es; }
+    PNN_HD uint32_t mask() const { return n == 32 ? 0xFFFFFFFFu : ((1u << (n & 31)) - 1u); }
+    PNN_HD uint32_t nar() const { return 1u << (n - 1); }
+    PNN_HD int bytes() const { return n <= 8 ? 1 : (n <= 16 ? 2 : 4); }
+};
+
+PNN_HD FmtRT fmt_of_code(int code) {
+    FmtRT f;
+    fmt_params(code, f.n, f.es);
+    return f;
+}
 
 PNN_HD int clz32(uint32_t x) {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -64,30 +112,33 @@ struct Real {
     bool sticky;
 };
 
-// Field decode of a pattern that is neither 0 nor NaR (Eq. 2).  Negative
-// patterns are two's-complemented first.  `nf` receives how many genuine
-// fraction bits the pattern carries (they sit at the top of r.frac).
+// Field decode of a pattern that is neither 0 nor NaR (Eq. 2), for any n <= 32.
+// Negative patterns are two's-complemented first.  The fraction comes back at
+// the top of a 32-bit word (a posit carries at most 27 fraction bits); `nf`
+// receives how many genuine fraction bits the pattern holds.
+PNN_HD void decode_core(uint32_t p, int n, int es, bool& neg, int& scale, uint32_t& frac, int& nf) {
+    const uint32_t mask = n == 32 ? 0xFFFFFFFFu : ((1u << (n & 31)) - 1u);
+    neg = (p >> (n - 1)) & 1u;
+    const uint32_t x = neg ? ((0u - p) & mask) : p;
+    const uint32_t y = x << (33 - n);          // first regime bit in bit 31, zeros shifted in below
+    const uint32_t lead = y >> 31;
+    const int run = clz32(lead ? ~y : y);      // regime run length, 1 .. n-1
+    const int k = lead ? run - 1 : -run;
+    const uint32_t rest = (y << run) << 1;     // drop the run and the bit that ended it
+    const int e = es ? (int)(rest >> ((32 - es) & 31)) : 0;  // cut-off exponent bits arrive as zeros
+    frac = rest << es;
+    scale = k * (1 << es) + e;
+    nf = n - 2 - run - es;
+    if (nf < 0) nf = 0;
+}
+
 template <class F>
 PNN_HD Real decode_fields(uint32_t p, int& nf) {
     Real r;
-    r.neg = (p >> (F::N - 1)) & 1u;
-    const uint32_t x = r.neg ? ((0u - p) & F::MASK) : p;
-    const uint32_t y = x << (33 - F::N);       // first regime bit in bit 31, zeros shifted in below
-    const uint32_t lead = y >> 31;
-    const int run = clz32(lead ? ~y : y);      // regime run length, 1 .. N-1
-    const int k = lead ? run - 1 : -run;
-    const uint32_t rest = (y << run) << 1;     // drop the run and the bit that ended it
-    int e = 0;
-    uint32_t fr = rest;
-    if (F::ES > 0) {
-        e = (int)(rest >> (32 - F::ES));       // cut-off exponent bits arrive as zeros
-        fr = rest << F::ES;
-    }
-    r.scale = k * (1 << F::ES) + e;
+    uint32_t fr;
+    decode_core(p, F::N, F::ES, r.neg, r.scale, fr, nf);
     r.frac = (uint64_t)fr << 32;
     r.sticky = false;
-    nf = F::N - 2 - run - F::ES;
-    if (nf < 0) nf = 0;
     return r;
 }
 
@@ -95,6 +146,16 @@ template <class F>
 PNN_HD Real decode_fields(uint32_t p) {
     int nf;
     return decode_fields<F>(p, nf);
+}
+
+PNN_HD Real decode_rt(uint32_t p, const FmtRT& f) {
+    Real r;
+    uint32_t fr;
+    int nf;
+    decode_core(p, f.n, f.es, r.neg, r.scale, fr, nf);
+    r.frac = (uint64_t)fr << 32;
+    r.sticky = false;
+    return r;
 }
 
 // Fixed-point view used by the quire: value = sig * 2^sh * minpos with sig odd or
@@ -110,19 +171,20 @@ PNN_HD void decode_fixed(uint32_t p, bool& neg, uint32_t& sig, int& sh) {
     sh = r.scale - nf + F::MAXS;
 }
 
-// The one rounding: nearest posit<N,ES>, ties to the even pattern, never to 0 or
+// The one rounding: nearest posit<n,es>, ties to the even pattern, never to 0 or
 // NaR.  The unbounded string regime | exponent | fraction is assembled at the
-// top of a 64-bit word and cut after N-1 bits.
-template <class F>
-PNN_HD uint32_t encode(const Real& r) {
+// top of a 64-bit word and cut after n-1 bits.  Any n <= 32.
+PNN_HD uint32_t encode_core(const Real& r, int n, int es) {
+    const int maxs = (n - 2) << es;
+    const uint32_t mask = n == 32 ? 0xFFFFFFFFu : ((1u << (n & 31)) - 1u);
     uint32_t body;
-    if (r.scale >= F::MAXS) {
-        body = F::NAR - 1u;  // maxpos and beyond
-    } else if (r.scale < -F::MAXS) {
-        body = 1u;           // below minpos
+    if (r.scale >= maxs) {
+        body = (1u << (n - 1)) - 1u;  // maxpos and beyond
+    } else if (r.scale < -maxs) {
+        body = 1u;                    // below minpos
     } else {
-        const int k = r.scale >> F::ES;  // floor
-        const uint32_t e = (uint32_t)(r.scale & ((1 << F::ES) - 1));
+        const int k = r.scale >> es;  // floor
+        const uint32_t e = (uint32_t)(r.scale & ((1 << es) - 1));
         int rl;
         uint64_t regime;
         if (k >= 0) {
@@ -132,17 +194,24 @@ PNN_HD uint32_t encode(const Real& r) {
             rl = 1 - k;
             regime = 1u;  // -k zeros, one one
         }
-        const int hl = rl + F::ES;  // 2 .. N-1+ES
-        const uint64_t head = (regime << F::ES) | e;
+        const int hl = rl + es;  // 2 .. n-1+es
+        const uint64_t head = (regime << es) | e;
         const uint64_t w = (head << (64 - hl)) | (r.frac >> hl);
         bool sticky = r.sticky || ((r.frac << (64 - hl)) != 0);
-        body = (uint32_t)(w >> (65 - F::N));
-        const uint32_t guard = (uint32_t)(w >> (64 - F::N)) & 1u;
-        sticky = sticky || ((w << F::N) != 0);
+        body = (uint32_t)(w >> (65 - n));
+        const uint32_t guard = (uint32_t)(w >> (64 - n)) & 1u;
+        sticky = sticky || ((w << n) != 0);
         body += guard & ((sticky ? 1u : 0u) | (body & 1u));
     }
-    return r.neg ? ((0u - body) & F::MASK) : body;
+    return r.neg ? ((0u - body) & mask) : body;
 }
+
+template <class F>
+PNN_HD uint32_t encode(const Real& r) {
+    return encode_core(r, F::N, F::ES);
+}
+
+PNN_HD uint32_t encode_rt(const Real& r, const FmtRT& f) { return encode_core(r, f.n, f.es); }
 
 // 32-bit variants for the bandwidth-bound kernels: a posit carries at most 27
 // fraction bits, so a decoded value fits a 32-bit fraction, and for formats of at
@@ -175,21 +244,8 @@ PNN_HD Real widen(const Real32& r) {
 template <class F>
 PNN_HD Real32 decode_fields32(uint32_t p) {
     Real32 r;
-    r.neg = (p >> (F::N - 1)) & 1u;
-    const uint32_t x = r.neg ? ((0u - p) & F::MASK) : p;
-    const uint32_t y = x << (33 - F::N);
-    const uint32_t lead = y >> 31;
-    const int run = clz32(lead ? ~y : y);
-    const int k = lead ? run - 1 : -run;
-    const uint32_t rest = (y << run) << 1;
-    int e = 0;
-    uint32_t fr = rest;
-    if (F::ES > 0) {
-        e = (int)(rest >> (32 - F::ES));
-        fr = rest << F::ES;
-    }
-    r.scale = k * (1 << F::ES) + e;
-    r.frac = fr;
+    int nf;
+    decode_core(p, F::N, F::ES, r.neg, r.scale, r.frac, nf);
     r.sticky = false;
     return r;
 }

@@ -62,10 +62,34 @@ PNN_HD void quire_merge(uint32_t (&q)[L], const uint32_t (&o)[L]) {
     }
 }
 
+// Narrow an accumulator held in L limbs to its true width QB (sign-extend from bit QB-1).
+template <int L, int QB>
+PNN_HD void quire_wrap(uint32_t (&q)[L]) {
+    if (QB >= 32 * L) return;
+    constexpr int top = (QB - 1) / 32, bit = (QB - 1) % 32;
+    const uint32_t ext = (q[top] >> bit) & 1u ? 0xFFFFFFFFu : 0u;
+    if (bit != 31) {
+        const uint32_t keep = (1u << (bit + 1)) - 1u;
+        q[top] = (q[top] & keep) | (ext & ~keep);
+    }
+#pragma unroll
+    for (int l = top + 1; l < L; ++l) q[l] = ext;
+}
+
+// Read the quire of FIN out as a real number (false when exactly zero).
+template <class FIN, int L>
+PNN_HD bool quire_read(const uint32_t (&qin)[L], Real& r) {
+    uint32_t q[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) q[l] = qin[l];
+    quire_wrap<L, FIN::QBITS>(q);
+    return quire_to_real<L>(q, FIN::QFRAC, r);
+}
+
 template <class FIN, class FOUT, int L>
 PNN_HD uint32_t quire_round(const uint32_t (&q)[L]) {
     Real r;
-    if (!quire_to_real<L>(q, FIN::QFRAC, r)) return 0u;
+    if (!quire_read<FIN, L>(q, r)) return 0u;
     return encode<FOUT>(r);
 }
 
@@ -119,32 +143,50 @@ struct Arith<P8> {
     PNN_HD static void add_value(uint32_t (&q)[1], Elem a) { q[0] += (uint32_t)a << P8::MAXS; }
 };
 
-// posit<16,1>: staged word = signed 13-bit significand in the low half, shift
-// (0..56, in units of minpos = 2^-28) in the high half.
-template <>
-struct Arith<P16> {
+// Formats of at most 16 bits other than posit<8,0> (posit<16,1> and the (8,1), (8,2),
+// (10,x), (12,x) family): staged word = signed significand (at most 14 bits) in the
+// low half, shift in units of minpos in the high half.  The quire is kept in two
+// limbs when it has at most 64 bits, in four up to 128 bits (a 96-bit quire is
+// accumulated modulo 2^128 and narrowed when it is read out, which is the same as
+// wrapping modulo 2^96 all along), else in QBITS/32 limbs.
+template <int N, int ES>
+struct Arith<Fmt<N, ES>> {
+    typedef Fmt<N, ES> F;
+    static_assert(N <= 16, "small-format arithmetic");
     typedef uint32_t Elem;
-    static constexpr int L = 4;
+    static constexpr int L = F::QBITS <= 64 ? 2 : (F::QBITS <= 128 ? 4 : F::QLIMBS);
     PNN_HD static Elem stage(uint32_t p) {
-        if (p == 0 || p == P16::NAR) return 0;
+        if (p == 0 || p == F::NAR) return 0;
         bool neg;
         uint32_t sig;
         int sh;
-        decode_fixed<P16>(p, neg, sig, sh);
+        decode_fixed<F>(p, neg, sig, sh);
         const int32_t v = neg ? -(int32_t)sig : (int32_t)sig;
         return ((uint32_t)sh << 16) | ((uint32_t)v & 0xFFFFu);
     }
-    PNN_HD static void mac(uint32_t (&q)[4], Elem a, Elem b) {
+    PNN_HD static void add_product(uint32_t (&q)[L], int32_t P, int s) {
+        if constexpr (L == 2) {
+            uint64_t acc = ((uint64_t)q[1] << 32) | q[0];
+            acc += (uint64_t)((int64_t)P << s);  // s <= 4*MAXS/2 + ... < 64 - product width
+            q[0] = (uint32_t)acc;
+            q[1] = (uint32_t)(acc >> 32);
+        } else if constexpr (L == 4) {
+            quire_add128(q, P, s);
+        } else {
+            quire_add32<L>(q, P, s);  // wider quires ((10,2), (12,2)): select-based limb placement
+        }
+    }
+    PNN_HD static void mac(uint32_t (&q)[L], Elem a, Elem b) {
         const int32_t sa = (int16_t)(a & 0xFFFFu), sb = (int16_t)(b & 0xFFFFu);
 #if defined(__HIP_DEVICE_COMPILE__)
         const int32_t P = __mul24(sa, sb);
 #else
         const int32_t P = sa * sb;
 #endif
-        quire_add128(q, P, (int)(a >> 16) + (int)(b >> 16));
+        add_product(q, P, (int)(a >> 16) + (int)(b >> 16));
     }
-    PNN_HD static void add_value(uint32_t (&q)[4], Elem a) {
-        quire_add128(q, (int16_t)(a & 0xFFFFu), (int)(a >> 16) + P16::MAXS);
+    PNN_HD static void add_value(uint32_t (&q)[L], Elem a) {
+        add_product(q, (int16_t)(a & 0xFFFFu), (int)(a >> 16) + F::MAXS);
     }
 };
 

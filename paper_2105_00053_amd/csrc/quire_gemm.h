@@ -172,19 +172,17 @@ struct SplitWs {
 constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_KT = 16;
 
-// Round an L-limb quire of format FIN to the output format chosen at run time
-// (0 = posit<8,0>, 1 = posit<16,1>, 2 = posit<32,2>) and store it.
+// Round an L-limb quire of format FIN to the output format chosen at run time (format
+// code of the C ABI) and store it in that format's container.
 template <class FIN, int L>
 __device__ __forceinline__ void round_store(const uint32_t (&q)[L], bool nar, int fout, void* C, int64_t at) {
+    const FmtRT fo = fmt_of_code(fout);
     Real r;
-    const bool nonzero = quire_to_real<L>(q, FIN::QFRAC, r);
-    if (fout == 0) {
-        ((uint8_t*)C)[at] = (uint8_t)(nar ? P8::NAR : nonzero ? encode<P8>(r) : 0u);
-    } else if (fout == 1) {
-        ((uint16_t*)C)[at] = (uint16_t)(nar ? P16::NAR : nonzero ? encode<P16>(r) : 0u);
-    } else {
-        ((uint32_t*)C)[at] = nar ? P32::NAR : nonzero ? encode<P32>(r) : 0u;
-    }
+    const bool nonzero = quire_read<FIN, L>(q, r);
+    const uint32_t res = nar ? fo.nar() : (nonzero ? encode_rt(r, fo) : 0u);
+    if (fo.n <= 8) ((uint8_t*)C)[at] = (uint8_t)res;
+    else if (fo.n <= 16) ((uint16_t*)C)[at] = (uint16_t)res;
+    else ((uint32_t*)C)[at] = res;
 }
 
 template <class FIN, class OpA, class OpB, class Out, int TM, int TN>

@@ -4,8 +4,10 @@ import torch
 
 import paper_2105_00053_amd as pn
 
-NP_DTYPE = {"p8": np.uint8, "p16": np.uint16, "p32": np.uint32}
-BITS = {"p8": 8, "p16": 16, "p32": 32}
+NP_DTYPE = {"p8": np.uint8, "p16": np.uint16, "p32": np.uint32, "p8_1": np.uint8, "p8_2": np.uint8,
+            "p10_1": np.uint16, "p10_2": np.uint16, "p12_1": np.uint16, "p12_2": np.uint16}
+BITS = {"p8": 8, "p16": 16, "p32": 32, "p8_1": 8, "p8_2": 8, "p10_1": 10, "p10_2": 10, "p12_1": 12, "p12_2": 12}
+GENERAL = ["p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2"]  # formats of the paper's experiments outside Table 1
 _VIEW = {np.dtype(np.uint8): torch.uint8, np.dtype(np.uint16): torch.int16, np.dtype(np.uint32): torch.int32}
 _NP_SIGNED = {np.dtype(np.uint8): np.uint8, np.dtype(np.uint16): np.int16, np.dtype(np.uint32): np.int32}
 

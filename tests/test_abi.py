@@ -50,7 +50,7 @@ def test_argument_validation_without_launch():
     null = ctypes.c_void_p(0)
     fake = ctypes.c_void_p(0x1000)  # never dereferenced: the calls below are rejected before any launch
     EINVAL = 1
-    assert L.posit_gemm(null, 7, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # unknown format
+    assert L.posit_gemm(null, 57, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # unknown format
     assert L.posit_gemm(null, 0, 0, 0, 0, -1, 4, 4, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL     # negative size
     assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 4, null, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # null A
     assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # lda < K

@@ -13,10 +13,10 @@ import workloads
 from oracle import fast
 from oracle import posit_oracle as po
 
-from gpu_util import BITS, NP_DTYPE, mismatches, rand_patterns, to_dev, to_np
+from gpu_util import BITS, GENERAL, NP_DTYPE, mismatches, rand_patterns, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
-PF = {"p8": po.P8, "p16": po.P16, "p32": po.P32}
+PF = {k: po.FORMATS[k] for k in BITS}
 
 
 def _assert_equal(got, want, what):
@@ -332,3 +332,106 @@ def test_avgpool_forward_backward(fin, fout):
     dy = rand_patterns(rng, (planes, H // kh, W // kw), fin, special=0.05)
     dx = pn.posit_avgpool2d_bwd(to_dev(dy), fin, fout, kh, kw)
     _assert_equal(to_np(dx, fout).flatten(), np.array(po.avgpool2d_bwd(dy.flatten().tolist(), planes, H, W, kh, kw, PF[fin], PF[fout])), "avgpool bwd")
+
+
+# ---------------- the formats of the paper's experiments outside Table 1 (Sec. 4: posit<8..12, 1..2>) ----------------
+
+@pytest.mark.parametrize("fmt", GENERAL)
+def test_general_formats_round_convert(fmt):
+    rng = np.random.default_rng(BITS[fmt] * 3 + len(fmt))
+    n = 60001
+    x = (rng.standard_normal(n) * np.exp2(rng.uniform(-60, 60, n))).astype(np.float32)
+    x[:5] = [0.0, -0.0, np.inf, np.nan, 1e-45]
+    _assert_equal(to_np(pn.posit_round(to_dev(x), fmt), fmt), fast.round_from_float(x, fmt), "round f32->" + fmt)
+    x64 = rng.standard_normal(n) * np.exp2(rng.uniform(-300, 300, n))
+    _assert_equal(to_np(pn.posit_round(to_dev(x64), fmt), fmt), fast.round_from_float(x64, fmt), "round f64->" + fmt)
+    pats = np.arange(1 << BITS[fmt], dtype=np.uint32).astype(NP_DTYPE[fmt])
+    for dst in GENERAL + ["p8", "p16", "p32"]:
+        _assert_equal(to_np(pn.posit_convert(to_dev(pats), fmt, dst), dst), fast.convert(pats, fmt, dst), "convert %s->%s" % (fmt, dst))
+    for src in ("p16", "p32"):
+        sp = rand_patterns(rng, 100001, src)
+        _assert_equal(to_np(pn.posit_convert(to_dev(sp), src, fmt), fmt), fast.convert(sp, src, fmt), "convert %s->%s" % (src, fmt))
+    for dst in ("f32", "f64"):
+        got = pn.posit_convert(to_dev(pats), fmt, dst).cpu().numpy()
+        want = fast.to_float(pats, fmt, dst)
+        nan = np.isnan(want)
+        assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], want[~nan])
+
+
+@pytest.mark.parametrize("fx,fy,fc", [("p12_2", "p12_2", "p8_2"), ("p8_2", "p12_2", None), ("p8_2", "p8_2", None), ("p10_1", "p12_1", "p8_1"),
+                                      ("p8_1", "p10_2", "p8"), ("p16", "p12_2", "p10_2"), ("p12_1", "p16", "p12_1")])
+def test_general_formats_axpy(fx, fy, fc):
+    test_axpy(fx, fy, fc)
+
+
+GENERAL_GEMM_CASES = [
+    ("p8_1", "p8_1", 70, 130, 100, 0, 0, 1, 1),
+    ("p8_2", "p8_2", 65, 63, 129, 1, 0, 0, 1),
+    ("p8_2", "p12_2", 130, 70, 300, 0, 1, 1, 0),
+    ("p10_1", "p10_1", 33, 129, 257, 1, 1, 1, 1),
+    ("p10_2", "p10_2", 64, 64, 200, 0, 0, 0, 1),
+    ("p12_1", "p12_1", 100, 50, 96, 0, 0, 1, 0),
+    ("p12_2", "p12_2", 130, 70, 100, 0, 0, 1, 1),
+    ("p12_2", "p8_2", 20, 33, 64, 0, 1, 0, 0),
+    ("p16", "p12_2", 40, 35, 50, 0, 0, 1, 1),
+    ("p8", "p10_1", 150, 140, 70, 0, 0, 0, 1),   # posit<8,0> packed-dot kernel, general output format
+    ("p8_1", "p32", 17, 5, 31, 1, 1, 0, 0),
+]
+
+
+@pytest.mark.parametrize("fin,fout,M,N,K,ta,tb,use_bias,nar", GENERAL_GEMM_CASES)
+def test_general_formats_gemm(fin, fout, M, N, K, ta, tb, use_bias, nar):
+    test_gemm_random_patterns(fin, fout, M, N, K, ta, tb, use_bias, nar)
+
+
+@pytest.mark.parametrize("fin,fout,M,N,K", [("p8_2", "p12_2", 32, 96, 8192), ("p12_2", "p12_2", 16, 50, 4096), ("p10_1", "p10_1", 24, 40, 4096),
+                                            ("p8_1", "p8_1", 8, 24, 70000)])
+def test_general_formats_gemm_split_reduction(fin, fout, M, N, K):
+    """Long reductions take the split-K path; posit<8,1> with maxpos operands in one row wraps its 64-bit quire."""
+    rng = np.random.default_rng(K + M)
+    A = rand_patterns(rng, (M, K), fin, special=0.0, allow_nar=False)
+    B = rand_patterns(rng, (K, N), fin, special=0.0, allow_nar=False)
+    if fin == "p8_1":
+        A[0, :] = 0x7F
+        B[:, 0] = 0x7F
+    assert pn.posit_gemm_workspace(fin, fout, False, False, M, N, K) > 0
+    got = pn.posit_gemm(to_dev(A), to_dev(B), fin, fout)
+    want, ovf = fast.gemm(A, B, fin, fout)
+    if fin == "p8_1":
+        assert ovf >= 1
+    _assert_equal(to_np(got, fout), want, "split gemm %s" % fin)
+
+
+@pytest.mark.parametrize("ci", [0, 1, 3])
+@pytest.mark.parametrize("fin,fout", [("p8_2", "p8_2"), ("p8_2", "p12_2"), ("p12_2", "p12_2"), ("p10_1", "p10_1"), ("p8_1", "p12_1"), ("p10_2", "p8_2")])
+def test_general_formats_conv(ci, fin, fout):
+    test_conv_all_three_passes(ci, fin, fout)
+
+
+@pytest.mark.parametrize("fmt", GENERAL)
+def test_general_formats_glue(fmt):
+    rng = np.random.default_rng(BITS[fmt] + len(fmt))
+    n = 20001
+    x = rand_patterns(rng, n, fmt, special=0.05)
+    y = to_np(pn.posit_relu(to_dev(x), fmt), fmt)
+    _assert_equal(y, np.array(po.relu(x.tolist(), PF[fmt])), "relu")
+    dy = rand_patterns(rng, n, "p12_2")
+    dx = to_np(pn.posit_relu_bwd(to_dev(y), to_dev(dy), fmt, "p12_2"), "p12_2")
+    _assert_equal(dx, np.array(po.relu_bwd(y.tolist(), dy.tolist(), PF[fmt], po.FORMATS["p12_2"])), "relu bwd")
+    planes, H, W = 6, 12, 10
+    for kh, kw in ((2, 2), (3, 2)):
+        xp = rand_patterns(rng, (planes, H, W), fmt, special=0.1)
+        yp, idx = pn.posit_maxpool2d_fwd(to_dev(xp), fmt, kh, kw)
+        wy, widx = po.maxpool2d_fwd(xp.flatten().tolist(), planes, H, W, kh, kw, PF[fmt])
+        _assert_equal(to_np(yp, fmt).flatten(), np.array(wy), "maxpool fwd")
+        _assert_equal(idx.cpu().numpy().flatten(), np.array(widx), "maxpool idx")
+        dyp = rand_patterns(rng, tuple(yp.shape), fmt)
+        dxp = pn.posit_maxpool2d_bwd(to_dev(dyp), idx, fmt, kh, kw)
+        _assert_equal(to_np(dxp, fmt).flatten(), np.array(po.maxpool2d_bwd(dyp.flatten().tolist(), widx, planes, H, W, kh, kw)), "maxpool bwd")
+    for fout, (kh, kw) in ((fmt, (2, 2)), ("p12_2", (2, 4)), ("p8", (2, 2))):
+        xp = rand_patterns(rng, (planes, 8, 12), fmt, special=0.05)
+        ya = pn.posit_avgpool2d_fwd(to_dev(xp), fmt, fout, kh, kw)
+        _assert_equal(to_np(ya, fout).flatten(), np.array(po.avgpool2d_fwd(xp.flatten().tolist(), planes, 8, 12, kh, kw, PF[fmt], PF[fout])), "avgpool fwd")
+        dya = rand_patterns(rng, (planes, 8 // kh, 12 // kw), fmt, special=0.05)
+        dxa = pn.posit_avgpool2d_bwd(to_dev(dya), fmt, fout, kh, kw)
+        _assert_equal(to_np(dxa, fout).flatten(), np.array(po.avgpool2d_bwd(dya.flatten().tolist(), planes, 8, 12, kh, kw, PF[fmt], PF[fout])), "avgpool bwd")

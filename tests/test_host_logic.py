@@ -11,8 +11,9 @@ from oracle import fast
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2105_00053_amd", "libpositnn_hostcheck.so")
-CODE = {"p8": 0, "p16": 1, "p32": 2, "f32": 100, "f64": 101}
-BITS = {"p8": 8, "p16": 16, "p32": 32}
+CODE = {"p8": 0, "p16": 1, "p32": 2, "f32": 100, "f64": 101, "p8_1": 3, "p8_2": 4, "p10_1": 5, "p10_2": 6, "p12_1": 7, "p12_2": 8}
+BITS = {"p8": 8, "p16": 16, "p32": 32, "p8_1": 8, "p8_2": 8, "p10_1": 10, "p10_2": 10, "p12_1": 12, "p12_2": 12}
+GENERAL = ["p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2"]
 
 
 @pytest.fixture(scope="module")
@@ -28,6 +29,8 @@ def hc():
     L.hostcheck_dot.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_dot.restype = ctypes.c_uint32
     L.hostcheck_conv_gather.argtypes = [ci, vp, ci, i64, i64, vp, vp, vp]
+    L.hostcheck_map_rt.argtypes = [ci, ci, i64, vp, vp]
+    L.hostcheck_axpy_rt.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     return L
 
 
@@ -120,6 +123,76 @@ def test_axpy_near_cancellation(hc, fx, fy):
             out = np.zeros(n, dtype=np.uint64)
             assert hc.hostcheck_axpy(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
             assert np.array_equal(out, fast.axpy(alpha, x, y, fx, fy).astype(np.uint64)), (alpha, delta)
+
+
+@pytest.mark.parametrize("fin,fout", [(f, f) for f in GENERAL] + [("p8_2", "p12_2"), ("p8_2", "p10_2"), ("p12_1", "p8"), ("p8_1", "p16"), ("p16", "p12_2")])
+def test_quire_dot_general_formats(hc, fin, fout):
+    test_quire_dot(hc, fin, fout)
+
+
+def test_general_quire_wraps_like_the_oracle(hc):
+    """posit<8,1> has a 64-bit quire that maxpos^2 = 2^48 minpos^2 leaves after 2^15 terms; the wrap is then
+    modulo 2^64 on both sides.  (The 96-bit quires would need 2^31 terms: out of any test's reach.)"""
+    fmt = "p8_1"
+    mp = (1 << (BITS[fmt] - 1)) - 1
+    a = np.full(70000, mp, dtype=np.uint32)
+    seen = 0
+    for K in (30000, 40000, 70000):
+        want, ovf = fast.gemm(a[:K].reshape(1, K), a[:K].reshape(K, 1), fmt, fmt, threads=1)
+        seen += ovf
+        assert hc.hostcheck_dot(CODE[fmt], CODE[fmt], K, _p(a), _p(a), 0, 0) == int(want[0, 0]), K
+    assert seen == 2  # the two longest runs did leave the quire range, so the wrap was exercised
+
+
+@pytest.mark.parametrize("src", GENERAL + ["p8", "p16", "f32", "f64"])
+@pytest.mark.parametrize("dst", GENERAL + ["p16", "f32"])
+def test_runtime_format_conversions(hc, src, dst):
+    rng = np.random.default_rng(len(src) * 7 + len(dst))
+    if src == "f32":
+        x = (rng.standard_normal(50000) * np.exp2(rng.uniform(-50, 50, 50000))).astype(np.float32)
+        x[:5] = [0.0, -0.0, np.inf, np.nan, 1e-45]
+        bits = x.view(np.uint32).astype(np.uint64)
+        want = fast.round_from_float(x, dst).astype(np.uint64) if dst != "f32" else None
+    elif src == "f64":
+        x = rng.standard_normal(50000) * np.exp2(rng.uniform(-200, 200, 50000))
+        bits = x.view(np.uint64).copy()
+        want = fast.round_from_float(x, dst).astype(np.uint64) if dst != "f32" else None
+    else:
+        bits = np.arange(1 << BITS[src], dtype=np.uint64)
+        want = None
+    if dst == "f32" and src in ("f32", "f64"):
+        pytest.skip("float to float is not a library operation")
+    out = np.zeros_like(bits)
+    assert hc.hostcheck_map_rt(CODE[src], CODE[dst], len(bits), _p(bits), _p(out)) == 0
+    if src in ("f32", "f64"):
+        assert np.array_equal(out, want)
+    elif dst == "f32":
+        ref = fast.to_float(bits, src, "f32")
+        got = out.astype(np.uint32).view(np.float32)
+        nan = np.isnan(ref)
+        assert np.array_equal(np.isnan(got), nan) and np.array_equal(got[~nan], ref[~nan])
+    else:
+        assert np.array_equal(out, fast.convert(bits, src, dst).astype(np.uint64))
+
+
+@pytest.mark.parametrize("fx,fy", [("p12_2", "p12_2"), ("p8_2", "p12_2"), ("p8_2", "p8_2"), ("p10_1", "p12_1"), ("p8_1", "p10_2"), ("p16", "p12_2")])
+def test_runtime_format_axpy(hc, fx, fy):
+    rng = np.random.default_rng(BITS[fx] * 11 + BITS[fy])
+    n = 50000
+    x = _patterns(rng, n, fx)
+    y = _patterns(rng, n, fy)
+    mask = (1 << BITS[fy]) - 1
+    lr = int(fast.round_from_float(np.array([-0.1], dtype=np.float32), fy)[0])
+    for alpha in (lr, 1 << (BITS[fy] - 2), 0, int(_patterns(rng, 1, fy, 0)[0])):
+        out = np.zeros(n, dtype=np.uint64)
+        assert hc.hostcheck_axpy_rt(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
+        assert np.array_equal(out, fast.axpy(alpha, x, y, fx, fy).astype(np.uint64)), alpha
+    t = fast.axpy(lr, x, np.zeros(n, dtype=np.uint64), fx, fy).astype(np.int64)
+    for delta in (0, 1, -1, 5):
+        y2 = ((-t + delta) & mask).astype(np.uint64)
+        out = np.zeros(n, dtype=np.uint64)
+        hc.hostcheck_axpy_rt(CODE[fx], CODE[fy], lr, n, _p(x), _p(y2), _p(out))
+        assert np.array_equal(out, fast.axpy(lr, x, y2, fx, fy).astype(np.uint64))
 
 
 @pytest.mark.parametrize("fin", ["p8", "p16", "p32"])

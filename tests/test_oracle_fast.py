@@ -7,7 +7,8 @@ import pytest
 from oracle import fast
 from oracle import posit_oracle as po
 
-F = {"p8": po.P8, "p16": po.P16, "p32": po.P32}
+F = dict(po.FORMATS)
+GENERAL = ["p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2"]
 
 
 def _rand_patterns(rng, shape, fmt, special=0.02):
@@ -19,21 +20,21 @@ def _rand_patterns(rng, shape, fmt, special=0.02):
     return a.astype(fast.DTYPES[fmt])
 
 
-@pytest.mark.parametrize("fmt", ["p8", "p16"])
+@pytest.mark.parametrize("fmt", ["p8", "p16"] + GENERAL)
 def test_convert_and_float_exhaustive(fmt):
     pats = np.arange(1 << F[fmt].n, dtype=np.uint32).astype(fast.DTYPES[fmt])
     f64 = fast.to_float(pats, fmt, "f64")
     f32 = fast.to_float(pats, fmt, "f32")
-    for p in range(0, 1 << F[fmt].n, 1 if fmt == "p8" else 3):
+    for p in range(0, 1 << F[fmt].n, 1 if F[fmt].n == 8 else 3):
         want = po.to_float(p, F[fmt], "f64")
         if p == F[fmt].nar:
             assert np.isnan(f64[p]) and np.isnan(f32[p])
         else:
             assert f64[p] == want and float(f32[p]) == want
     assert np.array_equal(fast.round_from_float(f64, fmt)[np.arange(len(pats)) != F[fmt].nar], pats[np.arange(len(pats)) != F[fmt].nar])
-    for dst in ("p8", "p16", "p32"):
+    for dst in ("p8", "p16", "p32", "p8_2", "p12_2", "p10_1"):
         got = fast.convert(pats, fmt, dst)
-        step = 1 if fmt == "p8" else 11
+        step = 1 if F[fmt].n == 8 else 11
         for p in range(0, 1 << F[fmt].n, step):
             assert int(got[p]) == po.convert(p, F[fmt], F[dst])
 
@@ -52,7 +53,7 @@ def test_p32_conversions_sample():
         assert int(c8[i]) == po.convert(p, po.P32, po.P8)
 
 
-@pytest.mark.parametrize("dst", ["p8", "p16", "p32"])
+@pytest.mark.parametrize("dst", ["p8", "p16", "p32"] + GENERAL)
 def test_round_from_float(dst):
     rng = np.random.default_rng(5)
     x = (rng.standard_normal(4000) * np.exp2(rng.uniform(-40, 40, 4000))).astype(np.float32)
@@ -68,7 +69,10 @@ def test_round_from_float(dst):
 
 
 @pytest.mark.parametrize("fin,fout,M,N,K", [("p8", "p8", 7, 9, 40), ("p8", "p16", 5, 6, 300), ("p16", "p16", 6, 5, 50),
-                                             ("p16", "p8", 4, 4, 33), ("p32", "p32", 4, 5, 20), ("p32", "p16", 3, 3, 9)])
+                                             ("p16", "p8", 4, 4, 33), ("p32", "p32", 4, 5, 20), ("p32", "p16", 3, 3, 9),
+                                             ("p8_2", "p8_2", 5, 4, 60), ("p8_2", "p12_2", 4, 4, 30), ("p8_1", "p8_1", 4, 5, 40),
+                                             ("p10_1", "p10_1", 4, 3, 30), ("p12_1", "p8_2", 3, 4, 25), ("p12_2", "p12_2", 3, 3, 20),
+                                             ("p10_2", "p16", 3, 3, 15)])
 def test_gemm_matches_python_oracle(fin, fout, M, N, K):
     rng = np.random.default_rng(M * 100 + K)
     A = _rand_patterns(rng, (M, K), fin)
@@ -93,7 +97,7 @@ def test_gemm_wrap_and_overflow_count():
     assert C[0, 0] == 0x7F and ovf == 0
 
 
-@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p16", "p16"), ("p32", "p32")])
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p16", "p16"), ("p32", "p32"), ("p8_2", "p8_2"), ("p8_2", "p12_2")])
 def test_conv_matches_python_oracle(fin, fout):
     rng = np.random.default_rng(F[fin].n + F[fout].n)
     for d in (dict(N=2, C=3, H=6, W=5, K=4, R=3, S=3, pad_h=1, pad_w=1),
@@ -114,7 +118,8 @@ def test_conv_matches_python_oracle(fin, fout):
         assert db.tolist() == po.conv2d_bias_grad(dy.flatten().tolist(), sh, F[fin], F[fout])
 
 
-@pytest.mark.parametrize("fx,fy,fc", [("p8", "p16", "p8"), ("p16", "p16", None), ("p8", "p8", None), ("p16", "p32", "p16"), ("p32", "p32", "p8")])
+@pytest.mark.parametrize("fx,fy,fc", [("p8", "p16", "p8"), ("p16", "p16", None), ("p8", "p8", None), ("p16", "p32", "p16"), ("p32", "p32", "p8"),
+                                      ("p12_2", "p12_2", "p8_2"), ("p8_2", "p12_2", None), ("p10_1", "p12_1", "p8_1")])
 def test_axpy_matches_python_oracle(fx, fy, fc):
     rng = np.random.default_rng(F[fx].n * 3 + F[fy].n)
     n = 1500

@@ -16,7 +16,9 @@ import pytest
 from oracle import posit_oracle as po
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "known_encodings.txt")
-FMT = {(8, 0): po.P8, (16, 1): po.P16, (32, 2): po.P32}
+FMT = {(8, 0): po.P8, (16, 1): po.P16, (32, 2): po.P32, (8, 1): po.P8_1, (8, 2): po.P8_2, (10, 1): po.P10_1,
+       (10, 2): po.P10_2, (12, 1): po.P12_1, (12, 2): po.P12_2}
+GENERAL = [po.P8_1, po.P8_2, po.P10_1, po.P10_2, po.P12_1, po.P12_2]
 
 
 def _golden_rows():
@@ -82,7 +84,7 @@ def _string_decode(p, n, es):
     return -v if sign else v
 
 
-@pytest.mark.parametrize("fmt", [po.P8, po.P16])
+@pytest.mark.parametrize("fmt", [po.P8, po.P16] + GENERAL)
 def test_decode_exhaustive_against_string_decoder(fmt):
     for p in range(1 << fmt.n):
         want = _string_decode(p, fmt.n, fmt.es)
@@ -105,7 +107,7 @@ def test_decode_p32_sample_against_string_decoder():
             assert got == Fraction(want)
 
 
-@pytest.mark.parametrize("fmt", [po.P8, po.P16])
+@pytest.mark.parametrize("fmt", [po.P8, po.P16] + GENERAL)
 def test_roundtrip_monotone_negation_exhaustive(fmt):
     n = fmt.n
     prev = None
@@ -136,13 +138,13 @@ def test_roundtrip_p32_sample():
         assert (v / po.P32.minpos).denominator == 1
 
 
-@pytest.mark.parametrize("fmt", [po.P8, po.P16])
+@pytest.mark.parametrize("fmt", [po.P8, po.P16] + GENERAL)
 def test_two_rounding_formulations_agree_at_every_midpoint(fmt):
     """R1 (bit string) == R2 (neighbour search) at all encoding midpoints and one
     quire unit either side; elsewhere nearest-in-value must also agree."""
     ulp = fmt.quire_unit
     wider = po.PositFormat(fmt.n + 1, fmt.es, 0)
-    step = 1 if fmt.n == 8 else 7
+    step = 1 if fmt.n <= 10 else 7
     for u in range(1, fmt.maxpos_pattern, step):
         lo = po.decode(u, fmt)
         hi = po.decode(u + 1, fmt)
@@ -266,3 +268,17 @@ def test_convert_widening_is_exact_and_narrowing_rounds():
         else:
             assert po.decode(q, po.P32) == v
             assert po.convert(p, po.P16, po.P8) == po.round_by_search(v, po.P8)
+
+
+def test_general_format_quire_widths_hold_many_products():
+    """Formats outside Table 1: maxpos = useed^(n-2) and the chosen quire width leaves at
+    least 2^(n-1) - 1 products of maxpos * maxpos without wrap (n-1 carry-guard bits)."""
+    for fmt in GENERAL:
+        assert po.decode(fmt.maxpos_pattern, fmt) == Fraction(fmt.useed) ** (fmt.n - 2)
+        assert po.decode(1, fmt) == 1 / Fraction(fmt.useed) ** (fmt.n - 2)
+        assert fmt.quire_bits % 32 == 0
+        biggest = (fmt.maxpos * fmt.maxpos) / fmt.quire_unit
+        limit = ((1 << (fmt.quire_bits - 1)) - 1) // biggest.numerator
+        assert limit >= 2 ** (fmt.n - 1) - 1
+        # and one limb less would not do
+        assert ((1 << (fmt.quire_bits - 33)) - 1) // biggest.numerator < 2 ** (fmt.n - 1) - 1
