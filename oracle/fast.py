@@ -23,10 +23,10 @@ def lib():
         path = _build.build(force=False)
         L = ctypes.CDLL(path)
         i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
-        L.oracle_gemm.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, i64, ci, ctypes.POINTER(i64)]
-        L.oracle_conv2d_fwd.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, vp, ci]
-        L.oracle_conv2d_bwd_data.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, ci]
-        L.oracle_conv2d_bwd_weight.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, vp, ci]
+        L.oracle_gemm.argtypes = [ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, i64, i64, ci, ctypes.POINTER(i64), ci]
+        L.oracle_conv2d_fwd.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, vp, ci, ci]
+        L.oracle_conv2d_bwd_data.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, ci, ci]
+        L.oracle_conv2d_bwd_weight.argtypes = [ci, ci, ctypes.POINTER(i64), vp, vp, vp, vp, ci, ci]
         L.oracle_round_f32.argtypes = [ci, i64, vp, vp]
         L.oracle_round_f64.argtypes = [ci, i64, vp, vp]
         L.oracle_convert.argtypes = [ci, ci, i64, vp, vp]
@@ -50,8 +50,11 @@ def _arr(a, fmt):
     return a
 
 
-def gemm(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, rows=None, threads=None):
-    """Returns C (and the number of outputs whose exact sum left the quire range)."""
+def gemm(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, rows=None, threads=None, noquire=False):
+    """Returns C (and the number of outputs whose exact sum left the quire range).
+
+    noquire (here and in the convolutions): no quire; every product and partial sum is rounded to fin, terms in
+    order of the reduction index, bias last (Sec. 3.3: the quire is an option; Table 2)."""
     A, B = _arr(A, fin), _arr(B, fin)
     M, K = (A.shape[1], A.shape[0]) if trans_a else A.shape
     N = B.shape[0] if trans_b else B.shape[1]
@@ -61,7 +64,7 @@ def gemm(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, rows=None, th
     lo, hi = (0, M) if rows is None else rows
     ovf = ctypes.c_int64(0)
     rc = lib().oracle_gemm(CODES[fin], CODES[fout], int(trans_a), int(trans_b), M, N, K, _ptr(A), A.shape[1],
-                           _ptr(B), B.shape[1], _ptr(bias), _ptr(C), N, lo, hi, threads or hw_threads(), ctypes.byref(ovf))
+                           _ptr(B), B.shape[1], _ptr(bias), _ptr(C), N, lo, hi, threads or hw_threads(), ctypes.byref(ovf), int(noquire))
     assert rc == 0
     return C, ovf.value
 
@@ -78,29 +81,29 @@ def out_hw(d):
     return oh, ow
 
 
-def conv2d_fwd(x, w, d, fin, fout, bias=None, threads=None):
+def conv2d_fwd(x, w, d, fin, fout, bias=None, threads=None, noquire=False):
     x, w = _arr(x, fin), _arr(w, fin)
     bias = None if bias is None else _arr(bias, fin)
     oh, ow = out_hw(d)
     y = np.zeros((d["N"], d["K"], oh, ow), dtype=DTYPES[fout])
-    rc = lib().oracle_conv2d_fwd(CODES[fin], CODES[fout], _desc(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), threads or hw_threads())
+    rc = lib().oracle_conv2d_fwd(CODES[fin], CODES[fout], _desc(d), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), threads or hw_threads(), int(noquire))
     assert rc == 0
     return y
 
 
-def conv2d_bwd_data(dy, w, d, fin, fout, threads=None):
+def conv2d_bwd_data(dy, w, d, fin, fout, threads=None, noquire=False):
     dy, w = _arr(dy, fin), _arr(w, fin)
     dx = np.zeros((d["N"], d["C"], d["H"], d["W"]), dtype=DTYPES[fout])
-    rc = lib().oracle_conv2d_bwd_data(CODES[fin], CODES[fout], _desc(d), _ptr(dy), _ptr(w), _ptr(dx), threads or hw_threads())
+    rc = lib().oracle_conv2d_bwd_data(CODES[fin], CODES[fout], _desc(d), _ptr(dy), _ptr(w), _ptr(dx), threads or hw_threads(), int(noquire))
     assert rc == 0
     return dx
 
 
-def conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=False, threads=None):
+def conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=False, threads=None, noquire=False):
     dy, x = _arr(dy, fin), _arr(x, fin)
     dw = np.zeros((d["K"], d["C"], d["R"], d["S"]), dtype=DTYPES[fout])
     db = np.zeros((d["K"],), dtype=DTYPES[fout]) if with_bias else None
-    rc = lib().oracle_conv2d_bwd_weight(CODES[fin], CODES[fout], _desc(d), _ptr(dy), _ptr(x), _ptr(dw), _ptr(db), threads or hw_threads())
+    rc = lib().oracle_conv2d_bwd_weight(CODES[fin], CODES[fout], _desc(d), _ptr(dy), _ptr(x), _ptr(dw), _ptr(db), threads or hw_threads(), int(noquire))
     assert rc == 0
     return (dw, db) if with_bias else dw
 

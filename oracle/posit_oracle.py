@@ -22,6 +22,11 @@ What each function follows
 * ``quire_*`` / ``gemm``: Sec. 2 (quire = exact sum of products) and Sec. 3.3
                           (quire accumulation in matrix products and
                           convolutions, one rounding at the end).
+* ``mul`` / ``add`` / ``*_noquire``: Sec. 3.3 makes the quire an option and
+                          Table 2 reports training "without quire": every
+                          product and every running sum is then a posit, rounded
+                          as it is produced, terms taken in order of the
+                          reduction index.
 * ``conv2d_*``          : Sec. 3.1 (layers inherit LibTorch semantics:
                           cross-correlation, NCHW / OIHW, zero padding) and its
                           two adjoints, which the framework writes by hand
@@ -46,7 +51,10 @@ dot-product limits, brute-force rational sums, integer matmul and float64
 library convolutions for posit<8,0>).  The choices "bias inside the quire",
 "one quire over the whole batch reduction" and "single rounding in the SGD
 update" cannot be pinned to the paper's own framework: parity unpinned for
-those three readings (the definition here is the contract).
+those three readings (the definition here is the contract).  The same holds
+for the order of the terms and the position of the bias (last) in the
+``*_noquire`` functions: parity unpinned against the paper's framework; their
+arithmetic (``mul``, ``add``) is pinned exhaustively for posit<8,0>.
 """
 
 from fractions import Fraction
@@ -496,6 +504,136 @@ def conv2d_bwd_weight(dy, x, sh, fin, fout):
 
 def conv2d_bias_grad(dy, sh, fin, fout):
     return _round_quires(conv2d_bias_grad_quire(dy, sh, fin), fin, fout)
+
+
+# --------------------------------------------------------------------------
+# accumulation without the quire (Sec. 3.3: the quire is an option; Table 2)
+# --------------------------------------------------------------------------
+
+def mul(pa, pb, fmt):
+    """posit x posit -> posit: the exact product rounded once."""
+    va, vb = _value(pa, fmt), _value(pb, fmt)
+    if va is NaR or vb is NaR:
+        return fmt.nar
+    return round_to_posit(va * vb, fmt)
+
+
+def add(pa, pb, fmt):
+    """posit + posit -> posit: the exact sum rounded once."""
+    va, vb = _value(pa, fmt), _value(pb, fmt)
+    if va is NaR or vb is NaR:
+        return fmt.nar
+    return round_to_posit(va + vb, fmt)
+
+
+def dot_noquire(a, b, fin, fout, bias=None):
+    """s_0 = 0, s_k = add(s_{k-1}, mul(a_k, b_k)) for k in order, then the bias, all in fin;
+    the final posit is converted to fout."""
+    acc = 0
+    for pa, pb in zip(a, b):
+        acc = add(acc, mul(pa, pb, fin), fin)
+    if bias is not None:
+        acc = add(acc, bias, fin)
+    return convert(acc, fin, fout) if acc != fin.nar else fout.nar
+
+
+def gemm_noquire(A, B, fin, fout, trans_a=False, trans_b=False, bias=None):
+    """As ``gemm`` with every dot product taken by ``dot_noquire`` (k ascending)."""
+    if trans_a:
+        A = [list(r) for r in zip(*A)] if A and A[0] else []
+    Bt = B if trans_b else ([list(r) for r in zip(*B)] if B and len(B[0]) else [])
+    return [[dot_noquire(A[i], Bt[j], fin, fout, None if bias is None else bias[j]) for j in range(len(Bt))]
+            for i in range(len(A))]
+
+
+def conv2d_fwd_terms(x, w, sh):
+    """For every output (n,k,oh,ow) in NCHW order: the two operand sequences of its dot product, terms
+    ordered by (c,r,s) as in the unfolded matrix; a padded position is the pattern 0."""
+    out = []
+    for n in range(sh.N):
+        for k in range(sh.K):
+            for oh in range(sh.OH):
+                for ow in range(sh.OW):
+                    a, b = [], []
+                    for c in range(sh.C):
+                        for r in range(sh.R):
+                            ih = oh * sh.stride_h + r - sh.pad_h
+                            for s in range(sh.S):
+                                iw = ow * sh.stride_w + s - sh.pad_w
+                                inside = 0 <= ih < sh.H and 0 <= iw < sh.W
+                                a.append(x[((n * sh.C + c) * sh.H + ih) * sh.W + iw] if inside else 0)
+                                b.append(w[((k * sh.C + c) * sh.R + r) * sh.S + s])
+                    out.append((a, b))
+    return out
+
+
+def conv2d_bwd_data_terms(dy, w, sh):
+    """For every dx[n,c,h,w]: operand sequences ordered by (k,r,s); a tap with no output position is 0."""
+    out = []
+    for n in range(sh.N):
+        for c in range(sh.C):
+            for h in range(sh.H):
+                for ww in range(sh.W):
+                    a, b = [], []
+                    for k in range(sh.K):
+                        for r in range(sh.R):
+                            t = h + sh.pad_h - r
+                            for s in range(sh.S):
+                                u = ww + sh.pad_w - s
+                                ok = (t >= 0 and t % sh.stride_h == 0 and t // sh.stride_h < sh.OH and
+                                      u >= 0 and u % sh.stride_w == 0 and u // sh.stride_w < sh.OW)
+                                a.append(dy[((n * sh.K + k) * sh.OH + t // sh.stride_h) * sh.OW + u // sh.stride_w] if ok else 0)
+                                b.append(w[((k * sh.C + c) * sh.R + r) * sh.S + s])
+                    out.append((a, b))
+    return out
+
+
+def conv2d_bwd_weight_terms(dy, x, sh):
+    """For every dw[k,c,r,s]: operand sequences ordered by (n,oh,ow)."""
+    out = []
+    for k in range(sh.K):
+        for c in range(sh.C):
+            for r in range(sh.R):
+                for s in range(sh.S):
+                    a, b = [], []
+                    for n in range(sh.N):
+                        for oh in range(sh.OH):
+                            ih = oh * sh.stride_h + r - sh.pad_h
+                            for ow in range(sh.OW):
+                                iw = ow * sh.stride_w + s - sh.pad_w
+                                inside = 0 <= ih < sh.H and 0 <= iw < sh.W
+                                a.append(dy[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow])
+                                b.append(x[((n * sh.C + c) * sh.H + ih) * sh.W + iw] if inside else 0)
+                    out.append((a, b))
+    return out
+
+
+def conv2d_bias_grad_terms(dy, sh, fin):
+    """For every dbias[k]: dy[n,k,:,:] ordered by (n,oh,ow), each against the value one."""
+    one = 1 << (fin.n - 2)
+    out = []
+    for k in range(sh.K):
+        a = [dy[(n * sh.K + k) * sh.OH * sh.OW + i] for n in range(sh.N) for i in range(sh.OH * sh.OW)]
+        out.append((a, [one] * len(a)))
+    return out
+
+
+def conv2d_fwd_noquire(x, w, sh, fin, fout, bias=None):
+    terms = conv2d_fwd_terms(x, w, sh)
+    per_k = sh.OH * sh.OW
+    return [dot_noquire(a, b, fin, fout, None if bias is None else bias[(i // per_k) % sh.K]) for i, (a, b) in enumerate(terms)]
+
+
+def conv2d_bwd_data_noquire(dy, w, sh, fin, fout):
+    return [dot_noquire(a, b, fin, fout) for a, b in conv2d_bwd_data_terms(dy, w, sh)]
+
+
+def conv2d_bwd_weight_noquire(dy, x, sh, fin, fout):
+    return [dot_noquire(a, b, fin, fout) for a, b in conv2d_bwd_weight_terms(dy, x, sh)]
+
+
+def conv2d_bias_grad_noquire(dy, sh, fin, fout):
+    return [dot_noquire(a, b, fin, fout) for a, b in conv2d_bias_grad_terms(dy, sh, fin)]
 
 
 # --------------------------------------------------------------------------

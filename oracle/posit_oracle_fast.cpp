@@ -14,7 +14,9 @@
 // Fig. 2; worker threads split the rows of the left operand = Sec. 3.3.
 // Readings where the paper is silent are those of the Python oracle (modular
 // quire, NaR absorbing, bias inside the quire, truncated exponent bits are 0,
-// padding and partner-less convolution taps are zero operands).
+// padding and partner-less convolution taps are zero operands; with the quire
+// switched off, Sec. 3.3 / Table 2, every product and running sum is rounded,
+// terms in order of the reduction index, bias last).
 //
 // Pins: agreement with the Python oracle on every entry point (tests), which is
 // itself pinned to the definition.  Not tuned: no blocking, no SIMD, no tables.
@@ -203,17 +205,68 @@ void store(void* p, int64_t i, uint32_t v, const Format& f) {
 }
 uint32_t nar_of(const Format& f) { return 1u << (f.n - 1); }
 
-void mac(Big& q, bool& nar, const Decoded& a, const Decoded& b) {
-    if (a.nar || b.nar) { nar = true; return; }
-    if (a.zero || b.zero) return;
-    q.add_shifted(a.sig * b.sig, a.sh + b.sh, a.neg != b.neg);
+// Posit Standard arithmetic on patterns, used when the quire is switched off (Sec. 3.3 makes it an
+// option; Table 2 trains without it): the exact product / sum rounded once.
+uint32_t mul_posit(const Decoded& a, const Decoded& b, const Format& f) {
+    if (a.nar || b.nar) return nar_of(f);
+    if (a.zero || b.zero) return 0;
+    Big prod;  // a.sig * b.sig by shift-and-add over the bits of b.sig
+    for (int i = 0; i < 64; ++i)
+        if ((b.sig >> i) & 1) prod.add_shifted(a.sig, i, false);
+    return round_big(a.neg != b.neg, prod, a.sh + b.sh - 2 * f.max_scale(), f);
 }
 
-void add_times_one(Big& q, bool& nar, const Decoded& a, const Format& f) {
-    if (a.nar) { nar = true; return; }
-    if (a.zero) return;
-    q.add_shifted(a.sig, a.sh + f.max_scale(), a.neg);  // the value one is 2^max_scale minpos
+uint32_t add_posit(uint32_t x, uint32_t y, const Format& f) {
+    const Decoded a = decode(x, f), b = decode(y, f);
+    if (a.nar || b.nar) return nar_of(f);
+    Big t;  // in units of minpos
+    if (!a.zero) t.add_shifted(a.sig, a.sh, a.neg);
+    if (!b.zero) t.add_shifted(b.sig, b.sh, b.neg);
+    const bool neg = t.negative();
+    if (neg) t.negate();
+    return round_big(neg, t, -f.max_scale(), f);
 }
+
+uint32_t convert_posit(uint32_t x, const Format& fs, const Format& fd) {
+    const Decoded d = decode(x, fs);
+    if (d.nar) return nar_of(fd);
+    if (d.zero) return 0;
+    Big m;
+    m.w[0] = d.sig;
+    return round_big(d.neg, m, d.sh - fs.max_scale(), fd);
+}
+
+// One output's accumulation.  With the quire: an exact sum in units of minpos^2, rounded once by
+// result().  Without it: a running posit of format fin, every product and every sum rounded as it
+// is formed, terms in the order they are offered.
+struct Accum {
+    const Format& f;
+    const bool noquire;
+    Big q;
+    bool nar = false;
+    uint32_t run = 0;
+    Accum(const Format& fin, int noquire_) : f(fin), noquire(noquire_ != 0) {}
+    void mac(const Decoded& a, const Decoded& b) {
+        if (noquire) { run = add_posit(run, mul_posit(a, b, f), f); return; }
+        if (a.nar || b.nar) { nar = true; return; }
+        if (a.zero || b.zero) return;
+        q.add_shifted(a.sig * b.sig, a.sh + b.sh, a.neg != b.neg);
+    }
+    void add_one_times(const Decoded& a) {  // + a * 1
+        Decoded one;
+        one.sig = 1;
+        one.sh = f.max_scale();  // the value one is 2^max_scale minpos
+        if (noquire) { run = add_posit(run, mul_posit(a, one, f), f); return; }
+        if (a.nar) { nar = true; return; }
+        if (a.zero) return;
+        q.add_shifted(a.sig, a.sh + f.max_scale(), a.neg);
+    }
+    bool overflowed() const { return !noquire && !nar && !q.fits(f.qbits); }
+    uint32_t result(const Format& fout) const {
+        if (noquire) return convert_posit(run, f, fout);
+        return nar ? nar_of(fout) : round_quire(q, f, fout);
+    }
+};
 
 // Worker threads split [0, rows) into contiguous chunks.
 void parallel_rows(int64_t rows, int nthreads, const std::function<void(int64_t, int64_t)>& fn) {
@@ -254,9 +307,11 @@ int oracle_hw_threads() {
 // C[M,N] = round_fout( op(A)[M,K] * op(B)[K,N] (+ bias[N]) ); row-major, ld in elements.
 // Only rows [row_lo, row_hi) of C are computed (for sampled checks and timing).
 // overflowed (nullable) receives the number of outputs whose exact sum left the quire range.
+// noquire != 0 (here and in the convolutions): no quire, every product and partial sum is rounded
+// to fin as it is formed, k ascending, bias last; the final posit is converted to fout.
 int oracle_gemm(int fin_c, int fout_c, int transA, int transB, int64_t M, int64_t N, int64_t K,
                 const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias,
-                void* C, int64_t ldc, int64_t row_lo, int64_t row_hi, int nthreads, int64_t* overflowed) {
+                void* C, int64_t ldc, int64_t row_lo, int64_t row_hi, int nthreads, int64_t* overflowed, int noquire) {
     Format fin, fout;
     if (!format_of(fin_c, &fin) || !format_of(fout_c, &fout)) return 1;
     if (row_lo < 0) row_lo = 0;
@@ -275,12 +330,11 @@ int oracle_gemm(int fin_c, int fout_c, int transA, int transB, int64_t M, int64_
         for (int64_t i = row_lo + lo; i < row_lo + hi; ++i) {
             for (int64_t k = 0; k < K; ++k) arow[(size_t)k] = decode(load(A, transA ? k * lda + i : i * lda + k, fin), fin);
             for (int64_t j = 0; j < N; ++j) {
-                Big q;
-                bool nar = false;
-                for (int64_t k = 0; k < K; ++k) mac(q, nar, arow[(size_t)k], Bd[(size_t)(j * K + k)]);
-                if (bias) add_times_one(q, nar, biasd[(size_t)j], fin);
-                if (!nar && !q.fits(fin.qbits)) ++local;
-                store(C, i * ldc + j, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);
+                Accum acc(fin, noquire);
+                for (int64_t k = 0; k < K; ++k) acc.mac(arow[(size_t)k], Bd[(size_t)(j * K + k)]);
+                if (bias) acc.add_one_times(biasd[(size_t)j]);
+                if (acc.overflowed()) ++local;
+                store(C, i * ldc + j, acc.result(fout), fout);
             }
         }
         __atomic_fetch_add(&total_ovf, local, __ATOMIC_RELAXED);
@@ -291,7 +345,7 @@ int oracle_gemm(int fin_c, int fout_c, int transA, int transB, int64_t M, int64_
 
 // y[n,k,oh,ow] = round( sum_{c,r,s} x[n,c,oh*sh+r-ph,ow*sw+s-pw] * w[k,c,r,s] (+ bias[k]) ), NCHW / OIHW
 int oracle_conv2d_fwd(int fin_c, int fout_c, const int64_t* d, const void* x, const void* w, const void* bias,
-                      void* y, int nthreads) {
+                      void* y, int nthreads, int noquire) {
     Format fin, fout;
     if (!format_of(fin_c, &fin) || !format_of(fout_c, &fout)) return 1;
     Conv c{d[0], d[1], d[2], d[3], d[4], d[5], d[6], d[7], d[8], d[9], d[10], 0, 0};
@@ -306,8 +360,7 @@ int oracle_conv2d_fwd(int fin_c, int fout_c, const int64_t* d, const void* x, co
             const int64_t n = nk / c.K, k = nk % c.K;
             for (int64_t oh = 0; oh < c.OH; ++oh)
                 for (int64_t ow = 0; ow < c.OW; ++ow) {
-                    Big q;
-                    bool nar = false;
+                    Accum acc(fin, noquire);
                     for (int64_t ci = 0; ci < c.C; ++ci)
                         for (int64_t r = 0; r < c.R; ++r) {
                             const int64_t ih = oh * c.sh + r - c.ph;
@@ -315,12 +368,12 @@ int oracle_conv2d_fwd(int fin_c, int fout_c, const int64_t* d, const void* x, co
                                 const int64_t iw = ow * c.sw + s - c.pw;
                                 const bool inside = ih >= 0 && ih < c.H && iw >= 0 && iw < c.W;
                                 // a padded position holds zero and is an operand like any other
-                                mac(q, nar, inside ? xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)] : zero,
+                                acc.mac(inside ? xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)] : zero,
                                     wd[(size_t)(((k * c.C + ci) * c.R + r) * c.S + s)]);
                             }
                         }
-                    if (bias) add_times_one(q, nar, bd[(size_t)k], fin);
-                    store(y, ((n * c.K + k) * c.OH + oh) * c.OW + ow, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);
+                    if (bias) acc.add_one_times(bd[(size_t)k]);
+                    store(y, ((n * c.K + k) * c.OH + oh) * c.OW + ow, acc.result(fout), fout);
                 }
         }
     });
@@ -328,7 +381,7 @@ int oracle_conv2d_fwd(int fin_c, int fout_c, const int64_t* d, const void* x, co
 }
 
 // dx[n,c,h,w] = round( sum over (k,r,s) and the (oh,ow) that read x[n,c,h,w] of dy[n,k,oh,ow] * w[k,c,r,s] )
-int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* dy, const void* w, void* dx, int nthreads) {
+int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* dy, const void* w, void* dx, int nthreads, int noquire) {
     Format fin, fout;
     if (!format_of(fin_c, &fin) || !format_of(fout_c, &fout)) return 1;
     Conv c{d[0], d[1], d[2], d[3], d[4], d[5], d[6], d[7], d[8], d[9], d[10], 0, 0};
@@ -341,8 +394,7 @@ int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* 
             const int64_t n = nc / c.C, ci = nc % c.C;
             for (int64_t h = 0; h < c.H; ++h)
                 for (int64_t ww = 0; ww < c.W; ++ww) {
-                    Big q;
-                    bool nar = false;
+                    Accum acc(fin, noquire);
                     for (int64_t k = 0; k < c.K; ++k)
                         for (int64_t r = 0; r < c.R; ++r) {
                             const int64_t t = h + c.ph - r;
@@ -351,11 +403,11 @@ int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* 
                                 const int64_t u = ww + c.pw - s;
                                 const bool ok = row_ok && u >= 0 && u % c.sw == 0 && u / c.sw < c.OW;
                                 // a tap with no output position behind it is a zero operand
-                                mac(q, nar, ok ? dyd[(size_t)(((n * c.K + k) * c.OH + t / c.sh) * c.OW + u / c.sw)] : zero,
+                                acc.mac(ok ? dyd[(size_t)(((n * c.K + k) * c.OH + t / c.sh) * c.OW + u / c.sw)] : zero,
                                     wd[(size_t)(((k * c.C + ci) * c.R + r) * c.S + s)]);
                             }
                         }
-                    store(dx, ((n * c.C + ci) * c.H + h) * c.W + ww, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);
+                    store(dx, ((n * c.C + ci) * c.H + h) * c.W + ww, acc.result(fout), fout);
                 }
         }
     });
@@ -364,7 +416,7 @@ int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* 
 
 // dw[k,c,r,s] = round( sum_{n,oh,ow} dy[n,k,oh,ow] * x[n,c,oh*sh+r-ph,ow*sw+s-pw] ); dbias[k] = round( sum dy[n,k,:,:] )
 int oracle_conv2d_bwd_weight(int fin_c, int fout_c, const int64_t* d, const void* dy, const void* x, void* dw,
-                             void* dbias, int nthreads) {
+                             void* dbias, int nthreads, int noquire) {
     Format fin, fout;
     if (!format_of(fin_c, &fin) || !format_of(fout_c, &fout)) return 1;
     Conv c{d[0], d[1], d[2], d[3], d[4], d[5], d[6], d[7], d[8], d[9], d[10], 0, 0};
@@ -377,30 +429,28 @@ int oracle_conv2d_bwd_weight(int fin_c, int fout_c, const int64_t* d, const void
             const int64_t k = kc / c.C, ci = kc % c.C;
             for (int64_t r = 0; r < c.R; ++r)
                 for (int64_t s = 0; s < c.S; ++s) {
-                    Big q;
-                    bool nar = false;
+                    Accum acc(fin, noquire);
                     for (int64_t n = 0; n < c.N; ++n)
                         for (int64_t oh = 0; oh < c.OH; ++oh) {
                             const int64_t ih = oh * c.sh + r - c.ph;
                             for (int64_t ow = 0; ow < c.OW; ++ow) {
                                 const int64_t iw = ow * c.sw + s - c.pw;
                                 const bool inside = ih >= 0 && ih < c.H && iw >= 0 && iw < c.W;
-                                mac(q, nar, dyd[(size_t)(((n * c.K + k) * c.OH + oh) * c.OW + ow)],
+                                acc.mac(dyd[(size_t)(((n * c.K + k) * c.OH + oh) * c.OW + ow)],
                                     inside ? xd[(size_t)(((n * c.C + ci) * c.H + ih) * c.W + iw)] : zero);
                             }
                         }
-                    store(dw, ((k * c.C + ci) * c.R + r) * c.S + s, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);
+                    store(dw, ((k * c.C + ci) * c.R + r) * c.S + s, acc.result(fout), fout);
                 }
         }
     });
     if (dbias) {
         for (int64_t k = 0; k < c.K; ++k) {
-            Big q;
-            bool nar = false;
+            Accum acc(fin, noquire);
             for (int64_t n = 0; n < c.N; ++n)
                 for (int64_t i = 0; i < c.OH * c.OW; ++i)
-                    add_times_one(q, nar, dyd[(size_t)((n * c.K + k) * c.OH * c.OW + i)], fin);
-            store(dbias, k, nar ? nar_of(fout) : round_quire(q, fin, fout), fout);
+                    acc.add_one_times(dyd[(size_t)((n * c.K + k) * c.OH * c.OW + i)]);
+            store(dbias, k, acc.result(fout), fout);
         }
     }
     return 0;
