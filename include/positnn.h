@@ -121,6 +121,28 @@ int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_de
 /* which: 0 = fwd, 1 = bwd_data, 2 = bwd_weight.  Bytes of workspace (0 = none). */
 size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
 
+/* The same four operations with the quire switched off (Sec. 3.3: the quire is an
+ * option of the framework; Table 2 reports training "without quire").  Each output
+ * is the chain  s_0 = 0,  s_t = round_fin( s_{t-1} + round_fin( a_t * b_t ) )  over
+ * the terms t of its dot product in ascending order of the reduction index
+ * (posit_gemm: k; fwd: (c,r,s); bwd_data: (k,r,s); bwd_weight and dbias: (n,oh,ow);
+ * the last index fastest), then  s = round_fin( s + bias )  when a bias is given,
+ * and the result stored is round_fout(s).  Padded positions and taps without a
+ * partner are zero operands as above; NaR is absorbing.  Arguments, layouts and
+ * status codes are those of the quire entry points; no workspace is needed (the
+ * order-dependent reduction is never split).  The result in general differs from
+ * the quire result; it is deterministic and independent of the launch shape. */
+int posit_gemm_noquire(void* stream, int fin, int fout, int transA, int transB,
+                       int64_t M, int64_t N, int64_t K,
+                       const void* A, int64_t lda, const void* B, int64_t ldb,
+                       const void* bias, void* C, int64_t ldc);
+int posit_conv2d_fwd_noquire(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                             const void* x, const void* w, const void* bias, void* y);
+int posit_conv2d_bwd_data_noquire(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                                  const void* dy, const void* w, void* dx);
+int posit_conv2d_bwd_weight_noquire(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
+                                    const void* dy, const void* x, void* dw, void* dbias);
+
 /* Float tensor -> posit tensor (Fig. 2, tensor conversion): dst[i] = round_dst(src[i]),
  * src_float in {PNN_F32, PNN_F64}.  NaN and +-Inf give NaR, -0.0 gives 0,
  * nonzero values never round to zero (they clamp to +-minpos / +-maxpos). */

@@ -63,9 +63,14 @@ def load():
     L.posit_maxpool2d_bwd.argtypes = [vp, ci, i64, i64, i64, i64, i64, vp, vp, vp]
     L.posit_avgpool2d_fwd.argtypes = [vp, ci, ci, i64, i64, i64, i64, i64, vp, vp]
     L.posit_avgpool2d_bwd.argtypes = [vp, ci, ci, i64, i64, i64, i64, i64, vp, vp]
+    L.posit_gemm_noquire.argtypes = [vp, ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64]
+    L.posit_conv2d_fwd_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
+    L.posit_conv2d_bwd_data_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp]
+    L.posit_conv2d_bwd_weight_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
     L.posit_status_string.argtypes = [ci]
     L.posit_status_string.restype = ctypes.c_char_p
     for name in ("posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight", "posit_round", "posit_convert", "posit_axpy",
+                 "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
                  "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"):
         getattr(L, name).restype = ci
     _lib = L
@@ -178,6 +183,55 @@ def posit_conv2d_bwd_weight(dy, x, desc, fin, fout, with_bias=False, out=None, o
     wp, wbytes, _keep = _workspace(posit_conv2d_workspace(2, fin, fout, desc), dy.device, workspace)
     _check(load().posit_conv2d_bwd_weight(_stream(), fin, fout, ctypes.byref(desc), _dev(dy, fin, "dy"), _dev(x, fin, "x"),
                                           _dev(out, fout, "dw"), _dev(out_bias, fout, "dbias") if with_bias else None, wp, wbytes))
+    return (out, out_bias) if with_bias else out
+
+
+def posit_gemm_noquire(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, out=None):
+    """As posit_gemm with the quire switched off: every product and running sum rounded to fin, k ascending, bias last."""
+    fin, fout = _code(fin), _code(fout)
+    if A.dim() != 2 or B.dim() != 2:
+        raise PositError("A and B must be 2-D")
+    M, K = (A.shape[1], A.shape[0]) if trans_a else (A.shape[0], A.shape[1])
+    N, Kb = (B.shape[0], B.shape[1]) if trans_b else (B.shape[1], B.shape[0])
+    if K != Kb:
+        raise PositError("inner dimensions differ: %d vs %d" % (K, Kb))
+    if bias is not None and bias.numel() != N:
+        raise PositError("bias must have N elements")
+    if out is None:
+        out = torch.empty((M, N), dtype=TORCH_DTYPE[fout], device=A.device)
+    _check(load().posit_gemm_noquire(_stream(), fin, fout, int(trans_a), int(trans_b), M, N, K,
+                                     _dev(A, fin, "A"), A.shape[1], _dev(B, fin, "B"), B.shape[1], _dev(bias, fin, "bias"),
+                                     _dev(out, fout, "out"), out.shape[1]))
+    return out
+
+
+def posit_conv2d_fwd_noquire(x, w, desc, fin, fout, bias=None, out=None):
+    fin, fout = _code(fin), _code(fout)
+    oh, ow = conv_out_hw(desc)
+    if out is None:
+        out = torch.empty((desc.N, desc.K, oh, ow), dtype=TORCH_DTYPE[fout], device=x.device)
+    _check(load().posit_conv2d_fwd_noquire(_stream(), fin, fout, ctypes.byref(desc), _dev(x, fin, "x"), _dev(w, fin, "w"),
+                                           _dev(bias, fin, "bias"), _dev(out, fout, "y")))
+    return out
+
+
+def posit_conv2d_bwd_data_noquire(dy, w, desc, fin, fout, out=None):
+    fin, fout = _code(fin), _code(fout)
+    if out is None:
+        out = torch.empty((desc.N, desc.C, desc.H, desc.W), dtype=TORCH_DTYPE[fout], device=dy.device)
+    _check(load().posit_conv2d_bwd_data_noquire(_stream(), fin, fout, ctypes.byref(desc), _dev(dy, fin, "dy"), _dev(w, fin, "w"),
+                                                _dev(out, fout, "dx")))
+    return out
+
+
+def posit_conv2d_bwd_weight_noquire(dy, x, desc, fin, fout, with_bias=False, out=None, out_bias=None):
+    fin, fout = _code(fin), _code(fout)
+    if out is None:
+        out = torch.empty((desc.K, desc.C, desc.R, desc.S), dtype=TORCH_DTYPE[fout], device=dy.device)
+    if with_bias and out_bias is None:
+        out_bias = torch.empty((desc.K,), dtype=TORCH_DTYPE[fout], device=dy.device)
+    _check(load().posit_conv2d_bwd_weight_noquire(_stream(), fin, fout, ctypes.byref(desc), _dev(dy, fin, "dy"), _dev(x, fin, "x"),
+                                                  _dev(out, fout, "dw"), _dev(out_bias, fout, "dbias") if with_bias else None))
     return (out, out_bias) if with_bias else out
 
 

@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void avgpool_fwd_kernel(const typename Storage
             if (v == FIN::NAR) nar = true;
             AR::mac(q, AR::stage(v), wq);
         }
-    round_store<FIN, AR::L>(q, nar, fout, y, o);
+    round_store<QuireAccum<FIN>, AR::L>(q, nar, fout, y, o);
 }
 
 template <class FIN>
@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void avgpool_bwd_kernel(const typename Storage
 #pragma unroll
     for (int l = 0; l < AR::L; ++l) q[l] = 0;
     AR::mac(q, AR::stage(v), AR::stage(weight));
-    round_store<FIN, AR::L>(q, v == FIN::NAR, fout, dx, i);
+    round_store<QuireAccum<FIN>, AR::L>(q, v == FIN::NAR, fout, dx, i);
 }
 
 inline unsigned blocks_for(int64_t n) { return (unsigned)((n + 255) / 256); }

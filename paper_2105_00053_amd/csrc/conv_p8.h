@@ -265,7 +265,7 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
                     ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire(q));
                 } else {
                     const uint32_t q1[1] = {(uint32_t)q};
-                    round_store<P8, 1>(q1, nar, fout, C, at);
+                    round_store<QuireAccum<P8>, 1>(q1, nar, fout, C, at);
                 }
             } else {
                 // partial quire; the merge kernel sees an (Mw x Nw) row-major problem

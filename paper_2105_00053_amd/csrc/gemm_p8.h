@@ -285,7 +285,7 @@ __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
                     for (int j = 0; j < 4; ++j) {
                         if (n + j >= N) continue;
                         const uint32_t q1[1] = {res[j]};
-                        round_store<P8, 1>(q1, narv[j], fout, C, (int64_t)m * ldc + n + j);
+                        round_store<QuireAccum<P8>, 1>(q1, narv[j], fout, C, (int64_t)m * ldc + n + j);
                     }
                 }
             }

@@ -4,6 +4,7 @@
 #include "elementwise_ops.h"
 #include "quire_arith.h"
 #include "conv_p8.h"
+#include "noquire_arith.h"
 
 using namespace pnn;
 
@@ -52,9 +53,58 @@ uint32_t dot_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int
     if (nar) return fo.nar();
     return quire_read<F, AR::L>(q, r) ? encode_rt(r, fo) : 0u;
 }
+
+// the same dot product with the quire switched off, through the kernel's accumulator policy
+template <class F>
+uint32_t dot_noquire_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    typedef NoQuire<F> AR;
+    uint32_t q[1] = {0};
+    bool nar = false;
+    for (int64_t i = 0; i < n; ++i) {
+        if (a[i] == F::NAR || b[i] == F::NAR) nar = true;
+        AR::mac(q, AR::stage(a[i]), AR::stage(b[i]));
+    }
+    if (has_bias) {
+        if (bias == F::NAR) nar = true;
+        else AR::add_value(q, AR::stage(bias));
+    }
+    const FmtRT fo = fmt_of_code(fout);
+    Real r;
+    if (nar) return fo.nar();
+    return AR::read(q, r) ? encode_rt(r, fo) : 0u;
+}
 }  // namespace
 
 extern "C" {
+
+uint32_t hostcheck_dot_noquire(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    switch (fin) {
+        case 0: return dot_noquire_host<P8>(fout, n, a, b, has_bias, bias);
+        case 1: return dot_noquire_host<P16>(fout, n, a, b, has_bias, bias);
+        case 2: return dot_noquire_host<P32>(fout, n, a, b, has_bias, bias);
+        case 3: return dot_noquire_host<P8_1>(fout, n, a, b, has_bias, bias);
+        case 4: return dot_noquire_host<P8_2>(fout, n, a, b, has_bias, bias);
+        case 5: return dot_noquire_host<P10_1>(fout, n, a, b, has_bias, bias);
+        case 6: return dot_noquire_host<P10_2>(fout, n, a, b, has_bias, bias);
+        case 7: return dot_noquire_host<P12_1>(fout, n, a, b, has_bias, bias);
+        default: return dot_noquire_host<P12_2>(fout, n, a, b, has_bias, bias);
+    }
+}
+
+// posit (x) posit -> posit, rounded once: op 0 = multiply, 1 = add; any patterns
+uint32_t hostcheck_posit_op(int fmt, int op, uint32_t a, uint32_t b) {
+    switch (fmt) {
+        case 0: return op ? posit_add<P8>(a, b) : posit_mul<P8>(a, b);
+        case 1: return op ? posit_add<P16>(a, b) : posit_mul<P16>(a, b);
+        case 2: return op ? posit_add<P32>(a, b) : posit_mul<P32>(a, b);
+        case 3: return op ? posit_add<P8_1>(a, b) : posit_mul<P8_1>(a, b);
+        case 4: return op ? posit_add<P8_2>(a, b) : posit_mul<P8_2>(a, b);
+        case 5: return op ? posit_add<P10_1>(a, b) : posit_mul<P10_1>(a, b);
+        case 6: return op ? posit_add<P10_2>(a, b) : posit_mul<P10_2>(a, b);
+        case 7: return op ? posit_add<P12_1>(a, b) : posit_mul<P12_1>(a, b);
+        default: return op ? posit_add<P12_2>(a, b) : posit_mul<P12_2>(a, b);
+    }
+}
 
 int hostcheck_round(int src_float, int dst, int64_t n, const uint64_t* in, uint64_t* out) {
     if (src_float == 100) {

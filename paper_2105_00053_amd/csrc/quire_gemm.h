@@ -172,25 +172,32 @@ struct SplitWs {
 constexpr int GEMM_THREADS = 256;
 constexpr int GEMM_KT = 16;
 
-// Round an L-limb quire of format FIN to the output format chosen at run time (format
+// Accumulator policy "quire": Arith<F> plus the read-out of the limbs as a real number.
+// SPLITTABLE: partial accumulators of slices of the reduction can be merged exactly.
+template <class F>
+struct QuireAccum : Arith<F> {
+    static constexpr bool SPLITTABLE = true;
+    PNN_HD static bool read(const uint32_t (&q)[Arith<F>::L], Real& r) { return quire_read<F, Arith<F>::L>(q, r); }
+};
+
+// Round an accumulator of policy AR to the output format chosen at run time (format
 // code of the C ABI) and store it in that format's container.
-template <class FIN, int L>
+template <class AR, int L>
 __device__ __forceinline__ void round_store(const uint32_t (&q)[L], bool nar, int fout, void* C, int64_t at) {
     const FmtRT fo = fmt_of_code(fout);
     Real r;
-    const bool nonzero = quire_read<FIN, L>(q, r);
+    const bool nonzero = AR::read(q, r);
     const uint32_t res = nar ? fo.nar() : (nonzero ? encode_rt(r, fo) : 0u);
     if (fo.n <= 8) ((uint8_t*)C)[at] = (uint8_t)res;
     else if (fo.n <= 16) ((uint16_t*)C)[at] = (uint16_t)res;
     else ((uint32_t*)C)[at] = res;
 }
 
-template <class FIN, class OpA, class OpB, class Out, int TM, int TN>
+template <class FIN, class OpA, class OpB, class Out, int TM, int TN, class AR>
 __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
     OpA opa, OpB opb, Out out, int64_t M, int64_t N, int64_t K, int64_t k_per_split,
     const typename Storage<FIN::N>::T* __restrict__ bias, void* __restrict__ C, int fout,
     SplitWs ws, int tiles_n) {
-    typedef Arith<FIN> AR;
     typedef typename AR::Elem Elem;
     constexpr int L = AR::L;
     constexpr int BM = 16 * TM, BN = 16 * TN, KT = GEMM_KT;
@@ -268,7 +275,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
                     if (bp == FIN::NAR) nar = true;
                     else AR::add_value(acc[i][j], AR::stage(bp));
                 }
-                round_store<FIN, L>(acc[i][j], nar, fout, C, out(m, n));
+                round_store<AR, L>(acc[i][j], nar, fout, C, out(m, n));
             }
         }
     } else {
@@ -357,7 +364,7 @@ __global__ __launch_bounds__(256) void split_merge_kernel(SplitWs ws, int splits
         if (bp == FIN::NAR) isnar = true;
         else AR::add_value(q, AR::stage(bp));
     }
-    round_store<FIN, L>(q, isnar, fout, C, out(m, n));
+    round_store<QuireAccum<FIN>, L>(q, isnar, fout, C, out(m, n));
 }
 
 // ---- host side ----
@@ -408,12 +415,13 @@ inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int 
     return p;
 }
 
-template <class FIN, class OpA, class OpB, class Out, int TM, int TN>
+template <class FIN, class OpA, class OpB, class Out, int TM, int TN, class AR = QuireAccum<FIN>>
 hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb, const Out& out,
                              int64_t M, int64_t N, int64_t K, const void* bias, void* C, int fout,
                              void* workspace, const GemmPlan& plan) {
     typedef typename Storage<FIN::N>::T TI;
-    constexpr int BM = 16 * TM, BN = 16 * TN, L = Arith<FIN>::L;
+    constexpr int BM = 16 * TM, BN = 16 * TN, L = AR::L;
+    if (plan.splits > 1 && !AR::SPLITTABLE) return hipErrorInvalidValue;  // order-dependent accumulation cannot be split
     const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     SplitWs ws;
     ws.limbs = nullptr;
@@ -427,7 +435,7 @@ hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb,
         hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
-    hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN>), grid, dim3(GEMM_THREADS), 0, stream,
+    hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN, AR>), grid, dim3(GEMM_THREADS), 0, stream,
                        opa, opb, out, M, N, K, plan.k_per_split, (const TI*)bias, C, fout, ws, (int)tiles_n);
     if (plan.splits > 1) launch_split_merge<FIN, Out>(stream, ws, plan.splits, M, N, bias, C, fout, out);
     return hipGetLastError();

@@ -29,7 +29,8 @@ def test_header_declares_the_expected_entry_points():
     assert _declared() == sorted([
         "posit_gemm", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
         "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string",
-        "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"])
+        "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd",
+        "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire"])
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -56,6 +57,10 @@ def test_argument_validation_without_launch():
     assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4, null, 0) == EINVAL      # lda < K
     assert L.posit_gemm(null, 0, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 2, null, 0) == EINVAL      # ldc < N
     assert L.posit_gemm(null, 0, 0, 0, 0, 0, 4, 4, null, 4, null, 4, null, null, 4, null, 0) == 0           # empty: ok, nothing touched
+    assert L.posit_gemm_noquire(null, 57, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4) == EINVAL
+    assert L.posit_gemm_noquire(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4) == EINVAL  # lda < K
+    assert L.posit_gemm_noquire(null, 0, 0, 0, 0, 0, 4, 4, null, 4, null, 4, null, null, 4) == 0
+    assert L.posit_conv2d_fwd_noquire(null, 0, 0, None, fake, fake, null, fake) == EINVAL
     assert L.posit_round(null, 0, 0, 4, fake, fake) == EINVAL      # source must be a float type
     assert L.posit_round(null, 100, 100, 4, fake, fake) == EINVAL  # destination must be a posit
     assert L.posit_round(null, 100, 0, 0, null, null) == 0

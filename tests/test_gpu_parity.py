@@ -435,3 +435,67 @@ def test_general_formats_glue(fmt):
         dya = rand_patterns(rng, (planes, 8 // kh, 12 // kw), fmt, special=0.05)
         dxa = pn.posit_avgpool2d_bwd(to_dev(dya), fmt, fout, kh, kw)
         _assert_equal(to_np(dxa, fout).flatten(), np.array(po.avgpool2d_bwd(dya.flatten().tolist(), planes, 8, 12, kh, kw, PF[fmt], PF[fout])), "avgpool bwd")
+
+
+# ---------------- accumulation without the quire (Sec. 3.3 option; Table 2) ----------------
+
+NOQUIRE_GEMM_CASES = [
+    ("p8", "p8", 70, 130, 100, 0, 0, 1, 1),
+    ("p8", "p16", 33, 40, 257, 1, 1, 1, 0),
+    ("p16", "p16", 65, 63, 129, 1, 0, 1, 1),
+    ("p16", "p8", 40, 35, 300, 0, 1, 0, 0),
+    ("p32", "p32", 33, 31, 70, 0, 0, 1, 1),
+    ("p8_2", "p8_2", 64, 64, 200, 0, 0, 1, 1),
+    ("p8_2", "p12_2", 30, 70, 150, 0, 1, 0, 0),
+    ("p10_1", "p10_1", 50, 20, 96, 0, 0, 1, 0),
+    ("p12_1", "p12_1", 20, 50, 96, 1, 0, 0, 1),
+    ("p12_2", "p8_2", 35, 33, 64, 0, 0, 1, 0),
+    ("p8_1", "p8_1", 1, 1, 1, 0, 0, 0, 0),
+    ("p10_2", "p16", 17, 5, 31, 1, 1, 0, 0),
+]
+
+
+@pytest.mark.parametrize("fin,fout,M,N,K,ta,tb,use_bias,nar", NOQUIRE_GEMM_CASES)
+def test_noquire_gemm(fin, fout, M, N, K, ta, tb, use_bias, nar):
+    rng = np.random.default_rng(M * 5 + N * 3 + K)
+    A = rand_patterns(rng, (K, M) if ta else (M, K), fin, allow_nar=bool(nar), special=0.01)
+    B = rand_patterns(rng, (N, K) if tb else (K, N), fin, allow_nar=bool(nar), special=0.01)
+    bias = rand_patterns(rng, (N,), fin, allow_nar=bool(nar)) if use_bias else None
+    got = pn.posit_gemm_noquire(to_dev(A), to_dev(B), fin, fout, trans_a=ta, trans_b=tb, bias=None if bias is None else to_dev(bias))
+    want, _ = fast.gemm(A, B, fin, fout, trans_a=ta, trans_b=tb, bias=bias, noquire=True)
+    _assert_equal(to_np(got, fout), want, "noquire gemm %s->%s %dx%dx%d" % (fin, fout, M, N, K))
+
+
+def test_noquire_gemm_small_values_long_reduction_differs_from_quire():
+    """Weights-times-activations-like data, K = 2048: the mode must follow the oracle term by term over a long
+    chain (never split), and it does differ from the quire result."""
+    A32, B32 = workloads.gemm_operands(2, 2048, sigma=0.1, extremes=False)
+    A = fast.round_from_float(A32[:96], "p16")
+    B = fast.round_from_float(B32[:, :80], "p16")
+    got = to_np(pn.posit_gemm_noquire(to_dev(A), to_dev(B), "p16", "p16"), "p16")
+    want, _ = fast.gemm(A, B, "p16", "p16", noquire=True)
+    _assert_equal(got, want, "noquire gemm K=2048")
+    quire, _ = fast.gemm(A, B, "p16", "p16")
+    assert (quire != want).any()
+    assert pn.posit_gemm_workspace("p16", "p16", False, False, 96, 80, 2048) > 0  # the quire path would split this reduction
+
+
+@pytest.mark.parametrize("ci", [0, 1, 2, 3])
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p16", "p16"), ("p8_2", "p12_2"), ("p10_1", "p8_1"), ("p32", "p32")])
+def test_noquire_conv_all_three_passes(ci, fin, fout):
+    d = CONV_CASES[ci]
+    rng = np.random.default_rng(ci * 10 + BITS[fin] + 1)
+    oh, ow = fast.out_hw(d)
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), fin, special=0.005)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), fin, special=0.005)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), fin, special=0.005)
+    bias = rand_patterns(rng, (d["K"],), fin, allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd_noquire(to_dev(x), to_dev(w), desc, fin, fout, bias=to_dev(bias))
+    _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, fin, fout, bias=bias, noquire=True), "noquire conv fwd")
+    dx = pn.posit_conv2d_bwd_data_noquire(to_dev(dy), to_dev(w), desc, fin, fout)
+    _assert_equal(to_np(dx, fout), fast.conv2d_bwd_data(dy, w, d, fin, fout, noquire=True), "noquire conv bwd_data")
+    dw, db = pn.posit_conv2d_bwd_weight_noquire(to_dev(dy), to_dev(x), desc, fin, fout, with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True, noquire=True)
+    _assert_equal(to_np(dw, fout), wdw, "noquire conv bwd_weight")
+    _assert_equal(to_np(db, fout), wdb, "noquire conv dbias")

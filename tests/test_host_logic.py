@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 from oracle import fast
+from oracle import posit_oracle as po
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 LIB = os.path.join(ROOT, "paper_2105_00053_amd", "libpositnn_hostcheck.so")
@@ -29,6 +30,10 @@ def hc():
     L.hostcheck_dot.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_dot.restype = ctypes.c_uint32
     L.hostcheck_conv_gather.argtypes = [ci, vp, ci, i64, i64, vp, vp, vp]
+    L.hostcheck_dot_noquire.restype = ctypes.c_uint32
+    L.hostcheck_dot_noquire.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
+    L.hostcheck_posit_op.restype = ctypes.c_uint32
+    L.hostcheck_posit_op.argtypes = [ci, ci, ctypes.c_uint32, ctypes.c_uint32]
     L.hostcheck_map_rt.argtypes = [ci, ci, i64, vp, vp]
     L.hostcheck_axpy_rt.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     return L
@@ -296,3 +301,49 @@ def test_conv_gather_descriptors_match_direct_indexing(hc):
                 assert ok and off == ((ko * C + c) * R + r) * S + s
                 _, _, _, oidx = query(1, 0, m, c)
                 assert oidx == ((n * C + c) * H + h) * W + w
+
+
+# ---------------- accumulation without the quire ----------------
+
+@pytest.mark.parametrize("fmt", ["p8", "p8_1", "p8_2"])
+def test_rounded_mul_add_exhaustive_8bit(hc, fmt):
+    """All 65536 pairs of an 8-bit format, both operations, against the Python oracle's mul / add."""
+    f = po.FORMATS[fmt]
+    for op, ref in ((0, po.mul), (1, po.add)):
+        for a in range(256):
+            for b in range(256):
+                assert hc.hostcheck_posit_op(CODE[fmt], op, a, b) == ref(a, b, f), (op, a, b)
+
+
+@pytest.mark.parametrize("fmt", ["p16", "p32", "p10_1", "p10_2", "p12_1", "p12_2"])
+def test_rounded_mul_add_sampled(hc, fmt):
+    f = po.FORMATS[fmt]
+    rng = np.random.default_rng(BITS[fmt])
+    n = 3000
+    a = _patterns(rng, n, fmt)
+    b = _patterns(rng, n, fmt)
+    # near-cancellation and neighbouring magnitudes, where the alignment window is exercised
+    b[: n // 3] = ((-a[: n // 3].astype(np.int64) + rng.integers(-3, 4, n // 3)) & f.mask).astype(np.uint64)
+    for x, y in zip(a.tolist(), b.tolist()):
+        assert hc.hostcheck_posit_op(CODE[fmt], 0, x, y) == po.mul(x, y, f), (x, y)
+        assert hc.hostcheck_posit_op(CODE[fmt], 1, x, y) == po.add(x, y, f), (x, y)
+
+
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p16", "p16"), ("p16", "p8"), ("p32", "p32"), ("p8_2", "p12_2"), ("p10_1", "p10_1"),
+                                      ("p12_2", "p8_2"), ("p8_1", "p8_1"), ("p12_1", "p16"), ("p10_2", "p10_2")])
+def test_noquire_dot_matches_oracle(hc, fin, fout):
+    rng = np.random.default_rng(BITS[fin] + 5 * BITS[fout])
+    for K in (1, 2, 17, 300):
+        for trial in range(6):
+            a = _patterns(rng, K, fin, special=0.03).astype(np.uint32)
+            b = _patterns(rng, K, fin, special=0.03).astype(np.uint32)
+            bias = int(_patterns(rng, 1, fin)[0])
+            want, _ = fast.gemm(a.reshape(1, K), b.reshape(K, 1), fin, fout, bias=np.array([bias]), noquire=True, threads=1)
+            got = hc.hostcheck_dot_noquire(CODE[fin], CODE[fout], K, _p(a), _p(b), 1, bias)
+            assert got == int(want[0, 0]), (K, trial)
+    # the worked example of the oracle's pin: 1 + forty times 1/64 sticks at 1 in posit<8,0>
+    if fin == "p8" and fout == "p8":
+        a = np.array([0x40] + [0x01] * 40, dtype=np.uint32)
+        b = np.full(41, 0x40, dtype=np.uint32)
+        assert hc.hostcheck_dot_noquire(0, 0, 41, _p(a), _p(b), 0, 0) == 0x40
+        assert hc.hostcheck_dot(0, 0, 41, _p(a), _p(b), 0, 0) == 0x54
