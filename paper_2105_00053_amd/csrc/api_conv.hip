@@ -60,12 +60,6 @@ GemmPlan conv_plan(const ConvDims& d) {
     return plan_split(d.M, d.N, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
 }
 
-// bias-gradient row sum: M = K channels, one column, same reduction as bwd_weight
-template <class F>
-GemmPlan dbias_plan(const ConvDims& d) {
-    return plan_split(d.M, 1, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
-}
-
 template <class F>
 size_t conv_ws(int which, const ConvGeom& g) {
     const ConvDims d = conv_dims(which, g);
@@ -74,10 +68,6 @@ size_t conv_ws(int which, const ConvGeom& g) {
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(which, g)) {
         const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
         b = p8_conv_plan(p.M, p.N, p.K).ws_bytes;
-    }
-    if (which == 2) {
-        const size_t b2 = dbias_plan<F>(d).ws_bytes;
-        if (b2 > b) b = b2;
     }
     return b;
 }
@@ -135,9 +125,7 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
         p8p = p8_problem(2, g, dy, x);
         plan = p8_conv_plan(p8p.M, p8p.N, p8p.K);
     }
-    const GemmPlan bplan = dbias_plan<F>(d);
-    const size_t need = (dbias && bplan.ws_bytes > plan.ws_bytes) ? bplan.ws_bytes : plan.ws_bytes;
-    if (need > 0 && (!ws || ws_bytes < need)) return PNN_EWORKSPACE;
+    if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
     ConvBwdWeightDy<T> a{(const T*)dy, g, d.M, d.K};
     ConvBwdWeightX<T> b{(const T*)x, g, d.N, d.K};
     RowMajorOut out{d.N};
@@ -147,14 +135,8 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     else
         e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
             st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
-    if (e == hipSuccess && dbias) {
-        // dbias[k] = sum dy[n,k,:,:] * 1 : the same kernel against a column of ones
-        // (stream order keeps the shared workspace safe)
-        OnesOperand ones{1u << (F::N - 2), 1, d.K};
-        RowMajorOut bout{1};
-        e = launch_quire_gemm<F, decltype(a), OnesOperand, RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
-            st, a, ones, bout, d.M, 1, d.K, nullptr, dbias, fout, ws, bplan);
-    }
+    // dbias[k] = sum dy[n,k,:,:] * 1 : one quire per channel
+    if (e == hipSuccess && dbias) e = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW);
     return hip_status(e);
 }
 

@@ -367,6 +367,78 @@ __global__ __launch_bounds__(256) void split_merge_kernel(SplitWs ws, int splits
     round_store<QuireAccum<FIN>, L>(q, isnar, fout, C, out(m, n));
 }
 
+// Bias gradient of a convolution (the row sum of the backward-weight pass against a column of
+// ones): dbias[k] = round_fout( sum_{n,i} dy[n][k][i] * 1 ), one quire per channel.  One
+// workgroup per channel; every thread adds 16-byte runs of the channel's planes into a private
+// quire, the 256 private quires are merged pairwise through LDS (exact: integer addition), and
+// thread 0 rounds once.
+template <class FIN>
+__global__ __launch_bounds__(256) void bias_grad_kernel(const typename Storage<FIN::N>::T* __restrict__ dy, void* __restrict__ dbias,
+                                                        int fout, int batch, int channels, int spatial, int vec) {
+    typedef Arith<FIN> AR;
+    typedef typename Storage<FIN::N>::T T;
+    constexpr int L = AR::L;
+    constexpr int V = 16 / (int)sizeof(T);
+    __shared__ uint32_t part[128][L];
+    __shared__ uint32_t nar_s;
+    const int k = blockIdx.x, t = threadIdx.x;
+    uint32_t q[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) q[l] = 0;
+    bool nar = false;
+    if (t == 0) nar_s = 0;
+    if (vec) {  // spatial is a multiple of V and the tensor is 16-byte aligned
+        const int per_plane = spatial / V;
+        const int chunks = batch * per_plane;
+        for (int c = t; c < chunks; c += 256) {
+            const int n = c / per_plane, i = (c - n * per_plane) * V;
+            const uint4 w = *reinterpret_cast<const uint4*>(dy + ((int64_t)n * channels + k) * spatial + i);
+            const uint32_t words[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int e = 0; e < V; ++e) {
+                const uint32_t v = (words[e * (int)sizeof(T) / 4] >> (8 * ((e * (int)sizeof(T)) & 3))) & (uint32_t)(T)~(T)0;
+                if (v == FIN::NAR) nar = true;
+                else AR::add_value(q, AR::stage(v));
+            }
+        }
+    } else {
+        const int total = batch * spatial;
+        for (int e = t; e < total; e += 256) {
+            const int n = e / spatial, i = e - n * spatial;
+            const uint32_t v = dy[((int64_t)n * channels + k) * spatial + i];
+            if (v == FIN::NAR) nar = true;
+            else AR::add_value(q, AR::stage(v));
+        }
+    }
+    __syncthreads();
+    if (nar) nar_s = 1;  // benign race: every writer stores the same value
+    for (int half = 128; half >= 1; half >>= 1) {
+        if (t >= half && t < 2 * half) {
+#pragma unroll
+            for (int l = 0; l < L; ++l) part[t - half][l] = q[l];
+        }
+        __syncthreads();
+        if (t < half) {
+            uint32_t o[L];
+#pragma unroll
+            for (int l = 0; l < L; ++l) o[l] = part[t][l];
+            quire_merge<L>(q, o);
+        }
+        __syncthreads();
+    }
+    if (t == 0) round_store<QuireAccum<FIN>, L>(q, nar_s != 0, fout, dbias, k);
+}
+
+template <class FIN>
+hipError_t launch_bias_grad(hipStream_t stream, const void* dy, void* dbias, int fout, int batch, int channels, int spatial) {
+    typedef typename Storage<FIN::N>::T T;
+    constexpr int V = 16 / (int)sizeof(T);
+    const int vec = (spatial % V == 0) && (((uintptr_t)dy) % 16 == 0);
+    hipLaunchKernelGGL(bias_grad_kernel<FIN>, dim3((unsigned)channels), dim3(256), 0, stream, (const T*)dy, dbias, fout, batch, channels,
+                       spatial, vec);
+    return hipGetLastError();
+}
+
 // ---- host side ----
 
 template <class FIN, class Out>
