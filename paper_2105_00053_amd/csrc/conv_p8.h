@@ -61,10 +61,19 @@ struct AffineIndex {
     }
 };
 
+// How the staging code may fetch an operand.  GENERIC: one byte at a time, each with its own
+// address and bounds test.  ROW_RUN: the 8 rows of an aligned group sit at 8 consecutive bytes
+// (same y, x advancing by xstep = 0 or 1), as for the image operand of the forward and
+// backward-data passes at unit stride.  K_RUN: the same along the reduction index, as for
+// weights, k-contiguous matrices and both operands of the backward-weight pass at unit stride.
+// A run is fetched as aligned 32-bit words and trimmed to the positions inside the bounds.
+enum P8GatherMode { P8_GENERIC = 0, P8_ROW_RUN = 1, P8_K_RUN = 2 };
+
 struct P8Gather {
     const uint8_t* base;
     int rows, K;     // extents of the virtual matrix
     int LY, LX;      // bounds for y and x
+    int mode, xstep; // P8GatherMode; x advance along a run
     AffineIndex row, k;
 };
 
@@ -82,29 +91,93 @@ struct P8ConvOut {
     }
 };
 
-// One operand slice: BR rows x 32 k.  Work item w handles k-pair w / (BR/8) and rows 8*(w % (BR/8)) .. +7.
+// Positions [jlo, jhi) of an 8-long run that lie inside the bounds: the run's first element has
+// coordinates (y, xs), x advances by xstep, at most jmax positions exist.
+__device__ __forceinline__ void p8_run_window(int y, int xs, int xstep, int jmax, int LY, int LX, int& jlo, int& jhi) {
+    const bool yok = (uint32_t)y < (uint32_t)LY;
+    if (xstep) {
+        jlo = xs < 0 ? -xs : 0;
+        jhi = LX - xs < jmax ? LX - xs : jmax;
+    } else {
+        jlo = 0;
+        jhi = ((uint32_t)xs < (uint32_t)LX) ? jmax : 0;
+    }
+    if (!yok) jhi = 0;
+    if (jhi <= jlo) { jlo = 0; jhi = 0; }
+}
+
+// The 8 bytes at byte offset `off` of `base` (4-byte aligned), positions outside [jlo, jhi) zeroed.
+// Only aligned 32-bit words that hold a wanted byte are read (the others are re-pointed at the
+// first wanted word, or at the start of the tensor when nothing is wanted), so no access leaves
+// the words the tensor itself occupies.
+__device__ __forceinline__ void p8_load_run8(const uint8_t* __restrict__ base, int off, int jlo, int jhi, uint32_t& lo, uint32_t& hi) {
+    const bool any = jlo < jhi;
+    const int wfirst = any ? ((off + jlo) & ~3) : 0, wlast = any ? ((off + jhi - 1) & ~3) : -4;
+    const int a4 = off & ~3;
+    uint32_t d[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int wa = a4 + 4 * i;
+        const bool need = wa >= wfirst && wa <= wlast;
+        const uint32_t v = *reinterpret_cast<const uint32_t*>(base + (need ? wa : wfirst));
+        d[i] = need ? v : 0u;
+    }
+    const uint32_t sh = (uint32_t)off & 3u;
+    const uint32_t l = __builtin_amdgcn_alignbyte(d[1], d[0], sh);  // bytes off .. off+3
+    const uint32_t h = __builtin_amdgcn_alignbyte(d[2], d[1], sh);  // bytes off+4 .. off+7
+    const uint64_t keep = any ? ((~0ull >> (8 * (8 - jhi))) & (~0ull << (8 * jlo))) : 0ull;
+    lo = l & (uint32_t)keep;
+    hi = h & (uint32_t)(keep >> 32);
+}
+
+// One operand slice: BR rows x 32 k, 16 bytes per work item.  GENERIC and ROW_RUN: item w handles
+// k-pair w / (BR/8) and rows 8*(w % (BR/8)) .. +7 (frag words 2h, 2h+1 = the 8 rows at k-half h).
+// K_RUN: item w handles row w % BR and the 16 k starting at 16*(w / BR) (frag words in k order).
+// `tshift` rotates the thread-to-item map so that a short operand does not share threads with
+// the other operand's items.
 template <int BR>
 struct P8GatherStage {
     static constexpr int GROUPS = BR / 8;
-    static constexpr int ITEMS = GROUPS * P8_KP;
+    static constexpr int ITEMS = GROUPS * P8_KP;  // = 2 * BR
     static constexpr int PER_THREAD = (ITEMS + 255) / 256;
 
-    // fetch the 16 bytes of every work item of this thread
-    __device__ __forceinline__ static void fetch(const P8Gather& op, const int4* __restrict__ rinfo, int k0, int kend, int t,
-                                                 P8Frag (&f)[PER_THREAD]) {
+    // fetch the 16 bytes of every work item of this thread; kinfo = (part, y, x) of the slice's 32 k
+    __device__ __forceinline__ static void fetch(const P8Gather& op, const int4* __restrict__ rinfo, const int4* __restrict__ kinfo,
+                                                 int k0, int kend, int rows_in_tile, int t, P8Frag (&f)[PER_THREAD]) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int w = t + 256 * i;
             f[i].w[0] = f[i].w[1] = f[i].w[2] = f[i].w[3] = 0;
             if (ITEMS % 256 != 0 && w >= ITEMS) continue;
-            const int kp = w / GROUPS, g = w % GROUPS;
-            int kpart[2], ky[2], kx[2];
+            if (op.mode == P8_K_RUN) {
+                const int row = w % BR, kq = w / BR;
+                const int4 ri = rinfo[row];
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int k = k0 + 2 * kp + h;
-                op.k.eval((uint32_t)(k < kend ? k : 0), kpart[h], ky[h], kx[h]);
-                if (k >= kend) ky[h] = OUT_OF_RANGE;
+                for (int h = 0; h < 2; ++h) {
+                    const int kl = 16 * kq + 8 * h;
+                    const int4 ki = kinfo[kl];
+                    const int left = kend - (k0 + kl);
+                    int jlo, jhi;
+                    p8_run_window(ri.y + ki.y, ri.z + ki.z, op.xstep, left < 8 ? left : 8, op.LY, op.LX, jlo, jhi);
+                    p8_load_run8(op.base, ri.x + ki.x, jlo, jhi, f[i].w[2 * h], f[i].w[2 * h + 1]);
+                }
+                continue;
             }
+            const int kp = w / GROUPS, g = w % GROUPS;
+            if (op.mode == P8_ROW_RUN) {
+                const int4 ri = rinfo[g * 8];
+                const int left = rows_in_tile - g * 8;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int4 ki = kinfo[2 * kp + h];
+                    int jlo, jhi;
+                    p8_run_window(ri.y + ki.y, ri.z + ki.z, op.xstep, left < 8 ? left : 8, op.LY, op.LX, jlo, jhi);
+                    p8_load_run8(op.base, ri.x + ki.x, jlo, jhi, f[i].w[2 * h], f[i].w[2 * h + 1]);
+                }
+                continue;
+            }
+            const int4 k0i = kinfo[2 * kp], k1i = kinfo[2 * kp + 1];
+            const int kpart[2] = {k0i.x, k1i.x}, ky[2] = {k0i.y, k1i.y}, kx[2] = {k0i.z, k1i.z};
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const int4 ri = rinfo[g * 8 + j];  // part, y, x
@@ -121,11 +194,22 @@ struct P8GatherStage {
     // decode + pack + store into dst[k-pair][row]; flags[row] for NaR
     template <int LD>
     __device__ __forceinline__ static void stage(const P8Frag (&f)[PER_THREAD], uint32_t (*dst)[LD], const uint16_t* tab,
-                                                 uint32_t* flags, int t) {
+                                                 uint32_t* flags, int t, int mode) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int w = t + 256 * i;
             if (ITEMS % 256 != 0 && w >= ITEMS) continue;
+            const uint32_t nar = nar_bytes(f[i].w[0]) | nar_bytes(f[i].w[1]) | nar_bytes(f[i].w[2]) | nar_bytes(f[i].w[3]);
+            if (mode == P8_K_RUN) {
+                const int row = w % BR, kq = w / BR;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {  // bytes 2j, 2j+1 of the 16 are k-pair 8*kq + j
+                    const uint32_t word = f[i].w[j >> 1] >> (16 * (j & 1));
+                    dst[8 * kq + j][row] = (uint32_t)tab[word & 0xFFu] | ((uint32_t)tab[(word >> 8) & 0xFFu] << 16);
+                }
+                if (nar) flags[row] = 1;
+                continue;
+            }
             const int kp = w / GROUPS, c = (w % GROUPS) * 8;
             uint32_t d[8];
 #pragma unroll
@@ -136,7 +220,6 @@ struct P8GatherStage {
             }
             *reinterpret_cast<uint4*>(&dst[kp][c]) = make_uint4(d[0], d[1], d[2], d[3]);
             *reinterpret_cast<uint4*>(&dst[kp][c + 4]) = make_uint4(d[4], d[5], d[6], d[7]);
-            const uint32_t nar = nar_bytes(f[i].w[0]) | nar_bytes(f[i].w[1]) | nar_bytes(f[i].w[2]) | nar_bytes(f[i].w[3]);
             if (nar) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -148,6 +231,14 @@ struct P8GatherStage {
         }
     }
 };
+
+// (part, y, x) of the 32 reduction indices of the slice starting at k0; beyond kend: never in bounds
+__device__ __forceinline__ void p8_fill_kinfo(const P8Gather& op, int4* kinfo, int k0, int kend, int lane) {
+    const int k = k0 + lane;
+    int4 ki = make_int4(0, OUT_OF_RANGE, 0, 0);
+    if (k < kend) op.k.eval((uint32_t)k, ki.x, ki.y, ki.z);
+    kinfo[lane] = ki;
+}
 
 // TY x TX threads (= 256), register tile TM x TN, workgroup tile BM = TY*TM by BN = TX*TN.
 // `bias` (nullable) is indexed by output column n.  With gridDim.z > 1 partial quires go to the workspace.
@@ -163,6 +254,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
     __shared__ __attribute__((aligned(16))) uint32_t Bs[2][P8_KP][BN];
     __shared__ int4 rinfoA[BM];
     __shared__ int4 rinfoB[BN];
+    __shared__ int4 kinfoA[2][P8_KT];  // slice kt uses kinfo[kt & 1], filled two iterations ahead
+    __shared__ int4 kinfoB[2][P8_KT];
     __shared__ uint16_t tab[256];
     __shared__ uint32_t rowNaR[BM];
     __shared__ uint32_t colNaR[BN];
@@ -195,14 +288,22 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
         for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
+    // B's work items start on the threads that A's leave idle when A has fewer items than threads
+    const int tb = (SA::ITEMS < 256) ? ((t + 128) & 255) : t;
+    if (t < P8_KT) p8_fill_kinfo(A, kinfoA[0], kbeg, kend, t);
+    else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[0], kbeg, kend, t - P8_KT);
     __syncthreads();
     {
         P8Frag fa[SA::PER_THREAD], fb[SB::PER_THREAD];
         if (nkt > 0) {
-            SA::fetch(A, rinfoA, kbeg, kend, t, fa);
-            SB::fetch(B, rinfoB, kbeg, kend, t, fb);
-            SA::template stage<BM>(fa, As[0], tab, rowNaR, t);
-            SB::template stage<BN>(fb, Bs[0], tab, colNaR, t);
+            SA::fetch(A, rinfoA, kinfoA[0], kbeg, kend, M - m0, t, fa);
+            SB::fetch(B, rinfoB, kinfoB[0], kbeg, kend, N - n0, tb, fb);
+            if (nkt > 1) {
+                if (t < P8_KT) p8_fill_kinfo(A, kinfoA[1], kbeg + P8_KT, kend, t);
+                else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[1], kbeg + P8_KT, kend, t - P8_KT);
+            }
+            SA::template stage<BM>(fa, As[0], tab, rowNaR, t, A.mode);
+            SB::template stage<BN>(fb, Bs[0], tab, colNaR, tb, B.mode);
         }
     }
     __syncthreads();
@@ -213,8 +314,13 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
         P8Frag fa[SA::PER_THREAD], fb[SB::PER_THREAD];
         if (more) {
             const int k0 = kbeg + (kt + 1) * P8_KT;
-            SA::fetch(A, rinfoA, k0, kend, t, fa);
-            SB::fetch(B, rinfoB, k0, kend, t, fb);
+            SA::fetch(A, rinfoA, kinfoA[cur ^ 1], k0, kend, M - m0, t, fa);
+            SB::fetch(B, rinfoB, kinfoB[cur ^ 1], k0, kend, N - n0, tb, fb);
+        }
+        if (kt + 2 < nkt) {  // kinfo[cur] was last read when slice kt was fetched, one barrier ago
+            const int k2 = kbeg + (kt + 2) * P8_KT;
+            if (t < P8_KT) p8_fill_kinfo(A, kinfoA[cur], k2, kend, t);
+            else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[cur], k2, kend, t - P8_KT);
         }
 #pragma unroll 2
         for (int kp = 0; kp < P8_KP; ++kp) {
@@ -235,8 +341,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
                 for (int j = 0; j < TN; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
         }
         if (more) {
-            SA::template stage<BM>(fa, As[cur ^ 1], tab, rowNaR, t);
-            SB::template stage<BN>(fb, Bs[cur ^ 1], tab, colNaR, t);
+            SA::template stage<BM>(fa, As[cur ^ 1], tab, rowNaR, t, A.mode);
+            SB::template stage<BN>(fb, Bs[cur ^ 1], tab, colNaR, tb, B.mode);
         }
         __syncthreads();
     }
@@ -299,6 +405,26 @@ inline AffineIndex affine(uint32_t d1, uint32_t d0, int p2, int p1, int p0, int 
     return a;
 }
 
+// x advance (0 or 1) when every aligned group of 8 consecutive indices maps to 8 consecutive bytes
+// at one y; -1 when the index does not run through memory that way.
+inline int affine_run_step(const AffineIndex& a) {
+    if (a.d0.d % 8 == 0) return (a.part0 == 1 && a.y0 == 0 && (a.x0 == 0 || a.x0 == 1)) ? a.x0 : -1;
+    if (a.d0.d != 1) return -1;
+    if (a.d1d0.d % 8 == 0) return (a.part1 == 1 && a.y1 == 0 && (a.x1 == 0 || a.x1 == 1)) ? a.x1 : -1;
+    if (a.d1d0.d == 1) return a.part2 == 1 ? 0 : -1;  // single index: y and x do not depend on it
+    return -1;
+}
+
+// Choose the cheapest fetch the operand's layout allows (word loads need a 4-byte aligned tensor).
+inline void p8_pick_mode(P8Gather& op) {
+    op.mode = P8_GENERIC;
+    op.xstep = 0;
+    if (((uintptr_t)op.base & 3u) != 0) return;
+    const int ks = affine_run_step(op.k), rs = affine_run_step(op.row);
+    if (ks >= 0) { op.mode = P8_K_RUN; op.xstep = ks; }
+    else if (rs >= 0) { op.mode = P8_ROW_RUN; op.xstep = rs; }
+}
+
 struct P8ConvProblem {
     P8Gather A, B;
     P8ConvOut out;
@@ -346,6 +472,8 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
     }
     p.Mw = p.transposed ? p.N : p.M;
     p.Nw = p.transposed ? p.M : p.N;
+    p8_pick_mode(p.A);
+    p8_pick_mode(p.B);
     return p;
 }
 
@@ -407,6 +535,8 @@ inline P8ConvProblem p8_gemm_problem(int transA, int transB, int M, int N, int K
     p.B.k = affine(1, 1, transB ? 1 : ldb, 0, 0, 0, 0, 0, 0, 0, 0, 0);
     p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1;
     p.Mw = M; p.Nw = N;
+    p8_pick_mode(p.A);
+    p8_pick_mode(p.B);
     return p;
 }
 

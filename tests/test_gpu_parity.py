@@ -249,6 +249,13 @@ CONV_CASES = [
     dict(N=4, C=6, H=14, W=14, K=16, R=5, S=5),           # LeNet conv2 shape, small batch
     dict(N=2, C=32, H=16, W=16, K=32, R=3, S=3, pad_h=1, pad_w=1),
     dict(N=1, C=4, H=5, W=5, K=7, R=1, S=1),
+    # output widths that are multiples of 8: the image operands are fetched as 8-byte runs trimmed at the borders
+    dict(N=2, C=3, H=8, W=16, K=5, R=3, S=3, pad_h=1, pad_w=1),
+    dict(N=3, C=2, H=12, W=8, K=4, R=5, S=5, pad_h=2, pad_w=2),
+    dict(N=2, C=4, H=6, W=24, K=9, R=1, S=1),
+    dict(N=1, C=2, H=10, W=18, K=3, R=3, S=3),
+    dict(N=2, C=2, H=9, W=16, K=3, R=3, S=1, pad_h=1, stride_h=2),
+    dict(N=5, C=3, H=16, W=16, K=70, R=3, S=3, pad_h=1, pad_w=1),   # more than one column tile
 ]
 
 
