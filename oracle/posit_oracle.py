@@ -27,6 +27,15 @@ What each function follows
                           product and every running sum is then a posit, rounded
                           as it is produced, terms taken in order of the
                           reduction index.
+* ``unary`` / ``unary_bwd`` / ``div`` / ``cross_entropy`` / ``mse``: Fig. 2 lists
+                          Sigmoid and TanH activations and the Cross Entropy and
+                          MSE losses, Sec. 3.3 / Fig. 3 give the loss its own posit
+                          precision and Sec. 4 (Table 4) uses posit(10,2) and
+                          posit(12,2) for it; no algorithm is printed.  Each
+                          elementary function is taken as the correctly rounded
+                          posit of the real function (``decimal``'s exp / ln at 120
+                          digits bracket the value), the losses as the chain of such
+                          operations written out in their docstrings.
 * ``conv2d_*``          : Sec. 3.1 (layers inherit LibTorch semantics:
                           cross-correlation, NCHW / OIHW, zero padding) and its
                           two adjoints, which the framework writes by hand
@@ -54,10 +63,14 @@ update" cannot be pinned to the paper's own framework: parity unpinned for
 those three readings (the definition here is the contract).  The same holds
 for the order of the terms and the position of the bias (last) in the
 ``*_noquire`` functions: parity unpinned against the paper's framework; their
-arithmetic (``mul``, ``add``) is pinned exhaustively for posit<8,0>.
+arithmetic (``mul``, ``add``) is pinned exhaustively for posit<8,0>.  The order
+of operations inside ``cross_entropy`` and ``mse`` is likewise a reading (parity
+unpinned against the paper's framework); their building blocks are pinned to
+libm within one rounding, to closed forms and to symmetries.
 """
 
 from fractions import Fraction
+import decimal
 import math
 
 
@@ -634,6 +647,148 @@ def conv2d_bwd_weight_noquire(dy, x, sh, fin, fout):
 
 def conv2d_bias_grad_noquire(dy, sh, fin, fout):
     return [dot_noquire(a, b, fin, fout) for a, b in conv2d_bias_grad_terms(dy, sh, fin)]
+
+
+# --------------------------------------------------------------------------
+# elementary functions, division, losses (Fig. 2: Sigmoid, TanH, Cross Entropy, MSE)
+# --------------------------------------------------------------------------
+
+_DEC = decimal.Context(prec=120, Emax=decimal.MAX_EMAX, Emin=decimal.MIN_EMIN, rounding=decimal.ROUND_HALF_EVEN)
+_DEC_SLACK = Fraction(1, 10 ** 100)  # far above the error of a few 120-digit operations
+
+
+def _to_decimal(x):
+    """Exact: posit values are dyadic rationals with short decimal expansions."""
+    x = Fraction(x)
+    d = _DEC.divide(decimal.Decimal(x.numerator), decimal.Decimal(x.denominator))
+    assert Fraction(d) == x
+    return d
+
+
+def _round_decimal(d, fmt):
+    """Round the real number that the 120-digit decimal d approximates (relative error far below
+    10^-100): both ends of the bracket must give the same pattern, which is then the correctly
+    rounded one.  Magnitudes beyond 10^+-60 lie outside every format here and clamp."""
+    if d == 0:
+        return 0
+    sign = -1 if d < 0 else 1
+    if d.adjusted() > 60:
+        return round_to_posit(sign * fmt.maxpos * 2, fmt)
+    if d.adjusted() < -60:
+        return round_to_posit(sign * fmt.minpos / 2, fmt)
+    v = Fraction(d)
+    lo, hi = round_to_posit(v * (1 - _DEC_SLACK), fmt), round_to_posit(v * (1 + _DEC_SLACK), fmt)
+    if lo != hi:
+        raise ArithmeticError("value too close to a rounding boundary for 120 digits")
+    return lo
+
+
+UNARY = ("sigmoid", "tanh", "exp", "log")
+
+
+def unary(fn, p, fmt):
+    """Correctly rounded posit of sigmoid(x) = 1/(1+e^-x), tanh(x), e^x or ln(x) at the value x of pattern p.
+    NaR gives NaR; ln of zero or of a negative value gives NaR; exact cases: tanh(0) = 0, ln(1) = 0."""
+    x = _value(p, fmt)
+    if x is NaR:
+        return fmt.nar
+    one = decimal.Decimal(1)
+    if fn == "exp":
+        return _round_decimal(_DEC.exp(_to_decimal(x)), fmt)
+    if fn == "log":
+        if x <= 0:
+            return fmt.nar
+        return 0 if x == 1 else _round_decimal(_DEC.ln(_to_decimal(x)), fmt)
+    if fn == "sigmoid":
+        return _round_decimal(_DEC.divide(one, _DEC.add(one, _DEC.exp(_to_decimal(-x)))), fmt)
+    if fn == "tanh":
+        if x == 0:
+            return 0
+        e2 = _DEC.exp(_to_decimal(2 * x))  # tanh = (e^2x - 1) / (e^2x + 1)
+        if e2.adjusted() > 200:
+            return _round_decimal(one, fmt)
+        if e2.adjusted() < -200:
+            return _round_decimal(-one, fmt)
+        return _round_decimal(_DEC.divide(_DEC.subtract(e2, one), _DEC.add(e2, one)), fmt)
+    raise ValueError(fn)
+
+
+def unary_bwd(fn, y, dy, fmt_y, fmt_d):
+    """Gradient through an activation from its forward OUTPUT y: sigmoid: dy*y*(1-y); tanh: dy*(1-y^2);
+    exact inside, one rounding to fmt_d."""
+    vy, vd = _value(y, fmt_y), _value(dy, fmt_d)
+    if vy is NaR or vd is NaR:
+        return fmt_d.nar
+    if fn == "sigmoid":
+        return round_to_posit(vd * vy * (1 - vy), fmt_d)
+    if fn == "tanh":
+        return round_to_posit(vd * (1 - vy * vy), fmt_d)
+    raise ValueError(fn)
+
+
+def div(pa, pb, fmt):
+    """posit / posit -> posit: the exact quotient rounded once; a zero divisor gives NaR."""
+    va, vb = _value(pa, fmt), _value(pb, fmt)
+    if va is NaR or vb is NaR or vb == 0:
+        return fmt.nar
+    return round_to_posit(va / vb, fmt)
+
+
+def neg(p, fmt):
+    return (-int(p)) & fmt.mask
+
+
+def _exact_sum_rounded(values, fmt, divisor=1):
+    """round( wrap_Q( sum of exact values ) / divisor ): the values are whole multiples of minpos^2 of fmt,
+    held in fmt's quire (which wraps modulo 2^Q like every quire here), then divided exactly."""
+    unit = fmt.minpos * fmt.minpos
+    total = sum(values, Fraction(0)) / unit
+    assert total.denominator == 1
+    return round_to_posit(Fraction(quire_wrap(total.numerator, fmt)) * unit / divisor, fmt)
+
+
+def cross_entropy(logits, labels, f_logits, f_loss, f_grad):
+    """Softmax cross entropy with mean reduction over the batch, computed in the loss format f_loss.
+
+    logits: rows of patterns in f_logits; labels: one class index per row.  Per row, with every operation
+    rounded to f_loss:  z_j = convert(logit_j);  m = max_j z_j;  t_j = add(z_j, -m);  e_j = exp(t_j);
+    S = round(sum_j e_j) (exact sum, one rounding);  p_j = div(e_j, S);  g_j = add(p_j, -[j == label]);
+    row loss = add(log(S), -t_label).  Outputs: dlogits[b][j] = round_f_grad(g_j / B) (exact division by the
+    batch size B, one rounding) and loss = round_f_loss((sum_b row loss_b) / B) (exact sum and division).
+    A NaR logit or a label outside 0..C-1 makes its row's gradient and the loss NaR."""
+    B = len(logits)
+    grads, row_losses, any_nar = [], [], False
+    for row, label in zip(logits, labels):
+        C = len(row)
+        z = [convert(p, f_logits, f_loss) for p in row]
+        if any(p == f_loss.nar for p in z) or not (0 <= label < C):
+            grads.append([f_grad.nar] * C)
+            any_nar = True
+            continue
+        m = max(z, key=lambda p: _value(p, f_loss))
+        t = [add(p, neg(m, f_loss), f_loss) for p in z]
+        e = [unary("exp", p, f_loss) for p in t]
+        S = _exact_sum_rounded([_value(p, f_loss) for p in e], f_loss)
+        prob = [div(p, S, f_loss) for p in e]
+        one = 1 << (f_loss.n - 2)
+        g = [add(prob[j], neg(one, f_loss) if j == label else 0, f_loss) for j in range(C)]
+        grads.append([round_to_posit(_value(p, f_loss) / B, f_grad) for p in g])
+        row_losses.append(add(unary("log", S, f_loss), neg(t[label], f_loss), f_loss))
+    if any_nar:
+        return f_loss.nar, grads
+    return _exact_sum_rounded([_value(p, f_loss) for p in row_losses], f_loss, divisor=B), grads
+
+
+def mse(pred, target, f_pred, f_loss, f_grad):
+    """Mean squared error over n elements in the loss format: d_i = add(convert(pred_i), -convert(target_i))
+    rounded to f_loss; loss = round_f_loss((sum_i d_i^2) / n), the squares summed exactly in f_loss's quire;
+    dpred_i = round_f_grad(2 d_i / n), exact inside.  NaR anywhere makes the loss NaR and that element's gradient NaR."""
+    n = len(pred)
+    d = [add(convert(p, f_pred, f_loss), neg(convert(t, f_pred, f_loss), f_loss), f_loss) for p, t in zip(pred, target)]
+    grads = [f_grad.nar if x == f_loss.nar else round_to_posit(2 * _value(x, f_loss) / n, f_grad) for x in d]
+    if any(x == f_loss.nar for x in d):
+        return f_loss.nar, grads
+    return _exact_sum_rounded([_value(x, f_loss) ** 2 for x in d], f_loss, divisor=n), grads
 
 
 # --------------------------------------------------------------------------
