@@ -143,6 +143,42 @@ int posit_conv2d_bwd_data_noquire(void* stream, int fin, int fout, const pnn_con
 int posit_conv2d_bwd_weight_noquire(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
                                     const void* dy, const void* x, void* dw, void* dbias);
 
+/* Elementary functions (Fig. 2: Sigmoid and TanH activations; exp and log are the pieces of the
+ * Cross Entropy loss).  The paper prints no algorithm: y[i] is the correctly rounded posit<fmt> of
+ * the real function at the value of x[i] (nearest, ties to the even pattern, never 0 or NaR for a
+ * nonzero finite value: e^x and sigmoid clamp to minpos / maxpos).  NaR gives NaR; log of zero or
+ * of a negative value gives NaR; exact cases: exp(0) = 1, log(1) = 0, tanh(0) = 0, sigmoid(0) = 1/2.
+ * Formats of at most 16 bits (PNN_EUNSUPPORTED for posit<32,2>). */
+typedef enum { PNN_SIGMOID = 0, PNN_TANH = 1, PNN_EXP = 2, PNN_LOG = 3 } pnn_function;
+int posit_unary(void* stream, int fn, int fmt, int64_t n, const void* x, void* y);
+
+/* Gradient through PNN_SIGMOID or PNN_TANH from the forward OUTPUT y_fwd (format fmt_y), in posit
+ * operations of the gradient's format fmt_d, each rounded: with y' = round_fmt_d(y_fwd),
+ * sigmoid: dx = dy * (y' * (1 - y'));  tanh: dx = dy * (1 - y' * y').  dy and dx are in fmt_d. */
+int posit_unary_bwd(void* stream, int fn, int fmt_y, int fmt_d, int64_t n,
+                    const void* y_fwd, const void* dy, void* dx);
+
+/* Softmax cross entropy with mean reduction (Fig. 2), computed in the loss format f_loss (Fig. 3: the
+ * loss stage has its own precision; Sec. 4, Table 4: posit(10,2) / posit(12,2)).  logits is
+ * [batch][classes] in f_logits, labels holds one int32 class index per row (device memory).  Per
+ * row, every operation rounded to f_loss: z_j = round(logit_j); m = max_j z_j; t_j = z_j - m;
+ * e_j = exp(t_j); S = round(sum_j e_j) with the sum exact (quire); p_j = e_j / S;
+ * g_j = p_j - [j == label]; row loss = log(S) - t_label.  Outputs (each may be NULL, not both):
+ * dlogits[b][j] = round_f_grad(g_j / batch), exact division, one rounding; loss (one pattern of
+ * f_loss) = round((sum_b row loss_b) / batch), exact sum (quire) and division, one rounding.  A NaR
+ * logit or a label outside 0..classes-1 makes that row's gradient and the loss NaR.  Formats of at
+ * most 16 bits.  One workgroup processes the whole batch: meant for batch x classes of a few 10^5. */
+int posit_cross_entropy(void* stream, int f_logits, int f_loss, int f_grad, int64_t batch, int64_t classes,
+                        const void* logits, const int32_t* labels, void* loss, void* dlogits);
+
+/* Mean squared error (Fig. 2) over n elements in the loss format: d_i = round_f_loss(pred_i) -
+ * round_f_loss(target_i) rounded to f_loss; loss = round_f_loss((sum_i d_i^2) / n), squares summed
+ * exactly in f_loss's quire; dpred_i = round_f_grad(2 d_i / n), exact inside.  pred and target are
+ * in f_pred.  NaR anywhere makes the loss and that element's gradient NaR.  Outputs may be NULL
+ * (not both).  Formats of at most 16 bits. */
+int posit_mse(void* stream, int f_pred, int f_loss, int f_grad, int64_t n,
+              const void* pred, const void* target, void* loss, void* dpred);
+
 /* Float tensor -> posit tensor (Fig. 2, tensor conversion): dst[i] = round_dst(src[i]),
  * src_float in {PNN_F32, PNN_F64}.  NaN and +-Inf give NaR, -0.0 gives 0,
  * nonzero values never round to zero (they clamp to +-minpos / +-maxpos). */

@@ -714,15 +714,15 @@ def unary(fn, p, fmt):
 
 
 def unary_bwd(fn, y, dy, fmt_y, fmt_d):
-    """Gradient through an activation from its forward OUTPUT y: sigmoid: dy*y*(1-y); tanh: dy*(1-y^2);
-    exact inside, one rounding to fmt_d."""
-    vy, vd = _value(y, fmt_y), _value(dy, fmt_d)
-    if vy is NaR or vd is NaR:
-        return fmt_d.nar
+    """Gradient through an activation from its forward OUTPUT y, in posit operations of the gradient's
+    format fmt_d, each rounded: with y' = convert(y), sigmoid: mul(dy, mul(y', add(1, -y'))); tanh:
+    mul(dy, add(1, -mul(y', y')))."""
+    yc = convert(y, fmt_y, fmt_d)
+    one = 1 << (fmt_d.n - 2)
     if fn == "sigmoid":
-        return round_to_posit(vd * vy * (1 - vy), fmt_d)
+        return mul(dy, mul(yc, add(one, neg(yc, fmt_d), fmt_d), fmt_d), fmt_d)
     if fn == "tanh":
-        return round_to_posit(vd * (1 - vy * vy), fmt_d)
+        return mul(dy, add(one, neg(mul(yc, yc, fmt_d), fmt_d), fmt_d), fmt_d)
     raise ValueError(fn)
 
 

@@ -67,10 +67,15 @@ def load():
     L.posit_conv2d_fwd_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
     L.posit_conv2d_bwd_data_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp]
     L.posit_conv2d_bwd_weight_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
+    L.posit_unary.argtypes = [vp, ci, ci, i64, vp, vp]
+    L.posit_unary_bwd.argtypes = [vp, ci, ci, ci, i64, vp, vp, vp]
+    L.posit_cross_entropy.argtypes = [vp, ci, ci, ci, i64, i64, vp, vp, vp, vp]
+    L.posit_mse.argtypes = [vp, ci, ci, ci, i64, vp, vp, vp, vp]
     L.posit_status_string.argtypes = [ci]
     L.posit_status_string.restype = ctypes.c_char_p
     for name in ("posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight", "posit_round", "posit_convert", "posit_axpy",
                  "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
+                 "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse",
                  "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"):
         getattr(L, name).restype = ci
     _lib = L
@@ -233,6 +238,50 @@ def posit_conv2d_bwd_weight_noquire(dy, x, desc, fin, fout, with_bias=False, out
     _check(load().posit_conv2d_bwd_weight_noquire(_stream(), fin, fout, ctypes.byref(desc), _dev(dy, fin, "dy"), _dev(x, fin, "x"),
                                                   _dev(out, fout, "dw"), _dev(out_bias, fout, "dbias") if with_bias else None))
     return (out, out_bias) if with_bias else out
+
+
+FUNCTIONS = {"sigmoid": 0, "tanh": 1, "exp": 2, "log": 3}
+
+
+def posit_unary(fn, x, fmt, out=None):
+    """y = correctly rounded fn(x) elementwise; fn in "sigmoid", "tanh", "exp", "log"."""
+    fmt = _code(fmt)
+    if out is None:
+        out = torch.empty_like(x)
+    _check(load().posit_unary(_stream(), FUNCTIONS[fn], fmt, x.numel(), _dev(x, fmt, "x"), _dev(out, fmt, "y")))
+    return out
+
+
+def posit_unary_bwd(fn, y_fwd, dy, fmt_y, fmt_d, out=None):
+    fmt_y, fmt_d = _code(fmt_y), _code(fmt_d)
+    if out is None:
+        out = torch.empty_like(dy)
+    _check(load().posit_unary_bwd(_stream(), FUNCTIONS[fn], fmt_y, fmt_d, dy.numel(), _dev(y_fwd, fmt_y, "y_fwd"),
+                                  _dev(dy, fmt_d, "dy"), _dev(out, fmt_d, "dx")))
+    return out
+
+
+def posit_cross_entropy(logits, labels, f_logits, f_loss, f_grad, want_loss=True, want_grad=True):
+    """Returns (loss, dlogits): loss a 1-element tensor of f_loss, dlogits [batch][classes] of f_grad (None when not wanted).
+    labels: int32 device tensor."""
+    f_logits, f_loss, f_grad = _code(f_logits), _code(f_loss), _code(f_grad)
+    if logits.dim() != 2 or labels.dtype != torch.int32 or labels.numel() != logits.shape[0] or not labels.is_contiguous() or not labels.is_cuda:
+        raise PositError("logits must be [batch][classes] and labels a contiguous int32 device tensor with one entry per row")
+    loss = torch.empty((1,), dtype=TORCH_DTYPE[f_loss], device=logits.device) if want_loss else None
+    grad = torch.empty(tuple(logits.shape), dtype=TORCH_DTYPE[f_grad], device=logits.device) if want_grad else None
+    _check(load().posit_cross_entropy(_stream(), f_logits, f_loss, f_grad, logits.shape[0], logits.shape[1], _dev(logits, f_logits, "logits"),
+                                      labels.data_ptr(), _dev(loss, f_loss, "loss") if want_loss else None,
+                                      _dev(grad, f_grad, "dlogits") if want_grad else None))
+    return loss, grad
+
+
+def posit_mse(pred, target, f_pred, f_loss, f_grad, want_loss=True, want_grad=True):
+    f_pred, f_loss, f_grad = _code(f_pred), _code(f_loss), _code(f_grad)
+    loss = torch.empty((1,), dtype=TORCH_DTYPE[f_loss], device=pred.device) if want_loss else None
+    grad = torch.empty(tuple(pred.shape), dtype=TORCH_DTYPE[f_grad], device=pred.device) if want_grad else None
+    _check(load().posit_mse(_stream(), f_pred, f_loss, f_grad, pred.numel(), _dev(pred, f_pred, "pred"), _dev(target, f_pred, "target"),
+                            _dev(loss, f_loss, "loss") if want_loss else None, _dev(grad, f_grad, "dpred") if want_grad else None))
+    return loss, grad
 
 
 def posit_round(src, fdst, out=None):

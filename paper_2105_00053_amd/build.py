@@ -19,7 +19,7 @@ HOSTCHECK = os.path.join(HERE, "libpositnn_hostcheck.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
-UNITS = ["api_elementwise.hip", "api_gemm.hip", "api_conv.hip", "api_glue.hip", "api_noquire.hip"]
+UNITS = ["api_elementwise.hip", "api_gemm.hip", "api_conv.hip", "api_glue.hip", "api_noquire.hip", "api_loss.hip"]
 DEVICE_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=" + ARCH,
                 "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                 "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

@@ -5,6 +5,7 @@
 #include "quire_arith.h"
 #include "conv_p8.h"
 #include "noquire_arith.h"
+#include "loss_ops.h"
 
 using namespace pnn;
 
@@ -91,8 +92,31 @@ uint32_t hostcheck_dot_noquire(int fin, int fout, int64_t n, const uint32_t* a, 
     }
 }
 
-// posit (x) posit -> posit, rounded once: op 0 = multiply, 1 = add; any patterns
+// posit<fmt> value times 2^pow2 divided by an integer, rounded once to format fout (the scaling step of the losses)
+uint32_t hostcheck_div_int(int fmt, int fout, uint32_t p, int pow2, uint32_t divisor) {
+    const FmtRT fi = fmt_of_code(fmt), fo = fmt_of_code(fout);
+    if (p == fi.nar()) return fo.nar();
+    if (p == 0) return 0;
+    Real r = decode_rt(p, fi);
+    r.scale += pow2;
+    return encode_rt(real_div_int(r, divisor), fo);
+}
+
+// posit (x) posit -> posit, rounded once: op 0 = multiply, 1 = add, 2 = divide (formats of at most 16 bits); any patterns
 uint32_t hostcheck_posit_op(int fmt, int op, uint32_t a, uint32_t b) {
+    if (op == 2) {
+        switch (fmt) {
+            case 0: return posit_div<P8>(a, b);
+            case 1: return posit_div<P16>(a, b);
+            case 3: return posit_div<P8_1>(a, b);
+            case 4: return posit_div<P8_2>(a, b);
+            case 5: return posit_div<P10_1>(a, b);
+            case 6: return posit_div<P10_2>(a, b);
+            case 7: return posit_div<P12_1>(a, b);
+            case 8: return posit_div<P12_2>(a, b);
+            default: return 0xFFFFFFFFu;
+        }
+    }
     switch (fmt) {
         case 0: return op ? posit_add<P8>(a, b) : posit_mul<P8>(a, b);
         case 1: return op ? posit_add<P16>(a, b) : posit_mul<P16>(a, b);

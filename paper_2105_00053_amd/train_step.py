@@ -37,11 +37,11 @@ class Net:
 
 
 def loss_gradient(logits_p8, labels):
-    """(softmax(logits) - onehot) / batch in float64 on the device, rounded to posit<16,1> then posit<8,0>."""
-    z = pn.posit_convert(logits_p8, "p8", "f64")
-    p = torch.softmax(z, dim=1)
-    p[torch.arange(p.shape[0], device=p.device), labels] -= 1.0
-    g16 = pn.posit_round((p / p.shape[0]).contiguous(), "p16")
+    """Softmax cross-entropy gradient in the posit<16,1> loss format (Sec. 4: a 16-bit loss next to 8-bit
+    layers), then its posit<8,0> copy for the backward pass.  labels: int32 device tensor."""
+    if labels.dtype != torch.int32:
+        labels = labels.to(torch.int32)
+    _, g16 = pn.posit_cross_entropy(logits_p8, labels, "p8", "p16", "p16", want_loss=False)
     return pn.posit_convert(g16, "p16", "p8"), g16
 
 

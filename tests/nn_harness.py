@@ -3,9 +3,10 @@
 Every quire dot product (convolutions, linear layers, their two backward passes, bias
 gradients, average pooling as a convolution with four weights of 1/4, the SGD update) is
 run twice on identical inputs: through the GPU library and through the C++ oracle, and
-compared bit for bit.  The glue that is not a dot product (ReLU, max-pool routing, the
-softmax/cross-entropy gradient) is evaluated once on the host and its result is fed to
-both sides, so the chain stays comparable layer by layer.
+compared bit for bit; so is the softmax cross-entropy gradient (library against the
+Python oracle).  The glue that is not arithmetic (ReLU, max-pool routing) is evaluated
+once on the host and its result is fed to both sides, so the chain stays comparable layer
+by layer.
 
 Formats (Sec. 3.3 mixed precision, stages of Fig. 3): activations, weights copies and
 back-propagated errors posit<8,0>; weight gradients rounded from the 32-bit quire straight
@@ -16,6 +17,7 @@ import torch
 
 import paper_2105_00053_amd as pn
 from oracle import fast
+from oracle import posit_oracle as po
 
 from gpu_util import to_dev, to_np
 
@@ -135,13 +137,14 @@ def training_step(net, batch, x_f32, params_f32, labels, check=True, timers=None
             x = np.ascontiguousarray(x.reshape(x.shape[0], -1))
     logits = x
 
-    # ---------------- loss gradient (host glue, fed to both sides) ----------------
-    z = fast.to_float(logits, "p8", "f64")
-    z = z - z.max(axis=1, keepdims=True)
-    p = np.exp(z)
-    p /= p.sum(axis=1, keepdims=True)
-    p[np.arange(len(labels)), labels] -= 1.0
-    g16 = fast.round_from_float(p / len(labels), "p16")
+    # ---------------- loss gradient: softmax cross entropy in the posit<16,1> loss format ----------------
+    lab32 = torch.from_numpy(np.asarray(labels, dtype=np.int32)).cuda()
+    loss_d, g16_d = pn.posit_cross_entropy(to_dev(logits), lab32, "p8", "p16", "p16")
+    want_loss, want_g = po.cross_entropy(logits.tolist(), [int(v) for v in labels], po.P8, po.P16, po.P16)
+    g16 = np.array(want_g, dtype=np.uint16)
+    if check:
+        _check("cross entropy dlogits", to_np(g16_d, "p16"), g16, log)
+        _check("cross entropy loss", to_np(loss_d, "p16"), np.array([want_loss]), log)
     dy = to_np(pn.posit_convert(to_dev(g16), "p16", "p8"), "p8")
     if check:
         _check("dlogits p16->p8", dy, fast.convert(g16, "p16", "p8"), log)

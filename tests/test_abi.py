@@ -30,7 +30,8 @@ def test_header_declares_the_expected_entry_points():
         "posit_gemm", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
         "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string",
         "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd",
-        "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire"])
+        "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
+        "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse"])
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -61,6 +62,14 @@ def test_argument_validation_without_launch():
     assert L.posit_gemm_noquire(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4) == EINVAL  # lda < K
     assert L.posit_gemm_noquire(null, 0, 0, 0, 0, 0, 4, 4, null, 4, null, 4, null, null, 4) == 0
     assert L.posit_conv2d_fwd_noquire(null, 0, 0, None, fake, fake, null, fake) == EINVAL
+    assert L.posit_unary(null, 7, 0, 4, fake, fake) == EINVAL           # unknown function
+    assert L.posit_unary(null, 0, 2, 4, fake, fake) == 2                # posit<32,2>: unsupported
+    assert L.posit_unary(null, 0, 0, 0, null, null) == 0
+    assert L.posit_unary_bwd(null, 2, 0, 0, 4, fake, fake, fake) == EINVAL  # no gradient entry for exp
+    assert L.posit_cross_entropy(null, 0, 1, 1, 4, 10, fake, fake, null, null) == EINVAL  # nothing asked for
+    assert L.posit_cross_entropy(null, 0, 2, 1, 4, 10, fake, fake, fake, fake) == 2
+    assert L.posit_cross_entropy(null, 0, 1, 1, 0, 10, null, null, fake, null) == EINVAL  # mean over an empty batch
+    assert L.posit_mse(null, 0, 1, 1, 4, fake, null, fake, fake) == EINVAL
     assert L.posit_round(null, 0, 0, 4, fake, fake) == EINVAL      # source must be a float type
     assert L.posit_round(null, 100, 100, 4, fake, fake) == EINVAL  # destination must be a posit
     assert L.posit_round(null, 100, 0, 0, null, null) == 0

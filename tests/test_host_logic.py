@@ -34,6 +34,8 @@ def hc():
     L.hostcheck_dot_noquire.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_posit_op.restype = ctypes.c_uint32
     L.hostcheck_posit_op.argtypes = [ci, ci, ctypes.c_uint32, ctypes.c_uint32]
+    L.hostcheck_div_int.restype = ctypes.c_uint32
+    L.hostcheck_div_int.argtypes = [ci, ci, ctypes.c_uint32, ci, ctypes.c_uint32]
     L.hostcheck_map_rt.argtypes = [ci, ci, i64, vp, vp]
     L.hostcheck_axpy_rt.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     return L
@@ -347,3 +349,44 @@ def test_noquire_dot_matches_oracle(hc, fin, fout):
         b = np.full(41, 0x40, dtype=np.uint32)
         assert hc.hostcheck_dot_noquire(0, 0, 41, _p(a), _p(b), 0, 0) == 0x40
         assert hc.hostcheck_dot(0, 0, 41, _p(a), _p(b), 0, 0) == 0x54
+
+
+# ---------------- division and the scaling step of the losses ----------------
+
+@pytest.mark.parametrize("fmt", ["p8", "p8_1", "p8_2"])
+def test_division_exhaustive_8bit(hc, fmt):
+    f = po.FORMATS[fmt]
+    for a in range(256):
+        for b in range(256):
+            assert hc.hostcheck_posit_op(CODE[fmt], 2, a, b) == po.div(a, b, f), (a, b)
+
+
+@pytest.mark.parametrize("fmt", ["p16", "p10_1", "p10_2", "p12_1", "p12_2"])
+def test_division_sampled(hc, fmt):
+    f = po.FORMATS[fmt]
+    rng = np.random.default_rng(BITS[fmt] + 9)
+    a = _patterns(rng, 4000, fmt)
+    b = _patterns(rng, 4000, fmt)
+    b[:500] = a[:500] + rng.integers(-2, 3, 500).astype(np.uint64) & f.mask  # quotients next to one
+    for x, y in zip(a.tolist(), b.tolist()):
+        assert hc.hostcheck_posit_op(CODE[fmt], 2, x, y) == po.div(x, y, f), (x, y)
+
+
+@pytest.mark.parametrize("fin,fout", [("p16", "p16"), ("p12_2", "p12_2"), ("p10_2", "p8_2"), ("p8", "p16"), ("p16", "p8"), ("p32", "p16")])
+def test_value_over_integer_rounds_once(hc, fin, fout):
+    """posit * 2^k / d rounded once (gradient scaling 1/batch, 2/n): against the exact rational."""
+    from fractions import Fraction
+    fi, fo = po.FORMATS[fin], po.FORMATS[fout]
+    rng = np.random.default_rng(BITS[fin] * 3 + BITS[fout])
+    pats = _patterns(rng, 1500, fin).tolist()
+    divs = [1, 2, 3, 7, 10, 64, 100, 128, 1000, 1280, 65537, 2 ** 31 - 1, 2 ** 32 - 1] + [int(v) for v in rng.integers(1, 2 ** 32, 20)]
+    for i, p in enumerate(pats):
+        d = divs[i % len(divs)]
+        k = (i // len(divs)) % 3 - 1
+        v = po.decode(p, fi)
+        want = fo.nar if p == fi.nar else po.round_to_posit(v * Fraction(2) ** k / d, fo)
+        assert hc.hostcheck_div_int(CODE[fin], CODE[fout], p, k, d) == want, (p, k, d)
+    # quotients that land exactly on a rounding tie: 3 * minpos-spacing cases, e.g. (1 + 3 ulp) / 2 in posit<8,0>
+    for p in range(1, 128):
+        for d in (2, 4, 8, 3, 6):
+            assert hc.hostcheck_div_int(0, 0, p, 0, d) == po.round_to_posit(po.decode(p, po.P8) / d, po.P8), (p, d)
