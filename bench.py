@@ -3,7 +3,7 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--size S] [--no-cpu]
 
-Workload (BASELINE config 5, the one the metric is quoted on): posit<8,0> quire
+Workload (benchmark config 5, the one the metric is quoted on): posit<8,0> quire
 GEMM with M = N = K = 4096, operands N(0,1) rounded to posit<8,0>, all inputs
 resident in HBM before timing starts.  One step is one pass over every stage of
 the path on that batch:
@@ -51,7 +51,7 @@ def _time_ms(torch, fn, reps, warm=2):
 
 
 def extra_measurements(torch, pn, workloads):
-    """The other BASELINE configs, for the record (not part of `value`): GEMM kernels of configs 2 and 5
+    """The other benchmark configs, for the record (not part of `value`): GEMM kernels of configs 2 and 5
     and whole training steps of configs 3 and 4 (device-resident, see paper_2105_00053_amd/train_step.py)."""
     import numpy as np
     from paper_2105_00053_amd import train_step
@@ -81,13 +81,13 @@ def main():
     ap.add_argument("--size", type=int, default=4096, help="M = N = K")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
-    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other BASELINE configs)")
+    ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other benchmark configs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy before timing (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (the path is data-parallel over rows of A; "
-              "see DESIGN.md for how it would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (the path is data-parallel over rows of A: "
+              "more GPUs would each take a block of rows); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
@@ -164,7 +164,7 @@ def main():
         "vs_baseline": None,
         "dtype": "int32",
         "data": "synthetic",
-        "config": {"workload": "posit<8,0> quire GEMM M=N=K=%d (BASELINE config 5), step = round A,B + gemm + convert + axpy" % S,
+        "config": {"workload": "posit<8,0> quire GEMM M=N=K=%d (benchmark config 5), step = round A,B + gemm + convert + axpy" % S,
                    "fin": "posit<8,0>", "fout": "posit<8,0>", "quire_bits": 32},
         "roofline": {
             "bound": "alu",

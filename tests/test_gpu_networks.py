@@ -1,4 +1,4 @@
-"""BASELINE configs 3 and 4: LeNet-5-shaped (batch 64) and CifarNet-shaped (batch 128)
+"""Benchmark configs 3 and 4: LeNet-5-shaped (batch 64) and CifarNet-shaped (batch 128)
 training steps, every dot-product layer bit-exact against the oracle (see nn_harness)."""
 import pytest
 
