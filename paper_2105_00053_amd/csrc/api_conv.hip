@@ -7,7 +7,7 @@
 //   bwd_weight rows k          x cols (c,r,s)    reduce over (n,oh,ow)
 #include "api_common.h"
 #include "conv_desc.h"
-#include "conv_p8.h"
+#include "conv_p8_pre.h"
 
 namespace pnn {
 
@@ -30,8 +30,10 @@ hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
+    P8ConvOut kout = p.out;
+    kout.vec4 = p.out.vec4 && ((uintptr_t)C & 3u) == 0;  // packed stores need an aligned output tensor
 #define PNN_LAUNCH_CONV(TY, TX, TM, TN)                                                                                   \
-    hipLaunchKernelGGL((p8_conv_kernel<TY, TX, TM, TN>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, \
+    hipLaunchKernelGGL((p8_conv_kernel<TY, TX, TM, TN>), grid, dim3(256), 0, st, p.A, p.B, kout, kbias, C, fout, p.M, p.N, \
                        p.K, (int)plan.k_per_split, tiles_n, ws, p.transposed)
     if (tl.bm == 128 && tl.bn == 128) PNN_LAUNCH_CONV(16, 16, 8, 8);
     else if (tl.bm == 256 && tl.bn == 64) PNN_LAUNCH_CONV(32, 8, 8, 8);
@@ -42,6 +44,53 @@ hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     if (plan.splits > 1) launch_split_merge<P8, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
     return hipGetLastError();
 }
+
+// Pre-decoded path: rewrite both operands into the workspace, then run the kernel that reads them.
+// Workspace layout: [operand A as int16][operand B as int16][partial quires and flags of a split reduction].
+template <class Out>
+hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const void* srcB, const uint8_t* bias, void* C, int fout,
+                         void* wsp, const GemmPlan& plan, const Out& merge_out) {
+    uint8_t* wbytes = (uint8_t*)wsp;
+    pp.job[0].src = (const uint8_t*)srcA; pp.job[0].dst = (uint16_t*)wbytes;
+    pp.job[1].src = (const uint8_t*)srcB; pp.job[1].dst = (uint16_t*)(wbytes + pp.bytes[0]);
+    pp.A.base = pp.job[0].dst;
+    pp.B.base = pp.job[1].dst;
+    const int64_t work0 = (int64_t)pp.job[0].rows * (pp.job[0].pitch / 8), work1 = (int64_t)pp.job[1].rows * (pp.job[1].pitch / 8);
+    int64_t blocks = ((work0 > work1 ? work0 : work1) + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(p8_predecode_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, st, pp.job[0], pp.job[1]);
+
+    const P8ConvTile tl = p8_conv_tile(pp.M, pp.N, pp.K);
+    const int tiles_m = (pp.M + tl.bm - 1) / tl.bm, tiles_n = (pp.N + tl.bn - 1) / tl.bn;
+    SplitWs ws;
+    ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)(wbytes + pp.bytes[0] + pp.bytes[1]);
+        ws.rowflag = ws.limbs + (size_t)plan.splits * pp.M * pp.N;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * pp.Mw;
+        const int64_t nflags = (int64_t)plan.splits * (pp.M + pp.N);
+        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
+    P8ConvOut kout = pp.out;
+    kout.vec4 = pp.out.vec4 && ((uintptr_t)C & 3u) == 0;
+#define PNN_LAUNCH_PRE(TY, TX, TM, TN)                                                                                       \
+    hipLaunchKernelGGL((p8_conv_pre_kernel<TY, TX, TM, TN>), grid, dim3(256), 0, st, pp.A, pp.B, kout, kbias, C, fout, pp.M, \
+                       pp.N, pp.K, (int)plan.k_per_split, tiles_n, ws, pp.transposed)
+    if (tl.bm == 128 && tl.bn == 128) PNN_LAUNCH_PRE(16, 16, 8, 8);
+    else if (tl.bm == 256 && tl.bn == 64) PNN_LAUNCH_PRE(32, 8, 8, 8);
+    else if (tl.bm == 256 && tl.bn == 32) PNN_LAUNCH_PRE(32, 8, 8, 4);
+    else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_PRE(16, 16, 8, 4);
+    else PNN_LAUNCH_PRE(16, 16, 4, 4);
+#undef PNN_LAUNCH_PRE
+    if (plan.splits > 1) launch_split_merge<P8, Out>(st, ws, plan.splits, pp.Mw, pp.Nw, bias, C, fout, merge_out);
+    return hipGetLastError();
+}
+
+// workspace of the pre-decoded path: the two rewritten operands, then the split partials
+inline size_t p8_pre_ws_bytes(const P8PrePlan& pp, const GemmPlan& plan) { return pp.bytes[0] + pp.bytes[1] + plan.ws_bytes; }
 
 hipError_t p8_conv_launch_rowmajor(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
                                    const GemmPlan& plan, int64_t ld) {
@@ -68,6 +117,8 @@ size_t conv_ws(int which, const ConvGeom& g) {
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(which, g)) {
         const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
         b = p8_conv_plan(p.M, p.N, p.K).ws_bytes;
+        const P8PrePlan pp = p8_pre_plan(which, g);
+        if (pp.ok) b = p8_pre_ws_bytes(pp, p8_conv_plan(pp.M, pp.N, pp.K));
     }
     return b;
 }
@@ -78,6 +129,13 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(0, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(0, g)) {
+        const P8PrePlan pp = p8_pre_plan(0, g);
+        if (pp.ok) {
+            const GemmPlan plan = p8_conv_plan(pp.M, pp.N, pp.K);
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, plan)) return PNN_EWORKSPACE;
+            NchwOut mout{(int64_t)g.OH * g.OW, (int64_t)g.K};
+            return hip_status(p8_pre_launch(st, pp, x, w, (const uint8_t*)bias, y, fout, ws, plan, mout));
+        }
         const P8ConvProblem p = p8_problem(0, g, x, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
         if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
@@ -98,6 +156,13 @@ int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, c
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(1, g)) {
+        const P8PrePlan pp = p8_pre_plan(1, g);
+        if (pp.ok) {
+            const GemmPlan plan = p8_conv_plan(pp.M, pp.N, pp.K);
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, plan)) return PNN_EWORKSPACE;
+            NchwOut mout{(int64_t)g.H * g.W, (int64_t)g.C};
+            return hip_status(p8_pre_launch(st, pp, dy, w, nullptr, dx, fout, ws, plan, mout));
+        }
         const P8ConvProblem p = p8_problem(1, g, dy, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
         if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
@@ -121,6 +186,17 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     const bool fastp8 = (F::N == 8 && F::ES == 0) && p8_conv_eligible(2, g);
     GemmPlan plan = conv_plan<F>(d);
     P8ConvProblem p8p;
+    if (fastp8) {
+        const P8PrePlan pp = p8_pre_plan(2, g);
+        if (pp.ok) {
+            const GemmPlan pplan = p8_conv_plan(pp.M, pp.N, pp.K);
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan)) return PNN_EWORKSPACE;
+            RowMajorOut pout{d.N};
+            hipError_t pe = p8_pre_launch(st, pp, x, dy, nullptr, dw, fout, ws, pplan, pout);  // operand A is x, B is dy
+            if (pe == hipSuccess && dbias) pe = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW);
+            return hip_status(pe);
+        }
+    }
     if (fastp8) {
         p8p = p8_problem(2, g, dy, x);
         plan = p8_conv_plan(p8p.M, p8p.N, p8p.K);

@@ -84,6 +84,7 @@ struct P8ConvOut {
     FastDiv md;          // m = c1 * md.d + c0
     int64_t m1, m0;      // mpart = c1 * m1 + c0 * m0
     int64_t nstride;
+    int vec4;            // rows 4q .. 4q+3 of one column are four consecutive bytes at a multiple of four
     PNN_HD int64_t at(int m, int n) const {
         const uint32_t c1 = md.div((uint32_t)m);
         const uint32_t c0 = (uint32_t)m - c1 * md.d;
@@ -240,6 +241,93 @@ __device__ __forceinline__ void p8_fill_kinfo(const P8Gather& op, int4* kinfo, i
     kinfo[lane] = ki;
 }
 
+// Epilogue shared by the convolution kernels: add the bias, round each 32-bit quire once and
+// store it (or park the partial quire and the NaR flags of a split reduction in the workspace).
+// Thread (ty, tx) owns rows (i>>2)*(TY*4) + ty*4 + (i&3) and columns (j>>2)*(TX*4) + tx*4 + (j&3).
+// With out.vec4 set, the four rows i&3 = 0..3 of one column land on four consecutive bytes that
+// start at a multiple of four, and posit<8,0> results are stored as one 32-bit word.
+template <int TY, int TX, int TM, int TN>
+__device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], const P8ConvOut& out, const uint8_t* __restrict__ bias,
+                                                 void* __restrict__ C, int fout, int M, int N, int m0, int n0, const SplitWs& ws,
+                                                 int ws_transposed, const uint16_t* tab, const uint32_t* rowNaR, const uint32_t* colNaR) {
+    const int t = threadIdx.x;
+    const int tx = t % TX, ty = t / TX;
+    constexpr int BM = TY * TM, BN = TX * TN;
+    if (gridDim.z == 1 && fout == 0 && out.vec4) {
+#pragma unroll
+        for (int ig = 0; ig < TM / 4; ++ig) {
+            const int lr = ig * (TY * 4) + ty * 4;
+            const int m = m0 + lr;
+            if (m >= M) continue;  // M is a multiple of four here: the four rows are all inside or all outside
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const int lc = (j >> 2) * (TX * 4) + tx * 4 + (j & 3);
+                const int n = n0 + lc;
+                if (n >= N) continue;
+                int32_t badd = 0;
+                bool cnar = colNaR[lc] != 0;
+                if (bias) {
+                    const uint32_t bp = bias[n];
+                    if (bp == 0x80u) cnar = true;
+                    else badd = (int32_t)(int16_t)tab[bp] << P8::MAXS;
+                }
+                uint32_t word = 0;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const bool nar = cnar || rowNaR[lr + r] != 0;
+                    word |= (nar ? 0x80u : p8_round_quire(acc[ig * 4 + r][j] + badd)) << (8 * r);
+                }
+                *reinterpret_cast<uint32_t*>((uint8_t*)C + out.at(m, n)) = word;
+            }
+        }
+        return;
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int lr = (i >> 2) * (TY * 4) + ty * 4 + (i & 3);
+        const int m = m0 + lr;
+        if (m >= M) continue;
+        const bool rnar = rowNaR[lr] != 0;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int lc = (j >> 2) * (TX * 4) + tx * 4 + (j & 3);
+            const int n = n0 + lc;
+            if (n >= N) continue;
+            if (gridDim.z == 1) {
+                int32_t q = acc[i][j];
+                bool nar = rnar || colNaR[lc] != 0;
+                if (bias) {
+                    const uint32_t bp = bias[n];
+                    if (bp == 0x80u) nar = true;
+                    else q += (int32_t)(int16_t)tab[bp] << P8::MAXS;
+                }
+                const int64_t at = out.at(m, n);
+                if (fout == 0) {
+                    ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire(q));
+                } else {
+                    const uint32_t q1[1] = {(uint32_t)q};
+                    round_store<QuireAccum<P8>, 1>(q1, nar, fout, C, at);
+                }
+            } else {
+                // partial quire; the merge kernel sees an (Mw x Nw) row-major problem
+                const int64_t z = blockIdx.z;
+                const int64_t idx = ws_transposed ? ((int64_t)n * M + m) : ((int64_t)m * N + n);
+                ws.limbs[z * (int64_t)M * N + idx] = (uint32_t)acc[i][j];
+            }
+        }
+    }
+    if (gridDim.z > 1) {
+        const int64_t z = blockIdx.z;
+        // flags in the orientation of the merge kernel: its rows are our columns when transposed
+        uint32_t* rflag = ws_transposed ? ws.colflag : ws.rowflag;
+        uint32_t* cflag = ws_transposed ? ws.rowflag : ws.colflag;
+        for (int r = t; r < BM; r += 256)
+            if (m0 + r < M && rowNaR[r]) atomicOr(&rflag[z * M + m0 + r], 1u);
+        for (int r = t; r < BN; r += 256)
+            if (n0 + r < N && colNaR[r]) atomicOr(&cflag[z * N + n0 + r], 1u);
+    }
+}
+
 // TY x TX threads (= 256), register tile TM x TN, workgroup tile BM = TY*TM by BN = TX*TN.
 // `bias` (nullable) is indexed by output column n.  With gridDim.z > 1 partial quires go to the workspace.
 template <int TY, int TX, int TM, int TN>
@@ -347,50 +435,7 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
         __syncthreads();
     }
 
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int lr = (i >> 2) * (TY * 4) + ty * 4 + (i & 3);
-        const int m = m0 + lr;
-        if (m >= M) continue;
-        const bool rnar = rowNaR[lr] != 0;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int lc = (j >> 2) * (TX * 4) + tx * 4 + (j & 3);
-            const int n = n0 + lc;
-            if (n >= N) continue;
-            if (gridDim.z == 1) {
-                int32_t q = acc[i][j];
-                bool nar = rnar || colNaR[lc] != 0;
-                if (bias) {
-                    const uint32_t bp = bias[n];
-                    if (bp == 0x80u) nar = true;
-                    else q += (int32_t)(int16_t)tab[bp] << P8::MAXS;
-                }
-                const int64_t at = out.at(m, n);
-                if (fout == 0) {
-                    ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire(q));
-                } else {
-                    const uint32_t q1[1] = {(uint32_t)q};
-                    round_store<QuireAccum<P8>, 1>(q1, nar, fout, C, at);
-                }
-            } else {
-                // partial quire; the merge kernel sees an (Mw x Nw) row-major problem
-                const int64_t z = blockIdx.z;
-                const int64_t idx = ws_transposed ? ((int64_t)n * M + m) : ((int64_t)m * N + n);
-                ws.limbs[z * (int64_t)M * N + idx] = (uint32_t)acc[i][j];
-            }
-        }
-    }
-    if (gridDim.z > 1) {
-        const int64_t z = blockIdx.z;
-        // flags in the orientation of the merge kernel: its rows are our columns when transposed
-        uint32_t* rflag = ws_transposed ? ws.colflag : ws.rowflag;
-        uint32_t* cflag = ws_transposed ? ws.rowflag : ws.colflag;
-        for (int r = t; r < BM; r += 256)
-            if (m0 + r < M && rowNaR[r]) atomicOr(&rflag[z * M + m0 + r], 1u);
-        for (int r = t; r < BN; r += 256)
-            if (n0 + r < N && colNaR[r]) atomicOr(&cflag[z * N + n0 + r], 1u);
-    }
+    p8_conv_epilogue<TY, TX, TM, TN>(acc, out, bias, C, fout, M, N, m0, n0, ws, ws_transposed, tab, rowNaR, colNaR);
 }
 
 // ---- posit<8,0> path: implicit GEMM on the packed dot-product kernel ----
@@ -450,7 +495,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t1; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, CRS, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(1, 1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(OHW); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW;
+        p.out.md = make_fastdiv(OHW); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW; p.out.vec4 = OHW % 4 == 0;
     } else if (which == 1) {  // t0 = dy, t1 = w ; stride 1 only
         p.M = g.N * HW; p.N = g.C; p.K = g.K * RS; p.transposed = 0;
         p.A.base = (const uint8_t*)t0; p.A.rows = p.M; p.A.K = p.K; p.A.LY = g.OH; p.A.LX = g.OW;
@@ -459,7 +504,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t1; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, RS, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(RS, 1, CRS, 1, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(HW); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW;
+        p.out.md = make_fastdiv(HW); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW; p.out.vec4 = HW % 4 == 0;
     } else {  // t0 = dy, t1 = x ; computed transposed: rows (c,r,s), columns ko
         p.M = CRS; p.N = g.K; p.K = g.N * OHW; p.transposed = 1;
         p.A.base = (const uint8_t*)t1; p.A.rows = p.M; p.A.K = p.K; p.A.LY = g.H; p.A.LX = g.W;
@@ -468,7 +513,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t0; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, OHW, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(OHW, 1, g.K * OHW, 1, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS;
+        p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS; p.out.vec4 = 0;
     }
     p.Mw = p.transposed ? p.N : p.M;
     p.Nw = p.transposed ? p.M : p.N;
@@ -533,7 +578,7 @@ inline P8ConvProblem p8_gemm_problem(int transA, int transB, int M, int N, int K
     p.B.base = (const uint8_t*)B; p.B.rows = N; p.B.K = K; p.B.LY = 1; p.B.LX = 1;
     p.B.row = affine(1, 1, transB ? ldb : 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
     p.B.k = affine(1, 1, transB ? 1 : ldb, 0, 0, 0, 0, 0, 0, 0, 0, 0);
-    p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1;
+    p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1; p.out.vec4 = 0;
     p.Mw = M; p.Nw = N;
     p8_pick_mode(p.A);
     p8_pick_mode(p.B);
