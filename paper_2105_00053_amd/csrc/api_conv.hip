@@ -53,6 +53,8 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
     uint8_t* wbytes = (uint8_t*)wsp;
     pp.job[0].src = (const uint8_t*)srcA; pp.job[0].dst = (uint16_t*)wbytes;
     pp.job[1].src = (const uint8_t*)srcB; pp.job[1].dst = (uint16_t*)(wbytes + pp.bytes[0]);
+    pp.job[0].aligned = ((uintptr_t)srcA & 3u) == 0;
+    pp.job[1].aligned = ((uintptr_t)srcB & 3u) == 0;
     pp.A.base = pp.job[0].dst;
     pp.B.base = pp.job[1].dst;
     const int64_t work0 = (int64_t)pp.job[0].rows * (pp.job[0].pitch / 8), work1 = (int64_t)pp.job[1].rows * (pp.job[1].pitch / 8);

@@ -37,6 +37,7 @@ struct P8PreJob {
     int rows, pitch;           // dst shape
     int H, W, Hp, pad_t, pad_l;  // IMAGE (rows = planes * Hp)
     int K, C, RS;              // ROWS / WT
+    int aligned;               // src is 4-byte aligned: runs of 8 source bytes are fetched as aligned words
 };
 
 __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob j1) {
@@ -51,22 +52,37 @@ __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob
     for (int64_t w = (int64_t)blockIdx.x * 256 + t; w < total; w += (int64_t)gridDim.x * 256) {
         const int row = (int)(w / groups), c0 = (int)(w - (int64_t)row * groups) * 8;
         uint32_t d[4] = {0, 0, 0, 0};
-        if (job.kind == P8_PRE_IMAGE) {
-            const int plane = row / job.Hp, y = row - plane * job.Hp - job.pad_t;
-            if ((uint32_t)y < (uint32_t)job.H) {
-                const uint8_t* line = job.src + ((int64_t)plane * job.H + y) * job.W;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const int x = c0 + e - job.pad_l;
-                    const uint32_t v = ((uint32_t)x < (uint32_t)job.W) ? tab[line[x]] : 0u;
-                    d[e >> 1] |= v << (16 * (e & 1));
+        if (job.kind == P8_PRE_IMAGE || job.kind == P8_PRE_ROWS) {
+            // the 8 source bytes are consecutive: positions [jlo, jhi) of them exist
+            int64_t line;
+            int x0, width;
+            bool live = true;
+            if (job.kind == P8_PRE_IMAGE) {
+                const int plane = row / job.Hp, y = row - plane * job.Hp - job.pad_t;
+                live = (uint32_t)y < (uint32_t)job.H;
+                line = ((int64_t)plane * job.H + y) * job.W;
+                x0 = c0 - job.pad_l;
+                width = job.W;
+            } else {
+                line = (int64_t)row * job.K;
+                x0 = c0;
+                width = job.K;
+            }
+            int jlo = x0 < 0 ? -x0 : 0, jhi = width - x0 < 8 ? width - x0 : 8;
+            if (!live || jhi <= jlo) { jlo = 0; jhi = 0; }
+            uint32_t lo = 0, hi = 0;
+            if (job.aligned && line + x0 + 8 < ((int64_t)1 << 31) && line + x0 > -((int64_t)1 << 31)) {
+                p8_load_run8(job.src, (int)(line + x0), jlo, jhi, lo, hi);
+            } else {
+                for (int e = jlo; e < jhi; ++e) {
+                    const uint32_t b = job.src[line + x0 + e];
+                    if (e < 4) lo |= b << (8 * e); else hi |= b << (8 * (e - 4));
                 }
             }
-        } else if (job.kind == P8_PRE_ROWS) {
-            const uint8_t* line = job.src + (int64_t)row * job.K;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const uint32_t v = (c0 + e < job.K) ? tab[line[c0 + e]] : 0u;
+                const uint32_t b = ((e < 4 ? lo : hi) >> (8 * (e & 3))) & 0xFFu;
+                const uint32_t v = (e >= jlo && e < jhi) ? tab[b] : 0u;
                 d[e >> 1] |= v << (16 * (e & 1));
             }
         } else {
