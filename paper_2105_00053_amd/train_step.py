@@ -3,11 +3,12 @@
 Chains the library's entry points (convolution / linear forward, backward-data,
 backward-weight, ReLU, pooling, SGD update) so that a LeNet-5-shaped or
 CifarNet-shaped step runs without leaving the GPU.  Pure orchestration: every
-number is produced by a kernel of libpositnn_hip.so, except the softmax /
-cross-entropy gradient, for which the paper gives no posit algorithm: it is
-evaluated in float64 by torch on the device (logits -> float64 exactly,
-softmax, minus one-hot, divided by the batch) and rounded to posit<16,1> by
-posit_round.
+number is produced by a kernel of libpositnn_hip.so, the softmax cross-entropy
+gradient included (posit_cross_entropy in the posit<16,1> loss format).  The
+kernels of a step are issued on one stream: replaying the step as a captured
+graph, or moving the weight-gradient branch to a second stream, was measured
+and brought nothing (the step is bound by its many short kernels on the GPU,
+not by launches on the host, and cross-stream waits cost more than they hide).
 
 Formats (mixed precision of Sec. 3.3 / Fig. 3): activations, weight copies and
 back-propagated errors posit<8,0>; weight gradients rounded from the quire to
