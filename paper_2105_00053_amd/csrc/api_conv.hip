@@ -122,6 +122,10 @@ size_t conv_ws(int which, const ConvGeom& g) {
         const P8PrePlan pp = p8_pre_plan(which, g);
         if (pp.ok) b = p8_pre_ws_bytes(pp, p8_conv_plan(pp.M, pp.N, pp.K));
     }
+    if (which == 2) {  // the bias gradient runs after the weight gradient and reuses the start of the workspace
+        const size_t b2 = bias_grad_ws_bytes<F>(g.N, g.K, g.OH * g.OW);
+        if (b2 > b) b = b2;
+    }
     return b;
 }
 
@@ -186,16 +190,17 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(2, g);
     const bool fastp8 = (F::N == 8 && F::ES == 0) && p8_conv_eligible(2, g);
+    const size_t bias_ws = bias_grad_ws_bytes<F>(g.N, g.K, g.OH * g.OW);
     GemmPlan plan = conv_plan<F>(d);
     P8ConvProblem p8p;
     if (fastp8) {
         const P8PrePlan pp = p8_pre_plan(2, g);
         if (pp.ok) {
             const GemmPlan pplan = p8_conv_plan(pp.M, pp.N, pp.K);
-            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan)) return PNN_EWORKSPACE;
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan) || (dbias && ws_bytes < bias_ws)) return PNN_EWORKSPACE;
             RowMajorOut pout{d.N};
             hipError_t pe = p8_pre_launch(st, pp, x, dy, nullptr, dw, fout, ws, pplan, pout);  // operand A is x, B is dy
-            if (pe == hipSuccess && dbias) pe = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW);
+            if (pe == hipSuccess && dbias) pe = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW, ws);
             return hip_status(pe);
         }
     }
@@ -204,6 +209,7 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
         plan = p8_conv_plan(p8p.M, p8p.N, p8p.K);
     }
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+    if (dbias && bias_ws > 0 && (!ws || ws_bytes < bias_ws)) return PNN_EWORKSPACE;
     ConvBwdWeightDy<T> a{(const T*)dy, g, d.M, d.K};
     ConvBwdWeightX<T> b{(const T*)x, g, d.N, d.K};
     RowMajorOut out{d.N};
@@ -213,8 +219,8 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     else
         e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
             st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
-    // dbias[k] = sum dy[n,k,:,:] * 1 : one quire per channel
-    if (e == hipSuccess && dbias) e = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW);
+    // dbias[k] = sum dy[n,k,:,:] * 1 : one quire per channel; its slice partials reuse the workspace (stream order)
+    if (e == hipSuccess && dbias) e = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW, ws);
     return hip_status(e);
 }
 

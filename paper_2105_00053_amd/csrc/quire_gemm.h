@@ -368,46 +368,59 @@ __global__ __launch_bounds__(256) void split_merge_kernel(SplitWs ws, int splits
 }
 
 // Bias gradient of a convolution (the row sum of the backward-weight pass against a column of
-// ones): dbias[k] = round_fout( sum_{n,i} dy[n][k][i] * 1 ), one quire per channel.  One
-// workgroup per channel; every thread adds 16-byte runs of the channel's planes into a private
-// quire, the 256 private quires are merged pairwise through LDS (exact: integer addition), and
-// thread 0 rounds once.
+// ones): dbias[k] = round_fout( sum_{n,i} dy[n][k][i] * 1 ), one quire per channel.  Workgroup
+// (k, s) sums slice s of the batch for channel k: every thread adds 16-byte runs of the channel's
+// planes into a private quire (posit<8,0> decodes through an LDS table), the 256 private quires
+// are merged pairwise through LDS (exact: integer addition).  With one slice thread 0 rounds and
+// stores; with several, the slice's quire and NaR flag go to the workspace and
+// bias_grad_finish_kernel merges the slices of a channel and rounds once.
 template <class FIN>
 __global__ __launch_bounds__(256) void bias_grad_kernel(const typename Storage<FIN::N>::T* __restrict__ dy, void* __restrict__ dbias,
-                                                        int fout, int batch, int channels, int spatial, int vec) {
+                                                        int fout, int batch, int channels, int spatial, int vec, int batch_per_slice,
+                                                        uint32_t* __restrict__ partial) {
     typedef Arith<FIN> AR;
     typedef typename Storage<FIN::N>::T T;
     constexpr int L = AR::L;
     constexpr int V = 16 / (int)sizeof(T);
+    constexpr bool TABLE = FIN::N == 8 && FIN::ES == 0;
     __shared__ uint32_t part[128][L];
     __shared__ uint32_t nar_s;
+    __shared__ int32_t tab[TABLE ? 256 : 1];
     const int k = blockIdx.x, t = threadIdx.x;
+    const int n_lo = blockIdx.y * batch_per_slice;
+    const int n_hi = n_lo + batch_per_slice < batch ? n_lo + batch_per_slice : batch;
+    const int nb = n_hi > n_lo ? n_hi - n_lo : 0;
     uint32_t q[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) q[l] = 0;
     bool nar = false;
     if (t == 0) nar_s = 0;
+    if constexpr (TABLE) {
+        tab[t] = (int32_t)AR::stage((uint32_t)t);
+        __syncthreads();
+    }
+    auto add = [&](uint32_t v) {
+        if (v == FIN::NAR) nar = true;
+        else if constexpr (TABLE) q[0] += (uint32_t)tab[v] << FIN::MAXS;
+        else AR::add_value(q, AR::stage(v));
+    };
     if (vec) {  // spatial is a multiple of V and the tensor is 16-byte aligned
         const int per_plane = spatial / V;
-        const int chunks = batch * per_plane;
+        const int chunks = nb * per_plane;
+#pragma unroll 4
         for (int c = t; c < chunks; c += 256) {
             const int n = c / per_plane, i = (c - n * per_plane) * V;
-            const uint4 w = *reinterpret_cast<const uint4*>(dy + ((int64_t)n * channels + k) * spatial + i);
+            const uint4 w = *reinterpret_cast<const uint4*>(dy + ((int64_t)(n_lo + n) * channels + k) * spatial + i);
             const uint32_t words[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
-            for (int e = 0; e < V; ++e) {
-                const uint32_t v = (words[e * (int)sizeof(T) / 4] >> (8 * ((e * (int)sizeof(T)) & 3))) & (uint32_t)(T)~(T)0;
-                if (v == FIN::NAR) nar = true;
-                else AR::add_value(q, AR::stage(v));
-            }
+            for (int e = 0; e < V; ++e)
+                add((words[e * (int)sizeof(T) / 4] >> (8 * ((e * (int)sizeof(T)) & 3))) & (uint32_t)(T)~(T)0);
         }
     } else {
-        const int total = batch * spatial;
+        const int total = nb * spatial;
         for (int e = t; e < total; e += 256) {
             const int n = e / spatial, i = e - n * spatial;
-            const uint32_t v = dy[((int64_t)n * channels + k) * spatial + i];
-            if (v == FIN::NAR) nar = true;
-            else AR::add_value(q, AR::stage(v));
+            add(dy[((int64_t)(n_lo + n) * channels + k) * spatial + i]);
         }
     }
     __syncthreads();
@@ -426,16 +439,71 @@ __global__ __launch_bounds__(256) void bias_grad_kernel(const typename Storage<F
         }
         __syncthreads();
     }
-    if (t == 0) round_store<QuireAccum<FIN>, L>(q, nar_s != 0, fout, dbias, k);
+    if (t != 0) return;
+    if (gridDim.y == 1) {
+        round_store<QuireAccum<FIN>, L>(q, nar_s != 0, fout, dbias, k);
+    } else {  // [slice][channel][L limbs + flag]
+        uint32_t* slot = partial + ((int64_t)blockIdx.y * channels + k) * (L + 1);
+#pragma unroll
+        for (int l = 0; l < L; ++l) slot[l] = q[l];
+        slot[L] = nar_s;
+    }
 }
 
 template <class FIN>
-hipError_t launch_bias_grad(hipStream_t stream, const void* dy, void* dbias, int fout, int batch, int channels, int spatial) {
+__global__ __launch_bounds__(256) void bias_grad_finish_kernel(const uint32_t* __restrict__ partial, int slices, int channels,
+                                                               void* __restrict__ dbias, int fout) {
+    constexpr int L = Arith<FIN>::L;
+    const int k = blockIdx.x * 256 + threadIdx.x;
+    if (k >= channels) return;
+    uint32_t q[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) q[l] = 0;
+    uint32_t nar = 0;
+    for (int s = 0; s < slices; ++s) {
+        const uint32_t* slot = partial + ((int64_t)s * channels + k) * (L + 1);
+        uint32_t o[L];
+#pragma unroll
+        for (int l = 0; l < L; ++l) o[l] = slot[l];
+        quire_merge<L>(q, o);
+        nar |= slot[L];
+    }
+    round_store<QuireAccum<FIN>, L>(q, nar != 0, fout, dbias, k);
+}
+
+// Slices of the batch per channel: enough workgroups to occupy the chip, at least 8192 elements each.
+inline int bias_grad_slices(int batch, int channels, int spatial) {
+    if (channels <= 0 || batch <= 1) return 1;
+    int want = (512 + channels - 1) / channels;
+    const int64_t per_channel = (int64_t)batch * spatial;
+    const int64_t by_work = per_channel / 8192;
+    if (want > by_work) want = (int)by_work;
+    if (want > batch) want = batch;
+    if (want > 64) want = 64;
+    return want < 1 ? 1 : want;
+}
+
+template <class FIN>
+size_t bias_grad_ws_bytes(int batch, int channels, int spatial) {
+    const int s = bias_grad_slices(batch, channels, spatial);
+    return s > 1 ? (size_t)s * channels * (Arith<FIN>::L + 1) * sizeof(uint32_t) : 0;
+}
+
+// `partial` must hold bias_grad_ws_bytes<FIN>() bytes (may be null when that is 0).
+template <class FIN>
+hipError_t launch_bias_grad(hipStream_t stream, const void* dy, void* dbias, int fout, int batch, int channels, int spatial,
+                            void* partial) {
     typedef typename Storage<FIN::N>::T T;
     constexpr int V = 16 / (int)sizeof(T);
     const int vec = (spatial % V == 0) && (((uintptr_t)dy) % 16 == 0);
-    hipLaunchKernelGGL(bias_grad_kernel<FIN>, dim3((unsigned)channels), dim3(256), 0, stream, (const T*)dy, dbias, fout, batch, channels,
-                       spatial, vec);
+    const int slices = bias_grad_slices(batch, channels, spatial);
+    const int per = (batch + slices - 1) / slices;
+    const int used = per > 0 ? (batch + per - 1) / per : 1;  // slices that actually hold images
+    hipLaunchKernelGGL(bias_grad_kernel<FIN>, dim3((unsigned)channels, (unsigned)(slices > 1 ? used : 1)), dim3(256), 0, stream,
+                       (const T*)dy, dbias, fout, batch, channels, spatial, vec, slices > 1 ? per : batch, (uint32_t*)partial);
+    if (slices > 1)
+        hipLaunchKernelGGL(bias_grad_finish_kernel<FIN>, dim3((unsigned)((channels + 255) / 256)), dim3(256), 0, stream,
+                           (const uint32_t*)partial, used, channels, dbias, fout);
     return hipGetLastError();
 }
 

@@ -300,6 +300,23 @@ def test_conv_bwd_weight_long_reduction_splits():
     _assert_equal(to_np(db, "p16"), wdb, "split dbias")
 
 
+@pytest.mark.parametrize("fin,fout", [("p8", "p16"), ("p16", "p16"), ("p8_2", "p12_2"), ("p32", "p32")])
+def test_bias_gradient_over_batch_slices(fin, fout):
+    """Enough images that the bias-gradient reduction is cut into slices of the batch and merged;
+    one channel carries a NaR, one sums to a large value."""
+    d = dict(N=24, C=1, H=32, W=32, K=3, R=1, S=1)
+    desc = _desc(d)
+    rng = np.random.default_rng(BITS[fin] + 77)
+    x = rand_patterns(rng, (24, 1, 32, 32), fin, special=0.0, allow_nar=False)
+    dy = rand_patterns(rng, (24, 3, 32, 32), fin, special=0.0, allow_nar=False)
+    dy[17, 1, 5, 9] = 1 << (BITS[fin] - 1)
+    dy[:, 2] = (1 << (BITS[fin] - 2)) + 3  # all slightly above one: the sum is about N * OH * OW
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dy), to_dev(x), desc, fin, fout, with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True)
+    _assert_equal(to_np(db, fout), wdb, "sliced dbias")
+    _assert_equal(to_np(dw, fout), wdw, "bwd_weight")
+
+
 # ---------------- layer glue ----------------
 
 @pytest.mark.parametrize("fmt", ["p8", "p16", "p32"])
