@@ -157,6 +157,97 @@ __global__ __launch_bounds__(256) void cross_entropy_kernel(FmtRT fz, FmtRT fg, 
     }
 }
 
+// The same computation with one lane per (row, class): CP = the power of two >= classes lanes serve a
+// row, 256 / CP rows are in flight per pass, the first lane of a row does the row's serial parts
+// (maximum, exact sum of the exponentials, row loss).  For classes <= 256; same results as
+// cross_entropy_kernel, which serves wider rows.
+template <class FL>
+__global__ __launch_bounds__(256) void cross_entropy_lanes_kernel(FmtRT fz, FmtRT fg, int B, int C, int CP, const void* __restrict__ logits,
+                                                                  const int32_t* __restrict__ labels, void* __restrict__ loss,
+                                                                  void* __restrict__ dlogits) {
+    typedef Arith<FL> AR;
+    constexpr int L = AR::L;
+    __shared__ uint32_t part[128][L];
+    __shared__ uint32_t bad_s;
+    __shared__ uint32_t zs[256], ts[256], es[256];  // per lane: converted logit, logit - max, its exponential
+    __shared__ uint32_t Ms[256], Ss[256], rowbad[256];  // per row in flight: maximum, rounded sum, NaR / bad label
+    const int t = threadIdx.x;
+    if (t == 0) bad_s = 0;
+    uint32_t ql[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) ql[l] = 0;
+    bool bad = false;
+    const uint32_t one = 1u << (FL::N - 2);
+    const int zb = fz.bytes(), gb = fg.bytes();
+    const int R = 256 / CP, rl = t / CP, j = t - rl * CP;
+    const int first = rl * CP;
+    for (int b0 = 0; b0 < B; b0 += R) {
+        const int b = b0 + rl;
+        const bool row_live = b < B, active = row_live && j < C;
+        const int64_t at = (int64_t)b * C + j;
+        const uint32_t z = active ? convert_in<FL>(load_pattern(logits, at, zb), fz) : 0u;
+        const int label = row_live ? labels[b] : 0;
+        zs[t] = z;
+        __syncthreads();
+        if (j == 0 && row_live) {
+            bool rn = label < 0 || label >= C;
+            uint32_t m = 0;
+            for (int jj = 0; jj < C; ++jj) {
+                const uint32_t zz = zs[first + jj];
+                if (zz == FL::NAR) rn = true;
+                else if (jj == 0 || ordered<FL>(zz) > ordered<FL>(m)) m = zz;
+            }
+            rowbad[rl] = rn;
+            Ms[rl] = m;
+        }
+        __syncthreads();
+        const bool rn = row_live && rowbad[rl] != 0;
+        uint32_t e = 0;
+        if (active && !rn) {
+            const uint32_t tj = posit_add<FL>(z, negate<FL>(Ms[rl]));
+            e = posit_unary<FL>(UNARY_EXP, tj);
+            ts[t] = tj;
+            es[t] = e;
+        }
+        __syncthreads();
+        if (j == 0 && row_live) {
+            if (rn) {
+                bad = true;
+            } else {
+                uint32_t qs[L];
+#pragma unroll
+                for (int l = 0; l < L; ++l) qs[l] = 0;
+                for (int jj = 0; jj < C; ++jj) AR::add_value(qs, AR::stage(es[first + jj]));
+                const uint32_t S = quire_round<FL, FL, L>(qs);
+                Ss[rl] = S;
+                const uint32_t row_loss = posit_add<FL>(posit_unary<FL>(UNARY_LOG, S), negate<FL>(ts[first + label]));
+                AR::add_value(ql, AR::stage(row_loss));
+            }
+        }
+        __syncthreads();
+        if (active && dlogits) {
+            uint32_t out = fg.nar();
+            if (!rn) {
+                const uint32_t p = posit_div<FL>(e, Ss[rl]);
+                const uint32_t g = posit_add<FL>(p, j == label ? negate<FL>(one) : 0u);
+                out = scaled_out<FL>(g, 0, (uint32_t)B, fg);
+            }
+            store_pattern(dlogits, at, gb, out);
+        }
+    }
+    __syncthreads();
+    if (bad) bad_s = 1;  // every writer stores the same value
+    block_merge<L>(ql, part, t);
+    if (t == 0 && loss) {
+        uint32_t res = FL::NAR;
+        if (!bad_s) {
+            Real r;
+            res = quire_read<FL, L>(ql, r) ? encode<FL>(real_div_int(r, (uint32_t)B)) : 0u;
+        }
+        store_pattern(loss, 0, FL::N <= 8 ? 1 : 2, res);
+    }
+}
+
 template <class FL>
 __global__ __launch_bounds__(256) void mse_kernel(FmtRT fp, FmtRT fg, int64_t n, const void* __restrict__ pred,
                                                   const void* __restrict__ target, void* __restrict__ loss, void* __restrict__ dpred) {
@@ -241,8 +332,15 @@ extern "C" int posit_cross_entropy(void* stream, int f_logits, int f_loss, int f
     if (!logits || !labels || (!loss && !dlogits)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     const FmtRT fz = fmt_of_code(f_logits), fg = fmt_of_code(f_grad);
-    PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_kernel<F>, dim3(1), dim3(256), 0, st, fz, fg, (int)batch, (int)classes, logits,
-                                                  labels, loss, dlogits))
+    if (classes <= 256) {
+        int cp = 1;
+        while (cp < classes) cp *= 2;
+        PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_lanes_kernel<F>, dim3(1), dim3(256), 0, st, fz, fg, (int)batch, (int)classes,
+                                                      cp, logits, labels, loss, dlogits))
+    } else {
+        PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_kernel<F>, dim3(1), dim3(256), 0, st, fz, fg, (int)batch, (int)classes,
+                                                      logits, labels, loss, dlogits))
+    }
     return hip_status(hipGetLastError());
 }
 

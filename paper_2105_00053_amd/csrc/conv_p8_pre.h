@@ -38,6 +38,7 @@ struct P8PreJob {
     int H, W, Hp, pad_t, pad_l;  // IMAGE (rows = planes * Hp)
     int K, C, RS;              // ROWS / WT
     int aligned;               // src is 4-byte aligned: runs of 8 source bytes are fetched as aligned words
+    FastDiv by_groups, by_hp;  // divisions by pitch / 8 and by Hp
 };
 
 __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob j1) {
@@ -48,9 +49,9 @@ __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob
     __syncthreads();
     if (job.kind == P8_PRE_NONE) return;
     const int groups = job.pitch / 8;
-    const int64_t total = (int64_t)job.rows * groups;
-    for (int64_t w = (int64_t)blockIdx.x * 256 + t; w < total; w += (int64_t)gridDim.x * 256) {
-        const int row = (int)(w / groups), c0 = (int)(w - (int64_t)row * groups) * 8;
+    const uint32_t total = (uint32_t)job.rows * (uint32_t)groups;  // rows * pitch < 2^30 is checked on the host
+    for (uint32_t w = blockIdx.x * 256u + t; w < total; w += gridDim.x * 256u) {
+        const int row = (int)job.by_groups.div(w), c0 = (int)(w - (uint32_t)row * (uint32_t)groups) * 8;
         uint32_t d[4] = {0, 0, 0, 0};
         if (job.kind == P8_PRE_IMAGE || job.kind == P8_PRE_ROWS) {
             // the 8 source bytes are consecutive: positions [jlo, jhi) of them exist
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob
             int x0, width;
             bool live = true;
             if (job.kind == P8_PRE_IMAGE) {
-                const int plane = row / job.Hp, y = row - plane * job.Hp - job.pad_t;
+                const int plane = (int)job.by_hp.div((uint32_t)row), y = row - plane * job.Hp - job.pad_t;
                 live = (uint32_t)y < (uint32_t)job.H;
                 line = ((int64_t)plane * job.H + y) * job.W;
                 x0 = c0 - job.pad_l;
@@ -393,6 +394,9 @@ inline P8PrePlan p8_pre_plan(int which, const ConvGeom& g) {
         p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS; p.out.vec4 = 0;
     }
     // a run may start up to 31 elements before the end of the last row and always reads 8: keep 64 bytes of slack
+    if ((int64_t)ja.rows * ja.pitch >= lim || (int64_t)jb.rows * jb.pitch >= lim) return p;
+    ja.by_groups = make_fastdiv((uint32_t)(ja.pitch / 8)); ja.by_hp = make_fastdiv((uint32_t)(ja.Hp > 0 ? ja.Hp : 1));
+    jb.by_groups = make_fastdiv((uint32_t)(jb.pitch / 8)); jb.by_hp = make_fastdiv(1);
     p.bytes[0] = round_up((size_t)ja.rows * ja.pitch * 2 + 64, 256);
     p.bytes[1] = round_up((size_t)jb.rows * jb.pitch * 2 + 64, 256);
     p.Mw = p.transposed ? p.N : p.M;

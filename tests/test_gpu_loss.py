@@ -47,7 +47,8 @@ def _logits(rng, B, C, fmt, scale):
 
 
 @pytest.mark.parametrize("fz,fl,fg,B,C,scale", [("p8", "p16", "p16", 64, 10, 2.0), ("p8_2", "p12_2", "p12_2", 128, 10, 3.0), ("p8_2", "p10_2", "p12_2", 37, 10, 1.0),
-                                                 ("p16", "p16", "p8", 300, 7, 5.0), ("p8_2", "p8_2", "p8_2", 16, 3, 1.0), ("p12_1", "p12_1", "p16", 5, 100, 2.0),
+                                                 ("p16", "p16", "p8", 300, 7, 5.0), ("p8_2", "p8_2", "p8_2", 16, 3, 1.0), ("p12_1", "p12_1", "p16", 5, 100, 2.0), ("p8_2", "p12_2", "p12_2", 9, 256, 2.0),
+                                                 ("p8", "p16", "p16", 3, 300, 2.0), ("p10_2", "p10_2", "p10_2", 70, 16, 2.0),
                                                  ("p8", "p8", "p8", 1, 1, 1.0)])
 def test_cross_entropy(fz, fl, fg, B, C, scale):
     rng = np.random.default_rng(B * 31 + C)
