@@ -21,6 +21,58 @@ __global__ __launch_bounds__(256) void relu_kernel(const T* __restrict__ x, T* _
     y[i] = (T)((as_signed(p, nbits) > 0 || p == (1u << (nbits - 1))) ? p : 0u);
 }
 
+// 16 bytes per thread; n16 = number of whole 16-byte groups (pointers 16-byte aligned)
+template <class T>
+__global__ __launch_bounds__(256) void relu_vec_kernel(const uint4* __restrict__ x, uint4* __restrict__ y, int64_t n16, int nbits) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n16) return;
+    constexpr int PER = 4 / (int)sizeof(T);  // elements per 32-bit word
+    constexpr int EB = 8 * (int)sizeof(T);
+    const uint32_t mask = nbits == 32 ? 0xFFFFFFFFu : ((1u << nbits) - 1u);
+    const uint4 v = x[i];
+    uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t o = 0;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const uint32_t p = (PER == 1 ? w[q] : (w[q] >> (EB * e))) & mask;
+            const uint32_t r = (as_signed(p, nbits) > 0 || p == (1u << (nbits - 1))) ? p : 0u;
+            o |= PER == 1 ? r : (r << (EB * e));
+        }
+        w[q] = o;
+    }
+    y[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
+// same-width forward output and gradient (the common case): 16 bytes of each per thread
+template <class T>
+__global__ __launch_bounds__(256) void relu_bwd_vec_kernel(const uint4* __restrict__ yf, const uint4* __restrict__ dy, uint4* __restrict__ dx,
+                                                           int64_t n16, int ybits, int dbits) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n16) return;
+    constexpr int PER = 4 / (int)sizeof(T);
+    constexpr int EB = 8 * (int)sizeof(T);
+    const uint32_t ymask = ybits == 32 ? 0xFFFFFFFFu : ((1u << ybits) - 1u);
+    const uint32_t emask = EB == 32 ? 0xFFFFFFFFu : ((1u << EB) - 1u);
+    const uint4 a = yf[i], b = dy[i];
+    const uint32_t ya[4] = {a.x, a.y, a.z, a.w}, da[4] = {b.x, b.y, b.z, b.w};
+    uint32_t w[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t o = 0;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) {
+            const uint32_t yv = (PER == 1 ? ya[q] : (ya[q] >> (EB * e))) & ymask;
+            const uint32_t dv = (PER == 1 ? da[q] : (da[q] >> (EB * e))) & emask;
+            const uint32_t r = yv == (1u << (ybits - 1)) ? (1u << (dbits - 1)) : (as_signed(yv, ybits) > 0 ? dv : 0u);
+            o |= PER == 1 ? r : (r << (EB * e));
+        }
+        w[q] = o;
+    }
+    dx[i] = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 template <class TY, class TD>
 __global__ __launch_bounds__(256) void relu_bwd_kernel(const TY* __restrict__ yf, const TD* __restrict__ dy, TD* __restrict__ dx, int64_t n,
                                                        int ybits, int dbits) {
@@ -172,7 +224,17 @@ extern "C" int posit_relu(void* stream, int fmt, int64_t n, const void* x, void*
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(relu_kernel<T>, dim3(blocks_for(n)), dim3(256), 0, st, (const T*)x, (T*)y, n, bits_of(fmt)))
+    int64_t done = 0;  // elements covered by the 16-byte kernel
+    if (aligned(x, 16) && aligned(y, 16)) {
+        const int64_t per16 = 16 / (int64_t)elem_size(fmt), n16 = n / per16;
+        if (n16 > 0)
+            PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(relu_vec_kernel<T>, dim3(blocks_for(n16)), dim3(256), 0, st, (const uint4*)x, (uint4*)y,
+                                                   n16, bits_of(fmt)))
+        done = n16 * per16;
+    }
+    if (done < n)
+        PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(relu_kernel<T>, dim3(blocks_for(n - done)), dim3(256), 0, st, (const T*)x + done,
+                                               (T*)y + done, n - done, bits_of(fmt)))
     return hip_status(hipGetLastError());
 }
 
@@ -181,7 +243,20 @@ extern "C" int posit_relu_bwd(void* stream, int fmt_y, int fmt_d, int64_t n, con
     if (n == 0) return PNN_OK;
     if (!y_fwd || !dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
-    PNN_BY_STORAGE(fmt_y, relu_bwd_pick<T>(st, fmt_y, fmt_d, n, y_fwd, dy, dx))
+    int64_t done = 0;
+    if (elem_size(fmt_y) == elem_size(fmt_d) && aligned(y_fwd, 16) && aligned(dy, 16) && aligned(dx, 16)) {
+        const int64_t per16 = 16 / (int64_t)elem_size(fmt_d), n16 = n / per16;
+        if (n16 > 0)
+            PNN_BY_STORAGE(fmt_d, hipLaunchKernelGGL(relu_bwd_vec_kernel<T>, dim3(blocks_for(n16)), dim3(256), 0, st, (const uint4*)y_fwd,
+                                                     (const uint4*)dy, (uint4*)dx, n16, bits_of(fmt_y), bits_of(fmt_d)))
+        done = n16 * per16;
+    }
+    if (done < n) {
+        const char* yb = (const char*)y_fwd + done * (int64_t)elem_size(fmt_y);
+        const char* db = (const char*)dy + done * (int64_t)elem_size(fmt_d);
+        char* xb = (char*)dx + done * (int64_t)elem_size(fmt_d);
+        PNN_BY_STORAGE(fmt_y, relu_bwd_pick<T>(st, fmt_y, fmt_d, n - done, yb, db, xb))
+    }
     return hip_status(hipGetLastError());
 }
 
