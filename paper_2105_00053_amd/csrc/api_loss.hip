@@ -26,14 +26,24 @@ __device__ __forceinline__ uint32_t convert_in(uint32_t p, const FmtRT& fs) {
     return encode<F>(decode_rt(p, fs));
 }
 
-// posit<F> value divided by an integer and rounded once to run-time format fd; 2^pow2 scales first
+// posit<F> value times 2^pow2 divided by an integer and rounded once to run-time format fd.  F has at
+// most 16 bits: the significand has at most 14 bits, so one 64-bit division gives a quotient of at
+// least 18 + 31 significant bits and a remainder that decides "sticky".
 template <class F>
 __device__ __forceinline__ uint32_t scaled_out(uint32_t g, int pow2, uint32_t divisor, const FmtRT& fd) {
     if (g == F::NAR) return fd.nar();
     if (g == 0) return 0u;
-    Real r = decode_fields<F>(g);
-    r.scale += pow2;
-    return encode_rt(real_div_int(r, divisor), fd);
+    const Real32 r = decode_fields32<F>(g);
+    const uint64_t sig = (1u << 14) | (r.frac >> 18);       // 1.fraction with 14 fraction bits
+    const uint64_t num = sig << 49;                           // < 2^64
+    const uint64_t q = num / divisor, rem = num - q * divisor;  // divisor < 2^32: q >= 2^31
+    const int top = 63 - clz64(q);
+    Real o;
+    o.neg = r.neg;
+    o.scale = r.scale + pow2 + (top - 63);  // num = sig * 2^49 = value * 2^(63 - scale)
+    o.frac = top == 0 ? 0 : (q << (64 - top));
+    o.sticky = rem != 0;
+    return encode_rt(o, fd);
 }
 
 template <class F>
@@ -181,7 +191,8 @@ __global__ __launch_bounds__(256) void cross_entropy_lanes_kernel(FmtRT fz, FmtR
     const int zb = fz.bytes(), gb = fg.bytes();
     const int R = 256 / CP, rl = t / CP, j = t - rl * CP;
     const int first = rl * CP;
-    for (int b0 = 0; b0 < B; b0 += R) {
+    // several workgroups share the rows when only the gradient is wanted (the host passes loss == null then)
+    for (int b0 = blockIdx.x * R; b0 < B; b0 += gridDim.x * R) {
         const int b = b0 + rl;
         const bool row_live = b < B, active = row_live && j < C;
         const int64_t at = (int64_t)b * C + j;
@@ -335,8 +346,14 @@ extern "C" int posit_cross_entropy(void* stream, int f_logits, int f_loss, int f
     if (classes <= 256) {
         int cp = 1;
         while (cp < classes) cp *= 2;
-        PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_lanes_kernel<F>, dim3(1), dim3(256), 0, st, fz, fg, (int)batch, (int)classes,
-                                                      cp, logits, labels, loss, dlogits))
+        // the mean over the batch is reduced inside one workgroup; without it the rows are independent
+        int64_t blocks = 1;
+        if (!loss) {
+            blocks = (batch * cp + 255) / 256;
+            if (blocks > 256) blocks = 256;
+        }
+        PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_lanes_kernel<F>, dim3((unsigned)blocks), dim3(256), 0, st, fz, fg, (int)batch,
+                                                      (int)classes, cp, logits, labels, loss, dlogits))
     } else {
         PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(cross_entropy_kernel<F>, dim3(1), dim3(256), 0, st, fz, fg, (int)batch, (int)classes,
                                                       logits, labels, loss, dlogits))
