@@ -91,6 +91,14 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
     return hipGetLastError();
 }
 
+// The pre-decoded path serves this pass: geometry fits, and no split reduction over padded rows.
+inline bool p8_pre_usable(int which, const ConvGeom& g, P8PrePlan* pp, GemmPlan* plan) {
+    *pp = p8_pre_plan(which, g);
+    if (!pp->ok) return false;
+    *plan = p8_conv_plan(pp->M, pp->N, pp->K);
+    return !(pp->padded_rows && plan->splits > 1);
+}
+
 // workspace of the pre-decoded path: the two rewritten operands, then the split partials
 inline size_t p8_pre_ws_bytes(const P8PrePlan& pp, const GemmPlan& plan) { return pp.bytes[0] + pp.bytes[1] + plan.ws_bytes; }
 
@@ -119,8 +127,9 @@ size_t conv_ws(int which, const ConvGeom& g) {
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(which, g)) {
         const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
         b = p8_conv_plan(p.M, p.N, p.K).ws_bytes;
-        const P8PrePlan pp = p8_pre_plan(which, g);
-        if (pp.ok) b = p8_pre_ws_bytes(pp, p8_conv_plan(pp.M, pp.N, pp.K));
+        P8PrePlan pp;
+        GemmPlan pplan;
+        if (p8_pre_usable(which, g, &pp, &pplan)) b = p8_pre_ws_bytes(pp, pplan);
     }
     if (which == 2) {  // the bias gradient runs after the weight gradient and reuses the start of the workspace
         const size_t b2 = bias_grad_ws_bytes<F>(g.N, g.K, g.OH * g.OW);
@@ -135,12 +144,12 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(0, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(0, g)) {
-        const P8PrePlan pp = p8_pre_plan(0, g);
-        if (pp.ok) {
-            const GemmPlan plan = p8_conv_plan(pp.M, pp.N, pp.K);
-            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, plan)) return PNN_EWORKSPACE;
+        P8PrePlan pp;
+        GemmPlan pplan;
+        if (p8_pre_usable(0, g, &pp, &pplan)) {
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan)) return PNN_EWORKSPACE;
             NchwOut mout{(int64_t)g.OH * g.OW, (int64_t)g.K};
-            return hip_status(p8_pre_launch(st, pp, x, w, (const uint8_t*)bias, y, fout, ws, plan, mout));
+            return hip_status(p8_pre_launch(st, pp, x, w, (const uint8_t*)bias, y, fout, ws, pplan, mout));
         }
         const P8ConvProblem p = p8_problem(0, g, x, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
@@ -162,12 +171,12 @@ int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, c
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(1, g)) {
-        const P8PrePlan pp = p8_pre_plan(1, g);
-        if (pp.ok) {
-            const GemmPlan plan = p8_conv_plan(pp.M, pp.N, pp.K);
-            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, plan)) return PNN_EWORKSPACE;
+        P8PrePlan pp;
+        GemmPlan pplan;
+        if (p8_pre_usable(1, g, &pp, &pplan)) {
+            if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan)) return PNN_EWORKSPACE;
             NchwOut mout{(int64_t)g.H * g.W, (int64_t)g.C};
-            return hip_status(p8_pre_launch(st, pp, dy, w, nullptr, dx, fout, ws, plan, mout));
+            return hip_status(p8_pre_launch(st, pp, dy, w, nullptr, dx, fout, ws, pplan, mout));
         }
         const P8ConvProblem p = p8_problem(1, g, dy, w);
         const GemmPlan plan = p8_conv_plan(p.M, p.N, p.K);
@@ -194,9 +203,9 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     GemmPlan plan = conv_plan<F>(d);
     P8ConvProblem p8p;
     if (fastp8) {
-        const P8PrePlan pp = p8_pre_plan(2, g);
-        if (pp.ok) {
-            const GemmPlan pplan = p8_conv_plan(pp.M, pp.N, pp.K);
+        P8PrePlan pp;
+        GemmPlan pplan;
+        if (p8_pre_usable(2, g, &pp, &pplan)) {
             if (!ws || ws_bytes < p8_pre_ws_bytes(pp, pplan) || (dbias && ws_bytes < bias_ws)) return PNN_EWORKSPACE;
             RowMajorOut pout{d.N};
             hipError_t pe = p8_pre_launch(st, pp, x, dy, nullptr, dw, fout, ws, pplan, pout);  // operand A is x, B is dy

@@ -85,10 +85,24 @@ struct P8ConvOut {
     int64_t m1, m0;      // mpart = c1 * m1 + c0 * m0
     int64_t nstride;
     int vec4;            // rows 4q .. 4q+3 of one column are four consecutive bytes at a multiple of four
-    PNN_HD int64_t at(int m, int n) const {
+    // rows laid out over a padded width: c0 = r * wd.d + col, only col < wvalid exists and then
+    // c0 stands for r * wvalid + col (wpad = 0: c0 is used as it is)
+    int wpad, wvalid;
+    FastDiv wd;
+    // the part of the index that depends on the row; -1: the row is padding and has no output element
+    PNN_HD int64_t row_part(int m) const {
         const uint32_t c1 = md.div((uint32_t)m);
-        const uint32_t c0 = (uint32_t)m - c1 * md.d;
-        return (int64_t)c1 * m1 + (int64_t)c0 * m0 + (int64_t)n * nstride;
+        uint32_t c0 = (uint32_t)m - c1 * md.d;
+        if (wpad) {
+            const uint32_t r = wd.div(c0), col = c0 - r * wd.d;
+            if (col >= (uint32_t)wvalid) return -1;
+            c0 = r * (uint32_t)wvalid + col;
+        }
+        return (int64_t)c1 * m1 + (int64_t)c0 * m0;
+    }
+    PNN_HD int64_t at(int m, int n) const {
+        const int64_t rp = row_part(m);
+        return rp < 0 ? -1 : rp + (int64_t)n * nstride;
     }
 };
 
@@ -259,6 +273,8 @@ __device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], c
             const int lr = ig * (TY * 4) + ty * 4;
             const int m = m0 + lr;
             if (m >= M) continue;  // M is a multiple of four here: the four rows are all inside or all outside
+            const int64_t rp = out.row_part(m);
+            if (rp < 0) continue;  // so are the four columns of a padded width (a multiple of four too)
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const int lc = (j >> 2) * (TX * 4) + tx * 4 + (j & 3);
@@ -277,7 +293,7 @@ __device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], c
                     const bool nar = cnar || rowNaR[lr + r] != 0;
                     word |= (nar ? 0x80u : p8_round_quire(acc[ig * 4 + r][j] + badd)) << (8 * r);
                 }
-                *reinterpret_cast<uint32_t*>((uint8_t*)C + out.at(m, n)) = word;
+                *reinterpret_cast<uint32_t*>((uint8_t*)C + rp + (int64_t)n * out.nstride) = word;
             }
         }
         return;
@@ -288,6 +304,8 @@ __device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], c
         const int m = m0 + lr;
         if (m >= M) continue;
         const bool rnar = rowNaR[lr] != 0;
+        const int64_t rp = gridDim.z == 1 ? out.row_part(m) : 0;
+        if (rp < 0) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int lc = (j >> 2) * (TX * 4) + tx * 4 + (j & 3);
@@ -301,7 +319,7 @@ __device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], c
                     if (bp == 0x80u) nar = true;
                     else q += (int32_t)(int16_t)tab[bp] << P8::MAXS;
                 }
-                const int64_t at = out.at(m, n);
+                const int64_t at = rp + (int64_t)n * out.nstride;
                 if (fout == 0) {
                     ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire(q));
                 } else {
@@ -495,7 +513,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t1; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, CRS, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(1, 1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(OHW); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW; p.out.vec4 = OHW % 4 == 0;
+        p.out.md = make_fastdiv(OHW); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW; p.out.vec4 = OHW % 4 == 0; p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
     } else if (which == 1) {  // t0 = dy, t1 = w ; stride 1 only
         p.M = g.N * HW; p.N = g.C; p.K = g.K * RS; p.transposed = 0;
         p.A.base = (const uint8_t*)t0; p.A.rows = p.M; p.A.K = p.K; p.A.LY = g.OH; p.A.LX = g.OW;
@@ -504,7 +522,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t1; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, RS, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(RS, 1, CRS, 1, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(HW); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW; p.out.vec4 = HW % 4 == 0;
+        p.out.md = make_fastdiv(HW); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW; p.out.vec4 = HW % 4 == 0; p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
     } else {  // t0 = dy, t1 = x ; computed transposed: rows (c,r,s), columns ko
         p.M = CRS; p.N = g.K; p.K = g.N * OHW; p.transposed = 1;
         p.A.base = (const uint8_t*)t1; p.A.rows = p.M; p.A.K = p.K; p.A.LY = g.H; p.A.LX = g.W;
@@ -513,7 +531,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
         p.B.base = (const uint8_t*)t0; p.B.rows = p.N; p.B.K = p.K; p.B.LY = 1; p.B.LX = 1;
         p.B.row = affine(1, 1, OHW, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(OHW, 1, g.K * OHW, 1, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS; p.out.vec4 = 0;
+        p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS; p.out.vec4 = 0; p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
     }
     p.Mw = p.transposed ? p.N : p.M;
     p.Nw = p.transposed ? p.M : p.N;
@@ -578,7 +596,7 @@ inline P8ConvProblem p8_gemm_problem(int transA, int transB, int M, int N, int K
     p.B.base = (const uint8_t*)B; p.B.rows = N; p.B.K = K; p.B.LY = 1; p.B.LX = 1;
     p.B.row = affine(1, 1, transB ? ldb : 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
     p.B.k = affine(1, 1, transB ? 1 : ldb, 0, 0, 0, 0, 0, 0, 0, 0, 0);
-    p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1; p.out.vec4 = 0;
+    p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1; p.out.vec4 = 0; p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
     p.Mw = M; p.Nw = N;
     p8_pick_mode(p.A);
     p8_pick_mode(p.B);

@@ -110,6 +110,9 @@ struct P16Operand {
     const uint16_t* base;
     AffineIndex row, k;
     int rows_run;
+    // k runs over a padded width (backward-weight, image operand): only columns < kvalid of it are terms of the
+    // reduction, and what the buffer holds beyond them (neighbouring data) is cleared when fetched; 0: no such columns
+    int kvalid;
 };
 
 struct __attribute__((packed, aligned(2))) P16Run {  // 8 consecutive int16, two-byte aligned
@@ -163,12 +166,26 @@ struct P16Stage {
         }
     }
 
+    // kvalid / kcol: see P16Operand::kvalid; the clearing is done here, where the fetched words are first
+    // used, so that the loads of fetch() stay in flight during the multiply-accumulate loop
     template <int LD>
-    __device__ __forceinline__ static void stage(const P16Frag (&f)[PER_THREAD], uint32_t (*dst)[LD], uint32_t* flags, int t, int rows_run) {
+    __device__ __forceinline__ static void stage(P16Frag (&f)[PER_THREAD], uint32_t (*dst)[LD], uint32_t* flags, int t, int rows_run,
+                                                 int kvalid, const int* __restrict__ kcol) {
 #pragma unroll
         for (int i = 0; i < PER_THREAD; ++i) {
             const int w = t + 256 * i;
             if (ITEMS % 256 != 0 && w >= ITEMS) continue;
+            if (kvalid && !rows_run) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int live = kvalid - kcol[16 * (w / BR) + 8 * h];  // leading elements of the run that are terms
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const int left = live - 2 * q;  // elements 2q, 2q+1 of the run
+                        if (left < 2) f[i].w[4 * h + q] = left == 1 ? (f[i].w[4 * h + q] & 0xFFFFu) : 0u;
+                    }
+                }
+            }
             uint32_t marks = 0;
 #pragma unroll
             for (int q = 0; q < 8; ++q) marks |= p16_marks(f[i].w[q]);
@@ -198,11 +215,12 @@ struct P16Stage {
     }
 };
 
-__device__ __forceinline__ void p16_fill_kpart(const P16Operand& op, int* kpart, int k0, int kend, int lane) {
+__device__ __forceinline__ void p16_fill_kpart(const P16Operand& op, int* kpart, int* kcol, int k0, int kend, int lane) {
     const int k = k0 + lane;
-    int part = -1, y, x;
+    int part = -1, y, x = 0;
     if (k < kend) op.k.eval((uint32_t)k, part, y, x);
     kpart[lane] = part;
+    kcol[lane] = x;  // column within the padded width (meaningful when op.kvalid is set)
 }
 
 template <int TY, int TX, int TM, int TN>
@@ -219,6 +237,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
     __shared__ int rpartB[BN];
     __shared__ int kpartA[2][P8_KT];  // slice kt uses kpart[kt & 1], filled two iterations ahead
     __shared__ int kpartB[2][P8_KT];
+    __shared__ int kcolA[2][P8_KT];
+    __shared__ int kcolB[2][P8_KT];
     __shared__ uint16_t tab[256];     // for the bias only
     __shared__ uint32_t rowNaR[BM];
     __shared__ uint32_t colNaR[BN];
@@ -252,8 +272,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
     const int tb = (SA::ITEMS < 256) ? ((t + 128) & 255) : t;  // B's items start on the threads A leaves idle
-    if (t < P8_KT) p16_fill_kpart(A, kpartA[0], kbeg, kend, t);
-    else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[0], kbeg, kend, t - P8_KT);
+    if (t < P8_KT) p16_fill_kpart(A, kpartA[0], kcolA[0], kbeg, kend, t);
+    else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[0], kcolB[0], kbeg, kend, t - P8_KT);
     __syncthreads();
     {
         P16Frag fa[SA::PER_THREAD], fb[SB::PER_THREAD];
@@ -261,11 +281,11 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
             SA::fetch(A, rpartA, kpartA[0], t, fa);
             SB::fetch(B, rpartB, kpartB[0], tb, fb);
             if (nkt > 1) {
-                if (t < P8_KT) p16_fill_kpart(A, kpartA[1], kbeg + P8_KT, kend, t);
-                else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[1], kbeg + P8_KT, kend, t - P8_KT);
+                if (t < P8_KT) p16_fill_kpart(A, kpartA[1], kcolA[1], kbeg + P8_KT, kend, t);
+                else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[1], kcolB[1], kbeg + P8_KT, kend, t - P8_KT);
             }
-            SA::template stage<BM>(fa, As[0], rowNaR, t, A.rows_run);
-            SB::template stage<BN>(fb, Bs[0], colNaR, tb, B.rows_run);
+            SA::template stage<BM>(fa, As[0], rowNaR, t, A.rows_run, A.kvalid, kcolA[0]);
+            SB::template stage<BN>(fb, Bs[0], colNaR, tb, B.rows_run, B.kvalid, kcolB[0]);
         }
     }
     __syncthreads();
@@ -280,8 +300,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
         }
         if (kt + 2 < nkt) {  // kpart[cur] was last read when slice kt was fetched, one barrier ago
             const int k2 = kbeg + (kt + 2) * P8_KT;
-            if (t < P8_KT) p16_fill_kpart(A, kpartA[cur], k2, kend, t);
-            else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[cur], k2, kend, t - P8_KT);
+            if (t < P8_KT) p16_fill_kpart(A, kpartA[cur], kcolA[cur], k2, kend, t);
+            else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[cur], kcolB[cur], k2, kend, t - P8_KT);
         }
 #pragma unroll 2
         for (int kp = 0; kp < P8_KP; ++kp) {
@@ -302,8 +322,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
                 for (int j = 0; j < TN; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
         }
         if (more) {
-            SA::template stage<BM>(fa, As[cur ^ 1], rowNaR, t, A.rows_run);
-            SB::template stage<BN>(fb, Bs[cur ^ 1], colNaR, tb, B.rows_run);
+            SA::template stage<BM>(fa, As[cur ^ 1], rowNaR, t, A.rows_run, A.kvalid, kcolA[cur ^ 1]);
+            SB::template stage<BN>(fb, Bs[cur ^ 1], colNaR, tb, B.rows_run, B.kvalid, kcolB[cur ^ 1]);
         }
         __syncthreads();
     }
@@ -314,6 +334,7 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
 
 struct P8PrePlan {
     bool ok;               // this pass and geometry can use the pre-decoded path
+    bool padded_rows;      // some rows of the kernel's problem are padding (no split reduction then)
     P8PreJob job[2];       // operand A, operand B (src / dst filled at launch)
     P16Operand A, B;       // bases filled at launch
     size_t bytes[2];       // workspace bytes of the two rewritten operands (each a multiple of 256)
@@ -325,11 +346,17 @@ struct P8PrePlan {
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // which: 0 forward, 1 backward-data, 2 backward-weight (computed transposed), as in p8_problem.
-// Needs unit stride and an output (forward, backward-weight) / input (backward-data) width that is
-// a multiple of 8, so that aligned groups of 8 rows (or of 8 reduction indices) are runs in memory.
+// Needs unit stride.  So that aligned groups of 8 rows (or of 8 reduction indices) are runs in
+// memory whatever the image width, the index that runs over output columns (forward,
+// backward-weight) or input columns (backward-data) runs over a width rounded up to a multiple
+// of 8: the extra columns read zeros or neighbouring data from the padded buffers, add nothing
+// to a reduction (the other operand is zero there) and are skipped when outputs are stored
+// (padded_rows: such rows exist, and a split reduction, whose partials are laid out by row, is
+// not offered).
 inline P8PrePlan p8_pre_plan(int which, const ConvGeom& g) {
     P8PrePlan p;
     p.ok = false;
+    p.padded_rows = false;
     if (g.sh != 1 || g.sw != 1 || !p8_conv_fits(g)) return p;
     const int OHW = g.OH * g.OW, HW = g.H * g.W, RS = g.R * g.S, CRS = g.C * RS;
     const int64_t lim = ((int64_t)1 << 30);
@@ -337,66 +364,84 @@ inline P8PrePlan p8_pre_plan(int which, const ConvGeom& g) {
     P8PreJob& jb = p.job[1];
     ja = P8PreJob{};
     jb = P8PreJob{};
+    p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
+    p.A.kvalid = 0;
+    p.B.kvalid = 0;
     if (which == 0) {
-        if (g.OW % 8 != 0) return p;
-        // x with its zero border: Hp = H + 2 ph rows of pitch Wp >= W + 2 pw
-        const int Hp = g.H + 2 * g.ph, Wp = (int)round_up((size_t)(g.W + 2 * g.pw), 8);
-        if ((int64_t)g.N * g.C * Hp * Wp >= lim) return p;
+        // x with its zero border: Hp = H + 2 ph rows; columns up to OWq - 1 + S - 1 are read
+        const int OWq = (int)round_up((size_t)g.OW, 8);
+        const int Hp = g.H + 2 * g.ph;
+        const int need = g.W + 2 * g.pw > OWq + g.S - 1 ? g.W + 2 * g.pw : OWq + g.S - 1;
+        const int Wp = (int)round_up((size_t)need, 8);
+        if ((int64_t)g.N * g.C * Hp * Wp >= lim || (int64_t)g.N * g.OH * OWq >= lim) return p;
         ja.kind = P8_PRE_IMAGE; ja.rows = g.N * g.C * Hp; ja.pitch = Wp; ja.H = g.H; ja.W = g.W; ja.Hp = Hp; ja.pad_t = g.ph; ja.pad_l = g.pw;
         const int Kp = (int)round_up((size_t)CRS, 32);
         jb.kind = P8_PRE_ROWS; jb.rows = g.K; jb.pitch = Kp; jb.K = CRS;
-        p.M = g.N * OHW; p.N = g.K; p.K = CRS; p.transposed = 0;
-        // rows (n, oh, ow) -> n*C*Hp*Wp + oh*Wp + ow ; k (c, r, s) -> c*Hp*Wp + r*Wp + s
-        p.A.row = affine(g.OH, g.OW, g.C * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
+        p.M = g.N * g.OH * OWq; p.N = g.K; p.K = CRS; p.transposed = 0;
+        p.padded_rows = OWq != g.OW;
+        // rows (n, oh, owq) -> n*C*Hp*Wp + oh*Wp + owq ; k (c, r, s) -> c*Hp*Wp + r*Wp + s
+        p.A.row = affine(g.OH, OWq, g.C * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
         p.A.k = affine(g.R, g.S, Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
         p.A.rows_run = 1;
         p.B.row = affine(1, 1, Kp, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(1, 1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.rows_run = 0;
-        p.out.md = make_fastdiv(OHW); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW; p.out.vec4 = OHW % 4 == 0;
+        p.out.md = make_fastdiv(g.OH * OWq); p.out.m1 = (int64_t)g.K * OHW; p.out.m0 = 1; p.out.nstride = OHW;
+        p.out.vec4 = g.OW % 4 == 0;
+        if (p.padded_rows) { p.out.wpad = 1; p.out.wvalid = g.OW; p.out.wd = make_fastdiv(OWq); }
     } else if (which == 1) {
-        if (g.W % 8 != 0) return p;
         // dx[h,w] reads dy[h + ph - r, w + pw - s]: border of R-1-ph rows and S-1-pw columns (a negative one is a crop: not handled here)
         const int bt = g.R - 1 - g.ph, bl = g.S - 1 - g.pw;
         if (bt < 0 || bl < 0) return p;
-        const int Hp = g.OH + 2 * bt, Wp = (int)round_up((size_t)(g.OW + 2 * bl), 8);
-        if (Hp < g.H + g.R - 1 || Wp < g.W + g.S - 1) return p;  // every tap of every row must land inside
-        if ((int64_t)g.N * g.K * Hp * Wp >= lim) return p;
+        const int Wq = (int)round_up((size_t)g.W, 8);
+        const int Hp = g.OH + 2 * bt;
+        const int need = g.OW + 2 * bl > Wq + g.S - 1 ? g.OW + 2 * bl : Wq + g.S - 1;
+        const int Wp = (int)round_up((size_t)need, 8);
+        if (Hp < g.H + g.R - 1) return p;  // every tap of every row must land inside
+        if ((int64_t)g.N * g.K * Hp * Wp >= lim || (int64_t)g.N * g.H * Wq >= lim) return p;
         ja.kind = P8_PRE_IMAGE; ja.rows = g.N * g.K * Hp; ja.pitch = Wp; ja.H = g.OH; ja.W = g.OW; ja.Hp = Hp; ja.pad_t = bt; ja.pad_l = bl;
         const int Kd = g.K * RS, Kp = (int)round_up((size_t)Kd, 32);
         jb.kind = P8_PRE_WT; jb.rows = g.C; jb.pitch = Kp; jb.K = Kd; jb.C = g.C; jb.RS = RS;
-        p.M = g.N * HW; p.N = g.C; p.K = Kd; p.transposed = 0;
-        // rows (n, h, w) -> n*K*Hp*Wp + h*Wp + w ; k (ko, r, s) -> ko*Hp*Wp + (R-1-r)*Wp + (S-1-s)
-        p.A.row = affine(g.H, g.W, g.K * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
+        p.M = g.N * g.H * Wq; p.N = g.C; p.K = Kd; p.transposed = 0;
+        p.padded_rows = Wq != g.W;
+        // rows (n, h, wq) -> n*K*Hp*Wp + h*Wp + wq ; k (ko, r, s) -> ko*Hp*Wp + (R-1-r)*Wp + (S-1-s)
+        p.A.row = affine(g.H, Wq, g.K * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
         p.A.k = affine(g.R, g.S, Hp * Wp, -Wp, -1, (g.R - 1) * Wp + (g.S - 1), 0, 0, 0, 0, 0, 0);
         p.A.rows_run = 1;
         p.B.row = affine(1, 1, Kp, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.k = affine(1, 1, 1, 0, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.rows_run = 0;
-        p.out.md = make_fastdiv(HW); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW; p.out.vec4 = HW % 4 == 0;
+        p.out.md = make_fastdiv(g.H * Wq); p.out.m1 = (int64_t)g.C * HW; p.out.m0 = 1; p.out.nstride = HW;
+        p.out.vec4 = g.W % 4 == 0;
+        if (p.padded_rows) { p.out.wpad = 1; p.out.wvalid = g.W; p.out.wd = make_fastdiv(Wq); }
     } else {
-        if (g.OW % 8 != 0) return p;
-        const int Hp = g.H + 2 * g.ph, Wp = (int)round_up((size_t)(g.W + 2 * g.pw), 8);
+        const int OWq = (int)round_up((size_t)g.OW, 8);
+        const int Hp = g.H + 2 * g.ph;
+        const int need = g.W + 2 * g.pw > OWq + g.S - 1 ? g.W + 2 * g.pw : OWq + g.S - 1;
+        const int Wp = (int)round_up((size_t)need, 8);
         if ((int64_t)g.N * g.C * Hp * Wp >= lim) return p;
         ja.kind = P8_PRE_IMAGE; ja.rows = g.N * g.C * Hp; ja.pitch = Wp; ja.H = g.H; ja.W = g.W; ja.Hp = Hp; ja.pad_t = g.ph; ja.pad_l = g.pw;
-        // dy keeps its layout [n][ko][oh*ow], one long row (OH*OW is a multiple of 8)
-        const int64_t total = (int64_t)g.N * g.K * OHW;
-        if (total >= lim) return p;
-        jb.kind = P8_PRE_ROWS; jb.rows = 1; jb.pitch = (int)round_up((size_t)total, 32); jb.K = (int)total;
-        p.M = CRS; p.N = g.K; p.K = g.N * OHW; p.transposed = 1;
-        // rows (c, r, s) -> c*Hp*Wp + r*Wp + s ; k (n, oh, ow) -> n*C*Hp*Wp + oh*Wp + ow
+        // dy as [n][ko][oh][owq], zero beyond the real width: the reduction index (n, oh, owq) runs over the padded width
+        if ((int64_t)g.N * g.K * g.OH * OWq >= lim) return p;
+        jb.kind = P8_PRE_IMAGE; jb.rows = g.N * g.K * g.OH; jb.pitch = OWq; jb.H = g.OH; jb.W = g.OW; jb.Hp = g.OH; jb.pad_t = 0; jb.pad_l = 0;
+        p.M = CRS; p.N = g.K; p.K = g.N * g.OH * OWq; p.transposed = 1;
+        // rows (c, r, s) -> c*Hp*Wp + r*Wp + s ; k (n, oh, owq) -> n*C*Hp*Wp + oh*Wp + owq
         p.A.row = affine(g.R, g.S, Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
-        p.A.k = affine(g.OH, g.OW, g.C * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 0, 0);
+        p.A.k = affine(g.OH, OWq, g.C * Hp * Wp, Wp, 1, 0, 0, 0, 0, 0, 1, 0);  // x = owq, the column within the padded width
         p.A.rows_run = 0;
-        p.B.row = affine(1, 1, OHW, 0, 0, 0, 0, 0, 0, 0, 0, 0);
-        p.B.k = affine(OHW, 1, g.K * OHW, 1, 0, 0, 0, 0, 0, 0, 0, 0);
+        p.A.kvalid = OWq != g.OW ? g.OW : 0;
+        const int OHWq = g.OH * OWq;
+        p.B.row = affine(1, 1, OHWq, 0, 0, 0, 0, 0, 0, 0, 0, 0);
+        p.B.k = affine(OHWq, 1, g.K * OHWq, 1, 0, 0, 0, 0, 0, 0, 0, 0);
         p.B.rows_run = 0;
         p.out.md = make_fastdiv(1); p.out.m1 = 1; p.out.m0 = 0; p.out.nstride = CRS; p.out.vec4 = 0;
     }
     // a run may start up to 31 elements before the end of the last row and always reads 8: keep 64 bytes of slack
     if ((int64_t)ja.rows * ja.pitch >= lim || (int64_t)jb.rows * jb.pitch >= lim) return p;
-    ja.by_groups = make_fastdiv((uint32_t)(ja.pitch / 8)); ja.by_hp = make_fastdiv((uint32_t)(ja.Hp > 0 ? ja.Hp : 1));
-    jb.by_groups = make_fastdiv((uint32_t)(jb.pitch / 8)); jb.by_hp = make_fastdiv(1);
+    for (P8PreJob* j : {&ja, &jb}) {
+        j->by_groups = make_fastdiv((uint32_t)(j->pitch / 8));
+        j->by_hp = make_fastdiv((uint32_t)(j->kind == P8_PRE_IMAGE && j->Hp > 0 ? j->Hp : 1));
+    }
     p.bytes[0] = round_up((size_t)ja.rows * ja.pitch * 2 + 64, 256);
     p.bytes[1] = round_up((size_t)jb.rows * jb.pitch * 2 + 64, 256);
     p.Mw = p.transposed ? p.N : p.M;
