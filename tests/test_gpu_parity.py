@@ -300,6 +300,44 @@ def test_conv_bwd_weight_long_reduction_splits():
     _assert_equal(to_np(db, "p16"), wdb, "split dbias")
 
 
+def _random_geometries(count, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        ph, pw = int(rng.integers(0, 4)), int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 21)), int(rng.integers(1, 21))
+        if H + 2 * ph < R or W + 2 * pw < S:
+            continue
+        unit = rng.random() < 0.75  # mostly unit stride: the pre-decoded path
+        out.append(dict(N=int(rng.integers(1, 4)), C=int(rng.integers(1, 6)), H=H, W=W, K=int(rng.integers(1, 7)), R=R, S=S, pad_h=ph, pad_w=pw,
+                        stride_h=1 if unit else int(rng.integers(1, 4)), stride_w=1 if unit else int(rng.integers(1, 4))))
+    return out
+
+
+@pytest.mark.parametrize("gi", range(40))
+def test_conv_random_geometries_posit8(gi):
+    """Seeded random shapes, pads larger than the filter allows for a border, one-pixel images, widths of every
+    residue modulo 8: all three passes and the bias gradient of the posit<8,0> paths."""
+    d = _random_geometries(40, 2105)[gi]
+    rng = np.random.default_rng(1000 + gi)
+    oh, ow = fast.out_hw(d)
+    fout = "p8" if gi % 2 else "p16"
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), "p8", special=0.01)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), "p8", special=0.01, allow_nar=gi % 3 == 0)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.01)
+    bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", fout, bias=to_dev(bias))
+    _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, "p8", fout, bias=bias), "fwd %s" % d)
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", fout)
+    _assert_equal(to_np(dx, fout), fast.conv2d_bwd_data(dy, w, d, "p8", fout), "bwd_data %s" % d)
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dy), to_dev(x), desc, "p8", fout, with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, "p8", fout, with_bias=True)
+    _assert_equal(to_np(dw, fout), wdw, "bwd_weight %s" % d)
+    _assert_equal(to_np(db, fout), wdb, "dbias %s" % d)
+
+
 @pytest.mark.parametrize("fin,fout", [("p8", "p16"), ("p16", "p16"), ("p8_2", "p12_2"), ("p32", "p32")])
 def test_bias_gradient_over_batch_slices(fin, fout):
     """Enough images that the bias-gradient reduction is cut into slices of the batch and merged;
