@@ -118,7 +118,11 @@ int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_de
                             const void* dy, const void* x, void* dw, void* dbias,
                             void* workspace, size_t workspace_bytes);
 
-/* which: 0 = fwd, 1 = bwd_data, 2 = bwd_weight.  Bytes of workspace (0 = none). */
+/* which: 0 = fwd, 1 = bwd_data, 2 = bwd_weight.  Bytes of workspace (0 = none) that the matching
+ * call needs: device memory, 16-byte aligned (PNN_EINVAL otherwise), contents undefined on entry and
+ * on return.  It holds the partial quires of a split reduction and, for posit<8,0> at unit stride,
+ * the two operands rewritten once as decoded 16-bit integers with the zero border written out
+ * (about twice the size of the tensors).  The calls of one stream may share one workspace. */
 size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
 
 /* The same four operations with the quire switched off (Sec. 3.3: the quire is an

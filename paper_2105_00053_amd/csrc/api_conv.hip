@@ -251,6 +251,7 @@ extern "C" int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2
     if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
     if (g.N == 0 || g.K == 0) return PNN_OK;
     if (!y || (g.C > 0 && (!x || !w))) return PNN_EINVAL;
+    if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     PNN_DISPATCH_POSIT(fin, return conv_fwd<F>(st, fout, g, x, w, bias, y, workspace, workspace_bytes))
     return PNN_EINVAL;
@@ -262,6 +263,7 @@ extern "C" int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_
     if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
     if (g.N == 0 || g.C == 0) return PNN_OK;
     if (!dx || (g.K > 0 && (!dy || !w))) return PNN_EINVAL;
+    if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     PNN_DISPATCH_POSIT(fin, return conv_bwd_data<F>(st, fout, g, dy, w, dx, workspace, workspace_bytes))
     return PNN_EINVAL;
@@ -273,6 +275,7 @@ extern "C" int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pn
     if (!is_posit(fin) || !is_posit(fout) || !conv_geom(desc, &g)) return PNN_EINVAL;
     if (g.K == 0 || g.C == 0) return PNN_OK;
     if (!dw || (g.N > 0 && (!dy || !x))) return PNN_EINVAL;
+    if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     PNN_DISPATCH_POSIT(fin, return conv_bwd_weight<F>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes))
     return PNN_EINVAL;

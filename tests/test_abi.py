@@ -81,6 +81,9 @@ def test_argument_validation_without_launch():
     d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 0, 1)  # zero stride
     assert L.posit_conv2d_bwd_data(null, 0, 0, ctypes.byref(d), fake, fake, fake, null, 0) == EINVAL
     assert L.posit_conv2d_bwd_weight(null, 0, 0, None, fake, fake, fake, null, null, 0) == EINVAL
+    d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 1, 1)
+    assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, null, 0) == 3  # needs its workspace
+    assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, ctypes.c_void_p(0x1004), 1 << 30) == EINVAL  # workspace alignment
     # a split reduction without the workspace it asks for
     need = L.posit_gemm_workspace(0, 1, 0, 0, 32, 288, 131072)
     assert need > 0
