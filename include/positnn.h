@@ -147,6 +147,19 @@ int posit_conv2d_bwd_data_noquire(void* stream, int fin, int fout, const pnn_con
 int posit_conv2d_bwd_weight_noquire(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
                                     const void* dy, const void* x, void* dw, void* dbias);
 
+/* The same update for several tensors in one launch (Fig. 2, optimizer: one SGD step touches every
+ * parameter tensor of the model, most of them small).  items is a HOST array of count entries; each
+ * is updated exactly as posit_axpy would: y[i] = round_fy(y[i] + alpha * x[i]), y_copy (nullable per
+ * item) receiving round_fcopy of the new y.  The tensors must not overlap. */
+typedef struct {
+    const void* x; /* device, fx */
+    void* y;       /* device, fy, in place */
+    void* y_copy;  /* device, fcopy, or NULL */
+    int64_t n;
+} pnn_axpy_item;
+int posit_axpy_multi(void* stream, int fx, int fy, uint32_t alpha_bits, int count,
+                     const pnn_axpy_item* items, int fcopy);
+
 /* Elementary functions (Fig. 2: Sigmoid and TanH activations; exp and log are the pieces of the
  * Cross Entropy loss).  The paper prints no algorithm: y[i] is the correctly rounded posit<fmt> of
  * the real function at the value of x[i] (nearest, ties to the even pattern, never 0 or NaR for a

@@ -5,5 +5,5 @@ from .binding import (  # noqa: F401
     posit_conv2d_bwd_weight, posit_conv2d_fwd, posit_conv2d_workspace, posit_convert, posit_gemm, posit_gemm_workspace,
     posit_round, posit_relu, posit_relu_bwd, posit_maxpool2d_fwd, posit_maxpool2d_bwd, posit_avgpool2d_fwd, posit_avgpool2d_bwd,
     posit_gemm_noquire, posit_conv2d_fwd_noquire, posit_conv2d_bwd_data_noquire, posit_conv2d_bwd_weight_noquire,
-    posit_unary, posit_unary_bwd, posit_cross_entropy, posit_mse,
+    posit_unary, posit_unary_bwd, posit_cross_entropy, posit_mse, posit_axpy_multi,
 )

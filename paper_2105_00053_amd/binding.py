@@ -24,6 +24,10 @@ _SAME_SIZE = {1: (torch.uint8, torch.int8), 2: (torch.uint16, torch.int16), 4: (
               8: (torch.float64, torch.int64, torch.uint64)}
 
 
+class AxpyItem(ctypes.Structure):
+    _fields_ = [("x", ctypes.c_void_p), ("y", ctypes.c_void_p), ("y_copy", ctypes.c_void_p), ("n", ctypes.c_int64)]
+
+
 class ConvDesc(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("N", "C", "H", "W", "K", "R", "S", "pad_h", "pad_w", "stride_h", "stride_w")]
 
@@ -67,6 +71,7 @@ def load():
     L.posit_conv2d_fwd_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
     L.posit_conv2d_bwd_data_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp]
     L.posit_conv2d_bwd_weight_noquire.argtypes = [vp, ci, ci, dp, vp, vp, vp, vp]
+    L.posit_axpy_multi.argtypes = [vp, ci, ci, u32, ci, ctypes.POINTER(AxpyItem), ci]
     L.posit_unary.argtypes = [vp, ci, ci, i64, vp, vp]
     L.posit_unary_bwd.argtypes = [vp, ci, ci, ci, i64, vp, vp, vp]
     L.posit_cross_entropy.argtypes = [vp, ci, ci, ci, i64, i64, vp, vp, vp, vp]
@@ -75,7 +80,7 @@ def load():
     L.posit_status_string.restype = ctypes.c_char_p
     for name in ("posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight", "posit_round", "posit_convert", "posit_axpy",
                  "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
-                 "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse",
+                 "posit_axpy_multi", "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse",
                  "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd"):
         getattr(L, name).restype = ci
     _lib = L
@@ -238,6 +243,26 @@ def posit_conv2d_bwd_weight_noquire(dy, x, desc, fin, fout, with_bias=False, out
     _check(load().posit_conv2d_bwd_weight_noquire(_stream(), fin, fout, ctypes.byref(desc), _dev(dy, fin, "dy"), _dev(x, fin, "x"),
                                                   _dev(out, fout, "dw"), _dev(out_bias, fout, "dbias") if with_bias else None))
     return (out, out_bias) if with_bias else out
+
+
+def posit_axpy_multi(alpha_bits, xs, ys, fx, fy, fcopy=None, y_copies=None):
+    """posit_axpy over lists of tensors in one launch (in place on ys; y_copies entries may be None)."""
+    fx, fy = _code(fx), _code(fy)
+    fc = _code(fcopy) if fcopy is not None else fy
+    if len(xs) != len(ys) or (y_copies is not None and len(y_copies) != len(ys)):
+        raise PositError("lists of different lengths")
+    items = (AxpyItem * max(1, len(xs)))()
+    for i, (x, y) in enumerate(zip(xs, ys)):
+        if x.numel() != y.numel():
+            raise PositError("x and y of item %d differ in size" % i)
+        c = y_copies[i] if y_copies is not None else None
+        if c is not None and c.numel() != y.numel():
+            raise PositError("copy of item %d differs in size" % i)
+        items[i].x = _dev(x, fx, "x").value
+        items[i].y = _dev(y, fy, "y").value
+        items[i].y_copy = _dev(c, fc, "y_copy").value if c is not None else None
+        items[i].n = y.numel()
+    _check(load().posit_axpy_multi(_stream(), fx, fy, int(alpha_bits) & 0xFFFFFFFF, len(xs), items, fc))
 
 
 FUNCTIONS = {"sigmoid": 0, "tanh": 1, "exp": 2, "log": 3}

@@ -224,6 +224,29 @@ __global__ __launch_bounds__(256) void axpy_rt_kernel(const void* __restrict__ x
     if (yc) store_elem(yc, i, cbytes, cp((uint64_t)r));
 }
 
+// Several tensors in one launch (the SGD update of a whole model: many small tensors, each a launch
+// of its own otherwise).  blockIdx.y picks the tensor; the descriptors travel as kernel arguments.
+constexpr int AXPY_MULTI_MAX = 16;
+struct AxpyItems {
+    const void* x[AXPY_MULTI_MAX];
+    void* y[AXPY_MULTI_MAX];
+    void* yc[AXPY_MULTI_MAX];
+    int64_t n[AXPY_MULTI_MAX];
+};
+
+__global__ __launch_bounds__(256) void axpy_multi_kernel(AxpyItems items, int xbytes, int ybytes, int cbytes, AxpyRT op, MapRT cp) {
+    const int it = blockIdx.y;
+    const void* x = items.x[it];
+    void* y = items.y[it];
+    void* yc = items.yc[it];
+    const int64_t n = items.n[it];
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const uint32_t r = op((uint32_t)load_elem(x, i, xbytes), (uint32_t)load_elem(y, i, ybytes));
+        store_elem(y, i, ybytes, r);
+        if (yc) store_elem(yc, i, cbytes, cp((uint64_t)r));
+    }
+}
+
 inline MapRT make_map(int src, int dst) {
     MapRT m;
     m.src_kind = src == PNN_F32 ? 1 : (src == PNN_F64 ? 2 : 0);
@@ -298,6 +321,42 @@ extern "C" int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int
         case PNN_POSIT16_1: return axpy_pick_y<P16>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
         default: return axpy_pick_y<P32>(st, fy, alpha_bits, n, x, y, fcopy, y_copy);
     }
+}
+
+extern "C" int posit_axpy_multi(void* stream, int fx, int fy, uint32_t alpha_bits, int count, const pnn_axpy_item* items, int fcopy) {
+    if (!is_posit(fx) || !is_posit(fy) || count < 0 || (count > 0 && !items)) return PNN_EINVAL;
+    bool any_copy = false;
+    for (int i = 0; i < count; ++i) {
+        if (items[i].n < 0) return PNN_EINVAL;
+        if (items[i].n > 0 && (!items[i].x || !items[i].y)) return PNN_EINVAL;
+        any_copy = any_copy || items[i].y_copy != nullptr;
+    }
+    if (any_copy && !is_posit(fcopy)) return PNN_EINVAL;
+    hipStream_t st = (hipStream_t)stream;
+    AxpyRT op;
+    op.fx = fmt_of_code(fx);
+    op.fy = fmt_of_code(fy);
+    op.alpha = alpha_bits;
+    const int fc = any_copy ? fcopy : fy;
+    bool launched = false;
+    for (int base = 0; base < count; base += AXPY_MULTI_MAX) {
+        AxpyItems pack;
+        int used = 0;
+        int64_t longest = 0;
+        for (int i = base; i < count && i < base + AXPY_MULTI_MAX; ++i) {
+            if (items[i].n == 0) continue;
+            pack.x[used] = items[i].x; pack.y[used] = items[i].y; pack.yc[used] = items[i].y_copy; pack.n[used] = items[i].n;
+            if (items[i].n > longest) longest = items[i].n;
+            ++used;
+        }
+        if (used == 0) continue;
+        int64_t blocks = (longest + 255) / 256;
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(axpy_multi_kernel, dim3((unsigned)blocks, (unsigned)used), dim3(256), 0, st, pack, (int)elem_size(fx),
+                           (int)elem_size(fy), (int)elem_size(fc), op, make_map(fy, fc));
+        launched = true;
+    }
+    return launched ? hip_status(hipGetLastError()) : PNN_OK;
 }
 
 extern "C" const char* posit_status_string(int status) {

@@ -87,18 +87,19 @@ def forward(net, x8, tape=None):
 def backward_and_update(net, tape, dy, alpha=ALPHA_MINUS_0P1, grads=None):
     """Back-propagates dy (posit<8,0>) through the tape and applies the SGD update layer by
     layer.  When `grads` is a list, (layer, dw, db) posit<16,1> tensors are appended to it."""
+    pending = []
     for kind, li, aux, saved in reversed(tape):
         if kind == "fc":
             dw = pn.posit_gemm(dy, saved, "p8", "p16", trans_a=True)
             ones = torch.full((dy.shape[0], 1), 0x40, dtype=torch.uint8, device=dy.device)
             db = pn.posit_gemm(dy, ones, "p8", "p16", trans_a=True).reshape(-1)
             dx = pn.posit_gemm(dy, net.w8[li], "p8", "p8")
-            _update(net, li, dw, db, alpha, grads)
+            _update(net, li, dw, db, alpha, grads, pending)
             dy = dx
         elif kind == "conv":
             dw, db = pn.posit_conv2d_bwd_weight(dy, saved, aux, "p8", "p16", with_bias=True)
             dx = pn.posit_conv2d_bwd_data(dy, net.w8[li], aux, "p8", "p8") if li > 0 else None
-            _update(net, li, dw, db, alpha, grads)
+            _update(net, li, dw, db, alpha, grads, pending)
             dy = dx
         elif kind == "relu":
             dy = pn.posit_relu_bwd(saved, dy, "p8", "p8")
@@ -108,13 +109,22 @@ def backward_and_update(net, tape, dy, alpha=ALPHA_MINUS_0P1, grads=None):
             dy = pn.posit_maxpool2d_bwd(dy, aux, "p8")
         elif kind == "flatten":
             dy = dy.reshape(saved)
+    _apply_updates(pending, alpha)
 
 
-def _update(net, li, dw, db, alpha, grads):
+def _update(net, li, dw, db, alpha, grads, pending):
+    """Queues the SGD update of layer li: all layers are updated by one launch when the backward pass is over
+    (nothing reads the weights between a layer's own backward-data and the next forward pass)."""
     if grads is not None:
         grads.append((li, dw.clone(), db.clone()))
-    pn.posit_axpy(alpha, dw.reshape(-1), net.w16[li].reshape(-1), "p16", "p16", fcopy="p8", y_copy=net.w8[li].reshape(-1))
-    pn.posit_axpy(alpha, db.reshape(-1), net.b16[li].reshape(-1), "p16", "p16", fcopy="p8", y_copy=net.b8[li].reshape(-1))
+    pending.append((dw, net.w16[li], net.w8[li]))
+    pending.append((db, net.b16[li], net.b8[li]))
+
+
+def _apply_updates(pending, alpha):
+    if pending:
+        pn.posit_axpy_multi(alpha, [g for g, _, _ in pending], [w for _, w, _ in pending], "p16", "p16", fcopy="p8",
+                            y_copies=[c for _, _, c in pending])
 
 
 def training_step(net, x_f32, labels, alpha=ALPHA_MINUS_0P1, grads=None):

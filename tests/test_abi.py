@@ -31,7 +31,7 @@ def test_header_declares_the_expected_entry_points():
         "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string",
         "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd",
         "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
-        "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse"])
+        "posit_unary", "posit_unary_bwd", "posit_cross_entropy", "posit_mse", "posit_axpy_multi"])
 
 
 def test_every_declared_symbol_is_exported(lib):
@@ -76,6 +76,13 @@ def test_argument_validation_without_launch():
     assert L.posit_convert(null, 100, 0, 4, fake, fake) == EINVAL
     assert L.posit_axpy(null, 0, 1, 0, 4, null, fake, -1, null) == EINVAL
     assert L.posit_axpy(null, 0, 1, 0, 4, fake, fake, 9, fake) == EINVAL  # bad copy format
+    items = (b.AxpyItem * 2)()
+    items[0].x, items[0].y, items[0].y_copy, items[0].n = 0x1000, 0x2000, None, 4
+    items[1].x, items[1].y, items[1].y_copy, items[1].n = None, 0x2000, None, 4
+    assert L.posit_axpy_multi(null, 0, 1, 0, 2, items, 0) == EINVAL   # item 1 has no x
+    assert L.posit_axpy_multi(null, 0, 1, 0, 0, None, 0) == 0
+    items[1].x, items[1].y_copy = 0x1000, 0x3000
+    assert L.posit_axpy_multi(null, 0, 1, 0, 2, items, 77) == EINVAL  # a copy is asked for in an unknown format
     d = b.ConvDesc(1, 1, 4, 4, 1, 5, 5, 0, 0, 1, 1)  # kernel larger than the padded image
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, null, 0) == EINVAL
     d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 0, 1)  # zero stride

@@ -90,6 +90,30 @@ def test_axpy(fx, fy, fc):
             _assert_equal(to_np(res, fy), want, "axpy y")
 
 
+@pytest.mark.parametrize("fx,fy,fc", [("p16", "p16", "p8"), ("p8_2", "p12_2", "p8_2"), ("p32", "p32", None), ("p8", "p16", None)])
+def test_axpy_multi(fx, fy, fc):
+    """Twenty tensors of assorted sizes (more than one launch holds, some empty, some without a copy) updated at once."""
+    rng = np.random.default_rng(BITS[fx] * 3 + BITS[fy])
+    sizes = [1, 0, 7, 300, 4097, 25, 0, 10, 64, 70001, 3, 864, 32, 9216, 5, 0, 129, 2, 1000, 31]
+    lr = int(fast.round_from_float(np.array([-0.1], np.float32), fy)[0])
+    xs = [rand_patterns(rng, n, fx) for n in sizes]
+    ys = [rand_patterns(rng, n, fy) for n in sizes]
+    xd, yd = [to_dev(a) for a in xs], [to_dev(a) for a in ys]
+    copies = None
+    if fc:
+        copies = [torch.zeros(n, dtype=pn.binding.TORCH_DTYPE[pn.binding.FORMAT_CODES[fc]], device="cuda") if i % 3 else None
+                  for i, n in enumerate(sizes)]
+    pn.posit_axpy_multi(lr, xd, yd, fx, fy, fcopy=fc, y_copies=copies)
+    for i, n in enumerate(sizes):
+        if n == 0:
+            continue
+        want = fast.axpy(lr, xs[i], ys[i], fx, fy, fc if fc else None)
+        wy = want[0] if fc else want
+        _assert_equal(to_np(yd[i], fy), wy, "tensor %d" % i)
+        if fc and copies[i] is not None:
+            _assert_equal(to_np(copies[i], fc), want[1], "copy %d" % i)
+
+
 # ---------------- GEMM ----------------
 
 def test_config1_p8_gemm_64_against_python_oracle():
