@@ -14,6 +14,11 @@ inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
 
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
+    if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K)) {  // one thread group per output: no workspace
+        GemmPlan p;
+        p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
+        return p;
+    }
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
     // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
     if ((F::N == 8 && F::ES == 0) && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
@@ -31,6 +36,9 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     RowMajorOut out;
     out.ld = ldc;
     hipError_t e;
+    if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K))
+        return hip_status(launch_p8_small_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
+                                               fout, M, N, K));
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
         const uint8_t* a8 = (const uint8_t*)A;
         const uint8_t* b8 = (const uint8_t*)B;

@@ -341,4 +341,101 @@ hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, con
     return hipGetLastError();
 }
 
+// ---- small problems ----
+//
+// A product with few outputs (the fully connected layers of a small network at batch 64: 64 x 120 x 400,
+// 120 x 400 x 64, ...) gives the tiled kernel one or two workgroups, which then walk the reduction
+// slice by slice, each slice a chain of global load -> LDS -> barrier -> multiply: tens of
+// microseconds of latency for a few MMAC.  Here every output gets S threads of its own (S a power
+// of two, splitting the reduction), outputs spread over as many workgroups as there are, operands
+// come straight from global memory (lanes of a wave share the A element and read consecutive B
+// elements) and decode through the LDS table; the S partial sums of an output meet in LDS (int32
+// addition modulo 2^32: exact in the 32-bit quire) and are rounded once.
+//   element strides: A(m,k) = A[m*a_m + k*a_k], B(k,n) = B[k*b_k + n*b_n]
+template <int UNUSED = 0>  // a template so that every translation unit may include this header
+__global__ __launch_bounds__(256) void p8_small_gemm_kernel(const uint8_t* __restrict__ A, int64_t a_m, int64_t a_k,
+                                                            const uint8_t* __restrict__ B, int64_t b_k, int64_t b_n,
+                                                            const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout,
+                                                            int M, int N, int K, int S, int k_per_split) {
+    __shared__ int32_t tab[256];
+    __shared__ uint32_t part[256];
+    __shared__ uint32_t nars[256];
+    const int t = threadIdx.x;
+    tab[t] = Arith<P8>::stage((uint32_t)t);
+    __syncthreads();
+    const int OB = 256 / S;  // outputs per workgroup
+    const int ol = t % OB, s = t / OB;
+    const int64_t o = (int64_t)blockIdx.x * OB + ol;
+    const bool live = o < (int64_t)M * N;
+    const int m = live ? (int)(o / N) : 0, n = live ? (int)(o - (int64_t)m * N) : 0;
+    const int k_lo = s * k_per_split, k_hi = k_lo + k_per_split < K ? k_lo + k_per_split : K;
+    uint32_t acc = 0, nar = 0;
+    if (live) {
+        const uint8_t* ap = A + (int64_t)m * a_m + (int64_t)k_lo * a_k;
+        const uint8_t* bp = B + (int64_t)n * b_n + (int64_t)k_lo * b_k;
+        int k = k_lo;
+        for (; k + 4 <= k_hi; k += 4) {
+            uint32_t a[4], b[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                a[u] = ap[u * a_k];
+                b[u] = bp[u * b_k];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                nar |= (a[u] == 0x80u) | (b[u] == 0x80u);
+                acc += (uint32_t)__mul24(tab[a[u]], tab[b[u]]);
+            }
+            ap += 4 * a_k;
+            bp += 4 * b_k;
+        }
+        for (; k < k_hi; ++k) {
+            const uint32_t a = *ap, b = *bp;
+            nar |= (a == 0x80u) | (b == 0x80u);
+            acc += (uint32_t)__mul24(tab[a], tab[b]);
+            ap += a_k;
+            bp += b_k;
+        }
+    }
+    part[t] = acc;
+    nars[t] = nar;
+    __syncthreads();
+    if (s != 0 || !live) return;
+    for (int z = 1; z < S; ++z) {
+        acc += part[z * OB + ol];
+        nar |= nars[z * OB + ol];
+    }
+    bool isnar = nar != 0;
+    if (bias) {
+        const uint32_t bpat = bias[n];
+        if (bpat == 0x80u) isnar = true;
+        else acc += (uint32_t)tab[bpat] << P8::MAXS;
+    }
+    const int64_t at = (int64_t)m * ldc + n;
+    if (fout == 0) {
+        ((uint8_t*)C)[at] = (uint8_t)(isnar ? 0x80u : p8_round_quire((int32_t)acc));
+    } else {
+        const uint32_t q1[1] = {acc};
+        round_store<QuireAccum<P8>, 1>(q1, isnar, fout, C, at);
+    }
+}
+
+// Problems the small kernel takes: few outputs and little work.
+inline bool p8_small_gemm_fits(int64_t M, int64_t N, int64_t K) {
+    return M * N <= 65536 && M * N * K <= ((int64_t)1 << 26) && K >= 1;
+}
+
+inline hipError_t launch_p8_small_gemm(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B,
+                                       int64_t ldb, const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N, int64_t K) {
+    // threads per output: keep at least 32 reduction steps per thread, and stop once about 1024 workgroups exist
+    int S = 1;
+    while (S < 64 && K / (2 * S) >= 32 && (M * N * S) / 256 < 1024) S *= 2;
+    const int kps = (int)((K + S - 1) / S);
+    const int OB = 256 / S;
+    const int64_t blocks = (M * N + OB - 1) / OB;
+    hipLaunchKernelGGL(p8_small_gemm_kernel<0>, dim3((unsigned)blocks), dim3(256), 0, stream, A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1,
+                       B, transB ? (int64_t)1 : ldb, transB ? ldb : (int64_t)1, bias, C, ldc, fout, (int)M, (int)N, (int)K, S, kps);
+    return hipGetLastError();
+}
+
 }  // namespace pnn

@@ -185,9 +185,10 @@ def test_gemm_padded_leading_dimensions_and_k0():
 @pytest.mark.parametrize("fin,fout,M,N,K", [("p8", "p16", 32, 288, 8192), ("p16", "p16", 16, 50, 4096), ("p32", "p32", 8, 20, 2048),
                                             ("p8", "p8", 6, 25, 50176)])
 def test_gemm_split_reduction(fin, fout, M, N, K):
-    """Small outputs with a long reduction take the split path (needs workspace);
-    the merged quires must give the same bits."""
-    assert pn.posit_gemm_workspace(fin, fout, 1, 0, M, N, K) > 0
+    """Small outputs with a long reduction: the reduction is split over workgroups (needs workspace) or, for the
+    smallest posit<8,0> problems, over the threads of an output; the merged quires must give the same bits."""
+    small_p8 = fin == "p8" and M * N * K <= 1 << 26
+    assert (pn.posit_gemm_workspace(fin, fout, 1, 0, M, N, K) > 0) != small_p8
     rng = np.random.default_rng(K)
     A = rand_patterns(rng, (K, M), fin, special=0.001)
     B = rand_patterns(rng, (K, N), fin, special=0.001)
