@@ -358,6 +358,7 @@ inline P8PrePlan p8_pre_plan(int which, const ConvGeom& g) {
     p.ok = false;
     p.padded_rows = false;
     if (g.sh != 1 || g.sw != 1 || !p8_conv_fits(g)) return p;
+    if (g.N <= 0 || g.C <= 0 || g.K <= 0) return p;  // an empty operand: nothing to rewrite, the gathered kernel copes
     const int OHW = g.OH * g.OW, HW = g.H * g.W, RS = g.R * g.S, CRS = g.C * RS;
     const int64_t lim = ((int64_t)1 << 30);
     P8PreJob& ja = p.job[0];

@@ -325,6 +325,27 @@ def test_conv_bwd_weight_long_reduction_splits():
     _assert_equal(to_np(db, "p16"), wdb, "split dbias")
 
 
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p16", "p16")])
+def test_conv_empty_reductions(fin, fout):
+    """No input channels: y is the rounded bias.  No images: dw and dbias are zero.  No output channels: dx is zero."""
+    rng = np.random.default_rng(3)
+    d = dict(N=2, C=0, H=8, W=8, K=3, R=3, S=3, pad_h=1, pad_w=1)
+    x = np.zeros((2, 0, 8, 8), dtype=NP_DTYPE[fin])
+    w = np.zeros((3, 0, 3, 3), dtype=NP_DTYPE[fin])
+    bias = rand_patterns(rng, (3,), fin, allow_nar=False)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), _desc(d), fin, fout, bias=to_dev(bias))
+    _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, fin, fout, bias=bias), "fwd without input channels")
+    assert (to_np(y, fout)[:, 1] == fast.convert(bias[1:2], fin, fout)[0]).all()
+    d = dict(N=0, C=2, H=8, W=8, K=3, R=3, S=3, pad_h=1, pad_w=1)
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(np.zeros((0, 3, 8, 8), dtype=NP_DTYPE[fin])), to_dev(np.zeros((0, 2, 8, 8), dtype=NP_DTYPE[fin])),
+                                        _desc(d), fin, fout, with_bias=True)
+    assert not to_np(dw, fout).any() and not to_np(db, fout).any()
+    d = dict(N=2, C=2, H=8, W=8, K=0, R=3, S=3, pad_h=1, pad_w=1)
+    dx = pn.posit_conv2d_bwd_data(to_dev(np.zeros((2, 0, 8, 8), dtype=NP_DTYPE[fin])), to_dev(np.zeros((0, 2, 3, 3), dtype=NP_DTYPE[fin])),
+                                  _desc(d), fin, fout)
+    assert dx.shape == (2, 2, 8, 8) and not to_np(dx, fout).any()
+
+
 def _random_geometries(count, seed):
     rng = np.random.default_rng(seed)
     out = []
