@@ -65,9 +65,12 @@ def extra_measurements(torch, pn, workloads):
         ws = torch.empty(max(16, pn.posit_gemm_workspace(fmt, fmt, False, False, S, S, S)), dtype=torch.uint8, device="cuda")
         ms = _time_ms(torch, lambda: pn.posit_gemm(Ap, Bp, fmt, fmt, out=C, workspace=ws), 10 if fmt != "p32" else 3)
         out["gemm_%s_%d" % (fmt, S)] = {"ms": round(ms, 4), "TMAC/s": round(S ** 3 / ms / 1e9, 3)}
-    for name, net in (("lenet5_step_batch64", workloads.LENET), ("cifarnet_step_batch128", workloads.CIFARNET)):
+    final = dict(compute="p8_2", master="p12_2", loss="p10_2")  # Sec. 4, Table 4: the configuration the paper ends up with
+    for name, net, fmts in (("lenet5_step_batch64", workloads.LENET, {}), ("cifarnet_step_batch128", workloads.CIFARNET, {}),
+                            ("lenet5_step_batch64_posit8_2_12_2_10_2", workloads.LENET, final),
+                            ("cifarnet_step_batch128_posit8_2_12_2_10_2", workloads.CIFARNET, final)):
         x, params, labels = workloads.network_inputs(net)
-        model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+        model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params], **fmts)
         xd, ld = dev(x), torch.from_numpy(labels).cuda()
         ms = _time_ms(torch, lambda: train_step.training_step(model, xd, ld), 10, warm=3)
         runner = train_step.GraphedStep(model, tuple(xd.shape))

@@ -14,6 +14,7 @@ _LIB_PATH = os.path.join(_HERE, "libpositnn_hip.so")
 
 P8, P16, P32, F32, F64 = 0, 1, 2, 100, 101
 P8_1, P8_2, P10_1, P10_2, P12_1, P12_2 = 3, 4, 5, 6, 7, 8  # formats of the paper's experiments outside Table 1
+FORMAT_BITS = {"p8": 8, "p16": 16, "p32": 32, "p8_1": 8, "p8_2": 8, "p10_1": 10, "p10_2": 10, "p12_1": 12, "p12_2": 12}
 FORMAT_CODES = {"p8": P8, "p16": P16, "p32": P32, "f32": F32, "f64": F64, "p8_1": P8_1, "p8_2": P8_2, "p10_1": P10_1,
                 "p10_2": P10_2, "p12_1": P12_1, "p12_2": P12_2}
 TORCH_DTYPE = {P8: torch.uint8, P16: torch.uint16, P32: torch.uint32, F32: torch.float32, F64: torch.float64,

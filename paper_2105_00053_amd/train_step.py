@@ -12,43 +12,53 @@ replays it: the LeNet-5-shaped step, about fifty short kernels, is bound by
 the host-side launches and runs 1.6x faster replayed; the CifarNet-shaped
 step is bound by its kernels and gains nothing.
 
-Formats (mixed precision of Sec. 3.3 / Fig. 3): activations, weight copies and
-back-propagated errors posit<8,0>; weight gradients rounded from the quire to
-posit<16,1>; master weights and optimizer posit<16,1>.
+Formats (mixed precision of Sec. 3.3 / Fig. 3) are those of the Net: activations, weight
+copies and back-propagated errors in its `compute` format; weight gradients rounded from the
+quire straight to its `master` format, which also holds the master weights and runs the
+optimizer; the loss in its `loss` format.  Defaults: posit<8,0>, posit<16,1>, posit<16,1>.
+Net(..., compute="p8_2", master="p12_2", loss="p10_2") is the configuration the paper ends up
+with (Sec. 4, Table 4: posit(8,2) everywhere, optimizer posit(12,2), loss posit(10,2)).
 """
 import torch
 
 from . import binding as pn
 
-ALPHA_MINUS_0P1 = 0xEB33  # posit<16,1> pattern of -(0x14CD), the rounded -0.1
+ALPHA_MINUS_0P1 = 0xEB33  # posit<16,1> pattern of -(0x14CD), the rounded -0.1 (default master format)
 
 
 class Net:
     """Weights of a layer list [("conv", cin, cout, k, pad) | ("fc", in, out) | ("relu",) |
-    ("avgpool",) | ("maxpool",) | ("flatten",)] as posit<16,1> masters and posit<8,0> copies."""
+    ("avgpool",) | ("maxpool",) | ("flatten",)] as masters (format `master`) and compute copies
+    (format `compute`).  `alpha` is the pattern of -0.1 in the master format, rounded by the library."""
 
-    def __init__(self, layers, params_f32):
+    def __init__(self, layers, params_f32, compute="p8", master="p16", loss="p16"):
         self.layers = layers
-        self.w16, self.b16, self.w8, self.b8 = [], [], [], []
+        self.compute, self.master, self.loss = compute, master, loss
+        self.w16, self.b16, self.w8, self.b8 = [], [], [], []  # masters and compute copies (names from the default formats)
         for w, b in params_f32:
-            w16 = pn.posit_round(w.contiguous(), "p16")
-            b16 = pn.posit_round(b.contiguous(), "p16")
+            w16 = pn.posit_round(w.contiguous(), master)
+            b16 = pn.posit_round(b.contiguous(), master)
             self.w16.append(w16)
             self.b16.append(b16)
-            self.w8.append(pn.posit_convert(w16, "p16", "p8"))
-            self.b8.append(pn.posit_convert(b16, "p16", "p8"))
+            self.w8.append(pn.posit_convert(w16, master, compute))
+            self.b8.append(pn.posit_convert(b16, master, compute))
+        self.one = 1 << (pn.FORMAT_BITS[compute] - 2)  # the pattern of the value one
+        lr = pn.posit_round(torch.tensor([-0.1], dtype=torch.float32, device=params_f32[0][0].device), master)
+        raw = lr.cpu().contiguous().view(torch.uint8).numpy()  # little-endian bytes of the one pattern
+        self.alpha = int.from_bytes(raw.tobytes(), "little")
 
 
-def loss_gradient(logits_p8, labels):
-    """Softmax cross-entropy gradient in the posit<16,1> loss format (Sec. 4: a 16-bit loss next to 8-bit
-    layers), then its posit<8,0> copy for the backward pass.  labels: int32 device tensor."""
+def loss_gradient(logits, labels, compute="p8", loss="p16"):
+    """Softmax cross-entropy gradient in the loss format (Sec. 4: a wider loss next to 8-bit layers), then its
+    copy in the compute format for the backward pass.  labels: int32 device tensor."""
     if labels.dtype != torch.int32:
         labels = labels.to(torch.int32)
-    _, g16 = pn.posit_cross_entropy(logits_p8, labels, "p8", "p16", "p16", want_loss=False)
-    return pn.posit_convert(g16, "p16", "p8"), g16
+    _, g = pn.posit_cross_entropy(logits, labels, compute, loss, loss, want_loss=False)
+    return pn.posit_convert(g, loss, compute), g
 
 
 def forward(net, x8, tape=None):
+    fc = net.compute
     li = 0
     x = x8
     for layer in net.layers:
@@ -56,27 +66,27 @@ def forward(net, x8, tape=None):
         if kind == "conv":
             _, cin, cout, k, pad = layer
             d = pn.conv_desc(tuple(x.shape), (cout, cin, k, k), (pad, pad), (1, 1))
-            y = pn.posit_conv2d_fwd(x, net.w8[li], d, "p8", "p8", bias=net.b8[li])
+            y = pn.posit_conv2d_fwd(x, net.w8[li], d, fc, fc, bias=net.b8[li])
             if tape is not None:
                 tape.append(("conv", li, d, x))
             x = y
             li += 1
         elif kind == "fc":
-            y = pn.posit_gemm(x, net.w8[li], "p8", "p8", trans_b=True, bias=net.b8[li])
+            y = pn.posit_gemm(x, net.w8[li], fc, fc, trans_b=True, bias=net.b8[li])
             if tape is not None:
                 tape.append(("fc", li, None, x))
             x = y
             li += 1
         elif kind == "relu":
-            x = pn.posit_relu(x, "p8")
+            x = pn.posit_relu(x, fc)
             if tape is not None:
                 tape.append(("relu", None, None, x))
         elif kind == "avgpool":
             if tape is not None:
                 tape.append(("avgpool", None, None, None))
-            x = pn.posit_avgpool2d_fwd(x, "p8", "p8")
+            x = pn.posit_avgpool2d_fwd(x, fc, fc)
         elif kind == "maxpool":
-            x, idx = pn.posit_maxpool2d_fwd(x, "p8")
+            x, idx = pn.posit_maxpool2d_fwd(x, fc)
             if tape is not None:
                 tape.append(("maxpool", None, idx, None))
         elif kind == "flatten":
@@ -86,32 +96,35 @@ def forward(net, x8, tape=None):
     return x
 
 
-def backward_and_update(net, tape, dy, alpha=ALPHA_MINUS_0P1, grads=None):
-    """Back-propagates dy (posit<8,0>) through the tape and applies the SGD update layer by
-    layer.  When `grads` is a list, (layer, dw, db) posit<16,1> tensors are appended to it."""
+def backward_and_update(net, tape, dy, alpha=None, grads=None):
+    """Back-propagates dy (compute format) through the tape and applies the SGD update (alpha: pattern of
+    minus the learning rate in the master format; default the net's -0.1).  When `grads` is a list,
+    (layer, dw, db) tensors in the master format are appended to it."""
+    fc, fm = net.compute, net.master
+    alpha = net.alpha if alpha is None else alpha
     pending = []
     for kind, li, aux, saved in reversed(tape):
         if kind == "fc":
-            dw = pn.posit_gemm(dy, saved, "p8", "p16", trans_a=True)
-            ones = torch.full((dy.shape[0], 1), 0x40, dtype=torch.uint8, device=dy.device)
-            db = pn.posit_gemm(dy, ones, "p8", "p16", trans_a=True).reshape(-1)
-            dx = pn.posit_gemm(dy, net.w8[li], "p8", "p8")
+            dw = pn.posit_gemm(dy, saved, fc, fm, trans_a=True)
+            ones = torch.full((dy.shape[0], 1), net.one, dtype=dy.dtype, device=dy.device)
+            db = pn.posit_gemm(dy, ones, fc, fm, trans_a=True).reshape(-1)
+            dx = pn.posit_gemm(dy, net.w8[li], fc, fc)
             _update(net, li, dw, db, alpha, grads, pending)
             dy = dx
         elif kind == "conv":
-            dw, db = pn.posit_conv2d_bwd_weight(dy, saved, aux, "p8", "p16", with_bias=True)
-            dx = pn.posit_conv2d_bwd_data(dy, net.w8[li], aux, "p8", "p8") if li > 0 else None
+            dw, db = pn.posit_conv2d_bwd_weight(dy, saved, aux, fc, fm, with_bias=True)
+            dx = pn.posit_conv2d_bwd_data(dy, net.w8[li], aux, fc, fc) if li > 0 else None
             _update(net, li, dw, db, alpha, grads, pending)
             dy = dx
         elif kind == "relu":
-            dy = pn.posit_relu_bwd(saved, dy, "p8", "p8")
+            dy = pn.posit_relu_bwd(saved, dy, fc, fc)
         elif kind == "avgpool":
-            dy = pn.posit_avgpool2d_bwd(dy, "p8", "p8")
+            dy = pn.posit_avgpool2d_bwd(dy, fc, fc)
         elif kind == "maxpool":
-            dy = pn.posit_maxpool2d_bwd(dy, aux, "p8")
+            dy = pn.posit_maxpool2d_bwd(dy, aux, fc)
         elif kind == "flatten":
             dy = dy.reshape(saved)
-    _apply_updates(pending, alpha)
+    _apply_updates(pending, alpha, fm, fc)
 
 
 def _update(net, li, dw, db, alpha, grads, pending):
@@ -123,18 +136,18 @@ def _update(net, li, dw, db, alpha, grads, pending):
     pending.append((db, net.b16[li], net.b8[li]))
 
 
-def _apply_updates(pending, alpha):
+def _apply_updates(pending, alpha, fm, fc):
     if pending:
-        pn.posit_axpy_multi(alpha, [g for g, _, _ in pending], [w for _, w, _ in pending], "p16", "p16", fcopy="p8",
+        pn.posit_axpy_multi(alpha, [g for g, _, _ in pending], [w for _, w, _ in pending], fm, fm, fcopy=fc,
                             y_copies=[c for _, _, c in pending])
 
 
-def training_step(net, x_f32, labels, alpha=ALPHA_MINUS_0P1, grads=None):
-    """One full step; returns the logits (posit<8,0>)."""
-    x8 = pn.posit_round(x_f32.contiguous(), "p8")
+def training_step(net, x_f32, labels, alpha=None, grads=None):
+    """One full step; returns the logits (compute format)."""
+    x8 = pn.posit_round(x_f32.contiguous(), net.compute)
     tape = []
     logits = forward(net, x8, tape)
-    dy, _ = loss_gradient(logits, labels)
+    dy, _ = loss_gradient(logits, labels, net.compute, net.loss)
     backward_and_update(net, tape, dy, alpha, grads)
     return logits
 
@@ -147,7 +160,7 @@ class GraphedStep:
     allocator's pools are settled; the weights are put back afterwards, so constructing a
     GraphedStep leaves the network as it was."""
 
-    def __init__(self, net, x_shape, alpha=ALPHA_MINUS_0P1):
+    def __init__(self, net, x_shape, alpha=None):
         dev = net.w16[0].device
         self.net = net
         self.x = torch.zeros(tuple(x_shape), dtype=torch.float32, device=dev)

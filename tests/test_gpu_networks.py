@@ -30,30 +30,41 @@ def test_config4_cifarnet_step_batch128():
         assert needed in names, needed
 
 
-@pytest.mark.parametrize("net,batch", [(workloads.LENET, 64), (workloads.CIFARNET, 128)])
-def test_device_resident_step_matches_layerwise_harness(net, batch):
+FINAL = ("p8_2", "p12_2", "p10_2")  # Sec. 4, Table 4: posit(8,2) layers, posit(12,2) optimizer, posit(10,2) loss
+
+
+@pytest.mark.parametrize("net,batch,fmts", [(workloads.LENET, 64, nn_harness.DEFAULT_FORMATS), (workloads.CIFARNET, 128, nn_harness.DEFAULT_FORMATS),
+                                            (workloads.LENET, 64, FINAL), (workloads.CIFARNET, 32, FINAL)])
+def test_device_resident_step_matches_layerwise_harness(net, batch, fmts):
     """The all-on-GPU step (library glue kernels for ReLU / pooling, nothing on the host) ends in
-    exactly the weights the layer-by-layer, oracle-checked harness ends in."""
+    exactly the weights the layer-by-layer, oracle-checked harness ends in, in the default formats
+    and in the configuration the paper ends up with."""
     import numpy as np
     import torch
 
+    from paper_2105_00053_amd import posit_round as pn_round
     from paper_2105_00053_amd import train_step
     from gpu_util import to_np
 
     x, params, labels = workloads.network_inputs(net, batch)
     state = {}
-    log = nn_harness.training_step(net, batch, x, params, labels, final_state=state)
+    fc, fm, fl = fmts
+    log = nn_harness.training_step(net, batch, x, params, labels, final_state=state, fmts=fmts)
     assert all(bad == 0 for _, _, bad in log)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
-    model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params])
+    model = train_step.Net(net["layers"], [(dev(w), dev(b)) for w, b in params], compute=fc, master=fm, loss=fl)
     logits = train_step.training_step(model, dev(x), torch.from_numpy(labels).cuda())
     torch.cuda.synchronize()
-    assert np.array_equal(to_np(logits, "p8"), state["logits"])
+    assert np.array_equal(to_np(logits, fc), state["logits"])
+    changed = 0
     for li in range(len(params)):
-        assert np.array_equal(to_np(model.w16[li], "p16"), state["W16"][li]), "master weights of layer %d" % li
-        assert np.array_equal(to_np(model.b16[li], "p16"), state["B16"][li])
-        assert np.array_equal(to_np(model.w8[li], "p8"), state["W8"][li])
-        assert np.array_equal(to_np(model.b8[li], "p8"), state["B8"][li])
+        assert np.array_equal(to_np(model.w16[li], fm), state["W16"][li]), "master weights of layer %d" % li
+        assert np.array_equal(to_np(model.b16[li], fm), state["B16"][li])
+        assert np.array_equal(to_np(model.w8[li], fc), state["W8"][li])
+        assert np.array_equal(to_np(model.b8[li], fc), state["B8"][li])
+        before = to_np(pn_round(dev(params[li][0]), fm), fm)
+        changed += int((before != state["W16"][li]).sum())
+    assert changed > 0, "the step must move some master weight"
 
 
 @pytest.mark.parametrize("net,batch", [(workloads.LENET, 64), (workloads.CIFARNET, 32)])
