@@ -8,6 +8,7 @@
 #include "api_common.h"
 #include "conv_desc.h"
 #include "conv_p8_pre.h"
+#include "conv_b8.h"
 
 namespace pnn {
 
@@ -114,6 +115,10 @@ hipError_t p8_conv_launch_nchw(hipStream_t st, const P8ConvProblem& p, const uin
     return p8_conv_launch(st, p, bias, C, fout, wsp, plan, o);
 }
 
+// posit(8,1) / posit(8,2): the byte-gather kernel with fp64 buckets
+template <class F>
+constexpr bool is_b8() { return F::N == 8 && F::ES != 0; }
+
 template <class F>
 GemmPlan conv_plan(const ConvDims& d) {
     return plan_split(d.M, d.N, d.K, 16 * ConvTile<F>::TM, 16 * ConvTile<F>::TN, Arith<F>::L);
@@ -130,6 +135,12 @@ size_t conv_ws(int which, const ConvGeom& g) {
         P8PrePlan pp;
         GemmPlan pplan;
         if (p8_pre_usable(which, g, &pp, &pplan)) b = p8_pre_ws_bytes(pp, pplan);
+    }
+    if constexpr (is_b8<F>()) {
+        if (p8_conv_eligible(which, g)) {
+            const P8ConvProblem p = p8_problem(which, g, nullptr, nullptr);
+            b = b8_conv_plan<F>(p.M, p.N, p.K).ws_bytes;
+        }
     }
     if (which == 2) {  // the bias gradient runs after the weight gradient and reuses the start of the workspace
         const size_t b2 = bias_grad_ws_bytes<F>(g.N, g.K, g.OH * g.OW);
@@ -157,6 +168,15 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
         NchwOut mout{(int64_t)g.OH * g.OW, (int64_t)g.K};
         return hip_status(p8_conv_launch(st, p, (const uint8_t*)bias, y, fout, ws, plan, mout));
     }
+    if constexpr (is_b8<F>()) {
+        if (p8_conv_eligible(0, g)) {
+            const P8ConvProblem p = p8_problem(0, g, x, w);
+            const GemmPlan plan = b8_conv_plan<F>(p.M, p.N, p.K);
+            if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+            NchwOut mout{(int64_t)g.OH * g.OW, (int64_t)g.K};
+            return hip_status(b8_conv_launch<F>(st, p, (const uint8_t*)bias, y, fout, ws, plan, mout));
+        }
+    }
     const GemmPlan plan = conv_plan<F>(d);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
     ConvFwdX<T> a{(const T*)x, g, d.M, d.K};
@@ -183,6 +203,15 @@ int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, c
         if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
         NchwOut mout{(int64_t)g.H * g.W, (int64_t)g.C};
         return hip_status(p8_conv_launch(st, p, nullptr, dx, fout, ws, plan, mout));
+    }
+    if constexpr (is_b8<F>()) {
+        if (p8_conv_eligible(1, g)) {
+            const P8ConvProblem p = p8_problem(1, g, dy, w);
+            const GemmPlan plan = b8_conv_plan<F>(p.M, p.N, p.K);
+            if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
+            NchwOut mout{(int64_t)g.H * g.W, (int64_t)g.C};
+            return hip_status(b8_conv_launch<F>(st, p, nullptr, dx, fout, ws, plan, mout));
+        }
     }
     const GemmPlan plan = conv_plan<F>(d);
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
@@ -217,15 +246,26 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
         p8p = p8_problem(2, g, dy, x);
         plan = p8_conv_plan(p8p.M, p8p.N, p8p.K);
     }
+    bool fastb8 = false;
+    if constexpr (is_b8<F>()) {
+        if (p8_conv_eligible(2, g)) {
+            fastb8 = true;
+            p8p = p8_problem(2, g, dy, x);
+            plan = b8_conv_plan<F>(p8p.M, p8p.N, p8p.K);
+        }
+    }
     if (plan.ws_bytes > 0 && (!ws || ws_bytes < plan.ws_bytes)) return PNN_EWORKSPACE;
     if (dbias && bias_ws > 0 && (!ws || ws_bytes < bias_ws)) return PNN_EWORKSPACE;
     ConvBwdWeightDy<T> a{(const T*)dy, g, d.M, d.K};
     ConvBwdWeightX<T> b{(const T*)x, g, d.N, d.K};
     RowMajorOut out{d.N};
     hipError_t e;
-    if (fastp8)
+    if (fastp8) {
         e = p8_conv_launch(st, p8p, nullptr, dw, fout, ws, plan, out);
-    else
+    } else if (fastb8) {
+        if constexpr (is_b8<F>()) e = b8_conv_launch<F>(st, p8p, nullptr, dw, fout, ws, plan, out);
+        else e = hipErrorInvalidValue;
+    } else
         e = launch_quire_gemm<F, decltype(a), decltype(b), RowMajorOut, ConvTile<F>::TM, ConvTile<F>::TN>(
             st, a, b, out, d.M, d.N, d.K, nullptr, dw, fout, ws, plan);
     // dbias[k] = sum dy[n,k,:,:] * 1 : one quire per channel; its slice partials reuse the workspace (stream order)

@@ -3,6 +3,7 @@
 // transposition cases).
 #include "api_common.h"
 #include "conv_p8.h"
+#include "conv_b8.h"
 
 namespace pnn {
 
@@ -12,8 +13,15 @@ template <> struct GemmTile<P32> { static constexpr int TM = 2, TN = 2; };
 // posit<8,0> problems with both output dimensions beyond one small tile take the dot2 kernel
 inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
 
+// posit(8,1) / posit(8,2): the byte-gather kernel with fp64 buckets
+template <class F>
+constexpr bool is_b8() { return F::N == 8 && F::ES != 0; }
+
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
+    if constexpr (is_b8<F>()) {
+        if (M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return b8_conv_plan<F>((int)M, (int)N, (int)K);
+    }
     if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K)) {  // one thread group per output: no workspace
         GemmPlan p;
         p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
@@ -53,6 +61,13 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     if ((F::N == 8 && F::ES == 0) && p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
         const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
         return hip_status(p8_conv_launch_rowmajor(st, p, (const uint8_t*)bias, C, fout, ws, plan, ldc));
+    }
+    if constexpr (is_b8<F>()) {
+        if (p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
+            const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
+            RowMajorOut mo{ldc};
+            return hip_status(b8_conv_launch<F>(st, p, (const uint8_t*)bias, C, fout, ws, plan, mo));
+        }
     }
     // op(A)[i,k]: k contiguous unless transA.  op(B)[k,j] seen as rows j: k contiguous only when transB.
     if (!transA && !transB) {

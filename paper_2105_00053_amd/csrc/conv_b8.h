@@ -1,0 +1,246 @@
+// Implicit-GEMM kernel for the 8-bit posit formats other than posit<8,0> (posit(8,1) and
+// posit(8,2) of the paper's experiments, Sec. 4; (8,2) is the format its final configuration
+// runs every layer in): convolution forward, backward-data, backward-weight (Sec. 3.1) and
+// plain matrix products, all quire-exact (Sec. 3.3).
+//
+// Operands are fetched with the byte-gather descriptors of the posit<8,0> kernel (affine row /
+// reduction index maps, 8-byte runs read as aligned words where the layout allows), decoded
+// through an LDS table of 256 doubles into LDS tiles of doubles, and multiplied into the fp64
+// buckets of BucketArith<F>; after every 32-wide slice of the reduction (2^G = 32 products per
+// output for both formats) the buckets are emptied into the integer quire limbs, which the
+// epilogue rounds once.  64 x 64 tile, 256 threads, 4 x 4 outputs per thread.
+#pragma once
+
+#include "conv_p8.h"
+
+namespace pnn {
+
+constexpr int B8_BM = 64, B8_BN = 64;
+
+template <int BR>
+struct B8Stage {
+    typedef P8GatherStage<BR> G;
+    // decode the 16 bytes of every work item and store them as doubles into dst[k][row]
+    __device__ __forceinline__ static void stage(const P8Frag (&f)[G::PER_THREAD], double (*dst)[BR], const double* tab, uint32_t* flags,
+                                                 int t, int mode) {
+#pragma unroll
+        for (int i = 0; i < G::PER_THREAD; ++i) {
+            const int w = t + 256 * i;
+            if (G::ITEMS % 256 != 0 && w >= G::ITEMS) continue;
+            const uint32_t nar = nar_bytes(f[i].w[0]) | nar_bytes(f[i].w[1]) | nar_bytes(f[i].w[2]) | nar_bytes(f[i].w[3]);
+            if (mode == P8_K_RUN) {  // one row, 16 consecutive k
+                const int row = w % BR, kq = w / BR;
+#pragma unroll
+                for (int b = 0; b < 16; ++b) dst[16 * kq + b][row] = tab[(f[i].w[b >> 2] >> (8 * (b & 3))) & 0xFFu];
+                if (nar) flags[row] = 1;
+                continue;
+            }
+            const int kp = w / G::GROUPS, c = (w % G::GROUPS) * 8;  // 8 rows at k = 2 kp and 2 kp + 1
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                double d[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) d[j] = tab[(f[i].w[2 * h + (j >> 2)] >> (8 * (j & 3))) & 0xFFu];
+#pragma unroll
+                for (int j = 0; j < 8; j += 2) *reinterpret_cast<double2*>(&dst[2 * kp + h][c + j]) = make_double2(d[j], d[j + 1]);
+            }
+            if (nar) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t lo = (f[i].w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                    const uint32_t hi = (f[i].w[2 + (j >> 2)] >> (8 * (j & 3))) & 0xFFu;
+                    if (lo == 0x80u || hi == 0x80u) flags[c + j] = 1;
+                }
+            }
+        }
+    }
+};
+
+// `bias` (nullable) is indexed by output column n.  With gridDim.z > 1 the partial quires of this
+// slice of the reduction go to the workspace (L limbs per output) and a merge kernel finishes.
+template <class F>
+__global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8ConvOut out, const uint8_t* __restrict__ bias,
+                                                      void* __restrict__ C, int fout, int M, int N, int K, int k_per_split,
+                                                      int tiles_n, SplitWs ws, int ws_transposed) {
+    typedef BucketAccum<F> AR;
+    static_assert(F::N == 8 && AR::BUCKETS > 0 && (1 << AR::G) >= P8_KT, "8-bit bucketed format, one flush per slice");
+    constexpr int BM = B8_BM, BN = B8_BN, TM = 4, TN = 4, L = AR::L, NB = AR::NB;
+    typedef P8GatherStage<BM> GA;
+    typedef P8GatherStage<BN> GB;
+    __shared__ __attribute__((aligned(16))) double As[2][P8_KT][BM];
+    __shared__ __attribute__((aligned(16))) double Bs[2][P8_KT][BN];
+    __shared__ int4 rinfoA[BM];
+    __shared__ int4 rinfoB[BN];
+    __shared__ int4 kinfoA[2][P8_KT];  // slice kt uses kinfo[kt & 1], filled two iterations ahead
+    __shared__ int4 kinfoB[2][P8_KT];
+    __shared__ double tab[256];
+    __shared__ uint32_t rowNaR[BM];
+    __shared__ uint32_t colNaR[BN];
+
+    const int t = threadIdx.x;
+    const int tx = t & 15, ty = t >> 4;
+    const int tile = blockIdx.x;
+    const int m0 = (tile / tiles_n) * BM, n0 = (tile % tiles_n) * BN;
+    const int kbeg = blockIdx.z * k_per_split;
+    const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
+
+    tab[t] = AR::stage((uint32_t)t);
+    if (t < BM) {
+        int4 ri = make_int4(0, OUT_OF_RANGE, 0, 0);
+        if (m0 + t < M) A.row.eval((uint32_t)(m0 + t), ri.x, ri.y, ri.z);
+        rinfoA[t] = ri;
+        rowNaR[t] = 0;
+    } else if (t < BM + BN) {
+        const int r = t - BM;
+        int4 ri = make_int4(0, OUT_OF_RANGE, 0, 0);
+        if (n0 + r < N) B.row.eval((uint32_t)(n0 + r), ri.x, ri.y, ri.z);
+        rinfoB[r] = ri;
+        colNaR[r] = 0;
+    }
+
+    uint32_t acc[TM][TN][L];
+    double bk[TM][TN][NB];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+#pragma unroll
+            for (int l = 0; l < L; ++l) acc[i][j][l] = 0;
+            AR::clear(bk[i][j]);
+        }
+
+    const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
+    const int tb = (t + 128) & 255;  // each operand has 128 work items: B's go to the threads A leaves idle
+    if (t < P8_KT) p8_fill_kinfo(A, kinfoA[0], kbeg, kend, t);
+    else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[0], kbeg, kend, t - P8_KT);
+    __syncthreads();
+    {
+        P8Frag fa[GA::PER_THREAD], fb[GB::PER_THREAD];
+        if (nkt > 0) {
+            GA::fetch(A, rinfoA, kinfoA[0], kbeg, kend, M - m0, t, fa);
+            GB::fetch(B, rinfoB, kinfoB[0], kbeg, kend, N - n0, tb, fb);
+            if (nkt > 1) {
+                if (t < P8_KT) p8_fill_kinfo(A, kinfoA[1], kbeg + P8_KT, kend, t);
+                else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[1], kbeg + P8_KT, kend, t - P8_KT);
+            }
+            B8Stage<BM>::stage(fa, As[0], tab, rowNaR, t, A.mode);
+            B8Stage<BN>::stage(fb, Bs[0], tab, colNaR, tb, B.mode);
+        }
+    }
+    __syncthreads();
+
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int cur = kt & 1;
+        const bool more = kt + 1 < nkt;
+        P8Frag fa[GA::PER_THREAD], fb[GB::PER_THREAD];
+        if (more) {
+            const int k0 = kbeg + (kt + 1) * P8_KT;
+            GA::fetch(A, rinfoA, kinfoA[cur ^ 1], k0, kend, M - m0, t, fa);
+            GB::fetch(B, rinfoB, kinfoB[cur ^ 1], k0, kend, N - n0, tb, fb);
+        }
+        if (kt + 2 < nkt) {  // kinfo[cur] was last read when slice kt was fetched, one barrier ago
+            const int k2 = kbeg + (kt + 2) * P8_KT;
+            if (t < P8_KT) p8_fill_kinfo(A, kinfoA[cur], k2, kend, t);
+            else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[cur], k2, kend, t - P8_KT);
+        }
+#pragma unroll 2
+        for (int kk = 0; kk < P8_KT; ++kk) {
+            double a[TM], b[TN];
+#pragma unroll
+            for (int q = 0; q < TM; q += 2) {
+                const double2 v = *reinterpret_cast<const double2*>(&As[cur][kk][ty * TM + q]);
+                a[q] = v.x; a[q + 1] = v.y;
+            }
+#pragma unroll
+            for (int q = 0; q < TN; q += 2) {
+                const double2 v = *reinterpret_cast<const double2*>(&Bs[cur][kk][tx * TN + q]);
+                b[q] = v.x; b[q + 1] = v.y;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) AR::mac(bk[i][j], a[i], b[j]);
+        }
+        // 32 products per output since the last flush: the buckets' guard bits are used up
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) AR::template flush<L>(acc[i][j], bk[i][j]);
+        if (more) {
+            B8Stage<BM>::stage(fa, As[cur ^ 1], tab, rowNaR, t, A.mode);
+            B8Stage<BN>::stage(fb, Bs[cur ^ 1], tab, colNaR, tb, B.mode);
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int lr = ty * TM + i;
+        const int m = m0 + lr;
+        if (m >= M) continue;
+        const bool rnar = rowNaR[lr] != 0;
+        const int64_t rp = gridDim.z == 1 ? out.row_part(m) : 0;
+        if (rp < 0) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int lc = tx * TN + j;
+            const int n = n0 + lc;
+            if (n >= N) continue;
+            if (gridDim.z == 1) {
+                bool nar = rnar || colNaR[lc] != 0;
+                if (bias) {
+                    const uint32_t bp = bias[n];
+                    if (bp == F::NAR) nar = true;
+                    else AR::add_bias(acc[i][j], bp);
+                }
+                round_store<AR, L>(acc[i][j], nar, fout, C, rp + (int64_t)n * out.nstride);
+            } else {
+                // partial quire; the merge kernel sees an (Mw x Nw) row-major problem
+                const int64_t z = blockIdx.z;
+                const int64_t idx = ws_transposed ? ((int64_t)n * M + m) : ((int64_t)m * N + n);
+#pragma unroll
+                for (int l = 0; l < L; ++l) ws.limbs[(z * (int64_t)M * N + idx) * L + l] = acc[i][j][l];
+            }
+        }
+    }
+    if (gridDim.z > 1) {
+        const int64_t z = blockIdx.z;
+        uint32_t* rflag = ws_transposed ? ws.colflag : ws.rowflag;  // flags in the orientation of the merge kernel
+        uint32_t* cflag = ws_transposed ? ws.rowflag : ws.colflag;
+        for (int r = t; r < BM; r += 256)
+            if (m0 + r < M && rowNaR[r]) atomicOr(&rflag[z * M + m0 + r], 1u);
+        for (int r = t; r < BN; r += 256)
+            if (n0 + r < N && colNaR[r]) atomicOr(&cflag[z * N + n0 + r], 1u);
+    }
+}
+
+template <class F>
+inline GemmPlan b8_conv_plan(int M, int N, int K) {
+    return plan_split(M, N, K, B8_BM, B8_BN, Arith<F>::L, P8_KT);
+}
+
+// Launch on a problem built by p8_problem / p8_gemm_problem; merge_out maps the merged (Mw x Nw)
+// result to the output tensor.
+template <class F, class Out>
+hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
+                          const GemmPlan& plan, const Out& merge_out) {
+    constexpr int L = Arith<F>::L;
+    const int tiles_m = (p.M + B8_BM - 1) / B8_BM, tiles_n = (p.N + B8_BN - 1) / B8_BN;
+    SplitWs ws;
+    ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)wsp;
+        ws.rowflag = ws.limbs + (size_t)plan.splits * p.M * p.N * L;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * p.Mw;
+        const int64_t nflags = (int64_t)plan.splits * (p.M + p.N);
+        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
+    hipLaunchKernelGGL((b8_conv_kernel<F>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, p.K,
+                       (int)plan.k_per_split, tiles_n, ws, p.transposed);
+    if (plan.splits > 1) launch_split_merge<F, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
+    return hipGetLastError();
+}
+
+}  // namespace pnn

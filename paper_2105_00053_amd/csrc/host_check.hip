@@ -74,9 +74,102 @@ uint32_t dot_noquire_host(int fout, int64_t n, const uint32_t* a, const uint32_t
     if (nar) return fo.nar();
     return AR::read(q, r) ? encode_rt(r, fo) : 0u;
 }
+
+// the same dot product through the fp64 buckets, emptied into the limbs on the kernel's schedule
+// (every FLUSH_SLICES slices of GEMM_KT products and at the end); 0xFFFFFFFF: format has no buckets
+template <class F>
+uint32_t dot_bucket_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    typedef BucketAccum<F> AR;
+    if constexpr (AR::BUCKETS == 0) {
+        return 0xFFFFFFFFu;
+    } else {
+        uint32_t q[AR::L];
+        for (int l = 0; l < AR::L; ++l) q[l] = 0;
+        double bk[AR::NB];
+        AR::clear(bk);
+        bool nar = false;
+        int since = 0;
+        for (int64_t k0 = 0; k0 < n; k0 += GEMM_KT) {
+            for (int64_t i = k0; i < n && i < k0 + GEMM_KT; ++i) {
+                if (a[i] == F::NAR || b[i] == F::NAR) nar = true;
+                AR::mac(bk, AR::stage(a[i]), AR::stage(b[i]));
+            }
+            if (++since == AR::FLUSH_SLICES) {
+                since = 0;
+                AR::template flush<AR::L>(q, bk);
+            }
+        }
+        AR::template flush<AR::L>(q, bk);
+        if (has_bias) {
+            if (bias == F::NAR) nar = true;
+            else AR::add_bias(q, bias);
+        }
+        const FmtRT fo = fmt_of_code(fout);
+        Real r;
+        if (nar) return fo.nar();
+        return AR::read(q, r) ? encode_rt(r, fo) : 0u;
+    }
+}
+// the limbs after adding m * 2^T(j) (bucket j = 1..B of the format, |m| <= 2^53) to zeroed limbs; returns the limb count
+template <class F, int J>
+int flush_one(int j, double m, uint32_t* out) {
+    typedef BucketAccum<F> AR;
+    if constexpr (J > AR::NB) {
+        return 0;
+    } else {
+        if (j != J) return flush_one<F, J + 1>(j, m, out);
+        uint32_t q[AR::L];
+        for (int l = 0; l < AR::L; ++l) q[l] = 0;
+        quire_add_double<AR::L, AR::T(J)>(q, m * pow2d(AR::T(J)));
+        for (int l = 0; l < AR::L; ++l) out[l] = q[l];
+        return AR::L;
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+uint32_t hostcheck_dot_bucket(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    switch (fin) {
+        case 1: return dot_bucket_host<P16>(fout, n, a, b, has_bias, bias);
+        case 3: return dot_bucket_host<P8_1>(fout, n, a, b, has_bias, bias);
+        case 4: return dot_bucket_host<P8_2>(fout, n, a, b, has_bias, bias);
+        case 5: return dot_bucket_host<P10_1>(fout, n, a, b, has_bias, bias);
+        case 6: return dot_bucket_host<P10_2>(fout, n, a, b, has_bias, bias);
+        case 7: return dot_bucket_host<P12_1>(fout, n, a, b, has_bias, bias);
+        case 8: return dot_bucket_host<P12_2>(fout, n, a, b, has_bias, bias);
+        default: return 0xFFFFFFFFu;
+    }
+}
+
+int hostcheck_bucket_flush(int fin, int j, double m, uint32_t* out) {
+    switch (fin) {
+        case 1: return flush_one<P16, 1>(j, m, out);
+        case 3: return flush_one<P8_1, 1>(j, m, out);
+        case 4: return flush_one<P8_2, 1>(j, m, out);
+        case 5: return flush_one<P10_1, 1>(j, m, out);
+        case 6: return flush_one<P10_2, 1>(j, m, out);
+        case 7: return flush_one<P12_1, 1>(j, m, out);
+        case 8: return flush_one<P12_2, 1>(j, m, out);
+        default: return 0;
+    }
+}
+
+// buckets, guard bits G (2^G products between flushes) and cut position T(1) of the format; 0 buckets: not bucketed
+void hostcheck_bucket_config(int fin, int* buckets, int* guard, int* top_cut) {
+    *buckets = 0; *guard = 0; *top_cut = 0;
+    switch (fin) {
+        case 1: *buckets = BucketArith<P16>::B; *guard = BucketArith<P16>::G; *top_cut = BucketArith<P16>::T(1); break;
+        case 3: *buckets = BucketArith<P8_1>::B; *guard = BucketArith<P8_1>::G; *top_cut = BucketArith<P8_1>::T(1); break;
+        case 4: *buckets = BucketArith<P8_2>::B; *guard = BucketArith<P8_2>::G; *top_cut = BucketArith<P8_2>::T(1); break;
+        case 5: *buckets = BucketArith<P10_1>::B; *guard = BucketArith<P10_1>::G; *top_cut = BucketArith<P10_1>::T(1); break;
+        case 6: *buckets = BucketArith<P10_2>::B; *guard = BucketArith<P10_2>::G; *top_cut = BucketArith<P10_2>::T(1); break;
+        case 7: *buckets = BucketArith<P12_1>::B; *guard = BucketArith<P12_1>::G; *top_cut = BucketArith<P12_1>::T(1); break;
+        case 8: *buckets = BucketArith<P12_2>::B; *guard = BucketArith<P12_2>::G; *top_cut = BucketArith<P12_2>::T(1); break;
+        default: break;
+    }
+}
 
 uint32_t hostcheck_dot_noquire(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
     switch (fin) {

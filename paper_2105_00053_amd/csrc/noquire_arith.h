@@ -90,9 +90,11 @@ struct NoQuire {
     typedef uint32_t Elem;
     static constexpr int L = 1;
     static constexpr bool SPLITTABLE = false;  // the result depends on the order of the terms
+    static constexpr int BUCKETS = 0;
     PNN_HD static Elem stage(uint32_t p) { return p == F::NAR ? 0u : p; }  // NaR is tracked by flags outside
     PNN_HD static void mac(uint32_t (&q)[1], Elem a, Elem b) { q[0] = posit_add<F>(q[0], posit_mul<F>(a, b)); }
     PNN_HD static void add_value(uint32_t (&q)[1], Elem a) { q[0] = posit_add<F>(q[0], a); }
+    PNN_HD static void add_bias(uint32_t (&q)[1], uint32_t pattern) { add_value(q, stage(pattern)); }
     // the running posit as a real number (false: zero)
     PNN_HD static bool read(const uint32_t (&q)[1], Real& r) {
         if (q[0] == 0) return false;

@@ -218,4 +218,126 @@ struct Arith<P32> {
     }
 };
 
+// ---- exact accumulation in fp64 "buckets" (formats of at most 16 bits other than posit<8,0>) ----
+//
+// The quire (Sec. 2) is an exact fixed-point sum; how the sum is carried between two
+// read-outs is free as long as it stays exact.  Scaled by 2^MAXS every finite operand is an
+// integer of at most 2^(2 MAXS), so a product is an integer P with |P| <= 2^R, R = 4 MAXS,
+// whose significand has at most 28 bits: P itself is always a double, only the *sum* is too
+// wide.  The sum is therefore kept in B doubles ("buckets"); bucket j only ever receives
+// multiples of 2^T_j that are at most 2^(53+T_j-G) in magnitude, so 2^G additions into it are
+// exact.  A product is cut into its bucket parts with exact floating-point steps:
+//     t = fma(a, b, C_1),  C_1 = 1.5 * 2^(52+T_1):  t - C_1 = P rounded to a multiple of 2^T_1  (= h_1)
+//     r = fma(a, b, -h_1)                         :  the rest, |r| <= 2^(T_1-1), exact
+//     (r + C_j) - C_j = h_j, r -= h_j             :  the same cut at T_j for the buckets in between
+// and the last bucket takes what is left.  With T_j = (B-j)(54-G): bucket 1 sees
+// |h_1| <= 2^R and needs R + G - T_1 <= 53, bucket j > 1 sees |h_j| <= 2^(T_(j-1)-1), i.e. exactly
+// 2^(53+T_j-G).  After at most 2^G products per output the buckets are emptied into the integer
+// quire limbs (one 64-bit integer per bucket, shifted by T_j), which is where the sum lives
+// between slices, across a split reduction and at the rounding.  Cost per product: 1, 5, 9 or 13
+// fp64 operations for B = 1..4, against 6 to 60 integer operations of the carry-propagating add.
+constexpr double pow2d(int e) {
+    double r = 1.0;
+    for (; e > 0; --e) r *= 2.0;
+    for (; e < 0; ++e) r *= 0.5;
+    return r;
+}
+
+constexpr int bucket_guard(int R, int B) { return (53 + 54 * (B - 1) - R) / B; }  // largest G the bounds above allow
+constexpr int bucket_count(int R) {
+    for (int B = 1; B <= 4; ++B)
+        if (53 + 54 * (B - 1) - R >= 5 * B) return B;
+    return 0;
+}
+
+// Add d (an integer multiple of 2^T, |d| <= 2^(53+T)) into the limbs.  The integer d / 2^T is read
+// off the mantissas of two sums with "1.5 * 2^e" constants: adding 1.5 * 2^(84+T) leaves
+// round(d / 2^(32+T)) in the low mantissa word (two's complement, |.| <= 2^21), and the exact rest
+// (|rest| <= 2^(31+T), either sign at a tie) plus 1.5 * 2^(52+T) leaves rest / 2^T there modulo 2^32;
+// d / 2^T = high * 2^32 + rest / 2^T, so its low word is that word and its high word is high minus
+// one when the rest is negative.
+template <int L, int T>
+PNN_HD void quire_add_double(uint32_t (&q)[L], double d) {
+    constexpr int idx = T / 32, off = T % 32;
+    constexpr double CH = 1.5 * pow2d(84 + T), CL = 1.5 * pow2d(52 + T);
+    const double th = d + CH;
+    const double rest = d - (th - CH);
+    const double tl = rest + CL;
+    const uint32_t lo = (uint32_t)__builtin_bit_cast(uint64_t, tl);
+    const uint32_t hi = (uint32_t)__builtin_bit_cast(uint64_t, th) - (rest < 0.0 ? 1u : 0u);
+    const int64_t v = (int64_t)(((uint64_t)hi << 32) | lo);
+    const uint64_t sl = (uint64_t)v << off;
+    const uint32_t w0 = (uint32_t)sl, w1 = (uint32_t)(sl >> 32);
+    const uint32_t w2 = off ? (uint32_t)((v >> 32) >> (32 - off)) : (uint32_t)(v >> 63);  // bits 64..95 of the sign-extended shift
+    const uint32_t ext = (uint32_t)(v >> 63);
+    uint32_t carry = 0;
+#pragma unroll
+    for (int l = idx; l < L; ++l) {
+        const uint32_t add = (l == idx) ? w0 : (l == idx + 1) ? w1 : (l == idx + 2) ? w2 : ext;
+        const uint64_t t = (uint64_t)q[l] + add + carry;
+        q[l] = (uint32_t)t;
+        carry = (uint32_t)(t >> 32);
+    }
+}
+
+template <class F>
+struct BucketArith {
+    static constexpr int R = 4 * F::MAXS;
+    static constexpr bool ELIGIBLE = F::N <= 16 && !(F::N == 8 && F::ES == 0);
+    static constexpr int B = ELIGIBLE ? bucket_count(R) : 0;
+    static constexpr int NB = B > 0 ? B : 1;
+    static constexpr int G = B > 0 ? (bucket_guard(R, NB) < 16 ? bucket_guard(R, NB) : 16) : 0;  // products per output between flushes: 2^G
+    static constexpr int T(int j) { return (NB - j) * (54 - G); }                                    // j = 1..B; T(B) = 0
+    static_assert(B == 0 || (G >= 5 && R + G - T(1) <= 53 && R <= 51 + T(1)), "bucket bounds");
+
+    typedef double Elem;
+    // value * 2^MAXS, an integer; zero and NaR stage as 0 (NaR is carried by the row / column flags)
+    PNN_HD static Elem stage(uint32_t p) {
+        if (p == 0 || p == F::NAR) return 0.0;
+        bool neg;
+        uint32_t sig;
+        int sh;
+        decode_fixed<F>(p, neg, sig, sh);
+        const double v = __builtin_ldexp((double)(int32_t)sig, sh);
+        return neg ? -v : v;
+    }
+    PNN_HD static void clear(double (&bk)[NB]) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) bk[j] = 0.0;
+    }
+    PNN_HD static void mac(double (&bk)[NB], Elem a, Elem b) {
+        if constexpr (NB == 1) {
+            bk[0] = __builtin_fma(a, b, bk[0]);
+        } else {
+            constexpr double C1 = 1.5 * pow2d(52 + T(1));
+            const double h1 = __builtin_fma(a, b, C1) - C1;
+            bk[0] += h1;
+            double r = __builtin_fma(a, b, -h1);
+            cut<2>(bk, r);
+            bk[NB - 1] += r;
+        }
+    }
+    template <int J>
+    PNN_HD static void cut(double (&bk)[NB], double& r) {
+        if constexpr (J < NB) {
+            constexpr double Cj = 1.5 * pow2d(52 + T(J));
+            const double h = (r + Cj) - Cj;
+            bk[J - 1] += h;
+            r -= h;
+            cut<J + 1>(bk, r);
+        }
+    }
+    // Empty the buckets into the limbs (L limbs, accumulated modulo 2^(32 L)).
+    template <int L>
+    PNN_HD static void flush(uint32_t (&q)[L], double (&bk)[NB]) {
+        flush_from<L, 1>(q, bk);
+        clear(bk);
+    }
+    template <int L, int J>
+    PNN_HD static void flush_from(uint32_t (&q)[L], const double (&bk)[NB]) {
+        quire_add_double<L, T(J)>(q, bk[J - 1]);
+        if constexpr (J < NB) flush_from<L, J + 1>(q, bk);
+    }
+};
+
 }  // namespace pnn

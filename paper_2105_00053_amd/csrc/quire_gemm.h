@@ -174,11 +174,35 @@ constexpr int GEMM_KT = 16;
 
 // Accumulator policy "quire": Arith<F> plus the read-out of the limbs as a real number.
 // SPLITTABLE: partial accumulators of slices of the reduction can be merged exactly.
+// BUCKETS: fp64 buckets carried per output beside the limbs (0: products go straight into the limbs).
 template <class F>
 struct QuireAccum : Arith<F> {
     static constexpr bool SPLITTABLE = true;
+    static constexpr int BUCKETS = 0;
     PNN_HD static bool read(const uint32_t (&q)[Arith<F>::L], Real& r) { return quire_read<F, Arith<F>::L>(q, r); }
+    PNN_HD static void add_bias(uint32_t (&q)[Arith<F>::L], uint32_t pattern) { Arith<F>::add_value(q, Arith<F>::stage(pattern)); }
 };
+
+// Accumulator policy "quire through fp64 buckets": the same exact sum, with the products of up to
+// 2^G reduction steps gathered in BUCKETS doubles per output before they enter the limbs
+// (BucketArith).  Everything outside the inner loop (bias, split merge, read-out) is integer.
+template <class F>
+struct BucketAccum : BucketArith<F> {
+    static constexpr int L = Arith<F>::L;
+    static constexpr bool SPLITTABLE = true;
+    static constexpr int BUCKETS = BucketArith<F>::B;
+    static constexpr int FLUSH_SLICES = (1 << BucketArith<F>::G) / GEMM_KT;  // slices of the reduction between two flushes
+    static_assert(BUCKETS == 0 || FLUSH_SLICES >= 1, "a slice must fit the guard bits");
+    PNN_HD static bool read(const uint32_t (&q)[L], Real& r) { return quire_read<F, L>(q, r); }
+    PNN_HD static void add_bias(uint32_t (&q)[L], uint32_t pattern) { Arith<F>::add_value(q, Arith<F>::stage(pattern)); }
+};
+
+template <class F, bool BUCKETED = (BucketArith<F>::B > 0)>
+struct DefaultAccumOf { typedef QuireAccum<F> type; };
+template <class F>
+struct DefaultAccumOf<F, true> { typedef BucketAccum<F> type; };
+template <class F>
+using DefaultAccum = typename DefaultAccumOf<F>::type;
 
 // Round an accumulator of policy AR to the output format chosen at run time (format
 // code of the C ABI) and store it in that format's container.
@@ -224,6 +248,15 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int l = 0; l < L; ++l) acc[i][j][l] = 0;
+    constexpr int NBK = AR::BUCKETS > 0 ? AR::BUCKETS : 1;
+    double bk[TM][TN][NBK];  // fp64 buckets of the bucketed policies (unused otherwise)
+    int since_flush = 0;
+    if constexpr (AR::BUCKETS > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) AR::clear(bk[i][j]);
+    }
 
     for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
         __syncthreads();  // previous slice fully consumed (and flags initialised)
@@ -255,8 +288,26 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) AR::mac(acc[i][j], a[i], b[j]);
+                for (int j = 0; j < TN; ++j) {
+                    if constexpr (AR::BUCKETS > 0) AR::mac(bk[i][j], a[i], b[j]);
+                    else AR::mac(acc[i][j], a[i], b[j]);
+                }
         }
+        if constexpr (AR::BUCKETS > 0) {
+            if (++since_flush == AR::FLUSH_SLICES) {  // the buckets' guard bits are used up: empty them into the limbs
+                since_flush = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) AR::template flush<L>(acc[i][j], bk[i][j]);
+            }
+        }
+    }
+    if constexpr (AR::BUCKETS > 0) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) AR::template flush<L>(acc[i][j], bk[i][j]);
     }
     __syncthreads();
 
@@ -273,7 +324,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
                 if (bias) {
                     const uint32_t bp = bias[n];
                     if (bp == FIN::NAR) nar = true;
-                    else AR::add_value(acc[i][j], AR::stage(bp));
+                    else AR::add_bias(acc[i][j], bp);
                 }
                 round_store<AR, L>(acc[i][j], nar, fout, C, out(m, n));
             }
@@ -555,7 +606,7 @@ inline GemmPlan plan_split(int64_t M, int64_t N, int64_t K, int BM, int BN, int 
     return p;
 }
 
-template <class FIN, class OpA, class OpB, class Out, int TM, int TN, class AR = QuireAccum<FIN>>
+template <class FIN, class OpA, class OpB, class Out, int TM, int TN, class AR = DefaultAccum<FIN>>
 hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb, const Out& out,
                              int64_t M, int64_t N, int64_t K, const void* bias, void* C, int fout,
                              void* workspace, const GemmPlan& plan) {

@@ -32,6 +32,10 @@ def hc():
     L.hostcheck_conv_gather.argtypes = [ci, vp, ci, i64, i64, vp, vp, vp]
     L.hostcheck_dot_noquire.restype = ctypes.c_uint32
     L.hostcheck_dot_noquire.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
+    L.hostcheck_dot_bucket.restype = ctypes.c_uint32
+    L.hostcheck_dot_bucket.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
+    L.hostcheck_bucket_config.argtypes = [ci, vp, vp, vp]
+    L.hostcheck_bucket_flush.argtypes = [ci, ci, ctypes.c_double, vp]
     L.hostcheck_posit_op.restype = ctypes.c_uint32
     L.hostcheck_posit_op.argtypes = [ci, ci, ctypes.c_uint32, ctypes.c_uint32]
     L.hostcheck_div_int.restype = ctypes.c_uint32
@@ -235,6 +239,184 @@ def test_quire_dot_wraps_like_the_oracle(hc):
     for K in (32767, 32768, 40000):
         want, _ = fast.gemm(a16[:K].reshape(1, K), a16[:K].reshape(K, 1), "p16", "p16", threads=1)
         assert hc.hostcheck_dot(1, 1, K, _p(a16), _p(a16), 0, 0) == int(want[0, 0])
+
+
+BUCKETED = ["p16", "p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2"]
+
+
+def _bucket_config(hc, fmt):
+    vals = [ctypes.c_int(0) for _ in range(3)]
+    hc.hostcheck_bucket_config(CODE[fmt], *[ctypes.byref(v) for v in vals])
+    return tuple(v.value for v in vals)
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_bounds_hold_for_the_format(hc, fmt):
+    """The inequalities that make the fp64 buckets exact, re-derived here from the format alone: with
+    R = 4 (n-2) 2^es the bit length of the largest product in quire units, B buckets cut at multiples
+    of 54-G, 2^G products of magnitude 2^R must not push the top bucket past 2^53 of its units, and
+    the rounding constant 1.5 * 2^(52+T1) must dominate a product."""
+    f = po.FORMATS[fmt]
+    R = 4 * (f.n - 2) * (1 << f.es)
+    B, G, T1 = _bucket_config(hc, fmt)
+    assert B >= 1 and G >= 5 and (1 << G) >= 16
+    assert T1 == (B - 1) * (54 - G)
+    assert R + G - T1 <= 53
+    assert R <= 51 + T1 or B == 1
+    assert 2 * (f.n - 2 - f.es) + 2 <= 53  # a product's significand is a double
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_dot_random(hc, fmt):
+    rng = np.random.default_rng(BITS[fmt] * 11 + CODE[fmt])
+    fouts = [fmt, "p16", "p8"]
+    for trial in range(240):
+        K = int(rng.integers(0, 100)) if trial % 6 else int(rng.integers(100, 3000))
+        special = [0.0, 0.05, 0.5][trial % 3]
+        a = _patterns(rng, K, fmt, special).astype(np.uint32)
+        b = _patterns(rng, K, fmt, special).astype(np.uint32)
+        if trial % 4:
+            nar = 1 << (BITS[fmt] - 1)
+            a[a == nar] = 1
+            b[b == nar] = 1
+        if trial % 7 == 3 and K >= 2:
+            a[1] = a[0]
+            b[1] = (-b[0].astype(np.int64)) & ((1 << BITS[fmt]) - 1)
+        has_bias = trial % 2
+        bias = int(_patterns(rng, 1, fmt, 0.1)[0])
+        fout = fouts[trial % 3]
+        got = hc.hostcheck_dot_bucket(CODE[fmt], CODE[fout], K, _p(a), _p(b), has_bias, bias)
+        want, _ = fast.gemm(a.reshape(1, K), b.reshape(K, 1), fmt, fout, bias=np.array([bias]) if has_bias else None, threads=1)
+        assert got == int(want[0, 0]), (trial, K, fout)
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_dot_at_the_bounds(hc, fmt):
+    """Inputs that fill the guard bits of every bucket: runs of maxpos^2 of one sign as long as several
+    flush intervals, minpos^2 terms underneath them, products just below / at / above every cut
+    position, and exact cancellation that leaves one unit of the quire."""
+    n = BITS[fmt]
+    full = (1 << n) - 1
+    maxpos, minpos, one = (1 << (n - 1)) - 1, 1, 1 << (n - 2)
+    neg = lambda p: (-p) & full
+    B, G, T1 = _bucket_config(hc, fmt)
+    flush = 1 << G
+    cases = []
+    for K in (flush - 1, flush, flush + 1, 2 * flush + 17, 5000):
+        cases.append((np.full(K, maxpos), np.full(K, maxpos)))                      # + maxpos^2 each
+        cases.append((np.full(K, maxpos), np.full(K, neg(maxpos))))                 # - maxpos^2 each
+        a = np.full(K, maxpos); b = np.full(K, maxpos); a[1::2] = minpos; b[1::2] = neg(minpos)
+        cases.append((a, b))                                                        # maxpos^2 - minpos^2 alternating
+        a = np.full(K, maxpos); b = np.full(K, maxpos); b[K // 2:] = neg(maxpos); a[-1] = minpos; b[-1] = minpos
+        cases.append((a, b))                                                        # cancels down to (K odd: +maxpos^2) + minpos^2
+    rng = np.random.default_rng(CODE[fmt])
+    # every pair of "power of two with full fraction" neighbours: products land on all bit positions, cut positions included
+    pos = np.arange(1, 1 << (n - 1), dtype=np.int64)
+    for rep in range(6):
+        K = 4096
+        a = rng.choice(pos, K); b = rng.choice(pos, K)
+        sgn = rng.random(K) < 0.5
+        a = np.where(sgn, a, (-a) & full)
+        # sort by magnitude so that long runs of similar scale hit one bucket
+        if rep % 2:
+            order = np.argsort(a & (full >> 1)); a, b = a[order], b[order]
+        cases.append((a, b))
+    for a, b in cases:
+        a = np.asarray(a).astype(np.uint32); b = np.asarray(b).astype(np.uint32)
+        K = len(a)
+        for fout in (fmt, "p32"):
+            got = hc.hostcheck_dot_bucket(CODE[fmt], CODE[fout], K, _p(a), _p(b), 0, 0)
+            want, _ = fast.gemm(a.reshape(1, K), b.reshape(K, 1), fmt, fout, threads=1)
+            assert got == int(want[0, 0]), (K, fout)
+            assert got == hc.hostcheck_dot(CODE[fmt], CODE[fout], K, _p(a), _p(b), 0, 0)
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_flush_converts_every_integer_exactly(hc, fmt):
+    """Emptying a bucket holding m * 2^T adds exactly m << T (two's complement) to the limbs: ties of
+    the high / low split (m = k 2^32 +- 2^31), the extremes +-2^53, small and random m."""
+    B, G, _ = _bucket_config(hc, fmt)
+    rng = np.random.default_rng(5)
+    ms = [0, 1, -1, 2**31, -2**31, 2**31 - 1, -2**31 - 1, 2**32, -2**32, 3 * 2**31, -3 * 2**31, 5 * 2**31, -5 * 2**31,
+          2**53, -2**53, 2**53 - 1, -(2**53 - 1), 2**52 + 2**31, -(2**52 + 2**31), (2**20 + 1) * 2**32 + 2**31, -((2**20 + 2) * 2**32 + 2**31)]
+    ms += [int(v) for v in rng.integers(-2**53, 2**53, 300)]
+    ms += [int(k) * 2**32 + int(r) for k, r in zip(rng.integers(-2**20, 2**20, 100), rng.choice([2**31, -2**31, 2**31 - 1, -2**31 + 1, 0], 100))]
+    out = (ctypes.c_uint32 * 16)()
+    for j in range(1, B + 1):
+        T = (B - j) * (54 - G)
+        for m in ms:
+            L = hc.hostcheck_bucket_flush(CODE[fmt], j, float(m), out)
+            assert L > 0 and float(m) == m
+            got = sum(int(out[l]) << (32 * l) for l in range(L))
+            assert got == (m << T) % (1 << (32 * L)), (fmt, j, m)
+
+
+def _product_pairs(fmt):
+    """Positive pattern pairs of the format with their products in quire units (Python integers)."""
+    f = po.FORMATS[fmt]
+    maxs = (f.n - 2) * (1 << f.es)
+    pats = range(1, 1 << (f.n - 1)) if f.n <= 10 else [p for p in range(1, 1 << (f.n - 1)) if p % 17 == 0 or (p & (p + 1)) == 0 or (p & (p - 1)) == 0]
+    vals = [(p, int(po.decode(p, f) * (1 << maxs))) for p in pats]
+    return vals
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_guard_bits_are_needed_and_enough(hc, fmt):
+    """For every bucket: as many copies of the largest product that lands wholly in it as fit
+    between two flushes (and 2x, 4x, 8x that many, which only stay exact because the buckets are
+    emptied in between), then one product worth a single unit of that bucket, then the copies again
+    with the other sign.  The exact sum is that one unit; any lost bit shows in the result."""
+    n = BITS[fmt]
+    full = (1 << n) - 1
+    B, G, T1 = _bucket_config(hc, fmt)
+    f = po.FORMATS[fmt]
+    R = 4 * (f.n - 2) * (1 << f.es)
+    cuts = [(B - j) * (54 - G) for j in range(1, B + 1)]  # T_1 .. T_B = 0
+    vals = _product_pairs(fmt)
+    by_value = {}
+    for p, v in vals:
+        by_value.setdefault(v, p)
+    import bisect
+    sorted_vals = sorted(by_value)
+    def pair_with_product(pred_best):
+        """(a, b, P) maximising / selecting P through pred_best(P) -> key or None."""
+        best = None
+        for p, v in vals[:: max(1, len(vals) // 400)] + vals[-40:] + vals[:40]:
+            for q, w in vals[:: max(1, len(vals) // 400)] + vals[-40:] + vals[:40]:
+                key = pred_best(v * w)
+                if key is not None and (best is None or key > best[0]):
+                    best = (key, p, q, v * w)
+        return best
+    flush = 1 << G
+    checked = 0
+    for j, T in enumerate(cuts, start=1):
+        upper = R if j == 1 else cuts[j - 2] - 1  # products of at most 2^upper land wholly in bucket j or below
+        big = pair_with_product(lambda P: P if (P <= (1 << upper) and P % (1 << T) == 0) else None)
+        small = pair_with_product(lambda P: -P if (P % (1 << (T + 1)) == (1 << T)) else None)  # lowest set bit is bit T; smallest such
+        assert big is not None and small is not None, (fmt, j)
+        _, ba, bb, bP = big
+        _, sa, sb, sP = small
+        for mult in (1, 2, 4, 8):
+            nb = mult * flush - 1
+            if nb > 300000:
+                continue
+            for lead in (0, 5, 16):
+                a = np.concatenate([np.zeros(lead), np.full(nb, ba), [sa], np.full(nb, ba)]).astype(np.uint32)
+                b = np.concatenate([np.zeros(lead), np.full(nb, bb), [sb], np.full(nb, (-bb) & full)]).astype(np.uint32)
+                K = len(a)
+                got = hc.hostcheck_dot_bucket(CODE[fmt], CODE["p32"], K, _p(a), _p(b), 0, 0)
+                want, _ = fast.gemm(np.array([[sa]]), np.array([[sb]]), fmt, "p32", threads=1)  # the one surviving product
+                assert got == int(want[0, 0]), (fmt, j, mult, lead)
+                checked += 1
+    assert checked >= 3 * B
+
+
+def test_bucket_dot_wraps_like_the_quire(hc):
+    """posit<8,1>: 56 quire bits in a 64-bit word; 2^16 products of maxpos^2 = 2^48 quire units overflow it."""
+    for K in (30000, 40000, 70000):
+        a = np.full(K, 0x7F, dtype=np.uint32)
+        want, _ = fast.gemm(a.reshape(1, K), a.reshape(K, 1), "p8_1", "p8_1", threads=1)
+        assert hc.hostcheck_dot_bucket(CODE["p8_1"], CODE["p8_1"], K, _p(a), _p(a), 0, 0) == int(want[0, 0])
 
 
 def test_conv_gather_descriptors_match_direct_indexing(hc):
