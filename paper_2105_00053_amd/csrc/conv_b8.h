@@ -8,14 +8,15 @@
 // through an LDS table of 256 doubles into LDS tiles of doubles, and multiplied into the fp64
 // buckets of BucketArith<F>; after every 32-wide slice of the reduction (2^G = 32 products per
 // output for both formats) the buckets are emptied into the integer quire limbs, which the
-// epilogue rounds once.  64 x 64 tile, 256 threads, 4 x 4 outputs per thread.
+// epilogue rounds once.  256 threads as 16 x 16, TM x TN outputs per thread: workgroup tiles of
+// 64 x 64, 128 x 32, 32 x 32 or 16 x 16, chosen per problem (small layers need many small tiles
+// to occupy the chip, a 32-channel layer wastes half of a 64-wide tile).
 #pragma once
 
 #include "conv_p8.h"
 
 namespace pnn {
 
-constexpr int B8_BM = 64, B8_BN = 64;
 
 template <int BR>
 struct B8Stage {
@@ -58,13 +59,14 @@ struct B8Stage {
 
 // `bias` (nullable) is indexed by output column n.  With gridDim.z > 1 the partial quires of this
 // slice of the reduction go to the workspace (L limbs per output) and a merge kernel finishes.
-template <class F>
+template <class F, int TM, int TN>
 __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8ConvOut out, const uint8_t* __restrict__ bias,
                                                       void* __restrict__ C, int fout, int M, int N, int K, int k_per_split,
                                                       int tiles_n, SplitWs ws, int ws_transposed) {
     typedef BucketAccum<F> AR;
     static_assert(F::N == 8 && AR::BUCKETS > 0 && (1 << AR::G) >= P8_KT, "8-bit bucketed format, one flush per slice");
-    constexpr int BM = B8_BM, BN = B8_BN, TM = 4, TN = 4, L = AR::L, NB = AR::NB;
+    constexpr int BM = 16 * TM, BN = 16 * TN, L = AR::L, NB = AR::NB;
+    static_assert(BM % 8 == 0 && BN % 8 == 0 && BM + BN <= 256, "tile shape");
     typedef P8GatherStage<BM> GA;
     typedef P8GatherStage<BN> GB;
     __shared__ __attribute__((aligned(16))) double As[2][P8_KT][BM];
@@ -110,7 +112,8 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
         }
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
-    const int tb = (t + 128) & 255;  // each operand has 128 work items: B's go to the threads A leaves idle
+    // B's work items go to the threads A's leave idle when both fit the workgroup
+    const int tb = (GA::ITEMS + GB::ITEMS <= 256) ? ((t + 256 - GA::ITEMS) & 255) : t;
     if (t < P8_KT) p8_fill_kinfo(A, kinfoA[0], kbeg, kend, t);
     else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[0], kbeg, kend, t - P8_KT);
     __syncthreads();
@@ -146,15 +149,25 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
 #pragma unroll 2
         for (int kk = 0; kk < P8_KT; ++kk) {
             double a[TM], b[TN];
+            if constexpr (TM % 2 == 0) {
 #pragma unroll
-            for (int q = 0; q < TM; q += 2) {
-                const double2 v = *reinterpret_cast<const double2*>(&As[cur][kk][ty * TM + q]);
-                a[q] = v.x; a[q + 1] = v.y;
+                for (int q = 0; q < TM; q += 2) {
+                    const double2 v = *reinterpret_cast<const double2*>(&As[cur][kk][ty * TM + q]);
+                    a[q] = v.x; a[q + 1] = v.y;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < TM; ++q) a[q] = As[cur][kk][ty * TM + q];
             }
+            if constexpr (TN % 2 == 0) {
 #pragma unroll
-            for (int q = 0; q < TN; q += 2) {
-                const double2 v = *reinterpret_cast<const double2*>(&Bs[cur][kk][tx * TN + q]);
-                b[q] = v.x; b[q + 1] = v.y;
+                for (int q = 0; q < TN; q += 2) {
+                    const double2 v = *reinterpret_cast<const double2*>(&Bs[cur][kk][tx * TN + q]);
+                    b[q] = v.x; b[q + 1] = v.y;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < TN; ++q) b[q] = Bs[cur][kk][tx * TN + q];
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -214,9 +227,31 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
     }
 }
 
+// Workgroup tile.  Larger tiles reuse staged operands more; smaller ones waste less of a ragged
+// edge and give the 256 CUs enough workgroups on small layers.  Score = useful fraction of the
+// tiles x how far the grid fills the chip (a long reduction can be split instead) x operand reuse.
+struct B8Tile { int bm, bn; };
+static const B8Tile B8_TILES[] = {{64, 64}, {128, 32}, {32, 32}, {16, 16}};
+
+inline B8Tile b8_tile(int M, int N, int K) {
+    const bool can_split = K >= 1024;
+    B8Tile best = B8_TILES[0];
+    double best_score = -1.0;
+    for (const B8Tile& t : B8_TILES) {
+        const int64_t blocks = (int64_t)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+        const double util = ((double)M * N) / ((double)blocks * t.bm * t.bn);
+        const double fill = (can_split || blocks >= 512) ? 1.0 : (double)blocks / 512.0;
+        const double reuse = (double)(t.bm * t.bn) / (t.bm + t.bn) / 32.0;  // MACs per staged element, relative to 64 x 64
+        const double score = util * fill * (0.5 + 0.5 * reuse);
+        if (score > best_score) { best_score = score; best = t; }
+    }
+    return best;
+}
+
 template <class F>
 inline GemmPlan b8_conv_plan(int M, int N, int K) {
-    return plan_split(M, N, K, B8_BM, B8_BN, Arith<F>::L, P8_KT);
+    const B8Tile tl = b8_tile(M, N, K);
+    return plan_split(M, N, K, tl.bm, tl.bn, Arith<F>::L, P8_KT);
 }
 
 // Launch on a problem built by p8_problem / p8_gemm_problem; merge_out maps the merged (Mw x Nw)
@@ -225,7 +260,8 @@ template <class F, class Out>
 hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t* bias, void* C, int fout, void* wsp,
                           const GemmPlan& plan, const Out& merge_out) {
     constexpr int L = Arith<F>::L;
-    const int tiles_m = (p.M + B8_BM - 1) / B8_BM, tiles_n = (p.N + B8_BN - 1) / B8_BN;
+    const B8Tile tl = b8_tile(p.M, p.N, p.K);
+    const int tiles_m = (p.M + tl.bm - 1) / tl.bm, tiles_n = (p.N + tl.bn - 1) / tl.bn;
     SplitWs ws;
     ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
     if (plan.splits > 1) {
@@ -237,8 +273,14 @@ hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
-    hipLaunchKernelGGL((b8_conv_kernel<F>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, p.K,
-                       (int)plan.k_per_split, tiles_n, ws, p.transposed);
+#define PNN_LAUNCH_B8(TM, TN)                                                                                                  \
+    hipLaunchKernelGGL((b8_conv_kernel<F, TM, TN>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, p.K, \
+                       (int)plan.k_per_split, tiles_n, ws, p.transposed)
+    if (tl.bm == 64) PNN_LAUNCH_B8(4, 4);
+    else if (tl.bm == 128) PNN_LAUNCH_B8(8, 2);
+    else if (tl.bm == 32) PNN_LAUNCH_B8(2, 2);
+    else PNN_LAUNCH_B8(1, 1);
+#undef PNN_LAUNCH_B8
     if (plan.splits > 1) launch_split_merge<F, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
     return hipGetLastError();
 }
