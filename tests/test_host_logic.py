@@ -351,63 +351,23 @@ def test_bucket_flush_converts_every_integer_exactly(hc, fmt):
             assert got == (m << T) % (1 << (32 * L)), (fmt, j, m)
 
 
-def _product_pairs(fmt):
-    """Positive pattern pairs of the format with their products in quire units (Python integers)."""
-    f = po.FORMATS[fmt]
-    maxs = (f.n - 2) * (1 << f.es)
-    pats = range(1, 1 << (f.n - 1)) if f.n <= 10 else [p for p in range(1, 1 << (f.n - 1)) if p % 17 == 0 or (p & (p + 1)) == 0 or (p & (p - 1)) == 0]
-    vals = [(p, int(po.decode(p, f) * (1 << maxs))) for p in pats]
-    return vals
-
-
 @pytest.mark.parametrize("fmt", BUCKETED)
 def test_bucket_guard_bits_are_needed_and_enough(hc, fmt):
     """For every bucket: as many copies of the largest product that lands wholly in it as fit
     between two flushes (and 2x, 4x, 8x that many, which only stay exact because the buckets are
     emptied in between), then one product worth a single unit of that bucket, then the copies again
     with the other sign.  The exact sum is that one unit; any lost bit shows in the result."""
-    n = BITS[fmt]
-    full = (1 << n) - 1
+    import bucket_cases
     B, G, T1 = _bucket_config(hc, fmt)
-    f = po.FORMATS[fmt]
-    R = 4 * (f.n - 2) * (1 << f.es)
-    cuts = [(B - j) * (54 - G) for j in range(1, B + 1)]  # T_1 .. T_B = 0
-    vals = _product_pairs(fmt)
-    by_value = {}
-    for p, v in vals:
-        by_value.setdefault(v, p)
-    import bisect
-    sorted_vals = sorted(by_value)
-    def pair_with_product(pred_best):
-        """(a, b, P) maximising / selecting P through pred_best(P) -> key or None."""
-        best = None
-        for p, v in vals[:: max(1, len(vals) // 400)] + vals[-40:] + vals[:40]:
-            for q, w in vals[:: max(1, len(vals) // 400)] + vals[-40:] + vals[:40]:
-                key = pred_best(v * w)
-                if key is not None and (best is None or key > best[0]):
-                    best = (key, p, q, v * w)
-        return best
-    flush = 1 << G
+    lay = bucket_cases.bucket_layout(fmt)
+    assert (B, G, T1) == (lay[0], lay[1], lay[2][0])  # the test's own derivation agrees with the library's constants
     checked = 0
-    for j, T in enumerate(cuts, start=1):
-        upper = R if j == 1 else cuts[j - 2] - 1  # products of at most 2^upper land wholly in bucket j or below
-        big = pair_with_product(lambda P: P if (P <= (1 << upper) and P % (1 << T) == 0) else None)
-        small = pair_with_product(lambda P: -P if (P % (1 << (T + 1)) == (1 << T)) else None)  # lowest set bit is bit T; smallest such
-        assert big is not None and small is not None, (fmt, j)
-        _, ba, bb, bP = big
-        _, sa, sb, sP = small
-        for mult in (1, 2, 4, 8):
-            nb = mult * flush - 1
-            if nb > 300000:
-                continue
-            for lead in (0, 5, 16):
-                a = np.concatenate([np.zeros(lead), np.full(nb, ba), [sa], np.full(nb, ba)]).astype(np.uint32)
-                b = np.concatenate([np.zeros(lead), np.full(nb, bb), [sb], np.full(nb, (-bb) & full)]).astype(np.uint32)
-                K = len(a)
-                got = hc.hostcheck_dot_bucket(CODE[fmt], CODE["p32"], K, _p(a), _p(b), 0, 0)
-                want, _ = fast.gemm(np.array([[sa]]), np.array([[sb]]), fmt, "p32", threads=1)  # the one surviving product
-                assert got == int(want[0, 0]), (fmt, j, mult, lead)
-                checked += 1
+    for a, b, (sa, sb) in bucket_cases.guard_cases(fmt):
+        K = len(a)
+        got = hc.hostcheck_dot_bucket(CODE[fmt], CODE["p32"], K, _p(a), _p(b), 0, 0)
+        want, _ = fast.gemm(np.array([[sa]]), np.array([[sb]]), fmt, "p32", threads=1)  # the one surviving product
+        assert got == int(want[0, 0]), (fmt, K)
+        checked += 1
     assert checked >= 3 * B
 
 
