@@ -20,13 +20,11 @@ PNN_HD void quire_add32(uint32_t (&q)[L], int32_t P, int s) {
     const uint32_t x0 = (uint32_t)wide;
     const uint32_t x1 = (uint32_t)((uint64_t)wide >> 32);
     const uint32_t ext = (uint32_t)((int32_t)x1 >> 31);
-    uint32_t carry = 0;
+    unsigned carry = 0;
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         const uint32_t add = (l < idx) ? 0u : (l == idx) ? x0 : (l == idx + 1) ? x1 : ext;
-        const uint64_t t = (uint64_t)q[l] + add + carry;
-        q[l] = (uint32_t)t;
-        carry = (uint32_t)(t >> 32);
+        q[l] = __builtin_addc(q[l], add, carry, &carry);
     }
 }
 
@@ -39,13 +37,11 @@ PNN_HD void quire_add64(uint32_t (&q)[L], int64_t P, int s) {
     const uint32_t x1 = (uint32_t)(lo >> 32);
     const uint32_t x2 = (uint32_t)((P >> 32) >> (32 - off));  // bits 64..95 of the sign-extended shift
     const uint32_t ext = (uint32_t)((int32_t)x2 >> 31);
-    uint32_t carry = 0;
+    unsigned carry = 0;
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         const uint32_t add = (l < idx) ? 0u : (l == idx) ? x0 : (l == idx + 1) ? x1 : (l == idx + 2) ? x2 : ext;
-        const uint64_t t = (uint64_t)q[l] + add + carry;
-        q[l] = (uint32_t)t;
-        carry = (uint32_t)(t >> 32);
+        q[l] = __builtin_addc(q[l], add, carry, &carry);
     }
 }
 
@@ -53,13 +49,9 @@ PNN_HD void quire_add64(uint32_t (&q)[L], int64_t P, int s) {
 // associative and exact modulo 2^(32 L).
 template <int L>
 PNN_HD void quire_merge(uint32_t (&q)[L], const uint32_t (&o)[L]) {
-    uint32_t carry = 0;
+    unsigned carry = 0;
 #pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const uint64_t t = (uint64_t)q[l] + o[l] + carry;
-        q[l] = (uint32_t)t;
-        carry = (uint32_t)(t >> 32);
-    }
+    for (int l = 0; l < L; ++l) q[l] = __builtin_addc(q[l], o[l], carry, &carry);
 }
 
 // Narrow an accumulator held in L limbs to its true width QB (sign-extend from bit QB-1).
@@ -270,13 +262,11 @@ PNN_HD void quire_add_double(uint32_t (&q)[L], double d) {
     const uint32_t w0 = (uint32_t)sl, w1 = (uint32_t)(sl >> 32);
     const uint32_t w2 = off ? (uint32_t)((v >> 32) >> (32 - off)) : (uint32_t)(v >> 63);  // bits 64..95 of the sign-extended shift
     const uint32_t ext = (uint32_t)(v >> 63);
-    uint32_t carry = 0;
+    unsigned carry = 0;
 #pragma unroll
     for (int l = idx; l < L; ++l) {
         const uint32_t add = (l == idx) ? w0 : (l == idx + 1) ? w1 : (l == idx + 2) ? w2 : ext;
-        const uint64_t t = (uint64_t)q[l] + add + carry;
-        q[l] = (uint32_t)t;
-        carry = (uint32_t)(t >> 32);
+        q[l] = __builtin_addc(q[l], add, carry, &carry);  // one add-with-carry per limb
     }
 }
 
