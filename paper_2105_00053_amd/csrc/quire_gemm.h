@@ -9,7 +9,9 @@
 // KT-wide slice of the reduction, the threads fetch patterns from HBM, decode
 // them once (Eq. 2) into the staged form of Arith<FIN>, and park them in LDS;
 // then each thread multiplies its TM x TN register tile against the slice,
-// adding every exact product into per-output quire limbs held in VGPRs.  NaR
+// adding every exact product into per-output quire limbs held in VGPRs
+// (directly, or through fp64 buckets that are emptied into the limbs before
+// their guard bits run out: accumulator policies below).  NaR
 // never enters the arithmetic: a NaR pattern is staged as zero and raises an
 // LDS flag for its row (of A) or column (of B), applied when the tile is
 // rounded.  With gridDim.z > 1 the reduction is split across workgroups, which
