@@ -228,8 +228,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
     constexpr int L = AR::L;
     constexpr int BM = 16 * TM, BN = 16 * TN, KT = GEMM_KT;
 
-    __shared__ Elem As[KT][BM + 1];
-    __shared__ Elem Bs[KT][BN + 1];
+    __shared__ Elem As[2][KT][BM + 1];  // double-buffered: slice kt + 1 is staged while slice kt is multiplied
+    __shared__ Elem Bs[2][KT][BN + 1];
     __shared__ uint32_t rowNaR[BM];
     __shared__ uint32_t colNaR[BN];
 
@@ -260,33 +260,64 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
             for (int j = 0; j < TN; ++j) AR::clear(bk[i][j]);
     }
 
-    for (int64_t k0 = kbeg; k0 < kend; k0 += KT) {
-        __syncthreads();  // previous slice fully consumed (and flags initialised)
-        // stage A: consecutive threads walk the dimension that is contiguous in memory
-        for (int e = tid; e < BM * KT; e += GEMM_THREADS) {
+    // Element e = tid + 256 i of a slice: consecutive threads walk the dimension that is contiguous in memory.
+    constexpr int EA = BM * KT / GEMM_THREADS, EB = BN * KT / GEMM_THREADS;
+    static_assert(BM * KT % GEMM_THREADS == 0 && BN * KT % GEMM_THREADS == 0, "whole elements per thread");
+    uint32_t pa[EA], pb[EB];  // patterns of the next slice, fetched before the current one is multiplied
+    auto fetch = [&](int64_t k0) {
+#pragma unroll
+        for (int i = 0; i < EA; ++i) {
+            const int e = tid + GEMM_THREADS * i;
             const int kk = OpA::KFAST ? (e % KT) : (e / BM);
             const int r = OpA::KFAST ? (e / KT) : (e % BM);
             const int64_t k = k0 + kk;
-            const uint32_t p = (k < kend) ? opa(m0 + r, k) : 0u;
-            if (p == FIN::NAR) rowNaR[r] = 1;
-            As[kk][r] = AR::stage(p);
+            pa[i] = (k < kend) ? opa(m0 + r, k) : 0u;
         }
-        for (int e = tid; e < BN * KT; e += GEMM_THREADS) {
+#pragma unroll
+        for (int i = 0; i < EB; ++i) {
+            const int e = tid + GEMM_THREADS * i;
             const int kk = OpB::KFAST ? (e % KT) : (e / BN);
             const int r = OpB::KFAST ? (e / KT) : (e % BN);
             const int64_t k = k0 + kk;
-            const uint32_t p = (k < kend) ? opb(n0 + r, k) : 0u;
-            if (p == FIN::NAR) colNaR[r] = 1;
-            Bs[kk][r] = AR::stage(p);
+            pb[i] = (k < kend) ? opb(n0 + r, k) : 0u;
         }
-        __syncthreads();
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < EA; ++i) {
+            const int e = tid + GEMM_THREADS * i;
+            const int kk = OpA::KFAST ? (e % KT) : (e / BM);
+            const int r = OpA::KFAST ? (e / KT) : (e % BM);
+            if (pa[i] == FIN::NAR) rowNaR[r] = 1;
+            As[buf][kk][r] = AR::stage(pa[i]);
+        }
+#pragma unroll
+        for (int i = 0; i < EB; ++i) {
+            const int e = tid + GEMM_THREADS * i;
+            const int kk = OpB::KFAST ? (e % KT) : (e / BN);
+            const int r = OpB::KFAST ? (e / KT) : (e % BN);
+            if (pb[i] == FIN::NAR) colNaR[r] = 1;
+            Bs[buf][kk][r] = AR::stage(pb[i]);
+        }
+    };
+
+    __syncthreads();  // flags initialised before any stage() raises one
+    if (kbeg < kend) {
+        fetch(kbeg);
+        stage(0);
+    }
+    __syncthreads();
+    int cur = 0;
+    for (int64_t k0 = kbeg; k0 < kend; k0 += KT, cur ^= 1) {
+        const bool more = k0 + KT < kend;
+        if (more) fetch(k0 + KT);
 #pragma unroll 2
         for (int kk = 0; kk < KT; ++kk) {
             Elem a[TM], b[TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i) a[i] = As[kk][ty * TM + i];
+            for (int i = 0; i < TM; ++i) a[i] = As[cur][kk][ty * TM + i];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) b[j] = Bs[kk][tx * TN + j];
+            for (int j = 0; j < TN; ++j) b[j] = Bs[cur][kk][tx * TN + j];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -304,6 +335,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
                     for (int j = 0; j < TN; ++j) AR::template flush<L>(acc[i][j], bk[i][j]);
             }
         }
+        if (more) stage(cur ^ 1);  // the other buffer was last read one barrier ago
+        __syncthreads();
     }
     if constexpr (AR::BUCKETS > 0) {
 #pragma unroll
