@@ -26,8 +26,6 @@ hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
         ws.limbs = (uint32_t*)wsp;
         ws.rowflag = ws.limbs + (size_t)plan.splits * p.M * p.N;
         ws.colflag = ws.rowflag + (size_t)plan.splits * p.Mw;
-        const int64_t nflags = (int64_t)plan.splits * (p.M + p.N);
-        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;
@@ -72,8 +70,6 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
         ws.limbs = (uint32_t*)(wbytes + pp.bytes[0] + pp.bytes[1]);
         ws.rowflag = ws.limbs + (size_t)plan.splits * pp.M * pp.N;
         ws.colflag = ws.rowflag + (size_t)plan.splits * pp.Mw;
-        const int64_t nflags = (int64_t)plan.splits * (pp.M + pp.N);
-        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;

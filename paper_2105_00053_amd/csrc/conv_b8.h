@@ -220,10 +220,14 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
         const int64_t z = blockIdx.z;
         uint32_t* rflag = ws_transposed ? ws.colflag : ws.rowflag;  // flags in the orientation of the merge kernel
         uint32_t* cflag = ws_transposed ? ws.rowflag : ws.colflag;
-        for (int r = t; r < BM; r += 256)
-            if (m0 + r < M && rowNaR[r]) atomicOr(&rflag[z * M + m0 + r], 1u);
-        for (int r = t; r < BN; r += 256)
-            if (n0 + r < N && colNaR[r]) atomicOr(&cflag[z * N + n0 + r], 1u);
+        // the first tile column stores the row flags of its tile row (identical in every column), the
+        // first tile row the column flags: every entry is written, so the workspace needs no clearing
+        if (n0 == 0)
+            for (int r = t; r < BM; r += 256)
+                if (m0 + r < M) rflag[z * M + m0 + r] = rowNaR[r];
+        if (m0 == 0)
+            for (int r = t; r < BN; r += 256)
+                if (n0 + r < N) cflag[z * N + n0 + r] = colNaR[r];
     }
 }
 
@@ -268,8 +272,6 @@ hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
         ws.limbs = (uint32_t*)wsp;
         ws.rowflag = ws.limbs + (size_t)plan.splits * p.M * p.N * L;
         ws.colflag = ws.rowflag + (size_t)plan.splits * p.Mw;
-        const int64_t nflags = (int64_t)plan.splits * (p.M + p.N);
-        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, st, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     const uint8_t* kbias = plan.splits > 1 ? nullptr : bias;

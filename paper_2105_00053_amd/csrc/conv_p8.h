@@ -339,10 +339,14 @@ __device__ __forceinline__ void p8_conv_epilogue(const int32_t (&acc)[TM][TN], c
         // flags in the orientation of the merge kernel: its rows are our columns when transposed
         uint32_t* rflag = ws_transposed ? ws.colflag : ws.rowflag;
         uint32_t* cflag = ws_transposed ? ws.rowflag : ws.colflag;
-        for (int r = t; r < BM; r += 256)
-            if (m0 + r < M && rowNaR[r]) atomicOr(&rflag[z * M + m0 + r], 1u);
-        for (int r = t; r < BN; r += 256)
-            if (n0 + r < N && colNaR[r]) atomicOr(&cflag[z * N + n0 + r], 1u);
+        // the first tile column stores the row flags of its tile row (identical in every column), the
+        // first tile row the column flags: every entry is written, so the workspace needs no clearing
+        if (n0 == 0)
+            for (int r = t; r < BM; r += 256)
+                if (m0 + r < M) rflag[z * M + m0 + r] = rowNaR[r];
+        if (m0 == 0)
+            for (int r = t; r < BN; r += 256)
+                if (n0 + r < N) cflag[z * N + n0 + r] = colNaR[r];
     }
 }
 

@@ -304,11 +304,13 @@ __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
                 if (n < N) lim[(int64_t)m * N + n] = (uint32_t)acc[i][j];
             }
         }
+        // the first tile column stores the row flags of its tile row (identical in every column), the
+        // first tile row the column flags: every entry is written, so the workspace needs no clearing
         if (t < P8_BM) {
-            if (m0 + t < M && rowNaR[t]) atomicOr(&ws.rowflag[z * M + m0 + t], 1u);
+            if (n0 == 0 && m0 + t < M) ws.rowflag[z * M + m0 + t] = rowNaR[t];
         } else {
             const int c = t - P8_BM;
-            if (n0 + c < N && colNaR[c]) atomicOr(&ws.colflag[z * N + n0 + c], 1u);
+            if (m0 == 0 && n0 + c < N) ws.colflag[z * N + n0 + c] = colNaR[c];
         }
     }
 }
@@ -328,8 +330,6 @@ hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, con
         ws.limbs = (uint32_t*)workspace;
         ws.rowflag = ws.limbs + (size_t)plan.splits * M * N;
         ws.colflag = ws.rowflag + (size_t)plan.splits * M;
-        const int64_t nflags = (int64_t)plan.splits * (M + N);
-        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((p8_gemm_kernel<A_KFAST, B_KFAST>), grid, dim3(256), 0, stream, A, lda, B, ldb, bias, C, ldc, fout,

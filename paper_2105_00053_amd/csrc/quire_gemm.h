@@ -379,19 +379,16 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
                 for (int l = 0; l < L; ++l) lim[(m * N + n) * L + l] = acc[i][j][l];
             }
         }
-        // several tiles share a row (or column) of flags: OR them together
-        for (int i = tid; i < BM; i += GEMM_THREADS)
-            if (m0 + i < M && rowNaR[i]) atomicOr(&ws.rowflag[z * M + m0 + i], 1u);
-        for (int i = tid; i < BN; i += GEMM_THREADS)
-            if (n0 + i < N && colNaR[i]) atomicOr(&ws.colflag[z * N + n0 + i], 1u);
+        // All tiles of a tile row see the same rows of A over this slice of the reduction, hence the same
+        // row flags: the tile in the first column stores them (every entry, set or not, so the workspace
+        // needs no clearing); likewise the first tile row stores the column flags.
+        if (n0 == 0)
+            for (int i = tid; i < BM; i += GEMM_THREADS)
+                if (m0 + i < M) ws.rowflag[z * M + m0 + i] = rowNaR[i];
+        if (m0 == 0)
+            for (int i = tid; i < BN; i += GEMM_THREADS)
+                if (n0 + i < N) ws.colflag[z * N + n0 + i] = colNaR[i];
     }
-}
-
-// Zero the NaR flags of a split reduction (the limb partials are fully overwritten).
-template <int UNUSED = 0>
-__global__ void split_clear_kernel(uint32_t* p, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
 }
 
 // Merge the per-split partial quires, add the bias, round once, store.  A
@@ -657,8 +654,6 @@ hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb,
         ws.limbs = (uint32_t*)workspace;
         ws.rowflag = ws.limbs + (size_t)plan.splits * M * N * L;
         ws.colflag = ws.rowflag + (size_t)plan.splits * M;
-        const int64_t nflags = (int64_t)plan.splits * (M + N);
-        hipLaunchKernelGGL(split_clear_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, ws.rowflag, nflags);
     }
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN, AR>), grid, dim3(GEMM_THREADS), 0, stream,

@@ -607,3 +607,51 @@ def test_noquire_conv_all_three_passes(ci, fin, fout):
     wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True, noquire=True)
     _assert_equal(to_np(dw, fout), wdw, "noquire conv bwd_weight")
     _assert_equal(to_np(db, fout), wdb, "noquire conv dbias")
+
+
+@pytest.mark.parametrize("fin,fout,M,N,K", [("p8", "p8", 200, 300, 4096), ("p8", "p16", 40, 300, 8192), ("p16", "p16", 150, 200, 2048),
+                                            ("p8_2", "p8_2", 150, 200, 2048), ("p8_1", "p16", 100, 40, 4096), ("p12_1", "p12_1", 70, 130, 2048),
+                                            ("p32", "p32", 40, 70, 1024)])
+def test_split_reduction_nar_flags_on_a_dirty_workspace(fin, fout, M, N, K):
+    """A split reduction over several tile rows and columns, NaR patterns in a few rows of A and columns
+    of B that only some slices of the reduction see, and a workspace full of ones: the flags of every
+    slice are stored afresh by the kernels, nothing depends on what the workspace held."""
+    need = pn.posit_gemm_workspace(fin, fout, False, False, M, N, K)
+    assert need > 0
+    rng = np.random.default_rng(M + N + K)
+    A = rand_patterns(rng, (M, K), fin, special=0.001, allow_nar=False)
+    B = rand_patterns(rng, (K, N), fin, special=0.001, allow_nar=False)
+    nar = 1 << (BITS[fin] - 1)
+    A[3, 7] = nar; A[M - 1, K - 1] = nar; A[M // 2, K // 2] = nar
+    B[11, 5] = nar; B[K - 2, N - 1] = nar
+    for fill in (0xFF, 0x00):
+        ws = torch.full((need + 64,), fill, dtype=torch.uint8, device="cuda")
+        got = pn.posit_gemm(to_dev(A), to_dev(B), fin, fout, workspace=ws)
+        want, _ = fast.gemm(A, B, fin, fout)
+        _assert_equal(to_np(got, fout), want, "split gemm with NaR, workspace filled with %#x" % fill)
+    onar = 1 << (BITS[fout] - 1)
+    assert (want[3] == onar).all() and (want[:, 5] == onar).all() and (want[:, N - 1] == onar).all()
+    assert (want == onar).sum() == 3 * N + 2 * M - 6
+
+
+@pytest.mark.parametrize("fin,fout", [("p8", "p16"), ("p8_2", "p12_2"), ("p16", "p16")])
+def test_conv_bwd_weight_split_nar_on_a_dirty_workspace(fin, fout):
+    """The backward-weight pass is computed transposed and splits its long reduction: NaR in dy (one
+    output channel) and in x (the taps that read that pixel), workspace full of ones."""
+    d = dict(N=16, C=5, H=20, W=20, K=70, R=3, S=3, pad_h=1, pad_w=1)
+    desc = _desc(d)
+    need = pn.posit_conv2d_workspace(2, fin, fout, desc)
+    assert need > 0
+    rng = np.random.default_rng(77)
+    x = rand_patterns(rng, (16, 5, 20, 20), fin, special=0.0, allow_nar=False)
+    dy = rand_patterns(rng, (16, 70, 20, 20), fin, special=0.0, allow_nar=False)
+    nar = 1 << (BITS[fin] - 1)
+    dy[9, 66, 4, 4] = nar
+    x[2, 3, 0, 19] = nar
+    ws = torch.full((need + 64,), 0xFF, dtype=torch.uint8, device="cuda")
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dy), to_dev(x), desc, fin, fout, with_bias=True, workspace=ws)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True)
+    _assert_equal(to_np(dw, fout), wdw, "split bwd_weight with NaR")
+    _assert_equal(to_np(db, fout), wdb, "dbias with NaR")
+    onar = 1 << (BITS[fout] - 1)
+    assert (wdw[66] == onar).all() and 0 < (wdw[0] == onar).sum() < wdw[0].size
