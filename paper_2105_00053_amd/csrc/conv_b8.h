@@ -9,8 +9,9 @@
 // buckets of BucketArith<F>; after every 32-wide slice of the reduction (2^G = 32 products per
 // output for both formats) the buckets are emptied into the integer quire limbs, which the
 // epilogue rounds once.  256 threads as 16 x 16, TM x TN outputs per thread: workgroup tiles of
-// 64 x 64, 128 x 32, 32 x 32 or 16 x 16, chosen per problem (small layers need many small tiles
-// to occupy the chip, a 32-channel layer wastes half of a 64-wide tile).
+// 64 x 64, 64 x 32, 32 x 32 or 16 x 16, chosen per problem (small layers need many small tiles
+// to occupy the chip, a 32-channel layer wastes half of a 64-wide tile; a 128 x 32 tile would need
+// 80 KB of LDS and leave each CU a single workgroup).
 #pragma once
 
 #include "conv_p8.h"
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
 // edge and give the 256 CUs enough workgroups on small layers.  Score = useful fraction of the
 // tiles x how far the grid fills the chip (a long reduction can be split instead) x operand reuse.
 struct B8Tile { int bm, bn; };
-static const B8Tile B8_TILES[] = {{64, 64}, {128, 32}, {32, 32}, {16, 16}};
+static const B8Tile B8_TILES[] = {{64, 64}, {64, 32}, {32, 32}, {16, 16}};
 
 inline B8Tile b8_tile(int M, int N, int K) {
     const bool can_split = K >= 1024;
@@ -278,8 +279,8 @@ hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
 #define PNN_LAUNCH_B8(TM, TN)                                                                                                  \
     hipLaunchKernelGGL((b8_conv_kernel<F, TM, TN>), grid, dim3(256), 0, st, p.A, p.B, p.out, kbias, C, fout, p.M, p.N, p.K, \
                        (int)plan.k_per_split, tiles_n, ws, p.transposed)
-    if (tl.bm == 64) PNN_LAUNCH_B8(4, 4);
-    else if (tl.bm == 128) PNN_LAUNCH_B8(8, 2);
+    if (tl.bm == 64 && tl.bn == 64) PNN_LAUNCH_B8(4, 4);
+    else if (tl.bm == 64) PNN_LAUNCH_B8(4, 2);
     else if (tl.bm == 32) PNN_LAUNCH_B8(2, 2);
     else PNN_LAUNCH_B8(1, 1);
 #undef PNN_LAUNCH_B8
