@@ -20,6 +20,11 @@ constexpr bool is_b8() { return F::N == 8 && F::ES != 0; }
 template <class F>
 GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
     if constexpr (is_b8<F>()) {
+        if (p8_small_gemm_fits(M, N, K)) {  // one thread group per output: no workspace
+            GemmPlan p;
+            p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
+            return p;
+        }
         if (M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return b8_conv_plan<F>((int)M, (int)N, (int)K);
     }
     if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K)) {  // one thread group per output: no workspace
@@ -63,6 +68,9 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
         return hip_status(p8_conv_launch_rowmajor(st, p, (const uint8_t*)bias, C, fout, ws, plan, ldc));
     }
     if constexpr (is_b8<F>()) {
+        if (p8_small_gemm_fits(M, N, K))
+            return hip_status(launch_b8_small_gemm<F>(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C,
+                                                      ldc, fout, M, N, K));
         if (p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
             const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
             RowMajorOut mo{ldc};

@@ -288,4 +288,103 @@ hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     return hipGetLastError();
 }
 
+// Small matrix products (the fully connected layers of the small networks: a few thousand outputs,
+// a reduction of a few hundred): one output per group of S threads that split the reduction, so that
+// the outputs spread over many workgroups instead of one or two tiles walking the reduction slice
+// by slice.  Each thread gathers its products in the fp64 buckets (emptied into its private limbs
+// every 32 products), the S partial quires of an output are summed through LDS (exact) and rounded once.
+//   element strides: A(m,k) = A[m*a_m + k*a_k], B(k,n) = B[k*b_k + n*b_n]
+template <class F>
+__global__ __launch_bounds__(256) void b8_small_gemm_kernel(const uint8_t* __restrict__ A, int64_t a_m, int64_t a_k,
+                                                            const uint8_t* __restrict__ B, int64_t b_k, int64_t b_n,
+                                                            const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout,
+                                                            int M, int N, int K, int S, int k_per_split) {
+    typedef BucketAccum<F> AR;
+    static_assert(F::N == 8 && AR::BUCKETS > 0 && (1 << AR::G) >= 32, "8-bit bucketed format");
+    constexpr int L = AR::L, NB = AR::NB;
+    __shared__ double tab[256];
+    __shared__ uint32_t part[256][L];
+    __shared__ uint32_t nars[256];
+    const int t = threadIdx.x;
+    tab[t] = AR::stage((uint32_t)t);
+    __syncthreads();
+    const int OB = 256 / S;  // outputs per workgroup
+    const int ol = t % OB, s = t / OB;
+    const int64_t o = (int64_t)blockIdx.x * OB + ol;
+    const bool live = o < (int64_t)M * N;
+    const int m = live ? (int)(o / N) : 0, n = live ? (int)(o - (int64_t)m * N) : 0;
+    const int k_lo = s * k_per_split, k_hi = k_lo + k_per_split < K ? k_lo + k_per_split : K;
+    uint32_t q[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) q[l] = 0;
+    double bk[NB];
+    AR::clear(bk);
+    uint32_t nar = 0;
+    if (live) {
+        const uint8_t* ap = A + (int64_t)m * a_m + (int64_t)k_lo * a_k;
+        const uint8_t* bp = B + (int64_t)n * b_n + (int64_t)k_lo * b_k;
+        for (int kb = k_lo; kb < k_hi; kb += 32) {  // at most 32 products between two flushes
+            const int ke = kb + 32 < k_hi ? kb + 32 : k_hi;
+            int k = kb;
+            for (; k + 4 <= ke; k += 4) {
+                uint32_t a[4], b[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = ap[u * a_k];
+                    b[u] = bp[u * b_k];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    nar |= (a[u] == 0x80u) | (b[u] == 0x80u);
+                    AR::mac(bk, tab[a[u]], tab[b[u]]);
+                }
+                ap += 4 * a_k;
+                bp += 4 * b_k;
+            }
+            for (; k < ke; ++k) {
+                const uint32_t a = *ap, b = *bp;
+                nar |= (a == 0x80u) | (b == 0x80u);
+                AR::mac(bk, tab[a], tab[b]);
+                ap += a_k;
+                bp += b_k;
+            }
+            AR::template flush<L>(q, bk);
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l) part[t][l] = q[l];
+    nars[t] = nar;
+    __syncthreads();
+    if (s != 0 || !live) return;
+    for (int z = 1; z < S; ++z) {
+        uint32_t o2[L];
+#pragma unroll
+        for (int l = 0; l < L; ++l) o2[l] = part[z * OB + ol][l];
+        quire_merge<L>(q, o2);
+        nar |= nars[z * OB + ol];
+    }
+    bool isnar = nar != 0;
+    if (bias) {
+        const uint32_t bpat = bias[n];
+        if (bpat == F::NAR) isnar = true;
+        else AR::add_bias(q, bpat);
+    }
+    round_store<AR, L>(q, isnar, fout, C, (int64_t)m * ldc + n);
+}
+
+template <class F>
+inline hipError_t launch_b8_small_gemm(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B,
+                                       int64_t ldb, const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N, int64_t K) {
+    // threads per output: keep at least 32 reduction steps per thread, and stop once about 1024 workgroups exist
+    int S = 1;
+    while (S < 64 && K / (2 * S) >= 32 && (M * N * S) / 256 < 1024) S *= 2;
+    const int kps = (int)((K + S - 1) / S);
+    const int OB = 256 / S;
+    const int64_t blocks = (M * N + OB - 1) / OB;
+    hipLaunchKernelGGL(b8_small_gemm_kernel<F>, dim3((unsigned)blocks), dim3(256), 0, stream, A, transA ? (int64_t)1 : lda,
+                       transA ? lda : (int64_t)1, B, transB ? (int64_t)1 : ldb, transB ? ldb : (int64_t)1, bias, C, ldc, fout, (int)M, (int)N,
+                       (int)K, S, kps);
+    return hipGetLastError();
+}
+
 }  // namespace pnn

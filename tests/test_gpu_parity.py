@@ -484,6 +484,11 @@ GENERAL_GEMM_CASES = [
     ("p16", "p12_2", 40, 35, 50, 0, 0, 1, 1),
     ("p8", "p10_1", 150, 140, 70, 0, 0, 0, 1),   # posit<8,0> packed-dot kernel, general output format
     ("p8_1", "p32", 17, 5, 31, 1, 1, 0, 0),
+    # beyond the small-problem kernel of the 8-bit formats: the tiled byte-gather kernel, all four transposition cases
+    ("p8_2", "p8_2", 300, 260, 900, 1, 1, 1, 1),
+    ("p8_2", "p12_2", 270, 300, 333, 0, 0, 1, 1),
+    ("p8_1", "p16", 520, 130, 700, 0, 1, 1, 1),
+    ("p8_1", "p8_1", 129, 520, 519, 1, 0, 0, 1),
 ]
 
 
@@ -493,16 +498,18 @@ def test_general_formats_gemm(fin, fout, M, N, K, ta, tb, use_bias, nar):
 
 
 @pytest.mark.parametrize("fin,fout,M,N,K", [("p8_2", "p12_2", 32, 96, 8192), ("p12_2", "p12_2", 16, 50, 4096), ("p10_1", "p10_1", 24, 40, 4096),
-                                            ("p8_1", "p8_1", 8, 24, 70000)])
+                                            ("p8_1", "p8_1", 8, 24, 70000), ("p8_2", "p12_2", 64, 288, 8192), ("p8_1", "p8_1", 40, 70, 70000)])
 def test_general_formats_gemm_split_reduction(fin, fout, M, N, K):
-    """Long reductions take the split-K path; posit<8,1> with maxpos operands in one row wraps its 64-bit quire."""
+    """Long reductions take the split-K path (the smallest 8-bit problems split over the threads of an output
+    instead, without workspace); posit<8,1> with maxpos operands in one row wraps its 64-bit quire."""
     rng = np.random.default_rng(K + M)
     A = rand_patterns(rng, (M, K), fin, special=0.0, allow_nar=False)
     B = rand_patterns(rng, (K, N), fin, special=0.0, allow_nar=False)
     if fin == "p8_1":
         A[0, :] = 0x7F
         B[:, 0] = 0x7F
-    assert pn.posit_gemm_workspace(fin, fout, False, False, M, N, K) > 0
+    small8 = BITS[fin] == 8 and M * N <= 65536 and M * N * K <= 1 << 26
+    assert (pn.posit_gemm_workspace(fin, fout, False, False, M, N, K) > 0) != small8
     got = pn.posit_gemm(to_dev(A), to_dev(B), fin, fout)
     want, ovf = fast.gemm(A, B, fin, fout)
     if fin == "p8_1":
@@ -610,7 +617,7 @@ def test_noquire_conv_all_three_passes(ci, fin, fout):
 
 
 @pytest.mark.parametrize("fin,fout,M,N,K", [("p8", "p8", 200, 300, 4096), ("p8", "p16", 40, 300, 8192), ("p16", "p16", 150, 200, 2048),
-                                            ("p8_2", "p8_2", 150, 200, 2048), ("p8_1", "p16", 100, 40, 4096), ("p12_1", "p12_1", 70, 130, 2048),
+                                            ("p8_2", "p8_2", 150, 200, 4096), ("p8_1", "p16", 100, 200, 8192), ("p12_1", "p12_1", 70, 130, 2048),
                                             ("p32", "p32", 40, 70, 1024)])
 def test_split_reduction_nar_flags_on_a_dirty_workspace(fin, fout, M, N, K):
     """A split reduction over several tile rows and columns, NaR patterns in a few rows of A and columns
