@@ -32,7 +32,11 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
         p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
         return p;
     }
-    if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) return plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
+    if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
+        GemmPlan p = plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
+        if (p8_packed_gemm_fits(M, N, K)) p.ws_bytes += p8_packed_layout(M, N, K).total();  // operands packed once, ahead of the split partials
+        return p;
+    }
     // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
     if ((F::N == 8 && F::ES == 0) && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
@@ -52,6 +56,11 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K))
         return hip_status(launch_p8_small_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                fout, M, N, K));
+    if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N) && p8_packed_gemm_fits(M, N, K)) {
+        if (((uintptr_t)ws & 15u) != 0) return PNN_EINVAL;  // the packed operands are read in 16-byte runs
+        return hip_status(launch_p8_gemm_packed(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
+                                                fout, M, N, K, ws, plan));
+    }
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
         const uint8_t* a8 = (const uint8_t*)A;
         const uint8_t* b8 = (const uint8_t*)B;

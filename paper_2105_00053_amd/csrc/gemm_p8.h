@@ -134,6 +134,100 @@ __device__ __forceinline__ void p8_stage(const P8Frag& f, uint32_t (*dst)[P8_BM]
     }
 }
 
+// ---- operands decoded and packed once (large products) ----
+//
+// For a product of some 10^10 MACs the per-slice decode of the kernel below (table look-ups and
+// packing: a sixth of its vector instructions) is worth doing once instead: p8_pack_kernel rewrites
+// an operand into the workspace as X2[k-pair][row] = (decoded X(row, 2kp), decoded X(row, 2kp+1)),
+// two int16 in a dword, exactly the word the LDS tiles hold, rows padded to a multiple of 128 and the
+// reduction to a multiple of 32 with zeros.  The main kernel then copies 16-byte runs of X2 straight
+// into LDS.  NaR patterns are stored as zero and raise flags[row] (cleared beforehand).
+//   element strides: X(row, k) = src[row * s_r + k * s_k], one of the strides is 1
+//   s_k == 1: a thread takes one row and 8 k-pairs (16 consecutive bytes); the 32 rows of a half wave
+//             make every store 128 contiguous bytes
+//   s_r == 1: a thread takes one k-pair and 4 consecutive rows (one 16-byte store)
+struct P8PackJob {
+    const uint8_t* src;
+    int64_t s_r, s_k;
+    int rows, K;
+    uint32_t* dst;
+    int Rp, Kp2;
+    uint32_t* flags;
+};
+
+// Both operands are packed by one launch: the first blocks0 workgroups take job0, the rest job1;
+// a job's workgroups are numbered along its rows first (bx), then along the reduction (by).
+template <int UNUSED = 0>
+__global__ __launch_bounds__(256) void p8_pack_kernel(P8PackJob job0, P8PackJob job1, unsigned blocks0) {
+    __shared__ uint16_t tab[256];
+    const int t = threadIdx.x;
+    tab[t] = (uint16_t)Arith<P8>::stage((uint32_t)t);
+    __syncthreads();
+    const bool first = blockIdx.x < blocks0;
+    const P8PackJob& job = first ? job0 : job1;
+    const unsigned lin = first ? blockIdx.x : blockIdx.x - blocks0;
+    const unsigned gx = job.s_k == 1 ? (unsigned)((job.Rp + 31) / 32) : (unsigned)((job.Rp / 4 + 63) / 64);
+    const unsigned bx = lin % gx, by = lin / gx;
+    const uint8_t* __restrict__ src = job.src;
+    const int64_t s_r = job.s_r, s_k = job.s_k;
+    const int rows = job.rows, K = job.K, Rp = job.Rp, Kp2 = job.Kp2;
+    uint32_t* __restrict__ dst = job.dst;
+    uint32_t* __restrict__ flags = job.flags;
+    if (s_k == 1) {
+        // block: 32 rows x 64 k-pairs (8 groups of 8); bx over row blocks, by over groups of 64 k-pairs
+        const int row = (int)bx * 32 + (t & 31);
+        const int kp0 = (int)by * 64 + (t >> 5) * 8;
+        if (row >= Rp || kp0 >= Kp2) return;
+        uint32_t out[8];
+        bool nar = false;
+        const uint8_t* p = src + (int64_t)row * s_r + 2 * (int64_t)kp0;
+        const bool inside = row < rows && 2 * kp0 + 16 <= K;
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (inside && (((uintptr_t)p) & 3u) == 0) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) w[i] = reinterpret_cast<const uint32_t*>(p)[i];
+        } else if (row < rows) {
+#pragma unroll
+            for (int b = 0; b < 16; ++b)
+                if (2 * kp0 + b < K) w[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t lo = (w[j >> 1] >> (16 * (j & 1))) & 0xFFu, hi = (w[j >> 1] >> (16 * (j & 1) + 8)) & 0xFFu;
+            nar |= (lo == 0x80u) | (hi == 0x80u);
+            out[j] = (uint32_t)tab[lo] | ((uint32_t)tab[hi] << 16);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (kp0 + j < Kp2) dst[(int64_t)(kp0 + j) * Rp + row] = out[j];
+        if (nar) atomicOr(&flags[row], 1u);
+    } else {
+        // block: 4 k-pairs x 256 rows; thread = (k-pair, 4 consecutive rows)
+        const int r4 = ((int)bx * 64 + (t & 63)) * 4;
+        const int kp = (int)by * 4 + (t >> 6);
+        if (r4 >= Rp || kp >= Kp2) return;
+        uint32_t out[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = r4 + i;
+            uint32_t lo = 0, hi = 0;
+            if (r < rows) {
+                if (2 * kp < K) lo = src[(int64_t)r * s_r + (int64_t)(2 * kp) * s_k];
+                if (2 * kp + 1 < K) hi = src[(int64_t)r * s_r + (int64_t)(2 * kp + 1) * s_k];
+            }
+            if (lo == 0x80u || hi == 0x80u) atomicOr(&flags[r], 1u);
+            out[i] = (uint32_t)tab[lo] | ((uint32_t)tab[hi] << 16);
+        }
+        *reinterpret_cast<uint4*>(dst + (int64_t)kp * Rp + r4) = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+}
+
+template <int UNUSED = 0>
+__global__ void p8_fill_zero_kernel(uint32_t* p, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
 // int32 quire (units of 2^-12) -> posit<8,0>, nearest, ties to even pattern,
 // clamped to +-minpos / +-maxpos.  32-bit arithmetic only: the bit string after
 // the sign is assembled at the top of a word and cut after 7 bits.
@@ -160,11 +254,14 @@ __device__ __forceinline__ uint32_t p8_round_quire(int32_t q) {
     return neg ? ((0u - body) & 0xFFu) : body;
 }
 
-template <bool A_KFAST, bool B_KFAST>
+// PACKED: A and B point at operands rewritten by p8_pack_kernel (lda, ldb: their padded row counts),
+// rowflag_g / colflag_g at the NaR flags that kernel raised.
+template <bool A_KFAST, bool B_KFAST, bool PACKED = false>
 __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
     const uint8_t* __restrict__ A, int64_t lda, const uint8_t* __restrict__ B, int64_t ldb,
     const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout,
-    int M, int N, int K, int k_per_split, int tiles_m, int tiles_n, int a_aligned, int b_aligned, SplitWs ws) {
+    int M, int N, int K, int k_per_split, int tiles_m, int tiles_n, int a_aligned, int b_aligned, SplitWs ws,
+    const uint32_t* __restrict__ rowflag_g = nullptr, const uint32_t* __restrict__ colflag_g = nullptr) {
     __shared__ __attribute__((aligned(16))) uint32_t As[2][P8_KP][P8_BM];
     __shared__ __attribute__((aligned(16))) uint32_t Bs[2][P8_KP][P8_BN];
     __shared__ uint16_t tab[256];
@@ -190,7 +287,11 @@ __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
     const int kend = (kbeg + k_per_split < K) ? kbeg + k_per_split : K;
 
     tab[t] = (uint16_t)Arith<P8>::stage((uint32_t)t);
-    if (t < P8_BM) rowNaR[t] = 0; else colNaR[t - P8_BM] = 0;
+    if constexpr (PACKED) {  // the flags are known beforehand (padded to whole tiles)
+        if (t < P8_BM) rowNaR[t] = rowflag_g[m0 + t]; else colNaR[t - P8_BM] = colflag_g[n0 + t - P8_BM];
+    } else {
+        if (t < P8_BM) rowNaR[t] = 0; else colNaR[t - P8_BM] = 0;
+    }
 
     int32_t acc[8][8];
 #pragma unroll
@@ -203,6 +304,52 @@ __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
 
     __syncthreads();  // table and flags ready
+    if constexpr (PACKED) {
+        // this thread's two 16-byte runs of a slice: k-pairs t/32 and t/32 + 8, rows (t%32)*4 .. +3; running pointers, one slice = 16 k-pairs
+        const uint32_t* pa = reinterpret_cast<const uint32_t*>(A) + (int64_t)(kbeg / 2 + (t >> 5)) * lda + m0 + (t & 31) * 4;
+        const uint32_t* pb = reinterpret_cast<const uint32_t*>(B) + (int64_t)(kbeg / 2 + (t >> 5)) * ldb + n0 + (t & 31) * 4;
+        const int64_t a_half = 8 * lda, b_half = 8 * ldb;
+        uint32_t* const sa = &As[0][t >> 5][(t & 31) * 4];
+        uint32_t* const sb = &Bs[0][t >> 5][(t & 31) * 4];
+        constexpr int HALF = 8 * P8_BM, BUF = P8_KP * P8_BM;  // dwords between the two runs / the two buffers
+        if (nkt > 0) {
+            const uint4 a0 = *reinterpret_cast<const uint4*>(pa), a1 = *reinterpret_cast<const uint4*>(pa + a_half);
+            const uint4 b0 = *reinterpret_cast<const uint4*>(pb), b1 = *reinterpret_cast<const uint4*>(pb + b_half);
+            *reinterpret_cast<uint4*>(sa) = a0; *reinterpret_cast<uint4*>(sa + HALF) = a1;
+            *reinterpret_cast<uint4*>(sb) = b0; *reinterpret_cast<uint4*>(sb + HALF) = b1;
+        }
+        __syncthreads();
+        for (int kt = 0; kt < nkt; ++kt) {
+            const int cur = kt & 1;
+            const bool more = kt + 1 < nkt;
+            uint4 fa0, fa1, fb0, fb1;
+            if (more) {
+                pa += 2 * a_half;
+                pb += 2 * b_half;
+                fa0 = *reinterpret_cast<const uint4*>(pa); fa1 = *reinterpret_cast<const uint4*>(pa + a_half);
+                fb0 = *reinterpret_cast<const uint4*>(pb); fb1 = *reinterpret_cast<const uint4*>(pb + b_half);
+            }
+#pragma unroll 2
+            for (int kp = 0; kp < P8_KP; ++kp) {
+                const uint4 a0 = *reinterpret_cast<const uint4*>(&As[cur][kp][ty * 4]);
+                const uint4 a1 = *reinterpret_cast<const uint4*>(&As[cur][kp][64 + ty * 4]);
+                const uint4 b0 = *reinterpret_cast<const uint4*>(&Bs[cur][kp][tx * 4]);
+                const uint4 b1 = *reinterpret_cast<const uint4*>(&Bs[cur][kp][64 + tx * 4]);
+                const uint32_t a[8] = {a0.x, a0.y, a0.z, a0.w, a1.x, a1.y, a1.z, a1.w};
+                const uint32_t b[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
+            }
+            if (more) {
+                const int nxt = (cur ^ 1) * BUF;
+                *reinterpret_cast<uint4*>(sa + nxt) = fa0; *reinterpret_cast<uint4*>(sa + nxt + HALF) = fa1;
+                *reinterpret_cast<uint4*>(sb + nxt) = fb0; *reinterpret_cast<uint4*>(sb + nxt + HALF) = fb1;
+            }
+            __syncthreads();
+        }
+    } else {
     if (nkt > 0) {
         const bool kin = kbeg + P8_KT <= kend;
         const P8Frag fa = p8_fetch<A_KFAST>(A, lda, M, m0, kbeg, kend, t, a_rows_in && kin);
@@ -240,6 +387,8 @@ __global__ __launch_bounds__(256, 4) void p8_gemm_kernel(
             p8_stage<B_KFAST>(fb, Bs[cur ^ 1], tab, colNaR, t);
         }
         __syncthreads();
+    }
+
     }
 
     // rows / columns of this thread's register tile
@@ -334,6 +483,76 @@ hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, con
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((p8_gemm_kernel<A_KFAST, B_KFAST>), grid, dim3(256), 0, stream, A, lda, B, ldb, bias, C, ldc, fout,
                        (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, a_al, b_al, ws);
+    if (plan.splits > 1) {
+        RowMajorOut out{ldc};
+        launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
+    }
+    return hipGetLastError();
+}
+
+// ---- large problems: operands packed once ----
+
+// Worth it when the saved per-slice decode outweighs one more pass over the operands.
+inline bool p8_packed_gemm_fits(int64_t M, int64_t N, int64_t K) {
+    return M >= 1024 && N >= 1024 && K >= 1024 && M * N * K >= ((int64_t)1 << 34) && M < ((int64_t)1 << 30) && N < ((int64_t)1 << 30);
+}
+
+struct P8PackedLayout {
+    int64_t Mp, Np, Kp2;          // rows padded to 128, k-pairs padded to 16
+    size_t a_bytes, b_bytes, flag_bytes;
+    size_t total() const { return a_bytes + b_bytes + flag_bytes; }
+};
+
+inline P8PackedLayout p8_packed_layout(int64_t M, int64_t N, int64_t K) {
+    P8PackedLayout l;
+    l.Mp = (M + P8_BM - 1) / P8_BM * P8_BM;
+    l.Np = (N + P8_BN - 1) / P8_BN * P8_BN;
+    l.Kp2 = (K + P8_KT - 1) / P8_KT * P8_KP;
+    l.a_bytes = (size_t)l.Kp2 * l.Mp * sizeof(uint32_t);
+    l.b_bytes = (size_t)l.Kp2 * l.Np * sizeof(uint32_t);
+    l.flag_bytes = (size_t)(l.Mp + l.Np) * sizeof(uint32_t);
+    return l;
+}
+
+inline dim3 p8_pack_grid(const P8PackJob& j) {
+    if (j.s_k == 1) return dim3((unsigned)((j.Rp + 31) / 32), (unsigned)((j.Kp2 + 63) / 64));
+    return dim3((unsigned)((j.Rp / 4 + 63) / 64), (unsigned)((j.Kp2 + 3) / 4));
+}
+
+inline void launch_p8_pack(hipStream_t stream, const P8PackJob& a, const P8PackJob& b) {
+    const dim3 ga = p8_pack_grid(a), gb = p8_pack_grid(b);
+    const unsigned na = ga.x * ga.y, nb = gb.x * gb.y;
+    hipLaunchKernelGGL(p8_pack_kernel<0>, dim3(na + nb), dim3(256), 0, stream, a, b, na);
+}
+
+// Workspace: [A2][B2][row flags (Mp)][column flags (Np)][partial quires and flags of a split reduction].
+inline hipError_t launch_p8_gemm_packed(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B,
+                                        int64_t ldb, const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N,
+                                        int64_t K, void* workspace, const GemmPlan& plan) {
+    const P8PackedLayout l = p8_packed_layout(M, N, K);
+    uint8_t* wb = (uint8_t*)workspace;
+    uint32_t* A2 = (uint32_t*)wb;
+    uint32_t* B2 = (uint32_t*)(wb + l.a_bytes);
+    uint32_t* rowflag = (uint32_t*)(wb + l.a_bytes + l.b_bytes);
+    uint32_t* colflag = rowflag + l.Mp;
+    const int64_t nflags = l.Mp + l.Np;
+    hipLaunchKernelGGL(p8_fill_zero_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, rowflag, nflags);
+    // op(A)(m, k): stride (lda, 1), transposed (1, lda); op(B)(k, n) seen as rows n: stride (1, ldb), transposed (ldb, 1)
+    const P8PackJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, A2, (int)l.Mp, (int)l.Kp2, rowflag};
+    const P8PackJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, B2, (int)l.Np, (int)l.Kp2, colflag};
+    launch_p8_pack(stream, ja, jb);
+    const int tiles_m = (int)(l.Mp / P8_BM), tiles_n = (int)(l.Np / P8_BN);
+    SplitWs ws;
+    ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
+    if (plan.splits > 1) {
+        ws.limbs = (uint32_t*)(wb + l.total());
+        ws.rowflag = ws.limbs + (size_t)plan.splits * M * N;
+        ws.colflag = ws.rowflag + (size_t)plan.splits * M;
+    }
+    dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
+    hipLaunchKernelGGL((p8_gemm_kernel<true, true, true>), grid, dim3(256), 0, stream, (const uint8_t*)A2, l.Mp, (const uint8_t*)B2, l.Np,
+                       bias, C, ldc, fout, (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, 1, 1, ws,
+                       (const uint32_t*)rowflag, (const uint32_t*)colflag);
     if (plan.splits > 1) {
         RowMajorOut out{ldc};
         launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);

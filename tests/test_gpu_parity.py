@@ -256,6 +256,42 @@ def test_config5_p8_gemm_large_sampled(S):
     assert np.array_equal(Cn, ((-C.astype(np.int16)) & 0xFF).astype(np.uint8))
 
 
+@pytest.mark.parametrize("M,N,K,ta,tb,fout", [(2100, 2050, 4000, 0, 0, "p8"), (2048, 2176, 4100, 1, 0, "p16"), (2300, 2048, 3999, 0, 1, "p8"),
+                                              (2050, 2100, 4033, 1, 1, "p8"), (1100, 1030, 16400, 0, 0, "p8")])
+def test_p8_gemm_packed_operands_path(M, N, K, ta, tb, fout):
+    """Products of more than 2^34 MACs first rewrite both operands (decoded, pair-packed, padded) into the
+    workspace: ragged sizes, the four transposition cases, NaR in rows and columns near the edges, a bias,
+    and (last case) a split reduction behind the packed operands.  Sampled rows against the oracle, the NaR
+    rows and columns in full."""
+    assert M * N * K >= 1 << 34
+    assert pn.posit_gemm_workspace("p8", fout, ta, tb, M, N, K) >= 4 * (K // 2) * (M + N)
+    rng = np.random.default_rng(M + K)
+    A = rand_patterns(rng, (K, M) if ta else (M, K), "p8", special=0.001, allow_nar=False)
+    B = rand_patterns(rng, (N, K) if tb else (K, N), "p8", special=0.001, allow_nar=False)
+    bias = rand_patterns(rng, (N,), "p8", allow_nar=False)
+    nar_rows, nar_cols = [5, M - 1], [0, N - 2]
+    for i, r in enumerate(nar_rows):
+        k = [K - 1, 17][i]
+        if ta: A[k, r] = 0x80
+        else: A[r, k] = 0x80
+    for i, c in enumerate(nar_cols):
+        k = [3, K - 2][i]
+        if tb: B[c, k] = 0x80
+        else: B[k, c] = 0x80
+    ws = torch.full((pn.posit_gemm_workspace("p8", fout, ta, tb, M, N, K) + 64,), 0xFF, dtype=torch.uint8, device="cuda")
+    got = to_np(pn.posit_gemm(to_dev(A), to_dev(B), "p8", fout, trans_a=ta, trans_b=tb, bias=to_dev(bias), workspace=ws), fout)
+    onar = 1 << (BITS[fout] - 1)
+    for r in nar_rows:
+        assert (got[r] == onar).all()
+    for c in nar_cols:
+        assert (got[:, c] == onar).all()
+    assert (got == onar).sum() == 2 * N + 2 * M - 4
+    rows = sorted(set([0, 4, 6, 127, 128, M - 2] + [int(r) for r in rng.integers(0, M, size=4)]) - set(nar_rows))
+    for r in rows:
+        want, _ = fast.gemm(A, B, "p8", fout, trans_a=ta, trans_b=tb, bias=bias, rows=(r, r + 1))
+        _assert_equal(got[r], want[r], "packed path row %d" % r)
+
+
 def test_gemm_is_deterministic():
     rng = np.random.default_rng(77)
     A = to_dev(rand_patterns(rng, (300, 500), "p16"))
