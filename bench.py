@@ -15,7 +15,8 @@ the path on that batch:
         posit<8,0> copy of the new W                  (posit_axpy)
 
 `value` is M*N*K multiply-accumulates divided by the time of the whole step.
-`roofline` is for the GEMM kernel alone, timed with HIP events on the launch
+`roofline` is for the posit_gemm call alone (the GEMM kernel and, at this size, the
+pass that packs its operands first), timed with HIP events on the launch
 stream: achieved MAC/s against the integer-VALU peak of the chip for the fastest
 exact primitive (one packed 16-bit dot-product lane-op = 2 MACs):
 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 = 78.6 TMAC/s.
@@ -32,9 +33,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s
-# HBM-side bytes per launch of the GEMM kernel at 4096^3, from two rocprofv3 --pmc passes
-# (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE 92322 KiB x 2.0 (copy-kernel scale) + WRITE_SIZE 16384 KiB.
-GEMM_4096_TRAFFIC_BYTES = int((2.0 * 92322 + 16384) * 1024)
+# HBM-side bytes per posit_gemm call at 4096^3 (operand packing pass + GEMM kernel), from two rocprofv3 --pmc
+# passes (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in KiB:
+# GEMM kernel 192048 / 16384, packing pass 16421 / 65536.
+GEMM_4096_TRAFFIC_BYTES = int((2.0 * (192048 + 16421) + 16384 + 65536) * 1024)
 
 
 def _time_ms(torch, fn, reps, warm=2):
@@ -175,7 +177,7 @@ def main():
                    "fin": "posit<8,0>", "fout": "posit<8,0>", "quire_bits": 32},
         "roofline": {
             "bound": "alu",
-            "kernel": "p8_gemm_kernel",
+            "kernel": "p8_gemm_kernel (with its operand packing pass: the posit_gemm call)",
             "achieved": round(achieved, 3),
             "peak": round(PEAK_TMACS, 1),
             "unit": "TMAC/s",
