@@ -79,8 +79,11 @@ typedef enum {
  * format `fin`, which also fixes the quire; C is in `fout`.  The sum is exact,
  * the bias enters the quire as bias*1, and one rounding (nearest, ties to the
  * even pattern, never to zero or NaR) produces C.  K == 0 gives the rounded
- * bias (or zero).  `workspace` (device, 16-byte aligned) must hold at least
- * posit_gemm_workspace(...) bytes; it may be NULL when that query returns 0. */
+ * bias (or zero).  `workspace` (device, 16-byte aligned, else PNN_EINVAL) must hold
+ * at least posit_gemm_workspace(...) bytes (else PNN_EWORKSPACE); it may be NULL
+ * when that query returns 0.  Its contents on entry do not matter and are not
+ * preserved (partial quires of a split reduction; for posit<8,0> products of
+ * more than 2^34 multiply-adds also both operands, decoded and packed). */
 int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
                int64_t M, int64_t N, int64_t K,
                const void* A, int64_t lda, const void* B, int64_t ldb,

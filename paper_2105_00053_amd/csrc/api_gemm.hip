@@ -57,7 +57,6 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
         return hip_status(launch_p8_small_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                fout, M, N, K));
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N) && p8_packed_gemm_fits(M, N, K)) {
-        if (((uintptr_t)ws & 15u) != 0) return PNN_EINVAL;  // the packed operands are read in 16-byte runs
         return hip_status(launch_p8_gemm_packed(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                 fout, M, N, K, ws, plan));
     }
@@ -128,6 +127,7 @@ extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int trans
         if (!A || !B) return PNN_EINVAL;
         if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return PNN_EINVAL;
     }
+    if (workspace && ((uintptr_t)workspace & 15u) != 0) return PNN_EINVAL;
     if (M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
     PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes))

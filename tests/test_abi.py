@@ -95,4 +95,8 @@ def test_argument_validation_without_launch():
     need = L.posit_gemm_workspace(0, 1, 0, 0, 32, 288, 131072)
     assert need > 0
     assert L.posit_gemm(null, 0, 1, 0, 0, 32, 288, 131072, fake, 131072, fake, 288, null, fake, 288, null, 0) == 3
-    assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 0
+    assert L.posit_gemm(null, 0, 1, 0, 0, 32, 288, 131072, fake, 131072, fake, 288, null, fake, 288, ctypes.c_void_p(0x1008), need) == EINVAL  # alignment
+    # posit<8,0> 4096^3: no split, but both operands are packed into the workspace (2 bytes per element) with their flags
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 2 * 2 * 4096 * 4096 + 2 * 4096 * 4
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 2048, 2048, 2048) == 4 * (2048 * 2048 + 2 * 2048) * 4  # four-way split, nothing packed
+    assert L.posit_gemm(null, 0, 0, 0, 0, 4096, 4096, 4096, fake, 4096, fake, 4096, null, fake, 4096, null, 0) == 3
