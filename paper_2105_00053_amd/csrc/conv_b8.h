@@ -61,7 +61,7 @@ struct B8Stage {
 // `bias` (nullable) is indexed by output column n.  With gridDim.z > 1 the partial quires of this
 // slice of the reduction go to the workspace (L limbs per output) and a merge kernel finishes.
 template <class F, int TM, int TN>
-__global__ __launch_bounds__(256, (TM * TN <= 8 ? 3 : 2)) void b8_conv_kernel(P8Gather A, P8Gather B, P8ConvOut out, const uint8_t* __restrict__ bias,
+__global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8ConvOut out, const uint8_t* __restrict__ bias,
                                                       void* __restrict__ C, int fout, int M, int N, int K, int k_per_split,
                                                       int tiles_n, SplitWs ws, int ws_transposed) {
     typedef BucketAccum<F> AR;
