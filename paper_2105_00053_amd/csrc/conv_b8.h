@@ -6,9 +6,9 @@
 // Operands are fetched with the byte-gather descriptors of the posit<8,0> kernel (affine row /
 // reduction index maps, 8-byte runs read as aligned words where the layout allows), decoded
 // through an LDS table of 256 doubles into LDS tiles of doubles, and multiplied into the fp64
-// buckets of BucketArith<F>; after every 32-wide slice of the reduction (2^G = 32 products per
-// output for both formats) the buckets are emptied into the integer quire limbs, which the
-// epilogue rounds once.  256 threads as 16 x 16, TM x TN outputs per thread: workgroup tiles of
+// doubles of CascadeArith<F>: the exact sum of an output stays in two or three doubles for the whole
+// reduction (carries between them every 16 and 32 products) and becomes the integer quire limbs
+// once, in the epilogue, which rounds them once.  256 threads as 16 x 16, TM x TN outputs per thread: workgroup tiles of
 // 64 x 64, 64 x 32, 32 x 32 or 16 x 16, chosen per problem (small layers need many small tiles
 // to occupy the chip, a 32-channel layer wastes half of a 64-wide tile; a 128 x 32 tile would need
 // 80 KB of LDS and leave each CU a single workgroup).
@@ -65,8 +65,9 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
                                                       void* __restrict__ C, int fout, int M, int N, int K, int k_per_split,
                                                       int tiles_n, SplitWs ws, int ws_transposed) {
     typedef BucketAccum<F> AR;
-    static_assert(F::N == 8 && AR::BUCKETS > 0 && (1 << AR::G) >= P8_KT, "8-bit bucketed format, one flush per slice");
-    constexpr int BM = 16 * TM, BN = 16 * TN, L = AR::L, NB = AR::NB;
+    typedef CascadeArith<F> CA;
+    static_assert(F::N == 8 && CA::ELIGIBLE && P8_KT == CA::TOP_EVERY && P8_KT == 2 * CA::LOW_EVERY, "carry schedule of a 32-wide slice");
+    constexpr int BM = 16 * TM, BN = 16 * TN, L = AR::L, NL = CA::NL;
     static_assert(BM % 8 == 0 && BN % 8 == 0 && BM + BN <= 256, "tile shape");
     typedef P8GatherStage<BM> GA;
     typedef P8GatherStage<BN> GB;
@@ -101,16 +102,11 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
         colNaR[r] = 0;
     }
 
-    uint32_t acc[TM][TN][L];
-    double bk[TM][TN][NB];
+    double sum[TM][TN][NL];  // the exact sum of each output, spread over NL doubles
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-#pragma unroll
-            for (int l = 0; l < L; ++l) acc[i][j][l] = 0;
-            AR::clear(bk[i][j]);
-        }
+        for (int j = 0; j < TN; ++j) CA::clear(sum[i][j]);
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
     // B's work items go to the threads A's leave idle when both fit the workgroup
@@ -147,39 +143,48 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
             if (t < P8_KT) p8_fill_kinfo(A, kinfoA[cur], k2, kend, t);
             else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[cur], k2, kend, t - P8_KT);
         }
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
 #pragma unroll 4
-        for (int kk = 0; kk < P8_KT; ++kk) {
-            double a[TM], b[TN];
-            if constexpr (TM % 2 == 0) {
+            for (int kq = 0; kq < CA::LOW_EVERY; ++kq) {
+                const int kk = half * CA::LOW_EVERY + kq;
+                double a[TM], b[TN];
+                if constexpr (TM % 2 == 0) {
 #pragma unroll
-                for (int q = 0; q < TM; q += 2) {
-                    const double2 v = *reinterpret_cast<const double2*>(&As[cur][kk][ty * TM + q]);
-                    a[q] = v.x; a[q + 1] = v.y;
+                    for (int q = 0; q < TM; q += 2) {
+                        const double2 v = *reinterpret_cast<const double2*>(&As[cur][kk][ty * TM + q]);
+                        a[q] = v.x; a[q + 1] = v.y;
+                    }
+                } else {
+#pragma unroll
+                    for (int q = 0; q < TM; ++q) a[q] = As[cur][kk][ty * TM + q];
                 }
-            } else {
+                if constexpr (TN % 2 == 0) {
 #pragma unroll
-                for (int q = 0; q < TM; ++q) a[q] = As[cur][kk][ty * TM + q];
-            }
-            if constexpr (TN % 2 == 0) {
+                    for (int q = 0; q < TN; q += 2) {
+                        const double2 v = *reinterpret_cast<const double2*>(&Bs[cur][kk][tx * TN + q]);
+                        b[q] = v.x; b[q + 1] = v.y;
+                    }
+                } else {
 #pragma unroll
-                for (int q = 0; q < TN; q += 2) {
-                    const double2 v = *reinterpret_cast<const double2*>(&Bs[cur][kk][tx * TN + q]);
-                    b[q] = v.x; b[q + 1] = v.y;
+                    for (int q = 0; q < TN; ++q) b[q] = Bs[cur][kk][tx * TN + q];
                 }
-            } else {
 #pragma unroll
-                for (int q = 0; q < TN; ++q) b[q] = Bs[cur][kk][tx * TN + q];
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) CA::mac(sum[i][j], a[i], b[j]);
             }
+            // 16 products per output since the last carry out of the low levels
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) AR::mac(bk[i][j], a[i], b[j]);
+                for (int j = 0; j < TN; ++j) CA::carry_low(sum[i][j]);
         }
-        // 32 products per output since the last flush: the buckets' guard bits are used up
+        // 32 products since the top bucket last carried into level 0
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) AR::template flush<L>(acc[i][j], bk[i][j]);
+            for (int j = 0; j < TN; ++j) CA::carry_top(sum[i][j]);
         if (more) {
             B8Stage<BM>::stage(fa, As[cur ^ 1], tab, rowNaR, t, A.mode);
             B8Stage<BN>::stage(fb, Bs[cur ^ 1], tab, colNaR, tb, B.mode);
@@ -200,20 +205,24 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
             const int lc = tx * TN + j;
             const int n = n0 + lc;
             if (n >= N) continue;
+            uint32_t q[L];  // the sum as integer quire limbs, modulo 2^(32 L)
+#pragma unroll
+            for (int l = 0; l < L; ++l) q[l] = 0;
+            CA::template to_limbs<L>(q, sum[i][j]);
             if (gridDim.z == 1) {
                 bool nar = rnar || colNaR[lc] != 0;
                 if (bias) {
                     const uint32_t bp = bias[n];
                     if (bp == F::NAR) nar = true;
-                    else AR::add_bias(acc[i][j], bp);
+                    else AR::add_bias(q, bp);
                 }
-                round_store<AR, L>(acc[i][j], nar, fout, C, rp + (int64_t)n * out.nstride);
+                round_store<AR, L>(q, nar, fout, C, rp + (int64_t)n * out.nstride);
             } else {
                 // partial quire; the merge kernel sees an (Mw x Nw) row-major problem
                 const int64_t z = blockIdx.z;
                 const int64_t idx = ws_transposed ? ((int64_t)n * M + m) : ((int64_t)m * N + n);
 #pragma unroll
-                for (int l = 0; l < L; ++l) ws.limbs[(z * (int64_t)M * N + idx) * L + l] = acc[i][j][l];
+                for (int l = 0; l < L; ++l) ws.limbs[(z * (int64_t)M * N + idx) * L + l] = q[l];
             }
         }
     }

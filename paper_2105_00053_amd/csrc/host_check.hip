@@ -110,6 +110,42 @@ uint32_t dot_bucket_host(int fout, int64_t n, const uint32_t* a, const uint32_t*
         return AR::read(q, r) ? encode_rt(r, fo) : 0u;
     }
 }
+// the same dot product with the whole sum kept in doubles (CascadeArith), carries on the kernel's schedule:
+// after every LOW_EVERY products out of the low levels, after every TOP_EVERY out of the top bucket; limbs at the end
+template <class F>
+uint32_t dot_cascade_host(int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    typedef CascadeArith<F> CA;
+    typedef BucketAccum<F> AR;
+    if constexpr (!CA::ELIGIBLE) {
+        return 0xFFFFFFFFu;
+    } else {
+        double c[CA::NL];
+        CA::clear(c);
+        bool nar = false;
+        for (int64_t k0 = 0; k0 < n; k0 += CA::TOP_EVERY) {
+            for (int half = 0; half < CA::TOP_EVERY / CA::LOW_EVERY; ++half) {
+                for (int64_t i = k0 + half * CA::LOW_EVERY; i < n && i < k0 + (half + 1) * CA::LOW_EVERY; ++i) {
+                    if (a[i] == F::NAR || b[i] == F::NAR) nar = true;
+                    CA::mac(c, AR::stage(a[i]), AR::stage(b[i]));
+                }
+                CA::carry_low(c);
+            }
+            CA::carry_top(c);
+        }
+        uint32_t q[AR::L];
+        for (int l = 0; l < AR::L; ++l) q[l] = 0;
+        CA::template to_limbs<AR::L>(q, c);
+        if (has_bias) {
+            if (bias == F::NAR) nar = true;
+            else AR::add_bias(q, bias);
+        }
+        const FmtRT fo = fmt_of_code(fout);
+        Real r;
+        if (nar) return fo.nar();
+        return AR::read(q, r) ? encode_rt(r, fo) : 0u;
+    }
+}
+
 // the limbs after adding m * 2^T(j) (bucket j = 1..B of the format, |m| <= 2^53) to zeroed limbs; returns the limb count
 template <class F, int J>
 int flush_one(int j, double m, uint32_t* out) {
@@ -129,6 +165,14 @@ int flush_one(int j, double m, uint32_t* out) {
 }  // namespace
 
 extern "C" {
+
+uint32_t hostcheck_dot_cascade(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
+    switch (fin) {
+        case 3: return dot_cascade_host<P8_1>(fout, n, a, b, has_bias, bias);
+        case 4: return dot_cascade_host<P8_2>(fout, n, a, b, has_bias, bias);
+        default: return 0xFFFFFFFFu;
+    }
+}
 
 uint32_t hostcheck_dot_bucket(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
     switch (fin) {

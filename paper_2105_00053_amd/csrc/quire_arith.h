@@ -330,4 +330,72 @@ struct BucketArith {
     }
 };
 
+// ---- the whole sum in doubles (posit(8,1), posit(8,2)) ----
+//
+// BucketArith empties its buckets into integer limbs before their guard bits run out.  For the two
+// 8-bit formats the kernel can instead carry between doubles and form the limbs once at the end:
+// one more double on top (level 0, multiples of 2^TOPG) and, from the bottom up, "carry" steps
+//     c = (x_j + 1.5 * 2^(52+g)) - 1.5 * 2^(52+g)   (x_j rounded to a multiple of g = the grain of level j-1)
+//     x_j -= c;  x_(j-1) += c                          (both exact: |x_j - c| <= g/2, and see the bounds)
+// Schedule and bounds, with R = 4 MAXS the bit length of the largest product:
+//   every LOW_EVERY = 16 products all levels below the top bucket carry upwards; the lowest level then holds
+//       at most half a grain of the level above plus 16 products' worth: 2^(T-1) + 16 * 2^(T-1) < 2^53 for the
+//       split remainders of posit(8,2) (T = T_1 = 49), 2^(TOPG-1) + 16 * 2^R < 2^53 for posit(8,1) (one bucket)
+//   every TOP_EVERY = 32 products the top bucket carries into level 0; before that it holds at most
+//       2^(TOPG-1) + 32 * 2^R + two carries from below <= 2^(53+T_1)
+//   level 0 holds the whole sum above 2^TOPG: K * 2^R / 2^TOPG <= 2^53 for K < 2^31.
+// Each level is a multiple of its grain of at most 2^53 grains, so quire_add_double converts it exactly.
+template <class F>
+struct CascadeArith : BucketArith<F> {
+    typedef BucketArith<F> BA;
+    static constexpr int NB = BA::NB;
+    static constexpr int NL = NB + 1;  // level 0 on top, levels 1..NB are the buckets of BucketArith (NB the lowest)
+    static constexpr int LOW_EVERY = 16, TOP_EVERY = 32;
+    static constexpr int TOPG = NB == 1 ? 40 : BA::T(1) + 51;
+    static constexpr int grain(int level) { return level == 0 ? TOPG : BA::T(level); }
+    static constexpr bool ELIGIBLE = BA::B > 0 && F::N == 8 && NB <= 2;
+    static_assert(!ELIGIBLE || BA::R + 31 - TOPG <= 53, "level 0 holds the sum of 2^31 products");
+    static_assert(!ELIGIBLE || NB != 1 || (TOPG - 1 <= 52 && BA::R + 4 <= 52), "one bucket: half a top grain + 16 products < 2^53");
+    static_assert(!ELIGIBLE || NB != 2 || (BA::T(1) + 4 <= 53 && TOPG - 1 <= 51 + BA::T(1) && BA::R + 5 <= 52 + BA::T(1)),
+                  "two buckets: 17 half grains in the low one; half a top grain + 32 products + carries in the high one");
+
+    PNN_HD static void clear(double (&c)[NL]) {
+#pragma unroll
+        for (int j = 0; j < NL; ++j) c[j] = 0.0;
+    }
+    PNN_HD static void mac(double (&c)[NL], double a, double b) {
+        if constexpr (NB == 1) {
+            c[1] = __builtin_fma(a, b, c[1]);
+        } else {
+            constexpr double C1 = 1.5 * pow2d(52 + BA::T(1));
+            const double h1 = __builtin_fma(a, b, C1) - C1;
+            c[1] += h1;
+            c[2] += __builtin_fma(a, b, -h1);
+        }
+    }
+    // carry level J into level J - 1
+    template <int J>
+    PNN_HD static void carry(double (&c)[NL]) {
+        constexpr double C = 1.5 * pow2d(52 + grain(J - 1));
+        const double up = (c[J] + C) - C;
+        c[J] -= up;
+        c[J - 1] += up;
+    }
+    // after every LOW_EVERY products: everything below the top bucket moves up (one bucket: straight into level 0)
+    PNN_HD static void carry_low(double (&c)[NL]) {
+        if constexpr (NB == 1) carry<1>(c);
+        else carry<2>(c);
+    }
+    // after every TOP_EVERY products (two buckets only): the top bucket moves into level 0
+    PNN_HD static void carry_top(double (&c)[NL]) {
+        if constexpr (NB == 2) carry<1>(c);
+    }
+    template <int L>
+    PNN_HD static void to_limbs(uint32_t (&q)[L], const double (&c)[NL]) {
+        quire_add_double<L, grain(0)>(q, c[0]);
+        quire_add_double<L, grain(1)>(q, c[1]);
+        if constexpr (NB == 2) quire_add_double<L, grain(2)>(q, c[2]);
+    }
+};
+
 }  // namespace pnn

@@ -34,6 +34,8 @@ def hc():
     L.hostcheck_dot_noquire.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_dot_bucket.restype = ctypes.c_uint32
     L.hostcheck_dot_bucket.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
+    L.hostcheck_dot_cascade.restype = ctypes.c_uint32
+    L.hostcheck_dot_cascade.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_bucket_config.argtypes = [ci, vp, vp, vp]
     L.hostcheck_bucket_flush.argtypes = [ci, ci, ctypes.c_double, vp]
     L.hostcheck_posit_op.restype = ctypes.c_uint32
@@ -369,6 +371,44 @@ def test_bucket_guard_bits_are_needed_and_enough(hc, fmt):
         assert got == int(want[0, 0]), (fmt, K)
         checked += 1
     assert checked >= 3 * B
+
+
+@pytest.mark.parametrize("fmt", ["p8_1", "p8_2"])
+def test_cascade_dot_random_and_at_the_bounds(hc, fmt):
+    """The 8-bit kernels keep the whole sum in doubles (carries between them every 16 and 32 products) and form the
+    integer quire once: random vectors, the guard-filling vectors of the buckets, and long runs of maxpos^2 of one
+    sign (the top level grows to K * maxpos^2) with minpos^2 terms and sign flips in between."""
+    import bucket_cases
+    n = BITS[fmt]
+    full = (1 << n) - 1
+    maxpos, minpos = (1 << (n - 1)) - 1, 1
+    neg = lambda p: (-p) & full
+    rng = np.random.default_rng(CODE[fmt] + 100)
+    cases = []
+    for trial in range(150):
+        K = int(rng.integers(0, 100)) if trial % 5 else int(rng.integers(100, 4000))
+        a = _patterns(rng, K, fmt, [0.0, 0.05, 0.5][trial % 3]).astype(np.uint32)
+        b = _patterns(rng, K, fmt, [0.0, 0.05, 0.5][trial % 3]).astype(np.uint32)
+        if trial % 4:
+            a[a == 1 << (n - 1)] = 1
+            b[b == 1 << (n - 1)] = 1
+        cases.append((a, b))
+    for a, b, _ in bucket_cases.guard_cases(fmt, mults=(1, 2, 4, 8), leads=(0, 5, 11, 16, 27)):
+        cases.append((a, b))
+    for K in (15, 16, 17, 31, 32, 33, 1000, 40000, 70000):
+        cases.append((np.full(K, maxpos), np.full(K, maxpos)))
+        cases.append((np.full(K, maxpos), np.full(K, neg(maxpos))))
+        a = np.full(K, maxpos); b = np.full(K, maxpos); a[1::2] = minpos; b[1::2] = neg(minpos)
+        cases.append((a, b))
+        a = np.full(K, maxpos); b = np.full(K, maxpos); b[K // 2:] = neg(maxpos); a[-1] = minpos; b[-1] = minpos
+        cases.append((a, b))
+    for a, b in cases:
+        a = np.asarray(a).astype(np.uint32); b = np.asarray(b).astype(np.uint32)
+        K = len(a)
+        for fout in (fmt, "p32"):
+            got = hc.hostcheck_dot_cascade(CODE[fmt], CODE[fout], K, _p(a), _p(b), 1, 3)
+            want, _ = fast.gemm(a.reshape(1, K), b.reshape(K, 1), fmt, fout, bias=np.array([3]), threads=1)
+            assert got == int(want[0, 0]), (fmt, K, fout)
 
 
 def test_bucket_dot_wraps_like_the_quire(hc):
