@@ -420,6 +420,30 @@ def test_conv_random_geometries_posit8(gi):
     _assert_equal(to_np(db, fout), wdb, "dbias %s" % d)
 
 
+@pytest.mark.parametrize("gi", range(24))
+def test_conv_random_geometries_posit8_es(gi):
+    """The same seeded random shapes through the byte-gather kernel of posit(8,1) / posit(8,2) (every tile
+    variant, every gather mode, strided backward-data falling back to the generic kernel)."""
+    d = _random_geometries(40, 2105)[gi + 8]
+    rng = np.random.default_rng(3000 + gi)
+    oh, ow = fast.out_hw(d)
+    fin = "p8_2" if gi % 2 else "p8_1"
+    fout = [fin, "p12_2", "p16"][gi % 3]
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), fin, special=0.01)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), fin, special=0.01, allow_nar=gi % 3 == 0)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), fin, special=0.01)
+    bias = rand_patterns(rng, (d["K"],), fin, allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, fin, fout, bias=to_dev(bias))
+    _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, fin, fout, bias=bias), "fwd %s" % d)
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, fin, fout)
+    _assert_equal(to_np(dx, fout), fast.conv2d_bwd_data(dy, w, d, fin, fout), "bwd_data %s" % d)
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dy), to_dev(x), desc, fin, fout, with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True)
+    _assert_equal(to_np(dw, fout), wdw, "bwd_weight %s" % d)
+    _assert_equal(to_np(db, fout), wdb, "dbias %s" % d)
+
+
 @pytest.mark.parametrize("fin,fout", [("p8", "p16"), ("p16", "p16"), ("p8_2", "p12_2"), ("p32", "p32")])
 def test_bias_gradient_over_batch_slices(fin, fout):
     """Enough images that the bias-gradient reduction is cut into slices of the batch and merged;
