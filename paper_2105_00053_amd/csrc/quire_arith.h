@@ -28,21 +28,29 @@ PNN_HD void quire_add32(uint32_t (&q)[L], int32_t P, int s) {
     }
 }
 
-// Same for a product of up to 63 bits plus sign (posit<32,2>: 28 x 28 bits).
+// Same for a product of up to 63 bits plus sign (posit<32,2>: 28 x 28 bits).  The three words of the
+// shifted product (sign extension above them) are moved to limb idx by a barrel shift over whole
+// limbs: log2(L) rounds of "take the limb `step` below if that bit of idx is set", of which only
+// the limbs that can differ from the sign extension cost a select (4 + 6 + 10 + 16 for L = 16,
+// against four compares and four selects per limb when every limb tests idx by itself).
 template <int L>
 PNN_HD void quire_add64(uint32_t (&q)[L], int64_t P, int s) {
     const int idx = s >> 5, off = s & 31;
     const uint64_t lo = (uint64_t)P << off;
-    const uint32_t x0 = (uint32_t)lo;
-    const uint32_t x1 = (uint32_t)(lo >> 32);
     const uint32_t x2 = (uint32_t)((P >> 32) >> (32 - off));  // bits 64..95 of the sign-extended shift
     const uint32_t ext = (uint32_t)((int32_t)x2 >> 31);
+    uint32_t v[L];
+#pragma unroll
+    for (int l = 0; l < L; ++l) v[l] = l == 0 ? (uint32_t)lo : l == 1 ? (uint32_t)(lo >> 32) : l == 2 ? x2 : ext;
+#pragma unroll
+    for (int step = 1; step < L; step <<= 1) {
+        const bool on = (idx & step) != 0;
+#pragma unroll
+        for (int l = L - 1; l >= 0; --l) v[l] = on ? (l >= step ? v[l - step] : 0u) : v[l];
+    }
     unsigned carry = 0;
 #pragma unroll
-    for (int l = 0; l < L; ++l) {
-        const uint32_t add = (l < idx) ? 0u : (l == idx) ? x0 : (l == idx + 1) ? x1 : (l == idx + 2) ? x2 : ext;
-        q[l] = __builtin_addc(q[l], add, carry, &carry);
-    }
+    for (int l = 0; l < L; ++l) q[l] = __builtin_addc(q[l], v[l], carry, &carry);
 }
 
 // Sum of two L-limb accumulators (split-K merge): plain multi-word addition,
