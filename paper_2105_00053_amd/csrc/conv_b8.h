@@ -5,19 +5,18 @@
 //
 // Operands are fetched with the byte-gather descriptors of the posit<8,0> kernel (affine row /
 // reduction index maps, 8-byte runs read as aligned words where the layout allows), decoded
-// through an LDS table of 256 doubles into LDS tiles of doubles, and multiplied into the fp64
-// doubles of CascadeArith<F>: the exact sum of an output stays in two or three doubles for the whole
-// reduction (carries between them every 16 and 32 products) and becomes the integer quire limbs
-// once, in the epilogue, which rounds them once.  256 threads as 16 x 16, TM x TN outputs per thread: workgroup tiles of
-// 64 x 64, 64 x 32, 32 x 32 or 16 x 16, chosen per problem (small layers need many small tiles
-// to occupy the chip, a 32-channel layer wastes half of a 64-wide tile; a 128 x 32 tile would need
-// 80 KB of LDS and leave each CU a single workgroup).
+// through a 256-entry LDS table into LDS tiles of doubles, and multiplied into the doubles of
+// CascadeArith<F>: the exact sum of an output stays in two or three doubles for the whole
+// reduction (carries between them every 16 and 32 products) and becomes the integer quire
+// limbs once, in the epilogue, which rounds them once.  256 threads as 16 x 16, TM x TN outputs
+// per thread: workgroup tiles of 64 x 64, 64 x 32, 32 x 32 or 16 x 16, chosen per problem (small
+// layers need many small tiles to occupy the chip, a 32-channel layer wastes half of a 64-wide
+// tile; a 128 x 32 tile would need 80 KB of LDS and leave each CU a single workgroup).
 #pragma once
 
 #include "conv_p8.h"
 
 namespace pnn {
-
 
 template <int BR>
 struct B8Stage {
