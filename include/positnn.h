@@ -93,6 +93,23 @@ int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
 /* Bytes of device workspace posit_gemm wants for this problem (0 = none). */
 size_t posit_gemm_workspace(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K);
 
+/* posit_gemm for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc).  Same result, arguments and status
+ * codes as posit_gemm, but the workspace is a fixed array of PNN_GEMM_STATIC_SCRATCH_BYTES inside
+ * the library's code object (each GPU the library runs on holds one copy until the process ends),
+ * so the call neither takes a workspace nor allocates or frees anything.  A problem whose
+ * posit_gemm_workspace() exceeds PNN_GEMM_STATIC_SCRATCH_BYTES returns PNN_EWORKSPACE with nothing
+ * launched (72 MiB covers the 4096^3 posit<8,0> product and every matrix product of the five
+ * benchmark configurations).  The device that owns the pointers and the stream must be the
+ * current device.  Every call on a GPU uses that GPU's one array, which keeps the previous call's
+ * contents (the kernels overwrite or clear what they read): calls that may overlap in time on one
+ * GPU -- from different streams or threads -- race on it and must be serialised by the caller. */
+#define PNN_GEMM_STATIC_SCRATCH_BYTES ((size_t)72 << 20)
+int posit_gemm_static(void* stream, int fin, int fout, int transA, int transB,
+                      int64_t M, int64_t N, int64_t K,
+                      const void* A, int64_t lda, const void* B, int64_t ldb,
+                      const void* bias, void* C, int64_t ldc);
+
 /* 2-D convolution geometry (Sec. 3.1: layers follow LibTorch semantics):
  * cross-correlation, activations NCHW, weights [K][C][R][S], zero padding,
  * dilation 1, one group.  Output size OH = (H + 2*pad_h - R) / stride_h + 1. */

@@ -51,6 +51,8 @@ def load():
     vp, i64, ci, sz, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t, ctypes.c_uint32
     L.posit_gemm.argtypes = [vp, ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64, vp, sz]
     L.posit_gemm.restype = ci
+    L.posit_gemm_static.argtypes = [vp, ci, ci, ci, ci, i64, i64, i64, vp, i64, vp, i64, vp, vp, i64]
+    L.posit_gemm_static.restype = ci
     L.posit_gemm_workspace.argtypes = [ci, ci, ci, ci, i64, i64, i64]
     L.posit_gemm_workspace.restype = sz
     dp = ctypes.POINTER(ConvDesc)
@@ -145,6 +147,26 @@ def posit_gemm(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, out=Non
     _check(load().posit_gemm(_stream(), fin, fout, int(trans_a), int(trans_b), M, N, K,
                              _dev(A, fin, "A"), A.shape[1], _dev(B, fin, "B"), B.shape[1], _dev(bias, fin, "bias"),
                              _dev(out, fout, "out"), out.shape[1], wp, wbytes))
+    return out
+
+
+def posit_gemm_static(A, B, fin, fout, trans_a=False, trans_b=False, bias=None, out=None):
+    """posit_gemm with the library's own fixed scratch array as workspace: the call allocates nothing
+    when `out` is given.  Calls that overlap in time on one GPU race on that array."""
+    fin, fout = _code(fin), _code(fout)
+    if A.dim() != 2 or B.dim() != 2:
+        raise PositError("A and B must be 2-D")
+    M, K = (A.shape[1], A.shape[0]) if trans_a else (A.shape[0], A.shape[1])
+    N, Kb = (B.shape[0], B.shape[1]) if trans_b else (B.shape[1], B.shape[0])
+    if K != Kb:
+        raise PositError("inner dimensions differ: %d vs %d" % (K, Kb))
+    if bias is not None and bias.numel() != N:
+        raise PositError("bias must have N elements")
+    if out is None:
+        out = torch.empty((M, N), dtype=TORCH_DTYPE[fout], device=A.device)
+    _check(load().posit_gemm_static(_stream(), fin, fout, int(trans_a), int(trans_b), M, N, K,
+                                    _dev(A, fin, "A"), A.shape[1], _dev(B, fin, "B"), B.shape[1], _dev(bias, fin, "bias"),
+                                    _dev(out, fout, "out"), out.shape[1]))
     return out
 
 

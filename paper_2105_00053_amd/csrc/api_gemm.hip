@@ -1,6 +1,8 @@
 // posit_gemm: quire-exact matrix product (paper Sec. 3.3; the Linear layer's
 // forward, backward-data and backward-weight passes of Sec. 3.1 are its
 // transposition cases).
+#include <mutex>
+
 #include "api_common.h"
 #include "conv_p8.h"
 #include "conv_b8.h"
@@ -117,9 +119,10 @@ extern "C" size_t posit_gemm_workspace(int fin, int fout, int transA, int transB
     return 0;
 }
 
-extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
-                          const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias, void* C, int64_t ldc,
-                          void* workspace, size_t workspace_bytes) {
+// Argument checks shared by the entry points below.  *launch is set when there is work to do.
+static int gemm_check_args(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                           const void* B, int64_t ldb, const void* C, int64_t ldc, bool* launch) {
+    *launch = false;
     if (!is_posit(fin) || !is_posit(fout) || M < 0 || N < 0 || K < 0) return PNN_EINVAL;
     if (M == 0 || N == 0) return PNN_OK;
     if (!C || ldc < N) return PNN_EINVAL;
@@ -127,9 +130,67 @@ extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int trans
         if (!A || !B) return PNN_EINVAL;
         if (lda < (transA ? M : K) || ldb < (transB ? K : N)) return PNN_EINVAL;
     }
-    if (workspace && ((uintptr_t)workspace & 15u) != 0) return PNN_EINVAL;
     if (M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
+    *launch = true;
+    return PNN_OK;
+}
+
+extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                          const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias, void* C, int64_t ldc,
+                          void* workspace, size_t workspace_bytes) {
+    bool launch;
+    const int rc = gemm_check_args(fin, fout, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, &launch);
+    if (!launch) return rc;
+    if (workspace && ((uintptr_t)workspace & 15u) != 0) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes))
+    return PNN_EINVAL;
+}
+
+// ---- posit_gemm for callers that cannot allocate device memory ----
+//
+// The workspace of posit_gemm (partial quires of a split reduction, packed operands) lives in a
+// fixed array inside the library's code object instead of a caller's buffer.  Each GPU the library
+// runs on holds its own copy of the array at its own address; in host code the array's name is
+// only a handle for hipGetSymbolAddress, never a device address, so the address is looked up once
+// per device (first call with that device current) and that pointer is what the kernels receive.
+
+static __device__ __align__(256) unsigned char scratch[PNN_GEMM_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];  // per device: device address of `scratch`, null until looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch`.
+int scratch_address(void** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return PNN_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PNN_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return PNN_OK;
+}
+}  // namespace
+
+extern "C" int posit_gemm_static(void* stream, int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K,
+                                 const void* A, int64_t lda, const void* B, int64_t ldb, const void* bias, void* C, int64_t ldc) {
+    bool launch;
+    const int rc = gemm_check_args(fin, fout, transA, transB, M, N, K, A, lda, B, ldb, C, ldc, &launch);
+    if (!launch) return rc;
+    const size_t need = posit_gemm_workspace(fin, fout, transA, transB, M, N, K);
+    if (need > PNN_GEMM_STATIC_SCRATCH_BYTES) return PNN_EWORKSPACE;  // beyond the fixed array: posit_gemm with a caller's workspace
+    void* ws = nullptr;
+    if (need > 0) {
+        const int rs = scratch_address(&ws);
+        if (rs != PNN_OK) return rs;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    const size_t ws_bytes = need > 0 ? (size_t)PNN_GEMM_STATIC_SCRATCH_BYTES : 0;
+    PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, ws, ws_bytes))
     return PNN_EINVAL;
 }

@@ -27,7 +27,7 @@ def lib():
 
 def test_header_declares_the_expected_entry_points():
     assert _declared() == sorted([
-        "posit_gemm", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
+        "posit_gemm", "posit_gemm_static", "posit_gemm_workspace", "posit_conv2d_fwd", "posit_conv2d_bwd_data", "posit_conv2d_bwd_weight",
         "posit_conv2d_workspace", "posit_round", "posit_convert", "posit_axpy", "posit_status_string",
         "posit_relu", "posit_relu_bwd", "posit_maxpool2d_fwd", "posit_maxpool2d_bwd", "posit_avgpool2d_fwd", "posit_avgpool2d_bwd",
         "posit_gemm_noquire", "posit_conv2d_fwd_noquire", "posit_conv2d_bwd_data_noquire", "posit_conv2d_bwd_weight_noquire",
@@ -100,3 +100,9 @@ def test_argument_validation_without_launch():
     assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 2 * 2 * 4096 * 4096 + 2 * 4096 * 4
     assert L.posit_gemm_workspace(0, 0, 0, 0, 2048, 2048, 2048) == 4 * (2048 * 2048 + 2 * 2048) * 4  # four-way split, nothing packed
     assert L.posit_gemm(null, 0, 0, 0, 0, 4096, 4096, 4096, fake, 4096, fake, 4096, null, fake, 4096, null, 0) == 3
+    # the variant with the library's own scratch array: same checks, and a problem beyond the array is refused before any launch
+    assert L.posit_gemm_static(null, 57, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4) == EINVAL
+    assert L.posit_gemm_static(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4) == EINVAL
+    assert L.posit_gemm_static(null, 0, 0, 0, 0, 0, 4, 4, null, 4, null, 4, null, null, 4) == 0
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 8192, 8192, 8192) > (72 << 20)
+    assert L.posit_gemm_static(null, 0, 0, 0, 0, 8192, 8192, 8192, fake, 8192, fake, 8192, null, fake, 8192) == 3
