@@ -50,9 +50,12 @@ What each function follows
 Readings of points the paper leaves open (all listed in the design notes):
 the quire is a Q-bit two's-complement integer whose unit is minpos^2 and which
 wraps modulo 2^Q; NaR is absorbing (NaR * 0 = NaR); a bias is added inside the
-quire; missing exponent bits read as zero; a convolution is the matrix product
-of its unfolded (im2col) form, so zero padding and taps without a partner are
-zero OPERANDS: a NaR weight makes its whole output channel NaR.
+quire; missing exponent bits read as zero; the forward convolution and its
+weight gradient are matrix products over the unfolded (im2col) input, whose
+padded entries are zero OPERANDS (a NaR weight makes its whole output channel
+NaR, a NaR gradient entry its whole filter); the input gradient is the sum of
+what the unfolded columns scatter back to each input position, so a filter tap
+that reaches no output position from there is no term of that position's sum.
 
 Parity pins: every function here is pinned by tests that do not reuse its own
 formula (exhaustive round trips, encodings fixed by the definition, Table 1's
@@ -422,8 +425,12 @@ def conv2d_fwd_quire(x, w, sh, fin, bias=None):
 
 
 def conv2d_bwd_data_quire(dy, w, sh, fin):
-    """Exact dx[n][c][h][w] = sum over (k,r,s) of dy[n][k][oh][ow]*w[k][c][r][s] with oh*sh+r-ph == h,
-    ow*sw+s-pw == w; a (k,r,s) without such an (oh,ow) multiplies the weight by a zero operand."""
+    """Exact dx[n][c][h][w] = sum of dy[n][k][oh][ow]*w[k][c][r][s] over the (k,r,s,oh,ow) with
+    oh*sh+r-ph == h and ow*sw+s-pw == w: the adjoint of the forward pass with respect to x.  It is
+    what LibTorch's data flow (Sec. 3.1) accumulates when it multiplies W^T by dY and scatters every
+    column entry back to the input position it was unfolded from: a (k,r,s) that reaches no output
+    position from (h,w) sends nothing there, so it is no term of that sum (and a NaR weight at
+    such a tap does not touch that position)."""
     dyu = _units_list(dy, fin)
     wu = _units_list(w, fin)
     out = []
@@ -441,9 +448,9 @@ def conv2d_bwd_data_quire(dy, w, sh, fin):
                             for s in range(sh.S):
                                 u = ww + sh.pad_w - s
                                 ow = u // sh.stride_w
-                                ok = row_ok and u >= 0 and u % sh.stride_w == 0 and ow < sh.OW
-                                # a tap with no output position behind it is a zero operand
-                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow] if ok else 0
+                                if not (row_ok and u >= 0 and u % sh.stride_w == 0 and ow < sh.OW):
+                                    continue  # no output position reads x[n][c][h][w] through this tap
+                                a = dyu[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow]
                                 b = wu[((k * sh.C + c) * sh.R + r) * sh.S + s]
                                 if a is NaR or b is NaR:
                                     nar = True
@@ -581,7 +588,8 @@ def conv2d_fwd_terms(x, w, sh):
 
 
 def conv2d_bwd_data_terms(dy, w, sh):
-    """For every dx[n,c,h,w]: operand sequences ordered by (k,r,s); a tap with no output position is 0."""
+    """For every dx[n,c,h,w]: operand sequences ordered by (k,r,s); only the taps that reach an output
+    position from (h,w) are terms."""
     out = []
     for n in range(sh.N):
         for c in range(sh.C):
@@ -595,7 +603,9 @@ def conv2d_bwd_data_terms(dy, w, sh):
                                 u = ww + sh.pad_w - s
                                 ok = (t >= 0 and t % sh.stride_h == 0 and t // sh.stride_h < sh.OH and
                                       u >= 0 and u % sh.stride_w == 0 and u // sh.stride_w < sh.OW)
-                                a.append(dy[((n * sh.K + k) * sh.OH + t // sh.stride_h) * sh.OW + u // sh.stride_w] if ok else 0)
+                                if not ok:
+                                    continue
+                                a.append(dy[((n * sh.K + k) * sh.OH + t // sh.stride_h) * sh.OW + u // sh.stride_w])
                                 b.append(w[((k * sh.C + c) * sh.R + r) * sh.S + s])
                     out.append((a, b))
     return out

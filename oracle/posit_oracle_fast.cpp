@@ -14,7 +14,8 @@
 // Fig. 2; worker threads split the rows of the left operand = Sec. 3.3.
 // Readings where the paper is silent are those of the Python oracle (modular
 // quire, NaR absorbing, bias inside the quire, truncated exponent bits are 0,
-// padding and partner-less convolution taps are zero operands; with the quire
+// padded positions are zero operands of the forward and weight-gradient passes,
+// filter taps that reach no output position are no terms of the input gradient; with the quire
 // switched off, Sec. 3.3 / Table 2, every product and running sum is rounded,
 // terms in order of the reduction index, bias last).
 //
@@ -402,8 +403,8 @@ int oracle_conv2d_bwd_data(int fin_c, int fout_c, const int64_t* d, const void* 
                             for (int64_t s = 0; s < c.S; ++s) {
                                 const int64_t u = ww + c.pw - s;
                                 const bool ok = row_ok && u >= 0 && u % c.sw == 0 && u / c.sw < c.OW;
-                                // a tap with no output position behind it is a zero operand
-                                acc.mac(ok ? dyd[(size_t)(((n * c.K + k) * c.OH + t / c.sh) * c.OW + u / c.sw)] : zero,
+                                if (!ok) continue;  // no output position reads x[n,c,h,w] through this tap: not a term of the sum
+                                acc.mac(dyd[(size_t)(((n * c.K + k) * c.OH + t / c.sh) * c.OW + u / c.sw)],
                                     wd[(size_t)(((k * c.C + ci) * c.R + r) * c.S + s)]);
                             }
                         }

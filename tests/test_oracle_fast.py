@@ -113,6 +113,14 @@ def test_conv_matches_python_oracle(fin, fout):
         assert y.flatten().tolist() == po.conv2d_fwd(x.flatten().tolist(), w.flatten().tolist(), sh, F[fin], F[fout], bias.tolist())
         dx = fast.conv2d_bwd_data(dy, w, d, fin, fout)
         assert dx.flatten().tolist() == po.conv2d_bwd_data(dy.flatten().tolist(), w.flatten().tolist(), sh, F[fin], F[fout])
+        # a NaR weight at a corner tap: NaR only at the input positions that tap reaches (both quire and no-quire chains)
+        wn = w.copy()
+        wn[0, 0, 0, 0] = F[fin].nar
+        dxn = fast.conv2d_bwd_data(dy, wn, d, fin, fout)
+        assert dxn.flatten().tolist() == po.conv2d_bwd_data(dy.flatten().tolist(), wn.flatten().tolist(), sh, F[fin], F[fout])
+        assert (dxn[:, 0] == F[fout].nar).any() and not (dxn[:, 0] == F[fout].nar).all()
+        dxq = fast.conv2d_bwd_data(dy, wn, d, fin, fout, noquire=True)
+        assert dxq.flatten().tolist() == po.conv2d_bwd_data_noquire(dy.flatten().tolist(), wn.flatten().tolist(), sh, F[fin], F[fout])
         dw, db = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True)
         assert dw.flatten().tolist() == po.conv2d_bwd_weight(dy.flatten().tolist(), x.flatten().tolist(), sh, F[fin], F[fout])
         assert db.tolist() == po.conv2d_bias_grad(dy.flatten().tolist(), sh, F[fin], F[fout])

@@ -263,8 +263,9 @@ def test_axpy():
 
 
 def test_conv_is_the_matrix_product_of_its_unfolded_form_including_nar():
-    """Zero padding materialised (pattern 0) and every pass written as a plain
-    gemm over the unfolded operand: same bits, NaR included (NaR * 0 = NaR)."""
+    """Forward and weight gradient: zero padding materialised (pattern 0) and the pass written as a plain
+    gemm over the unfolded input: same bits, NaR included (NaR * 0 = NaR).  Input gradient: the sum of
+    what the unfolded columns scatter back to each input position."""
     rng = random.Random(12)
     sh = po.ConvShape(2, 2, 4, 5, 3, 3, 2, 1, 1, 2, 1)
     fmt = po.P8
@@ -300,22 +301,38 @@ def test_conv_is_the_matrix_product_of_its_unfolded_form_including_nar():
     DW = po.gemm(dyT, cols, fmt, po.P16)
     dw = po.conv2d_bwd_weight(dy, x, sh, fmt, po.P16)
     assert dw == [DW[k][j] for k in range(sh.K) for j in range(sh.C * sh.R * sh.S)]
-    # backward-data: rows (n,h,w), columns c, reduction (k,r,s)
-
-    def dyat(n, k, h, ww, r, s):
-        t, u = h + sh.pad_h - r, ww + sh.pad_w - s
-        if t < 0 or u < 0 or t % sh.stride_h or u % sh.stride_w:
-            return 0
-        oh, ow = t // sh.stride_h, u // sh.stride_w
-        return dy[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow] if oh < sh.OH and ow < sh.OW else 0
-
-    rows = [[dyat(n, k, h, ww, r, s) for k in range(sh.K) for r in range(sh.R) for s in range(sh.S)]
-            for n in range(sh.N) for h in range(sh.H) for ww in range(sh.W)]
-    Wc = [[w[((k * sh.C + c) * sh.R + r) * sh.S + s] for k in range(sh.K) for r in range(sh.R) for s in range(sh.S)]
-          for c in range(sh.C)]
-    DX = po.gemm(rows, Wc, fmt, fmt, trans_b=True)
+    # backward-data follows the scatter of LibTorch's flow (W^T times dY, every column entry sent back to
+    # the input position it was unfolded from): the terms of a position are collected by walking the
+    # FORWARD index map, the opposite loop order of the oracle's gather
+    terms = {}
+    for n in range(sh.N):
+        for k in range(sh.K):
+            for oh in range(sh.OH):
+                for ow in range(sh.OW):
+                    for c in range(sh.C):
+                        for r in range(sh.R):
+                            for s in range(sh.S):
+                                h, ww = oh * sh.stride_h + r - sh.pad_h, ow * sh.stride_w + s - sh.pad_w
+                                if 0 <= h < sh.H and 0 <= ww < sh.W:
+                                    a, b = terms.setdefault((n, c, h, ww), ([], []))
+                                    a.append(dy[((n * sh.K + k) * sh.OH + oh) * sh.OW + ow])
+                                    b.append(w[((k * sh.C + c) * sh.R + r) * sh.S + s])
     dx = po.conv2d_bwd_data(dy, w, sh, fmt, fmt)
     for n in range(sh.N):
         for c in range(sh.C):
-            for i in range(sh.H * sh.W):
-                assert dx[(n * sh.C + c) * sh.H * sh.W + i] == DX[n * sh.H * sh.W + i][c]
+            for h in range(sh.H):
+                for ww in range(sh.W):
+                    a, b = terms.get((n, c, h, ww), ([], []))
+                    assert dx[((n * sh.C + c) * sh.H + h) * sh.W + ww] == po.dot(a, b, fmt, fmt), (n, c, h, ww)
+    # the NaR weight w[5] = w[k=0][c=0][r=2][s=1] reaches input row h from output row oh only when
+    # 2*oh + 2 - 1 == h, i.e. odd h, and column ww from ow = ww: channel 0 is NaR on rows 1 and 3 only
+    # (for every n and ww), apart from what the one NaR entry of dy adds
+    assert (sh.stride_h, sh.pad_h, sh.R, sh.S) == (2, 1, 3, 2)
+    dy_clean = [p if p != 0x80 else 0x40 for p in dy]
+    dxc = po.conv2d_bwd_data(dy_clean, w, sh, fmt, fmt)
+    for n in range(sh.N):
+        for c in range(sh.C):
+            for h in range(sh.H):
+                for ww in range(sh.W):
+                    is_nar = dxc[((n * sh.C + c) * sh.H + h) * sh.W + ww] == 0x80
+                    assert is_nar == (c == 0 and h % 2 == 1 and ww - 1 + sh.pad_w >= 0 and ww - 1 + sh.pad_w < sh.OW), (n, c, h, ww)

@@ -270,6 +270,13 @@ def test_convert_widening_is_exact_and_narrowing_rounds():
             assert po.convert(p, po.P16, po.P8) == po.round_by_search(v, po.P8)
 
 
+def test_quire_width_formula_reproduces_table_1():
+    """Table 1 prints the quire width of the three standard formats: 32, 128 and 512 bits.  The
+    formula used for the formats Table 1 does not list must return exactly those for the ones it does."""
+    assert [po.general_quire_bits(n, es) for n, es in ((8, 0), (16, 1), (32, 2))] == [32, 128, 512]
+    assert (po.P8.quire_bits, po.P16.quire_bits, po.P32.quire_bits) == (32, 128, 512)
+
+
 def test_general_format_quire_widths_hold_many_products():
     """Formats outside Table 1: maxpos = useed^(n-2) and the chosen quire width leaves at
     least 2^(n-1) - 1 products of maxpos * maxpos without wrap (n-1 carry-guard bits)."""
