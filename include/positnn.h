@@ -126,7 +126,12 @@ int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2d_desc* des
                      void* workspace, size_t workspace_bytes);
 
 /* Adjoint with respect to x: dx[n,c,h,w] = round_fout( sum of dy[n,k,oh,ow] * w[k,c,r,s]
- * over all (k,r,s,oh,ow) with oh*stride_h+r-pad_h == h and ow*stride_w+s-pad_w == w ). */
+ * over all (k,r,s,oh,ow) with oh*stride_h+r-pad_h == h and ow*stride_w+s-pad_w == w ): what
+ * LibTorch's flow (W^T times dY, columns scattered back, Sec. 3.1) accumulates per position.
+ * A tap (k,r,s) that reaches no output position from (h,w) is no term of that sum, so a NaR
+ * weight makes NaR only the positions its tap reaches, a NaR dy entry the positions it is
+ * scattered to (in the forward and backward-weight passes, by contrast, padded positions are
+ * zero operands of a matrix product and NaR * 0 = NaR spreads over the whole channel / filter). */
 int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_conv2d_desc* desc,
                           const void* dy, const void* w, void* dx,
                           void* workspace, size_t workspace_bytes);
@@ -151,8 +156,9 @@ size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_des
  * the terms t of its dot product in ascending order of the reduction index
  * (posit_gemm: k; fwd: (c,r,s); bwd_data: (k,r,s); bwd_weight and dbias: (n,oh,ow);
  * the last index fastest), then  s = round_fin( s + bias )  when a bias is given,
- * and the result stored is round_fout(s).  Padded positions and taps without a
- * partner are zero operands as above; NaR is absorbing.  Arguments, layouts and
+ * and the result stored is round_fout(s).  Padded positions are zero operands as
+ * above (adding their zero products changes no chain) and bwd_data has the terms of
+ * posit_conv2d_bwd_data; NaR is absorbing.  Arguments, layouts and
  * status codes are those of the quire entry points; no workspace is needed (the
  * order-dependent reduction is never split).  The result in general differs from
  * the quire result; it is deterministic and independent of the launch shape. */

@@ -182,8 +182,9 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
         st, a, b, out, d.M, d.N, d.K, bias, y, fout, ws, plan));
 }
 
+// The product kernels of this pass treat NaR weights as zeros; the outputs such a weight reaches are marked last.
 template <class F>
-int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
+int conv_bwd_data_product(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(1, g)) {
@@ -216,6 +217,14 @@ int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, c
     NchwOut out{(int64_t)g.H * g.W, (int64_t)g.C};
     return hip_status(launch_quire_gemm<F, decltype(a), decltype(b), NchwOut, ConvTile<F>::TM, ConvTile<F>::TN>(
         st, a, b, out, d.M, d.N, d.K, nullptr, dx, fout, ws, plan));
+}
+
+template <class F>
+int conv_bwd_data(hipStream_t st, int fout, const ConvGeom& g, const void* dy, const void* w, void* dx, void* ws, size_t ws_bytes) {
+    const int rc = conv_bwd_data_product<F>(st, fout, g, dy, w, dx, ws, ws_bytes);
+    if (rc != PNN_OK) return rc;
+    launch_bwd_data_nar_weights<F>(st, w, g, dx, fout);
+    return hip_status(hipGetLastError());
 }
 
 template <class F>

@@ -73,7 +73,10 @@ int conv_bwd_data_noquire(hipStream_t st, int fout, const ConvGeom& g, const voi
     ConvBwdDataDy<T> a{(const T*)dy, g, d.M, d.K};
     ConvBwdDataW<T> b{(const T*)w, g, d.N, d.K};
     NchwOut out{(int64_t)g.H * g.W, (int64_t)g.C};
-    return hip_status(launch_noquire<F>(st, a, b, out, d.M, d.N, d.K, nullptr, dx, fout));
+    const hipError_t e = launch_noquire<F>(st, a, b, out, d.M, d.N, d.K, nullptr, dx, fout);
+    if (e != hipSuccess) return PNN_EHIP;
+    launch_bwd_data_nar_weights<F>(st, w, g, dx, fout);  // NaR weights were zeros above: mark the positions their taps reach
+    return hip_status(hipGetLastError());
 }
 
 template <class F>

@@ -21,7 +21,8 @@ namespace pnn {
 template <int BR>
 struct B8Stage {
     typedef P8GatherStage<BR> G;
-    // decode the 16 bytes of every work item and store them as doubles into dst[k][row]
+    // decode the 16 bytes of every work item and store them as doubles into dst[k][row]; flags may be null
+    // (NaR patterns of that operand are then zeros and nothing more)
     __device__ __forceinline__ static void stage(const P8Frag (&f)[G::PER_THREAD], double (*dst)[BR], const double* tab, uint32_t* flags,
                                                  int t, int mode) {
 #pragma unroll
@@ -33,7 +34,7 @@ struct B8Stage {
                 const int row = w % BR, kq = w / BR;
 #pragma unroll
                 for (int b = 0; b < 16; ++b) dst[16 * kq + b][row] = tab[(f[i].w[b >> 2] >> (8 * (b & 3))) & 0xFFu];
-                if (nar) flags[row] = 1;
+                if (nar && flags) flags[row] = 1;
                 continue;
             }
             const int kp = w / G::GROUPS, c = (w % G::GROUPS) * 8;  // 8 rows at k = 2 kp and 2 kp + 1
@@ -45,7 +46,7 @@ struct B8Stage {
 #pragma unroll
                 for (int j = 0; j < 8; j += 2) *reinterpret_cast<double2*>(&dst[2 * kp + h][c + j]) = make_double2(d[j], d[j + 1]);
             }
-            if (nar) {
+            if (nar && flags) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t lo = (f[i].w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -108,6 +109,8 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
         for (int j = 0; j < TN; ++j) CA::clear(sum[i][j]);
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
+    uint32_t* const aflags = A.quiet_nar ? nullptr : rowNaR;
+    uint32_t* const bflags = B.quiet_nar ? nullptr : colNaR;
     // B's work items go to the threads A's leave idle when both fit the workgroup
     const int tb = (GA::ITEMS + GB::ITEMS <= 256) ? ((t + 256 - GA::ITEMS) & 255) : t;
     if (t < P8_KT) p8_fill_kinfo(A, kinfoA[0], kbeg, kend, t);
@@ -122,8 +125,8 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
                 if (t < P8_KT) p8_fill_kinfo(A, kinfoA[1], kbeg + P8_KT, kend, t);
                 else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[1], kbeg + P8_KT, kend, t - P8_KT);
             }
-            B8Stage<BM>::stage(fa, As[0], tab, rowNaR, t, A.mode);
-            B8Stage<BN>::stage(fb, Bs[0], tab, colNaR, tb, B.mode);
+            B8Stage<BM>::stage(fa, As[0], tab, aflags, t, A.mode);
+            B8Stage<BN>::stage(fb, Bs[0], tab, bflags, tb, B.mode);
         }
     }
     __syncthreads();
@@ -185,8 +188,8 @@ __global__ __launch_bounds__(256) void b8_conv_kernel(P8Gather A, P8Gather B, P8
 #pragma unroll
             for (int j = 0; j < TN; ++j) CA::carry_top(sum[i][j]);
         if (more) {
-            B8Stage<BM>::stage(fa, As[cur ^ 1], tab, rowNaR, t, A.mode);
-            B8Stage<BN>::stage(fb, Bs[cur ^ 1], tab, colNaR, tb, B.mode);
+            B8Stage<BM>::stage(fa, As[cur ^ 1], tab, aflags, t, A.mode);
+            B8Stage<BN>::stage(fb, Bs[cur ^ 1], tab, bflags, tb, B.mode);
         }
         __syncthreads();
     }

@@ -74,6 +74,8 @@ struct P8Gather {
     int rows, K;     // extents of the virtual matrix
     int LY, LX;      // bounds for y and x
     int mode, xstep; // P8GatherMode; x advance along a run
+    int quiet_nar;   // NaR patterns of this operand count as zero and raise no row / column flag (the weights of
+                     // the backward-data pass, whose NaR entries reach only part of a channel: marked by a kernel of their own)
     AffineIndex row, k;
 };
 
@@ -206,7 +208,7 @@ struct P8GatherStage {
         }
     }
 
-    // decode + pack + store into dst[k-pair][row]; flags[row] for NaR
+    // decode + pack + store into dst[k-pair][row]; flags[row] for NaR (flags may be null: NaR is then just a zero)
     template <int LD>
     __device__ __forceinline__ static void stage(const P8Frag (&f)[PER_THREAD], uint32_t (*dst)[LD], const uint16_t* tab,
                                                  uint32_t* flags, int t, int mode) {
@@ -222,7 +224,7 @@ struct P8GatherStage {
                     const uint32_t word = f[i].w[j >> 1] >> (16 * (j & 1));
                     dst[8 * kq + j][row] = (uint32_t)tab[word & 0xFFu] | ((uint32_t)tab[(word >> 8) & 0xFFu] << 16);
                 }
-                if (nar) flags[row] = 1;
+                if (nar && flags) flags[row] = 1;
                 continue;
             }
             const int kp = w / GROUPS, c = (w % GROUPS) * 8;
@@ -235,7 +237,7 @@ struct P8GatherStage {
             }
             *reinterpret_cast<uint4*>(&dst[kp][c]) = make_uint4(d[0], d[1], d[2], d[3]);
             *reinterpret_cast<uint4*>(&dst[kp][c + 4]) = make_uint4(d[4], d[5], d[6], d[7]);
-            if (nar) {
+            if (nar && flags) {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t lo = (f[i].w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
@@ -398,6 +400,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
         for (int j = 0; j < TN; ++j) acc[i][j] = 0;
 
     const int nkt = (kend - kbeg + P8_KT - 1) / P8_KT;
+    uint32_t* const aflags = A.quiet_nar ? nullptr : rowNaR;
+    uint32_t* const bflags = B.quiet_nar ? nullptr : colNaR;
     // B's work items start on the threads that A's leave idle when A has fewer items than threads
     const int tb = (SA::ITEMS < 256) ? ((t + 128) & 255) : t;
     if (t < P8_KT) p8_fill_kinfo(A, kinfoA[0], kbeg, kend, t);
@@ -412,8 +416,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
                 if (t < P8_KT) p8_fill_kinfo(A, kinfoA[1], kbeg + P8_KT, kend, t);
                 else if (t < 2 * P8_KT) p8_fill_kinfo(B, kinfoB[1], kbeg + P8_KT, kend, t - P8_KT);
             }
-            SA::template stage<BM>(fa, As[0], tab, rowNaR, t, A.mode);
-            SB::template stage<BN>(fb, Bs[0], tab, colNaR, tb, B.mode);
+            SA::template stage<BM>(fa, As[0], tab, aflags, t, A.mode);
+            SB::template stage<BN>(fb, Bs[0], tab, bflags, tb, B.mode);
         }
     }
     __syncthreads();
@@ -451,8 +455,8 @@ __global__ __launch_bounds__(256, 3) void p8_conv_kernel(P8Gather A, P8Gather B,
                 for (int j = 0; j < TN; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
         }
         if (more) {
-            SA::template stage<BM>(fa, As[cur ^ 1], tab, rowNaR, t, A.mode);
-            SB::template stage<BN>(fb, Bs[cur ^ 1], tab, colNaR, tb, B.mode);
+            SA::template stage<BM>(fa, As[cur ^ 1], tab, aflags, t, A.mode);
+            SB::template stage<BN>(fb, Bs[cur ^ 1], tab, bflags, tb, B.mode);
         }
         __syncthreads();
     }
@@ -539,6 +543,8 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
     }
     p.Mw = p.transposed ? p.N : p.M;
     p.Nw = p.transposed ? p.M : p.N;
+    p.A.quiet_nar = 0;
+    p.B.quiet_nar = which == 1;  // backward-data: a NaR weight reaches only the positions its tap reaches
     p8_pick_mode(p.A);
     p8_pick_mode(p.B);
     return p;
@@ -602,6 +608,7 @@ inline P8ConvProblem p8_gemm_problem(int transA, int transB, int M, int N, int K
     p.B.k = affine(1, 1, transB ? 1 : ldb, 0, 0, 0, 0, 0, 0, 0, 0, 0);
     p.out.md = make_fastdiv(1); p.out.m1 = ldc; p.out.m0 = 0; p.out.nstride = 1; p.out.vec4 = 0; p.out.wpad = 0; p.out.wvalid = 0; p.out.wd = make_fastdiv(1);
     p.Mw = M; p.Nw = N;
+    p.A.quiet_nar = 0; p.B.quiet_nar = 0;
     p8_pick_mode(p.A);
     p8_pick_mode(p.B);
     return p;

@@ -8,7 +8,8 @@
 // NaR becomes the marker -32768) in a layout where nothing is left to test:
 //   image operands get their zero border written out, with a row pitch that is a multiple of 8;
 //   matrix operands get a row pitch padded with zeros to a multiple of 32;
-//   the backward-data weights are transposed to [c][(ko,r,s)] on the way.
+//   the backward-data weights are transposed to [c][(ko,r,s)] on the way (their NaR entries become
+//   zeros: which outputs such a weight makes NaR depends on the tap, see bwd_data_nar_weights_kernel).
 // The main kernel then fetches 16-byte runs (8 consecutive rows at one k, or 8 consecutive k
 // of one row) with no predicate other than "row / k inside the problem", and stages them with
 // at most one permute per 32-bit LDS word.  A marker never needs removing: it raises the NaR
@@ -93,7 +94,8 @@ __global__ __launch_bounds__(256) void p8_predecode_kernel(P8PreJob j0, P8PreJob
                 uint32_t v = 0;
                 if (col < job.K) {
                     const int ko = col / job.RS, rs = col - ko * job.RS;
-                    v = tab[job.src[((int64_t)ko * job.C + row) * job.RS + rs]];
+                    const uint32_t b = job.src[((int64_t)ko * job.C + row) * job.RS + rs];
+                    v = b == 0x80u ? 0u : tab[b];  // a NaR weight of this pass is a zero here: the outputs it reaches are marked afterwards
                 }
                 d[e >> 1] |= v << (16 * (e & 1));
             }

@@ -29,6 +29,7 @@ namespace pnn {
 template <class T, bool KFAST_>
 struct MatrixOperand {
     static constexpr bool KFAST = KFAST_;
+    static constexpr bool RAISES_NAR = true;  // a NaR pattern of this operand makes its whole row (column) of outputs NaR
     const T* p;
     int64_t ld, rows, K;
     __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
@@ -40,6 +41,7 @@ struct MatrixOperand {
 // A column of ones (pattern `one`): turns the kernel into a row sum (bias gradient).
 struct OnesOperand {
     static constexpr bool KFAST = true;
+    static constexpr bool RAISES_NAR = true;
     uint32_t one;
     int64_t rows, K;
     __device__ __forceinline__ uint32_t operator()(int64_t row, int64_t k) const {
@@ -55,6 +57,7 @@ struct ConvGeom {
 template <class T>
 struct ConvFwdX {
     static constexpr bool KFAST = false;
+    static constexpr bool RAISES_NAR = true;
     const T* x;
     ConvGeom g;
     int64_t rows, K;
@@ -76,6 +79,7 @@ struct ConvFwdX {
 template <class T>
 struct ConvBwdDataDy {
     static constexpr bool KFAST = false;
+    static constexpr bool RAISES_NAR = true;
     const T* dy;
     ConvGeom g;
     int64_t rows, K;
@@ -95,10 +99,12 @@ struct ConvBwdDataDy {
     }
 };
 
-// Backward-data, right operand: row = c, k = (ko, r, s) -> w[ko, c, r, s]
+// Backward-data, right operand: row = c, k = (ko, r, s) -> w[ko, c, r, s].  A NaR weight is staged as zero and
+// raises no flag: it makes NaR only the input positions its tap reaches (bwd_data_nar_weights_kernel).
 template <class T>
 struct ConvBwdDataW {
     static constexpr bool KFAST = true;
+    static constexpr bool RAISES_NAR = false;
     const T* w;
     ConvGeom g;
     int64_t rows, K;
@@ -114,6 +120,7 @@ struct ConvBwdDataW {
 template <class T>
 struct ConvBwdWeightDy {
     static constexpr bool KFAST = true;
+    static constexpr bool RAISES_NAR = true;
     const T* dy;
     ConvGeom g;
     int64_t rows, K;
@@ -129,6 +136,7 @@ struct ConvBwdWeightDy {
 template <class T>
 struct ConvBwdWeightX {
     static constexpr bool KFAST = true;
+    static constexpr bool RAISES_NAR = true;
     const T* x;
     ConvGeom g;
     int64_t rows, K;
@@ -288,7 +296,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
             const int e = tid + GEMM_THREADS * i;
             const int kk = OpA::KFAST ? (e % KT) : (e / BM);
             const int r = OpA::KFAST ? (e / KT) : (e % BM);
-            if (pa[i] == FIN::NAR) rowNaR[r] = 1;
+            if (OpA::RAISES_NAR && pa[i] == FIN::NAR) rowNaR[r] = 1;
             As[buf][kk][r] = AR::stage(pa[i]);
         }
 #pragma unroll
@@ -296,7 +304,7 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
             const int e = tid + GEMM_THREADS * i;
             const int kk = OpB::KFAST ? (e % KT) : (e / BN);
             const int r = OpB::KFAST ? (e / KT) : (e % BN);
-            if (pb[i] == FIN::NAR) colNaR[r] = 1;
+            if (OpB::RAISES_NAR && pb[i] == FIN::NAR) colNaR[r] = 1;
             Bs[buf][kk][r] = AR::stage(pb[i]);
         }
     };
@@ -588,6 +596,45 @@ hipError_t launch_bias_grad(hipStream_t stream, const void* dy, void* dbias, int
         hipLaunchKernelGGL(bias_grad_finish_kernel<FIN>, dim3((unsigned)((channels + 255) / 256)), dim3(256), 0, stream,
                            (const uint32_t*)partial, used, channels, dbias, fout);
     return hipGetLastError();
+}
+
+// Backward-data pass, NaR weights.  dx[n,c,h,w] sums dy[n,k,oh,ow] * w[k,c,r,s] over the (k,r,s,oh,ow) with
+// oh*sh + r - ph == h and ow*sw + s - pw == w, so a NaR weight w[k,c,r,s] makes NaR exactly the positions of
+// channel c that its tap (r,s) reaches from some output position -- not the whole channel, as a column flag of
+// the implicit matrix product would.  The product kernels therefore stage NaR weights of this pass as zeros, and
+// this kernel, launched after them on the same stream, writes NaR to those positions: one thread per weight, which
+// returns at once unless its weight is NaR (the common case: one read of the weight tensor).
+template <class T>
+__global__ __launch_bounds__(256) void bwd_data_nar_weights_kernel(const T* __restrict__ w, uint32_t w_nar, ConvGeom g, void* __restrict__ dx,
+                                                                   int fout) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)g.K * g.C * g.R * g.S;
+    if (i >= total || (uint32_t)w[i] != w_nar) return;
+    const int s = (int)(i % g.S), r = (int)((i / g.S) % g.R), c = (int)((i / ((int64_t)g.R * g.S)) % g.C);
+    const FmtRT fo = fmt_of_code(fout);
+    const uint32_t nar = fo.nar();
+    for (int n = 0; n < g.N; ++n)
+        for (int oh = 0; oh < g.OH; ++oh) {
+            const int h = oh * g.sh + r - g.ph;
+            if (h < 0 || h >= g.H) continue;
+            for (int ow = 0; ow < g.OW; ++ow) {
+                const int x = ow * g.sw + s - g.pw;
+                if (x < 0 || x >= g.W) continue;
+                const int64_t at = (((int64_t)n * g.C + c) * g.H + h) * g.W + x;
+                if (fo.n <= 8) ((uint8_t*)dx)[at] = (uint8_t)nar;
+                else if (fo.n <= 16) ((uint16_t*)dx)[at] = (uint16_t)nar;
+                else ((uint32_t*)dx)[at] = nar;
+            }
+        }
+}
+
+template <class FIN>
+void launch_bwd_data_nar_weights(hipStream_t stream, const void* w, const ConvGeom& g, void* dx, int fout) {
+    typedef typename Storage<FIN::N>::T T;
+    const int64_t total = (int64_t)g.K * g.C * g.R * g.S;
+    if (total <= 0 || g.N <= 0) return;
+    hipLaunchKernelGGL(bwd_data_nar_weights_kernel<T>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, (const T*)w,
+                       (uint32_t)FIN::NAR, g, dx, fout);
 }
 
 // ---- host side ----

@@ -329,8 +329,6 @@ def _desc(d):
 @pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p16", "p16"), ("p32", "p32")])
 def test_conv_all_three_passes(ci, fin, fout):
     d = CONV_CASES[ci]
-    if fin == "p32" and ci == 4:
-        pytest.skip("kept small for the 512-bit quire")
     rng = np.random.default_rng(ci * 10 + BITS[fin])
     oh, ow = fast.out_hw(d)
     x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), fin, special=0.005)
@@ -346,6 +344,33 @@ def test_conv_all_three_passes(ci, fin, fout):
     wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, fin, fout, with_bias=True)
     _assert_equal(to_np(dw, fout), wdw, "conv bwd_weight")
     _assert_equal(to_np(db, fout), wdb, "conv dbias")
+
+
+@pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p8_2", "p8_2"), ("p8_1", "p12_2"), ("p16", "p16"), ("p12_2", "p8_2"), ("p32", "p32")])
+@pytest.mark.parametrize("geom", ["unit stride (operands rewritten)", "pad beyond the filter (byte gather)", "strided (generic kernel)"])
+def test_conv_bwd_data_nar_weight_reaches_only_its_taps_positions(fin, fout, geom):
+    """One NaR weight at a corner tap: the input gradient is NaR exactly where that tap reaches an output position (the
+    scatter of LibTorch's flow), not over the whole channel; through every kernel family that serves this pass, and
+    through the chain without quire."""
+    d = {"unit stride (operands rewritten)": dict(N=2, C=3, H=9, W=16, K=4, R=3, S=3, pad_h=1, pad_w=1),
+         "pad beyond the filter (byte gather)": dict(N=2, C=3, H=7, W=9, K=4, R=2, S=3, pad_h=3, pad_w=0),
+         "strided (generic kernel)": dict(N=2, C=3, H=11, W=10, K=4, R=3, S=2, pad_h=1, pad_w=0, stride_h=2, stride_w=3)}[geom]
+    rng = np.random.default_rng(BITS[fin] * 5 + len(geom))
+    oh, ow = fast.out_hw(d)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), fin, allow_nar=False)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), fin, allow_nar=False)
+    w[1, 2, 0, 0] = 1 << (BITS[fin] - 1)
+    w[3, 0, d["R"] - 1, d["S"] - 1] = 1 << (BITS[fin] - 1)
+    desc = _desc(d)
+    nar_out = 1 << (BITS[fout] - 1)
+    want = fast.conv2d_bwd_data(dy, w, d, fin, fout)
+    for c in (0, 2):  # the footprint is a proper, non-empty part of the channel; channel 1 holds no NaR at all
+        assert (want[:, c] == nar_out).any() and not (want[:, c] == nar_out).all()
+    assert not (want[:, 1] == nar_out).any()
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, fin, fout)
+    _assert_equal(to_np(dx, fout), want, "bwd_data with NaR weights")
+    dxq = pn.posit_conv2d_bwd_data_noquire(to_dev(dy), to_dev(w), desc, fin, fout)
+    _assert_equal(to_np(dxq, fout), fast.conv2d_bwd_data(dy, w, d, fin, fout, noquire=True), "bwd_data without quire, NaR weights")
 
 
 def test_conv_bwd_weight_long_reduction_splits():
