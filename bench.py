@@ -52,6 +52,47 @@ def _time_ms(torch, fn, reps, warm=2):
     return e0.elapsed_time(e1) / reps
 
 
+HBM_PEAK_TBS = 8.0  # MI355X HBM3E, published
+
+
+def elementwise_measurements(torch, pn, n=1 << 27):
+    """The bandwidth-bound entry points at n = 2^27 elements: algorithmic bytes per element (every input pattern read
+    once, every output pattern written once) over the mean launch time, as TB/s and as a fraction of the 8 TB/s HBM
+    peak; `copy` is torch's device-to-device copy of the same size class, the rate this machine reaches on a plain copy."""
+    out = {}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2105000535)
+    xf = torch.randn(n, dtype=torch.float32, device="cuda", generator=gen)
+    p8 = pn.posit_round(xf, "p8")
+    p16 = pn.posit_round(xf, "p16")
+    g16 = pn.posit_round(xf * 0.01, "p16")
+    o8 = torch.empty(n, dtype=torch.uint8, device="cuda")
+    o16 = torch.empty(n, dtype=torch.uint16, device="cuda")
+    of = torch.empty(n, dtype=torch.float32, device="cuda")
+    w16 = p16.clone()
+    p12 = pn.posit_round(xf, "p12_2")
+    g12 = pn.posit_round(xf * 0.01, "p12_2")
+    w12 = p12.clone()
+    lr16, lr12 = 0xEB33, int(pn.posit_round(torch.tensor([-0.1], dtype=torch.float32, device="cuda"), "p12_2").cpu().view(torch.int16)[0]) & 0xFFF
+    cases = [
+        ("copy_f32 (torch, reference)", 8, lambda: of.copy_(xf)),
+        ("round_f32_to_p8", 5, lambda: pn.posit_round(xf, "p8", out=o8)),
+        ("round_f32_to_p16", 6, lambda: pn.posit_round(xf, "p16", out=o16)),
+        ("convert_p8_to_p16", 3, lambda: pn.posit_convert(p8, "p8", "p16", out=o16)),
+        ("convert_p16_to_p8", 3, lambda: pn.posit_convert(p16, "p16", "p8", out=o8)),
+        ("convert_p16_to_f32", 6, lambda: pn.posit_convert(p16, "p16", "f32", out=of)),
+        ("axpy_p16_p16", 6, lambda: pn.posit_axpy(lr16, g16, w16, "p16", "p16")),
+        ("axpy_p16_p16_copy_p8", 7, lambda: pn.posit_axpy(lr16, g16, w16, "p16", "p16", fcopy="p8", y_copy=o8)),
+        ("axpy_p12_2_p12_2_copy_p8_2", 7, lambda: pn.posit_axpy(lr12, g12, w12, "p12_2", "p12_2", fcopy="p8_2", y_copy=o8)),
+    ]
+    for name, bytes_per_elem, fn in cases:
+        ms = _time_ms(torch, fn, 10, warm=2)
+        tbs = n * bytes_per_elem / (ms * 1e-3) / 1e12
+        out["elementwise_2^27_" + name] = {"ms": round(ms, 4), "B/elem": bytes_per_elem, "TB/s": round(tbs, 3),
+                                           "frac_of_hbm_peak": round(tbs / HBM_PEAK_TBS, 3)}
+    return out
+
+
 def extra_measurements(torch, pn, workloads):
     """The other benchmark configs, for the record (not part of `value`): GEMM kernels of configs 2 and 5
     and whole training steps of configs 3 and 4 (device-resident, see paper_2105_00053_amd/train_step.py)."""
@@ -67,6 +108,7 @@ def extra_measurements(torch, pn, workloads):
         ws = torch.empty(max(16, pn.posit_gemm_workspace(fmt, fmt, False, False, S, S, S)), dtype=torch.uint8, device="cuda")
         ms = _time_ms(torch, lambda: pn.posit_gemm(Ap, Bp, fmt, fmt, out=C, workspace=ws), 10 if fmt != "p32" else 3)
         out["gemm_%s_%d" % (fmt, S)] = {"ms": round(ms, 4), "TMAC/s": round(S ** 3 / ms / 1e9, 3)}
+    out.update(elementwise_measurements(torch, pn))
     final = dict(compute="p8_2", master="p12_2", loss="p10_2")  # Sec. 4, Table 4: the configuration the paper ends up with
     for name, net, fmts in (("lenet5_step_batch64", workloads.LENET, {}), ("cifarnet_step_batch128", workloads.CIFARNET, {}),
                             ("lenet5_step_batch64_posit8_2_12_2_10_2", workloads.LENET, final),
@@ -90,6 +132,7 @@ def main():
     ap.add_argument("--size", type=int, default=4096, help="M = N = K")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
+    ap.add_argument("--sustained-steps", type=int, default=200, help="steps of the longer run reported as `sustained` (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other benchmark configs)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy before timing (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -160,6 +203,18 @@ def main():
     value = macs / (ms_per_step * 1e-3) / 1e9  # GMAC/s over the whole step
     achieved = macs / (gemm_ms * 1e-3) / 1e12  # TMAC/s of the GEMM kernel
 
+    # a longer run of the same step, for a sustained figure beside the short timed region (clocks settle under load)
+    sustained = None
+    if args.sustained_steps > 0:
+        torch.cuda.synchronize()
+        ts = time.perf_counter()
+        for _ in range(args.sustained_steps):
+            step()
+        torch.cuda.synchronize()
+        sustained_ms = (time.perf_counter() - ts) * 1e3 / args.sustained_steps
+        sustained = {"steps": args.sustained_steps, "ms_per_step": round(sustained_ms, 4),
+                     "GMAC/s": round(macs / (sustained_ms * 1e-3) / 1e9, 1)}
+
     result = {
         "metric": "quire-exact posit MAC/s (GMAC/s) + % of integer-VALU peak, posit<8,0> GEMM",
         "value": round(value, 1),
@@ -188,6 +243,8 @@ def main():
         },
     }
 
+    if sustained:
+        result["sustained"] = sustained
     if not args.no_extra:
         result["extra"] = extra_measurements(torch, pn, workloads)
 

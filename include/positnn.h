@@ -90,7 +90,9 @@ int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
                const void* bias, void* C, int64_t ldc,
                void* workspace, size_t workspace_bytes);
 
-/* Bytes of device workspace posit_gemm wants for this problem (0 = none). */
+/* Bytes of device workspace posit_gemm wants for this problem (0 = none).  The arguments are those of
+ * the call it sizes; the answer depends on fin, M, N and K only (fout, transA, transB are accepted so
+ * that the query can follow any future kernel choice without a change of this interface). */
 size_t posit_gemm_workspace(int fin, int fout, int transA, int transB, int64_t M, int64_t N, int64_t K);
 
 /* posit_gemm for callers that cannot allocate device memory (code under HIP graph capture,
@@ -147,7 +149,8 @@ int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_de
  * call needs: device memory, 16-byte aligned (PNN_EINVAL otherwise), contents undefined on entry and
  * on return.  It holds the partial quires of a split reduction and, for posit<8,0> at unit stride,
  * the two operands rewritten once as decoded 16-bit integers with the zero border written out
- * (about twice the size of the tensors).  The calls of one stream may share one workspace. */
+ * (about twice the size of the tensors).  The calls of one stream may share one workspace.  The answer
+ * depends on which, fin and desc (fout is accepted for the same reason as in posit_gemm_workspace). */
 size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
 
 /* The same four operations with the quire switched off (Sec. 3.3: the quire is an
@@ -266,6 +269,8 @@ int posit_maxpool2d_bwd(void* stream, int fmt, int64_t planes, int64_t H, int64_
 
 /* Non-overlapping kh x kw average pooling with kh*kw a power of two: the exact quire dot product of the
  * window with the weight 1/(kh*kw), one rounding: y = round_fout( sum_window x * 2^-log2(kh*kw) ).
+ * The weight must be a posit of fin: a window that is no power of two, or larger than 1/minpos of fin
+ * (posit<8,0>: more than 64 elements), gives PNN_EUNSUPPORTED.
  * Identical to posit_conv2d_fwd on a one-channel image with a constant kernel and stride = window. */
 int posit_avgpool2d_fwd(void* stream, int fin, int fout, int64_t planes, int64_t H, int64_t W, int64_t kh, int64_t kw,
                         const void* x, void* y);

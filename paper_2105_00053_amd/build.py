@@ -20,8 +20,12 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
 UNITS = ["api_elementwise.hip", "api_gemm.hip", "api_conv.hip", "api_glue.hip", "api_noquire.hip", "api_loss.hip"]
+# Floating-point model, stated rather than left to the compiler's default: the fp64 "buckets" that carry exact
+# sums rely on every operation being the IEEE one that is written -- (r + C) - C must round r, not fold to r, and a
+# multiply-add is fused only where the source says fma().  So: no fast-math, no contraction across operations.
+FP_FLAGS = ["-fno-fast-math", "-ffp-contract=off"]
 DEVICE_FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=" + ARCH,
-                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"] + FP_FLAGS + [
                 "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
 
 
@@ -46,7 +50,7 @@ def build(verbose=False):
         objs = list(ex.map(_compile, UNITS))
     _run([HIPCC, "-shared", "-fPIC", "--offload-arch=" + ARCH, "-o", LIB] + objs)
     # host-only build of the scalar functions, for CPU unit tests
-    _run([HIPCC, "-O2", "-std=c++17", "-fPIC", "-shared", "--cuda-host-only", "-x", "hip",
+    _run([HIPCC, "-O2", "-std=c++17", "-fPIC", "-shared", "--cuda-host-only", "-x", "hip"] + FP_FLAGS + [
           "-Wno-unused-command-line-argument", os.path.join(CSRC, "host_check.hip"), "-o", HOSTCHECK])
     if verbose:
         print("built", LIB, "and", HOSTCHECK)

@@ -27,6 +27,9 @@ inline size_t elem_size(int f) {
 }
 inline bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 inline int hip_status(hipError_t e) { return e == hipSuccess ? PNN_OK : PNN_EHIP; }
+// Entry points report their own launches through hipGetLastError(); an error left behind by an earlier, unrelated
+// HIP call of this thread would otherwise be blamed on a call that launched fine.  Read (and so reset) it first.
+inline void discard_stale_hip_error() { (void)hipGetLastError(); }
 
 // Calls fn.template operator()<F>() ... with the format class of a posit code.
 #define PNN_DISPATCH_POSIT(code, CALL)                    \

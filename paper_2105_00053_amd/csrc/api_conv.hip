@@ -40,8 +40,9 @@ hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_CONV(16, 16, 8, 4);
     else PNN_LAUNCH_CONV(16, 16, 4, 4);
 #undef PNN_LAUNCH_CONV
-    if (plan.splits > 1) launch_split_merge<P8, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
-    return hipGetLastError();
+    PNN_CHECK_LAUNCH();
+    if (plan.splits > 1) return launch_split_merge<P8, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
+    return hipSuccess;
 }
 
 // Pre-decoded path: rewrite both operands into the workspace, then run the kernel that reads them.
@@ -61,6 +62,7 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(p8_predecode_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, st, pp.job[0], pp.job[1]);
+    PNN_CHECK_LAUNCH();
 
     const P8ConvTile tl = p8_conv_tile(pp.M, pp.N, pp.K);
     const int tiles_m = (pp.M + tl.bm - 1) / tl.bm, tiles_n = (pp.N + tl.bn - 1) / tl.bn;
@@ -84,8 +86,9 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
     else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_PRE(16, 16, 8, 4);
     else PNN_LAUNCH_PRE(16, 16, 4, 4);
 #undef PNN_LAUNCH_PRE
-    if (plan.splits > 1) launch_split_merge<P8, Out>(st, ws, plan.splits, pp.Mw, pp.Nw, bias, C, fout, merge_out);
-    return hipGetLastError();
+    PNN_CHECK_LAUNCH();
+    if (plan.splits > 1) return launch_split_merge<P8, Out>(st, ws, plan.splits, pp.Mw, pp.Nw, bias, C, fout, merge_out);
+    return hipSuccess;
 }
 
 // The pre-decoded path serves this pass: geometry fits, and no split reduction over padded rows.
@@ -298,6 +301,7 @@ extern "C" int posit_conv2d_fwd(void* stream, int fin, int fout, const pnn_conv2
     if (!y || (g.C > 0 && (!x || !w))) return PNN_EINVAL;
     if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_fwd<F>(st, fout, g, x, w, bias, y, workspace, workspace_bytes))
     return PNN_EINVAL;
 }
@@ -310,6 +314,7 @@ extern "C" int posit_conv2d_bwd_data(void* stream, int fin, int fout, const pnn_
     if (!dx || (g.K > 0 && (!dy || !w))) return PNN_EINVAL;
     if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_bwd_data<F>(st, fout, g, dy, w, dx, workspace, workspace_bytes))
     return PNN_EINVAL;
 }
@@ -322,6 +327,7 @@ extern "C" int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pn
     if (!dw || (g.N > 0 && (!dy || !x))) return PNN_EINVAL;
     if (workspace && !aligned(workspace, 16)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_bwd_weight<F>(st, fout, g, dy, x, dw, dbias, workspace, workspace_bytes))
     return PNN_EINVAL;
 }

@@ -62,6 +62,7 @@ int launch_map_p8(hipStream_t st, const void* src, void* dst, int64_t n, Op op) 
             hipLaunchKernelGGL((map_p8_table_kernel<TD, Op>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
                                (const uint8_t*)src, (TD*)dst, nvec, op);
             done = nvec * V;
+            if (hipGetLastError() != hipSuccess) return PNN_EHIP;  // stop at the first failed launch
         }
     }
     if (done < n) {
@@ -83,6 +84,7 @@ int launch_map(hipStream_t st, const void* src, void* dst, int64_t n, Op op) {
             hipLaunchKernelGGL((map_vec_kernel<TS, TD, V, Op>), dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st,
                                (const TS*)src, (TD*)dst, nvec, op);
             done = nvec * V;
+            if (hipGetLastError() != hipSuccess) return PNN_EHIP;  // stop at the first failed launch
         }
     }
     if (done < n) {
@@ -139,6 +141,7 @@ int launch_axpy(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* 
             hipLaunchKernelGGL((axpy_vec_kernel<TX, TY, TC, V, Axpy<FX, FY>, PositToPosit<FY, FC>>),
                                dim3((unsigned)((nvec + 255) / 256)), dim3(256), 0, st, (const TX*)x, (TY*)y, (TC*)yc, nvec, op, cp);
             done = nvec * V;
+            if (hipGetLastError() != hipSuccess) return PNN_EHIP;  // stop at the first failed launch
         }
     }
     if (done < n) {
@@ -271,6 +274,7 @@ extern "C" int posit_round(void* stream, int src_float, int dst_posit, int64_t n
     if (n == 0) return PNN_OK;
     if (!src || !dst) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     if (!is_standard(dst_posit)) return launch_map_rt(st, src_float, dst_posit, n, src, dst);
     if (src_float == PNN_F32) {
         switch (dst_posit) {
@@ -291,6 +295,7 @@ extern "C" int posit_convert(void* stream, int src, int dst, int64_t n, const vo
     if (n == 0) return PNN_OK;
     if (!src_ptr || !dst_ptr) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     if (!is_standard(src) || !is_standard(dst)) return launch_map_rt(st, src, dst, n, src_ptr, dst_ptr);
     switch (src) {
         case PNN_POSIT8_0: return convert_from<P8>(st, dst, n, src_ptr, dst_ptr);
@@ -306,6 +311,7 @@ extern "C" int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     if (!is_standard(fx) || !is_standard(fy) || (y_copy && !is_standard(fcopy))) {
         AxpyRT op;
         op.fx = fmt_of_code(fx);
@@ -333,6 +339,7 @@ extern "C" int posit_axpy_multi(void* stream, int fx, int fy, uint32_t alpha_bit
     }
     if (any_copy && !is_posit(fcopy)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     AxpyRT op;
     op.fx = fmt_of_code(fx);
     op.fy = fmt_of_code(fy);

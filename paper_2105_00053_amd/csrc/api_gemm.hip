@@ -143,6 +143,7 @@ extern "C" int posit_gemm(void* stream, int fin, int fout, int transA, int trans
     if (!launch) return rc;
     if (workspace && ((uintptr_t)workspace & 15u) != 0) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, workspace, workspace_bytes))
     return PNN_EINVAL;
 }
@@ -190,6 +191,7 @@ extern "C" int posit_gemm_static(void* stream, int fin, int fout, int transA, in
         if (rs != PNN_OK) return rs;
     }
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const size_t ws_bytes = need > 0 ? (size_t)PNN_GEMM_STATIC_SCRATCH_BYTES : 0;
     PNN_DISPATCH_POSIT(fin, return gemm_dispatch<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc, ws, ws_bytes))
     return PNN_EINVAL;

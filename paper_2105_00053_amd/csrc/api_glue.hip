@@ -182,6 +182,13 @@ inline uint32_t pow2_pattern(int nbits, int es, int s) {
     return s == 0 ? (1u << (nbits - 2)) : body;
 }
 
+// The pooling weight 2^-s is a posit of format `code` only down to minpos = 2^-((n-2) 2^es).
+inline bool pool_weight_fits(int code, int s) {
+    int n, es;
+    fmt_params(code, n, es);
+    return s <= ((n - 2) << es);
+}
+
 inline int window_shift(int64_t kh, int64_t kw) {
     const int64_t a = kh * kw;
     if (a <= 0 || (a & (a - 1))) return -1;
@@ -224,6 +231,7 @@ extern "C" int posit_relu(void* stream, int fmt, int64_t n, const void* x, void*
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     int64_t done = 0;  // elements covered by the 16-byte kernel
     if (aligned(x, 16) && aligned(y, 16)) {
         const int64_t per16 = 16 / (int64_t)elem_size(fmt), n16 = n / per16;
@@ -243,6 +251,7 @@ extern "C" int posit_relu_bwd(void* stream, int fmt_y, int fmt_d, int64_t n, con
     if (n == 0) return PNN_OK;
     if (!y_fwd || !dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     int64_t done = 0;
     if (elem_size(fmt_y) == elem_size(fmt_d) && aligned(y_fwd, 16) && aligned(dy, 16) && aligned(dx, 16)) {
         const int64_t per16 = 16 / (int64_t)elem_size(fmt_d), n16 = n / per16;
@@ -266,6 +275,7 @@ extern "C" int posit_maxpool2d_fwd(void* stream, int fmt, int64_t planes, int64_
     if (planes == 0) return PNN_OK;
     if (!x || !y || !idx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const int64_t total = planes * (H / kh) * (W / kw);
     PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(maxpool_fwd_kernel<T>, dim3(blocks_for(total)), dim3(256), 0, st, (const T*)x, (T*)y,
                                            (uint8_t*)idx, total, (int)H, (int)W, (int)kh, (int)kw, bits_of(fmt)))
@@ -278,6 +288,7 @@ extern "C" int posit_maxpool2d_bwd(void* stream, int fmt, int64_t planes, int64_
     if (planes == 0) return PNN_OK;
     if (!dy || !dx || !idx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const int64_t total = planes * H * W;
     PNN_BY_STORAGE(fmt, hipLaunchKernelGGL(maxpool_bwd_kernel<T>, dim3(blocks_for(total)), dim3(256), 0, st, (const T*)dy,
                                            (const uint8_t*)idx, (T*)dx, total, (int)H, (int)W, (int)kh, (int)kw))
@@ -288,10 +299,11 @@ extern "C" int posit_avgpool2d_fwd(void* stream, int fin, int fout, int64_t plan
                                    const void* x, void* y) {
     if (!is_posit(fin) || !is_posit(fout) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
     const int s = window_shift(kh, kw);
-    if (s < 0) return PNN_EUNSUPPORTED;
+    if (s < 0 || !pool_weight_fits(fin, s)) return PNN_EUNSUPPORTED;  // window not a power of two, or 1/window below minpos of fin
     if (planes == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const int64_t total = planes * (H / kh) * (W / kw);
     PNN_DISPATCH_POSIT(fin, hipLaunchKernelGGL(avgpool_fwd_kernel<F>, dim3(blocks_for(total)), dim3(256), 0, st,
                                                (const typename Storage<F::N>::T*)x, y, fout, total, (int)H, (int)W, (int)kh, (int)kw,
@@ -303,10 +315,11 @@ extern "C" int posit_avgpool2d_bwd(void* stream, int fin, int fout, int64_t plan
                                    const void* dy, void* dx) {
     if (!is_posit(fin) || !is_posit(fout) || !pool_args_ok(planes, H, W, kh, kw)) return PNN_EINVAL;
     const int s = window_shift(kh, kw);
-    if (s < 0) return PNN_EUNSUPPORTED;
+    if (s < 0 || !pool_weight_fits(fin, s)) return PNN_EUNSUPPORTED;
     if (planes == 0) return PNN_OK;
     if (!dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const int64_t total = planes * H * W;
     PNN_DISPATCH_POSIT(fin, hipLaunchKernelGGL(avgpool_bwd_kernel<F>, dim3(blocks_for(total)), dim3(256), 0, st,
                                                (const typename Storage<F::N>::T*)dy, dx, fout, total, (int)H, (int)W, (int)kh, (int)kw,

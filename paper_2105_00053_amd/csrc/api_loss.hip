@@ -318,6 +318,7 @@ extern "C" int posit_unary(void* stream, int fn, int fmt, int64_t n, const void*
     if (n == 0) return PNN_OK;
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_SMALL(fmt, hipLaunchKernelGGL(unary_kernel<F>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, fn, x, y, n))
     return hip_status(hipGetLastError());
 }
@@ -328,6 +329,7 @@ extern "C" int posit_unary_bwd(void* stream, int fn, int fmt_y, int fmt_d, int64
     if (n == 0) return PNN_OK;
     if (!y_fwd || !dy || !dx) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const FmtRT fy = fmt_of_code(fmt_y);
     PNN_DISPATCH_SMALL(fmt_d, hipLaunchKernelGGL(unary_bwd_kernel<F>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, fn, fy, y_fwd,
                                                  dy, dx, n))
@@ -342,6 +344,7 @@ extern "C" int posit_cross_entropy(void* stream, int f_logits, int f_loss, int f
     if (batch == 0 || classes == 0) return loss ? PNN_EINVAL : PNN_OK;  // a mean over nothing has no value
     if (!logits || !labels || (!loss && !dlogits)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const FmtRT fz = fmt_of_code(f_logits), fg = fmt_of_code(f_grad);
     if (classes <= 256) {
         int cp = 1;
@@ -369,6 +372,7 @@ extern "C" int posit_mse(void* stream, int f_pred, int f_loss, int f_grad, int64
     if (n == 0) return !loss ? PNN_OK : PNN_EINVAL;
     if (!pred || !target || (!loss && !dpred)) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     const FmtRT fp = fmt_of_code(f_pred), fg = fmt_of_code(f_grad);
     PNN_DISPATCH_SMALL(f_loss, hipLaunchKernelGGL(mse_kernel<F>, dim3(1), dim3(256), 0, st, fp, fg, n, pred, target, loss, dpred))
     return hip_status(hipGetLastError());

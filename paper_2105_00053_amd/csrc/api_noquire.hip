@@ -111,6 +111,7 @@ extern "C" int posit_gemm_noquire(void* stream, int fin, int fout, int transA, i
     }
     if (M >= ((int64_t)1 << 31) || N >= ((int64_t)1 << 31) || K >= ((int64_t)1 << 31) || M * N >= ((int64_t)1 << 40)) return PNN_EUNSUPPORTED;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return gemm_noquire<F>(st, fout, transA, transB, M, N, K, A, lda, B, ldb, bias, C, ldc))
     return PNN_EINVAL;
 }
@@ -122,6 +123,7 @@ extern "C" int posit_conv2d_fwd_noquire(void* stream, int fin, int fout, const p
     if (g.N == 0 || g.K == 0) return PNN_OK;
     if (!y || (g.C > 0 && (!x || !w))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_fwd_noquire<F>(st, fout, g, x, w, bias, y))
     return PNN_EINVAL;
 }
@@ -133,6 +135,7 @@ extern "C" int posit_conv2d_bwd_data_noquire(void* stream, int fin, int fout, co
     if (g.N == 0 || g.C == 0) return PNN_OK;
     if (!dx || (g.K > 0 && (!dy || !w))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_bwd_data_noquire<F>(st, fout, g, dy, w, dx))
     return PNN_EINVAL;
 }
@@ -144,6 +147,7 @@ extern "C" int posit_conv2d_bwd_weight_noquire(void* stream, int fin, int fout, 
     if (g.K == 0 || g.C == 0) return PNN_OK;
     if (!dw || (g.N > 0 && (!dy || !x))) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
+    discard_stale_hip_error();
     PNN_DISPATCH_POSIT(fin, return conv_bwd_weight_noquire<F>(st, fout, g, dy, x, dw, dbias))
     return PNN_EINVAL;
 }

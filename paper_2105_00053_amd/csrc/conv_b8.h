@@ -295,8 +295,9 @@ hipError_t b8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     else if (tl.bm == 32) PNN_LAUNCH_B8(2, 2);
     else PNN_LAUNCH_B8(1, 1);
 #undef PNN_LAUNCH_B8
-    if (plan.splits > 1) launch_split_merge<F, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
-    return hipGetLastError();
+    PNN_CHECK_LAUNCH();
+    if (plan.splits > 1) return launch_split_merge<F, Out>(st, ws, plan.splits, p.Mw, p.Nw, bias, C, fout, merge_out);
+    return hipSuccess;
 }
 
 // Small matrix products (the fully connected layers of the small networks: a few thousand outputs,

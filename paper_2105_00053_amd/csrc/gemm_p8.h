@@ -483,11 +483,12 @@ hipError_t launch_p8_gemm(hipStream_t stream, const uint8_t* A, int64_t lda, con
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((p8_gemm_kernel<A_KFAST, B_KFAST>), grid, dim3(256), 0, stream, A, lda, B, ldb, bias, C, ldc, fout,
                        (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, a_al, b_al, ws);
+    PNN_CHECK_LAUNCH();
     if (plan.splits > 1) {
         RowMajorOut out{ldc};
-        launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
+        return launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 // ---- large problems: operands packed once ----
@@ -529,6 +530,9 @@ inline void launch_p8_pack(hipStream_t stream, const P8PackJob& a, const P8PackJ
 inline hipError_t launch_p8_gemm_packed(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B,
                                         int64_t ldb, const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N,
                                         int64_t K, void* workspace, const GemmPlan& plan) {
+    // the packed kernel walks whole 32-wide slices from kbeg with no masking at kend (the padding holds zeros), so
+    // the slices of a split reduction must begin on slice boundaries or neighbours would both count the overlap
+    if (plan.splits > 1 && plan.k_per_split % P8_KT != 0) return hipErrorInvalidValue;
     const P8PackedLayout l = p8_packed_layout(M, N, K);
     uint8_t* wb = (uint8_t*)workspace;
     uint32_t* A2 = (uint32_t*)wb;
@@ -537,10 +541,12 @@ inline hipError_t launch_p8_gemm_packed(hipStream_t stream, int transA, int tran
     uint32_t* colflag = rowflag + l.Mp;
     const int64_t nflags = l.Mp + l.Np;
     hipLaunchKernelGGL(p8_fill_zero_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, rowflag, nflags);
+    PNN_CHECK_LAUNCH();
     // op(A)(m, k): stride (lda, 1), transposed (1, lda); op(B)(k, n) seen as rows n: stride (1, ldb), transposed (ldb, 1)
     const P8PackJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, A2, (int)l.Mp, (int)l.Kp2, rowflag};
     const P8PackJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, B2, (int)l.Np, (int)l.Kp2, colflag};
     launch_p8_pack(stream, ja, jb);
+    PNN_CHECK_LAUNCH();
     const int tiles_m = (int)(l.Mp / P8_BM), tiles_n = (int)(l.Np / P8_BN);
     SplitWs ws;
     ws.limbs = nullptr; ws.rowflag = nullptr; ws.colflag = nullptr;
@@ -553,11 +559,12 @@ inline hipError_t launch_p8_gemm_packed(hipStream_t stream, int transA, int tran
     hipLaunchKernelGGL((p8_gemm_kernel<true, true, true>), grid, dim3(256), 0, stream, (const uint8_t*)A2, l.Mp, (const uint8_t*)B2, l.Np,
                        bias, C, ldc, fout, (int)M, (int)N, (int)K, (int)plan.k_per_split, tiles_m, tiles_n, 1, 1, ws,
                        (const uint32_t*)rowflag, (const uint32_t*)colflag);
+    PNN_CHECK_LAUNCH();
     if (plan.splits > 1) {
         RowMajorOut out{ldc};
-        launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
+        return launch_split_merge<P8, RowMajorOut>(stream, ws, plan.splits, M, N, bias, C, fout, out);
     }
-    return hipGetLastError();
+    return hipSuccess;
 }
 
 // ---- small problems ----

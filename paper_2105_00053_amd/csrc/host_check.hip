@@ -162,9 +162,38 @@ int flush_one(int j, double m, uint32_t* out) {
     }
 }
 
+// the buckets after one product of staged operands a * b entered cleared buckets; cuts[j] = T(j + 1); returns the bucket count
+template <class F>
+int split_one(uint32_t a, uint32_t b, double* parts, int* cuts) {
+    typedef BucketArith<F> BA;
+    double bk[BA::NB];
+    BA::clear(bk);
+    BA::mac(bk, BA::stage(a), BA::stage(b));
+    for (int j = 0; j < BA::NB; ++j) {
+        parts[j] = bk[j];
+        cuts[j] = BA::T(j + 1);
+    }
+    return BA::NB;
+}
+
 }  // namespace
 
 extern "C" {
+
+// One product cut into its bucket parts (the error-free split of BucketArith::mac): parts[j] must be a multiple of
+// 2^cuts[j], and the parts must add up to the product.
+int hostcheck_bucket_split(int fin, uint32_t a, uint32_t b, double* parts, int* cuts) {
+    switch (fin) {
+        case 1: return split_one<P16>(a, b, parts, cuts);
+        case 3: return split_one<P8_1>(a, b, parts, cuts);
+        case 4: return split_one<P8_2>(a, b, parts, cuts);
+        case 5: return split_one<P10_1>(a, b, parts, cuts);
+        case 6: return split_one<P10_2>(a, b, parts, cuts);
+        case 7: return split_one<P12_1>(a, b, parts, cuts);
+        case 8: return split_one<P12_2>(a, b, parts, cuts);
+        default: return 0;
+    }
+}
 
 uint32_t hostcheck_dot_cascade(int fin, int fout, int64_t n, const uint32_t* a, const uint32_t* b, int has_bias, uint32_t bias) {
     switch (fin) {

@@ -21,6 +21,14 @@
 
 #include "quire_arith.h"
 
+// After a kernel launch inside a chain of launches: stop at the first failure, so that no later kernel
+// reads what a kernel that never ran should have written.
+#define PNN_CHECK_LAUNCH()                                 \
+    do {                                                   \
+        const hipError_t pnn_e_ = hipGetLastError();       \
+        if (pnn_e_ != hipSuccess) return pnn_e_;           \
+    } while (0)
+
 namespace pnn {
 
 // ---- operand functors: pattern of virtual element (row, k); zero outside ----
@@ -592,6 +600,7 @@ hipError_t launch_bias_grad(hipStream_t stream, const void* dy, void* dbias, int
     const int used = per > 0 ? (batch + per - 1) / per : 1;  // slices that actually hold images
     hipLaunchKernelGGL(bias_grad_kernel<FIN>, dim3((unsigned)channels, (unsigned)(slices > 1 ? used : 1)), dim3(256), 0, stream,
                        (const T*)dy, dbias, fout, batch, channels, spatial, vec, slices > 1 ? per : batch, (uint32_t*)partial);
+    PNN_CHECK_LAUNCH();
     if (slices > 1)
         hipLaunchKernelGGL(bias_grad_finish_kernel<FIN>, dim3((unsigned)((channels + 255) / 256)), dim3(256), 0, stream,
                            (const uint32_t*)partial, used, channels, dbias, fout);
@@ -640,7 +649,7 @@ void launch_bwd_data_nar_weights(hipStream_t stream, const void* w, const ConvGe
 // ---- host side ----
 
 template <class FIN, class Out>
-void launch_split_merge(hipStream_t stream, const SplitWs& ws, int splits, int64_t M, int64_t N, const void* bias, void* C, int fout,
+hipError_t launch_split_merge(hipStream_t stream, const SplitWs& ws, int splits, int64_t M, int64_t N, const void* bias, void* C, int fout,
                         const Out& out) {
     typedef typename Storage<FIN::N>::T TI;
     const int64_t total = M * N;
@@ -651,6 +660,7 @@ void launch_split_merge(hipStream_t stream, const SplitWs& ws, int splits, int64
         hipLaunchKernelGGL((split_merge_kernel<FIN, Out, 1>), dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, ws, splits, M, N,
                            (const TI*)bias, C, fout, out);
     }
+    return hipGetLastError();
 }
 
 struct GemmPlan {
@@ -705,8 +715,9 @@ hipError_t launch_quire_gemm(hipStream_t stream, const OpA& opa, const OpB& opb,
     dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)plan.splits);
     hipLaunchKernelGGL((quire_gemm_kernel<FIN, OpA, OpB, Out, TM, TN, AR>), grid, dim3(GEMM_THREADS), 0, stream,
                        opa, opb, out, M, N, K, plan.k_per_split, (const TI*)bias, C, fout, ws, (int)tiles_n);
-    if (plan.splits > 1) launch_split_merge<FIN, Out>(stream, ws, plan.splits, M, N, bias, C, fout, out);
-    return hipGetLastError();
+    PNN_CHECK_LAUNCH();
+    if (plan.splits > 1) return launch_split_merge<FIN, Out>(stream, ws, plan.splits, M, N, bias, C, fout, out);
+    return hipSuccess;
 }
 
 }  // namespace pnn

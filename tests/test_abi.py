@@ -91,6 +91,12 @@ def test_argument_validation_without_launch():
     d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 1, 1)
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, null, 0) == 3  # needs its workspace
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, ctypes.c_void_p(0x1004), 1 << 30) == EINVAL  # workspace alignment
+    # average pooling: the weight 1/(kh*kw) must be a posit of fin.  posit<8,0> stops at minpos = 1/64
+    assert L.posit_avgpool2d_fwd(null, 0, 0, 1, 16, 16, 16, 8, fake, fake) == 2   # 1/128 < minpos
+    assert L.posit_avgpool2d_bwd(null, 0, 0, 1, 16, 16, 16, 8, fake, fake) == 2
+    assert L.posit_avgpool2d_fwd(null, 0, 0, 0, 16, 16, 8, 8, null, null) == 0    # 1/64 = minpos: accepted (no planes: nothing launched)
+    assert L.posit_avgpool2d_fwd(null, 4, 4, 0, 16, 16, 16, 8, null, null) == 0   # posit(8,2) reaches 2^-24
+    assert L.posit_avgpool2d_fwd(null, 0, 0, 1, 6, 6, 3, 2, fake, fake) == 2      # window of 6: no power of two
     # a split reduction without the workspace it asks for
     need = L.posit_gemm_workspace(0, 1, 0, 0, 32, 288, 131072)
     assert need > 0

@@ -34,12 +34,12 @@ FINAL = ("p8_2", "p12_2", "p10_2")  # Sec. 4, Table 4: posit(8,2) layers, posit(
 
 
 @pytest.mark.parametrize("net,batch,fmts", [(workloads.LENET, 64, nn_harness.DEFAULT_FORMATS), (workloads.CIFARNET, 128, nn_harness.DEFAULT_FORMATS),
-                                            (workloads.LENET, 64, FINAL), (workloads.CIFARNET, 32, FINAL),
+                                            (workloads.LENET, 64, FINAL), (workloads.CIFARNET, 128, FINAL),
                                             (workloads.LENET, 64, ("p8_1", "p16", "p12_1")), (workloads.CIFARNET, 32, ("p8_1", "p12_1", "p16"))])
 def test_device_resident_step_matches_layerwise_harness(net, batch, fmts):
     """The all-on-GPU step (library glue kernels for ReLU / pooling, nothing on the host) ends in
     exactly the weights the layer-by-layer, oracle-checked harness ends in, in the default formats
-    and in the configuration the paper ends up with."""
+    and in the configuration the paper ends up with (both at the batch sizes the benchmark times)."""
     import numpy as np
     import torch
 

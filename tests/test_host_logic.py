@@ -2,6 +2,7 @@
 compiled for the host, against the oracle.  Runs without a GPU; the kernels
 call exactly these functions."""
 import ctypes
+from fractions import Fraction
 import os
 
 import numpy as np
@@ -38,6 +39,7 @@ def hc():
     L.hostcheck_dot_cascade.argtypes = [ci, ci, i64, vp, vp, ci, ctypes.c_uint32]
     L.hostcheck_bucket_config.argtypes = [ci, vp, vp, vp]
     L.hostcheck_bucket_flush.argtypes = [ci, ci, ctypes.c_double, vp]
+    L.hostcheck_bucket_split.argtypes = [ci, ctypes.c_uint32, ctypes.c_uint32, vp, vp]
     L.hostcheck_posit_op.restype = ctypes.c_uint32
     L.hostcheck_posit_op.argtypes = [ci, ci, ctypes.c_uint32, ctypes.c_uint32]
     L.hostcheck_div_int.restype = ctypes.c_uint32
@@ -266,6 +268,45 @@ def test_bucket_bounds_hold_for_the_format(hc, fmt):
     assert R + G - T1 <= 53
     assert R <= 51 + T1 or B == 1
     assert 2 * (f.n - 2 - f.es) + 2 <= 53  # a product's significand is a double
+
+
+@pytest.mark.parametrize("fmt", BUCKETED)
+def test_bucket_split_of_a_product_is_error_free_and_not_folded_away(hc, fmt):
+    """One product cut into its bucket parts: every part is a whole multiple of its bucket's unit 2^T_j, at most half
+    a unit of the bucket above, and the parts add up to the product exactly.  A build that re-associated
+    (r + C) - C into r (fast-math) would leave bits below 2^T_j in bucket j and fail the first property."""
+    f = po.FORMATS[fmt]
+    B, G, T1 = _bucket_config(hc, fmt)
+    rng = np.random.default_rng(CODE[fmt])
+    parts = (ctypes.c_double * 4)()
+    cuts = (ctypes.c_int * 4)()
+    pats = [int(p) for p in _patterns(rng, 300, fmt, 0.0)] + [1, (1 << (f.n - 1)) - 1, 3, (1 << (f.n - 1)) - 2, (1 << (f.n - 2)) + 1]
+    straddles = 0
+    for a in pats:
+        for b in pats[::7]:
+            if a in (0, f.nar) or b in (0, f.nar):
+                continue
+            nb = hc.hostcheck_bucket_split(CODE[fmt], a, b, parts, cuts)
+            assert nb == max(B, 1)
+            exact = po.decode(a, f) * po.decode(b, f) / f.quire_unit
+            assert exact.denominator == 1
+            total = 0
+            for j in range(nb):
+                v = Fraction(parts[j])
+                assert v.denominator == 1 and int(v) % (1 << cuts[j]) == 0, (fmt, a, b, j)
+                if j > 0:
+                    assert abs(int(v)) <= 1 << (cuts[j - 1] - 1)
+                total += int(v)
+            assert total == exact.numerator
+            straddles += sum(1 for j in range(nb) if parts[j] != 0.0) > 1
+    if B > 1:
+        assert straddles > 0, "some product must have bits on both sides of a cut"
+
+
+def test_build_states_the_floating_point_model():
+    from paper_2105_00053_amd import build
+    assert "-fno-fast-math" in build.DEVICE_FLAGS and "-ffp-contract=off" in build.DEVICE_FLAGS
+    assert not any(f in build.DEVICE_FLAGS for f in ("-ffast-math", "-Ofast", "-funsafe-math-optimizations", "-ffp-contract=fast"))
 
 
 @pytest.mark.parametrize("fmt", BUCKETED)
