@@ -3,14 +3,9 @@
 // handles a short vector of consecutive elements so that the widest type moves
 // 16 bytes per access; a scalar kernel covers unaligned pointers and the tail.
 #include "api_common.h"
-#include "elementwise_ops.h"
+#include "elementwise_fast.h"
 
 namespace pnn {
-
-template <class T, int V>
-struct alignas(sizeof(T) * V) Pack {
-    T v[V];
-};
 
 template <class TS, class TD, int V, class Op>
 __global__ __launch_bounds__(256) void map_vec_kernel(const TS* __restrict__ src, TD* __restrict__ dst, int64_t nvec, Op op) {
@@ -152,6 +147,61 @@ int launch_axpy(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* 
     return hip_status(hipGetLastError());
 }
 
+// ---- large tensors, formats of at most 16 bits: binary64 arithmetic with LDS decode tables ----
+
+// Below this many elements the per-workgroup table set-up outweighs what the cheaper per-element work saves.
+constexpr int64_t AXPY_F64_MIN_16 = (int64_t)1 << 22;  // posit<16,1> tables: 128 KB per workgroup
+constexpr int64_t AXPY_F64_MIN_12 = (int64_t)1 << 19;  // 12-bit formats: a few KB
+constexpr int64_t NARROW_STEP_MIN = (int64_t)1 << 20;
+
+inline int compute_units() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    return cus;
+}
+
+// Launches the binary64 kernel on the first n - n % 8 elements; returns false (nothing launched) when it does not apply.
+template <class FX, class FY, class FC, bool COPY>
+bool launch_axpy_f64(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* y, void* yc, int64_t* done) {
+    typedef typename Storage<FX::N>::T TX;
+    typedef typename Storage<FY::N>::T TY;
+    typedef typename Storage<FC::N>::T TC;
+    constexpr int V = 8;
+    constexpr bool BIG = FY::N > 12;  // the decode table fills most of a compute unit's LDS: one workgroup each
+    const int64_t nvec = n / V;
+    if (n < (BIG ? AXPY_F64_MIN_16 : AXPY_F64_MIN_12) || nvec == 0) return false;
+    if (!aligned(x, sizeof(TX) * V) || !aligned(y, sizeof(TY) * V) || (COPY && !aligned(yc, sizeof(TC) * V))) return false;
+    constexpr int THREADS = 1024;
+    int64_t blocks = (int64_t)compute_units() * (BIG ? 1 : 2);
+    const int64_t need = (nvec + THREADS - 1) / THREADS;
+    if (blocks > need) blocks = need;
+    hipLaunchKernelGGL((axpy_f64_kernel<FX, FY, FC, COPY, THREADS>), dim3((unsigned)blocks), dim3(THREADS), 0, st, (const TX*)x, (TY*)y,
+                       (TC*)yc, nvec, alpha);
+    *done = nvec * V;
+    return true;
+}
+
+// Format triples the binary64 kernel is built for: the default mixed-precision set-up (16-bit optimizer, 8-bit
+// compute copy) and the paper's final one (posit(12,2) optimizer, posit(8,2) layers: Sec. 4, Table 4).
+inline bool axpy_f64_dispatch(hipStream_t st, int fx, int fy, int fcopy, bool copy, uint32_t alpha, int64_t n, const void* x, void* y,
+                              void* yc, int64_t* done) {
+#define PNN_AXPY_F64(FX, FY, FC, CX, CY, CC)                                                                  \
+    if (fx == CX && fy == CY) {                                                                               \
+        if (!copy) return launch_axpy_f64<FX, FY, FC, false>(st, alpha, n, x, y, nullptr, done);              \
+        if (fcopy == CC) return launch_axpy_f64<FX, FY, FC, true>(st, alpha, n, x, y, yc, done);              \
+        return false;                                                                                         \
+    }
+    PNN_AXPY_F64(P16, P16, P8, PNN_POSIT16_1, PNN_POSIT16_1, PNN_POSIT8_0)
+    PNN_AXPY_F64(P8, P16, P8, PNN_POSIT8_0, PNN_POSIT16_1, PNN_POSIT8_0)
+    PNN_AXPY_F64(P12_2, P12_2, P8_2, PNN_POSIT12_2, PNN_POSIT12_2, PNN_POSIT8_2)
+    PNN_AXPY_F64(P8_2, P12_2, P8_2, PNN_POSIT8_2, PNN_POSIT12_2, PNN_POSIT8_2)
+#undef PNN_AXPY_F64
+    return false;
+}
+
 template <class FX, class FY>
 int axpy_pick_copy(hipStream_t st, uint32_t alpha, int64_t n, const void* x, void* y, int fcopy, void* yc) {
     if (!yc) return launch_axpy<FX, FY, FY>(st, alpha, n, x, y, nullptr);
@@ -185,6 +235,18 @@ int convert_from(hipStream_t st, int dst, int64_t n, const void* s, void* d) {
             case PNN_F64: return launch_map_p8<uint64_t>(st, s, d, n, PositToF64<FS>());
         }
         return PNN_EINVAL;
+    }
+    if (FS::N == 16 && dst == PNN_POSIT8_0 && n >= NARROW_STEP_MIN && aligned(s, 16) && aligned(d, 8)) {
+        // step-table kernel on whole vectors of 8, the generic kernel on what is left
+        const int64_t nvec = n / 8;
+        int64_t blocks = (nvec + 255) / 256;
+        const int64_t cap = (int64_t)compute_units() * 8;
+        if (blocks > cap) blocks = cap;
+        hipLaunchKernelGGL((narrow_step_kernel<P16, P8>), dim3((unsigned)blocks), dim3(256), 0, st, (const uint16_t*)s, (uint8_t*)d, nvec);
+        if (hipGetLastError() != hipSuccess) return PNN_EHIP;
+        const int64_t done = nvec * 8;
+        if (done == n) return PNN_OK;
+        return launch_map<TS, uint8_t>(st, (const TS*)s + done, (uint8_t*)d + done, n - done, PositToPosit<FS, P8>());
     }
     switch (dst) {
         case PNN_POSIT8_0: return launch_map<TS, uint8_t>(st, s, d, n, PositToPosit<FS, P8>());
@@ -312,6 +374,18 @@ extern "C" int posit_axpy(void* stream, int fx, int fy, uint32_t alpha_bits, int
     if (!x || !y) return PNN_EINVAL;
     hipStream_t st = (hipStream_t)stream;
     discard_stale_hip_error();
+    {
+        int64_t done = 0;
+        if (axpy_f64_dispatch(st, fx, fy, fcopy, y_copy != nullptr, alpha_bits, n, x, y, y_copy, &done)) {
+            if (hipGetLastError() != hipSuccess) return PNN_EHIP;
+            if (done == n) return PNN_OK;
+            // the last n % 8 elements go through the generic path below
+            x = (const uint8_t*)x + done * elem_size(fx);
+            y = (uint8_t*)y + done * elem_size(fy);
+            if (y_copy) y_copy = (uint8_t*)y_copy + done * elem_size(fcopy);
+            n -= done;
+        }
+    }
     if (!is_standard(fx) || !is_standard(fy) || (y_copy && !is_standard(fcopy))) {
         AxpyRT op;
         op.fx = fmt_of_code(fx);

@@ -1,7 +1,7 @@
 // Host build of the scalar device functions (decode, encode, quire read-out,
 // exact add) so that unit tests can drive them on a machine without a GPU.
 // Test scaffolding: nothing in the library links or calls this file.
-#include "elementwise_ops.h"
+#include "elementwise_fast.h"
 #include "quire_arith.h"
 #include "conv_p8.h"
 #include "noquire_arith.h"
@@ -327,6 +327,43 @@ int hostcheck_axpy_rt(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t*
     op.alpha = alpha;
     for (int64_t i = 0; i < n; ++i) out[i] = op((uint32_t)x[i], (uint32_t)y[i]);
     return 0;
+}
+
+// the arithmetic of the large-tensor update kernel (binary64 product, error-free sum, one rounding), element by element
+int hostcheck_axpy_f64(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t* x, const uint64_t* y, uint64_t* out) {
+#define CASE(FX, FY, a, b)                                                                                                  \
+    if (fx == a && fy == b) {                                                                                               \
+        const double ad = f64_of_pattern<FY>(alpha);                                                                        \
+        for (int64_t i = 0; i < n; ++i) out[i] = axpy_f64<FY>(ad, f64_of_pattern<FX>((uint32_t)x[i]), f64_of_pattern<FY>((uint32_t)y[i])); \
+        return 0;                                                                                                           \
+    }
+    CASE(P16, P16, 1, 1) CASE(P8, P16, 0, 1) CASE(P12_2, P12_2, 8, 8) CASE(P8_2, P12_2, 4, 8) CASE(P8, P8, 0, 0) CASE(P10_1, P12_1, 5, 7)
+#undef CASE
+    return 1;
+}
+
+// posit<16,1> -> posit<8,0> through the step table of the narrowing kernel
+int hostcheck_narrow_step(int64_t n, const uint64_t* in, uint64_t* out) {
+    for (int64_t i = 0; i < n; ++i) {
+        const uint32_t p = (uint32_t)in[i] & 0xFFFFu;
+        out[i] = narrow_step_apply(narrow_step_entry<P16, P8>(p >> 6), p);
+    }
+    return 0;
+}
+
+// one rounding of the binary64 s (exact value: s, or just off s as the two flags say) to posit code fmt
+uint32_t hostcheck_round_f64(int fmt, double s, int inexact, int toward_zero) {
+    switch (fmt) {
+        case 0: return round_f64_to_posit<P8>(s, inexact, toward_zero);
+        case 1: return round_f64_to_posit<P16>(s, inexact, toward_zero);
+        case 3: return round_f64_to_posit<P8_1>(s, inexact, toward_zero);
+        case 4: return round_f64_to_posit<P8_2>(s, inexact, toward_zero);
+        case 5: return round_f64_to_posit<P10_1>(s, inexact, toward_zero);
+        case 6: return round_f64_to_posit<P10_2>(s, inexact, toward_zero);
+        case 7: return round_f64_to_posit<P12_1>(s, inexact, toward_zero);
+        case 8: return round_f64_to_posit<P12_2>(s, inexact, toward_zero);
+        default: return 0xFFFFFFFFu;
+    }
 }
 
 int hostcheck_convert(int src, int dst, int64_t n, const uint64_t* in, uint64_t* out) {

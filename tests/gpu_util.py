@@ -49,3 +49,18 @@ def mismatches(got, want):
     assert got.shape == want.shape, (got.shape, want.shape)
     bad = np.argwhere(got != want)
     return bad
+
+
+def oracle_axpy_chunked(alpha, x, y, fx, fy, fc=None, workers=16):
+    """fast.axpy (single-threaded C++ oracle) over slices of a long tensor in parallel threads: elementwise, so the
+    slices are independent; ctypes releases the interpreter lock during the call."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import fast
+    n = len(x)
+    bounds = [n * i // workers for i in range(workers + 1)]
+    with ThreadPoolExecutor(workers) as ex:
+        parts = list(ex.map(lambda i: fast.axpy(alpha, x[bounds[i]:bounds[i + 1]], y[bounds[i]:bounds[i + 1]], fx, fy, fc), range(workers)))
+    if fc:
+        return np.concatenate([p[0] for p in parts]), np.concatenate([p[1] for p in parts])
+    return np.concatenate(parts)

@@ -13,7 +13,7 @@ import workloads
 from oracle import fast
 from oracle import posit_oracle as po
 
-from gpu_util import BITS, GENERAL, NP_DTYPE, mismatches, rand_patterns, to_dev, to_np
+from gpu_util import BITS, GENERAL, NP_DTYPE, mismatches, oracle_axpy_chunked, rand_patterns, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 PF = {k: po.FORMATS[k] for k in BITS}
@@ -88,6 +88,43 @@ def test_axpy(fx, fy, fc):
             _assert_equal(to_np(res[1], fc), want[1], "axpy copy")
         else:
             _assert_equal(to_np(res, fy), want, "axpy y")
+
+
+@pytest.mark.parametrize("fx,fy,fc,n", [("p16", "p16", "p8", (1 << 22) + 13), ("p16", "p16", None, 1 << 22), ("p8", "p16", "p8", (1 << 22) + 8),
+                                        ("p8", "p16", None, (1 << 22) + 1), ("p12_2", "p12_2", "p8_2", (1 << 19) + 5),
+                                        ("p12_2", "p12_2", None, 1 << 19), ("p8_2", "p12_2", "p8_2", (1 << 19) + 7), ("p8_2", "p12_2", None, (1 << 20) + 3)])
+def test_axpy_large_tensors_take_the_binary64_kernel(fx, fy, fc, n):
+    """Sizes from which posit_axpy switches to the kernel with LDS decode tables and binary64 arithmetic (whole vectors
+    of 8, the generic kernel on the ragged tail): every pattern of y occurs, against random x, with special patterns,
+    near-cancelling pairs and pairs far apart; two values of alpha."""
+    rng = np.random.default_rng(n % 1000 + BITS[fx])
+    mask = (1 << BITS[fy]) - 1
+    x = rand_patterns(rng, n, fx, special=0.01)
+    y = rand_patterns(rng, n, fy, special=0.01)
+    y[: 1 << BITS[fy]] = np.arange(1 << BITS[fy], dtype=np.uint32).astype(NP_DTYPE[fy])
+    lr = int(fast.round_from_float(np.array([-0.1], np.float32), fy)[0])
+    # a stretch where y nearly cancels alpha * x
+    m = 200000
+    t = fast.axpy(lr, x[-m:], np.zeros(m, dtype=NP_DTYPE[fy]), fx, fy).astype(np.int64)
+    y[-m:] = ((-t + rng.integers(-2, 3, m)) & mask).astype(NP_DTYPE[fy])
+    for alpha in (lr, int(rand_patterns(rng, 1, fy, 0, allow_nar=False)[0])):
+        yd = to_dev(y)
+        res = pn.posit_axpy(alpha, to_dev(x), yd, fx, fy, fc)
+        want = oracle_axpy_chunked(alpha, x, y, fx, fy, fc)
+        if fc:
+            _assert_equal(to_np(res[0], fy), want[0], "axpy y")
+            _assert_equal(to_np(res[1], fc), want[1], "axpy copy")
+        else:
+            _assert_equal(to_np(res, fy), want, "axpy y")
+
+
+def test_convert_posit16_to_posit8_large_takes_the_step_table_kernel():
+    n = (1 << 21) + 11
+    rng = np.random.default_rng(5)
+    pats = rng.integers(0, 1 << 16, n, dtype=np.uint32).astype(np.uint16)
+    pats[: 1 << 16] = np.arange(1 << 16, dtype=np.uint32).astype(np.uint16)
+    got = to_np(pn.posit_convert(to_dev(pats), "p16", "p8"), "p8")
+    _assert_equal(got, fast.convert(pats, "p16", "p8"), "convert p16->p8, large")
 
 
 @pytest.mark.parametrize("fx,fy,fc", [("p16", "p16", "p8"), ("p8_2", "p12_2", "p8_2"), ("p32", "p32", None), ("p8", "p16", None)])

@@ -46,6 +46,10 @@ def hc():
     L.hostcheck_div_int.argtypes = [ci, ci, ctypes.c_uint32, ci, ctypes.c_uint32]
     L.hostcheck_map_rt.argtypes = [ci, ci, i64, vp, vp]
     L.hostcheck_axpy_rt.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
+    L.hostcheck_axpy_f64.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
+    L.hostcheck_narrow_step.argtypes = [i64, vp, vp]
+    L.hostcheck_round_f64.restype = ctypes.c_uint32
+    L.hostcheck_round_f64.argtypes = [ci, ctypes.c_double, ci, ci]
     return L
 
 
@@ -138,6 +142,87 @@ def test_axpy_near_cancellation(hc, fx, fy):
             out = np.zeros(n, dtype=np.uint64)
             assert hc.hostcheck_axpy(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
             assert np.array_equal(out, fast.axpy(alpha, x, y, fx, fy).astype(np.uint64)), (alpha, delta)
+
+
+F64_PAIRS = [("p16", "p16"), ("p8", "p16"), ("p12_2", "p12_2"), ("p8_2", "p12_2"), ("p8", "p8"), ("p10_1", "p12_1")]
+
+
+@pytest.mark.parametrize("fx,fy", F64_PAIRS)
+def test_axpy_through_binary64_with_error_free_sum(hc, fx, fy):
+    """The arithmetic of the large-tensor update kernel: product in binary64, sum with its exact error term, one
+    rounding.  Random patterns, special patterns, sums that cancel almost completely, and terms so far apart that
+    the smaller one lies wholly below the larger one's last bit (where the error term alone decides a tie)."""
+    rng = np.random.default_rng(BITS[fx] * 3 + BITS[fy] + CODE[fy])
+    n = 80000
+    mask = (1 << BITS[fy]) - 1
+    x = _patterns(rng, n, fx)
+    y = _patterns(rng, n, fy)
+    lr = int(fast.round_from_float(np.array([-0.1], dtype=np.float32), fy)[0])
+    alphas = [lr, 1 << (BITS[fy] - 2), int(_patterns(rng, 1, fy, 0)[0]), 0, 1 << (BITS[fy] - 1), 1, mask, (1 << (BITS[fy] - 1)) - 1,
+              (1 << (BITS[fy] - 2)) | (1 << (BITS[fy] - 1))]
+    for alpha in alphas:
+        out = np.zeros(n, dtype=np.uint64)
+        assert hc.hostcheck_axpy_f64(CODE[fx], CODE[fy], alpha, n, _p(x), _p(y), _p(out)) == 0
+        assert np.array_equal(out, fast.axpy(alpha, x, y, fx, fy).astype(np.uint64)), alpha
+    # near cancellation: y = -round(alpha x) nudged by a few patterns
+    xs = _patterns(rng, n, fx, special=0.0)
+    for alpha in (lr, int(_patterns(rng, 1, fy, 0)[0]) | 1):
+        t = fast.axpy(alpha, xs, np.zeros(n, dtype=np.uint64), fx, fy).astype(np.int64)
+        for delta in (0, 1, -1, 3, -7, 64):
+            y2 = ((-t + delta) & mask).astype(np.uint64)
+            out = np.zeros(n, dtype=np.uint64)
+            hc.hostcheck_axpy_f64(CODE[fx], CODE[fy], alpha, n, _p(xs), _p(y2), _p(out))
+            assert np.array_equal(out, fast.axpy(alpha, xs, y2, fx, fy).astype(np.uint64)), (alpha, delta)
+    # far apart: huge y with tiny alpha x and the other way round, both signs: every y that sits exactly on a tie of the
+    # coarser neighbourhood is decided by the sign of the tiny term
+    big = np.array([p for p in range(1, 1 << (BITS[fy] - 1))] * 2, dtype=np.uint64)
+    big[len(big) // 2:] = ((-big[len(big) // 2:].astype(np.int64)) & mask).astype(np.uint64)
+    for tiny_x, alpha in ((1, 1), (1, mask), ((1 << BITS[fx]) - 1, 3), (3, lr)):
+        xt = np.full(len(big), tiny_x, dtype=np.uint64)
+        out = np.zeros(len(big), dtype=np.uint64)
+        hc.hostcheck_axpy_f64(CODE[fx], CODE[fy], alpha, len(big), _p(xt), _p(big), _p(out))
+        assert np.array_equal(out, fast.axpy(alpha, xt, big, fx, fy).astype(np.uint64)), (tiny_x, alpha)
+
+
+def test_narrowing_step_table_posit16_to_posit8_all_patterns(hc):
+    pats = np.arange(1 << 16, dtype=np.uint64)
+    out = np.zeros_like(pats)
+    assert hc.hostcheck_narrow_step(len(pats), _p(pats), _p(out)) == 0
+    assert np.array_equal(out, fast.convert(pats, "p16", "p8").astype(np.uint64))
+
+
+@pytest.mark.parametrize("fmt", ["p8", "p16", "p8_1", "p8_2", "p10_1", "p10_2", "p12_1", "p12_2"])
+def test_round_binary64_to_posit_with_sticky_flags(hc, fmt):
+    """round_f64_to_posit against the oracle's rounding of exact rationals: every tie point and every pattern value of
+    the format as the binary64 s, exact, with 'a little more' and 'a little less' (the two flag settings), both signs;
+    random binary64 values with all 52 fraction bits in use; values beyond maxpos and below minpos."""
+    f = po.FORMATS[fmt]
+    wide = po.PositFormat(f.n + 1, f.es, 0)
+    eps = Fraction(1, 1 << 300)
+    cases = []
+    for p in range(1, 1 << f.n):  # values of the (n+1)-bit format: the patterns of fmt and the ties between them
+        v = po.decode(p, wide)
+        if v is po.NaR:
+            continue
+        cases.append(v)
+    rng = np.random.default_rng(f.n * 7 + f.es)
+    maxs = (f.n - 2) << f.es
+    for _ in range(3000):
+        m = 1 + Fraction(int(rng.integers(0, 1 << 52)), 1 << 52)
+        e = int(rng.integers(-maxs - 4, maxs + 4))
+        cases.append((m * Fraction(2) ** e) * (1 if rng.random() < 0.5 else -1))
+    cases += [Fraction(2) ** (maxs + 40), -Fraction(2) ** (maxs + 40), Fraction(2) ** (-maxs - 40), -Fraction(2) ** (-maxs - 40)]
+    for v in cases:
+        s = float(v)
+        assert Fraction(s) == v
+        assert hc.hostcheck_round_f64(CODE[fmt], s, 0, 0) == po.round_to_posit(v, f), v
+        up = v + eps if v > 0 else v - eps    # magnitude a little larger
+        dn = v - eps if v > 0 else v + eps    # magnitude a little smaller
+        assert hc.hostcheck_round_f64(CODE[fmt], s, 1, 0) == po.round_to_posit(up, f), ("more", v)
+        assert hc.hostcheck_round_f64(CODE[fmt], s, 1, 1) == po.round_to_posit(dn, f), ("less", v)
+    assert hc.hostcheck_round_f64(CODE[fmt], 0.0, 0, 0) == 0
+    assert hc.hostcheck_round_f64(CODE[fmt], -0.0, 0, 0) == 0
+    assert hc.hostcheck_round_f64(CODE[fmt], float("nan"), 0, 0) == f.nar
 
 
 @pytest.mark.parametrize("fin,fout", [(f, f) for f in GENERAL] + [("p8_2", "p12_2"), ("p8_2", "p10_2"), ("p12_1", "p8"), ("p8_1", "p16"), ("p16", "p12_2")])
