@@ -5,6 +5,7 @@
 
 #include "api_common.h"
 #include "conv_p8.h"
+#include "gemm_p8_w4.h"
 #include "conv_b8.h"
 
 namespace pnn {
@@ -14,6 +15,10 @@ template <> struct GemmTile<P32> { static constexpr int TM = 2, TN = 2; };
 
 // posit<8,0> problems with both output dimensions beyond one small tile take the dot2 kernel
 inline bool use_p8_kernel(int64_t M, int64_t N) { return M > 64 && N > 64; }
+
+// ... and of those, the ones with too few 128 x 128 tiles to fill the chip go to the 64 x 64 kernel whose four waves
+// split the reduction (larger products decode and pack their operands once instead)
+inline bool use_p8_w4(int64_t M, int64_t N, int64_t K) { return use_p8_kernel(M, N) && p8_w4_fits(M, N, K) && !p8_packed_gemm_fits(M, N, K); }
 
 // posit(8,1) / posit(8,2): the byte-gather kernel with fp64 buckets
 template <class F>
@@ -34,6 +39,7 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
         p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
         return p;
     }
+    if ((F::N == 8 && F::ES == 0) && use_p8_w4(M, N, K)) return p8_w4_plan(M, N, K).gemm;  // the reduction is cut inside the workgroup first
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
         GemmPlan p = plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
         if (p8_packed_gemm_fits(M, N, K)) p.ws_bytes += p8_packed_layout(M, N, K).total();  // operands packed once, ahead of the split partials
@@ -58,6 +64,16 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K))
         return hip_status(launch_p8_small_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                fout, M, N, K));
+    if ((F::N == 8 && F::ES == 0) && use_p8_w4(M, N, K)) {
+        const uint8_t* a8 = (const uint8_t*)A;
+        const uint8_t* b8 = (const uint8_t*)B;
+        const uint8_t* bias8 = (const uint8_t*)bias;
+        if (!transA && !transB) e = launch_p8_gemm_w4<true, false>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws);
+        else if (!transA && transB) e = launch_p8_gemm_w4<true, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws);
+        else if (transA && !transB) e = launch_p8_gemm_w4<false, false>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws);
+        else e = launch_p8_gemm_w4<false, true>(st, a8, lda, b8, ldb, bias8, C, ldc, fout, M, N, K, ws);
+        return hip_status(e);
+    }
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N) && p8_packed_gemm_fits(M, N, K)) {
         return hip_status(launch_p8_gemm_packed(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                 fout, M, N, K, ws, plan));

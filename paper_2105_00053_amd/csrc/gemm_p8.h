@@ -228,30 +228,28 @@ __global__ void p8_fill_zero_kernel(uint32_t* p, int64_t n) {
     if (i < n) p[i] = 0;
 }
 
-// int32 quire (units of 2^-12) -> posit<8,0>, nearest, ties to even pattern,
-// clamped to +-minpos / +-maxpos.  32-bit arithmetic only: the bit string after
-// the sign is assembled at the top of a word and cut after 7 bits.
-__device__ __forceinline__ uint32_t p8_round_quire(int32_t q) {
-    if (q == 0) return 0u;
-    const bool neg = q < 0;
-    const uint32_t mag = neg ? (0u - (uint32_t)q) : (uint32_t)q;
-    const int lz = __clz((int)mag);
-    const int k = 19 - lz;  // floor(log2(mag)) - 12
-    uint32_t body;
-    if (k >= 6) {
-        body = 0x7Fu;
-    } else if (k < -6) {
-        body = 0x01u;
-    } else {
-        const uint32_t frac = (mag << lz) << 1;  // fraction bits at the top, leading one gone
-        uint32_t s;
-        if (k >= 0) s = (uint32_t)((int32_t)0x80000000 >> k) | (frac >> (k + 2));  // k+1 ones, a zero, fraction
-        else s = (0x80000000u | (frac >> 1)) >> (-k);                              // -k zeros, a one, fraction
-        const uint32_t r = s >> 24;  // 7 kept bits and the guard bit
-        const uint32_t sticky = (s & 0x00FFFFFFu) ? 1u : 0u;
-        body = (r >> 1) + ((r & 1u) & (sticky | ((r >> 1) & 1u)));
-    }
-    return neg ? ((0u - body) & 0xFFu) : body;
+// int32 quire (units of 2^-12) -> posit<8,0>, nearest, ties to even pattern, clamped to +-minpos / +-maxpos.
+// Straight-line code (an epilogue calls it for every output of a tile; branches per call cost more than they save):
+// with k = floor(log2 |value|), kk = k for k >= 0 and -k-1 otherwise, an arithmetic right shift by kk of "10" followed by
+// the fraction gives kk+1 ones, a zero and the fraction; for negative k the fraction is complemented before and the whole
+// word after the shift, which turns that head into kk+1 zeros and a one.  The eight fraction bits that the shifts can
+// push out are folded into bit 8 first, which always lies below the guard bit and is never pushed out itself.
+PNN_HD uint32_t p8_round_quire(int32_t q) {
+    const uint32_t sm = (uint32_t)(q >> 31);  // all ones for a negative sum
+    const uint32_t mag = ((uint32_t)q ^ sm) - sm;
+    const int lz = clz32(mag);
+    const int k0 = 19 - lz;                              // floor(log2(mag)) - 12
+    const bool beyond = k0 >= 6 || k0 < -6;              // at or past maxpos / below minpos: the end pattern, no fraction
+    const int k = k0 > 6 ? 6 : (k0 < -6 ? -6 : k0);
+    const uint32_t frac = beyond ? 0u : ((mag << (lz & 31)) << 1);  // fraction bits at the top, leading one gone
+    const uint32_t sg = (uint32_t)(k >> 31);
+    const uint32_t kk = (uint32_t)k ^ sg;
+    const uint32_t jam = (frac & 0xFFu) ? 0x100u : 0u;
+    const uint32_t w = 0x80000000u | (((frac | jam) ^ sg) >> 2);
+    const uint32_t x = (uint32_t)((int32_t)w >> kk) ^ sg;  // 7 kept bits, the guard bit, sticky bits
+    const uint32_t body = (x + 0x00FFFFFFu + ((x >> 25) & 1u)) >> 25;
+    const uint32_t pat = ((body ^ sm) - sm) & 0xFFu;
+    return q == 0 ? 0u : pat;
 }
 
 // PACKED: A and B point at operands rewritten by p8_pack_kernel (lda, ldb: their padded row counts),

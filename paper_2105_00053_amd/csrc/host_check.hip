@@ -342,6 +342,12 @@ int hostcheck_axpy_f64(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t
     return 1;
 }
 
+// the epilogue rounding of the posit<8,0> kernels: 32-bit quire (units of minpos^2 = 2^-12) -> pattern
+int hostcheck_p8_round_quire(int64_t n, const int32_t* in, uint32_t* out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = p8_round_quire(in[i]);
+    return 0;
+}
+
 // posit<16,1> -> posit<8,0> through the step table of the narrowing kernel
 int hostcheck_narrow_step(int64_t n, const uint64_t* in, uint64_t* out) {
     for (int64_t i = 0; i < n; ++i) {

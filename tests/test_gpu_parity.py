@@ -192,6 +192,35 @@ def test_gemm_random_patterns(fin, fout, M, N, K, ta, tb, use_bias, nar):
     _assert_equal(to_np(got, fout), want, "gemm %s->%s %dx%dx%d" % (fin, fout, M, N, K))
 
 
+@pytest.mark.parametrize("M,N,K,ta,tb,fout,use_bias", [
+    (65, 65, 128, 0, 0, "p8", 0), (130, 257, 1000, 0, 1, "p16", 1), (200, 150, 4096, 1, 0, "p8", 1), (129, 300, 555, 1, 1, "p8", 0),
+    (256, 192, 2048, 0, 0, "p32", 1), (70, 2000, 130, 0, 0, "p8", 0), (1000, 66, 129, 1, 0, "p8", 1), (384, 320, 1056, 0, 1, "p8", 0),
+    (1280, 1152, 160, 1, 1, "p16", 0), (300, 260, 9000, 0, 0, "p8", 1)])
+def test_p8_gemm_reduction_cut_inside_the_workgroup(M, N, K, ta, tb, fout, use_bias):
+    """posit<8,0> products with too few 128 x 128 tiles to fill the chip: 64 x 64 tiles, the four waves of a workgroup
+    each take a quarter of the reduction and merge in LDS.  Ragged edges in all three dimensions, quarters that are no
+    whole number of slices (and waves left with nothing: K = 128 .. 160), unaligned pitches (K = 555, 129: byte-wise
+    fetch), the four transposition cases, NaR in both operands near the edges, bias, three output formats."""
+    # a long reduction over few tiles is cut across workgroups as well (workspace + merge kernel)
+    assert (pn.posit_gemm_workspace("p8", fout, ta, tb, M, N, K) > 0) == ((M, N, K) in ((200, 150, 4096), (256, 192, 2048), (300, 260, 9000)))
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    A = rand_patterns(rng, (M, K), "p8", special=0.002, allow_nar=False)
+    B = rand_patterns(rng, (K, N), "p8", special=0.002, allow_nar=False)
+    A[M - 1, K - 1] = 0x80   # last row of C is NaR
+    A[min(M - 1, 70), 0] = 0x80
+    B[0, N - 1] = 0x80       # last column of C is NaR
+    B[K - 1, min(N - 1, 65)] = 0x80
+    bias = rand_patterns(rng, (N,), "p8", allow_nar=False) if use_bias else None
+    if use_bias:
+        bias[1] = 0x80
+    Ain, Bin = (np.ascontiguousarray(A.T) if ta else A), (np.ascontiguousarray(B.T) if tb else B)
+    got = to_np(pn.posit_gemm(to_dev(Ain), to_dev(Bin), "p8", fout, trans_a=ta, trans_b=tb, bias=None if bias is None else to_dev(bias)), fout)
+    want, _ = fast.gemm(Ain, Bin, "p8", fout, trans_a=ta, trans_b=tb, bias=bias)
+    _assert_equal(got, want, "w4 gemm %dx%dx%d" % (M, N, K))
+    nar = 1 << (BITS[fout] - 1)
+    assert (want[M - 1] == nar).all() and (want[:, N - 1] == nar).all()
+
+
 def test_gemm_padded_leading_dimensions_and_k0():
     rng = np.random.default_rng(8)
     M, N, K = 37, 29, 41

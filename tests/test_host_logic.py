@@ -48,6 +48,7 @@ def hc():
     L.hostcheck_axpy_rt.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     L.hostcheck_axpy_f64.argtypes = [ci, ci, ctypes.c_uint32, i64, vp, vp, vp]
     L.hostcheck_narrow_step.argtypes = [i64, vp, vp]
+    L.hostcheck_p8_round_quire.argtypes = [i64, vp, vp]
     L.hostcheck_round_f64.restype = ctypes.c_uint32
     L.hostcheck_round_f64.argtypes = [ci, ctypes.c_double, ci, ci]
     return L
@@ -182,6 +183,31 @@ def test_axpy_through_binary64_with_error_free_sum(hc, fx, fy):
         out = np.zeros(len(big), dtype=np.uint64)
         hc.hostcheck_axpy_f64(CODE[fx], CODE[fy], alpha, len(big), _p(xt), _p(big), _p(out))
         assert np.array_equal(out, fast.axpy(alpha, xt, big, fx, fy).astype(np.uint64)), (tiny_x, alpha)
+
+
+def test_posit8_quire_rounding_of_the_kernel_epilogues(hc):
+    """p8_round_quire (32-bit quire in units of 2^-12 -> posit<8,0>) against the oracle's rounding of the exact rational:
+    every sum up to 2^14 units, every tie between neighbouring patterns and its two neighbours, powers of two and their
+    neighbours, the extremes of the 32-bit range, random sums; both signs."""
+    f = po.P8
+    wide = po.PositFormat(9, 0, 0)
+    vals = set(range(0, 1 << 14))
+    for p in range(1, 256):   # values of posit<9,0>: the patterns of posit<8,0> and the ties between them
+        v = po.decode(p, wide) * 4096
+        if v.denominator == 1:
+            vals.update((int(v) - 1, int(v), int(v) + 1))
+    for e in range(31):
+        vals.update(((1 << e) - 1, 1 << e, (1 << e) + 1, 3 << max(e - 1, 0)))
+    rng = np.random.default_rng(8)
+    vals.update(int(v) for v in rng.integers(0, 1 << 31, 20000))
+    vals.update(int(v) >> int(s) for v, s in zip(rng.integers(0, 1 << 31, 20000), rng.integers(0, 31, 20000)))
+    vals.update(((1 << 31) - 1, (1 << 31) - 2))
+    qs = sorted(v for v in vals if 0 <= v < (1 << 31))
+    q = np.array(qs + [-v for v in qs] + [-(1 << 31)], dtype=np.int64).astype(np.int32)
+    out = np.zeros(len(q), dtype=np.uint32)
+    assert hc.hostcheck_p8_round_quire(len(q), _p(q), _p(out)) == 0
+    for qi, got in zip(q.tolist(), out.tolist()):
+        assert got == po.round_to_posit(Fraction(qi, 4096), f), qi
 
 
 def test_narrowing_step_table_posit16_to_posit8_all_patterns(hc):

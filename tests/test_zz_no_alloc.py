@@ -53,12 +53,13 @@ def _case(seed, fin, fout, M, N, K, ta, tb, use_bias, check_oracle):
 
 
 def test_static_scratch_matches_posit_gemm_on_successive_calls():
-    # posit<8,0>, split reduction (partial quires + NaR flags in the scratch array); then a smaller split problem
-    _case(1, "p8", "p16", 288, 96, 16384, 1, 0, True, True)
-    _case(2, "p8", "p8", 200, 150, 4096, 0, 0, False, True)
+    # posit<8,0>, reduction split across workgroups (partial quires + NaR flags in the scratch array: the shapes with at
+    # most 64 rows that the gather kernel takes); then a smaller split problem
+    _case(1, "p8", "p16", 32, 288, 65536, 1, 0, True, True)
+    _case(2, "p8", "p8", 48, 200, 8192, 0, 0, False, True)
     # the packed-operand path (operands, flags and nothing else in the array) followed by a split product
     _case(3, "p8", "p8", 4000, 4096, 1100, 0, 1, True, False)
-    _case(4, "p8", "p8", 1024, 1024, 1024, 0, 0, False, True)
+    _case(4, "p8", "p8", 64, 512, 16384, 0, 0, False, True)
     # multi-limb quires: posit<16,1>, posit<32,2>, posit(8,2) -> posit(12,2); each followed by a smaller one
     _case(5, "p16", "p16", 96, 160, 4096, 1, 0, True, True)
     _case(6, "p16", "p8", 40, 50, 2048, 0, 1, False, True)
