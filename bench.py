@@ -93,6 +93,36 @@ def elementwise_measurements(torch, pn, n=1 << 27):
     return out
 
 
+def copy_calibration(torch):
+    """One 256 MiB device-to-device copy: the kernel of known size that scales rocprofv3's FETCH_SIZE / WRITE_SIZE."""
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    torch.cuda.synchronize()
+    dst.copy_(src)  # reads 256 MiB, writes 256 MiB
+    torch.cuda.synchronize()
+    del src, dst
+
+
+def issue_rates():
+    """Measured instruction-issue rates of this GPU (paper_2105_00053_amd/csrc/issue_rates.hip): the practical ceilings
+    the kernels' lane-operation counts are priced against, beside the nominal 256 CU x 64 lanes x 2.4 GHz = 39.3 T/s."""
+    import ctypes
+    path = os.path.join(ROOT, "paper_2105_00053_amd", "libpositnn_rates.so")
+    if not os.path.exists(path):
+        raise RuntimeError("libpositnn_rates.so is not built: run python -m paper_2105_00053_amd.build")
+    lib = ctypes.CDLL(path)
+    rates = (ctypes.c_double * 4)()
+    info = (ctypes.c_int * 2)()
+    if lib.pnn_issue_rates(rates, info) != 0:
+        raise RuntimeError("pnn_issue_rates failed")
+    nominal = info[0] * 64 * 2.4e9
+    return {"compute_units": info[0], "clock_kHz_reported": info[1], "nominal_lane_ops_per_s_T": round(nominal / 1e12, 2),
+            "dot2_i16_lane_ops_per_s_T": round(rates[0] / 1e12, 2), "dot2_i16_TMAC_per_s": round(2 * rates[0] / 1e12, 2),
+            "fma_f64_lane_ops_per_s_T": round(rates[1] / 1e12, 2), "int32_lane_ops_per_s_T": round(rates[2] / 1e12, 2),
+            "lds_read_b128_TB_per_s": round(rates[3] / 1e12, 2)}
+
+
 def extra_measurements(torch, pn, workloads):
     """The other benchmark configs, for the record (not part of `value`): GEMM kernels of configs 2 and 5
     and whole training steps of configs 3 and 4 (device-resident, see paper_2105_00053_amd/train_step.py)."""
@@ -134,6 +164,10 @@ def main():
     ap.add_argument("--cpu-rows", type=int, default=0, help="rows of C the CPU baseline computes (0 = auto)")
     ap.add_argument("--sustained-steps", type=int, default=200, help="steps of the longer run reported as `sustained` (0 = skip)")
     ap.add_argument("--no-extra", action="store_true", help="skip the secondary measurements (other benchmark configs)")
+    ap.add_argument("--only-elementwise", action="store_true",
+                    help="run only the bandwidth-bound entry points at 2^27 elements and print their rates (the command the elementwise profiles use)")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="run only the instruction-issue microbenchmarks (csrc/issue_rates.hip) and print the measured rates")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one 256 MiB device copy before timing (scale reference for rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -153,6 +187,14 @@ def main():
         sys.exit(3)
     pn.load()
     torch.cuda.set_device(0)
+    if args.issue_rates:
+        print(json.dumps(issue_rates()))
+        return
+    if args.only_elementwise:
+        if args.copy_calibration:
+            copy_calibration(torch)
+        print(json.dumps(elementwise_measurements(torch, pn)))
+        return
     S = args.size
     A32, B32 = workloads.gemm_operands(5, S)
     Af = torch.from_numpy(A32).cuda()
@@ -181,13 +223,7 @@ def main():
         pn.posit_axpy(lr_bits, C16, W, "p16", "p16", fcopy="p8", y_copy=W8)
 
     if args.copy_calibration:
-        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
-        src.fill_(1)
-        torch.cuda.synchronize()
-        dst.copy_(src)  # reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration(torch)
 
     for _ in range(args.warmup):
         step()
@@ -240,6 +276,7 @@ def main():
             "kernel_ms": round(gemm_ms, 4),
             "algorithmic_bytes": 3 * S * S,
             "traffic": GEMM_4096_TRAFFIC_BYTES if S == 4096 else None,
+            "traffic_source": "stored constant from profiles/p8_gemm_4096_hbm_traffic.md (two rocprofv3 --pmc runs), not measured by this run",
         },
     }
 

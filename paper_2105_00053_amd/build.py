@@ -16,6 +16,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libpositnn_hip.so")
 HOSTCHECK = os.path.join(HERE, "libpositnn_hostcheck.so")
+RATES = os.path.join(HERE, "libpositnn_rates.so")  # instruction-issue microbenchmarks for bench.py --issue-rates
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 ARCH = "gfx950"
 
@@ -52,8 +53,9 @@ def build(verbose=False):
     # host-only build of the scalar functions, for CPU unit tests
     _run([HIPCC, "-O2", "-std=c++17", "-fPIC", "-shared", "--cuda-host-only", "-x", "hip"] + FP_FLAGS + [
           "-Wno-unused-command-line-argument", os.path.join(CSRC, "host_check.hip"), "-o", HOSTCHECK])
+    _run([HIPCC] + DEVICE_FLAGS + ["-shared", os.path.join(CSRC, "issue_rates.hip"), "-o", RATES])
     if verbose:
-        print("built", LIB, "and", HOSTCHECK)
+        print("built", LIB, ",", HOSTCHECK, "and", RATES)
     return LIB
 
 
