@@ -7,6 +7,8 @@
 #include "conv_p8.h"
 #include "gemm_p8_w4.h"
 #include "conv_b8.h"
+#include "gemm_bucket_pre.h"
+#include "gemm_p16_window.h"
 
 namespace pnn {
 
@@ -47,6 +49,8 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
     }
     // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
     if ((F::N == 8 && F::ES == 0) && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
+    if (F::N == 16 && pw_fits(M, N, K)) return pw_plan(M, N, K).gemm;          // posit<16,1>: operands decoded once, two buckets + outlier bitmaps
+    if (bucket_pre_fits<F>(M, N, K)) return bucket_pre_plan<F>(M, N, K).gemm;  // operands decoded once into the workspace
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
 }
 
@@ -102,6 +106,13 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
             RowMajorOut mo{ldc};
             return hip_status(b8_conv_launch<F>(st, p, (const uint8_t*)bias, C, fout, ws, plan, mo));
         }
+    }
+    if constexpr (F::N == 16) {
+        if (pw_fits(M, N, K)) return hip_status(launch_pw_gemm(st, transA, transB, A, lda, B, ldb, bias, C, ldc, fout, M, N, K, ws));
+    }
+    if constexpr (bucket_pre_format<F>()) {
+        if (bucket_pre_fits<F>(M, N, K))
+            return hip_status(launch_bucket_pre_gemm<F>(st, transA, transB, A, lda, B, ldb, bias, C, ldc, fout, M, N, K, ws));
     }
     // op(A)[i,k]: k contiguous unless transA.  op(B)[k,j] seen as rows j: k contiguous only when transB.
     if (!transA && !transB) {

@@ -221,6 +221,65 @@ def test_p8_gemm_reduction_cut_inside_the_workgroup(M, N, K, ta, tb, fout, use_b
     assert (want[M - 1] == nar).all() and (want[:, N - 1] == nar).all()
 
 
+@pytest.mark.parametrize("fin,fout,M,N,K,ta,tb,use_bias", [
+    ("p16", "p16", 96, 96, 64, 0, 0, 0), ("p16", "p8", 100, 130, 200, 1, 0, 1), ("p16", "p16", 200, 150, 1100, 0, 1, 1),
+    ("p16", "p32", 129, 257, 333, 1, 1, 0), ("p16", "p16", 128, 128, 2048, 0, 0, 1), ("p16", "p16", 97, 99, 70000, 0, 0, 0),
+    ("p16", "p16", 1700, 1600, 130, 0, 0, 1), ("p12_2", "p12_2", 130, 140, 520, 0, 1, 1), ("p12_2", "p8_2", 1700, 1600, 90, 1, 0, 0),
+    ("p10_1", "p10_1", 300, 200, 777, 1, 1, 1), ("p10_2", "p12_2", 111, 222, 4096, 0, 0, 0), ("p12_1", "p12_1", 2000, 1400, 100, 0, 0, 0),
+    ("p10_2", "p10_2", 900, 900, 2500, 0, 0, 0)])  # enough tiles, but more products per output than the buckets' guard bits allow: cut anyway
+def test_bucket_formats_gemm_with_operands_decoded_once(fin, fout, M, N, K, ta, tb, use_bias):
+    """posit<16,1> and the 10- / 12-bit formats beyond 96 x 96 outputs: both operands are decoded into the workspace
+    first (so the call always needs one), 32 x 32 or 64 x 64 tiles, the reduction cut across workgroups for few tiles
+    or beyond 2^16 products per output.  Ragged edges in all three dimensions, the four transposition cases, NaR in
+    both operands at the edges, bias with a NaR entry, several output formats; random patterns over the whole
+    regime range, so sums span all buckets."""
+    assert pn.posit_gemm_workspace(fin, fout, ta, tb, M, N, K) >= 8 * K * (M + N)
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    A = rand_patterns(rng, (M, K), fin, special=0.002, allow_nar=False)
+    B = rand_patterns(rng, (K, N), fin, special=0.002, allow_nar=False)
+    nar_in = 1 << (BITS[fin] - 1)
+    A[M - 1, K - 1] = nar_in   # last row of C is NaR
+    A[min(M - 1, 70), 0] = nar_in
+    B[0, N - 1] = nar_in       # last column of C is NaR
+    B[K - 1, min(N - 1, 65)] = nar_in
+    bias = rand_patterns(rng, (N,), fin, allow_nar=False) if use_bias else None
+    if use_bias:
+        bias[1] = nar_in
+    Ain, Bin = (np.ascontiguousarray(A.T) if ta else A), (np.ascontiguousarray(B.T) if tb else B)
+    got = to_np(pn.posit_gemm(to_dev(Ain), to_dev(Bin), fin, fout, trans_a=ta, trans_b=tb, bias=None if bias is None else to_dev(bias)), fout)
+    want, _ = fast.gemm(Ain, Bin, fin, fout, trans_a=ta, trans_b=tb, bias=bias)
+    _assert_equal(got, want, "decoded-once gemm %s %dx%dx%d" % (fin, M, N, K))
+    nar = 1 << (BITS[fout] - 1)
+    assert (want[M - 1] == nar).all() and (want[:, N - 1] == nar).all() and (want[70, :N - 1] == nar).all()
+    assert (want[:M - 1, :N - 1] != nar).sum() > (M - 3) * (N - 3)
+
+
+@pytest.mark.parametrize("share,M,N,K,ta,tb", [(0.0, 130, 140, 1300, 0, 0), (0.3, 130, 140, 1300, 0, 1), (1.0, 100, 97, 300, 1, 0),
+                                               (0.05, 200, 300, 2500, 1, 1), (0.5, 1100, 1050, 96, 0, 0)])
+def test_p16_gemm_long_regime_operands_take_the_integer_correction(share, M, N, K, ta, tb):
+    """posit<16,1> operands outside the band the two fp64 buckets cover (|x| below about 2^-23 or above 2^18) are
+    multiplied in integer arithmetic by the owner of each output.  A given share of both operands is replaced by
+    such values (either sign, down to minpos and up to maxpos), from none to all of them; where an outlier of A
+    meets an outlier of B the product must be counted once."""
+    rng = np.random.default_rng(int(share * 100) + K)
+    A = fast.round_from_float(rng.standard_normal((M, K)).astype(np.float32), "p16")
+    B = fast.round_from_float((rng.standard_normal((K, N)) * 0.05).astype(np.float32), "p16")
+    for X in (A, B):
+        pick = rng.random(X.shape) < share
+        n = int(pick.sum())
+        tiny = rng.integers(1, 0x0040, n)          # minpos .. about 2^-22
+        huge = rng.integers(0x7F00, 0x8000, n)     # about 2^14 .. maxpos
+        mag = np.where(rng.random(n) < 0.5, tiny, huge)
+        pat = np.where(rng.random(n) < 0.5, mag, (0x10000 - mag) & 0xFFFF)
+        X[pick] = pat.astype(np.uint16)
+    A[3, 5] = 0x8000  # NaR row
+    Ain, Bin = (np.ascontiguousarray(A.T) if ta else A), (np.ascontiguousarray(B.T) if tb else B)
+    got = to_np(pn.posit_gemm(to_dev(Ain), to_dev(Bin), "p16", "p16", trans_a=ta, trans_b=tb), "p16")
+    want, _ = fast.gemm(Ain, Bin, "p16", "p16", trans_a=ta, trans_b=tb)
+    _assert_equal(got, want, "p16 gemm, outlier share %.2f" % share)
+    assert (want[3] == 0x8000).all() and (want[4] != 0x8000).all()
+
+
 def test_gemm_padded_leading_dimensions_and_k0():
     rng = np.random.default_rng(8)
     M, N, K = 37, 29, 41
