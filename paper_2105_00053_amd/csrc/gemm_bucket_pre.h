@@ -11,9 +11,9 @@
 // reduction cut over gridDim.z when the tiles alone would not fill the chip (partial quires through the
 // workspace, merged and rounded once by split_merge_kernel).
 //
-// The buckets of an output are emptied into quire limbs once, after the loop: a slice of the reduction given to
-// one workgroup never exceeds 2^G products (G = the guard bits of BucketArith<F>), the planner cuts longer
-// reductions.
+// The buckets of an output are emptied into quire limbs after the loop; where a workgroup's part of the reduction
+// exceeds 2^G products (G = the guard bits of BucketArith<F>) the 32 x 32 kernel is instantiated with the limbs
+// held in registers all along and empties the buckets into them every 2^G products (FLUSH).
 #pragma once
 
 #include "quire_gemm.h"
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void bucket_predecode_kernel(const typename St
 // C tile (16 TM x 16 TN) = sum over k in [z kq, (z + 1) kq) of Ap[k][m] * Bp[k][n], exactly, in the buckets of
 // BucketArith<F>.  Ap / Bp: decoded operands, pitches Mp / Np (multiples of the tile), kq a multiple of BP_KT,
 // every (k, m) and (k, n) the grid touches is inside the padded arrays.
-template <class F, int TM, int TN>
+template <class F, int TM, int TN, bool FLUSH>
 __global__ __launch_bounds__(BP_THREADS) void bucket_pre_gemm_kernel(const double* __restrict__ Ap, const double* __restrict__ Bp, int64_t Mp,
                                                                      int64_t Np, int64_t kq,
                                                                      const typename Storage<F::N>::T* __restrict__ bias,
@@ -107,6 +107,17 @@ __global__ __launch_bounds__(BP_THREADS) void bucket_pre_gemm_kernel(const doubl
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) BA::clear(bk[i][j]);
+
+    uint32_t acc[FLUSH ? TM : 1][FLUSH ? TN : 1][L];  // FLUSH: the limbs the buckets are emptied into along the way
+    if constexpr (FLUSH) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int l = 0; l < L; ++l) acc[i][j][l] = 0;
+    }
+    int since_flush = 0;  // products in the buckets
 
     double2 ra[CA], rb[CB];
     auto fetch = [&](int64_t k0) {
@@ -171,6 +182,16 @@ __global__ __launch_bounds__(BP_THREADS) void bucket_pre_gemm_kernel(const doubl
 #pragma unroll
                 for (int j = 0; j < TN; ++j) BA::mac(bk[i][j], a[i], b[j]);
         }
+        if constexpr (FLUSH) {
+            since_flush += KT;
+            if (since_flush + KT > (1 << BA::G)) {  // the next slice would exceed the guard bits
+                since_flush = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) BA::template flush<L>(acc[i][j], bk[i][j]);
+            }
+        }
         if (more) stage(cur ^ 1);  // the other buffer was last read one barrier ago
         __syncthreads();
     }
@@ -188,7 +209,7 @@ __global__ __launch_bounds__(BP_THREADS) void bucket_pre_gemm_kernel(const doubl
             bool nar = (rowNaR[ty * TM + i] | colNaR[tx * TN + j]) != 0;
             uint32_t q[L];
 #pragma unroll
-            for (int l = 0; l < L; ++l) q[l] = 0;
+            for (int l = 0; l < L; ++l) q[l] = FLUSH ? acc[FLUSH ? i : 0][FLUSH ? j : 0][l] : 0u;
             if (!nar) BA::template flush<L>(q, bk[i][j]);  // a NaR output's buckets hold NaNs: nothing to read off
             if (lim) {
 #pragma unroll
@@ -218,6 +239,7 @@ __global__ __launch_bounds__(BP_THREADS) void bucket_pre_gemm_kernel(const doubl
 struct BucketPrePlan {
     GemmPlan gemm;       // splits, k per split (multiple of BP_KT), workspace bytes in all
     int tile;            // 32 or 64: outputs per tile edge
+    bool flush;          // a workgroup adds more products per output than the buckets' guard bits allow at once
     int64_t Mp, Np, Kp;  // padded extents of the decoded operands
     size_t b_off, split_off;  // byte offsets inside the workspace (decoded A at 0)
 };
@@ -240,13 +262,12 @@ BucketPrePlan bucket_pre_plan(int64_t M, int64_t N, int64_t K) {
         if (splits > K / 256) splits = K / 256;
         if (splits > 64) splits = 64;
     }
-    const int64_t max_k = (int64_t)1 << BucketArith<F>::G;  // products one output may add before its buckets must be emptied
-    if ((K + splits - 1) / splits > max_k) splits = (K + max_k - 1) / max_k;
     if (splits < 1) splits = 1;
     int64_t kq = (K + splits - 1) / splits;
     kq = (kq + BP_KT - 1) / BP_KT * BP_KT;
-    if (kq > max_k) kq = max_k / BP_KT * BP_KT;
     splits = (K + kq - 1) / kq;
+    p.flush = kq > ((int64_t)1 << BucketArith<F>::G);
+    if (p.flush) p.tile = 32;  // 4 outputs per thread leave room for their limbs
     p.gemm.splits = (int)splits;
     p.gemm.k_per_split = kq;
     p.Kp = splits * kq;
@@ -286,11 +307,14 @@ hipError_t launch_bucket_pre_gemm(hipStream_t st, int transA, int transB, const 
     }
     const int64_t tiles_m = (M + p.tile - 1) / p.tile, tiles_n = (N + p.tile - 1) / p.tile;
     const dim3 grid((unsigned)(tiles_m * tiles_n), 1, (unsigned)p.gemm.splits);
-    if (p.tile == 64)
-        hipLaunchKernelGGL((bucket_pre_gemm_kernel<F, 4, 4>), grid, dim3(BP_THREADS), 0, st, Ap, Bp, p.Mp, p.Np, p.gemm.k_per_split,
+    if (p.flush)
+        hipLaunchKernelGGL((bucket_pre_gemm_kernel<F, 2, 2, true>), grid, dim3(BP_THREADS), 0, st, Ap, Bp, p.Mp, p.Np, p.gemm.k_per_split,
+                           (const T*)bias, C, ldc, fout, M, N, ws, (int)tiles_n);
+    else if (p.tile == 64)
+        hipLaunchKernelGGL((bucket_pre_gemm_kernel<F, 4, 4, false>), grid, dim3(BP_THREADS), 0, st, Ap, Bp, p.Mp, p.Np, p.gemm.k_per_split,
                            (const T*)bias, C, ldc, fout, M, N, ws, (int)tiles_n);
     else
-        hipLaunchKernelGGL((bucket_pre_gemm_kernel<F, 2, 2>), grid, dim3(BP_THREADS), 0, st, Ap, Bp, p.Mp, p.Np, p.gemm.k_per_split,
+        hipLaunchKernelGGL((bucket_pre_gemm_kernel<F, 2, 2, false>), grid, dim3(BP_THREADS), 0, st, Ap, Bp, p.Mp, p.Np, p.gemm.k_per_split,
                            (const T*)bias, C, ldc, fout, M, N, ws, (int)tiles_n);
     PNN_CHECK_LAUNCH();
     if (p.gemm.splits > 1) {
