@@ -4,6 +4,7 @@
 #include "elementwise_fast.h"
 #include "quire_arith.h"
 #include "conv_p8.h"
+#include "p16_window_arith.h"
 #include "noquire_arith.h"
 #include "loss_ops.h"
 
@@ -340,6 +341,37 @@ int hostcheck_axpy_f64(int fx, int fy, uint32_t alpha, int64_t n, const uint64_t
     CASE(P16, P16, 1, 1) CASE(P8, P16, 0, 1) CASE(P12_2, P12_2, 8, 8) CASE(P8_2, P12_2, 4, 8) CASE(P8, P8, 0, 0) CASE(P10_1, P12_1, 5, 7)
 #undef CASE
     return 1;
+}
+
+// The two-bucket dot product of the posit<16,1> GEMM on the host: main operands through pw_mac (at most PW_MAXK products
+// between two flushes), products with an outlier operand through the integer multiply-accumulate, as the kernel's
+// correction phase takes them; q receives the four quire limbs.  outliers[0..1] count the outliers of a and b.
+int hostcheck_pw_dot(int64_t n, const uint32_t* a, const uint32_t* b, uint32_t* q, int* outliers) {
+    typedef Arith<P16> AI;
+    uint32_t acc[4] = {0, 0, 0, 0};
+    double hi = 0.0, lo = 0.0;
+    int64_t since = 0;
+    outliers[0] = outliers[1] = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        double va, vb;
+        const bool oa = pw_classify(a[i], va), ob = pw_classify(b[i], vb);
+        outliers[0] += oa;
+        outliers[1] += ob;
+        if (oa || ob) {
+            if (a[i] != P16::NAR && b[i] != P16::NAR) AI::mac(acc, AI::stage(a[i]), AI::stage(b[i]));
+            continue;
+        }
+        if (va != va || vb != vb) continue;  // NaR: the kernel decides those outputs by flags
+        pw_mac(hi, lo, va, vb);
+        if (++since == PW_MAXK) {
+            pw_flush(acc, hi, lo);
+            hi = lo = 0.0;
+            since = 0;
+        }
+    }
+    pw_flush(acc, hi, lo);
+    for (int l = 0; l < 4; ++l) q[l] = acc[l];
+    return 0;
 }
 
 // the epilogue rounding of the posit<8,0> kernels: 32-bit quire (units of minpos^2 = 2^-12) -> pattern

@@ -210,6 +210,82 @@ def test_posit8_quire_rounding_of_the_kernel_epilogues(hc):
         assert got == po.round_to_posit(Fraction(qi, 4096), f), qi
 
 
+def _pw_dot(hc, a, b):
+    a = np.ascontiguousarray(a, dtype=np.uint32)
+    b = np.ascontiguousarray(b, dtype=np.uint32)
+    q = np.zeros(4, dtype=np.uint32)
+    outl = np.zeros(2, dtype=np.int32)
+    assert hc.hostcheck_pw_dot(len(a), _p(a), _p(b), _p(q), _p(outl)) == 0
+    got = sum(int(w) << (32 * i) for i, w in enumerate(q))
+    want = sum(po.decode(int(x), po.P16) * po.decode(int(y), po.P16) for x, y in zip(a, b)
+               if int(x) != 0x8000 and int(y) != 0x8000) * (1 << 56)  # quire units: minpos^2 = 2^-56
+    assert want.denominator == 1
+    assert got == int(want) % (1 << 128), (got, int(want))
+    return outl
+
+
+def test_posit16_two_bucket_window_dot_product_at_its_bounds(hc):
+    """The posit<16,1> GEMM keeps operands that are multiples of 2^-24 below 2^19 in two fp64 buckets for up to 1024
+    products and takes every other operand through integer arithmetic.  Against exact rationals: the classification
+    itself (every pattern: an operand counts as main exactly when it lies in that band), 1024 and more products of the
+    largest and of the smallest main operands (the guard bits of both buckets filled, either sign), sums that cancel
+    down to one unit, random patterns over the whole range (a few outliers each), and vectors of outliers only."""
+    P = po.P16
+    main = []
+    for p in range(1, 1 << 16):
+        if p == 0x8000:
+            continue
+        v = abs(po.decode(p, P)) * (1 << 28)        # scaled value, an integer
+        assert v.denominator == 1
+        iv = int(v)
+        # the kernel's rule looks at the weight of the pattern's last fraction bit (set or not), which depends on the
+        # regime only: 15 body bits = regime run + its terminating bit + one exponent bit + fraction
+        mag = p if p < 0x8000 else 0x10000 - p
+        body = format(mag, "015b")
+        run = len(body) - len(body.lstrip(body[0]))
+        nf = max(0, 15 - run - 1 - 1)
+        last_bit_weight = (iv.bit_length() - 1) - nf
+        is_main = last_bit_weight >= 4 and iv < (1 << 47)
+        if is_main:
+            assert iv % 16 == 0      # what the arithmetic needs: a multiple of 2^4 below 2^47
+            main.append(p)
+    assert len(main) > 0.95 * 65534  # the band covers all but the longest regimes
+    # classification of every pattern through one-element dot products with 1.0 (itself a main operand)
+    allp = np.arange(1, 1 << 16, dtype=np.uint32)
+    allp = allp[allp != 0x8000]
+    for chunk in np.array_split(allp, 64):
+        outl = _pw_dot(hc, chunk, np.full(len(chunk), 0x4000, dtype=np.uint32))
+        assert outl[0] == len(set(chunk.tolist()) - set(main)) and outl[1] == 0
+    pos = [p for p in main if p < 0x8000]
+    big, small = max(pos), min(pos)
+    neg = lambda p: (0x10000 - p) & 0xFFFF
+    rng = np.random.default_rng(16)
+    for n in (1024, 2048, 5000):
+        _pw_dot(hc, [big] * n, [big] * n)                       # hi bucket to its last guard bit
+        _pw_dot(hc, [big] * n, [neg(big)] * n)
+        _pw_dot(hc, [small] * n, [small] * n)
+        # largest rests in the lo bucket: products just below a tie of the cut
+        a = rng.choice(pos, n)
+        b = rng.choice(pos, n)
+        _pw_dot(hc, a, b)
+        # cancellation: every product twice with opposite sign, then one small unit
+        a2 = np.concatenate([a, a, [small]])
+        b2 = np.concatenate([b, [neg(int(x)) for x in b], [small]])
+        perm = rng.permutation(len(a2))
+        _pw_dot(hc, a2[perm], b2[perm])
+    for _ in range(20):
+        n = int(rng.integers(1, 3000))
+        a = rng.integers(0, 1 << 16, n)
+        b = rng.integers(0, 1 << 16, n)
+        _pw_dot(hc, a, b)
+    outliers = [p for p in range(1, 1 << 16) if p != 0x8000 and p not in set(main)]
+    a = rng.choice(outliers, 500)
+    b = rng.choice(outliers, 500)
+    outl = _pw_dot(hc, a, b)
+    assert outl[0] == 500 and outl[1] == 500
+    _pw_dot(hc, a, rng.choice(pos, 500))
+
+
 def test_narrowing_step_table_posit16_to_posit8_all_patterns(hc):
     pats = np.arange(1 << 16, dtype=np.uint64)
     out = np.zeros_like(pats)
