@@ -568,7 +568,15 @@ inline P8ConvTile p8_conv_tile(int M, int N, int K) {
     for (const P8ConvTile& t : P8_CONV_TILES) {
         const int64_t blocks = p8_conv_blocks(t, M, N);
         const double util = ((double)M * N) / ((double)blocks * t.bm * t.bn);  // useful fraction of the tiles
-        const double fill = (can_split || blocks >= 512) ? 1.0 : (double)blocks / 512.0;
+        // workgroups once the reduction is split the way plan_split() will (at least 256 steps per slice, at most 256 slices)
+        int64_t slices = 1;
+        if (can_split && blocks < 1024) {
+            slices = (1024 + blocks - 1) / blocks;
+            if (slices > K / 256) slices = K / 256;
+            if (slices > 256) slices = 256;
+        }
+        const int64_t workgroups = blocks * slices;
+        const double fill = workgroups >= 512 ? 1.0 : (double)workgroups / 512.0;
         // operand reuse: MACs per staged element, relative to the 128 x 128 tile
         const double reuse = (double)(t.bm * t.bn) / (t.bm + t.bn) / 64.0;
         const double score = util * fill * (0.5 + 0.5 * reuse);

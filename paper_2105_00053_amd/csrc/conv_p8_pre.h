@@ -305,24 +305,37 @@ __global__ __launch_bounds__(256, 3) void p8_conv_pre_kernel(P16Operand A, P16Op
             if (t < P8_KT) p16_fill_kpart(A, kpartA[cur], kcolA[cur], k2, kend, t);
             else if (t < 2 * P8_KT) p16_fill_kpart(B, kpartB[cur], kcolB[cur], k2, kend, t - P8_KT);
         }
-#pragma unroll 2
-        for (int kp = 0; kp < P8_KP; ++kp) {
-            uint32_t a[TM], b[TN];
+        // register fragments of k-pair kp + 1 are read from LDS while the dot products of k-pair kp issue
+        uint32_t a[2][TM], b[2][TN];
+        auto load_frag = [&](int kp, int buf) {
 #pragma unroll
             for (int q = 0; q < TM / 4; ++q) {
                 const uint4 v = *reinterpret_cast<const uint4*>(&As[cur][kp][q * (TY * 4) + ty * 4]);
-                a[4 * q] = v.x; a[4 * q + 1] = v.y; a[4 * q + 2] = v.z; a[4 * q + 3] = v.w;
+                a[buf][4 * q] = v.x; a[buf][4 * q + 1] = v.y; a[buf][4 * q + 2] = v.z; a[buf][4 * q + 3] = v.w;
             }
 #pragma unroll
             for (int q = 0; q < TN / 4; ++q) {
                 const uint4 v = *reinterpret_cast<const uint4*>(&Bs[cur][kp][q * (TX * 4) + tx * 4]);
-                b[4 * q] = v.x; b[4 * q + 1] = v.y; b[4 * q + 2] = v.z; b[4 * q + 3] = v.w;
+                b[buf][4 * q] = v.x; b[buf][4 * q + 1] = v.y; b[buf][4 * q + 2] = v.z; b[buf][4 * q + 3] = v.w;
             }
+        };
+        auto multiply = [&](int buf) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = dot2_acc(a[i], b[j], acc[i][j]);
+                for (int j = 0; j < TN; ++j) acc[i][j] = dot2_acc(a[buf][i], b[buf][j], acc[i][j]);
+        };
+        load_frag(0, 0);
+#pragma unroll 1
+        for (int kp = 0; kp < P8_KP - 2; kp += 2) {
+            load_frag(kp + 1, 1);
+            multiply(0);
+            load_frag(kp + 2, 0);
+            multiply(1);
         }
+        load_frag(P8_KP - 1, 1);
+        multiply(0);
+        multiply(1);
         if (more) {
             SA::template stage<BM>(fa, As[cur ^ 1], rowNaR, t, A.rows_run, A.kvalid, kcolA[cur ^ 1]);
             SB::template stage<BN>(fb, Bs[cur ^ 1], colNaR, tb, B.rows_run, B.kvalid, kcolB[cur ^ 1]);

@@ -644,9 +644,11 @@ __global__ __launch_bounds__(256) void p8_small_gemm_kernel(const uint8_t* __res
     }
 }
 
-// Problems the small kernel takes: few outputs and little work.
+// Problems the small kernel takes: little work, and either few outputs or a reduction of at most two slices (the
+// tiled kernels execute their long instruction stream once per workgroup there: instruction fetch, not arithmetic,
+// sets their time -- 19 us for 128 x 2048 x 10 against 4).
 inline bool p8_small_gemm_fits(int64_t M, int64_t N, int64_t K) {
-    return M * N <= 65536 && M * N * K <= ((int64_t)1 << 26) && K >= 1;
+    return M * N * K <= ((int64_t)1 << 26) && K >= 1 && (M * N <= 65536 || (K <= 64 && M * N <= ((int64_t)1 << 21)));
 }
 
 inline hipError_t launch_p8_small_gemm(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B,

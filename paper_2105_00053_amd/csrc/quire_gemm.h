@@ -410,7 +410,8 @@ __global__ __launch_bounds__(GEMM_THREADS) void quire_gemm_kernel(
 // Merge the per-split partial quires, add the bias, round once, store.  A
 // 256-thread workgroup handles 32 consecutive outputs; its 8 thread rows each sum
 // every 8th split (independent loads in flight, 128-byte coalesced rows), then the
-// 8 partial quires of an output are combined through LDS with carry-propagating adds.
+// 8 partial quires of an output are combined through LDS with carry-propagating adds
+// (8 outputs and 32 thread rows where there are few outputs and 200 or more splits).
 // Integer addition modulo 2^(32 L) is associative, so the order does not matter.
 // With few splits one thread per output (ZG = 1) is enough.
 template <class FIN, class Out, int MERGE_ZG>
@@ -653,7 +654,10 @@ hipError_t launch_split_merge(hipStream_t stream, const SplitWs& ws, int splits,
                         const Out& out) {
     typedef typename Storage<FIN::N>::T TI;
     const int64_t total = M * N;
-    if (splits >= 16) {
+    if (splits >= 200 && total <= ((int64_t)1 << 18)) {  // few outputs, very many slices (backward-weight): 32 thread rows share the slices of an output
+        hipLaunchKernelGGL((split_merge_kernel<FIN, Out, 32>), dim3((unsigned)((total + 7) / 8)), dim3(256), 0, stream, ws, splits, M, N,
+                           (const TI*)bias, C, fout, out);
+    } else if (splits >= 16) {
         hipLaunchKernelGGL((split_merge_kernel<FIN, Out, 8>), dim3((unsigned)((total + 31) / 32)), dim3(256), 0, stream, ws, splits, M, N,
                            (const TI*)bias, C, fout, out);
     } else {

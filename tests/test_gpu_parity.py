@@ -178,6 +178,10 @@ GEMM_CASES = [
     ("p32", "p32", 40, 35, 50, 0, 0, 1, 1),
     ("p32", "p16", 33, 31, 40, 1, 1, 0, 0),
     ("p32", "p8", 16, 16, 33, 0, 1, 0, 0),
+    # many outputs, a reduction of at most two slices: the one-thread-per-output kernel, not the tiled ones
+    ("p8", "p8", 128, 2048, 10, 0, 0, 1, 1),
+    ("p8", "p16", 300, 400, 40, 1, 1, 0, 1),
+    ("p8", "p8", 1000, 700, 64, 0, 1, 1, 0),
 ]
 
 
