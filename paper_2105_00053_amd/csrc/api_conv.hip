@@ -38,6 +38,7 @@ hipError_t p8_conv_launch(hipStream_t st, const P8ConvProblem& p, const uint8_t*
     else if (tl.bm == 256 && tl.bn == 64) PNN_LAUNCH_CONV(32, 8, 8, 8);
     else if (tl.bm == 256 && tl.bn == 32) PNN_LAUNCH_CONV(32, 8, 8, 4);
     else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_CONV(16, 16, 8, 4);
+    else if (tl.bm == 128 && tl.bn == 32) PNN_LAUNCH_CONV(32, 8, 4, 4);
     else PNN_LAUNCH_CONV(16, 16, 4, 4);
 #undef PNN_LAUNCH_CONV
     PNN_CHECK_LAUNCH();
@@ -84,6 +85,7 @@ hipError_t p8_pre_launch(hipStream_t st, P8PrePlan pp, const void* srcA, const v
     else if (tl.bm == 256 && tl.bn == 64) PNN_LAUNCH_PRE(32, 8, 8, 8);
     else if (tl.bm == 256 && tl.bn == 32) PNN_LAUNCH_PRE(32, 8, 8, 4);
     else if (tl.bm == 128 && tl.bn == 64) PNN_LAUNCH_PRE(16, 16, 8, 4);
+    else if (tl.bm == 128 && tl.bn == 32) PNN_LAUNCH_PRE(32, 8, 4, 4);
     else PNN_LAUNCH_PRE(16, 16, 4, 4);
 #undef PNN_LAUNCH_PRE
     PNN_CHECK_LAUNCH();

@@ -555,7 +555,7 @@ inline P8ConvProblem p8_problem(int which, const ConvGeom& g, const void* t0, co
 // layers.  Pick the largest tile that still yields >= 512 workgroups (counting the
 // reduction split), else the one with the most workgroups.
 struct P8ConvTile { int bm, bn; };
-static const P8ConvTile P8_CONV_TILES[] = {{128, 128}, {256, 64}, {256, 32}, {128, 64}, {64, 64}};
+static const P8ConvTile P8_CONV_TILES[] = {{128, 128}, {256, 64}, {256, 32}, {128, 64}, {64, 64}, {128, 32}};
 
 inline int64_t p8_conv_blocks(const P8ConvTile& t, int M, int N) {
     return (int64_t)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
@@ -576,7 +576,7 @@ inline P8ConvTile p8_conv_tile(int M, int N, int K) {
             if (slices > 256) slices = 256;
         }
         const int64_t workgroups = blocks * slices;
-        const double fill = workgroups >= 512 ? 1.0 : (double)workgroups / 512.0;
+        const double fill = workgroups >= 1024 ? 1.0 : (double)workgroups / 1024.0;  // four waves per SIMD
         // operand reuse: MACs per staged element, relative to the 128 x 128 tile
         const double reuse = (double)(t.bm * t.bn) / (t.bm + t.bn) / 64.0;
         const double score = util * fill * (0.5 + 0.5 * reuse);

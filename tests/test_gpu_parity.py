@@ -516,6 +516,29 @@ def test_conv_all_three_passes(ci, fin, fout):
     _assert_equal(to_np(db, fout), wdb, "conv dbias")
 
 
+@pytest.mark.parametrize("geom", [dict(N=37, C=8, H=33, W=33, K=16, R=3, S=3, pad_h=1, pad_w=1),
+                                  dict(N=29, C=6, H=30, W=40, K=27, R=3, S=3, pad_h=1, pad_w=1)])
+def test_p8_conv_many_rows_few_channels(geom):
+    """Tens of thousands of output positions and at most 32 channels: the 128 x 32 tile (four waves per SIMD instead of
+    two), ragged in rows and columns, through the byte-gather kernel (width 33) and the pre-decoded one (width 40)."""
+    d = geom
+    rng = np.random.default_rng(d["W"])
+    oh, ow = fast.out_hw(d)
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), "p8", special=0.001)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), "p8", special=0.001, allow_nar=False)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.001)
+    bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", "p8", bias=to_dev(bias))
+    _assert_equal(to_np(y, "p8"), fast.conv2d_fwd(x, w, d, "p8", "p8", bias=bias), "conv fwd")
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", "p8")
+    _assert_equal(to_np(dx, "p8"), fast.conv2d_bwd_data(dy, w, d, "p8", "p8"), "conv bwd_data")
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dy), to_dev(x), desc, "p8", "p16", with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dy, x, d, "p8", "p16", with_bias=True)
+    _assert_equal(to_np(dw, "p16"), wdw, "conv bwd_weight")
+    _assert_equal(to_np(db, "p16"), wdb, "conv bias gradient")
+
+
 @pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p8_2", "p8_2"), ("p8_1", "p12_2"), ("p16", "p16"), ("p12_2", "p8_2"), ("p32", "p32")])
 @pytest.mark.parametrize("geom", ["unit stride (operands rewritten)", "pad beyond the filter (byte gather)", "strided (generic kernel)"])
 def test_conv_bwd_data_nar_weight_reaches_only_its_taps_positions(fin, fout, geom):
