@@ -159,6 +159,15 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
     const int kend = (kbeg + kq < K) ? kbeg + kq : K;
     const int nkt = kbeg < kend ? (kend - kbeg + P8_KT - 1) / P8_KT : 0;
 
+    // eight waves (registers to spare): the first slice's loads are in flight while the decode table is built
+    constexpr bool EARLY_FETCH = WAVES == 8;
+    W4Frag fa0, fb0;
+    auto fetch_first = [&]() {
+        const bool kin = kbeg + P8_KT <= kend;
+        fa0 = w4_fetch<A_KFAST>(A, lda, M, m0, kbeg, kend, lane, (m0 + W4_T <= M) && a_aligned && kin);
+        fb0 = w4_fetch<B_KFAST>(B, ldb, N, n0, kbeg, kend, lane, (n0 + W4_T <= N) && b_aligned && kin);
+    };
+    if (EARLY_FETCH && nkt > 0) fetch_first();
     if (t < 256) tab[t] = (uint16_t)Arith<P8>::stage((uint32_t)t);
     rowNaR[w][lane] = 0;
     colNaR[w][lane] = 0;
@@ -176,11 +185,9 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
 
     __syncthreads();  // table and flags ready
     if (nkt > 0) {
-        const bool kin = kbeg + P8_KT <= kend;
-        const W4Frag fa = w4_fetch<A_KFAST>(A, lda, M, m0, kbeg, kend, lane, a_rows_in && kin);
-        const W4Frag fb = w4_fetch<B_KFAST>(B, ldb, N, n0, kbeg, kend, lane, b_rows_in && kin);
-        w4_stage<A_KFAST>(fa, As, tab, rowNaR[w], lane);
-        w4_stage<B_KFAST>(fb, Bs, tab, colNaR[w], lane);
+        if (!EARLY_FETCH) fetch_first();
+        w4_stage<A_KFAST>(fa0, As, tab, rowNaR[w], lane);
+        w4_stage<B_KFAST>(fb0, Bs, tab, colNaR[w], lane);
     }
     __builtin_amdgcn_wave_barrier();
     for (int kt = 0; kt < nkt; ++kt) {
@@ -221,16 +228,54 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
     // after the barriers of the reduction below)
     if (t < W4_T) rowNaR[0][t] = any_flag(rowNaR, t);
     else if (t < 2 * W4_T) colNaR[0][t - W4_T] = any_flag(colNaR, t - W4_T);
-    if constexpr (WAVES == 8) {          // eight partial tiles -> four: wave w + 4 hands its registers to wave w
-        if (w >= 4) {
-            uint32_t* dst = red + (w - 4) * 4096 + lane;
+    // In the end wave w owns the registers i = w * RPW .. w * RPW + RPW - 1 of every lane's 8 x 8 block, i.e. the rows
+    // (i / 4) * 32 + ty * 4 + i % 4 of the tile: one row per wave with eight waves, two with four.
+    constexpr int RPW = 8 / WAVES;
+    int32_t fin[RPW][8];
+    auto row_of = [&](int ii) { const int i = w * RPW + ii; return (i >> 2) * 32 + ty * 4 + (i & 3); };
+    if constexpr (WAVES == 8) {
+        // Eight partial tiles, eight owners: in round r the waves hand their registers of rows 4r .. 4r + 3 to the
+        // owners of those rows (slot (owner, writer): 8 registers x 64 lanes as two 16-byte words per lane; 28 slots of
+        // 2 KB), and each owner adds the seven slots meant for it to its own registers.
+#pragma unroll
+        for (int r = 0; r < 2; ++r) {
+            if (r) __syncthreads();  // the owners of round 0 have read their slots
+#pragma unroll
+            for (int o = 0; o < 4; ++o) {
+                const int i = 4 * r + o;
+                if (w == i) continue;  // uniform over the wave
+                const int wr = w < i ? w : w - 1;
+                uint4* dst = reinterpret_cast<uint4*>(red + (o * 7 + wr) * 512) + lane;
+                dst[0] = make_uint4((uint32_t)acc[i][0], (uint32_t)acc[i][1], (uint32_t)acc[i][2], (uint32_t)acc[i][3]);
+                dst[64] = make_uint4((uint32_t)acc[i][4], (uint32_t)acc[i][5], (uint32_t)acc[i][6], (uint32_t)acc[i][7]);
+            }
+            __syncthreads();
+            if ((w >> 2) != r) continue;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                if (i != w) continue;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) fin[0][j] = acc[i][j];
+            }
+#pragma unroll
+            for (int wr = 0; wr < 7; ++wr) {
+                const uint4* src = reinterpret_cast<const uint4*>(red + ((w & 3) * 7 + wr) * 512) + lane;
+                const uint4 v0 = src[0], v1 = src[64];
+                fin[0][0] += (int32_t)v0.x; fin[0][1] += (int32_t)v0.y; fin[0][2] += (int32_t)v0.z; fin[0][3] += (int32_t)v0.w;
+                fin[0][4] += (int32_t)v1.x; fin[0][5] += (int32_t)v1.y; fin[0][6] += (int32_t)v1.z; fin[0][7] += (int32_t)v1.w;
+            }
+        }
+    } else {
+        // four partial tiles -> one: waves 2, 3 hand theirs to waves 0, 1, which then spread the quarters
+        if (w >= 2 && w < 4) {
+            uint32_t* dst = red + (w - 2) * 4096 + lane;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
 #pragma unroll
                 for (int j = 0; j < 8; ++j) dst[(i * 8 + j) * 64] = (uint32_t)acc[i][j];
         }
         __syncthreads();
-        if (w < 4) {
+        if (w < 2) {
             const uint32_t* src = red + w * 4096 + lane;
 #pragma unroll
             for (int i = 0; i < 8; ++i)
@@ -238,65 +283,46 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
                 for (int j = 0; j < 8; ++j) acc[i][j] += (int32_t)src[(i * 8 + j) * 64];
         }
         __syncthreads();
-    }
-    if (w >= 2 && w < 4) {
-        uint32_t* dst = red + (w - 2) * 4096 + lane;
+        // wave 0 parks the quarters 1, 2, 3 of its sum in slots 0, 1, 2 of region X; wave 1 the quarters 0, 2, 3 of its sum
+        // in slots 0, 1, 2 of region Y (a slot: 16 registers x 64 lanes)
+        uint32_t* X = red;
+        uint32_t* Y = red + 3 * 1024;
+        if (w < 2) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
+            for (int qq = 0; qq < 4; ++qq) {
+                if (qq == w) continue;  // own quarter stays in registers
+                const int slot = (w == 0) ? qq - 1 : (qq == 0 ? 0 : qq - 1);
+                uint32_t* dst = (w == 0 ? X : Y) + slot * 1024 + lane;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) dst[(i * 8 + j) * 64] = (uint32_t)acc[i][j];
-    }
-    __syncthreads();
-    if (w < 2) {
-        const uint32_t* src = red + w * 4096 + lane;
+                for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) acc[i][j] += (int32_t)src[(i * 8 + j) * 64];
-    }
-    __syncthreads();
-    // wave 0 parks the quarters 1, 2, 3 of its sum in slots 0, 1, 2 of region X; wave 1 the quarters 0, 2, 3 of its sum
-    // in slots 0, 1, 2 of region Y (a slot: 16 registers x 64 lanes)
-    uint32_t* X = red;
-    uint32_t* Y = red + 3 * 1024;
-    if (w < 2) {
-#pragma unroll
-        for (int qq = 0; qq < 4; ++qq) {
-            if (qq == w) continue;  // own quarter stays in registers
-            const int slot = (w == 0) ? qq - 1 : (qq == 0 ? 0 : qq - 1);
-            uint32_t* dst = (w == 0 ? X : Y) + slot * 1024 + lane;
+                    for (int j = 0; j < 8; ++j) dst[(ii * 8 + j) * 64] = (uint32_t)acc[2 * qq + ii][j];
+            }
+        }
+        __syncthreads();
+        {
+            const int xs = w - 1;                  // slot of quarter w in X (w >= 1)
+            const int ys = w == 0 ? 0 : w - 1;     // slot of quarter w in Y (w != 1)
 #pragma unroll
             for (int ii = 0; ii < 2; ++ii)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) dst[(ii * 8 + j) * 64] = (uint32_t)acc[2 * qq + ii][j];
+                for (int j = 0; j < 8; ++j) {
+                    const int at = (ii * 8 + j) * 64 + lane;
+                    int32_t v;
+                    if (w == 0) v = acc[ii][j] + (int32_t)Y[ys * 1024 + at];
+                    else if (w == 1) v = acc[2 + ii][j] + (int32_t)X[xs * 1024 + at];
+                    else v = (int32_t)X[xs * 1024 + at] + (int32_t)Y[ys * 1024 + at];
+                    fin[ii][j] = v;
+                }
         }
     }
-    __syncthreads();
-    if (WAVES == 8 && w >= 4) return;  // their sums went to waves 0..3; no barrier follows
-    int32_t fin[2][8];
-    {
-        const int xs = w - 1;                  // slot of quarter w in X (w >= 1)
-        const int ys = w == 0 ? 0 : w - 1;     // slot of quarter w in Y (w != 1)
-#pragma unroll
-        for (int ii = 0; ii < 2; ++ii)
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int at = (ii * 8 + j) * 64 + lane;
-                int32_t v;
-                if (w == 0) v = acc[ii][j] + (int32_t)Y[ys * 1024 + at];
-                else if (w == 1) v = acc[2 + ii][j] + (int32_t)X[xs * 1024 + at];
-                else v = (int32_t)X[xs * 1024 + at] + (int32_t)Y[ys * 1024 + at];
-                fin[ii][j] = v;
-            }
-    }
 
-    // wave w holds rows (w / 2) * 32 + ty * 4 + (w % 2) * 2 + {0, 1} of the tile
     if (gridDim.z > 1) {  // a slice of the reduction: park the partial quires and the NaR flags of this slice
         const int64_t z = blockIdx.z;
         uint32_t* lim = ws.limbs + z * (int64_t)M * N;
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int m = m0 + (w >> 1) * 32 + ty * 4 + (w & 1) * 2 + ii;
+        for (int ii = 0; ii < RPW; ++ii) {
+            const int m = m0 + row_of(ii);
             if (m >= M) continue;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
@@ -318,14 +344,14 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
     // The quires with the bias and the NaR verdicts first, then ONE test of the output format around the whole tile: the
     // posit<8,0> path is a compact run of code (a format test inside the loops would scatter it between sixteen copies of
     // the general encoder, and a wave pays an instruction-cache miss for every jump over one of them).
-    uint32_t qv[2][8];
-    bool narv[2][8];
+    uint32_t qv[RPW][8];
+    bool narv[RPW][8];
     const uint4 c0 = *reinterpret_cast<const uint4*>(&colNaR[0][tx * 4]);
     const uint4 c1 = *reinterpret_cast<const uint4*>(&colNaR[0][32 + tx * 4]);
     const uint32_t cflag[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
-    for (int ii = 0; ii < 2; ++ii) {
-        const int lr = (w >> 1) * 32 + ty * 4 + (w & 1) * 2 + ii;
+    for (int ii = 0; ii < RPW; ++ii) {
+        const int lr = row_of(ii);
         const bool rnar = rowNaR[0][lr] != 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
@@ -343,8 +369,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
     }
     if (fout == 0) {
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int m = m0 + (w >> 1) * 32 + ty * 4 + (w & 1) * 2 + ii;
+        for (int ii = 0; ii < RPW; ++ii) {
+            const int m = m0 + row_of(ii);
             if (m >= M) continue;
 #pragma unroll
             for (int jh = 0; jh < 2; ++jh) {
@@ -364,8 +390,8 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
         }
     } else {
 #pragma unroll
-        for (int ii = 0; ii < 2; ++ii) {
-            const int m = m0 + (w >> 1) * 32 + ty * 4 + (w & 1) * 2 + ii;
+        for (int ii = 0; ii < RPW; ++ii) {
+            const int m = m0 + row_of(ii);
             if (m >= M) continue;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
