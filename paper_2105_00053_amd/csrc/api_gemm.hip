@@ -9,6 +9,7 @@
 #include "conv_b8.h"
 #include "gemm_bucket_pre.h"
 #include "gemm_p16_window.h"
+#include "gemm_p32_lds.h"
 
 namespace pnn {
 
@@ -49,6 +50,11 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
     }
     // other posit<8,0> shapes go to the gather kernel (tile chosen per shape); the plan does not depend on pitches
     if ((F::N == 8 && F::ES == 0) && M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return p8_conv_plan((int)M, (int)N, (int)K);
+    if (F::N == 32 && p32_lds_fits(M, N, K)) {  // the quire of every output lives in LDS for the whole reduction: no workspace
+        GemmPlan p;
+        p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
+        return p;
+    }
     if (F::N == 16 && pw_fits(M, N, K)) return pw_plan(M, N, K).gemm;          // posit<16,1>: operands decoded once, two buckets + outlier bitmaps
     if (bucket_pre_fits<F>(M, N, K)) return bucket_pre_plan<F>(M, N, K).gemm;  // operands decoded once into the workspace
     return plan_split(M, N, K, 16 * GemmTile<F>::TM, 16 * GemmTile<F>::TN, Arith<F>::L);
@@ -105,6 +111,27 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
             const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
             RowMajorOut mo{ldc};
             return hip_status(b8_conv_launch<F>(st, p, (const uint8_t*)bias, C, fout, ws, plan, mo));
+        }
+    }
+    if constexpr (F::N == 32) {
+        if (p32_lds_fits(M, N, K)) {
+            if (!transA && !transB) {
+                MatrixOperand<T, true> a{(const T*)A, lda, M, K};
+                MatrixOperand<T, false> b{(const T*)B, ldb, N, K};
+                return hip_status(launch_p32_lds_gemm(st, a, b, M, N, K, bias, C, ldc, fout));
+            } else if (!transA && transB) {
+                MatrixOperand<T, true> a{(const T*)A, lda, M, K};
+                MatrixOperand<T, true> b{(const T*)B, ldb, N, K};
+                return hip_status(launch_p32_lds_gemm(st, a, b, M, N, K, bias, C, ldc, fout));
+            } else if (transA && !transB) {
+                MatrixOperand<T, false> a{(const T*)A, lda, M, K};
+                MatrixOperand<T, false> b{(const T*)B, ldb, N, K};
+                return hip_status(launch_p32_lds_gemm(st, a, b, M, N, K, bias, C, ldc, fout));
+            } else {
+                MatrixOperand<T, false> a{(const T*)A, lda, M, K};
+                MatrixOperand<T, true> b{(const T*)B, ldb, N, K};
+                return hip_status(launch_p32_lds_gemm(st, a, b, M, N, K, bias, C, ldc, fout));
+            }
         }
     }
     if constexpr (F::N == 16) {

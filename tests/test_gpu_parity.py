@@ -284,6 +284,34 @@ def test_p16_gemm_long_regime_operands_take_the_integer_correction(share, M, N, 
     assert (want[3] == 0x8000).all() and (want[4] != 0x8000).all()
 
 
+@pytest.mark.parametrize("M,N,K,ta,tb,fout,use_bias", [(450, 470, 77, 0, 0, "p32", 1), (449, 433, 130, 1, 0, "p16", 0), (600, 330, 40, 0, 1, "p32", 1),
+                                                       (400, 500, 1, 1, 1, "p8", 1)])
+def test_p32_gemm_quire_in_lds(M, N, K, ta, tb, fout, use_bias):
+    """posit<32,2> products with at least 768 tiles of 16 x 16 outputs: one output per thread, its 512-bit quire in LDS
+    as lazily carried 64-bit limbs.  Random patterns over the whole regime range (products land on every limb, both
+    signs), ragged edges, the four transposition cases, NaR rows and columns, bias, three output formats; no workspace."""
+    assert pn.posit_gemm_workspace("p32", fout, ta, tb, M, N, K) == 0
+    rng = np.random.default_rng(M + 3 * N + 7 * K)
+    A = rand_patterns(rng, (M, K), "p32", special=0.002, allow_nar=False)
+    B = rand_patterns(rng, (K, N), "p32", special=0.002, allow_nar=False)
+    A[M - 1, K - 1] = 1 << 31   # last row of C is NaR
+    B[0, N - 1] = 1 << 31       # last column of C is NaR
+    # extreme products: maxpos^2, minpos^2 and their negatives in one dot product
+    A[0, 0], B[0, 0] = 0x7FFFFFFF, 0x7FFFFFFF
+    if K > 2:
+        A[0, 1], B[1, 0] = 0x00000001, 0x00000001
+        A[0, 2], B[2, 0] = 0x80000001, 0x7FFFFFFF   # -maxpos * maxpos: cancels the first term exactly
+    bias = rand_patterns(rng, (N,), "p32", allow_nar=False) if use_bias else None
+    if use_bias:
+        bias[1] = 1 << 31
+    Ain, Bin = (np.ascontiguousarray(A.T) if ta else A), (np.ascontiguousarray(B.T) if tb else B)
+    got = to_np(pn.posit_gemm(to_dev(Ain), to_dev(Bin), "p32", fout, trans_a=ta, trans_b=tb, bias=None if bias is None else to_dev(bias)), fout)
+    want, _ = fast.gemm(Ain, Bin, "p32", fout, trans_a=ta, trans_b=tb, bias=bias)
+    _assert_equal(got, want, "p32 gemm with the quire in LDS %dx%dx%d" % (M, N, K))
+    nar = 1 << (BITS[fout] - 1)
+    assert (want[M - 1] == nar).all() and (want[:, N - 1] == nar).all() and (want[:M - 1, 2:N - 1] != nar).all()
+
+
 def test_gemm_padded_leading_dimensions_and_k0():
     rng = np.random.default_rng(8)
     M, N, K = 37, 29, 41
