@@ -6,6 +6,7 @@
 #include "api_common.h"
 #include "conv_p8.h"
 #include "gemm_p8_w4.h"
+#include "gemm_p8_mfma.h"
 #include "conv_b8.h"
 #include "gemm_bucket_pre.h"
 #include "gemm_p16_window.h"
@@ -42,6 +43,11 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
         p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
         return p;
     }
+    if ((F::N == 8 && F::ES == 0) && p8_mfma_fits(M, N, K)) {  // digit planes of both operands for the integer matrix cores
+        GemmPlan p;
+        p.splits = 1; p.k_per_split = K; p.ws_bytes = p8_mfma_layout(M, N, K).total();
+        return p;
+    }
     if ((F::N == 8 && F::ES == 0) && use_p8_w4(M, N, K)) return p8_w4_plan(M, N, K).gemm;  // the reduction is cut inside the workgroup first
     if ((F::N == 8 && F::ES == 0) && use_p8_kernel(M, N)) {
         GemmPlan p = plan_split(M, N, K, P8_BM, P8_BN, 1, P8_KT);
@@ -74,6 +80,9 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
     if ((F::N == 8 && F::ES == 0) && p8_small_gemm_fits(M, N, K))
         return hip_status(launch_p8_small_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
                                                fout, M, N, K));
+    if ((F::N == 8 && F::ES == 0) && p8_mfma_fits(M, N, K))
+        return hip_status(launch_p8_mfma_gemm(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc, fout,
+                                              M, N, K, ws));
     if ((F::N == 8 && F::ES == 0) && use_p8_w4(M, N, K)) {
         const uint8_t* a8 = (const uint8_t*)A;
         const uint8_t* b8 = (const uint8_t*)B;

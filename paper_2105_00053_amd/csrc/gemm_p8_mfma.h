@@ -1,0 +1,253 @@
+// posit<8,0> matrix product with the 32-bit quire of Table 1 (paper Sec. 2, Sec. 3.3) on the integer matrix cores.
+//
+// A decoded posit<8,0> is an integer v of at most 13 bits plus sign (units of minpos = 2^-6), and the quire is the
+// int32 sum of the products modulo 2^32.  Integer matrix instructions multiply int8 by int8 into int32 exactly, so v is
+// written in two base-128 digits, v = 128 hi + lo with hi = v >> 7 in [-32, 32] and lo = v & 127 in [0, 127], and
+//     a b = 2^14 (ah bh) + 2^7 (ah bl + al bh) + (al bl):
+// three int32 sums per output -- HH, X (both cross terms share it) and LL -- fed by four int8 products per posit
+// product, combined once after the reduction as (HH << 14) + (X << 7) + LL in 32-bit arithmetic.  Every step is exact
+// modulo 2^32 (a sum that wraps in one of the three accumulators wraps the same way in the combination, since the
+// shifts only discard high bits), so the result is the quire's bit for bit, wrap-around included.  The int8 matrix
+// rate of the chip is 64 times the rate of the packed 16-bit dot product per instruction slot, which leaves a factor
+// of 8 after the four products: v_mfma_i32_32x32x32_i8 does 32768 int8 products in 32 cycles on one SIMD.
+//
+// Lane layout of that instruction (checked on the hardware): lane l holds, for A, row l % 32 and the 16 consecutive
+// reduction indices starting at 16 (l / 32); for B column l % 32 and the same indices; register r of the result is
+// row (r % 4) + 8 (r / 4) + 4 (l / 32), column l % 32.  The order of the reduction indices inside a block does not
+// matter as long as both operands use the same one.
+//
+// A first launch (p8_digits_kernel) decodes both operands through the LDS table and writes their digit planes into the
+// workspace in exactly the order the instruction wants them: [k block of 32][row block of 32][digit][lane][16 bytes],
+// zero-padded to whole tiles, NaR as zero plus a flag per row / column.  The product kernel then never rearranges
+// anything: 16-byte copies from there into LDS, 16-byte LDS reads into the operand registers.  128 x 128 outputs per
+// workgroup of four waves, 64 x 64 per wave as 2 x 2 blocks x 3 sums = 192 accumulator registers.
+#pragma once
+
+#include "gemm_p8.h"
+
+namespace pnn {
+
+typedef int pm_v4i __attribute__((ext_vector_type(4)));
+typedef int pm_v16i __attribute__((ext_vector_type(16)));
+
+constexpr int PM_TILE = 128;   // outputs per workgroup tile edge
+constexpr int PM_KSTEP = 2;    // k blocks (of 32) per staged step
+
+struct P8DigitJob {
+    const uint8_t* src;
+    int64_t s_r, s_k;   // element (row, k) at src[row * s_r + k * s_k]
+    int rows, K;
+    uint8_t* dst;       // [KB][RB][2][64][16]
+    int RB, KB;         // padded extents in blocks of 32
+    uint32_t* flags;    // one per (padded) row, zeroed beforehand
+};
+
+// Both operands in one launch: the first blocks0 workgroups take job0, the rest job1.  A workgroup handles one k block
+// and eight row blocks: 512 lane slots of 16 bytes per digit, two per thread.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8DigitJob job1, unsigned blocks0) {
+    __shared__ int16_t tab[256];
+    const int t = threadIdx.x;
+    tab[t] = (int16_t)Arith<P8>::stage((uint32_t)t);  // zero for the zero pattern and for NaR
+    __syncthreads();
+    const bool first = blockIdx.x < blocks0;
+    const P8DigitJob& job = first ? job0 : job1;
+    const unsigned lin = first ? blockIdx.x : blockIdx.x - blocks0;
+    const unsigned gx = (unsigned)((job.RB + 7) / 8);
+    const int bx = (int)(lin % gx), kb = (int)(lin / gx);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int slot = t + 256 * h;
+        const int rb = bx * 8 + (slot >> 6), lane = slot & 63;
+        if (rb >= job.RB) continue;
+        const int row = rb * 32 + (lane & 31), k0 = kb * 32 + 16 * (lane >> 5);
+        uint32_t w[4] = {0, 0, 0, 0};
+        if (row < job.rows) {
+            const uint8_t* p = job.src + (int64_t)row * job.s_r + (int64_t)k0 * job.s_k;
+            if (job.s_k == 1 && k0 + 16 <= job.K && (((uintptr_t)p) & 15u) == 0) {
+                const uint4 v = *reinterpret_cast<const uint4*>(p);
+                w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
+            } else {
+#pragma unroll
+                for (int b = 0; b < 16; ++b)
+                    if (k0 + b < job.K) w[b >> 2] |= (uint32_t)p[(int64_t)b * job.s_k] << (8 * (b & 3));
+            }
+        }
+        uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+        bool nar = false;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            const uint32_t pat = (w[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+            nar |= pat == 0x80u;
+            const int v = tab[pat];
+            hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
+            lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
+        }
+        uint4* out = reinterpret_cast<uint4*>(job.dst) + ((int64_t)(kb * job.RB + rb) * 2) * 64 + lane;
+        out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        out[64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        if (nar) atomicOr(&job.flags[row], 1u);
+    }
+}
+
+// Ad / Bd: digit planes of p8_digits_kernel with RBA / RBB row blocks (multiples of 4) and KB k blocks (a multiple of
+// PM_KSTEP); rowflag / colflag: the NaR flags it raised.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB,
+                                                              const uint32_t* __restrict__ rowflag, const uint32_t* __restrict__ colflag,
+                                                              const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M,
+                                                              int N, int tiles_m, int tiles_n) {
+    // [buffer][operand][k block of the step][row block of the tile][digit][lane]: 64 KB
+    __shared__ uint4 stage[2][2][PM_KSTEP][4][2][64];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, w = t >> 6;
+    const int wy = w >> 1, wx = w & 1;
+
+    // XCD-aware order: consecutive workgroup ids go round-robin to the 8 XCDs, so give each XCD a contiguous run of
+    // tiles, walked in bands of 8 tile-rows, column by column inside a band (neighbours share operand panels in L2)
+    const int nblk = tiles_m * tiles_n;
+    int lid = blockIdx.x;
+    if ((nblk & 7) == 0) lid = (blockIdx.x & 7) * (nblk >> 3) + (blockIdx.x >> 3);
+    const int band = lid / (8 * tiles_n);
+    const int band_rows = (tiles_m - band * 8) < 8 ? (tiles_m - band * 8) : 8;
+    const int in_band = lid - band * 8 * tiles_n;
+    const int tm = band * 8 + in_band % band_rows, tn = in_band / band_rows;
+
+    pm_v16i hh[2][2], xx[2][2], ll[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) hh[i][j][r] = xx[i][j][r] = ll[i][j][r] = 0;
+
+    // One step is 32 runs of 1 KB (operand, k block of the step, row block and digit), each a run in the workspace too.
+    // Wave w copies runs 8 w .. 8 w + 7 straight into LDS: the load writes 16 bytes per lane at consecutive LDS
+    // addresses from a wave-uniform base, which is exactly a run, and passes through no register.
+    const uint4* ga = reinterpret_cast<const uint4*>(Ad) + (int64_t)tm * 4 * 2 * 64;
+    const uint4* gb = reinterpret_cast<const uint4*>(Bd) + (int64_t)tn * 4 * 2 * 64;
+    const int64_t a_kb = (int64_t)RBA * 2 * 64, b_kb = (int64_t)RBB * 2 * 64;  // words per k block
+    auto issue = [&](int kb0, int buf) {
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int run = w * 8 + c;
+            const int op = run >> 4, kk = (run >> 3) & 1, sub = run & 7;
+            const uint4* src = (op ? gb + (kb0 + kk) * b_kb : ga + (kb0 + kk) * a_kb) + sub * 64 + lane;
+            uint4* dst = &stage[buf][op][kk][0][0][0] + sub * 64;  // the same for every lane
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+        }
+    };
+    static_assert(PM_KSTEP == 2, "run numbering");
+
+    issue(0, 0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's runs are in LDS
+    __syncthreads();
+    int cur = 0;
+    for (int kb0 = 0; kb0 < KB; kb0 += PM_KSTEP, cur ^= 1) {
+        if (kb0 + PM_KSTEP < KB) issue(kb0 + PM_KSTEP, cur ^ 1);  // the other buffer was last read one barrier ago
+#pragma unroll
+        for (int kk = 0; kk < PM_KSTEP; ++kk) {
+            pm_v4i ah[2], al[2], bh[2], bl[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                ah[i] = __builtin_bit_cast(pm_v4i, stage[cur][0][kk][2 * wy + i][0][lane]);
+                al[i] = __builtin_bit_cast(pm_v4i, stage[cur][0][kk][2 * wy + i][1][lane]);
+                bh[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][0][lane]);
+                bl[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][1][lane]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah[i], bh[j], hh[i][j], 0, 0, 0);
+                    xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah[i], bl[j], xx[i][j], 0, 0, 0);
+                    xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al[i], bh[j], xx[i][j], 0, 0, 0);
+                    ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al[i], bl[j], ll[i][j], 0, 0, 0);
+                }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the next step's runs of this wave are in LDS
+        __syncthreads();
+    }
+
+    // ---- the three sums into the quire, round once, store ----
+    const int m_base = tm * PM_TILE + wy * 64, n_base = tn * PM_TILE + wx * 64;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const int n = n_base + j * 32 + (lane & 31);
+        if (n >= N) continue;
+        bool cnar = colflag[n] != 0;
+        int32_t badd = 0;
+        if (bias) {
+            const uint32_t bp = bias[n];
+            if (bp == 0x80u) cnar = true;
+            else badd = (int32_t)Arith<P8>::stage(bp) << P8::MAXS;  // + bias * 1
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m_base + i * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+                if (m >= M) continue;
+                const uint32_t q = ((uint32_t)hh[i][j][r] << 14) + ((uint32_t)xx[i][j][r] << 7) + (uint32_t)ll[i][j][r] + (uint32_t)badd;
+                const bool nar = cnar || rowflag[m] != 0;
+                const int64_t at = (int64_t)m * ldc + n;
+                if (fout == 0) {
+                    ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire((int32_t)q));
+                } else {
+                    const uint32_t q1[1] = {q};
+                    round_store<QuireAccum<P8>, 1>(q1, nar, fout, C, at);
+                }
+            }
+        }
+    }
+}
+
+// ---- host side ----
+
+struct P8MfmaLayout {
+    int RBA, RBB, KB;  // padded extents in blocks of 32
+    size_t a_bytes, b_bytes, flag_bytes;
+    size_t total() const { return a_bytes + b_bytes + flag_bytes; }
+};
+
+inline bool p8_mfma_fits(int64_t M, int64_t N, int64_t K) {
+    return M >= 1024 && N >= 1024 && K >= 512 && M * N * K >= ((int64_t)1 << 33) && M <= ((int64_t)1 << 20) && N <= ((int64_t)1 << 20) &&
+           K <= ((int64_t)1 << 20);
+}
+
+inline P8MfmaLayout p8_mfma_layout(int64_t M, int64_t N, int64_t K) {
+    P8MfmaLayout l;
+    l.RBA = (int)((M + PM_TILE - 1) / PM_TILE) * 4;
+    l.RBB = (int)((N + PM_TILE - 1) / PM_TILE) * 4;
+    l.KB = (int)((K + 32 * PM_KSTEP - 1) / (32 * PM_KSTEP)) * PM_KSTEP;
+    l.a_bytes = (size_t)l.KB * l.RBA * 2048;
+    l.b_bytes = (size_t)l.KB * l.RBB * 2048;
+    l.flag_bytes = ((size_t)(l.RBA + l.RBB) * 32 * sizeof(uint32_t) + 255) / 256 * 256;
+    return l;
+}
+
+inline hipError_t launch_p8_mfma_gemm(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                                      const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N, int64_t K, void* workspace) {
+    const P8MfmaLayout l = p8_mfma_layout(M, N, K);
+    uint8_t* base = (uint8_t*)workspace;
+    uint8_t* Ad = base;
+    uint8_t* Bd = base + l.a_bytes;
+    uint32_t* flags = (uint32_t*)(base + l.a_bytes + l.b_bytes);
+    const int64_t nflags = (int64_t)(l.RBA + l.RBB) * 32;
+    hipLaunchKernelGGL(p8_fill_zero_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, flags, nflags);
+    PNN_CHECK_LAUNCH();
+    // op(A)[m,k] is A[m * lda + k] unless transA; op(B)[k,n] is B[k * ldb + n] unless transB
+    P8DigitJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, Ad, l.RBA, l.KB, flags};
+    P8DigitJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, Bd, l.RBB, l.KB, flags + (size_t)l.RBA * 32};
+    const unsigned blocks0 = (unsigned)((l.RBA + 7) / 8) * (unsigned)l.KB, blocks1 = (unsigned)((l.RBB + 7) / 8) * (unsigned)l.KB;
+    hipLaunchKernelGGL(p8_digits_kernel<0>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
+    PNN_CHECK_LAUNCH();
+    const int tiles_m = l.RBA / 4, tiles_n = l.RBB / 4;
+    hipLaunchKernelGGL(p8_mfma_gemm_kernel<0>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, flags,
+                       flags + (size_t)l.RBA * 32, bias, C, ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace pnn
