@@ -18,9 +18,12 @@
 //
 // A first launch (p8_digits_kernel) decodes both operands through the LDS table and writes their digit planes into the
 // workspace in exactly the order the instruction wants them: [k block of 32][row block of 32][digit][lane][16 bytes],
-// zero-padded to whole tiles, NaR as zero plus a flag per row / column.  The product kernel then never rearranges
+// zero-padded to whole tiles; NaR is the high digit -128, which no value has (|hi| <= 32).  The product kernel then never rearranges
 // anything: 16-byte copies from there into LDS, 16-byte LDS reads into the operand registers.  128 x 128 outputs per
-// workgroup of four waves, 64 x 64 per wave as 2 x 2 blocks x 3 sums = 192 accumulator registers.
+// workgroup of four waves, 64 x 64 per wave as 2 x 2 blocks x 3 sums = 192 accumulator registers.  Every wave sees
+// the whole reduction of its rows and columns, so the waves find the NaR markers themselves (three vector operations
+// per high-digit register, the two waves that share a block splitting it): no flag arrays, no atomics, no clearing
+// launch.
 #pragma once
 
 #include "gemm_p8.h"
@@ -32,6 +35,11 @@ typedef int pm_v16i __attribute__((ext_vector_type(16)));
 
 constexpr int PM_TILE = 128;   // outputs per workgroup tile edge
 constexpr int PM_KSTEP = 2;    // k blocks (of 32) per staged step
+constexpr int PM_NAR_HI = -128;  // high digit that marks NaR
+
+// Bits 7 of the bytes of the result mark the bytes of w whose top two bits are "10": among high digits (values in
+// [-32, 32]: top bits 00 or 11) only the NaR marker.  The other bits of the result are noise, masked when read.
+__device__ __forceinline__ uint32_t pm_marker_bits(uint32_t w) { return w & ~(w << 1); }
 
 struct P8DigitJob {
     const uint8_t* src;
@@ -39,7 +47,6 @@ struct P8DigitJob {
     int rows, K;
     uint8_t* dst;       // [KB][RB][2][64][16]
     int RB, KB;         // padded extents in blocks of 32
-    uint32_t* flags;    // one per (padded) row, zeroed beforehand
 };
 
 // Both operands in one launch: the first blocks0 workgroups take job0, the rest job1.  A workgroup handles one k block
@@ -48,7 +55,7 @@ template <int UNUSED = 0>
 __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8DigitJob job1, unsigned blocks0) {
     __shared__ int16_t tab[256];
     const int t = threadIdx.x;
-    tab[t] = (int16_t)Arith<P8>::stage((uint32_t)t);  // zero for the zero pattern and for NaR
+    tab[t] = t == 0x80 ? (int16_t)(PM_NAR_HI * 128) : (int16_t)Arith<P8>::stage((uint32_t)t);
     __syncthreads();
     const bool first = blockIdx.x < blocks0;
     const P8DigitJob& job = first ? job0 : job1;
@@ -74,27 +81,23 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
             }
         }
         uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
-        bool nar = false;
 #pragma unroll
         for (int b = 0; b < 16; ++b) {
             const uint32_t pat = (w[b >> 2] >> (8 * (b & 3))) & 0xFFu;
-            nar |= pat == 0x80u;
-            const int v = tab[pat];
+            const int v = tab[pat];  // -16384 for NaR: high digit -128, low digit 0
             hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
             lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
         }
         uint4* out = reinterpret_cast<uint4*>(job.dst) + ((int64_t)(kb * job.RB + rb) * 2) * 64 + lane;
         out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
         out[64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
-        if (nar) atomicOr(&job.flags[row], 1u);
     }
 }
 
 // Ad / Bd: digit planes of p8_digits_kernel with RBA / RBB row blocks (multiples of 4) and KB k blocks (a multiple of
-// PM_KSTEP); rowflag / colflag: the NaR flags it raised.
+// PM_KSTEP).
 template <int UNUSED = 0>
-__global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB,
-                                                              const uint32_t* __restrict__ rowflag, const uint32_t* __restrict__ colflag,
+__global__ __launch_bounds__(256, 2) void p8_mfma_gemm_kernel(const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB,
                                                               const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M,
                                                               int N, int tiles_m, int tiles_n) {
     // [buffer][operand][k block of the step][row block of the tile][digit][lane]: 64 KB
@@ -114,6 +117,7 @@ __global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __r
     const int in_band = lid - band * 8 * tiles_n;
     const int tm = band * 8 + in_band % band_rows, tn = in_band / band_rows;
 
+    uint32_t row_nar = 0, col_nar = 0;  // markers met in this lane's row of row block wx / column of column block wy (its half of every k block)
     pm_v16i hh[2][2], xx[2][2], ll[2][2];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -157,6 +161,13 @@ __global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __r
                 bh[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][0][lane]);
                 bl[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][1][lane]);
             }
+            // the two waves that share a row block (column block) split the search for NaR markers: wave (wy, wx) looks
+            // at its row block wx and its column block wy
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                row_nar |= pm_marker_bits((uint32_t)(wx ? ah[1][q] : ah[0][q]));
+                col_nar |= pm_marker_bits((uint32_t)(wy ? bh[1][q] : bh[0][q]));
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -172,12 +183,25 @@ __global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __r
     }
 
     // ---- the three sums into the quire, round once, store ----
+    // NaR: lanes l and l + 32 hold the two halves of the reduction of row (column) l % 32 of the block their wave
+    // searched; the verdicts of the tile's 128 rows and 128 columns meet in LDS (the staging buffers are free now).
+    uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0][0][0][0][0]);
+    uint32_t* colv = rowv + PM_TILE;
+    row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;
+    col_nar = (col_nar | (uint32_t)__shfl_xor((int)col_nar, 32)) & 0x80808080u;
+    if (lane < 32) {
+        rowv[wy * 64 + wx * 32 + lane] = row_nar;
+        colv[wx * 64 + wy * 32 + lane] = col_nar;
+    }
+    __syncthreads();
+    rowv += wy * 64;
+    colv += wx * 64;
     const int m_base = tm * PM_TILE + wy * 64, n_base = tn * PM_TILE + wx * 64;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
         const int n = n_base + j * 32 + (lane & 31);
         if (n >= N) continue;
-        bool cnar = colflag[n] != 0;
+        bool cnar = colv[j * 32 + (lane & 31)] != 0;
         int32_t badd = 0;
         if (bias) {
             const uint32_t bp = bias[n];
@@ -188,10 +212,11 @@ __global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __r
         for (int i = 0; i < 2; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = m_base + i * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+                const int lr = i * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+                const int m = m_base + lr;
                 if (m >= M) continue;
                 const uint32_t q = ((uint32_t)hh[i][j][r] << 14) + ((uint32_t)xx[i][j][r] << 7) + (uint32_t)ll[i][j][r] + (uint32_t)badd;
-                const bool nar = cnar || rowflag[m] != 0;
+                const bool nar = cnar || rowv[lr] != 0;
                 const int64_t at = (int64_t)m * ldc + n;
                 if (fout == 0) {
                     ((uint8_t*)C)[at] = (uint8_t)(nar ? 0x80u : p8_round_quire((int32_t)q));
@@ -208,8 +233,8 @@ __global__ __launch_bounds__(256, 1) void p8_mfma_gemm_kernel(const uint8_t* __r
 
 struct P8MfmaLayout {
     int RBA, RBB, KB;  // padded extents in blocks of 32
-    size_t a_bytes, b_bytes, flag_bytes;
-    size_t total() const { return a_bytes + b_bytes + flag_bytes; }
+    size_t a_bytes, b_bytes;
+    size_t total() const { return a_bytes + b_bytes; }
 };
 
 inline bool p8_mfma_fits(int64_t M, int64_t N, int64_t K) {
@@ -224,7 +249,6 @@ inline P8MfmaLayout p8_mfma_layout(int64_t M, int64_t N, int64_t K) {
     l.KB = (int)((K + 32 * PM_KSTEP - 1) / (32 * PM_KSTEP)) * PM_KSTEP;
     l.a_bytes = (size_t)l.KB * l.RBA * 2048;
     l.b_bytes = (size_t)l.KB * l.RBB * 2048;
-    l.flag_bytes = ((size_t)(l.RBA + l.RBB) * 32 * sizeof(uint32_t) + 255) / 256 * 256;
     return l;
 }
 
@@ -234,19 +258,15 @@ inline hipError_t launch_p8_mfma_gemm(hipStream_t stream, int transA, int transB
     uint8_t* base = (uint8_t*)workspace;
     uint8_t* Ad = base;
     uint8_t* Bd = base + l.a_bytes;
-    uint32_t* flags = (uint32_t*)(base + l.a_bytes + l.b_bytes);
-    const int64_t nflags = (int64_t)(l.RBA + l.RBB) * 32;
-    hipLaunchKernelGGL(p8_fill_zero_kernel<0>, dim3((unsigned)((nflags + 255) / 256)), dim3(256), 0, stream, flags, nflags);
-    PNN_CHECK_LAUNCH();
     // op(A)[m,k] is A[m * lda + k] unless transA; op(B)[k,n] is B[k * ldb + n] unless transB
-    P8DigitJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, Ad, l.RBA, l.KB, flags};
-    P8DigitJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, Bd, l.RBB, l.KB, flags + (size_t)l.RBA * 32};
+    P8DigitJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, Ad, l.RBA, l.KB};
+    P8DigitJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, Bd, l.RBB, l.KB};
     const unsigned blocks0 = (unsigned)((l.RBA + 7) / 8) * (unsigned)l.KB, blocks1 = (unsigned)((l.RBB + 7) / 8) * (unsigned)l.KB;
     hipLaunchKernelGGL(p8_digits_kernel<0>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
     const int tiles_m = l.RBA / 4, tiles_n = l.RBB / 4;
-    hipLaunchKernelGGL(p8_mfma_gemm_kernel<0>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, flags,
-                       flags + (size_t)l.RBA * 32, bias, C, ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
+    hipLaunchKernelGGL(p8_mfma_gemm_kernel<0>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, bias, C, ldc,
+                       fout, (int)M, (int)N, tiles_m, tiles_n);
     return hipGetLastError();
 }
 
