@@ -15,11 +15,14 @@ the path on that batch:
         posit<8,0> copy of the new W                  (posit_axpy)
 
 `value` is M*N*K multiply-accumulates divided by the time of the whole step.
-`roofline` is for the posit_gemm call alone (the GEMM kernel and, at this size, the
-pass that packs its operands first), timed with HIP events on the launch
-stream: achieved MAC/s against the integer-VALU peak of the chip for the fastest
-exact primitive (one packed 16-bit dot-product lane-op = 2 MACs):
-256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2 = 78.6 TMAC/s.
+`roofline` is for the posit_gemm call alone (at this size: the pass that writes the operands'
+int8 digit planes, then the integer-matrix-core kernel), timed with HIP events on the launch
+stream.  The kernel forms every posit product exactly from four int8 x int8 products
+(two base-128 digits per operand, int32 sums), so its bound is the int8 MFMA rate:
+achieved = 8 int8 operations per posit MAC x M*N*K / time against the published 5.0 POP/s.
+The line also carries the posit MAC rate against the integer-VALU peak the metric names
+(one packed 16-bit dot-product lane-op = 2 MACs: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz x 2
+= 78.6 TMAC/s), which the previous, vector-ALU kernel was bound by.
 `cpu_baseline` times the (untuned) C++ oracle on a sample of rows of the same GEMM.
 """
 import argparse
@@ -32,11 +35,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s
-# HBM-side bytes per posit_gemm call at 4096^3 (operand packing pass + GEMM kernel), from two rocprofv3 --pmc
-# passes (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in KiB:
-# GEMM kernel 192048 / 16384, packing pass 16421 / 65536.
-GEMM_4096_TRAFFIC_BYTES = int((2.0 * (192048 + 16421) + 16384 + 65536) * 1024)
+PEAK_TMACS = 256 * 4 * 16 * 2.4e9 * 2 / 1e12  # 78.6 TMAC/s: integer vector ALU, packed 16-bit dot products
+PEAK_INT8_TOPS = 5000.0                       # dense int8 MFMA, published
+INT8_OPS_PER_POSIT_MAC = 8                    # four int8 multiply-accumulates: (128 ah + al)(128 bh + bl)
+# HBM-side bytes per posit_gemm call at 4096^3 (digit-plane pass + GEMM kernel), from two rocprofv3 --pmc passes
+# (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in KiB.
+GEMM_4096_TRAFFIC_KIB = (180119, 20682, 16542, 65536)  # (FETCH gemm, WRITE gemm, FETCH digit pass, WRITE digit pass)
 
 
 def _time_ms(torch, fn, reps, warm=2):
@@ -251,6 +255,11 @@ def main():
         sustained = {"steps": args.sustained_steps, "ms_per_step": round(sustained_ms, 4),
                      "GMAC/s": round(macs / (sustained_ms * 1e-3) / 1e9, 1)}
 
+    traffic, traffic_source = None, "not measured for this size"
+    if S == 4096 and GEMM_4096_TRAFFIC_KIB:
+        fg, wg, fd, wd = GEMM_4096_TRAFFIC_KIB
+        traffic = int((2.0 * (fg + fd) + wg + wd) * 1024)
+        traffic_source = "stored constant from profiles/p8_gemm_4096_hbm_traffic.md (two rocprofv3 --pmc runs), not measured by this run"
     result = {
         "metric": "quire-exact posit MAC/s (GMAC/s) + % of integer-VALU peak, posit<8,0> GEMM",
         "value": round(value, 1),
@@ -262,21 +271,25 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "int32",
+        "dtype": "int32",  # int8 x int8 digit products summed in int32, combined modulo 2^32: the quire of Table 1
         "data": "synthetic",
         "config": {"workload": "posit<8,0> quire GEMM M=N=K=%d (benchmark config 5), step = round A,B + gemm + convert + axpy" % S,
                    "fin": "posit<8,0>", "fout": "posit<8,0>", "quire_bits": 32},
         "roofline": {
-            "bound": "alu",
-            "kernel": "p8_gemm_kernel (with its operand packing pass: the posit_gemm call)",
-            "achieved": round(achieved, 3),
-            "peak": round(PEAK_TMACS, 1),
-            "unit": "TMAC/s",
-            "frac": round(achieved / PEAK_TMACS, 4),
+            "bound": "mfma",
+            "kernel": "p8_mfma_gemm_kernel (with its digit-plane pass: the posit_gemm call)",
+            "achieved": round(achieved * INT8_OPS_PER_POSIT_MAC, 1),
+            "peak": PEAK_INT8_TOPS,
+            "unit": "TOP/s (int8)",
+            "frac": round(achieved * INT8_OPS_PER_POSIT_MAC / PEAK_INT8_TOPS, 4),
             "kernel_ms": round(gemm_ms, 4),
+            "int8_ops_per_posit_mac": INT8_OPS_PER_POSIT_MAC,
+            "posit_TMAC_per_s": round(achieved, 3),
+            "integer_valu_peak_TMAC_per_s": round(PEAK_TMACS, 1),
+            "x_integer_valu_peak": round(achieved / PEAK_TMACS, 3),
             "algorithmic_bytes": 3 * S * S,
-            "traffic": GEMM_4096_TRAFFIC_BYTES if S == 4096 else None,
-            "traffic_source": "stored constant from profiles/p8_gemm_4096_hbm_traffic.md (two rocprofv3 --pmc runs), not measured by this run",
+            "traffic": traffic,
+            "traffic_source": traffic_source,
         },
     }
 

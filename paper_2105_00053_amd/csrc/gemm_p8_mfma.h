@@ -43,7 +43,7 @@ __device__ __forceinline__ uint32_t pm_marker_bits(uint32_t w) { return w & ~(w 
 
 struct P8DigitJob {
     const uint8_t* src;
-    int64_t s_r, s_k;   // element (row, k) at src[row * s_r + k * s_k]
+    int64_t s_r, s_k;   // element (row, k) at src[row * s_r + k * s_k]; one of the two is 1
     int rows, K;
     uint8_t* dst;       // [KB][RB][2][64][16]
     int RB, KB;         // padded extents in blocks of 32
@@ -62,6 +62,30 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
     const unsigned lin = first ? blockIdx.x : blockIdx.x - blocks0;
     const unsigned gx = (unsigned)((job.RB + 7) / 8);
     const int bx = (int)(lin % gx), kb = (int)(lin / gx);
+    // Rows contiguous in memory (s_r == 1: an operand stored reduction index major): the 32 x 256 patterns of the
+    // workgroup's block go through LDS, read as 16-byte runs along the rows and picked up along k.
+    __shared__ __attribute__((aligned(16))) uint8_t tile[32][256];
+    const bool via_lds = job.s_k != 1;
+    if (via_lds) {
+        const int kk = t >> 3, seg = (t & 7) * 32;  // thread: 32 consecutive rows at one k
+        const int k = kb * 32 + kk;
+        const int row0 = bx * 256 + seg;
+        uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k < job.K && row0 < job.rows) {
+            const uint8_t* p = job.src + (int64_t)k * job.s_k + row0;
+            if (row0 + 32 <= job.rows && (((uintptr_t)p) & 15u) == 0) {
+                const uint4 v0 = reinterpret_cast<const uint4*>(p)[0], v1 = reinterpret_cast<const uint4*>(p)[1];
+                w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w; w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
+            } else {
+                for (int b = 0; b < 32; ++b)
+                    if (row0 + b < job.rows) w[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
+            }
+        }
+        uint4* d = reinterpret_cast<uint4*>(&tile[kk][seg]);
+        d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        __syncthreads();
+    }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
         const int slot = t + 256 * h;
@@ -69,15 +93,18 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
         if (rb >= job.RB) continue;
         const int row = rb * 32 + (lane & 31), k0 = kb * 32 + 16 * (lane >> 5);
         uint32_t w[4] = {0, 0, 0, 0};
-        if (row < job.rows) {
+        if (via_lds) {
+#pragma unroll
+            for (int b = 0; b < 16; ++b) w[b >> 2] |= (uint32_t)tile[16 * (lane >> 5) + b][(slot >> 6) * 32 + (lane & 31)] << (8 * (b & 3));
+        } else if (row < job.rows) {
             const uint8_t* p = job.src + (int64_t)row * job.s_r + (int64_t)k0 * job.s_k;
-            if (job.s_k == 1 && k0 + 16 <= job.K && (((uintptr_t)p) & 15u) == 0) {
+            if (k0 + 16 <= job.K && (((uintptr_t)p) & 15u) == 0) {
                 const uint4 v = *reinterpret_cast<const uint4*>(p);
                 w[0] = v.x; w[1] = v.y; w[2] = v.z; w[3] = v.w;
             } else {
 #pragma unroll
                 for (int b = 0; b < 16; ++b)
-                    if (k0 + b < job.K) w[b >> 2] |= (uint32_t)p[(int64_t)b * job.s_k] << (8 * (b & 3));
+                    if (k0 + b < job.K) w[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
             }
         }
         uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
