@@ -116,7 +116,7 @@ def issue_rates():
     if not os.path.exists(path):
         raise RuntimeError("libpositnn_rates.so is not built: run python -m paper_2105_00053_amd.build")
     lib = ctypes.CDLL(path)
-    rates = (ctypes.c_double * 4)()
+    rates = (ctypes.c_double * 5)()
     info = (ctypes.c_int * 2)()
     if lib.pnn_issue_rates(rates, info) != 0:
         raise RuntimeError("pnn_issue_rates failed")
@@ -124,7 +124,7 @@ def issue_rates():
     return {"compute_units": info[0], "clock_kHz_reported": info[1], "nominal_lane_ops_per_s_T": round(nominal / 1e12, 2),
             "dot2_i16_lane_ops_per_s_T": round(rates[0] / 1e12, 2), "dot2_i16_TMAC_per_s": round(2 * rates[0] / 1e12, 2),
             "fma_f64_lane_ops_per_s_T": round(rates[1] / 1e12, 2), "int32_lane_ops_per_s_T": round(rates[2] / 1e12, 2),
-            "lds_read_b128_TB_per_s": round(rates[3] / 1e12, 2)}
+            "lds_read_b128_TB_per_s": round(rates[3] / 1e12, 2), "mfma_i32_32x32x32_i8_POP_per_s": round(rates[4] / 1e15, 2)}
 
 
 def extra_measurements(torch, pn, workloads):

@@ -79,6 +79,29 @@ __global__ __launch_bounds__(THREADS) void lds128_rate_kernel(int* out, int a0, 
     out[blockIdx.x * THREADS + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
 }
 
+// v_mfma_i32_32x32x32_i8 from registers: 8 independent accumulator blocks per wave, one wave per SIMD
+typedef int rate_v4i __attribute__((ext_vector_type(4)));
+typedef int rate_v16i __attribute__((ext_vector_type(16)));
+constexpr int MFMA_CHAINS = 8;
+__global__ __launch_bounds__(THREADS, 1) void mfma_i8_rate_kernel(int* out, int a0, int b0) {
+    rate_v16i acc[MFMA_CHAINS];
+#pragma unroll
+    for (int i = 0; i < MFMA_CHAINS; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0;
+    const rate_v4i a = {a0 + (int)threadIdx.x, a0, 3, 5}, b = {7, b0 ^ (int)threadIdx.x, 11, 13};
+    for (int it = 0; it < REPEATS; ++it) {
+#pragma unroll
+        for (int i = 0; i < MFMA_CHAINS; ++i) acc[i] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, acc[i], 0, 0, 0);
+    }
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < MFMA_CHAINS; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s ^= acc[i][r];
+    out[blockIdx.x * THREADS + threadIdx.x] = s;
+}
+
 template <class K>
 int time_kernel(K kernel, int blocks, int* out, float* ms) {
     hipEvent_t e0, e1;
@@ -99,7 +122,8 @@ int time_kernel(K kernel, int blocks, int* out, float* ms) {
 }  // namespace
 
 // rates[0]: v_dot2_i32_i16 lane-operations/s, [1]: fp64 fma lane-operations/s, [2]: 32-bit integer
-// operations/s (xor + add pairs, two operations per pair), [3]: LDS bytes/s through 16-byte reads.  info[0] = compute units,
+// operations/s (xor + add pairs, two operations per pair), [3]: LDS bytes/s through 16-byte reads, [4]: int8
+// operations/s of v_mfma_i32_32x32x32_i8 (2 per multiply-accumulate).  info[0] = compute units,
 // info[1] = clock in kHz as the runtime reports it.  Returns 0 on success.
 extern "C" int pnn_issue_rates(double* rates, int* info) {
     hipDeviceProp_t p;
@@ -120,6 +144,8 @@ extern "C" int pnn_issue_rates(double* rates, int* info) {
     rates[2] = 2 * lane_ops / (ms * 1e-3);
     bad |= time_kernel(lds128_rate_kernel, blocks, out, &ms);
     rates[3] = (double)blocks * THREADS * REPEATS * 8 * 16 / (ms * 1e-3);
+    bad |= time_kernel(mfma_i8_rate_kernel, p.multiProcessorCount, out, &ms);  // one workgroup of four waves per compute unit
+    rates[4] = 2.0 * p.multiProcessorCount * (THREADS / 64) * (double)REPEATS * MFMA_CHAINS * 32768.0 / (ms * 1e-3);
     hipFree(out);
     return bad;
 }

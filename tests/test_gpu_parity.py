@@ -396,9 +396,9 @@ def test_config5_p8_gemm_1024_full_and_p32_wide_quire():
 @pytest.mark.timeout(400)
 @pytest.mark.parametrize("S", [2048, 4096])
 def test_config5_p8_gemm_large_full(S):
-    """Full benchmark size, same launch path as bench.py (at 4096 the packed-operand kernel the headline figure is
-    timed on): every one of the S x S outputs against the C++ oracle (about 45 s of host time at 4096), a few
-    entries again through the Python oracle."""
+    """Full benchmark size, same launch path as bench.py (the integer-matrix-core kernel the headline figure is
+    timed on: two int8 digits per operand, three int32 sums per output): every one of the S x S outputs against the
+    C++ oracle (about 45 s of host time at 4096), a few entries again through the Python oracle."""
     A, B = workloads.gemm_operands(5, S)
     Ap, Bp = fast.round_from_float(A, "p8"), fast.round_from_float(B, "p8")
     C = to_np(pn.posit_gemm(to_dev(Ap), to_dev(Bp), "p8", "p8"), "p8")
@@ -418,10 +418,10 @@ def test_config5_p8_gemm_large_full(S):
 @pytest.mark.parametrize("M,N,K,ta,tb,fout", [(2100, 2050, 4000, 0, 0, "p8"), (2048, 2176, 4100, 1, 0, "p16"), (2300, 2048, 3999, 0, 1, "p8"),
                                               (2050, 2100, 4033, 1, 1, "p8"), (1100, 1030, 16400, 0, 0, "p8")])
 def test_p8_gemm_packed_operands_path(M, N, K, ta, tb, fout):
-    """Products of more than 2^34 MACs first rewrite both operands (decoded, pair-packed, padded) into the
-    workspace: ragged sizes, the four transposition cases, NaR in rows and columns near the edges, a bias,
-    and (last case) a split reduction behind the packed operands.  Sampled rows against the oracle, the NaR
-    rows and columns in full."""
+    """Products of more than 2^33 MACs first rewrite both operands into the workspace (int8 digit planes in the lane
+    order of the matrix instruction, NaR as a marker digit) and run on the matrix cores: ragged sizes, the four
+    transposition cases (an operand stored reduction-index-major is transposed through LDS), NaR in rows and columns
+    near the edges, a bias, a workspace full of ones.  Sampled rows against the oracle, the NaR rows and columns in full."""
     assert M * N * K >= 1 << 34
     assert pn.posit_gemm_workspace("p8", fout, ta, tb, M, N, K) >= 4 * (K // 2) * (M + N)
     rng = np.random.default_rng(M + K)
