@@ -33,7 +33,10 @@ namespace pnn {
 typedef int pm_v4i __attribute__((ext_vector_type(4)));
 typedef int pm_v16i __attribute__((ext_vector_type(16)));
 
-constexpr int PM_TILE = 128;   // outputs per workgroup tile edge
+constexpr int PM_MIN_MN = 512;                   // smallest output extent each way
+constexpr int64_t PM_MIN_MNK = (int64_t)1 << 28;  // smallest product count
+constexpr int PM_MIN_TILES = 81;                 // fewest 64 x 64 tiles: below, kernels that cut the reduction across workgroups win
+constexpr int PM_MIN_WGS = 512;                  // workgroups wanted before a larger tile is chosen
 constexpr int PM_KSTEP = 2;    // k blocks (of 32) per staged step
 constexpr int PM_NAR_HI = -128;  // high digit that marks NaR
 
@@ -121,17 +124,19 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
     }
 }
 
-// Ad / Bd: digit planes of p8_digits_kernel with RBA / RBB row blocks (multiples of 4) and KB k blocks (a multiple of
-// PM_KSTEP).
-template <int UNUSED = 0>
-__global__ __launch_bounds__(256, 2) void p8_mfma_gemm_kernel(const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB,
-                                                              const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M,
-                                                              int N, int tiles_m, int tiles_n) {
-    // [buffer][operand][k block of the step][row block of the tile][digit][lane]: 64 KB
-    __shared__ uint4 stage[2][2][PM_KSTEP][4][2][64];
+// Ad / Bd: digit planes of p8_digits_kernel with RBA / RBB row blocks (multiples of 2 BI / 2 BJ) and KB k blocks (a
+// multiple of PM_KSTEP).  Four waves as 2 x 2; a wave owns BI x BJ blocks of 32 x 32 outputs, the workgroup 64 BI x 64 BJ.
+template <int BI, int BJ>
+__global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) void p8_mfma_gemm_kernel(
+    const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB, const uint8_t* __restrict__ bias, void* __restrict__ C,
+    int64_t ldc, int fout, int M, int N, int tiles_m, int tiles_n) {
+    constexpr int NA = 2 * BI * 2, NB = 2 * BJ * 2;  // runs of 1 KB (row block, digit) per k block and operand
+    constexpr int TR = 64 * BI, TC = 64 * BJ;        // tile extents
+    // [buffer][k block of the step][A runs, then B runs][lane]: 64 KB for 128 x 128 outputs
+    __shared__ uint4 stage[2][PM_KSTEP][(NA + NB) * 64];
 
     const int t = threadIdx.x;
-    const int lane = t & 63, w = t >> 6;
+    const int lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);  // the wave number, known to be uniform
     const int wy = w >> 1, wx = w & 1;
 
     // XCD-aware order: consecutive workgroup ids go round-robin to the 8 XCDs, so give each XCD a contiguous run of
@@ -144,88 +149,108 @@ __global__ __launch_bounds__(256, 2) void p8_mfma_gemm_kernel(const uint8_t* __r
     const int in_band = lid - band * 8 * tiles_n;
     const int tm = band * 8 + in_band % band_rows, tn = in_band / band_rows;
 
-    uint32_t row_nar = 0, col_nar = 0;  // markers met in this lane's row of row block wx / column of column block wy (its half of every k block)
-    pm_v16i hh[2][2], xx[2][2], ll[2][2];
+    // markers met in this lane's row of the row block / column of the column block this wave searches (its half of every k block)
+    uint32_t row_nar = 0, col_nar = 0;
+    pm_v16i hh[BI][BJ], xx[BI][BJ], ll[BI][BJ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < BI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < BJ; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) hh[i][j][r] = xx[i][j][r] = ll[i][j][r] = 0;
 
-    // One step is 32 runs of 1 KB (operand, k block of the step, row block and digit), each a run in the workspace too.
-    // Wave w copies runs 8 w .. 8 w + 7 straight into LDS: the load writes 16 bytes per lane at consecutive LDS
-    // addresses from a wave-uniform base, which is exactly a run, and passes through no register.
-    const uint4* ga = reinterpret_cast<const uint4*>(Ad) + (int64_t)tm * 4 * 2 * 64;
-    const uint4* gb = reinterpret_cast<const uint4*>(Bd) + (int64_t)tn * 4 * 2 * 64;
+    // One step is PM_KSTEP (NA + NB) runs of 1 KB, each a run in the workspace too.  Every wave copies a quarter of them
+    // straight into LDS: the load writes 16 bytes per lane at consecutive LDS addresses from a wave-uniform base, which
+    // is exactly a run, and passes through no register.
+    const uint4* ga = reinterpret_cast<const uint4*>(Ad) + (int64_t)tm * NA * 64;
+    const uint4* gb = reinterpret_cast<const uint4*>(Bd) + (int64_t)tn * NB * 64;
     const int64_t a_kb = (int64_t)RBA * 2 * 64, b_kb = (int64_t)RBB * 2 * 64;  // words per k block
-    auto issue = [&](int kb0, int buf) {
+    constexpr int RUNS = PM_KSTEP * (NA + NB) / 4;  // per wave and step
+    static_assert(PM_KSTEP * (NA + NB) % 4 == 0, "runs split evenly over the four waves");
+    // Where this wave's runs come from and how far they move per step: wave-uniform, worked out once, so that the
+    // loop issues its copies without a branch.  Run number kk (NA + NB) + sub is also its place in the buffer.
+    const uint4* src[RUNS];
+    int64_t adv[RUNS];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
-            const int run = w * 8 + c;
-            const int op = run >> 4, kk = (run >> 3) & 1, sub = run & 7;
-            const uint4* src = (op ? gb + (kb0 + kk) * b_kb : ga + (kb0 + kk) * a_kb) + sub * 64 + lane;
-            uint4* dst = &stage[buf][op][kk][0][0][0] + sub * 64;  // the same for every lane
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+    for (int c = 0; c < RUNS; ++c) {
+        const int run = w * RUNS + c;
+        const int kk = run / (NA + NB), sub = run % (NA + NB);
+        const bool isb = sub >= NA;
+        src[c] = isb ? gb + kk * b_kb + (sub - NA) * 64 : ga + kk * a_kb + sub * 64;
+        adv[c] = PM_KSTEP * (isb ? b_kb : a_kb);
+    }
+    auto issue = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < RUNS; ++c) {
+            uint4* dst = &stage[buf][0][0] + (w * RUNS + c) * 64;  // the same for every lane
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src[c] + lane),
                                              (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
+            src[c] += adv[c];
         }
     };
-    static_assert(PM_KSTEP == 2, "run numbering");
 
-    issue(0, 0);
+    // the two waves that share a row block (column block) split the search for NaR markers when a wave has two blocks
+    // each way: wave (wy, wx) looks at its row block wx and its column block wy; with one block both waves look at it
+    const int ia = BI == 2 ? wx : 0, jb = BJ == 2 ? wy : 0;
+
+    issue(0);
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's runs are in LDS
     __syncthreads();
     int cur = 0;
     for (int kb0 = 0; kb0 < KB; kb0 += PM_KSTEP, cur ^= 1) {
-        if (kb0 + PM_KSTEP < KB) issue(kb0 + PM_KSTEP, cur ^ 1);  // the other buffer was last read one barrier ago
+        if (kb0 + PM_KSTEP < KB) issue(cur ^ 1);  // the other buffer was last read one barrier ago
 #pragma unroll
         for (int kk = 0; kk < PM_KSTEP; ++kk) {
-            pm_v4i ah[2], al[2], bh[2], bl[2];
+            pm_v4i ah[BI], al[BI], bh[BJ], bl[BJ];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) {
-                ah[i] = __builtin_bit_cast(pm_v4i, stage[cur][0][kk][2 * wy + i][0][lane]);
-                al[i] = __builtin_bit_cast(pm_v4i, stage[cur][0][kk][2 * wy + i][1][lane]);
-                bh[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][0][lane]);
-                bl[i] = __builtin_bit_cast(pm_v4i, stage[cur][1][kk][2 * wx + i][1][lane]);
+            for (int i = 0; i < BI; ++i) {
+                ah[i] = __builtin_bit_cast(pm_v4i, stage[cur][kk][((BI * wy + i) * 2 + 0) * 64 + lane]);
+                al[i] = __builtin_bit_cast(pm_v4i, stage[cur][kk][((BI * wy + i) * 2 + 1) * 64 + lane]);
             }
-            // the two waves that share a row block (column block) split the search for NaR markers: wave (wy, wx) looks
-            // at its row block wx and its column block wy
+#pragma unroll
+            for (int j = 0; j < BJ; ++j) {
+                bh[j] = __builtin_bit_cast(pm_v4i, stage[cur][kk][(NA + (BJ * wx + j) * 2 + 0) * 64 + lane]);
+                bl[j] = __builtin_bit_cast(pm_v4i, stage[cur][kk][(NA + (BJ * wx + j) * 2 + 1) * 64 + lane]);
+            }
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                row_nar |= pm_marker_bits((uint32_t)(wx ? ah[1][q] : ah[0][q]));
-                col_nar |= pm_marker_bits((uint32_t)(wy ? bh[1][q] : bh[0][q]));
+                row_nar |= pm_marker_bits((uint32_t)(ia ? ah[BI - 1][q] : ah[0][q]));
+                col_nar |= pm_marker_bits((uint32_t)(jb ? bh[BJ - 1][q] : bh[0][q]));
             }
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int i = 0; i < BI; ++i)
 #pragma unroll
-                for (int j = 0; j < 2; ++j) {
+                for (int j = 0; j < BJ; ++j) {
                     hh[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah[i], bh[j], hh[i][j], 0, 0, 0);
                     xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah[i], bl[j], xx[i][j], 0, 0, 0);
                     xx[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al[i], bh[j], xx[i][j], 0, 0, 0);
                     ll[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(al[i], bl[j], ll[i][j], 0, 0, 0);
                 }
         }
+        // keep the wait behind the step's matrix instructions: they need no memory, and hoisting the barrier over them
+        // would shorten the time the copies have to arrive
+        __builtin_amdgcn_sched_barrier(0);
         __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the next step's runs of this wave are in LDS
         __syncthreads();
     }
 
     // ---- the three sums into the quire, round once, store ----
     // NaR: lanes l and l + 32 hold the two halves of the reduction of row (column) l % 32 of the block their wave
-    // searched; the verdicts of the tile's 128 rows and 128 columns meet in LDS (the staging buffers are free now).
-    uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0][0][0][0][0]);
-    uint32_t* colv = rowv + PM_TILE;
+    // searched; the verdicts of the tile's rows and columns meet in LDS (the staging buffers are free now).
+    uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0][0]);
+    uint32_t* colv = rowv + TR;
     row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;
     col_nar = (col_nar | (uint32_t)__shfl_xor((int)col_nar, 32)) & 0x80808080u;
     if (lane < 32) {
-        rowv[wy * 64 + wx * 32 + lane] = row_nar;
-        colv[wx * 64 + wy * 32 + lane] = col_nar;
+        rowv[(wy * BI + ia) * 32 + lane] = row_nar;  // with one block per wave both waves of the pair write the same verdict
+        colv[(wx * BJ + jb) * 32 + lane] = col_nar;
     }
     __syncthreads();
-    rowv += wy * 64;
-    colv += wx * 64;
-    const int m_base = tm * PM_TILE + wy * 64, n_base = tn * PM_TILE + wx * 64;
+    rowv += wy * 32 * BI;
+    colv += wx * 32 * BJ;
+    const int m_base = tm * TR + wy * 32 * BI, n_base = tn * TC + wx * 32 * BJ;
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
+    for (int j = 0; j < BJ; ++j) {
         const int n = n_base + j * 32 + (lane & 31);
         if (n >= N) continue;
         bool cnar = colv[j * 32 + (lane & 31)] != 0;
@@ -236,7 +261,7 @@ __global__ __launch_bounds__(256, 2) void p8_mfma_gemm_kernel(const uint8_t* __r
             else badd = (int32_t)Arith<P8>::stage(bp) << P8::MAXS;  // + bias * 1
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < BI; ++i) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int lr = i * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
@@ -259,21 +284,29 @@ __global__ __launch_bounds__(256, 2) void p8_mfma_gemm_kernel(const uint8_t* __r
 // ---- host side ----
 
 struct P8MfmaLayout {
+    int BI, BJ;        // blocks of 32 per wave each way: the workgroup tile is 64 BI x 64 BJ
     int RBA, RBB, KB;  // padded extents in blocks of 32
     size_t a_bytes, b_bytes;
     size_t total() const { return a_bytes + b_bytes; }
 };
 
 inline bool p8_mfma_fits(int64_t M, int64_t N, int64_t K) {
-    return M >= 1024 && N >= 1024 && K >= 512 && M * N * K >= ((int64_t)1 << 33) && M <= ((int64_t)1 << 20) && N <= ((int64_t)1 << 20) &&
+    return M >= PM_MIN_MN && N >= PM_MIN_MN && K >= 256 && M * N * K >= PM_MIN_MNK && ((M + 63) / 64) * ((N + 63) / 64) >= PM_MIN_TILES && M <= ((int64_t)1 << 20) && N <= ((int64_t)1 << 20) &&
            K <= ((int64_t)1 << 20);
 }
 
+// The largest tile that still gives every compute unit two workgroups; 64 x 64 otherwise.
 inline P8MfmaLayout p8_mfma_layout(int64_t M, int64_t N, int64_t K) {
+    auto cdiv = [](int64_t a, int64_t b) { return (a + b - 1) / b; };
     P8MfmaLayout l;
-    l.RBA = (int)((M + PM_TILE - 1) / PM_TILE) * 4;
-    l.RBB = (int)((N + PM_TILE - 1) / PM_TILE) * 4;
-    l.KB = (int)((K + 32 * PM_KSTEP - 1) / (32 * PM_KSTEP)) * PM_KSTEP;
+    l.BI = l.BJ = 1;
+    if (cdiv(M, 128) * cdiv(N, 128) >= PM_MIN_WGS) l.BI = l.BJ = 2;
+    else if (M >= N && cdiv(M, 128) * cdiv(N, 64) >= PM_MIN_WGS) l.BI = 2;
+    else if (cdiv(M, 64) * cdiv(N, 128) >= PM_MIN_WGS) l.BJ = 2;
+    else if (cdiv(M, 128) * cdiv(N, 64) >= PM_MIN_WGS) l.BI = 2;
+    l.RBA = (int)cdiv(M, 64 * l.BI) * 2 * l.BI;
+    l.RBB = (int)cdiv(N, 64 * l.BJ) * 2 * l.BJ;
+    l.KB = (int)cdiv(K, 32 * PM_KSTEP) * PM_KSTEP;
     l.a_bytes = (size_t)l.KB * l.RBA * 2048;
     l.b_bytes = (size_t)l.KB * l.RBB * 2048;
     return l;
@@ -291,9 +324,16 @@ inline hipError_t launch_p8_mfma_gemm(hipStream_t stream, int transA, int transB
     const unsigned blocks0 = (unsigned)((l.RBA + 7) / 8) * (unsigned)l.KB, blocks1 = (unsigned)((l.RBB + 7) / 8) * (unsigned)l.KB;
     hipLaunchKernelGGL(p8_digits_kernel<0>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
-    const int tiles_m = l.RBA / 4, tiles_n = l.RBB / 4;
-    hipLaunchKernelGGL(p8_mfma_gemm_kernel<0>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, bias, C, ldc,
-                       fout, (int)M, (int)N, tiles_m, tiles_n);
+    const int tiles_m = l.RBA / (2 * l.BI), tiles_n = l.RBB / (2 * l.BJ);
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+#define PNN_PM_LAUNCH(bi, bj)                                                                                                                    \
+    hipLaunchKernelGGL((p8_mfma_gemm_kernel<bi, bj>), grid, dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M, (int)N, \
+                       tiles_m, tiles_n)
+    if (l.BI == 2 && l.BJ == 2) PNN_PM_LAUNCH(2, 2);
+    else if (l.BI == 2) PNN_PM_LAUNCH(2, 1);
+    else if (l.BJ == 2) PNN_PM_LAUNCH(1, 2);
+    else PNN_PM_LAUNCH(1, 1);
+#undef PNN_PM_LAUNCH
     return hipGetLastError();
 }
 
