@@ -102,9 +102,12 @@ def test_argument_validation_without_launch():
     assert need > 0
     assert L.posit_gemm(null, 0, 1, 0, 0, 32, 288, 131072, fake, 131072, fake, 288, null, fake, 288, null, 0) == 3
     assert L.posit_gemm(null, 0, 1, 0, 0, 32, 288, 131072, fake, 131072, fake, 288, null, fake, 288, ctypes.c_void_p(0x1008), need) == EINVAL  # alignment
-    # posit<8,0> 4096^3: no split, but both operands are packed into the workspace (2 bytes per element) with their flags
-    assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 2 * 2 * 4096 * 4096 + 2 * 4096 * 4
-    assert L.posit_gemm_workspace(0, 0, 0, 0, 2048, 2048, 2048) == 0  # 64 x 64 tiles, the reduction cut inside the workgroup
+    # posit<8,0> from 2^28 products up: no split, but both operands are rewritten into the workspace as two int8 digit
+    # planes (2 bytes per element, padded to whole tiles and k steps); NaR travels as a marker digit, no flag arrays
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 4096, 4096, 4096) == 2 * 4096 * (4096 + 4096)
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 2048, 2048, 2048) == 2 * 2048 * (2048 + 2048)
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 600, 540, 1700) == 2 * 1728 * (640 + 576)  # 64 x 64 tiles, k in steps of 64
+    assert L.posit_gemm_workspace(0, 0, 0, 0, 512, 512, 512) == 0   # below: the reduction cut inside the workgroup
     assert L.posit_gemm(null, 0, 0, 0, 0, 4096, 4096, 4096, fake, 4096, fake, 4096, null, fake, 4096, null, 0) == 3
     # the variant with the library's own scratch array: same checks, and a problem beyond the array is refused before any launch
     assert L.posit_gemm_static(null, 57, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4) == EINVAL
