@@ -8,6 +8,7 @@
 #include "api_common.h"
 #include "conv_desc.h"
 #include "conv_p8_pre.h"
+#include "conv_p8_mfma.h"
 #include "conv_b8.h"
 
 namespace pnn {
@@ -136,6 +137,8 @@ size_t conv_ws(int which, const ConvGeom& g) {
         P8PrePlan pp;
         GemmPlan pplan;
         if (p8_pre_usable(which, g, &pp, &pplan)) b = p8_pre_ws_bytes(pp, pplan);
+        const P8ConvMfmaPlan mp = p8_conv_mfma_plan(which, g);
+        if (mp.ok) b = mp.total();
     }
     if constexpr (is_b8<F>()) {
         if (p8_conv_eligible(which, g)) {
@@ -156,6 +159,11 @@ int conv_fwd(hipStream_t st, int fout, const ConvGeom& g, const void* x, const v
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(0, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(0, g)) {
+        const P8ConvMfmaPlan mp = p8_conv_mfma_plan(0, g);
+        if (mp.ok) {  // integer matrix cores
+            if (!ws || ws_bytes < mp.total()) return PNN_EWORKSPACE;
+            return hip_status(launch_p8_conv_mfma(st, mp, x, w, (const uint8_t*)bias, y, fout, ws));
+        }
         P8PrePlan pp;
         GemmPlan pplan;
         if (p8_pre_usable(0, g, &pp, &pplan)) {
@@ -193,6 +201,11 @@ int conv_bwd_data_product(hipStream_t st, int fout, const ConvGeom& g, const voi
     typedef typename Storage<F::N>::T T;
     const ConvDims d = conv_dims(1, g);
     if ((F::N == 8 && F::ES == 0) && p8_conv_eligible(1, g)) {
+        const P8ConvMfmaPlan mp = p8_conv_mfma_plan(1, g);
+        if (mp.ok) {  // integer matrix cores
+            if (!ws || ws_bytes < mp.total()) return PNN_EWORKSPACE;
+            return hip_status(launch_p8_conv_mfma(st, mp, dy, w, nullptr, dx, fout, ws));
+        }
         P8PrePlan pp;
         GemmPlan pplan;
         if (p8_pre_usable(1, g, &pp, &pplan)) {

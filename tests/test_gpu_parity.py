@@ -570,6 +570,44 @@ def test_p8_conv_many_rows_few_channels(geom):
     _assert_equal(to_np(db, "p16"), wdb, "conv bias gradient")
 
 
+@pytest.mark.parametrize("geom,fout", [(dict(N=10, C=20, H=31, W=33, K=40, R=3, S=3, pad_h=1, pad_w=1), "p8"),
+                                       (dict(N=17, C=8, H=64, W=64, K=40, R=3, S=3, pad_h=1, pad_w=1), "p8"),
+                                       (dict(N=8, C=24, H=20, W=52, K=72, R=2, S=3, pad_h=1, pad_w=1), "p16"),
+                                       (dict(N=13, C=16, H=30, W=30, K=32, R=5, S=5, pad_h=0, pad_w=0), "p8"),
+                                       (dict(N=9, C=33, H=32, W=32, K=64, R=3, S=3, pad_h=2, pad_w=0), "p8")])
+def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
+    """Unit-stride posit<8,0> forward and backward-data convolutions of 2^26 products and more (8192 output positions,
+    16 output channels) run as implicit matrix products on the integer matrix cores: the input rewritten as int8 digit
+    planes pixel-major in groups of 16 channels, gathered tap by tap.  Channel counts that do not fill a group, 64 x 64,
+    64 x 128 and 128 x 64 tiles, ragged position counts, filters 2 x 3 and 5 x 5, no padding and padding beyond the
+    filter's half, NaR in the input (every output whose window holds it), a NaR weight (forward: its whole output
+    channel, padding counts as an operand; backward-data: the positions its tap reaches), a NaR bias."""
+    d = geom
+    rng = np.random.default_rng(d["C"] * 7 + d["K"])
+    oh, ow = fast.out_hw(d)
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), "p8", special=0.0005)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), "p8", special=0.001, allow_nar=False)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.0005)
+    bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
+    desc = _desc(d)
+    assert pn.posit_conv2d_workspace(0, "p8", fout, desc) >= 2 * x.size  # the digit planes of the input
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", fout, bias=to_dev(bias))
+    _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, "p8", fout, bias=bias), "conv fwd")
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", fout)
+    _assert_equal(to_np(dx, fout), fast.conv2d_bwd_data(dy, w, d, "p8", fout), "conv bwd_data")
+    # NaR among the weights and in the bias
+    w2, b2 = w.copy(), bias.copy()
+    w2[1, d["C"] - 1, d["R"] - 1, 0] = 0x80
+    w2[d["K"] - 1, 0, 0, d["S"] - 1] = 0x80
+    b2[2] = 0x80
+    y2 = to_np(pn.posit_conv2d_fwd(to_dev(x), to_dev(w2), desc, "p8", fout, bias=to_dev(b2)), fout)
+    _assert_equal(y2, fast.conv2d_fwd(x, w2, d, "p8", fout, bias=b2), "conv fwd, NaR weights")
+    onar = 1 << (BITS[fout] - 1)
+    assert (y2[:, 1] == onar).all() and (y2[:, 2] == onar).all() and (y2[:, d["K"] - 1] == onar).all()
+    dx2 = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w2), desc, "p8", fout)
+    _assert_equal(to_np(dx2, fout), fast.conv2d_bwd_data(dy, w2, d, "p8", fout), "conv bwd_data, NaR weights")
+
+
 @pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p8_2", "p8_2"), ("p8_1", "p12_2"), ("p16", "p16"), ("p12_2", "p8_2"), ("p32", "p32")])
 @pytest.mark.parametrize("geom", ["unit stride (operands rewritten)", "pad beyond the filter (byte gather)", "strided (generic kernel)"])
 def test_conv_bwd_data_nar_weight_reaches_only_its_taps_positions(fin, fout, geom):
