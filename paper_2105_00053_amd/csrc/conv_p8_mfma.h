@@ -422,4 +422,175 @@ inline hipError_t launch_p8_conv_mfma(hipStream_t stream, const P8ConvMfmaPlan& 
     return hipGetLastError();
 }
 
+
+// ---- backward-weight: dw[k][c][r][s] = sum over (n, oh, ow) of dy[n][k][oh][ow] x[n][c][oh sh + r - ph][ow sw + s - pw] ----
+//
+// A matrix product with few outputs (K x CRS) and a long reduction (the positions).  The matrix instruction wants 16
+// consecutive reduction indices per lane, here 16 consecutive positions of one channel: runs of dy as it lies in
+// memory, but runs of x shifted by the tap and cut by the padding.  So this pass does unfold: one launch writes the digit
+// planes of dy (rows k) and of the unfolded input (rows (c, r, s), zeros where the tap leaves the tensor) in the
+// layout of the matrix product kernel, [k block][row block][digit][lane][16 bytes], and that kernel runs in its split
+// form, a few hundred slices of the positions per output tile, merged by the usual launch.  The unfolded planes are
+// 2 R S times the input, written and read once; that traffic, not the matrix cores, sets the time.
+
+struct __attribute__((packed, aligned(1))) P8Run16 { uint32_t w[4]; };  // 16 bytes at any address
+
+struct P8ConvBwPlan {
+    bool ok;
+    ConvGeom g;
+    int M, N;                  // outputs: K x CRS
+    int64_t P;                 // reduction: N OH OW positions
+    int RBA, RBB, KB;          // padded extents in blocks of 32 (KB = splits * kb_per_split)
+    int splits, kb_per_split;
+    size_t a_bytes, b_bytes, part_bytes;
+    size_t total() const { return a_bytes + b_bytes + part_bytes; }
+};
+
+inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g) {
+    P8ConvBwPlan p;
+    p.ok = false;
+    p.g = g;
+    const int64_t crs = (int64_t)g.C * g.R * g.S;
+    p.P = (int64_t)g.N * g.OH * g.OW;
+    if (g.K < 16 || crs < 16 || crs > 65536 || g.K > 65536 || p.P < 4096 || p.P >= ((int64_t)1 << 30)) return p;
+    if ((int64_t)g.K * crs * p.P < ((int64_t)1 << 26)) return p;
+    if ((int64_t)g.N * g.C * g.H * g.W >= ((int64_t)1 << 31) || (int64_t)g.N * g.K * g.OH * g.OW >= ((int64_t)1 << 31)) return p;
+    p.M = g.K;
+    p.N = (int)crs;
+    const int tiles_m = (p.M + 63) / 64, tiles_n = (p.N + 63) / 64;
+    p.RBA = tiles_m * 2;
+    p.RBB = tiles_n * 2;
+    const int64_t kb_total = (p.P + 31) / 32;
+    int64_t splits = (1024 + tiles_m * tiles_n - 1) / (tiles_m * tiles_n);  // about four workgroups per compute unit
+    if (splits > kb_total / 8) splits = kb_total / 8;                        // at least 8 k blocks per slice
+    if (splits < 1) splits = 1;
+    int64_t kbps = (kb_total + splits - 1) / splits;
+    kbps = (kbps + PM_KSTEP - 1) / PM_KSTEP * PM_KSTEP;
+    splits = (kb_total + kbps - 1) / kbps;
+    p.splits = (int)splits;
+    p.kb_per_split = (int)kbps;
+    p.KB = (int)(splits * kbps);
+    p.a_bytes = (size_t)p.KB * p.RBA * 2048;
+    p.b_bytes = (size_t)p.KB * p.RBB * 2048;
+    if (p.a_bytes + p.b_bytes >= ((size_t)1 << 32)) return p;
+    p.part_bytes = ((size_t)p.splits * p.M * p.N + (size_t)p.splits * (p.M + p.N)) * 4;
+    p.ok = true;
+    return p;
+}
+
+// The first ablocks workgroups write the planes of dy, the rest those of the unfolded input.  One thread per
+// (k block, row block, lane): 16 consecutive positions of one row.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(256) void p8_conv_bw_digits_kernel(const uint8_t* __restrict__ dy, const uint8_t* __restrict__ x, P8ConvBwPlan p,
+                                                                uint8_t* __restrict__ Ad, uint8_t* __restrict__ Bd, unsigned ablocks) {
+    __shared__ int16_t tab[256];
+    const int t = threadIdx.x;
+    tab[t] = t == 0x80 ? (int16_t)(PM_NAR_HI * 128) : (int16_t)Arith<P8>::stage((uint32_t)t);
+    __syncthreads();
+    const ConvGeom& g = p.g;
+    const int ohw = g.OH * g.OW;
+    const bool first = blockIdx.x < ablocks;
+    const int RB = first ? p.RBA : p.RBB;
+    const int64_t idx = (int64_t)(first ? blockIdx.x : blockIdx.x - ablocks) * 256 + t;
+    if (idx >= (int64_t)p.KB * RB * 64) return;
+    const int lane = (int)(idx & 63);
+    const int rb = (int)((idx >> 6) % RB), kb = (int)((idx >> 6) / RB);
+    const int row = rb * 32 + (lane & 31);
+    const int64_t p0 = (int64_t)kb * 32 + 16 * (lane >> 5);
+    uint32_t pat[16];
+#pragma unroll
+    for (int b = 0; b < 16; ++b) pat[b] = 0;
+    if (p0 < p.P && row < (first ? p.M : p.N)) {
+        int img = (int)(p0 / ohw);
+        int rem = (int)(p0 - (int64_t)img * ohw);
+        if (first) {
+            const uint8_t* q = dy + ((int64_t)img * g.K + row) * ohw + rem;
+            if (rem + 16 <= ohw && ((uintptr_t)q & 15u) == 0) {  // within one image (hence within the tensor), aligned
+                const uint4 v = *reinterpret_cast<const uint4*>(q);
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int b = 0; b < 16; ++b) pat[b] = (wv[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+            } else {
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    if (p0 + b < p.P) pat[b] = dy[((int64_t)img * g.K + row) * ohw + rem];
+                    if (++rem == ohw) { rem = 0; ++img; }
+                }
+            }
+        } else {
+            const int rs = g.R * g.S;
+            const int c = row / rs, tp = row - c * rs;
+            const int r = tp / g.S, s = tp - r * g.S;
+            int oh = rem / g.OW, ow = rem - oh * g.OW;
+            // Unit stride and the 16 positions in one output row: they read 16 consecutive bytes of one input row, cut
+            // by at most a few columns of padding at either end.  One 16-byte load (of any alignment) from the nearest
+            // start inside the row, shifted by the bytes that fall into the padding.
+            const int iw0 = ow + s - g.pw;
+            const int start = iw0 < 0 ? 0 : (iw0 + 16 > g.W ? g.W - 16 : iw0);
+            const int d = iw0 - start;  // < 0: the run begins in the left padding; > 0: it ends in the right padding
+            if (g.sw == 1 && g.W >= 16 && ow + 16 <= g.OW && p0 + 16 <= p.P && d >= -3 && d <= 3) {
+                const int ih = oh * g.sh + r - g.ph;
+                if ((unsigned)ih < (unsigned)g.H) {
+                    const P8Run16 v = *reinterpret_cast<const P8Run16*>(x + (((int64_t)img * g.C + c) * g.H + ih) * g.W + start);
+                    uint32_t wv[4] = {v.w[0], v.w[1], v.w[2], v.w[3]};
+                    if (d < 0) {
+                        const int sh = -8 * d;
+#pragma unroll
+                        for (int i = 3; i >= 0; --i) wv[i] = (wv[i] << sh) | (i > 0 ? wv[i - 1] >> (32 - sh) : 0u);
+                    } else if (d > 0) {
+                        const int sh = 8 * d;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) wv[i] = (wv[i] >> sh) | (i < 3 ? wv[i + 1] << (32 - sh) : 0u);
+                    }
+#pragma unroll
+                    for (int b = 0; b < 16; ++b) pat[b] = (wv[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+                }  // a row of padding: zeros
+            } else {
+#pragma unroll
+                for (int b = 0; b < 16; ++b) {
+                    const int ih = oh * g.sh + r - g.ph, iw = ow * g.sw + s - g.pw;
+                    if (p0 + b < p.P && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W)
+                        pat[b] = x[(((int64_t)img * g.C + c) * g.H + ih) * g.W + iw];
+                    if (++ow == g.OW) {
+                        ow = 0;
+                        if (++oh == g.OH) { oh = 0; ++img; }
+                    }
+                }
+            }
+        }
+    }
+    uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < 16; ++b) {
+        const int v = tab[pat[b]];
+        hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
+        lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
+    }
+    uint4* out = reinterpret_cast<uint4*>(first ? Ad : Bd) + ((int64_t)(kb * RB + rb) * 2) * 64 + lane;
+    out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+    out[64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+}
+
+// workspace: [planes of dy][planes of the unfolded input][partial sums and flags of the slices]
+inline hipError_t launch_p8_conv_bw_mfma(hipStream_t stream, const P8ConvBwPlan& p, const void* dy, const void* x, void* dw, int fout,
+                                         void* workspace) {
+    uint8_t* base = (uint8_t*)workspace;
+    uint8_t* Ad = base;
+    uint8_t* Bd = base + p.a_bytes;
+    SplitWs ws;
+    ws.limbs = reinterpret_cast<uint32_t*>(base + p.a_bytes + p.b_bytes);
+    ws.rowflag = ws.limbs + (size_t)p.splits * p.M * p.N;
+    ws.colflag = ws.rowflag + (size_t)p.splits * p.M;
+    const unsigned ablocks = (unsigned)(((int64_t)p.KB * p.RBA * 64 + 255) / 256), bblocks = (unsigned)(((int64_t)p.KB * p.RBB * 64 + 255) / 256);
+    hipLaunchKernelGGL(p8_conv_bw_digits_kernel<0>, dim3(ablocks + bblocks), dim3(256), 0, stream, (const uint8_t*)dy, (const uint8_t*)x, p, Ad, Bd,
+                       ablocks);
+    PNN_CHECK_LAUNCH();
+    const int tiles_m = p.RBA / 2, tiles_n = p.RBB / 2;
+    hipLaunchKernelGGL((p8_mfma_gemm_kernel<1, 1, true>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)p.splits), dim3(256), 0, stream, Ad, Bd, p.RBA,
+                       p.RBB, p.KB, (const uint8_t*)nullptr, (void*)nullptr, (int64_t)0, fout, p.M, p.N, tiles_m, tiles_n, p.kb_per_split, ws);
+    PNN_CHECK_LAUNCH();
+    RowMajorOut out{(int64_t)p.N};
+    return launch_split_merge<P8, RowMajorOut>(stream, ws, p.splits, p.M, p.N, nullptr, dw, fout, out);
+}
+
 }  // namespace pnn

@@ -126,10 +126,14 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
 
 // Ad / Bd: digit planes of p8_digits_kernel with RBA / RBB row blocks (multiples of 2 BI / 2 BJ) and KB k blocks (a
 // multiple of PM_KSTEP).  Four waves as 2 x 2; a wave owns BI x BJ blocks of 32 x 32 outputs, the workgroup 64 BI x 64 BJ.
-template <int BI, int BJ>
+//
+// SPLIT: workgroup (tile, z) reduces the kb_per_split k blocks from z kb_per_split on and leaves its 32-bit sums and
+// its NaR verdicts in the workspace of a split reduction (ws: partial quires [z][M N], row flags [z][M], column flags
+// [z][N]); the merging launch adds, rounds and stores.  For products with few output tiles and a long reduction.
+template <int BI, int BJ, bool SPLIT = false>
 __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) void p8_mfma_gemm_kernel(
     const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, int RBA, int RBB, int KB, const uint8_t* __restrict__ bias, void* __restrict__ C,
-    int64_t ldc, int fout, int M, int N, int tiles_m, int tiles_n) {
+    int64_t ldc, int fout, int M, int N, int tiles_m, int tiles_n, int kb_per_split = 0, SplitWs ws = SplitWs{nullptr, nullptr, nullptr}) {
     constexpr int NA = 2 * BI * 2, NB = 2 * BJ * 2;  // runs of 1 KB (row block, digit) per k block and operand
     constexpr int TR = 64 * BI, TC = 64 * BJ;        // tile extents
     // [buffer][k block of the step][A runs, then B runs][lane]: 64 KB for 128 x 128 outputs
@@ -178,6 +182,7 @@ __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) voi
         const bool isb = sub >= NA;
         src[c] = isb ? gb + kk * b_kb + (sub - NA) * 64 : ga + kk * a_kb + sub * 64;
         adv[c] = PM_KSTEP * (isb ? b_kb : a_kb);
+        if (SPLIT) src[c] += (int64_t)blockIdx.y * kb_per_split * (isb ? b_kb : a_kb);
     }
     auto issue = [&](int buf) {
 #pragma unroll
@@ -197,8 +202,9 @@ __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) voi
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's runs are in LDS
     __syncthreads();
     int cur = 0;
-    for (int kb0 = 0; kb0 < KB; kb0 += PM_KSTEP, cur ^= 1) {
-        if (kb0 + PM_KSTEP < KB) issue(cur ^ 1);  // the other buffer was last read one barrier ago
+    const int nkb = SPLIT ? kb_per_split : KB;
+    for (int kb0 = 0; kb0 < nkb; kb0 += PM_KSTEP, cur ^= 1) {
+        if (kb0 + PM_KSTEP < nkb) issue(cur ^ 1);  // the other buffer was last read one barrier ago
 #pragma unroll
         for (int kk = 0; kk < PM_KSTEP; ++kk) {
             pm_v4i ah[BI], al[BI], bh[BJ], bl[BJ];
@@ -246,6 +252,28 @@ __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) voi
         colv[(wx * BJ + jb) * 32 + lane] = col_nar;
     }
     __syncthreads();
+    if (SPLIT) {
+        const int64_t z = blockIdx.y;
+        // the first tile column stores the row flags of its tile row (the same in every column), the first tile row the
+        // column flags: every entry is written, so the workspace needs no clearing
+        if (tn == 0 && t < TR && tm * TR + t < M) ws.rowflag[z * M + tm * TR + t] = rowv[t];
+        if (tm == 0 && t < TC && tn * TC + t < N) ws.colflag[z * N + tn * TC + t] = colv[t];
+        uint32_t* lim = ws.limbs + z * (int64_t)M * N;
+#pragma unroll
+        for (int j = 0; j < BJ; ++j) {
+            const int n = tn * TC + (wx * BJ + j) * 32 + (lane & 31);
+            if (n >= N) continue;
+#pragma unroll
+            for (int i = 0; i < BI; ++i) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int m = tm * TR + (wy * BI + i) * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+                    if (m < M) lim[(int64_t)m * N + n] = ((uint32_t)hh[i][j][r] << 14) + ((uint32_t)xx[i][j][r] << 7) + (uint32_t)ll[i][j][r];
+                }
+            }
+        }
+        return;
+    }
     rowv += wy * 32 * BI;
     colv += wx * 32 * BJ;
     const int m_base = tm * TR + wy * 32 * BI, n_base = tn * TC + wx * 32 * BJ;
@@ -328,7 +356,7 @@ inline hipError_t launch_p8_mfma_gemm(hipStream_t stream, int transA, int transB
     const dim3 grid((unsigned)(tiles_m * tiles_n));
 #define PNN_PM_LAUNCH(bi, bj)                                                                                                                    \
     hipLaunchKernelGGL((p8_mfma_gemm_kernel<bi, bj>), grid, dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M, (int)N, \
-                       tiles_m, tiles_n)
+                       tiles_m, tiles_n, 0, SplitWs{nullptr, nullptr, nullptr})
     if (l.BI == 2 && l.BJ == 2) PNN_PM_LAUNCH(2, 2);
     else if (l.BI == 2) PNN_PM_LAUNCH(2, 1);
     else if (l.BJ == 2) PNN_PM_LAUNCH(1, 2);

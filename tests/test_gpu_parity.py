@@ -581,7 +581,8 @@ def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
     planes pixel-major in groups of 16 channels, gathered tap by tap.  Channel counts that do not fill a group, 64 x 64,
     64 x 128 and 128 x 64 tiles, ragged position counts, filters 2 x 3 and 5 x 5, no padding and padding beyond the
     filter's half, NaR in the input (every output whose window holds it), a NaR weight (forward: its whole output
-    channel, padding counts as an operand; backward-data: the positions its tap reaches), a NaR bias."""
+    channel, padding counts as an operand; backward-data: the positions its tap reaches), a NaR bias.  Backward-weight
+    runs there too, as a matrix product over unfolded digit planes with the positions cut into slices."""
     d = geom
     rng = np.random.default_rng(d["C"] * 7 + d["K"])
     oh, ow = fast.out_hw(d)
@@ -595,6 +596,18 @@ def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
     _assert_equal(to_np(y, fout), fast.conv2d_fwd(x, w, d, "p8", fout, bias=bias), "conv fwd")
     dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", fout)
     _assert_equal(to_np(dx, fout), fast.conv2d_bwd_data(dy, w, d, "p8", fout), "conv bwd_data")
+    # backward-weight: the positions are the reduction, cut into slices; dy and the unfolded input as digit planes
+    # (every output sums over all positions: one NaR each in dy and x, or nothing but NaR would come out)
+    dyw, xw = dy.copy(), x.copy()
+    dyw[dyw == 0x80] = 0x41
+    xw[xw == 0x80] = 0xC3
+    dyw[0, 3, 1, 1] = 0x80
+    xw[1, 2, 5, 5] = 0x80
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dyw), to_dev(xw), desc, "p8", "p16", with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dyw, xw, d, "p8", "p16", with_bias=True)
+    _assert_equal(to_np(dw, "p16"), wdw, "conv bwd_weight")
+    _assert_equal(to_np(db, "p16"), wdb, "conv bias gradient")
+    assert (wdw[3] == 0x8000).all() and (wdw[:, 2] == 0x8000).any() and not (wdw[4] == 0x8000).all()
     # NaR among the weights and in the bias
     w2, b2 = w.copy(), bias.copy()
     w2[1, d["C"] - 1, d["R"] - 1, 0] = 0x80
