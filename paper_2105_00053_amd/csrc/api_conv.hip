@@ -140,7 +140,7 @@ size_t conv_ws(int which, const ConvGeom& g) {
         const P8ConvMfmaPlan mp = p8_conv_mfma_plan(which, g);
         if (mp.ok) b = mp.total();
         if (which == 2) {
-            const P8ConvBwPlan bp = p8_conv_bw_plan(g);
+            const P8ConvBwPlan bp = p8_conv_bw_plan(g, true);
             if (bp.ok) b = bp.total();
         }
     }
@@ -259,12 +259,10 @@ int conv_bwd_weight(hipStream_t st, int fout, const ConvGeom& g, const void* dy,
     GemmPlan plan = conv_plan<F>(d);
     P8ConvProblem p8p;
     if (fastp8) {
-        const P8ConvBwPlan bp = p8_conv_bw_plan(g);
-        if (bp.ok) {  // integer matrix cores, split reduction
-            if (!ws || ws_bytes < bp.total() || (dbias && ws_bytes < bias_ws)) return PNN_EWORKSPACE;
-            hipError_t pe = launch_p8_conv_bw_mfma(st, bp, dy, x, dw, fout, ws);
-            if (pe == hipSuccess && dbias) pe = launch_bias_grad<F>(st, dy, dbias, fout, g.N, g.K, g.OH * g.OW, ws);
-            return hip_status(pe);
+        const P8ConvBwPlan bp = p8_conv_bw_plan(g, dbias != nullptr);
+        if (bp.ok) {  // integer matrix cores, split reduction; the bias gradient rides along as a column of ones
+            if (!ws || ws_bytes < bp.total()) return PNN_EWORKSPACE;
+            return hip_status(launch_p8_conv_bw_mfma(st, bp, dy, x, dw, dbias, fout, ws));
         }
         P8PrePlan pp;
         GemmPlan pplan;

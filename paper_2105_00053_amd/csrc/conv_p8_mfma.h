@@ -438,7 +438,8 @@ struct __attribute__((packed, aligned(1))) P8Run16 { uint32_t w[4]; };  // 16 by
 struct P8ConvBwPlan {
     bool ok;
     ConvGeom g;
-    int M, N;                  // outputs: K x CRS
+    int M, N;                  // outputs: K x CRS, or K x (CRS + 1) with the bias gradient as the last column
+    int crs;
     int64_t P;                 // reduction: N OH OW positions
     int RBA, RBB, KB;          // padded extents in blocks of 32 (KB = splits * kb_per_split)
     int splits, kb_per_split;
@@ -446,7 +447,7 @@ struct P8ConvBwPlan {
     size_t total() const { return a_bytes + b_bytes + part_bytes; }
 };
 
-inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g) {
+inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g, bool with_bias) {
     P8ConvBwPlan p;
     p.ok = false;
     p.g = g;
@@ -456,7 +457,8 @@ inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g) {
     if ((int64_t)g.K * crs * p.P < ((int64_t)1 << 26)) return p;
     if ((int64_t)g.N * g.C * g.H * g.W >= ((int64_t)1 << 31) || (int64_t)g.N * g.K * g.OH * g.OW >= ((int64_t)1 << 31)) return p;
     p.M = g.K;
-    p.N = (int)crs;
+    p.crs = (int)crs;
+    p.N = (int)crs + (with_bias ? 1 : 0);  // db[k] = sum over the positions of dy[k] * 1: a column of ones
     const int tiles_m = (p.M + 63) / 64, tiles_n = (p.N + 63) / 64;
     p.RBA = tiles_m * 2;
     p.RBB = tiles_n * 2;
@@ -518,6 +520,10 @@ __global__ __launch_bounds__(256) void p8_conv_bw_digits_kernel(const uint8_t* _
                 }
             }
         } else {
+            if (row == p.crs) {  // the column of ones behind the unfolded input
+#pragma unroll
+                for (int b = 0; b < 16; ++b) pat[b] = p0 + b < p.P ? 0x40u : 0u;
+            }
             const int rs = g.R * g.S;
             const int c = row / rs, tp = row - c * rs;
             const int r = tp / g.S, s = tp - r * g.S;
@@ -528,7 +534,8 @@ __global__ __launch_bounds__(256) void p8_conv_bw_digits_kernel(const uint8_t* _
             const int iw0 = ow + s - g.pw;
             const int start = iw0 < 0 ? 0 : (iw0 + 16 > g.W ? g.W - 16 : iw0);
             const int d = iw0 - start;  // < 0: the run begins in the left padding; > 0: it ends in the right padding
-            if (g.sw == 1 && g.W >= 16 && ow + 16 <= g.OW && p0 + 16 <= p.P && d >= -3 && d <= 3) {
+            if (row == p.crs) {
+            } else if (g.sw == 1 && g.W >= 16 && ow + 16 <= g.OW && p0 + 16 <= p.P && d >= -3 && d <= 3) {
                 const int ih = oh * g.sh + r - g.ph;
                 if ((unsigned)ih < (unsigned)g.H) {
                     const P8Run16 v = *reinterpret_cast<const P8Run16*>(x + (((int64_t)img * g.C + c) * g.H + ih) * g.W + start);
@@ -572,8 +579,8 @@ __global__ __launch_bounds__(256) void p8_conv_bw_digits_kernel(const uint8_t* _
 }
 
 // workspace: [planes of dy][planes of the unfolded input][partial sums and flags of the slices]
-inline hipError_t launch_p8_conv_bw_mfma(hipStream_t stream, const P8ConvBwPlan& p, const void* dy, const void* x, void* dw, int fout,
-                                         void* workspace) {
+inline hipError_t launch_p8_conv_bw_mfma(hipStream_t stream, const P8ConvBwPlan& p, const void* dy, const void* x, void* dw, void* dbias,
+                                         int fout, void* workspace) {
     uint8_t* base = (uint8_t*)workspace;
     uint8_t* Ad = base;
     uint8_t* Bd = base + p.a_bytes;
@@ -589,6 +596,10 @@ inline hipError_t launch_p8_conv_bw_mfma(hipStream_t stream, const P8ConvBwPlan&
     hipLaunchKernelGGL((p8_mfma_gemm_kernel<1, 1, true>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)p.splits), dim3(256), 0, stream, Ad, Bd, p.RBA,
                        p.RBB, p.KB, (const uint8_t*)nullptr, (void*)nullptr, (int64_t)0, fout, p.M, p.N, tiles_m, tiles_n, p.kb_per_split, ws);
     PNN_CHECK_LAUNCH();
+    if (p.N > p.crs) {
+        WeightAndBiasOut out{(int64_t)p.crs, dbias};
+        return launch_split_merge<P8, WeightAndBiasOut>(stream, ws, p.splits, p.M, p.N, nullptr, dw, fout, out);
+    }
     RowMajorOut out{(int64_t)p.N};
     return launch_split_merge<P8, RowMajorOut>(stream, ws, p.splits, p.M, p.N, nullptr, dw, fout, out);
 }

@@ -178,6 +178,29 @@ struct NchwOut {
     }
 };
 
+// Backward-weight of a convolution with the bias gradient as one more column (the product of dy with a column of
+// ones): columns below `weights` go to the weight gradient, row-major with that pitch; column `weights` to bias_grad[row].
+struct WeightAndBiasOut {
+    int64_t weights;
+    void* bias_grad;
+    __device__ __forceinline__ int64_t operator()(int64_t row, int64_t col) const { return row * weights + col; }
+};
+
+// Where a merged output goes: the tensor C at the functor's index, unless the functor names another tensor.
+template <class Out>
+__device__ __forceinline__ void* merge_dest(const Out& out, void* C, int64_t m, int64_t n, int64_t& at) {
+    at = out(m, n);
+    return C;
+}
+__device__ __forceinline__ void* merge_dest(const WeightAndBiasOut& out, void* C, int64_t m, int64_t n, int64_t& at) {
+    if (n == out.weights) {
+        at = m;
+        return out.bias_grad;
+    }
+    at = out(m, n);
+    return C;
+}
+
 // Workspace layout for a split reduction, per split z:
 //   limbs  [z][M*N][L] uint32   partial quires
 //   rowflag[z][M], colflag[z][N] uint32   NaR seen in that row of A / column of B
@@ -464,7 +487,9 @@ __global__ __launch_bounds__(256) void split_merge_kernel(SplitWs ws, int splits
         if (bp == FIN::NAR) isnar = true;
         else AR::add_value(q, AR::stage(bp));
     }
-    round_store<QuireAccum<FIN>, L>(q, isnar, fout, C, out(m, n));
+    int64_t at;
+    void* dst = merge_dest(out, C, m, n, at);
+    round_store<QuireAccum<FIN>, L>(q, isnar, fout, dst, at);
 }
 
 // Bias gradient of a convolution (the row sum of the backward-weight pass against a column of
