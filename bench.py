@@ -142,6 +142,27 @@ def extra_measurements(torch, pn, workloads):
         ws = torch.empty(max(16, pn.posit_gemm_workspace(fmt, fmt, False, False, S, S, S)), dtype=torch.uint8, device="cuda")
         ms = _time_ms(torch, lambda: pn.posit_gemm(Ap, Bp, fmt, fmt, out=C, workspace=ws), 10 if fmt != "p32" else 3)
         out["gemm_%s_%d" % (fmt, S)] = {"ms": round(ms, 4), "TMAC/s": round(S ** 3 / ms / 1e9, 3)}
+    # posit<8,0> convolutions, the three passes: two layers of the CifarNet-shaped net (batch 128) and a 64-channel
+    # 56 x 56 layer at batch 256; 3 x 3 filters, padding 1, whole calls (operand rewriting and merging launches included)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(2105000536)
+    for N, C, H, K in ((128, 32, 32, 32), (128, 64, 16, 64), (256, 64, 56, 64)):
+        d = pn.ConvDesc(N, C, H, H, K, 3, 3, 1, 1, 1, 1)
+        x = pn.posit_round(torch.randn((N, C, H, H), device="cuda", generator=gen), "p8")
+        w = pn.posit_round(torch.randn((K, C, 3, 3), device="cuda", generator=gen) * 0.2, "p8")
+        dy = pn.posit_round(torch.randn((N, K, H, H), device="cuda", generator=gen), "p8")
+        b = pn.posit_round(torch.randn((K,), device="cuda", generator=gen), "p8")
+        y, dx = torch.empty_like(dy), torch.empty_like(x)
+        dw, db = torch.empty((K, C, 3, 3), dtype=torch.uint16, device="cuda"), torch.empty((K,), dtype=torch.uint16, device="cuda")
+        wss = [torch.empty(max(16, pn.posit_conv2d_workspace(i, "p8", "p8" if i < 2 else "p16", d)), dtype=torch.uint8, device="cuda") for i in range(3)]
+        gmac = N * H * H * K * C * 9 / 1e9
+        entry = {"GMAC": round(gmac, 2)}
+        for name, fn in (("fwd", lambda: pn.posit_conv2d_fwd(x, w, d, "p8", "p8", bias=b, out=y, workspace=wss[0])),
+                         ("bwd_data", lambda: pn.posit_conv2d_bwd_data(dy, w, d, "p8", "p8", out=dx, workspace=wss[1])),
+                         ("bwd_weight", lambda: pn.posit_conv2d_bwd_weight(dy, x, d, "p8", "p16", with_bias=True, out=dw, out_bias=db, workspace=wss[2]))):
+            ms = _time_ms(torch, fn, 10, warm=2)
+            entry[name] = {"ms": round(ms, 4), "TMAC/s": round(gmac / ms, 2)}
+        out["conv_p8_N%d_C%d_%dx%d_K%d_3x3" % (N, C, H, H, K)] = entry
     out.update(elementwise_measurements(torch, pn))
     final = dict(compute="p8_2", master="p12_2", loss="p10_2")  # Sec. 4, Table 4: the configuration the paper ends up with
     for name, net, fmts in (("lenet5_step_batch64", workloads.LENET, {}), ("cifarnet_step_batch128", workloads.CIFARNET, {}),
