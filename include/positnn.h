@@ -82,8 +82,10 @@ typedef enum {
  * bias (or zero).  `workspace` (device, 16-byte aligned, else PNN_EINVAL) must hold
  * at least posit_gemm_workspace(...) bytes (else PNN_EWORKSPACE); it may be NULL
  * when that query returns 0.  Its contents on entry do not matter and are not
- * preserved (partial quires of a split reduction; for posit<8,0> products of
- * more than 2^34 multiply-adds also both operands, decoded and packed). */
+ * preserved (partial quires of a split reduction; both operands rewritten once:
+ * for posit<8,0> products of 2^28 multiply-adds and more as two int8 digit planes
+ * each, 2 bytes per element; for posit<16,1> and the 10- / 12-bit formats from
+ * 96 x 96 outputs on as doubles, 8 bytes per element). */
 int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
                int64_t M, int64_t N, int64_t K,
                const void* A, int64_t lda, const void* B, int64_t ldb,
@@ -147,9 +149,11 @@ int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_de
 
 /* which: 0 = fwd, 1 = bwd_data, 2 = bwd_weight.  Bytes of workspace (0 = none) that the matching
  * call needs: device memory, 16-byte aligned (PNN_EINVAL otherwise), contents undefined on entry and
- * on return.  It holds the partial quires of a split reduction and, for posit<8,0> at unit stride,
- * the two operands rewritten once as decoded 16-bit integers with the zero border written out
- * (about twice the size of the tensors).  The calls of one stream may share one workspace.  The answer
+ * on return.  It holds the partial quires of a split reduction and, for posit<8,0>, the operands
+ * rewritten once: as decoded 16-bit integers with the zero border written out (about twice the size of
+ * the tensors), or, from 2^26 multiply-adds on, as int8 digit planes (forward and backward-data: twice
+ * the gathered tensor, channels padded to 16; backward-weight: 2 R S times the input, unfolded, plus
+ * twice dy).  The calls of one stream may share one workspace.  The answer
  * depends on which, fin and desc (fout is accepted for the same reason as in posit_gemm_workspace). */
 size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
 
