@@ -91,6 +91,16 @@ def test_argument_validation_without_launch():
     d = b.ConvDesc(1, 1, 4, 4, 1, 3, 3, 0, 0, 1, 1)
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, null, 0) == 3  # needs its workspace
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, ctypes.c_void_p(0x1004), 1 << 30) == EINVAL  # workspace alignment
+    # workspace of the posit<8,0> convolutions that run on the matrix cores (32 -> 32 channels, 32 x 32, batch 128, 3 x 3, pad 1):
+    # forward / backward-data: weight planes (9 k blocks x 1 row block x 2 KB) + input planes (131072 pixels x 2 groups of 16
+    # channels x 32 bytes) + 256 bytes of zeros; backward-weight: planes of dy (2 row blocks) and of the unfolded input with its
+    # column of ones (289 columns: 10 row blocks) over 205 slices of 20 k blocks, then the slices' partial sums and flags
+    d = b.ConvDesc(128, 32, 32, 32, 32, 3, 3, 1, 1, 1, 1)
+    assert L.posit_conv2d_workspace(0, 0, 0, ctypes.byref(d)) == 9 * 2048 + 131072 * 2 * 32 + 256
+    assert L.posit_conv2d_workspace(1, 0, 0, ctypes.byref(d)) == 9 * 2048 + 131072 * 2 * 32 + 256
+    assert L.posit_conv2d_workspace(2, 0, 1, ctypes.byref(d)) == 4100 * (2 + 10) * 2048 + (205 * 32 * 289 + 205 * (32 + 289)) * 4
+    d = b.ConvDesc(128, 32, 32, 32, 32, 3, 3, 1, 1, 2, 2)  # strided: forward keeps the dot-product kernel (no digit planes)
+    assert L.posit_conv2d_workspace(0, 0, 0, ctypes.byref(d)) < 131072 * 2 * 32
     # average pooling: the weight 1/(kh*kw) must be a posit of fin.  posit<8,0> stops at minpos = 1/64
     assert L.posit_avgpool2d_fwd(null, 0, 0, 1, 16, 16, 16, 8, fake, fake) == 2   # 1/128 < minpos
     assert L.posit_avgpool2d_bwd(null, 0, 0, 1, 16, 16, 16, 8, fake, fake) == 2
