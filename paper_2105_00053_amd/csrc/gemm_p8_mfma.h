@@ -33,10 +33,11 @@ namespace pnn {
 typedef int pm_v4i __attribute__((ext_vector_type(4)));
 typedef int pm_v16i __attribute__((ext_vector_type(16)));
 
-constexpr int PM_MIN_MN = 512;                   // smallest output extent each way
+constexpr int PM_MIN_MN = 128;                   // smallest output extent each way
 constexpr int64_t PM_MIN_MNK = (int64_t)1 << 28;  // smallest product count
 constexpr int PM_MIN_TILES = 81;                 // fewest 64 x 64 tiles: below, kernels that cut the reduction across workgroups win
 constexpr int PM_MIN_WGS = 512;                  // workgroups wanted before a larger tile is chosen
+constexpr int PM_MIN_KB_SPLIT = 16;              // fewest k blocks of 32 per slice
 constexpr int PM_KSTEP = 2;    // k blocks (of 32) per staged step
 constexpr int PM_NAR_HI = -128;  // high digit that marks NaR
 
@@ -314,13 +315,25 @@ __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) voi
 struct P8MfmaLayout {
     int BI, BJ;        // blocks of 32 per wave each way: the workgroup tile is 64 BI x 64 BJ
     int RBA, RBB, KB;  // padded extents in blocks of 32
-    size_t a_bytes, b_bytes;
-    size_t total() const { return a_bytes + b_bytes; }
+    int splits, kb_per_split;  // slices of the reduction (1: none) and their length in k blocks; KB = splits * kb_per_split
+    size_t a_bytes, b_bytes, part_bytes;
+    size_t total() const { return a_bytes + b_bytes + part_bytes; }
 };
 
+// Slices for a product with fewer than PM_MIN_TILES tiles of 64 x 64: about two workgroups per compute unit, each
+// slice at least PM_MIN_KB_SPLIT k blocks long; fewer than 2 means the split form does not serve the shape.
+inline int64_t p8_mfma_slices(int64_t M, int64_t N, int64_t K) {
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64), kb_total = (K + 31) / 32;
+    int64_t s = (PM_MIN_WGS + tiles - 1) / tiles;
+    if (s > kb_total / PM_MIN_KB_SPLIT) s = kb_total / PM_MIN_KB_SPLIT;
+    return s;
+}
+
 inline bool p8_mfma_fits(int64_t M, int64_t N, int64_t K) {
-    return M >= PM_MIN_MN && N >= PM_MIN_MN && K >= 256 && M * N * K >= PM_MIN_MNK && ((M + 63) / 64) * ((N + 63) / 64) >= PM_MIN_TILES && M <= ((int64_t)1 << 20) && N <= ((int64_t)1 << 20) &&
-           K <= ((int64_t)1 << 20);
+    if (K < 256 || M * N * K < PM_MIN_MNK || M > ((int64_t)1 << 20) || N > ((int64_t)1 << 20) || K > ((int64_t)1 << 20)) return false;
+    const int64_t tiles = ((M + 63) / 64) * ((N + 63) / 64);
+    if (tiles >= PM_MIN_TILES) return M >= PM_MIN_MN && N >= PM_MIN_MN;
+    return M >= PM_MIN_MN && N >= PM_MIN_MN && M * N < ((int64_t)1 << 24) && p8_mfma_slices(M, N, K) >= 2;
 }
 
 // The largest tile that still gives every compute unit two workgroups; 64 x 64 otherwise.
@@ -335,6 +348,20 @@ inline P8MfmaLayout p8_mfma_layout(int64_t M, int64_t N, int64_t K) {
     l.RBA = (int)cdiv(M, 64 * l.BI) * 2 * l.BI;
     l.RBB = (int)cdiv(N, 64 * l.BJ) * 2 * l.BJ;
     l.KB = (int)cdiv(K, 32 * PM_KSTEP) * PM_KSTEP;
+    l.splits = 1;
+    l.kb_per_split = l.KB;
+    l.part_bytes = 0;
+    if (cdiv(M, 64) * cdiv(N, 64) < PM_MIN_TILES) {  // few outputs, long reduction: 64 x 64 tiles (chosen above), slices of k blocks
+        const int64_t kb_total = cdiv(K, 32);
+        int64_t splits = p8_mfma_slices(M, N, K);
+        if (splits < 1) splits = 1;
+        int64_t kbps = cdiv(cdiv(kb_total, splits), PM_KSTEP) * PM_KSTEP;
+        splits = cdiv(kb_total, kbps);
+        l.splits = (int)splits;
+        l.kb_per_split = (int)kbps;
+        l.KB = (int)(splits * kbps);
+        l.part_bytes = splits > 1 ? ((size_t)splits * M * N + (size_t)splits * (M + N)) * 4 : 0;
+    }
     l.a_bytes = (size_t)l.KB * l.RBA * 2048;
     l.b_bytes = (size_t)l.KB * l.RBB * 2048;
     return l;
@@ -353,6 +380,17 @@ inline hipError_t launch_p8_mfma_gemm(hipStream_t stream, int transA, int transB
     hipLaunchKernelGGL(p8_digits_kernel<0>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
     const int tiles_m = l.RBA / (2 * l.BI), tiles_n = l.RBB / (2 * l.BJ);
+    if (l.splits > 1) {
+        SplitWs ws;
+        ws.limbs = reinterpret_cast<uint32_t*>(base + l.a_bytes + l.b_bytes);
+        ws.rowflag = ws.limbs + (size_t)l.splits * M * N;
+        ws.colflag = ws.rowflag + (size_t)l.splits * M;
+        hipLaunchKernelGGL((p8_mfma_gemm_kernel<1, 1, true>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)l.splits), dim3(256), 0, stream, Ad, Bd, l.RBA,
+                           l.RBB, l.KB, (const uint8_t*)nullptr, (void*)nullptr, (int64_t)0, fout, (int)M, (int)N, tiles_m, tiles_n, l.kb_per_split, ws);
+        PNN_CHECK_LAUNCH();
+        RowMajorOut out{ldc};
+        return launch_split_merge<P8, RowMajorOut>(stream, ws, l.splits, M, N, bias, C, fout, out);
+    }
     const dim3 grid((unsigned)(tiles_m * tiles_n));
 #define PNN_PM_LAUNCH(bi, bj)                                                                                                                    \
     hipLaunchKernelGGL((p8_mfma_gemm_kernel<bi, bj>), grid, dim3(256), 0, stream, Ad, Bd, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M, (int)N, \

@@ -418,14 +418,16 @@ def test_config5_p8_gemm_large_full(S):
 @pytest.mark.parametrize("M,N,K,ta,tb,fout", [(2100, 2050, 4000, 0, 0, "p8"), (2048, 2176, 4100, 1, 0, "p16"), (2300, 2048, 3999, 0, 1, "p8"),
                                               (2050, 2100, 4033, 1, 1, "p8"), (1100, 1030, 16400, 0, 0, "p8"),
                                               (600, 540, 1700, 0, 0, "p8"), (2200, 1900, 300, 1, 0, "p8"), (1900, 2200, 290, 0, 1, "p16"),
-                                              (1030, 1025, 1024, 1, 1, "p8")])
+                                              (1030, 1025, 1024, 1, 1, "p8"), (200, 300, 9000, 0, 1, "p8"), (384, 640, 2100, 1, 0, "p16"),
+                                              (130, 4100, 600, 0, 0, "p8")])
 def test_p8_gemm_packed_operands_path(M, N, K, ta, tb, fout):
-    """Products of 2^28 MACs and more (outputs at least 512 each way, 81 tiles of 64 x 64) first rewrite both operands into the workspace (int8 digit planes in the lane
+    """Products of 2^28 MACs and more (outputs at least 128 each way) first rewrite both operands into the workspace (int8 digit planes in the lane
     order of the matrix instruction, NaR as a marker digit) and run on the matrix cores: ragged sizes, the four
     transposition cases (an operand stored reduction-index-major is transposed through LDS), NaR in rows and columns
-    near the edges, a bias, a workspace full of ones; the last four cases take the 64 x 64, 128 x 64 and 64 x 128 tiles
-    chosen when 128 x 128 would leave compute units idle.  Sampled rows against the oracle, the NaR rows and columns in full."""
-    assert M * N * K >= 1 << 28 and min(M, N) >= 512 and -(-M // 64) * -(-N // 64) >= 81
+    near the edges, a bias, a workspace full of ones; the cases after the first five take the 64 x 64, 128 x 64 and
+    64 x 128 tiles chosen when 128 x 128 would leave compute units idle, two of them (fewer than 81 tiles of 64 x 64) the
+    split form: slices of the reduction per tile, merged by a second launch; the last is 130 rows thin.  Sampled rows against the oracle, the NaR rows and columns in full."""
+    assert M * N * K >= 1 << 28 and min(M, N) >= 128
     assert pn.posit_gemm_workspace("p8", fout, ta, tb, M, N, K) >= 4 * (K // 2) * (M + N)
     rng = np.random.default_rng(M + K)
     A = rand_patterns(rng, (K, M) if ta else (M, K), "p8", special=0.001, allow_nar=False)
