@@ -425,26 +425,28 @@ inline hipError_t launch_p8_conv_mfma(hipStream_t stream, const P8ConvMfmaPlan& 
 
 // ---- backward-weight: dw[k][c][r][s] = sum over (n, oh, ow) of dy[n][k][oh][ow] x[n][c][oh sh + r - ph][ow sw + s - pw] ----
 //
-// A matrix product with few outputs (K x CRS) and a long reduction (the positions).  The matrix instruction wants 16
-// consecutive reduction indices per lane, here 16 consecutive positions of one channel: runs of dy as it lies in
-// memory, but runs of x shifted by the tap and cut by the padding.  So this pass does unfold: one launch writes the digit
-// planes of dy (rows k) and of the unfolded input (rows (c, r, s), zeros where the tap leaves the tensor) in the
-// layout of the matrix product kernel, [k block][row block][digit][lane][16 bytes], and that kernel runs in its split
-// form, a few hundred slices of the positions per output tile, merged by the usual launch.  The unfolded planes are
-// 2 R S times the input, written and read once; that traffic, not the matrix cores, sets the time.
-
-struct __attribute__((packed, aligned(1))) P8Run16 { uint32_t w[4]; };  // 16 bytes at any address
+// A matrix product with few outputs (K x CRS) and a long reduction (image, position).  The matrix instruction wants 16
+// consecutive reduction indices per lane.  Ordered position-major, IMAGE-minor these are 16 images at one pixel, so the
+// pass is the forward kernel's gather with batch and channels trading places: one launch rewrites x as digit planes
+// [c][h][w][group of 16 images][digit][16 bytes] and dy in the row-block layout of the matrix kernel (rows k, reduction
+// index 16 ((oh OW + ow) NG + g) + image, through an LDS tile so that reads and writes are both contiguous); the product
+// kernel copies dy's runs from wave-uniform addresses and gathers x: lane (column (c, r, s), 16 reduction indices)
+// names the 16 bytes of pixel (oh sh + r - ph, ow sw + s - pw) of channel c and image group g, or a block of zeros in the
+// padding.  Nothing is unfolded; any stride.  The reduction is cut into slices ((tile, z) reduces kb_per_split k blocks,
+// about 512 workgroups in all) whose 32-bit sums and NaR verdicts the merging launch adds, rounds and stores.  The bias
+// gradient, db[k] = sum of dy[.][k][.][.] * 1, is one more column: its lanes gather a block that holds 1 for every image
+// of the group, and the merge routes the column to its own tensor.
 
 struct P8ConvBwPlan {
     bool ok;
     ConvGeom g;
-    int M, N;                  // outputs: K x CRS, or K x (CRS + 1) with the bias gradient as the last column
-    int crs;
-    int64_t P;                 // reduction: N OH OW positions
-    int RBA, RBB, KB;          // padded extents in blocks of 32 (KB = splits * kb_per_split)
+    int M, N, crs;             // outputs: K x CRS, or K x (CRS + 1) with the bias gradient as the last column
+    int NG;                    // groups of 16 images
+    int K16;                   // reduction length in 16s: OH OW NG
+    int RBA, RBB, KB;          // row blocks of dy's planes, column blocks, k blocks (= splits * kb_per_split)
     int splits, kb_per_split;
-    size_t a_bytes, b_bytes, part_bytes;
-    size_t total() const { return a_bytes + b_bytes + part_bytes; }
+    size_t a_bytes, x_bytes, ones_bytes, part_bytes;
+    size_t total() const { return a_bytes + x_bytes + ones_bytes + 256 + part_bytes; }
 };
 
 inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g, bool with_bias) {
@@ -452,149 +454,337 @@ inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g, bool with_bias) {
     p.ok = false;
     p.g = g;
     const int64_t crs = (int64_t)g.C * g.R * g.S;
-    p.P = (int64_t)g.N * g.OH * g.OW;
-    if (g.K < 16 || crs < 16 || crs > 65536 || g.K > 65536 || p.P < 4096 || p.P >= ((int64_t)1 << 30)) return p;
-    if ((int64_t)g.K * crs * p.P < ((int64_t)1 << 26)) return p;
-    if ((int64_t)g.N * g.C * g.H * g.W >= ((int64_t)1 << 31) || (int64_t)g.N * g.K * g.OH * g.OW >= ((int64_t)1 << 31)) return p;
+    const int64_t P = (int64_t)g.N * g.OH * g.OW;
+    if (g.K < 16 || crs < 16 || crs > 65536 || g.K > 65536 || P < 4096 || P >= ((int64_t)1 << 30)) return p;
+    if ((int64_t)g.K * crs * P < ((int64_t)1 << 26)) return p;
+    p.NG = (g.N + 15) / 16;
+    const int64_t k16 = (int64_t)g.OH * g.OW * p.NG;
+    if ((int64_t)g.C * g.H * g.W * p.NG * 2 >= ((int64_t)1 << 30) || k16 >= ((int64_t)1 << 28) || g.H > 16384 || g.W > 16384) return p;
+    p.K16 = (int)k16;
     p.M = g.K;
     p.crs = (int)crs;
-    p.N = (int)crs + (with_bias ? 1 : 0);  // db[k] = sum over the positions of dy[k] * 1: a column of ones
+    p.N = (int)crs + (with_bias ? 1 : 0);
     const int tiles_m = (p.M + 63) / 64, tiles_n = (p.N + 63) / 64;
     p.RBA = tiles_m * 2;
     p.RBB = tiles_n * 2;
-    const int64_t kb_total = (p.P + 31) / 32;
-    int64_t splits = (1024 + tiles_m * tiles_n - 1) / (tiles_m * tiles_n);  // about four workgroups per compute unit
+    const int64_t kb_total = (k16 + 1) / 2;
+    int64_t splits = (512 + tiles_m * tiles_n - 1) / (tiles_m * tiles_n);  // about two workgroups per compute unit (measured against one and four)
     if (splits > kb_total / 8) splits = kb_total / 8;                        // at least 8 k blocks per slice
     if (splits < 1) splits = 1;
-    int64_t kbps = (kb_total + splits - 1) / splits;
-    kbps = (kbps + PM_KSTEP - 1) / PM_KSTEP * PM_KSTEP;
+    const int64_t kbps = (kb_total + splits - 1) / splits;
     splits = (kb_total + kbps - 1) / kbps;
     p.splits = (int)splits;
     p.kb_per_split = (int)kbps;
     p.KB = (int)(splits * kbps);
     p.a_bytes = (size_t)p.KB * p.RBA * 2048;
-    p.b_bytes = (size_t)p.KB * p.RBB * 2048;
-    if (p.a_bytes + p.b_bytes >= ((size_t)1 << 32)) return p;
+    p.x_bytes = (size_t)g.C * g.H * g.W * p.NG * 32;
+    p.ones_bytes = (size_t)p.NG * 32;
+    if (p.a_bytes >= ((size_t)1 << 32)) return p;
     p.part_bytes = ((size_t)p.splits * p.M * p.N + (size_t)p.splits * (p.M + p.N)) * 4;
     p.ok = true;
     return p;
 }
 
-// The first ablocks workgroups write the planes of dy, the rest those of the unfolded input.  One thread per
-// (k block, row block, lane): 16 consecutive positions of one row.
-template <int UNUSED = 0>
+constexpr int PCB_PITCH = 68;  // bytes per row of the transposition tile: 64 positions + 4, so that rows fall on different banks
+
+// ablocks workgroups rewrite dy, the rest x (and the blocks of ones and zeros).
+//   dy: workgroup (row block rb, image group g, chunk of 64 positions) loads the 16 x 32 x 64 patterns with the positions
+//       along the lanes, keeps them in LDS, and writes, per position and row, the 16 images' digits: 512 contiguous bytes
+//       per position and digit in [k block][row block][digit][lane][16 bytes].  Positions beyond OH OW (up to the padded
+//       reduction length 2 KB) are written as zeros.
+//   x:  one thread per (channel, PX consecutive pixels, image group); 16 loads a pixel-plane apart, coalesced along the pixels.
+template <int PX>
 __global__ __launch_bounds__(256) void p8_conv_bw_digits_kernel(const uint8_t* __restrict__ dy, const uint8_t* __restrict__ x, P8ConvBwPlan p,
-                                                                uint8_t* __restrict__ Ad, uint8_t* __restrict__ Bd, unsigned ablocks) {
+                                                                uint8_t* __restrict__ Ad, uint8_t* __restrict__ xb, uint4* __restrict__ ones,
+                                                                uint4* __restrict__ zero, unsigned ablocks, int chunks) {
     __shared__ int16_t tab[256];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[16][32][PCB_PITCH];
     const int t = threadIdx.x;
     tab[t] = t == 0x80 ? (int16_t)(PM_NAR_HI * 128) : (int16_t)Arith<P8>::stage((uint32_t)t);
-    __syncthreads();
     const ConvGeom& g = p.g;
     const int ohw = g.OH * g.OW;
-    const bool first = blockIdx.x < ablocks;
-    const int RB = first ? p.RBA : p.RBB;
-    const int64_t idx = (int64_t)(first ? blockIdx.x : blockIdx.x - ablocks) * 256 + t;
-    if (idx >= (int64_t)p.KB * RB * 64) return;
-    const int lane = (int)(idx & 63);
-    const int rb = (int)((idx >> 6) % RB), kb = (int)((idx >> 6) / RB);
-    const int row = rb * 32 + (lane & 31);
-    const int64_t p0 = (int64_t)kb * 32 + 16 * (lane >> 5);
-    uint32_t pat[16];
+    if (blockIdx.x < ablocks) {
+        const int chunk = (int)(blockIdx.x % (unsigned)chunks);
+        const int gi = (int)((blockIdx.x / (unsigned)chunks) % (unsigned)p.NG);
+        const int rb = (int)(blockIdx.x / (unsigned)(chunks * p.NG));
+        // loads in batches of eight before their LDS stores, so that eight are in flight per thread
+        if (ohw % 4 == 0 && ((uintptr_t)dy & 3u) == 0) {  // four positions per load
+#pragma unroll 1
+            for (int base = 0; base < 32; base += 8) {
+                uint32_t v[8];
 #pragma unroll
-    for (int b = 0; b < 16; ++b) pat[b] = 0;
-    if (p0 < p.P && row < (first ? p.M : p.N)) {
-        int img = (int)(p0 / ohw);
-        int rem = (int)(p0 - (int64_t)img * ohw);
-        if (first) {
-            const uint8_t* q = dy + ((int64_t)img * g.K + row) * ohw + rem;
-            if (rem + 16 <= ohw && ((uintptr_t)q & 15u) == 0) {  // within one image (hence within the tensor), aligned
-                const uint4 v = *reinterpret_cast<const uint4*>(q);
-                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+                for (int u = 0; u < 8; ++u) {
+                    const int item = (base + u) * 256 + t;
+                    const int pair = item >> 4, q4 = item & 15;
+                    const int img = gi * 16 + (pair >> 5), row = rb * 32 + (pair & 31), pos = chunk * 64 + q4 * 4;
+                    v[u] = (img < g.N && row < g.K && pos < ohw) ? *reinterpret_cast<const uint32_t*>(dy + ((int64_t)img * g.K + row) * ohw + pos) : 0u;
+                }
 #pragma unroll
-                for (int b = 0; b < 16; ++b) pat[b] = (wv[b >> 2] >> (8 * (b & 3))) & 0xFFu;
-            } else {
-#pragma unroll
-                for (int b = 0; b < 16; ++b) {
-                    if (p0 + b < p.P) pat[b] = dy[((int64_t)img * g.K + row) * ohw + rem];
-                    if (++rem == ohw) { rem = 0; ++img; }
+                for (int u = 0; u < 8; ++u) {
+                    const int item = (base + u) * 256 + t;
+                    const int pair = item >> 4, q4 = item & 15;
+                    *reinterpret_cast<uint32_t*>(&tile[pair >> 5][pair & 31][q4 * 4]) = v[u];
                 }
             }
         } else {
-            if (row == p.crs) {  // the column of ones behind the unfolded input
+#pragma unroll 1
+            for (int base = 0; base < 128; base += 8) {
+                uint8_t v[8];
 #pragma unroll
-                for (int b = 0; b < 16; ++b) pat[b] = p0 + b < p.P ? 0x40u : 0u;
-            }
-            const int rs = g.R * g.S;
-            const int c = row / rs, tp = row - c * rs;
-            const int r = tp / g.S, s = tp - r * g.S;
-            int oh = rem / g.OW, ow = rem - oh * g.OW;
-            // Unit stride and the 16 positions in one output row: they read 16 consecutive bytes of one input row, cut
-            // by at most a few columns of padding at either end.  One 16-byte load (of any alignment) from the nearest
-            // start inside the row, shifted by the bytes that fall into the padding.
-            const int iw0 = ow + s - g.pw;
-            const int start = iw0 < 0 ? 0 : (iw0 + 16 > g.W ? g.W - 16 : iw0);
-            const int d = iw0 - start;  // < 0: the run begins in the left padding; > 0: it ends in the right padding
-            if (row == p.crs) {
-            } else if (g.sw == 1 && g.W >= 16 && ow + 16 <= g.OW && p0 + 16 <= p.P && d >= -3 && d <= 3) {
-                const int ih = oh * g.sh + r - g.ph;
-                if ((unsigned)ih < (unsigned)g.H) {
-                    const P8Run16 v = *reinterpret_cast<const P8Run16*>(x + (((int64_t)img * g.C + c) * g.H + ih) * g.W + start);
-                    uint32_t wv[4] = {v.w[0], v.w[1], v.w[2], v.w[3]};
-                    if (d < 0) {
-                        const int sh = -8 * d;
+                for (int u = 0; u < 8; ++u) {
+                    const int pair = (base + u) * 4 + (t >> 6), pos = chunk * 64 + (t & 63);
+                    const int img = gi * 16 + (pair >> 5), row = rb * 32 + (pair & 31);
+                    v[u] = (img < g.N && row < g.K && pos < ohw) ? dy[((int64_t)img * g.K + row) * ohw + pos] : (uint8_t)0;
+                }
 #pragma unroll
-                        for (int i = 3; i >= 0; --i) wv[i] = (wv[i] << sh) | (i > 0 ? wv[i - 1] >> (32 - sh) : 0u);
-                    } else if (d > 0) {
-                        const int sh = 8 * d;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) wv[i] = (wv[i] >> sh) | (i < 3 ? wv[i + 1] << (32 - sh) : 0u);
-                    }
-#pragma unroll
-                    for (int b = 0; b < 16; ++b) pat[b] = (wv[b >> 2] >> (8 * (b & 3))) & 0xFFu;
-                }  // a row of padding: zeros
-            } else {
-#pragma unroll
-                for (int b = 0; b < 16; ++b) {
-                    const int ih = oh * g.sh + r - g.ph, iw = ow * g.sw + s - g.pw;
-                    if (p0 + b < p.P && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W)
-                        pat[b] = x[(((int64_t)img * g.C + c) * g.H + ih) * g.W + iw];
-                    if (++ow == g.OW) {
-                        ow = 0;
-                        if (++oh == g.OH) { oh = 0; ++img; }
-                    }
+                for (int u = 0; u < 8; ++u) {
+                    const int pair = (base + u) * 4 + (t >> 6);
+                    tile[pair >> 5][pair & 31][t & 63] = v[u];
                 }
             }
         }
+        __syncthreads();
+        for (int item = t; item < 64 * 32; item += 256) {
+            const int pl = item >> 5, rr = item & 31;
+            const int64_t k16 = (int64_t)(chunk * 64 + pl) * p.NG + gi;
+            if (k16 >= 2 * (int64_t)p.KB) continue;
+            uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+#pragma unroll
+            for (int b = 0; b < 16; ++b) {
+                const int v = tab[tile[b][rr][pl]];
+                hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
+                lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
+            }
+            const int kb = (int)(k16 >> 1), lane = (int)(k16 & 1) * 32 + rr;
+            uint4* out = reinterpret_cast<uint4*>(Ad) + ((int64_t)(kb * p.RBA + rb) * 2) * 64 + lane;
+            out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+            out[64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        }
+        return;
     }
-    uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+    __syncthreads();
+    const int64_t idx = (int64_t)(blockIdx.x - ablocks) * 256 + t;
+    if (idx < 2) zero[idx] = make_uint4(0, 0, 0, 0);  // what the product kernel reads for padding (no memset: graph capture)
+    if (idx < p.NG) {  // the column of ones: 1 = 64 units of 2^-6 = low digit 64, for the images the group really has
+        uint32_t lo[4] = {0, 0, 0, 0};
+        for (int b = 0; b < 16; ++b)
+            if ((int)idx * 16 + b < g.N) lo[b >> 2] |= 64u << (8 * (b & 3));
+        ones[idx * 2] = make_uint4(0, 0, 0, 0);
+        ones[idx * 2 + 1] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
+    const int HW = g.H * g.W;
+    const int64_t planes = (int64_t)g.C * HW;  // pixels of all channels of one image
+    const int64_t groups = planes / PX;
+    if (idx >= groups * p.NG) return;
+    const int gi = (int)(idx / groups);
+    const int64_t pix = (idx - (int64_t)gi * groups) * PX;  // (c, h, w) as one index
+    const int nimg = g.N - gi * 16 < 16 ? g.N - gi * 16 : 16;
+    const uint8_t* q = x + (int64_t)gi * 16 * planes + pix;
+    uint32_t word[16];
 #pragma unroll
     for (int b = 0; b < 16; ++b) {
-        const int v = tab[pat[b]];
-        hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
-        lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
+        if (b >= nimg) word[b] = 0;
+        else if (PX == 4) word[b] = *reinterpret_cast<const uint32_t*>(q + (int64_t)b * planes);
+        else word[b] = q[(int64_t)b * planes];
     }
-    uint4* out = reinterpret_cast<uint4*>(first ? Ad : Bd) + ((int64_t)(kb * RB + rb) * 2) * 64 + lane;
-    out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
-    out[64] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+#pragma unroll
+    for (int px = 0; px < PX; ++px) {
+        uint32_t hi[4] = {0, 0, 0, 0}, lo[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            const int v = tab[(word[b] >> (8 * px)) & 0xFFu];
+            hi[b >> 2] |= ((uint32_t)(v >> 7) & 0xFFu) << (8 * (b & 3));
+            lo[b >> 2] |= ((uint32_t)v & 0x7Fu) << (8 * (b & 3));
+        }
+        uint4* out = reinterpret_cast<uint4*>(xb) + ((pix + px) * p.NG + gi) * 2;
+        out[0] = make_uint4(hi[0], hi[1], hi[2], hi[3]);
+        out[1] = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+    }
 }
 
-// workspace: [planes of dy][planes of the unfolded input][partial sums and flags of the slices]
+struct P8ConvBwArgs {
+    const uint8_t* Ad;    // dy's digit planes
+    const uint8_t* xb;    // x's digit planes, image-minor
+    const uint8_t* ones;  // per image group: the digits of 1 for the images it has
+    const uint8_t* zero;  // 32 bytes of zeros
+    int RBA, kb_per_split;
+    int NG, OH, OW, H, W, R, S, ph, pw, sh, sw;
+    int crs, M, N;
+    SplitWs ws;
+    int tiles_m, tiles_n;
+};
+
+// 64 x 64 outputs per workgroup of four waves (2 x 2, one block of 32 x 32 each); workgroup (tile, z) reduces slice z.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(256, 4) void p8_conv_bw_mfma_kernel(P8ConvBwArgs a) {
+    constexpr int NA = 4, NB = 4;  // runs of 1 KB (block, digit) per k block and operand
+    constexpr int TR = 64, TC = 64;
+    __shared__ uint4 stage[PCM_STAGES][(NA + NB) * 64];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wy = w >> 1, wx = w & 1;
+    const int tm = blockIdx.x % a.tiles_m, tn = blockIdx.x / a.tiles_m;
+    const int z = blockIdx.y;
+    const int kb0 = z * a.kb_per_split;
+
+    uint32_t row_nar = 0, col_nar = 0;
+    pm_v16i hh, xx, ll;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) hh[r] = xx[r] = ll[r] = 0;
+
+    // dy: wave w copies run w of the k block's four (row block w / 2, digit w % 2) from a wave-uniform address
+    const int64_t a_kb = (int64_t)a.RBA * 2 * 64;
+    const uint4* asrc = reinterpret_cast<const uint4*>(a.Ad) + kb0 * a_kb + (int64_t)tm * NA * 64 + w * 64;
+    // x: wave w gathers digit w % 2 of column block w / 2; lane l serves column l % 32 of the block and the 16 reduction
+    // indices (one pixel, one image group) of half l / 32
+    const int cb = w >> 1, digit = w & 1;
+    const int n = tn * TC + cb * 32 + (lane & 31);
+    int kind = 2, cbase = 0, dr = 0, ds = 0;  // kind 0: a column (c, r, s); 1: the column of ones; 2: beyond the columns
+    if (n < a.crs) {
+        const int rs = a.R * a.S;
+        const int c = n / rs, tp = n - c * rs;
+        const int r = tp / a.S, s = tp - r * a.S;
+        kind = 0;
+        cbase = c * a.H * a.W * a.NG * 2 + digit;
+        dr = r - a.ph;
+        ds = s - a.pw;
+    } else if (n < a.N) {
+        kind = 1;
+    }
+    // the reduction index of this lane's half, as (oh, ow, image group), stepped from k block to k block
+    int oh, ow, gi;
+    {
+        const int k16 = kb0 * 2 + (lane >> 5);
+        const int pos = k16 / a.NG;
+        gi = k16 - pos * a.NG;
+        oh = pos / a.OW;
+        ow = pos - oh * a.OW;
+    }
+    const uint4* xq = reinterpret_cast<const uint4*>(a.xb);
+    const uint4* onesq = reinterpret_cast<const uint4*>(a.ones) + digit;
+    const uint4* zeroq = reinterpret_cast<const uint4*>(a.zero);
+
+    int issued = 0;
+    auto issue = [&]() {
+        uint4* sbuf = &stage[issued % PCM_STAGES][0];
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(asrc + lane),
+                                         (__attribute__((address_space(3))) void*)(sbuf + w * 64), 16, 0, 0);
+        asrc += a_kb;
+        const uint4* s = zeroq;
+        if (oh < a.OH) {  // inside the reduction (its padded end reads zeros)
+            if (kind == 0) {
+                const int ih = oh * a.sh + dr, iw = ow * a.sw + ds;
+                if ((unsigned)ih < (unsigned)a.H && (unsigned)iw < (unsigned)a.W) s = xq + (cbase + ((ih * a.W + iw) * a.NG + gi) * 2);
+            } else if (kind == 1) {
+                s = onesq + gi * 2;
+            }
+        }
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)s,
+                                         (__attribute__((address_space(3))) void*)(sbuf + (NA + cb * 2 + digit) * 64), 16, 0, 0);
+        gi += 2;  // the next k block: two reduction indices of 16 further
+        while (gi >= a.NG) {
+            gi -= a.NG;
+            if (++ow == a.OW) {
+                ow = 0;
+                ++oh;
+            }
+        }
+        ++issued;
+    };
+    constexpr int LOADS = 2;  // copies per wave and k block
+
+    const int nkb = a.kb_per_split;
+#pragma unroll
+    for (int k = 0; k < PCM_STAGES - 1; ++k)
+        if (k < nkb) issue();
+    for (int kb = 0; kb < nkb; ++kb) {
+        // k block kb has arrived once at most the copies of the PCM_STAGES - 2 blocks issued after it are outstanding
+        // (copies complete in order); near the end fewer were issued, so wait for all
+        if (kb + PCM_STAGES - 2 < nkb) __builtin_amdgcn_s_waitcnt(pcm_vmcnt((PCM_STAGES - 2) * LOADS));
+        else __builtin_amdgcn_s_waitcnt(pcm_vmcnt(0));
+        __syncthreads();  // everyone's copies of block kb are in LDS, and everyone has finished reading block kb - 1
+        if (kb + PCM_STAGES - 1 < nkb) issue();  // into the buffer of block kb - 1
+        const uint4* sb = &stage[kb % PCM_STAGES][0];
+        const pm_v4i ah = __builtin_bit_cast(pm_v4i, sb[(wy * 2 + 0) * 64 + lane]);
+        const pm_v4i al = __builtin_bit_cast(pm_v4i, sb[(wy * 2 + 1) * 64 + lane]);
+        const pm_v4i bh = __builtin_bit_cast(pm_v4i, sb[(NA + wx * 2 + 0) * 64 + lane]);
+        const pm_v4i bl = __builtin_bit_cast(pm_v4i, sb[(NA + wx * 2 + 1) * 64 + lane]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            row_nar |= pm_marker_bits((uint32_t)ah[q]);
+            col_nar |= pm_marker_bits((uint32_t)bh[q]);
+        }
+        hh = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bh, hh, 0, 0, 0);
+        xx = __builtin_amdgcn_mfma_i32_32x32x32_i8(ah, bl, xx, 0, 0, 0);
+        xx = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bh, xx, 0, 0, 0);
+        ll = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bl, ll, 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);  // a block's reads and matrix instructions stay inside its own iteration
+    }
+    __syncthreads();  // the last block is read: the buffers are free for the verdicts
+
+    // ---- this slice's sums and verdicts into the split workspace ----
+    uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0]);
+    uint32_t* colv = rowv + TR;
+    row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;
+    col_nar = (col_nar | (uint32_t)__shfl_xor((int)col_nar, 32)) & 0x80808080u;
+    if (lane < 32) {
+        if (wx == 0) rowv[wy * 32 + lane] = row_nar;  // the two waves of a row block saw the same rows
+        if (wy == 0) colv[wx * 32 + lane] = col_nar;
+    }
+    __syncthreads();
+    const int64_t M = a.M, N = a.N;
+    // the first tile column stores the row flags of its tile row (the same in every column), the first tile row the
+    // column flags: every entry is written, so the workspace needs no clearing
+    if (tn == 0 && t < TR && tm * TR + t < M) a.ws.rowflag[z * M + tm * TR + t] = rowv[t];
+    if (tm == 0 && t < TC && tn * TC + t < N) a.ws.colflag[z * N + tn * TC + t] = colv[t];
+    uint32_t* lim = a.ws.limbs + z * M * N;
+    const int nn = tn * TC + wx * 32 + (lane & 31);
+    if (nn < N) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int m = tm * TR + wy * 32 + (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+            if (m < M) lim[(int64_t)m * N + nn] = ((uint32_t)hh[r] << 14) + ((uint32_t)xx[r] << 7) + (uint32_t)ll[r];
+        }
+    }
+}
+
+// workspace: [planes of dy][planes of x][blocks of ones][256 bytes of zeros][partial sums and flags of the slices]
 inline hipError_t launch_p8_conv_bw_mfma(hipStream_t stream, const P8ConvBwPlan& p, const void* dy, const void* x, void* dw, void* dbias,
                                          int fout, void* workspace) {
     uint8_t* base = (uint8_t*)workspace;
     uint8_t* Ad = base;
-    uint8_t* Bd = base + p.a_bytes;
+    uint8_t* xb = base + p.a_bytes;
+    uint8_t* ones = xb + p.x_bytes;
+    uint8_t* zero = ones + p.ones_bytes;
     SplitWs ws;
-    ws.limbs = reinterpret_cast<uint32_t*>(base + p.a_bytes + p.b_bytes);
+    ws.limbs = reinterpret_cast<uint32_t*>(zero + 256);
     ws.rowflag = ws.limbs + (size_t)p.splits * p.M * p.N;
     ws.colflag = ws.rowflag + (size_t)p.splits * p.M;
-    const unsigned ablocks = (unsigned)(((int64_t)p.KB * p.RBA * 64 + 255) / 256), bblocks = (unsigned)(((int64_t)p.KB * p.RBB * 64 + 255) / 256);
-    hipLaunchKernelGGL(p8_conv_bw_digits_kernel<0>, dim3(ablocks + bblocks), dim3(256), 0, stream, (const uint8_t*)dy, (const uint8_t*)x, p, Ad, Bd,
-                       ablocks);
+    const ConvGeom& g = p.g;
+    const int posmax = (2 * p.KB + p.NG - 1) / p.NG;  // positions up to the padded end of the reduction
+    const int chunks = (posmax + 63) / 64;
+    const unsigned ablocks = (unsigned)p.RBA * (unsigned)p.NG * (unsigned)chunks;
+    const int64_t planes = (int64_t)g.C * g.H * g.W;
+    if (planes % 4 == 0 && ((uintptr_t)x & 3u) == 0) {
+        const unsigned xblocks = (unsigned)((planes / 4 * p.NG + 255) / 256);
+        hipLaunchKernelGGL(p8_conv_bw_digits_kernel<4>, dim3(ablocks + xblocks), dim3(256), 0, stream, (const uint8_t*)dy, (const uint8_t*)x, p, Ad, xb,
+                           reinterpret_cast<uint4*>(ones), reinterpret_cast<uint4*>(zero), ablocks, chunks);
+    } else {
+        const unsigned xblocks = (unsigned)((planes * p.NG + 255) / 256);
+        hipLaunchKernelGGL(p8_conv_bw_digits_kernel<1>, dim3(ablocks + xblocks), dim3(256), 0, stream, (const uint8_t*)dy, (const uint8_t*)x, p, Ad, xb,
+                           reinterpret_cast<uint4*>(ones), reinterpret_cast<uint4*>(zero), ablocks, chunks);
+    }
     PNN_CHECK_LAUNCH();
-    const int tiles_m = p.RBA / 2, tiles_n = p.RBB / 2;
-    hipLaunchKernelGGL((p8_mfma_gemm_kernel<1, 1, true>), dim3((unsigned)(tiles_m * tiles_n), (unsigned)p.splits), dim3(256), 0, stream, Ad, Bd, p.RBA,
-                       p.RBB, p.KB, (const uint8_t*)nullptr, (void*)nullptr, (int64_t)0, fout, p.M, p.N, tiles_m, tiles_n, p.kb_per_split, ws);
+    P8ConvBwArgs a;
+    a.Ad = Ad; a.xb = xb; a.ones = ones; a.zero = zero;
+    a.RBA = p.RBA; a.kb_per_split = p.kb_per_split;
+    a.NG = p.NG; a.OH = g.OH; a.OW = g.OW; a.H = g.H; a.W = g.W; a.R = g.R; a.S = g.S; a.ph = g.ph; a.pw = g.pw; a.sh = g.sh; a.sw = g.sw;
+    a.crs = p.crs; a.M = p.M; a.N = p.N;
+    a.ws = ws;
+    a.tiles_m = p.RBA / 2;
+    a.tiles_n = p.RBB / 2;
+    hipLaunchKernelGGL(p8_conv_bw_mfma_kernel<0>, dim3((unsigned)(a.tiles_m * a.tiles_n), (unsigned)p.splits), dim3(256), 0, stream, a);
     PNN_CHECK_LAUNCH();
     if (p.N > p.crs) {
         WeightAndBiasOut out{(int64_t)p.crs, dbias};

@@ -93,12 +93,13 @@ def test_argument_validation_without_launch():
     assert L.posit_conv2d_fwd(null, 0, 0, ctypes.byref(d), fake, fake, null, fake, ctypes.c_void_p(0x1004), 1 << 30) == EINVAL  # workspace alignment
     # workspace of the posit<8,0> convolutions that run on the matrix cores (32 -> 32 channels, 32 x 32, batch 128, 3 x 3, pad 1):
     # forward / backward-data: weight planes (9 k blocks x 1 row block x 2 KB) + input planes (131072 pixels x 2 groups of 16
-    # channels x 32 bytes) + 256 bytes of zeros; backward-weight: planes of dy (2 row blocks) and of the unfolded input with its
-    # column of ones (289 columns: 10 row blocks) over 205 slices of 20 k blocks, then the slices' partial sums and flags
+    # channels x 32 bytes) + 256 bytes of zeros; backward-weight: planes of dy (2 row blocks, 103 slices of 40 k blocks of two
+    # pixels x 8 groups of 16 images), planes of x image-minor (32 x 32 x 32 pixels x 8 groups x 32 bytes), a block of ones per
+    # group, 256 bytes of zeros, then the slices' partial sums and flags (289 columns: the weights and the bias gradient)
     d = b.ConvDesc(128, 32, 32, 32, 32, 3, 3, 1, 1, 1, 1)
     assert L.posit_conv2d_workspace(0, 0, 0, ctypes.byref(d)) == 9 * 2048 + 131072 * 2 * 32 + 256
     assert L.posit_conv2d_workspace(1, 0, 0, ctypes.byref(d)) == 9 * 2048 + 131072 * 2 * 32 + 256
-    assert L.posit_conv2d_workspace(2, 0, 1, ctypes.byref(d)) == 4100 * (2 + 10) * 2048 + (205 * 32 * 289 + 205 * (32 + 289)) * 4
+    assert L.posit_conv2d_workspace(2, 0, 1, ctypes.byref(d)) == 4120 * 2 * 2048 + 32 * 32 * 32 * 8 * 32 + 8 * 32 + 256 + (103 * 32 * 289 + 103 * (32 + 289)) * 4
     d = b.ConvDesc(128, 32, 32, 32, 32, 3, 3, 1, 1, 2, 2)  # strided: forward keeps the dot-product kernel (no digit planes)
     assert L.posit_conv2d_workspace(0, 0, 0, ctypes.byref(d)) < 131072 * 2 * 32
     # average pooling: the weight 1/(kh*kw) must be a posit of fin.  posit<8,0> stops at minpos = 1/64
