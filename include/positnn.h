@@ -152,8 +152,8 @@ int posit_conv2d_bwd_weight(void* stream, int fin, int fout, const pnn_conv2d_de
  * on return.  It holds the partial quires of a split reduction and, for posit<8,0>, the operands
  * rewritten once: as decoded 16-bit integers with the zero border written out (about twice the size of
  * the tensors), or, from 2^26 multiply-adds on, as int8 digit planes (forward and backward-data: twice
- * the gathered tensor, channels padded to 16; backward-weight: 2 R S times the input, unfolded, plus
- * twice dy).  The calls of one stream may share one workspace.  The answer
+ * the gathered tensor, channels padded to 16; backward-weight: twice x and twice dy, the batch padded
+ * to 16).  The calls of one stream may share one workspace.  The answer
  * depends on which, fin and desc (fout is accepted for the same reason as in posit_gemm_workspace). */
 size_t posit_conv2d_workspace(int which, int fin, int fout, const pnn_conv2d_desc* desc);
 

@@ -15,8 +15,8 @@
 // reduction order; for backward-data they are taken transposed and flipped, NaR as zero (the outputs a NaR weight
 // reaches are marked by the pass that follows, as for the other backward-data kernels).
 //
-// Stride 1 only.  Backward-weight reduces over the positions, where 16 consecutive indices are 16 pixels of a shifted
-// row that crosses the padding: it stays on the dot-product kernels.
+// These two passes: stride 1 only.  Backward-weight, whose reduction runs over images and positions, is the second half
+// of this file.
 #pragma once
 
 #include "gemm_p8_mfma.h"
