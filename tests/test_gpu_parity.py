@@ -777,11 +777,12 @@ def test_relu_forward_backward(fmt):
     _assert_equal(dx, np.array(po.relu_bwd(y.tolist(), dy.tolist(), PF[fmt], po.P16)), "relu bwd")
 
 
-@pytest.mark.parametrize("fmt", ["p8", "p16"])
-@pytest.mark.parametrize("kh,kw", [(2, 2), (3, 2)])
-def test_maxpool_forward_backward(fmt, kh, kw):
+@pytest.mark.parametrize("fmt", ["p8", "p16", "p32"])
+@pytest.mark.parametrize("kh,kw,W", [(2, 2, 10), (3, 2, 10), (2, 2, 12), (3, 4, 12), (2, 3, 12)])
+def test_maxpool_forward_backward(fmt, kh, kw, W):
+    """Width 10: one element per thread; width 12: the backward kernel that handles four elements of a row per thread."""
     rng = np.random.default_rng(kh + kw + BITS[fmt])
-    planes, H, W = 14, 12, 10
+    planes, H = 14, 12
     x = rand_patterns(rng, (2, 7, H, W), fmt, special=0.1)
     y, idx = pn.posit_maxpool2d_fwd(to_dev(x), fmt, kh, kw)
     wy, widx = po.maxpool2d_fwd(x.flatten().tolist(), planes, H, W, kh, kw, PF[fmt])
