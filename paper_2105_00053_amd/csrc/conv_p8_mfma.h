@@ -306,10 +306,10 @@ __global__ __launch_bounds__(256, (BI * BJ == 2 ? 3 : 4)) void p8_conv_mfma_kern
             }
         __builtin_amdgcn_sched_barrier(0);  // a block's reads and matrix instructions stay inside its own iteration
     }
-    __syncthreads();  // the last block is read: the buffers are free for the verdicts
+    __syncthreads();  // the last block is read: the buffers are free for the NaR flags
 
     // ---- the three sums into the quire, round once, store ----
-    // Row verdicts (NaR weight or NaR bias in the channel) and the bias addends meet in LDS; column verdicts too.
+    // Row flags (NaR weight or NaR bias in the channel) and the bias addends meet in LDS; column flags too.
     uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0]);
     uint32_t* colv = rowv + TR;
     int32_t* rowb = reinterpret_cast<int32_t*>(colv + TC);
@@ -328,7 +328,7 @@ __global__ __launch_bounds__(256, (BI * BJ == 2 ? 3 : 4)) void p8_conv_mfma_kern
             rowv[lr] = row_nar;
             rowb[lr] = badd;
         }
-        colv[(wx * BJ + jb) * 32 + lane] = col_nar;  // with one block per wave both waves of the pair write the same verdict
+        colv[(wx * BJ + jb) * 32 + lane] = col_nar;  // with one block per wave both waves of the pair write the same flag
     }
     __syncthreads();
     rowv += wy * 32 * BI;
@@ -336,11 +336,11 @@ __global__ __launch_bounds__(256, (BI * BJ == 2 ? 3 : 4)) void p8_conv_mfma_kern
     colv += wx * 32 * BJ;
     // The matrix instruction leaves a lane with one position and 16 BI channels: stored from there, every store
     // instruction would write 1 byte per lane, 32 bytes per channel row.  The rounded tile goes through LDS instead
-    // (buffers 1 .. of the ring; buffer 0 holds the verdicts) and leaves in 16-byte runs along the positions.
+    // (buffers 1 .. of the ring; buffer 0 holds the NaR flags) and leaves in 16-byte runs along the positions.
     const FmtRT fo = fmt_of_code(a.fout);
     const int esz = fo.n <= 8 ? 1 : (fo.n <= 16 ? 2 : 4);
     uint8_t* tileb = reinterpret_cast<uint8_t*>(&stage[1][0]);
-    static_assert((PCM_STAGES - 1) * (NA + NB) * 1024 >= TR * TC * 4, "the rounded tile fits behind the verdicts");
+    static_assert((PCM_STAGES - 1) * (NA + NB) * 1024 >= TR * TC * 4, "the rounded tile fits behind the NaR flags");
 #pragma unroll
     for (int j = 0; j < BJ; ++j) {
         const int lc = (wx * BJ + j) * 32 + (lane & 31);
@@ -433,7 +433,7 @@ inline hipError_t launch_p8_conv_mfma(hipStream_t stream, const P8ConvMfmaPlan& 
 // kernel copies dy's runs from wave-uniform addresses and gathers x: lane (column (c, r, s), 16 reduction indices)
 // names the 16 bytes of pixel (oh sh + r - ph, ow sw + s - pw) of channel c and image group g, or a block of zeros in the
 // padding.  Nothing is unfolded; any stride.  The reduction is cut into slices ((tile, z) reduces kb_per_split k blocks,
-// about 512 workgroups in all) whose 32-bit sums and NaR verdicts the merging launch adds, rounds and stores.  The bias
+// about 512 workgroups in all) whose 32-bit sums and NaR flags the merging launch adds, rounds and stores.  The bias
 // gradient, db[k] = sum of dy[.][k][.][.] * 1, is one more column: its lanes gather a block that holds 1 for every image
 // of the group, and the merge routes the column to its own tensor.
 
@@ -721,9 +721,9 @@ __global__ __launch_bounds__(256, 4) void p8_conv_bw_mfma_kernel(P8ConvBwArgs a)
         ll = __builtin_amdgcn_mfma_i32_32x32x32_i8(al, bl, ll, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);  // a block's reads and matrix instructions stay inside its own iteration
     }
-    __syncthreads();  // the last block is read: the buffers are free for the verdicts
+    __syncthreads();  // the last block is read: the buffers are free for the NaR flags
 
-    // ---- this slice's sums and verdicts into the split workspace ----
+    // ---- this slice's sums and NaR flags into the split workspace ----
     uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0]);
     uint32_t* colv = rowv + TR;
     row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;

@@ -129,7 +129,7 @@ __global__ __launch_bounds__(256) void p8_digits_kernel(P8DigitJob job0, P8Digit
 // multiple of PM_KSTEP).  Four waves as 2 x 2; a wave owns BI x BJ blocks of 32 x 32 outputs, the workgroup 64 BI x 64 BJ.
 //
 // SPLIT: workgroup (tile, z) reduces the kb_per_split k blocks from z kb_per_split on and leaves its 32-bit sums and
-// its NaR verdicts in the workspace of a split reduction (ws: partial quires [z][M N], row flags [z][M], column flags
+// its NaR flags in the workspace of a split reduction (ws: partial quires [z][M N], row flags [z][M], column flags
 // [z][N]); the merging launch adds, rounds and stores.  For products with few output tiles and a long reduction.
 template <int BI, int BJ, bool SPLIT = false>
 __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) void p8_mfma_gemm_kernel(
@@ -243,13 +243,13 @@ __global__ __launch_bounds__(256, (BI * BJ == 4 ? 2 : BI * BJ == 2 ? 3 : 4)) voi
 
     // ---- the three sums into the quire, round once, store ----
     // NaR: lanes l and l + 32 hold the two halves of the reduction of row (column) l % 32 of the block their wave
-    // searched; the verdicts of the tile's rows and columns meet in LDS (the staging buffers are free now).
+    // searched; the NaR flags of the tile's rows and columns meet in LDS (the staging buffers are free now).
     uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0][0]);
     uint32_t* colv = rowv + TR;
     row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;
     col_nar = (col_nar | (uint32_t)__shfl_xor((int)col_nar, 32)) & 0x80808080u;
     if (lane < 32) {
-        rowv[(wy * BI + ia) * 32 + lane] = row_nar;  // with one block per wave both waves of the pair write the same verdict
+        rowv[(wy * BI + ia) * 32 + lane] = row_nar;  // with one block per wave both waves of the pair write the same flag
         colv[(wx * BJ + jb) * 32 + lane] = col_nar;
     }
     __syncthreads();

@@ -341,7 +341,7 @@ __global__ __launch_bounds__(64 * WAVES, WAVES == 8 ? 2 : 4) void p8_gemm_w4_ker
         return;
     }
     // ---- round once and store ----
-    // The quires with the bias and the NaR verdicts first, then ONE test of the output format around the whole tile: the
+    // The quires with the bias and the NaR flags first, then ONE test of the output format around the whole tile: the
     // posit<8,0> path is a compact run of code (a format test inside the loops would scatter it between sixteen copies of
     // the general encoder, and a wave pays an instruction-cache miss for every jump over one of them).
     uint32_t qv[RPW][8];
