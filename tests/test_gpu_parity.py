@@ -623,6 +623,49 @@ def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
     _assert_equal(to_np(dx2, fout), fast.conv2d_bwd_data(dy, w2, d, "p8", fout), "conv bwd_data, NaR weights")
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_p8_conv_matrix_core_random_geometries(seed):
+    """Random geometries large enough for the matrix-core convolutions (2^26 products, 8192 positions): filters 1 x 1 to
+    5 x 4, padding from none to the filter size, odd channel and batch counts (groups of 16 partly filled), strides 1 and
+    2 (at stride 2 only backward-weight runs there).  All three passes against the oracle, bias and bias gradient included."""
+    rng = np.random.default_rng(1000 + seed)
+    while True:
+        R, S = int(rng.integers(1, 6)), int(rng.integers(1, 5))
+        d = dict(C=int(rng.integers(8, 41)), K=int(rng.integers(16, 81)), H=int(rng.integers(12, 41)), W=int(rng.integers(12, 41)), R=R, S=S,
+                 pad_h=int(rng.integers(0, R + 1)), pad_w=int(rng.integers(0, S + 1)))
+        if seed % 4 == 3:
+            d["stride_h"], d["stride_w"] = 2, int(rng.integers(1, 3))
+        d["N"] = 1
+        oh, ow = fast.out_hw(d)
+        if oh < 1 or ow < 1:
+            continue
+        need = max(-(-8192 // (oh * ow)), -(-(1 << 26) // (oh * ow * d["K"] * d["C"] * R * S)))
+        d["N"] = need + int(rng.integers(0, 3))
+        if d["N"] <= 96 and d["N"] * oh * ow * d["K"] * d["C"] * R * S < 3 << 27:
+            break
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), "p8", special=0.0002)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), "p8", special=0.001, allow_nar=False)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.0002)
+    bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", "p8", bias=to_dev(bias))
+    _assert_equal(to_np(y, "p8"), fast.conv2d_fwd(x, w, d, "p8", "p8", bias=bias), "conv fwd %r" % d)
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", "p16")
+    _assert_equal(to_np(dx, "p16"), fast.conv2d_bwd_data(dy, w, d, "p8", "p16"), "conv bwd_data %r" % d)
+    dyw, xw = dy.copy(), x.copy()   # every output of this pass sums over all positions: keep a few NaR only
+    dyw[dyw == 0x80] = 0x3F
+    xw[xw == 0x80] = 0xC1
+    dyw[d["N"] - 1, 1, oh - 1, 0] = 0x80
+    xw[0, d["C"] - 1, d["H"] // 2, d["W"] // 2] = 0x80
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dyw), to_dev(xw), desc, "p8", "p16", with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dyw, xw, d, "p8", "p16", with_bias=True)
+    _assert_equal(to_np(dw, "p16"), wdw, "conv bwd_weight %r" % d)
+    _assert_equal(to_np(db, "p16"), wdb, "conv bias gradient %r" % d)
+    dw2 = pn.posit_conv2d_bwd_weight(to_dev(dyw), to_dev(xw), desc, "p8", "p8")   # without the bias gradient's column
+    dw2 = dw2[0] if isinstance(dw2, tuple) else dw2
+    _assert_equal(to_np(dw2, "p8"), fast.conv2d_bwd_weight(dyw, xw, d, "p8", "p8"), "conv bwd_weight, no bias gradient %r" % d)
+
+
 @pytest.mark.parametrize("fin,fout", [("p8", "p8"), ("p8", "p16"), ("p8_2", "p8_2"), ("p8_1", "p12_2"), ("p16", "p16"), ("p12_2", "p8_2"), ("p32", "p32")])
 @pytest.mark.parametrize("geom", ["unit stride (operands rewritten)", "pad beyond the filter (byte gather)", "strided (generic kernel)"])
 def test_conv_bwd_data_nar_weight_reaches_only_its_taps_positions(fin, fout, geom):
