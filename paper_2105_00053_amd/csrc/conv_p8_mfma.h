@@ -29,6 +29,19 @@ constexpr int PCM_STAGES = 4;    // k blocks in flight per workgroup
 // s_waitcnt immediate: at most n vector-memory operations outstanding, the other counters unconstrained
 constexpr int pcm_vmcnt(int n) { return (n & 0xF) | ((n >> 4) << 14) | 0x0F70; }
 
+// The barrier of the ring: the bare instruction.  __syncthreads() puts a fence in front of it that waits for EVERY
+// outstanding copy of the wave, the ones running ahead included, which would shorten the ring to one block.  What the
+// ring needs holds without a fence: a wave's copies of the block it is about to read have landed (the counted wait in
+// front of the barrier), and every wave's LDS reads of the block about to be overwritten have returned (their data was
+// consumed by matrix instructions earlier in program order; nothing may be scheduled across the barrier).
+__device__ __forceinline__ void pcm_ring_barrier() {
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 struct P8ConvMfmaPlan {
     bool ok;
     int which;                 // 0 forward, 1 backward-data
@@ -276,7 +289,7 @@ __global__ __launch_bounds__(256, (BI * BJ == 2 ? 3 : 4)) void p8_conv_mfma_kern
         // (copies complete in order); near the end fewer were issued, so wait for all
         if (kb + PCM_STAGES - 2 < a.KB) __builtin_amdgcn_s_waitcnt(pcm_vmcnt((PCM_STAGES - 2) * LOADS));
         else __builtin_amdgcn_s_waitcnt(pcm_vmcnt(0));
-        __syncthreads();  // everyone's copies of block kb are in LDS, and everyone has finished reading block kb - 1
+        pcm_ring_barrier();  // everyone's copies of block kb are in LDS, and everyone has finished reading block kb - 1
         if (kb + PCM_STAGES - 1 < a.KB) issue(kb + PCM_STAGES - 1);  // into the buffer of block kb - 1
         const uint4* sb = &stage[kb % PCM_STAGES][0];
         pm_v4i ah[BI], al[BI], bh[BJ], bl[BJ];
@@ -703,7 +716,7 @@ __global__ __launch_bounds__(256, 4) void p8_conv_bw_mfma_kernel(P8ConvBwArgs a)
         // (copies complete in order); near the end fewer were issued, so wait for all
         if (kb + PCM_STAGES - 2 < nkb) __builtin_amdgcn_s_waitcnt(pcm_vmcnt((PCM_STAGES - 2) * LOADS));
         else __builtin_amdgcn_s_waitcnt(pcm_vmcnt(0));
-        __syncthreads();  // everyone's copies of block kb are in LDS, and everyone has finished reading block kb - 1
+        pcm_ring_barrier();  // everyone's copies of block kb are in LDS, and everyone has finished reading block kb - 1
         if (kb + PCM_STAGES - 1 < nkb) issue();  // into the buffer of block kb - 1
         const uint4* sb = &stage[kb % PCM_STAGES][0];
         const pm_v4i ah = __builtin_bit_cast(pm_v4i, sb[(wy * 2 + 0) * 64 + lane]);
