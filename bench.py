@@ -40,7 +40,7 @@ PEAK_INT8_TOPS = 5000.0                       # dense int8 MFMA, published
 INT8_OPS_PER_POSIT_MAC = 8                    # four int8 multiply-accumulates: (128 ah + al)(128 bh + bl)
 # HBM-side bytes per posit_gemm call at 4096^3 (digit-plane pass + GEMM kernel), from two rocprofv3 --pmc passes
 # (profiles/p8_gemm_4096_hbm_traffic.md): FETCH_SIZE x 2.0 (copy-kernel scale) + WRITE_SIZE, in KiB.
-GEMM_4096_TRAFFIC_KIB = (180119, 20682, 16542, 65536)  # (FETCH gemm, WRITE gemm, FETCH digit pass, WRITE digit pass)
+GEMM_4096_TRAFFIC_KIB = (189582, 21375, 16493, 65536)  # (FETCH gemm, WRITE gemm, FETCH digit pass, WRITE digit pass)
 
 
 def _time_ms(torch, fn, reps, warm=2):
