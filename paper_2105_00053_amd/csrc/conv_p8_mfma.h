@@ -79,7 +79,7 @@ inline P8ConvMfmaPlan p8_conv_mfma_plan(int which, const ConvGeom& g) {
     const int64_t macs = p.P * p.MO * p.CI * g.R * g.S;
     if (macs < ((int64_t)1 << 26) || p.P < 8192 || p.MO < 16 || p.CI < 8) return p;
     p.WY = p.MO > 32 ? 2 : 1;
-    p.BI = p.MO > 64 ? 2 : 1;
+    p.BI = (p.MO > 64 && ((p.MO + 127) / 128) * ((p.P + 63) / 64) >= 256) ? 2 : 1;  // 128-row tiles only if every compute unit still gets one
     const int64_t tiles_m = (p.MO + 32 * p.WY * p.BI - 1) / (32 * p.WY * p.BI);
     p.BJ = (p.WY == 2 && p.BI == 1 && tiles_m * ((p.P + 127) / 128) >= PM_MIN_WGS) ? 2 : 1;
     p.RBA = (int)tiles_m * p.WY * p.BI;

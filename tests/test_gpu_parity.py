@@ -576,12 +576,13 @@ def test_p8_conv_many_rows_few_channels(geom):
                                        (dict(N=17, C=8, H=64, W=64, K=40, R=3, S=3, pad_h=1, pad_w=1), "p8"),
                                        (dict(N=8, C=24, H=20, W=52, K=72, R=2, S=3, pad_h=1, pad_w=1), "p16"),
                                        (dict(N=13, C=16, H=30, W=30, K=32, R=5, S=5, pad_h=0, pad_w=0), "p8"),
-                                       (dict(N=9, C=33, H=32, W=32, K=64, R=3, S=3, pad_h=2, pad_w=0), "p8")])
+                                       (dict(N=9, C=33, H=32, W=32, K=64, R=3, S=3, pad_h=2, pad_w=0), "p8"),
+                                       (dict(N=16, C=16, H=32, W=32, K=80, R=3, S=3, pad_h=1, pad_w=1), "p8")])
 def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
     """Unit-stride posit<8,0> forward and backward-data convolutions of 2^26 products and more (8192 output positions,
     16 output channels) run as implicit matrix products on the integer matrix cores: the input rewritten as int8 digit
-    planes pixel-major in groups of 16 channels, gathered tap by tap.  Channel counts that do not fill a group, 64 x 64,
-    64 x 128 and 128 x 64 tiles, ragged position counts, filters 2 x 3 and 5 x 5, no padding and padding beyond the
+    planes pixel-major in groups of 16 channels, gathered tap by tap.  Channel counts that do not fill a group, 32 x 128,
+    64 x 64, 64 x 128 and (last case: 80 output channels over 16384 positions) 128 x 64 tiles, ragged position counts, filters 2 x 3 and 5 x 5, no padding and padding beyond the
     filter's half, NaR in the input (every output whose window holds it), a NaR weight (forward: its whole output
     channel, padding counts as an operand; backward-data: the positions its tap reaches), a NaR bias.  Backward-weight
     runs there too, as a matrix product over unfolded digit planes with the positions cut into slices."""
