@@ -77,7 +77,7 @@ inline P8ConvMfmaPlan p8_conv_mfma_plan(int which, const ConvGeom& g) {
     if (pin * p.Cg * 2 >= ((int64_t)1 << 30) || p.P >= ((int64_t)1 << 30) || p.P * p.MO >= ((int64_t)1 << 40)) return p;
     // worth the two rewriting launches: enough products, enough positions to fill the chip, enough rows to use a block
     const int64_t macs = p.P * p.MO * p.CI * g.R * g.S;
-    if (macs < ((int64_t)1 << 26) || p.P < 8192 || p.MO < 16 || p.CI < 8) return p;
+    if (macs < ((int64_t)1 << 24) || p.P < 8192 || p.MO < 4 || p.CI < 8) return p;
     p.WY = p.MO > 32 ? 2 : 1;
     p.BI = (p.MO > 64 && ((p.MO + 127) / 128) * ((p.P + 63) / 64) >= 256) ? 2 : 1;  // 128-row tiles only if every compute unit still gets one
     const int64_t tiles_m = (p.MO + 32 * p.WY * p.BI - 1) / (32 * p.WY * p.BI);
@@ -468,8 +468,8 @@ inline P8ConvBwPlan p8_conv_bw_plan(const ConvGeom& g, bool with_bias) {
     p.g = g;
     const int64_t crs = (int64_t)g.C * g.R * g.S;
     const int64_t P = (int64_t)g.N * g.OH * g.OW;
-    if (g.K < 16 || crs < 16 || crs > 65536 || g.K > 65536 || P < 4096 || P >= ((int64_t)1 << 30)) return p;
-    if ((int64_t)g.K * crs * P < ((int64_t)1 << 26)) return p;
+    if (g.K < 4 || crs < 16 || crs > 65536 || g.K > 65536 || P < 4096 || P >= ((int64_t)1 << 30)) return p;
+    if ((int64_t)g.K * crs * P < ((int64_t)1 << 22)) return p;  // below, the three launches cost more than the dot-product kernel
     p.NG = (g.N + 15) / 16;
     const int64_t k16 = (int64_t)g.OH * g.OW * p.NG;
     if ((int64_t)g.C * g.H * g.W * p.NG * 2 >= ((int64_t)1 << 30) || k16 >= ((int64_t)1 << 28) || g.H > 16384 || g.W > 16384) return p;

@@ -624,6 +624,36 @@ def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
     _assert_equal(to_np(dx2, fout), fast.conv2d_bwd_data(dy, w2, d, "p8", fout), "conv bwd_data, NaR weights")
 
 
+@pytest.mark.parametrize("geom", [dict(N=64, C=1, H=28, W=28, K=6, R=5, S=5, pad_h=2, pad_w=2),
+                                  dict(N=64, C=6, H=14, W=14, K=16, R=5, S=5),
+                                  dict(N=40, C=16, H=15, W=15, K=5, R=3, S=3, pad_h=1, pad_w=1)])
+def test_p8_conv_matrix_cores_small_layers(geom):
+    """The LeNet-5-shaped layers and one more with 5 output channels: a few million products, 4 to 16 channels.  Backward-weight
+    runs on the matrix cores from 2^22 products and 4 output channels on (most of a 64-row tile is padding: the launches, not
+    the multiplies, set the time), backward-data and forward from 2^24 products, 4 output and 8 input channels on."""
+    d = geom
+    rng = np.random.default_rng(d["C"] * 31 + d["K"])
+    oh, ow = fast.out_hw(d)
+    x = rand_patterns(rng, (d["N"], d["C"], d["H"], d["W"]), "p8", special=0.0002)
+    w = rand_patterns(rng, (d["K"], d["C"], d["R"], d["S"]), "p8", special=0.001, allow_nar=False)
+    dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.0002)
+    bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
+    desc = _desc(d)
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", "p8", bias=to_dev(bias))
+    _assert_equal(to_np(y, "p8"), fast.conv2d_fwd(x, w, d, "p8", "p8", bias=bias), "conv fwd")
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", "p8")
+    _assert_equal(to_np(dx, "p8"), fast.conv2d_bwd_data(dy, w, d, "p8", "p8"), "conv bwd_data")
+    dyw, xw = dy.copy(), x.copy()
+    dyw[dyw == 0x80] = 0x3F
+    xw[xw == 0x80] = 0xC1
+    dyw[3, d["K"] - 1, 0, ow - 1] = 0x80
+    xw[d["N"] - 1, 0, d["H"] - 1, 1] = 0x80
+    dw, db = pn.posit_conv2d_bwd_weight(to_dev(dyw), to_dev(xw), desc, "p8", "p16", with_bias=True)
+    wdw, wdb = fast.conv2d_bwd_weight(dyw, xw, d, "p8", "p16", with_bias=True)
+    _assert_equal(to_np(dw, "p16"), wdw, "conv bwd_weight")
+    _assert_equal(to_np(db, "p16"), wdb, "conv bias gradient")
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_p8_conv_matrix_core_random_geometries(seed):
     """Random geometries large enough for the matrix-core convolutions (2^26 products, 8192 positions): filters 1 x 1 to
