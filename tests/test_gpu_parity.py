@@ -575,7 +575,7 @@ def test_p8_conv_many_rows_few_channels(geom):
 @pytest.mark.parametrize("geom,fout", [(dict(N=10, C=20, H=31, W=33, K=40, R=3, S=3, pad_h=1, pad_w=1), "p8"),
                                        (dict(N=17, C=8, H=64, W=64, K=40, R=3, S=3, pad_h=1, pad_w=1), "p8"),
                                        (dict(N=8, C=24, H=20, W=52, K=72, R=2, S=3, pad_h=1, pad_w=1), "p16"),
-                                       (dict(N=13, C=16, H=30, W=30, K=32, R=5, S=5, pad_h=0, pad_w=0), "p8"),
+                                       (dict(N=13, C=16, H=30, W=30, K=32, R=5, S=5, pad_h=0, pad_w=0), "p32"),
                                        (dict(N=9, C=33, H=32, W=32, K=64, R=3, S=3, pad_h=2, pad_w=0), "p8"),
                                        (dict(N=16, C=16, H=32, W=32, K=80, R=3, S=3, pad_h=1, pad_w=1), "p8")])
 def test_p8_conv_on_the_integer_matrix_cores(geom, fout):
@@ -639,10 +639,11 @@ def test_p8_conv_matrix_cores_small_layers(geom):
     dy = rand_patterns(rng, (d["N"], d["K"], oh, ow), "p8", special=0.0002)
     bias = rand_patterns(rng, (d["K"],), "p8", allow_nar=False)
     desc = _desc(d)
-    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", "p8", bias=to_dev(bias))
-    _assert_equal(to_np(y, "p8"), fast.conv2d_fwd(x, w, d, "p8", "p8", bias=bias), "conv fwd")
-    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", "p8")
-    _assert_equal(to_np(dx, "p8"), fast.conv2d_bwd_data(dy, w, d, "p8", "p8"), "conv bwd_data")
+    fo = "p32" if d["K"] == 5 else "p8"   # the 32-bit container through the tile-in-LDS epilogue as well
+    y = pn.posit_conv2d_fwd(to_dev(x), to_dev(w), desc, "p8", fo, bias=to_dev(bias))
+    _assert_equal(to_np(y, fo), fast.conv2d_fwd(x, w, d, "p8", fo, bias=bias), "conv fwd")
+    dx = pn.posit_conv2d_bwd_data(to_dev(dy), to_dev(w), desc, "p8", fo)
+    _assert_equal(to_np(dx, fo), fast.conv2d_bwd_data(dy, w, d, "p8", fo), "conv bwd_data")
     dyw, xw = dy.copy(), x.copy()
     dyw[dyw == 0x80] = 0x3F
     xw[xw == 0x80] = 0xC1
