@@ -7,6 +7,7 @@
 #include "conv_p8.h"
 #include "gemm_p8_w4.h"
 #include "gemm_p8_mfma.h"
+#include "gemm_b8_mfma.h"
 #include "conv_b8.h"
 #include "gemm_bucket_pre.h"
 #include "gemm_p16_window.h"
@@ -34,6 +35,11 @@ GemmPlan gemm_plan(int64_t M, int64_t N, int64_t K) {
         if (p8_small_gemm_fits(M, N, K)) {  // one thread group per output: no workspace
             GemmPlan p;
             p.splits = 1; p.k_per_split = K; p.ws_bytes = 0;
+            return p;
+        }
+        if (b8_mfma_fits<F>(M, N, K)) {  // digit planes of both operands for the integer matrix cores
+            GemmPlan p;
+            p.splits = 1; p.k_per_split = K; p.ws_bytes = b8_mfma_layout<F>(M, N, K).total();
             return p;
         }
         if (M < ((int64_t)1 << 31) && N < ((int64_t)1 << 31) && K < ((int64_t)1 << 31)) return b8_conv_plan<F>((int)M, (int)N, (int)K);
@@ -116,6 +122,9 @@ int gemm_dispatch(hipStream_t st, int fout, int transA, int transB, int64_t M, i
         if (p8_small_gemm_fits(M, N, K))
             return hip_status(launch_b8_small_gemm<F>(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C,
                                                       ldc, fout, M, N, K));
+        if (b8_mfma_fits<F>(M, N, K))
+            return hip_status(launch_b8_mfma_gemm<F>(st, transA, transB, (const uint8_t*)A, lda, (const uint8_t*)B, ldb, (const uint8_t*)bias, C, ldc,
+                                                     fout, M, N, K, ws));
         if (p8_gemm_as_gather_fits(transA, transB, M, N, K, lda, ldb)) {
             const P8ConvProblem p = p8_gemm_problem(transA, transB, (int)M, (int)N, (int)K, A, (int)lda, B, (int)ldb, ldc);
             RowMajorOut mo{ldc};

@@ -1,0 +1,316 @@
+// posit(8,1) / posit(8,2) matrix product with the exact quire (paper Sec. 2, Sec. 3.3; the formats of Sec. 4) on the
+// integer matrix cores: the digit decomposition of gemm_p8_mfma.h carried over the whole range of the format.
+//
+// These formats have few significand bits and a wide range.  In units of minpos a decoded posit(8,2) is an integer v of
+// at most 49 bits plus sign (a 4-bit significand over 49 binades), a posit(8,1) one of 25 bits; written in ND = 8
+// (resp. 4) base-128 digits that all carry the sign of v, v = sum_i d_i 128^i with d_i in [-127, 127], at most two
+// adjacent digits are non-zero.  A product is then
+//     a b = sum_s 128^s  sum_{i + j = s} a_i b_j ,
+// 2 ND - 1 int32 sums per output fed by ND^2 int8 products per posit product, combined once after the reduction into
+// the quire (exact: every partial sum stays below 2^31 for reductions of up to 8192, which is what this kernel takes).
+// No window and no outliers: the whole range is covered.
+//
+// Most of the ND^2 digit products multiply zeros.  The digit kernel therefore writes, per (k block of 32, row block of
+// 32) one byte whose bit i says whether digit plane i holds anything, and the product kernel skips every digit pair one
+// of whose planes is empty: data spread over a few binades (activations, weights, gradients of one layer) fills two to
+// four adjacent planes, 4 to 16 of the 64 products.  The skipping is by whole planes of a block, uniform for a wave,
+// and changes nothing in the result.
+//
+// Layout of the rewritten operands: [k block][row block][digit][lane][16 bytes] in the lane order of
+// v_mfma_i32_32x32x32_i8 (see gemm_p8_mfma.h), NaR as the top digit -128, which no value has (|d_i| <= 127, and the
+// top digit of a value is at most 8 in magnitude).
+#pragma once
+
+#include "gemm_p8_mfma.h"
+
+namespace pnn {
+
+template <class F>
+struct B8Mfma {
+    static constexpr int BITS = 2 * F::MAXS + 2;         // magnitude up to 2^(2 MAXS) and the sign
+    static constexpr int ND = (BITS + 6) / 7;            // base-128 digits
+    static constexpr int NC = 2 * ND - 1;                // digit positions of a product
+    static constexpr int MAXK = 8192;                    // ND * 2^14 * K < 2^31
+    static_assert(ND <= 8, "one mask byte per block");
+    static_assert((int64_t)ND * 16384 * MAXK <= ((int64_t)1 << 31), "int32 sums");
+};
+
+constexpr int64_t B8_NAR_VALUE = (int64_t)1 << 62;  // stands for NaR in the table of values (no value is that large)
+
+// The value of a pattern in units of minpos.
+template <class F>
+__device__ __forceinline__ int64_t b8_fixed(uint32_t p) {
+    if (p == 0) return 0;
+    if (p == F::NAR) return B8_NAR_VALUE;
+    bool neg;
+    uint32_t sig;
+    int sh;
+    decode_fixed<F>(p, neg, sig, sh);
+    const int64_t v = (int64_t)sig << sh;
+    return neg ? -v : v;
+}
+
+struct B8DigitJob {
+    const uint8_t* src;
+    int64_t s_r, s_k;   // element (row, k) at src[row * s_r + k * s_k]; one of the two is 1
+    int rows, K;
+    uint8_t* dst;       // [KB][RB][ND][64][16]
+    uint8_t* mask;      // [KB][RB]: bit i set when digit plane i of the block holds a non-zero byte
+    int RB, KB;
+};
+
+// Both operands in one launch: the first blocks0 workgroups take job0, the rest job1.  A workgroup handles one k block
+// and eight row blocks (one wave per row block and pass), an operand stored reduction-index-major goes through an LDS tile.
+template <class F>
+__global__ __launch_bounds__(256) void b8_digits_kernel(B8DigitJob job0, B8DigitJob job1, unsigned blocks0) {
+    constexpr int ND = B8Mfma<F>::ND;
+    __shared__ int64_t tab[256];
+    __shared__ __attribute__((aligned(16))) uint8_t tile[32][256];
+    const int t = threadIdx.x;
+    tab[t] = b8_fixed<F>((uint32_t)t);
+    const bool first = blockIdx.x < blocks0;
+    const B8DigitJob& job = first ? job0 : job1;
+    const unsigned lin = first ? blockIdx.x : blockIdx.x - blocks0;
+    const unsigned gx = (unsigned)((job.RB + 7) / 8);
+    const int bx = (int)(lin % gx), kb = (int)(lin / gx);
+    const bool via_lds = job.s_k != 1;
+    if (via_lds) {
+        const int kk = t >> 3, seg = (t & 7) * 32;  // thread: 32 consecutive rows at one k
+        const int k = kb * 32 + kk;
+        const int row0 = bx * 256 + seg;
+        uint32_t w[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (k < job.K && row0 < job.rows) {
+            const uint8_t* p = job.src + (int64_t)k * job.s_k + row0;
+            if (row0 + 32 <= job.rows && (((uintptr_t)p) & 15u) == 0) {
+                const uint4 v0 = reinterpret_cast<const uint4*>(p)[0], v1 = reinterpret_cast<const uint4*>(p)[1];
+                w[0] = v0.x; w[1] = v0.y; w[2] = v0.z; w[3] = v0.w; w[4] = v1.x; w[5] = v1.y; w[6] = v1.z; w[7] = v1.w;
+            } else {
+                for (int b = 0; b < 32; ++b)
+                    if (row0 + b < job.rows) w[b >> 2] |= (uint32_t)p[b] << (8 * (b & 3));
+            }
+        }
+        uint4* d = reinterpret_cast<uint4*>(&tile[kk][seg]);
+        d[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        d[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    }
+    __syncthreads();  // the table, and the tile if there is one
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int slot = t + 256 * h;
+        const int rb = bx * 8 + (slot >> 6), lane = slot & 63;  // a wave: one row block
+        if (rb >= job.RB) continue;
+        const int row = rb * 32 + (lane & 31), k0 = kb * 32 + 16 * (lane >> 5);
+        uint32_t pat[16];
+#pragma unroll
+        for (int b = 0; b < 16; ++b) pat[b] = 0;
+        if (via_lds) {
+#pragma unroll
+            for (int b = 0; b < 16; ++b) pat[b] = tile[16 * (lane >> 5) + b][(slot >> 6) * 32 + (lane & 31)];
+        } else if (row < job.rows) {
+            const uint8_t* p = job.src + (int64_t)row * job.s_r + (int64_t)k0 * job.s_k;
+            if (k0 + 16 <= job.K && (((uintptr_t)p) & 15u) == 0) {
+                const uint4 v = *reinterpret_cast<const uint4*>(p);
+                const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                for (int b = 0; b < 16; ++b) pat[b] = (wv[b >> 2] >> (8 * (b & 3))) & 0xFFu;
+            } else {
+#pragma unroll
+                for (int b = 0; b < 16; ++b)
+                    if (k0 + b < job.K) pat[b] = p[b];
+            }
+        }
+        uint32_t dig[ND][4];
+#pragma unroll
+        for (int i = 0; i < ND; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) dig[i][q] = 0;
+#pragma unroll
+        for (int b = 0; b < 16; ++b) {
+            const int64_t v = tab[pat[b]];
+            if (v == B8_NAR_VALUE) {
+                dig[ND - 1][b >> 2] |= 0x80u << (8 * (b & 3));  // the marker: top digit -128 above zeros
+                continue;
+            }
+            const bool neg = v < 0;
+            const uint64_t mag = (uint64_t)(neg ? -v : v);
+#pragma unroll
+            for (int i = 0; i < ND; ++i) {
+                const int d = (int)((mag >> (7 * i)) & 0x7Fu);
+                dig[i][b >> 2] |= ((uint32_t)(neg ? -d : d) & 0xFFu) << (8 * (b & 3));
+            }
+        }
+        uint4* out = reinterpret_cast<uint4*>(job.dst) + ((int64_t)(kb * job.RB + rb) * ND) * 64 + lane;
+        uint32_t m = 0;
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            out[i * 64] = make_uint4(dig[i][0], dig[i][1], dig[i][2], dig[i][3]);
+            if (__ballot((dig[i][0] | dig[i][1] | dig[i][2] | dig[i][3]) != 0) != 0) m |= 1u << i;
+        }
+        if (lane == 0) job.mask[(int64_t)kb * job.RB + rb] = (uint8_t)m;
+    }
+}
+
+// Ad / Bd: digit planes with RBA / RBB row blocks (multiples of 2) and KB k blocks; ma / mb their masks.
+// 64 x 64 outputs per workgroup of four waves (2 x 2), one block of 32 x 32 and its 2 ND - 1 sums per wave.
+template <class F>
+__global__ __launch_bounds__(256, (B8Mfma<F>::NC * 16 > 160 ? 1 : 2)) void b8_mfma_gemm_kernel(
+    const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, const uint8_t* __restrict__ ma, const uint8_t* __restrict__ mb, int RBA, int RBB,
+    int KB, const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M, int N, int tiles_m, int tiles_n) {
+    constexpr int ND = B8Mfma<F>::ND, NC = B8Mfma<F>::NC;
+    constexpr int RPB = 4 * ND;  // runs of 1 KB per k block: two row blocks and two column blocks of ND planes
+    typedef QuireAccum<F> AR;
+    constexpr int L = AR::L;
+    __shared__ uint4 stage[2][RPB * 64];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63, w = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int wy = w >> 1, wx = w & 1;
+    const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+
+    pm_v16i acc[NC];
+#pragma unroll
+    for (int s = 0; s < NC; ++s)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[s][r] = 0;
+
+    // copies: wave w takes ND of the k block's 4 ND runs (A: row block 0, 1; B: column block 0, 1), wave-uniform addresses
+    const int64_t a_kb = (int64_t)RBA * ND * 64, b_kb = (int64_t)RBB * ND * 64;  // words per k block
+    const uint4* src = (w < 2) ? reinterpret_cast<const uint4*>(Ad) + ((int64_t)tm * 2 + w) * ND * 64
+                               : reinterpret_cast<const uint4*>(Bd) + ((int64_t)tn * 2 + (w - 2)) * ND * 64;
+    const int64_t adv = (w < 2) ? a_kb : b_kb;
+    auto issue = [&](int buf) {
+#pragma unroll
+        for (int c = 0; c < ND; ++c)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * 64 + lane),
+                                             (__attribute__((address_space(3))) void*)(&stage[buf][0] + (w * ND + c) * 64), 16, 0, 0);
+        src += adv;
+    };
+    // masks of this wave's row block and column block, one k block ahead (every lane loads the same byte)
+    const uint8_t* pma = ma + (tm * 2 + wy);
+    const uint8_t* pmb = mb + (tn * 2 + wx);
+    uint32_t mka_next = pma[0], mkb_next = pmb[0];
+
+    uint32_t row_nar = 0, col_nar = 0;
+    issue(0);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    int cur = 0;
+    for (int kb = 0; kb < KB; ++kb, cur ^= 1) {
+        const uint32_t mka = __builtin_amdgcn_readfirstlane(mka_next), mkb = __builtin_amdgcn_readfirstlane(mkb_next);
+        if (kb + 1 < KB) {
+            issue(cur ^ 1);  // the other buffer was last read one barrier ago
+            mka_next = pma[(int64_t)(kb + 1) * RBA];
+            mkb_next = pmb[(int64_t)(kb + 1) * RBB];
+        }
+        const uint4* sa = &stage[cur][0] + (wy * ND) * 64 + lane;
+        const uint4* sb = &stage[cur][0] + ((2 + wx) * ND) * 64 + lane;
+        pm_v4i b[ND];
+#pragma unroll
+        for (int j = 0; j < ND; ++j)
+            if (mkb & (1u << j)) b[j] = __builtin_bit_cast(pm_v4i, sb[j * 64]);
+        if (mkb & (1u << (ND - 1))) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) col_nar |= pm_marker_bits((uint32_t)b[ND - 1][q]);
+        }
+#pragma unroll
+        for (int i = 0; i < ND; ++i) {
+            if (!(mka & (1u << i))) continue;
+            const pm_v4i a = __builtin_bit_cast(pm_v4i, sa[i * 64]);
+            if (i == ND - 1) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) row_nar |= pm_marker_bits((uint32_t)a[q]);
+            }
+#pragma unroll
+            for (int j = 0; j < ND; ++j)
+                if (mkb & (1u << j)) acc[i + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[j], acc[i + j], 0, 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the next k block's runs of this wave are in LDS
+        __syncthreads();
+    }
+
+    // ---- the sums into the quire, round once, store ----
+    uint32_t* rowv = reinterpret_cast<uint32_t*>(&stage[0][0]);
+    uint32_t* colv = rowv + 64;
+    row_nar = (row_nar | (uint32_t)__shfl_xor((int)row_nar, 32)) & 0x80808080u;
+    col_nar = (col_nar | (uint32_t)__shfl_xor((int)col_nar, 32)) & 0x80808080u;
+    if (lane < 32) {
+        if (wx == 0) rowv[wy * 32 + lane] = row_nar;  // the two waves of a row block saw the same rows
+        if (wy == 0) colv[wx * 32 + lane] = col_nar;
+    }
+    __syncthreads();
+    const int n = tn * 64 + wx * 32 + (lane & 31);
+    if (n >= N) return;
+    bool cnar = colv[wx * 32 + (lane & 31)] != 0;
+    uint32_t bp = 0;
+    if (bias) {
+        bp = bias[n];
+        if (bp == F::NAR) cnar = true;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int lr = (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
+        const int m = tm * 64 + wy * 32 + lr;
+        if (m >= M) continue;
+        uint32_t q[L];
+#pragma unroll
+        for (int l = 0; l < L; ++l) q[l] = 0;
+#pragma unroll
+        for (int s = 0; s < NC; ++s) Arith<F>::add_product(q, acc[s][r], 7 * s);
+        if (bias && bp != F::NAR) AR::add_bias(q, bp);
+        const bool nar = cnar || rowv[wy * 32 + lr] != 0;
+        round_store<AR, L>(q, nar, fout, C, (int64_t)m * ldc + n);
+    }
+}
+
+// ---- host side ----
+
+template <class F>
+struct B8MfmaLayout {
+    int RBA, RBB, KB;
+    size_t a_bytes, b_bytes, ma_bytes, mb_bytes;
+    size_t total() const { return a_bytes + b_bytes + ma_bytes + mb_bytes; }
+};
+
+template <class F>
+inline bool b8_mfma_fits(int64_t M, int64_t N, int64_t K) {
+    return M >= 128 && N >= 128 && K >= 256 && K <= B8Mfma<F>::MAXK && M * N * K >= ((int64_t)1 << 25) && ((M + 63) / 64) * ((N + 63) / 64) >= 32 &&
+           M <= ((int64_t)1 << 20) && N <= ((int64_t)1 << 20);
+}
+
+template <class F>
+inline B8MfmaLayout<F> b8_mfma_layout(int64_t M, int64_t N, int64_t K) {
+    constexpr int ND = B8Mfma<F>::ND;
+    B8MfmaLayout<F> l;
+    l.RBA = (int)((M + 63) / 64) * 2;
+    l.RBB = (int)((N + 63) / 64) * 2;
+    l.KB = (int)((K + 31) / 32);
+    l.a_bytes = (size_t)l.KB * l.RBA * ND * 1024;
+    l.b_bytes = (size_t)l.KB * l.RBB * ND * 1024;
+    l.ma_bytes = ((size_t)l.KB * l.RBA + 255) / 256 * 256;
+    l.mb_bytes = ((size_t)l.KB * l.RBB + 255) / 256 * 256;
+    return l;
+}
+
+template <class F>
+inline hipError_t launch_b8_mfma_gemm(hipStream_t stream, int transA, int transB, const uint8_t* A, int64_t lda, const uint8_t* B, int64_t ldb,
+                                      const uint8_t* bias, void* C, int64_t ldc, int fout, int64_t M, int64_t N, int64_t K, void* workspace) {
+    const B8MfmaLayout<F> l = b8_mfma_layout<F>(M, N, K);
+    uint8_t* base = (uint8_t*)workspace;
+    uint8_t* Ad = base;
+    uint8_t* Bd = Ad + l.a_bytes;
+    uint8_t* ma = Bd + l.b_bytes;
+    uint8_t* mb = ma + l.ma_bytes;
+    // op(A)[m,k] is A[m * lda + k] unless transA; op(B)[k,n] is B[k * ldb + n] unless transB
+    B8DigitJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, Ad, ma, l.RBA, l.KB};
+    B8DigitJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, Bd, mb, l.RBB, l.KB};
+    const unsigned blocks0 = (unsigned)((l.RBA + 7) / 8) * (unsigned)l.KB, blocks1 = (unsigned)((l.RBB + 7) / 8) * (unsigned)l.KB;
+    hipLaunchKernelGGL(b8_digits_kernel<F>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
+    PNN_CHECK_LAUNCH();
+    const int tiles_m = l.RBA / 2, tiles_n = l.RBB / 2;
+    hipLaunchKernelGGL(b8_mfma_gemm_kernel<F>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, l.RBA, l.RBB, l.KB, bias, C, ldc,
+                       fout, (int)M, (int)N, tiles_m, tiles_n);
+    return hipGetLastError();
+}
+
+}  // namespace pnn

@@ -456,6 +456,49 @@ def test_p8_gemm_packed_operands_path(M, N, K, ta, tb, fout):
         _assert_equal(got[r], want[r], "packed path row %d" % r)
 
 
+@pytest.mark.parametrize("fin", ["p8_2", "p8_1"])
+@pytest.mark.parametrize("M,N,K,ta,tb,fout", [(520, 1000, 700, 0, 0, None), (600, 900, 1030, 1, 0, "p16"), (900, 530, 999, 0, 1, None),
+                                              (515, 1100, 800, 1, 1, "p12_2"), (1024, 1024, 1024, 0, 0, None)])
+def test_b8_gemm_on_the_integer_matrix_cores(fin, M, N, K, ta, tb, fout):
+    """posit(8,1) / posit(8,2) products of 2^28 MACs and more (128 outputs each way, reductions up to 8192) rewrite both
+    operands as signed base-128 digit planes over the whole range of the format (4 / 8 planes) and run on the integer
+    matrix cores, skipping the digit planes a block does not use.  Patterns uniform over the whole format (every plane
+    in use), the four transposition cases, ragged sizes, NaR in rows and columns near the edges, a bias, a workspace full
+    of ones; the last case is Gaussian data (few planes in use: the skipping at work).  Sampled rows against the oracle,
+    the NaR rows and columns in full."""
+    fout = fout or fin
+    assert pn.posit_gemm_workspace(fin, fout, ta, tb, M, N, K) >= 4 * K * (M + N)   # at least four planes per operand
+    rng = np.random.default_rng(M + K + BITS[fin])
+    if M == 1024:
+        A = fast.round_from_float(rng.standard_normal((M, K)).astype(np.float32), fin)
+        B = fast.round_from_float((0.05 * rng.standard_normal((K, N))).astype(np.float32), fin)
+    else:
+        A = rand_patterns(rng, (K, M) if ta else (M, K), fin, special=0.001, allow_nar=False)
+        B = rand_patterns(rng, (N, K) if tb else (K, N), fin, special=0.001, allow_nar=False)
+    bias = rand_patterns(rng, (N,), fin, allow_nar=False)
+    nar_rows, nar_cols = [5, M - 1], [0, N - 2]
+    for i, r in enumerate(nar_rows):
+        k = [K - 1, 17][i]
+        if ta: A[k, r] = 0x80
+        else: A[r, k] = 0x80
+    for i, c in enumerate(nar_cols):
+        k = [3, K - 2][i]
+        if tb: B[c, k] = 0x80
+        else: B[k, c] = 0x80
+    ws = torch.full((pn.posit_gemm_workspace(fin, fout, ta, tb, M, N, K) + 64,), 0xFF, dtype=torch.uint8, device="cuda")
+    got = to_np(pn.posit_gemm(to_dev(A), to_dev(B), fin, fout, trans_a=ta, trans_b=tb, bias=to_dev(bias), workspace=ws), fout)
+    onar = 1 << (BITS[fout] - 1)
+    for r in nar_rows:
+        assert (got[r] == onar).all()
+    for c in nar_cols:
+        assert (got[:, c] == onar).all()
+    assert (got == onar).sum() == 2 * N + 2 * M - 4
+    rows = sorted(set([0, 4, 6, 31, 32, 63, 64, M - 2] + [int(r) for r in rng.integers(0, M, size=6)]) - set(nar_rows))
+    for r in rows:
+        want, _ = fast.gemm(A, B, fin, fout, trans_a=ta, trans_b=tb, bias=bias, rows=(r, r + 1))
+        _assert_equal(got[r], want[r], "matrix-core path of %s, row %d" % (fin, r))
+
+
 @pytest.mark.parametrize("M,N,K,ta,tb,kernel", [(130, 130, 259, 0, 0, "tiled dot2"), (131, 140, 300, 1, 1, "tiled dot2, transposed"),
                                                 (40, 300, 8200, 0, 0, "byte gather"), (20, 30, 300, 0, 1, "small problem"),
                                                 (1100, 1030, 16400, 0, 0, "packed operands")])
