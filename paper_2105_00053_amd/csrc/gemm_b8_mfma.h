@@ -178,29 +178,36 @@ __global__ __launch_bounds__(256, (B8Mfma<F>::NC * 16 > 160 ? 1 : 2)) void b8_mf
     const uint4* src = (w < 2) ? reinterpret_cast<const uint4*>(Ad) + ((int64_t)tm * 2 + w) * ND * 64
                                : reinterpret_cast<const uint4*>(Bd) + ((int64_t)tn * 2 + (w - 2)) * ND * 64;
     const int64_t adv = (w < 2) ? a_kb : b_kb;
-    auto issue = [&](int buf) {
+    // the empty planes of the block are not copied either (nobody reads them): mk is the mask of the block being copied
+    auto issue = [&](int buf, uint32_t mk) {
 #pragma unroll
         for (int c = 0; c < ND; ++c)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * 64 + lane),
-                                             (__attribute__((address_space(3))) void*)(&stage[buf][0] + (w * ND + c) * 64), 16, 0, 0);
+            if (mk & (1u << c))
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * 64 + lane),
+                                                 (__attribute__((address_space(3))) void*)(&stage[buf][0] + (w * ND + c) * 64), 16, 0, 0);
         src += adv;
     };
-    // masks of this wave's row block and column block, one k block ahead (every lane loads the same byte)
+    // masks, one k block ahead (every lane loads the same byte): of the row block and the column block this wave
+    // multiplies, and of the block it copies (waves 0, 1: row blocks 0, 1 of A; waves 2, 3: column blocks 0, 1 of B)
     const uint8_t* pma = ma + (tm * 2 + wy);
     const uint8_t* pmb = mb + (tn * 2 + wx);
+    const uint8_t* pmc = (w < 2) ? ma + (tm * 2 + w) : mb + (tn * 2 + (w - 2));
+    const int64_t mc_kb = (w < 2) ? RBA : RBB;
     uint32_t mka_next = pma[0], mkb_next = pmb[0];
+    uint32_t mkc_next = KB > 1 ? pmc[mc_kb] : 0u;  // of k block 1
 
     uint32_t row_nar = 0, col_nar = 0;
-    issue(0);
+    issue(0, __builtin_amdgcn_readfirstlane((uint32_t)pmc[0]));
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
     int cur = 0;
     for (int kb = 0; kb < KB; ++kb, cur ^= 1) {
         const uint32_t mka = __builtin_amdgcn_readfirstlane(mka_next), mkb = __builtin_amdgcn_readfirstlane(mkb_next);
         if (kb + 1 < KB) {
-            issue(cur ^ 1);  // the other buffer was last read one barrier ago
+            issue(cur ^ 1, __builtin_amdgcn_readfirstlane(mkc_next));  // the other buffer was last read one barrier ago
             mka_next = pma[(int64_t)(kb + 1) * RBA];
             mkb_next = pmb[(int64_t)(kb + 1) * RBB];
+            if (kb + 2 < KB) mkc_next = pmc[(int64_t)(kb + 2) * mc_kb];
         }
         const uint4* sa = &stage[cur][0] + (wy * ND) * 64 + lane;
         const uint4* sb = &stage[cur][0] + ((2 + wx) * ND) * 64 + lane;
