@@ -31,6 +31,10 @@ struct B8Mfma {
     static constexpr int ND = (BITS + 6) / 7;            // base-128 digits
     static constexpr int NC = 2 * ND - 1;                // digit positions of a product
     static constexpr int MAXK = 8192;                    // ND * 2^14 * K < 2^31
+    // When all that an operand holds lies in WIN adjacent digit planes (the usual case for the tensors of one layer: a
+    // few binades around one scale), a product kernel with 2 WIN - 1 sums instead of 2 ND - 1 serves, at twice the
+    // waves per SIMD.  0: the format has no such variant (its ND is that small already).
+    static constexpr int WIN = ND > 5 ? 5 : 0;           // 9 sums: 144 registers, two workgroups per CU
     static_assert(ND <= 8, "one mask byte per block");
     static_assert((int64_t)ND * 16384 * MAXK <= ((int64_t)1 << 31), "int32 sums");
 };
@@ -150,13 +154,60 @@ __global__ __launch_bounds__(256) void b8_digits_kernel(B8DigitJob job0, B8Digit
     }
 }
 
+// all[o] = the OR of the n[o] mask bytes of operand o (o = blockIdx.x: 0, 1): which digit planes the operand uses at all.
+// m0 / m1 are 16-byte aligned.
+template <int UNUSED = 0>
+__global__ __launch_bounds__(1024) void b8_mask_union_kernel(const uint8_t* __restrict__ m0, int64_t n0, const uint8_t* __restrict__ m1, int64_t n1,
+                                                             uint32_t* __restrict__ all) {
+    __shared__ uint32_t part[16];
+    const uint8_t* m = blockIdx.x == 0 ? m0 : m1;
+    const int64_t n = blockIdx.x == 0 ? n0 : n1;
+    const int t = threadIdx.x;
+    uint32_t u = 0;
+    const int64_t n16 = n >> 4;
+    for (int64_t i = t; i < n16; i += 1024) {
+        const uint4 v = reinterpret_cast<const uint4*>(m)[i];
+        u |= v.x | v.y | v.z | v.w;
+    }
+    u |= u >> 16;
+    u |= u >> 8;
+    for (int64_t i = (n16 << 4) + t; i < n; i += 1024) u |= m[i];
+    u &= 0xFFu;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) u |= (uint32_t)__shfl_xor((int)u, d);
+    if ((t & 63) == 0) part[t >> 6] = u;
+    __syncthreads();
+    if (t == 0) {
+        uint32_t r = 0;
+        for (int i = 0; i < 16; ++i) r |= part[i];
+        all[blockIdx.x] = r;
+    }
+}
+
 // Ad / Bd: digit planes with RBA / RBB row blocks (multiples of 2) and KB k blocks; ma / mb their masks.
-// 64 x 64 outputs per workgroup of four waves (2 x 2), one block of 32 x 32 and its 2 ND - 1 sums per wave.
-template <class F>
-__global__ __launch_bounds__(256, (B8Mfma<F>::NC * 16 > 160 ? 1 : 2)) void b8_mfma_gemm_kernel(
-    const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, const uint8_t* __restrict__ ma, const uint8_t* __restrict__ mb, int RBA, int RBB,
-    int KB, const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M, int N, int tiles_m, int tiles_n) {
-    constexpr int ND = B8Mfma<F>::ND, NC = B8Mfma<F>::NC;
+// 64 x 64 outputs per workgroup of four waves (2 x 2), one block of 32 x 32 and its sums per wave.
+//
+// NP = ND: every digit plane takes part, 2 ND - 1 sums.  NP = B8Mfma<F>::WIN < ND: the planes oa .. oa + NP - 1 of A and
+// ob .. ob + NP - 1 of B, where oa / ob is the lowest plane that the operand uses anywhere; sum s then stands at digit
+// position s + oa + ob.  all[0] / all[1] (the OR of the operand's masks) says which of the two applies: both kernels
+// are launched and the one whose case it is not returns at once.
+template <class F, int NP>
+__global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfma_gemm_kernel(
+    const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, const uint8_t* __restrict__ ma, const uint8_t* __restrict__ mb,
+    const uint32_t* __restrict__ all, int RBA, int RBB, int KB, const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M, int N,
+    int tiles_m, int tiles_n) {
+    constexpr int ND = B8Mfma<F>::ND, NC = 2 * NP - 1, WIN = B8Mfma<F>::WIN;
+    int oa = 0, ob = 0;
+    if constexpr (WIN != 0) {
+        const uint32_t ga = __builtin_amdgcn_readfirstlane(all[0]), gb = __builtin_amdgcn_readfirstlane(all[1]);
+        const int la = ga ? __builtin_ctz(ga) : 0, lb = gb ? __builtin_ctz(gb) : 0;
+        const bool narrow = (ga >> la) < (1u << WIN) && (gb >> lb) < (1u << WIN);
+        if (narrow != (NP == WIN)) return;
+        if (NP == WIN) {
+            oa = la;
+            ob = lb;
+        }
+    }
     constexpr int RPB = 4 * ND;  // runs of 1 KB per k block: two row blocks and two column blocks of ND planes
     typedef QuireAccum<F> AR;
     constexpr int L = AR::L;
@@ -202,33 +253,35 @@ __global__ __launch_bounds__(256, (B8Mfma<F>::NC * 16 > 160 ? 1 : 2)) void b8_mf
     __syncthreads();
     int cur = 0;
     for (int kb = 0; kb < KB; ++kb, cur ^= 1) {
-        const uint32_t mka = __builtin_amdgcn_readfirstlane(mka_next), mkb = __builtin_amdgcn_readfirstlane(mkb_next);
+        const uint32_t mka = __builtin_amdgcn_readfirstlane(mka_next) >> oa, mkb = __builtin_amdgcn_readfirstlane(mkb_next) >> ob;
         if (kb + 1 < KB) {
             issue(cur ^ 1, __builtin_amdgcn_readfirstlane(mkc_next));  // the other buffer was last read one barrier ago
             mka_next = pma[(int64_t)(kb + 1) * RBA];
             mkb_next = pmb[(int64_t)(kb + 1) * RBB];
             if (kb + 2 < KB) mkc_next = pmc[(int64_t)(kb + 2) * mc_kb];
         }
-        const uint4* sa = &stage[cur][0] + (wy * ND) * 64 + lane;
-        const uint4* sb = &stage[cur][0] + ((2 + wx) * ND) * 64 + lane;
-        pm_v4i b[ND];
+        const uint4* sa = &stage[cur][0] + (wy * ND + oa) * 64 + lane;
+        const uint4* sb = &stage[cur][0] + ((2 + wx) * ND + ob) * 64 + lane;
+        pm_v4i b[NP];
 #pragma unroll
-        for (int j = 0; j < ND; ++j)
-            if (mkb & (1u << j)) b[j] = __builtin_bit_cast(pm_v4i, sb[j * 64]);
-        if (mkb & (1u << (ND - 1))) {
+        for (int j = 0; j < NP; ++j) {
+            if (!(mkb & (1u << j))) continue;
+            b[j] = __builtin_bit_cast(pm_v4i, sb[j * 64]);
+            if (ob + j == ND - 1) {  // the plane of the NaR marker
 #pragma unroll
-            for (int q = 0; q < 4; ++q) col_nar |= pm_marker_bits((uint32_t)b[ND - 1][q]);
+                for (int q = 0; q < 4; ++q) col_nar |= pm_marker_bits((uint32_t)b[j][q]);
+            }
         }
 #pragma unroll
-        for (int i = 0; i < ND; ++i) {
+        for (int i = 0; i < NP; ++i) {
             if (!(mka & (1u << i))) continue;
             const pm_v4i a = __builtin_bit_cast(pm_v4i, sa[i * 64]);
-            if (i == ND - 1) {
+            if (oa + i == ND - 1) {
 #pragma unroll
                 for (int q = 0; q < 4; ++q) row_nar |= pm_marker_bits((uint32_t)a[q]);
             }
 #pragma unroll
-            for (int j = 0; j < ND; ++j)
+            for (int j = 0; j < NP; ++j)
                 if (mkb & (1u << j)) acc[i + j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b[j], acc[i + j], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);
@@ -263,7 +316,7 @@ __global__ __launch_bounds__(256, (B8Mfma<F>::NC * 16 > 160 ? 1 : 2)) void b8_mf
 #pragma unroll
         for (int l = 0; l < L; ++l) q[l] = 0;
 #pragma unroll
-        for (int s = 0; s < NC; ++s) Arith<F>::add_product(q, acc[s][r], 7 * s);
+        for (int s = 0; s < NC; ++s) Arith<F>::add_product(q, acc[s][r], 7 * (s + oa + ob));
         if (bias && bp != F::NAR) AR::add_bias(q, bp);
         const bool nar = cnar || rowv[wy * 32 + lr] != 0;
         round_store<AR, L>(q, nar, fout, C, (int64_t)m * ldc + n);
@@ -276,7 +329,7 @@ template <class F>
 struct B8MfmaLayout {
     int RBA, RBB, KB;
     size_t a_bytes, b_bytes, ma_bytes, mb_bytes;
-    size_t total() const { return a_bytes + b_bytes + ma_bytes + mb_bytes; }
+    size_t total() const { return a_bytes + b_bytes + ma_bytes + mb_bytes + 256; }  // and the two words of all masks
 };
 
 template <class F>
@@ -308,6 +361,7 @@ inline hipError_t launch_b8_mfma_gemm(hipStream_t stream, int transA, int transB
     uint8_t* Bd = Ad + l.a_bytes;
     uint8_t* ma = Bd + l.b_bytes;
     uint8_t* mb = ma + l.ma_bytes;
+    uint32_t* all = (uint32_t*)(mb + l.mb_bytes);
     // op(A)[m,k] is A[m * lda + k] unless transA; op(B)[k,n] is B[k * ldb + n] unless transB
     B8DigitJob ja{A, transA ? (int64_t)1 : lda, transA ? lda : (int64_t)1, (int)M, (int)K, Ad, ma, l.RBA, l.KB};
     B8DigitJob jb{B, transB ? ldb : (int64_t)1, transB ? (int64_t)1 : ldb, (int)N, (int)K, Bd, mb, l.RBB, l.KB};
@@ -315,8 +369,16 @@ inline hipError_t launch_b8_mfma_gemm(hipStream_t stream, int transA, int transB
     hipLaunchKernelGGL(b8_digits_kernel<F>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
     const int tiles_m = l.RBA / 2, tiles_n = l.RBB / 2;
-    hipLaunchKernelGGL(b8_mfma_gemm_kernel<F>, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, l.RBA, l.RBB, l.KB, bias, C, ldc,
-                       fout, (int)M, (int)N, tiles_m, tiles_n);
+    constexpr int ND = B8Mfma<F>::ND, WIN = B8Mfma<F>::WIN;
+    if constexpr (WIN != 0) {
+        hipLaunchKernelGGL(b8_mask_union_kernel<0>, dim3(2), dim3(1024), 0, stream, ma, (int64_t)l.KB * l.RBA, mb, (int64_t)l.KB * l.RBB, all);
+        PNN_CHECK_LAUNCH();
+        hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB,
+                           bias, C, ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
+        PNN_CHECK_LAUNCH();
+    }
+    hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, ND>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C,
+                       ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
     return hipGetLastError();
 }
 

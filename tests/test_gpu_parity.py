@@ -499,6 +499,52 @@ def test_b8_gemm_on_the_integer_matrix_cores(fin, M, N, K, ta, tb, fout):
         _assert_equal(got[r], want[r], "matrix-core path of %s, row %d" % (fin, r))
 
 
+@pytest.mark.parametrize("fin", ["p8_2", "p8_1"])
+@pytest.mark.parametrize("case", ["gaussian", "offset", "offset and NaR", "wide"])
+def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
+    """posit(8,2) operands whose digits all lie in five adjacent planes take a product kernel with nine sums, counted
+    from the lowest plane each operand uses; anything wider (and posit(8,1) always) takes the one over all planes.
+    gaussian: planes from 0 up.  offset: A in +-[1, 64), B in +-[2^-10, 2^-4): both windows start above plane 0.
+    offset and NaR: values from 1/8 up and NaR, whose marker in the top plane is then inside the window.  wide: Gaussian
+    data plus a few huge and a few tiny values.  Sampled rows and the NaR rows / columns against the oracle."""
+    M, N, K, ta, tb = 640, 520, 1100, 0, 1
+    rng = np.random.default_rng(len(case) + BITS[fin] + int(fin[-1]))
+
+    def signed_log_uniform(shape, lo, hi):
+        mag = np.exp2(rng.uniform(lo, hi, size=shape))
+        return (mag * rng.choice([-1.0, 1.0], size=shape)).astype(np.float32)
+
+    if case == "gaussian":
+        Af, Bf = rng.standard_normal((M, K)), 0.05 * rng.standard_normal((N, K))
+    elif case == "offset":
+        Af, Bf = signed_log_uniform((M, K), 0, 6), signed_log_uniform((N, K), -10, -4)
+    elif case == "offset and NaR":
+        Af, Bf = signed_log_uniform((M, K), 0, 6), signed_log_uniform((N, K), -3, 3)
+    else:
+        Af, Bf = rng.standard_normal((M, K)), rng.standard_normal((N, K))
+        Af[rng.integers(0, M, 5), rng.integers(0, K, 5)] = 3000.0
+        Bf[rng.integers(0, N, 5), rng.integers(0, K, 5)] = 1e-6
+    A = fast.round_from_float(np.asarray(Af, dtype=np.float32), fin)
+    B = fast.round_from_float(np.asarray(Bf, dtype=np.float32), fin)
+    nar_rows, nar_cols = [], []
+    if case == "offset and NaR":
+        nar_rows, nar_cols = [7, M - 1], [N - 3]
+        A[7, K - 1] = A[M - 1, 40] = 0x80
+        B[N - 3, 0] = 0x80
+    ws = torch.full((pn.posit_gemm_workspace(fin, fin, ta, tb, M, N, K) + 64,), 0xFF, dtype=torch.uint8, device="cuda")
+    got = to_np(pn.posit_gemm(to_dev(A), to_dev(B), fin, fin, trans_a=ta, trans_b=tb, workspace=ws), fin)
+    for r in nar_rows:
+        assert (got[r] == 0x80).all()
+    for c in nar_cols:
+        assert (got[:, c] == 0x80).all()
+    assert (got == 0x80).sum() == len(nar_rows) * N + len(nar_cols) * (M - len(nar_rows))
+    rows = sorted(set([0, 31, 32, 63, 64, M - 2] + [int(r) for r in rng.integers(0, M, size=6)]) - set(nar_rows))
+    for r in rows:
+        want, _ = fast.gemm(A, B, fin, fin, trans_a=ta, trans_b=tb, rows=(r, r + 1))
+        _assert_equal(got[r], want[r], "%s, %s operands, row %d" % (fin, case, r))
+    assert len(set(got[rows].ravel().tolist())) > 8   # not a constant
+
+
 @pytest.mark.parametrize("M,N,K,ta,tb,kernel", [(130, 130, 259, 0, 0, "tiled dot2"), (131, 140, 300, 1, 1, "tiled dot2, transposed"),
                                                 (40, 300, 8200, 0, 0, "byte gather"), (20, 30, 300, 0, 1, "small problem"),
                                                 (1100, 1030, 16400, 0, 0, "packed operands")])
