@@ -135,7 +135,7 @@ def extra_measurements(torch, pn, workloads):
     out = {}
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
     for cfg, fmt, S, sigma, ext in ((5, "p8", 1024, 1.0, False), (5, "p8", 2048, 1.0, False), (2, "p16", 1024, 0.1, True), (5, "p32", 1024, 1.0, False),
-                                    (5, "p8_2", 1024, 1.0, False)):
+                                    (5, "p8_2", 1024, 1.0, False), (5, "p8_2", 4096, 1.0, False)):
         A, B = workloads.gemm_operands(cfg, S, sigma=sigma, extremes=ext)
         Ap, Bp = pn.posit_round(dev(A), fmt), pn.posit_round(dev(B), fmt)
         C = torch.empty((S, S), dtype=Ap.dtype, device="cuda")
