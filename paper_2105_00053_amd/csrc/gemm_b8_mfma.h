@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfm
             ob = lb;
         }
     }
-    constexpr int RPB = 4 * ND;  // runs of 1 KB per k block: two row blocks and two column blocks of ND planes
+    constexpr int RPB = 4 * NP;  // runs of 1 KB per k block: two row blocks and two column blocks of NP planes
     typedef QuireAccum<F> AR;
     constexpr int L = AR::L;
     __shared__ uint4 stage[2][RPB * 64];
@@ -229,13 +229,16 @@ __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfm
     const uint4* src = (w < 2) ? reinterpret_cast<const uint4*>(Ad) + ((int64_t)tm * 2 + w) * ND * 64
                                : reinterpret_cast<const uint4*>(Bd) + ((int64_t)tn * 2 + (w - 2)) * ND * 64;
     const int64_t adv = (w < 2) ? a_kb : b_kb;
+    const int oc = (w < 2) ? oa : ob;  // the first plane that takes part, of the operand this wave copies
+    src += oc * 64;
     // the empty planes of the block are not copied either (nobody reads them): mk is the mask of the block being copied
     auto issue = [&](int buf, uint32_t mk) {
+        mk >>= oc;
 #pragma unroll
-        for (int c = 0; c < ND; ++c)
+        for (int c = 0; c < NP; ++c)
             if (mk & (1u << c))
                 __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + c * 64 + lane),
-                                                 (__attribute__((address_space(3))) void*)(&stage[buf][0] + (w * ND + c) * 64), 16, 0, 0);
+                                                 (__attribute__((address_space(3))) void*)(&stage[buf][0] + (w * NP + c) * 64), 16, 0, 0);
         src += adv;
     };
     // masks, one k block ahead (every lane loads the same byte): of the row block and the column block this wave
@@ -260,8 +263,8 @@ __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfm
             mkb_next = pmb[(int64_t)(kb + 1) * RBB];
             if (kb + 2 < KB) mkc_next = pmc[(int64_t)(kb + 2) * mc_kb];
         }
-        const uint4* sa = &stage[cur][0] + (wy * ND + oa) * 64 + lane;
-        const uint4* sb = &stage[cur][0] + ((2 + wx) * ND + ob) * 64 + lane;
+        const uint4* sa = &stage[cur][0] + (wy * NP) * 64 + lane;
+        const uint4* sb = &stage[cur][0] + ((2 + wx) * NP) * 64 + lane;
         pm_v4i b[NP];
 #pragma unroll
         for (int j = 0; j < NP; ++j) {
