@@ -31,10 +31,12 @@ struct B8Mfma {
     static constexpr int ND = (BITS + 6) / 7;            // base-128 digits
     static constexpr int NC = 2 * ND - 1;                // digit positions of a product
     static constexpr int MAXK = 8192;                    // ND * 2^14 * K < 2^31
-    // When all that an operand holds lies in WIN adjacent digit planes (the usual case for the tensors of one layer: a
-    // few binades around one scale), a product kernel with 2 WIN - 1 sums instead of 2 ND - 1 serves, at twice the
-    // waves per SIMD.  0: the format has no such variant (its ND is that small already).
-    static constexpr int WIN = ND > 5 ? 5 : 0;           // 9 sums: 144 registers, two workgroups per CU
+    // When all that an operand holds lies in a few adjacent digit planes (the usual case for the tensors of one layer: a
+    // few binades around one scale), a product kernel over WIN4 or WIN5 planes serves, with 7 or 9 sums instead of
+    // 2 ND - 1: 112 / 144 registers, three / two waves per SIMD instead of one.  0: the format has no such variants
+    // (its ND is that small already).
+    static constexpr int WIN4 = ND > 5 ? 4 : 0, WIN5 = ND > 5 ? 5 : 0;
+    static constexpr int64_t WIN5_MIN_MNK = (int64_t)1 << 31;  // below, the launch of a third kernel costs more than it saves
     static_assert(ND <= 8, "one mask byte per block");
     static_assert((int64_t)ND * 16384 * MAXK <= ((int64_t)1 << 31), "int32 sums");
 };
@@ -187,23 +189,26 @@ __global__ __launch_bounds__(1024) void b8_mask_union_kernel(const uint8_t* __re
 // Ad / Bd: digit planes with RBA / RBB row blocks (multiples of 2) and KB k blocks; ma / mb their masks.
 // 64 x 64 outputs per workgroup of four waves (2 x 2), one block of 32 x 32 and its sums per wave.
 //
-// NP = ND: every digit plane takes part, 2 ND - 1 sums.  NP = B8Mfma<F>::WIN < ND: the planes oa .. oa + NP - 1 of A and
+// NP = ND: every digit plane takes part, 2 ND - 1 sums.  NP < ND: the planes oa .. oa + NP - 1 of A and
 // ob .. ob + NP - 1 of B, where oa / ob is the lowest plane that the operand uses anywhere; sum s then stands at digit
-// position s + oa + ob.  all[0] / all[1] (the OR of the operand's masks) says which of the two applies: both kernels
-// are launched and the one whose case it is not returns at once.
+// position s + oa + ob.  all[0] / all[1] (the OR of the operand's masks) gives the span of planes the operands use; the
+// kernels of several NP are launched one after the other, each told the next smaller NP launched (below, 0 if none),
+// and only the smallest one that covers the span does the work: the others return at once.
 template <class F, int NP>
 __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfma_gemm_kernel(
     const uint8_t* __restrict__ Ad, const uint8_t* __restrict__ Bd, const uint8_t* __restrict__ ma, const uint8_t* __restrict__ mb,
     const uint32_t* __restrict__ all, int RBA, int RBB, int KB, const uint8_t* __restrict__ bias, void* __restrict__ C, int64_t ldc, int fout, int M, int N,
-    int tiles_m, int tiles_n) {
-    constexpr int ND = B8Mfma<F>::ND, NC = 2 * NP - 1, WIN = B8Mfma<F>::WIN;
+    int tiles_m, int tiles_n, int below) {
+    constexpr int ND = B8Mfma<F>::ND, NC = 2 * NP - 1;
     int oa = 0, ob = 0;
-    if constexpr (WIN != 0) {
+    if constexpr (B8Mfma<F>::WIN4 != 0) {
         const uint32_t ga = __builtin_amdgcn_readfirstlane(all[0]), gb = __builtin_amdgcn_readfirstlane(all[1]);
         const int la = ga ? __builtin_ctz(ga) : 0, lb = gb ? __builtin_ctz(gb) : 0;
-        const bool narrow = (ga >> la) < (1u << WIN) && (gb >> lb) < (1u << WIN);
-        if (narrow != (NP == WIN)) return;
-        if (NP == WIN) {
+        const uint32_t u = (ga >> la) | (gb >> lb);
+        const int span = u ? 32 - __builtin_clz(u) : 0;  // planes from the lowest to the highest one in use
+        if (below > 0 && span <= below) return;          // a smaller kernel serves
+        if constexpr (NP < ND) {
+            if (span > NP) return;                       // a larger one
             oa = la;
             ob = lb;
         }
@@ -372,16 +377,25 @@ inline hipError_t launch_b8_mfma_gemm(hipStream_t stream, int transA, int transB
     hipLaunchKernelGGL(b8_digits_kernel<F>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
     const int tiles_m = l.RBA / 2, tiles_n = l.RBB / 2;
-    constexpr int ND = B8Mfma<F>::ND, WIN = B8Mfma<F>::WIN;
-    if constexpr (WIN != 0) {
+    constexpr int ND = B8Mfma<F>::ND, WIN4 = B8Mfma<F>::WIN4, WIN5 = B8Mfma<F>::WIN5;
+    const dim3 grid((unsigned)(tiles_m * tiles_n));
+    int below = 0;
+    if constexpr (WIN4 != 0) {
         hipLaunchKernelGGL(b8_mask_union_kernel<0>, dim3(2), dim3(1024), 0, stream, ma, (int64_t)l.KB * l.RBA, mb, (int64_t)l.KB * l.RBB, all);
         PNN_CHECK_LAUNCH();
-        hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB,
-                           bias, C, ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
+        hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN4>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M,
+                           (int)N, tiles_m, tiles_n, 0);
         PNN_CHECK_LAUNCH();
+        below = WIN4;
+        if (M * N * K >= B8Mfma<F>::WIN5_MIN_MNK) {
+            hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN5>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M,
+                               (int)N, tiles_m, tiles_n, WIN4);
+            PNN_CHECK_LAUNCH();
+            below = WIN5;
+        }
     }
-    hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, ND>), dim3((unsigned)(tiles_m * tiles_n)), dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C,
-                       ldc, fout, (int)M, (int)N, tiles_m, tiles_n);
+    hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, ND>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M, (int)N,
+                       tiles_m, tiles_n, below);
     return hipGetLastError();
 }
 

@@ -500,14 +500,16 @@ def test_b8_gemm_on_the_integer_matrix_cores(fin, M, N, K, ta, tb, fout):
 
 
 @pytest.mark.parametrize("fin", ["p8_2", "p8_1"])
-@pytest.mark.parametrize("case", ["gaussian", "offset", "offset and NaR", "wide"])
+@pytest.mark.parametrize("case", ["gaussian", "offset", "offset and NaR", "wide", "five planes", "zero"])
 def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
-    """posit(8,2) operands whose digits all lie in five adjacent planes take a product kernel with nine sums, counted
-    from the lowest plane each operand uses; anything wider (and posit(8,1) always) takes the one over all planes.
+    """posit(8,2) operands whose digits all lie in four (five, from 2^31 products on) adjacent planes take a product
+    kernel with seven (nine) sums, counted from the lowest plane each operand uses; anything wider (and posit(8,1)
+    always) takes the one over all planes.
     gaussian: planes from 0 up.  offset: A in +-[1, 64), B in +-[2^-10, 2^-4): both windows start above plane 0.
     offset and NaR: values from 1/8 up and NaR, whose marker in the top plane is then inside the window.  wide: Gaussian
-    data plus a few huge and a few tiny values.  Sampled rows and the NaR rows / columns against the oracle."""
-    M, N, K, ta, tb = 640, 520, 1100, 0, 1
+    data plus a few huge and a few tiny values.  five planes: A over 2^-13 .. 2^16 in a product large enough for the
+    nine-sum kernel.  zero: A is all zeros (no plane in use).  Sampled rows and the NaR rows / columns against the oracle."""
+    M, N, K, ta, tb = (1280, 1300, 1400, 0, 1) if case == "five planes" else (640, 520, 1100, 0, 1)
     rng = np.random.default_rng(len(case) + BITS[fin] + int(fin[-1]))
 
     def signed_log_uniform(shape, lo, hi):
@@ -520,6 +522,10 @@ def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
         Af, Bf = signed_log_uniform((M, K), 0, 6), signed_log_uniform((N, K), -10, -4)
     elif case == "offset and NaR":
         Af, Bf = signed_log_uniform((M, K), 0, 6), signed_log_uniform((N, K), -3, 3)
+    elif case == "five planes":
+        Af, Bf = signed_log_uniform((M, K), -13, 16), rng.standard_normal((N, K))
+    elif case == "zero":
+        Af, Bf = np.zeros((M, K)), rng.standard_normal((N, K))
     else:
         Af, Bf = rng.standard_normal((M, K)), rng.standard_normal((N, K))
         Af[rng.integers(0, M, 5), rng.integers(0, K, 5)] = 3000.0
@@ -542,7 +548,10 @@ def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
     for r in rows:
         want, _ = fast.gemm(A, B, fin, fin, trans_a=ta, trans_b=tb, rows=(r, r + 1))
         _assert_equal(got[r], want[r], "%s, %s operands, row %d" % (fin, case, r))
-    assert len(set(got[rows].ravel().tolist())) > 8   # not a constant
+    if case == "zero":
+        assert (got == 0).all()
+    else:
+        assert len(set(got[rows].ravel().tolist())) > 8   # not a constant
 
 
 @pytest.mark.parametrize("M,N,K,ta,tb,kernel", [(130, 130, 259, 0, 0, "tiled dot2"), (131, 140, 300, 1, 1, "tiled dot2, transposed"),
