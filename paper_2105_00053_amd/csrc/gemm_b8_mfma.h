@@ -32,11 +32,12 @@ struct B8Mfma {
     static constexpr int NC = 2 * ND - 1;                // digit positions of a product
     static constexpr int MAXK = 8192;                    // ND * 2^14 * K < 2^31
     // When all that an operand holds lies in a few adjacent digit planes (the usual case for the tensors of one layer: a
-    // few binades around one scale), a product kernel over WIN4 or WIN5 planes serves, with 7 or 9 sums instead of
-    // 2 ND - 1: 112 / 144 registers, three / two waves per SIMD instead of one.  0: the format has no such variants
-    // (its ND is that small already).
-    static constexpr int WIN4 = ND > 5 ? 4 : 0, WIN5 = ND > 5 ? 5 : 0;
-    static constexpr int64_t WIN5_MIN_MNK = (int64_t)1 << 31;  // below, the launch of a third kernel costs more than it saves
+    // few binades around one scale), a product kernel over WINA or WINB planes serves: posit(8,2) 4 or 5 planes, 7 or 9
+    // sums instead of 15 (112 / 144 registers, three / two waves per SIMD instead of one); posit(8,1) 3 planes, 5 sums
+    // instead of 7.  0: no such variant.
+    static constexpr int WINA = ND > 5 ? 4 : (ND == 4 ? 3 : 0), WINB = ND > 5 ? 5 : 0;
+    // below these sizes the launches of the union and of one more product kernel cost more than the variant saves
+    static constexpr int64_t WINA_MIN_MNK = ND > 5 ? 0 : (int64_t)1 << 32, WINB_MIN_MNK = (int64_t)1 << 31;
     static_assert(ND <= 8, "one mask byte per block");
     static_assert((int64_t)ND * 16384 * MAXK <= ((int64_t)1 << 31), "int32 sums");
 };
@@ -201,7 +202,7 @@ __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfm
     int tiles_m, int tiles_n, int below) {
     constexpr int ND = B8Mfma<F>::ND, NC = 2 * NP - 1;
     int oa = 0, ob = 0;
-    if constexpr (B8Mfma<F>::WIN4 != 0) {
+    if constexpr (B8Mfma<F>::WINA != 0) {
         const uint32_t ga = __builtin_amdgcn_readfirstlane(all[0]), gb = __builtin_amdgcn_readfirstlane(all[1]);
         const int la = ga ? __builtin_ctz(ga) : 0, lb = gb ? __builtin_ctz(gb) : 0;
         const uint32_t u = (ga >> la) | (gb >> lb);
@@ -377,21 +378,23 @@ inline hipError_t launch_b8_mfma_gemm(hipStream_t stream, int transA, int transB
     hipLaunchKernelGGL(b8_digits_kernel<F>, dim3(blocks0 + blocks1), dim3(256), 0, stream, ja, jb, blocks0);
     PNN_CHECK_LAUNCH();
     const int tiles_m = l.RBA / 2, tiles_n = l.RBB / 2;
-    constexpr int ND = B8Mfma<F>::ND, WIN4 = B8Mfma<F>::WIN4, WIN5 = B8Mfma<F>::WIN5;
+    constexpr int ND = B8Mfma<F>::ND, WINA = B8Mfma<F>::WINA, WINB = B8Mfma<F>::WINB;
     const dim3 grid((unsigned)(tiles_m * tiles_n));
     int below = 0;
-    if constexpr (WIN4 != 0) {
+    if constexpr (WINA != 0) if (M * N * K >= B8Mfma<F>::WINA_MIN_MNK) {
         hipLaunchKernelGGL(b8_mask_union_kernel<0>, dim3(2), dim3(1024), 0, stream, ma, (int64_t)l.KB * l.RBA, mb, (int64_t)l.KB * l.RBB, all);
         PNN_CHECK_LAUNCH();
-        hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN4>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M,
+        hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WINA>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M,
                            (int)N, tiles_m, tiles_n, 0);
         PNN_CHECK_LAUNCH();
-        below = WIN4;
-        if (M * N * K >= B8Mfma<F>::WIN5_MIN_MNK) {
-            hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WIN5>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M,
-                               (int)N, tiles_m, tiles_n, WIN4);
-            PNN_CHECK_LAUNCH();
-            below = WIN5;
+        below = WINA;
+        if constexpr (WINB != 0) {
+            if (M * N * K >= B8Mfma<F>::WINB_MIN_MNK) {
+                hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, WINB>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout,
+                                   (int)M, (int)N, tiles_m, tiles_n, WINA);
+                PNN_CHECK_LAUNCH();
+                below = WINB;
+            }
         }
     }
     hipLaunchKernelGGL((b8_mfma_gemm_kernel<F, ND>), grid, dim3(256), 0, stream, Ad, Bd, ma, mb, all, l.RBA, l.RBB, l.KB, bias, C, ldc, fout, (int)M, (int)N,

@@ -500,23 +500,23 @@ def test_b8_gemm_on_the_integer_matrix_cores(fin, M, N, K, ta, tb, fout):
 
 
 @pytest.mark.parametrize("fin", ["p8_2", "p8_1"])
-@pytest.mark.parametrize("case", ["gaussian", "offset", "offset and NaR", "wide", "five planes", "zero"])
+@pytest.mark.parametrize("case", ["gaussian", "offset", "offset and NaR", "wide", "five planes", "gaussian, large", "zero"])
 def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
     """posit(8,2) operands whose digits all lie in four (five, from 2^31 products on) adjacent planes take a product
-    kernel with seven (nine) sums, counted from the lowest plane each operand uses; anything wider (and posit(8,1)
-    always) takes the one over all planes.
+    kernel with seven (nine) sums, counted from the lowest plane each operand uses; anything wider takes the one over
+    all planes.  posit(8,1) has a three-plane kernel, used from 2^32 products on.
     gaussian: planes from 0 up.  offset: A in +-[1, 64), B in +-[2^-10, 2^-4): both windows start above plane 0.
     offset and NaR: values from 1/8 up and NaR, whose marker in the top plane is then inside the window.  wide: Gaussian
     data plus a few huge and a few tiny values.  five planes: A over 2^-13 .. 2^16 in a product large enough for the
-    nine-sum kernel.  zero: A is all zeros (no plane in use).  Sampled rows and the NaR rows / columns against the oracle."""
-    M, N, K, ta, tb = (1280, 1300, 1400, 0, 1) if case == "five planes" else (640, 520, 1100, 0, 1)
+    nine-sum kernel.  gaussian, large: the size at which posit(8,1) takes its narrow kernel.  zero: A is all zeros (no plane in use).  Sampled rows and the NaR rows / columns against the oracle."""
+    M, N, K, ta, tb = (1664, 1700, 1536, 0, 1) if case in ("five planes", "gaussian, large") else (640, 520, 1100, 0, 1)
     rng = np.random.default_rng(len(case) + BITS[fin] + int(fin[-1]))
 
     def signed_log_uniform(shape, lo, hi):
         mag = np.exp2(rng.uniform(lo, hi, size=shape))
         return (mag * rng.choice([-1.0, 1.0], size=shape)).astype(np.float32)
 
-    if case == "gaussian":
+    if case in ("gaussian", "gaussian, large"):
         Af, Bf = rng.standard_normal((M, K)), 0.05 * rng.standard_normal((N, K))
     elif case == "offset":
         Af, Bf = signed_log_uniform((M, K), 0, 6), signed_log_uniform((N, K), -10, -4)
