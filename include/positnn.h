@@ -84,7 +84,8 @@ typedef enum {
  * when that query returns 0.  Its contents on entry do not matter and are not
  * preserved (partial quires of a split reduction; both operands rewritten once:
  * for posit<8,0> products of 2^28 multiply-adds and more as two int8 digit planes
- * each, 2 bytes per element; for posit<16,1> and the 10- / 12-bit formats from
+ * each, 2 bytes per element; for posit<8,1> / posit<8,2> products of 2^25 and more
+ * (128 outputs each way, K from 256 to 8192) as four / eight; for posit<16,1> and the 10- / 12-bit formats from
  * 96 x 96 outputs on as doubles, 8 bytes per element). */
 int posit_gemm(void* stream, int fin, int fout, int transA, int transB,
                int64_t M, int64_t N, int64_t K,
