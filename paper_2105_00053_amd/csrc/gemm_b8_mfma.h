@@ -150,8 +150,11 @@ __global__ __launch_bounds__(256) void b8_digits_kernel(B8DigitJob job0, B8Digit
         uint32_t m = 0;
 #pragma unroll
         for (int i = 0; i < ND; ++i) {
-            out[i * 64] = make_uint4(dig[i][0], dig[i][1], dig[i][2], dig[i][3]);
-            if (__ballot((dig[i][0] | dig[i][1] | dig[i][2] | dig[i][3]) != 0) != 0) m |= 1u << i;
+            // an empty plane is not written: the mask keeps the product kernel from copying or reading it
+            if (__ballot((dig[i][0] | dig[i][1] | dig[i][2] | dig[i][3]) != 0) != 0) {
+                m |= 1u << i;
+                out[i * 64] = make_uint4(dig[i][0], dig[i][1], dig[i][2], dig[i][3]);
+            }
         }
         if (lane == 0) job.mask[(int64_t)kb * job.RB + rb] = (uint8_t)m;
     }
