@@ -554,6 +554,48 @@ def test_b8_gemm_matrix_cores_narrow_and_wide_operands(fin, case):
         assert len(set(got[rows].ravel().tolist())) > 8   # not a constant
 
 
+def test_b8_gemm_graph_replay_follows_the_data():
+    """Which posit(8,2) product kernel does the work is decided on the device, from the operands' plane masks, so a
+    captured call must follow the data of each replay: narrow operands, then operands over the whole range, then NaR,
+    then narrow ones again, every replay compared with an eager call on the same operands (bit for bit) and the first
+    one with the oracle on sampled rows."""
+    fin, M, N, K = "p8_2", 384, 448, 1024
+    rng = np.random.default_rng(82)
+    narrow = lambda shape, s: fast.round_from_float((s * rng.standard_normal(shape)).astype(np.float32), fin)
+    fills = [(narrow((M, K), 1.0), narrow((K, N), 0.05)),
+             (rand_patterns(rng, (M, K), fin, allow_nar=False), rand_patterns(rng, (K, N), fin, allow_nar=False)),
+             (narrow((M, K), 1.0), narrow((K, N), 1.0)),
+             (narrow((M, K), 0.01), narrow((K, N), 8.0))]
+    fills[2][0][17, 5] = 0x80
+    A = torch.zeros((M, K), dtype=torch.uint8, device="cuda")
+    B = torch.zeros((K, N), dtype=torch.uint8, device="cuda")
+    C = torch.zeros((M, N), dtype=torch.uint8, device="cuda")
+    ws = torch.full((pn.posit_gemm_workspace(fin, fin, 0, 0, M, N, K),), 0xFF, dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        pn.posit_gemm(A, B, fin, fin, out=C, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        pn.posit_gemm(A, B, fin, fin, out=C, workspace=ws)
+    for i, (a, b) in enumerate(fills):
+        A.copy_(to_dev(a)); B.copy_(to_dev(b))
+        C.fill_(0x55)
+        graph.replay()
+        torch.cuda.synchronize()
+        got = to_np(C, fin).copy()
+        eager = to_np(pn.posit_gemm(to_dev(a), to_dev(b), fin, fin), fin)
+        assert np.array_equal(got, eager), "replay %d" % i
+        if i == 2:
+            assert (got[17] == 0x80).all() and (got == 0x80).sum() == N
+        if i == 0:
+            for r in (0, 100, M - 1):
+                want, _ = fast.gemm(a, b, fin, fin, rows=(r, r + 1))
+                _assert_equal(got[r], want[r], "replay 0, row %d" % r)
+
+
 @pytest.mark.parametrize("M,N,K,ta,tb,kernel", [(130, 130, 259, 0, 0, "tiled dot2"), (131, 140, 300, 1, 1, "tiled dot2, transposed"),
                                                 (40, 300, 8200, 0, 0, "byte gather"), (20, 30, 300, 0, 1, "small problem"),
                                                 (1100, 1030, 16400, 0, 0, "packed operands")])
