@@ -324,11 +324,27 @@ __global__ __launch_bounds__(256, ((2 * NP - 1) * 16 > 160 ? 1 : 2)) void b8_mfm
         const int lr = (r & 3) + 8 * (r >> 2) + 4 * (lane >> 5);
         const int m = tm * 64 + wy * 32 + lr;
         if (m >= M) continue;
+        // the sums at their digit positions (shifts known at compile time), then the offset of the window: the quire,
+        // modulo 2^(32 L) like every addition into it
         uint32_t q[L];
+        if constexpr (L == 4) {
+            __int128 v = 0;
 #pragma unroll
-        for (int l = 0; l < L; ++l) q[l] = 0;
+            for (int s = 0; s < NC; ++s) v += (__int128)acc[s][r] << (7 * s);
+            const unsigned __int128 x = (unsigned __int128)v << (7 * (oa + ob));
+            q[0] = (uint32_t)x;
+            q[1] = (uint32_t)(x >> 32);
+            q[2] = (uint32_t)(x >> 64);
+            q[3] = (uint32_t)(x >> 96);
+        } else {
+            static_assert(L == 2, "64-bit or 128-bit quire");
+            uint64_t v = 0;
 #pragma unroll
-        for (int s = 0; s < NC; ++s) Arith<F>::add_product(q, acc[s][r], 7 * (s + oa + ob));
+            for (int s = 0; s < NC; ++s) v += (uint64_t)(int64_t)acc[s][r] << (7 * s);
+            const uint64_t x = v << (7 * (oa + ob));
+            q[0] = (uint32_t)x;
+            q[1] = (uint32_t)(x >> 32);
+        }
         if (bias && bp != F::NAR) AR::add_bias(q, bp);
         const bool nar = cnar || rowv[wy * 32 + lr] != 0;
         round_store<AR, L>(q, nar, fout, C, (int64_t)m * ldc + n);
