@@ -120,6 +120,14 @@ def test_argument_validation_without_launch():
     assert L.posit_gemm_workspace(0, 0, 0, 0, 600, 540, 1700) == 2 * 1728 * (640 + 576)  # 64 x 64 tiles, k in steps of 64
     assert L.posit_gemm_workspace(0, 0, 0, 0, 512, 512, 512) == 0   # below: the reduction cut inside the workgroup
     assert L.posit_gemm(null, 0, 0, 0, 0, 4096, 4096, 4096, fake, 4096, fake, 4096, null, fake, 4096, null, 0) == 3
+    # posit(8,1) / posit(8,2) from 2^25 products up (128 outputs each way, K 256 .. 8192): four / eight digit planes per
+    # operand in blocks of 32 x 32, a mask byte per block, and the two words of the unions of the masks
+    planes = lambda nd, M, N, K: nd * 1024 * ((K + 31) // 32) * (2 * ((M + 63) // 64) + 2 * ((N + 63) // 64))
+    masks = lambda M, N, K: sum((((K + 31) // 32) * 2 * ((R + 63) // 64) + 255) // 256 * 256 for R in (M, N))
+    assert L.posit_gemm_workspace(4, 4, 0, 0, 1024, 1024, 1024) == planes(8, 1024, 1024, 1024) + masks(1024, 1024, 1024) + 256
+    assert L.posit_gemm_workspace(3, 3, 0, 0, 1024, 1024, 1024) == planes(4, 1024, 1024, 1024) + masks(1024, 1024, 1024) + 256
+    assert L.posit_gemm_workspace(4, 4, 0, 0, 600, 540, 1700) == planes(8, 600, 540, 1700) + masks(600, 540, 1700) + 256
+    assert L.posit_gemm_workspace(4, 4, 0, 0, 1024, 1024, 8224) < planes(8, 1024, 1024, 8224)   # beyond 8192: the fp64 buckets
     # the variant with the library's own scratch array: same checks, and a problem beyond the array is refused before any launch
     assert L.posit_gemm_static(null, 57, 0, 0, 0, 4, 4, 4, fake, 4, fake, 4, null, fake, 4) == EINVAL
     assert L.posit_gemm_static(null, 0, 0, 0, 0, 4, 4, 8, fake, 4, fake, 4, null, fake, 4) == EINVAL
